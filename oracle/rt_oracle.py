@@ -1,0 +1,202 @@
+"""ctypes front end of the fp64 CPU oracle (oracle/rt_oracle.c) -- TEST INFRASTRUCTURE ONLY.
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg import this module.
+It builds the C file with gcc on first use (a second or two) and never touches the GPU
+library.  All arrays are float64 numpy, C-contiguous:
+    x, y : [B, N, d]        K, V : [kv_cap, B, H, dh]        weights : [out, in]
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rt_oracle.c")
+_LIB = os.path.join(_HERE, "librt_oracle.so")
+
+_MLP_FN = C.CFUNCTYPE(None, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_int, C.c_void_p)
+_DP = C.POINTER(C.c_double)
+
+
+class _Params(C.Structure):
+    _fields_ = [
+        ("d", C.c_int32), ("H", C.c_int32), ("dh", C.c_int32), ("F", C.c_int32),
+        ("alpha", C.c_double), ("attn_scale", C.c_double), ("eps", C.c_double),
+        ("norm_free", C.c_int32), ("threads", C.c_int32),
+        ("Wq", _DP), ("Wk", _DP), ("Wv", _DP), ("Wo", _DP), ("W1", _DP), ("W2", _DP),
+        ("g_attn", _DP), ("g_mlp", _DP), ("g_kv", _DP), ("g_q", _DP), ("g_k", _DP),
+        ("mlp", _MLP_FN), ("mlp_user", C.c_void_p),
+    ]
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (plain -O3, no fast-math) into oracle/librt_oracle.so."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp%d" % os.getpid()
+        cmd = ["gcc", "-O3", "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-fno-fast-math",
+               "-ffp-contract=off", _SRC, "-o", tmp, "-lm"]
+        subprocess.run(cmd, check=True)
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        build()
+        L = C.CDLL(_LIB)
+        PP = C.POINTER(_Params)
+        L.rto_layer_prefill.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int, _DP]
+        L.rto_layer_prefill.restype = C.c_int
+        L.rto_layer_prefill_tiled.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int]
+        L.rto_layer_prefill_tiled.restype = C.c_int
+        L.rto_transformer_layer.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int, _DP]
+        L.rto_transformer_layer.restype = C.c_int
+        L.rto_decode_step.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int]
+        L.rto_decode_step.restype = C.c_int
+        L.rto_update_tile.argtypes = [_DP, C.c_int, C.c_int, _DP, _DP, C.c_int, C.c_int, C.c_int, C.c_double,
+                                      _DP, _DP, _DP]
+        L.rto_update_tile.restype = None
+        L.rto_schedule.argtypes = [C.c_int, C.POINTER(C.c_int32), C.c_int]
+        L.rto_schedule.restype = C.c_int
+        L.rto_max_threads.restype = C.c_int
+        _lib = L
+    return _lib
+
+
+def _f64(a):
+    return np.ascontiguousarray(a, dtype=np.float64)
+
+
+def _ptr(a):
+    return a.ctypes.data_as(_DP) if a is not None else _DP()
+
+
+class Layer:
+    """Parameters of one RT layer for the oracle.
+
+    weights: dict with Wq, Wk, Wv [d,d], optional Wo [d,d] (missing/None = identity),
+             W1 [F,d], W2 [d,F] (not needed when `mlp` is given).
+    gains:   optional dict g_attn, g_mlp, g_kv, g_q, g_k (missing = ones; g_kv missing = g_attn).
+    mlp:     optional Python callable  u(np.ndarray[d]) -> np.ndarray[d]  replacing the MLP block.
+    """
+
+    def __init__(self, weights, H, *, gains=None, alpha=1.0, attn_scale=1.0, eps=1e-6, norm_free=False,
+                 mlp=None, threads=0):
+        self._keep = []
+        w = {k: (_f64(v) if v is not None else None) for k, v in weights.items()}
+        d = w["Wq"].shape[0]
+        assert d % H == 0
+        self.d, self.H, self.dh = d, H, d // H
+        self.F = w["W1"].shape[0] if w.get("W1") is not None else 0
+        g = dict(gains or {})
+        if g.get("g_kv") is None and g.get("g_attn") is not None:
+            g["g_kv"] = g["g_attn"]
+        g = {k: (_f64(v) if v is not None else None) for k, v in g.items()}
+        p = _Params()
+        p.d, p.H, p.dh, p.F = d, H, self.dh, self.F
+        p.alpha, p.attn_scale, p.eps = float(alpha), float(attn_scale), float(eps)
+        p.norm_free, p.threads = int(bool(norm_free)), int(threads)
+        for name in ("Wq", "Wk", "Wv", "Wo", "W1", "W2"):
+            a = w.get(name)
+            setattr(p, name, _ptr(a))
+            self._keep.append(a)
+        for name in ("g_attn", "g_mlp", "g_kv", "g_q", "g_k"):
+            a = g.get(name)
+            setattr(p, name, _ptr(a))
+            self._keep.append(a)
+        if mlp is not None:
+            def _cb(inp, out, n, _user, _f=mlp):
+                u = np.ctypeslib.as_array(inp, shape=(n,)).copy()
+                r = np.asarray(_f(u), dtype=np.float64)
+                np.ctypeslib.as_array(out, shape=(n,))[:] = r
+            self._cb = _MLP_FN(_cb)
+            p.mlp = self._cb
+        self.p = p
+
+    # ------------------------------------------------------------------ entry points
+    def _alloc(self, x, kv_cap):
+        x = _f64(x)
+        B, N, d = x.shape
+        assert d == self.d
+        kv_cap = N if kv_cap is None else kv_cap
+        y = np.zeros((B, N, d))
+        K = np.zeros((kv_cap, B, self.H, self.dh))
+        V = np.zeros((kv_cap, B, self.H, self.dh))
+        return x, B, N, kv_cap, y, K, V
+
+    def prefill(self, x, kv_cap=None, want_attw=False):
+        """Token-by-token recurrence of the RT layer definition.  Returns (y, K, V[, attw])."""
+        x, B, N, kv_cap, y, K, V = self._alloc(x, kv_cap)
+        aw = np.zeros((B, self.H, N, N)) if want_attw else None
+        rc = lib().rto_layer_prefill(C.byref(self.p), _ptr(x), B, N, _ptr(y), _ptr(K), _ptr(V), kv_cap, _ptr(aw))
+        if rc:
+            raise RuntimeError("rto_layer_prefill failed: %d" % rc)
+        return (y, K, V, aw) if want_attw else (y, K, V)
+
+    def prefill_tiled(self, x, kv_cap=None):
+        """Appendix C, Algorithms 1 + 2 literally (running statistics, tiled schedule)."""
+        x, B, N, kv_cap, y, K, V = self._alloc(x, kv_cap)
+        rc = lib().rto_layer_prefill_tiled(C.byref(self.p), _ptr(x), B, N, _ptr(y), _ptr(K), _ptr(V), kv_cap)
+        if rc:
+            raise RuntimeError("rto_layer_prefill_tiled failed: %d" % rc)
+        return y, K, V
+
+    def transformer(self, x, want_attw=False):
+        """Standard causal Transformer layer with the same parameters (Sec. 2.1)."""
+        x, B, N, kv_cap, y, K, V = self._alloc(x, None)
+        aw = np.zeros((B, self.H, N, N)) if want_attw else None
+        rc = lib().rto_transformer_layer(C.byref(self.p), _ptr(x), B, N, _ptr(y), _ptr(K), _ptr(V), kv_cap, _ptr(aw))
+        if rc:
+            raise RuntimeError("rto_transformer_layer failed: %d" % rc)
+        return (y, K, V, aw) if want_attw else (y, K, V)
+
+    def decode_step(self, x_t, t, K, V):
+        """One position given persistent rows 0..t-1 of K, V (modified in place at row t)."""
+        x_t = _f64(x_t)
+        B = x_t.shape[0]
+        assert K.dtype == np.float64 and K.flags.c_contiguous and V.flags.c_contiguous
+        y_t = np.zeros((B, self.d))
+        rc = lib().rto_decode_step(C.byref(self.p), _ptr(x_t), B, int(t), _ptr(y_t), _ptr(K), _ptr(V), K.shape[0])
+        if rc:
+            raise RuntimeError("rto_decode_step failed: %d" % rc)
+        return y_t
+
+
+def update_tile(q, k, v, m, l, o, scale=1.0):
+    """Algorithm 2 on dense [nq,dh] / [nkv,dh] tiles; m, l [nq], o [nq,dh] updated in place."""
+    q, k, v = _f64(q), _f64(k), _f64(v)
+    nq, dh = q.shape
+    nkv = k.shape[0]
+    for a in (m, l, o):
+        assert a.dtype == np.float64 and a.flags.c_contiguous
+    lib().rto_update_tile(_ptr(q), nq, dh, _ptr(k), _ptr(v), nkv, dh, dh, float(scale), _ptr(m), _ptr(l), _ptr(o))
+
+
+def schedule(N):
+    """Events (t, P, u, v, s, e) of Algorithm 1, 1-based inclusive ranges."""
+    cap = max(1, N)
+    buf = (C.c_int32 * (6 * cap))()
+    n = lib().rto_schedule(int(N), buf, cap)
+    a = np.frombuffer(buf, dtype=np.int32).reshape(cap, 6)[:n].copy()
+    return [tuple(int(v) for v in r) for r in a]
+
+
+def max_threads():
+    return int(lib().rto_max_threads())
+
+
+def stack_prefill(layers, x0):
+    """L stacked RT layers: the output of one layer is the input of the next (Sec. 2.2)."""
+    out = []
+    x = x0
+    for lay in layers:
+        y, K, V = lay.prefill(x)
+        out.append((y, K, V))
+        x = y
+    return out
