@@ -1,0 +1,147 @@
+#!/usr/bin/env python3
+"""Benchmark of the RT-layer prefill hot path on one MI355X.
+
+A step is one rt_layer_prefill call (pre-pass, the N sequential base cases, every cross-block update)
+on one batch of synthetic input already resident in HBM.  Prints one JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def algorithmic_bytes(B, N, d, H, F, E, p_min):
+    """Bytes one layer call must move (per-call totals), by term.
+
+    weights      : the five matrices of the sequential loop are needed at every position (11 d^2 E per
+                   position when streamed) plus the three pre-pass matrices once.
+    attention    : every cross-block event reads its q, k, v tiles once and writes a partial state that is
+                   read once: (3*64*E + 2*66*4) bytes per (query, level, head, batch row), plus the direct
+                   window rows.
+    activations  : x read twice, Q / K_tmp / V_tmp written and read once, y / K / V written: 11 d E per token.
+    """
+    import math
+    levels = 0
+    attn = 0
+    for t1 in range(1, N):
+        P = t1 & -t1
+        if P >= p_min:
+            nq = min(P, N - t1)
+            attn += B * H * (P * 2 * 64 * E + nq * 64 * E + 2 * nq * 66 * 4)
+    window = sum((t & (p_min - 1)) for t in range(N)) * B * H * 2 * 64 * E
+    return {
+        "weights_seq": N * (2 * d * d + 2 * d * F + d * d) * E * 1.0,
+        "weights_pre": 3 * d * d * E * 1.0,
+        "attention": float(attn + window),
+        "activations": 11.0 * B * N * d * E,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=5)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg3")
+    ap.add_argument("--engine", default="auto", choices=["auto", "stepwise", "graph", "persistent"])
+    ap.add_argument("--p-min", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-sample-positions", type=int, default=1024)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on exactly one GPU (one process, one device); --gpus %d is not supported"
+              % args.gpus, file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2604_21215_amd import binding, inputs as gen, torch_io as tio
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    wl = gen.WORKLOADS[args.workload]
+    li = gen.make_layer_inputs(wl)
+    flags = {"auto": 0, "stepwise": binding.RT_FLAG_ENGINE_STEPWISE,
+             "graph": binding.RT_FLAG_ENGINE_STEPWISE | binding.RT_FLAG_HIP_GRAPH,
+             "persistent": binding.RT_FLAG_ENGINE_PERSISTENT}[args.engine]
+    stream = torch.cuda.current_stream()
+    ctx = binding.RTContext(wl.d, wl.H, wl.F, wl.B, wl.N, wl.dtype, p_min=args.p_min, resid_scale=wl.resid_scale,
+                            attn_scale=1.0, rms_eps=1e-6, flags=flags, stream=stream.cuda_stream)
+    dl = tio.DeviceLayer(li.weights, li.gains, wl.dtype)
+    xd = tio.to_device(li.x, wl.dtype)
+    y = torch.empty_like(xd)
+    K = torch.zeros((wl.N, wl.B, wl.H, wl.head_dim), dtype=xd.dtype, device=xd.device)
+    V = torch.zeros_like(K)
+
+    for _ in range(args.warmup):
+        ctx.rt_layer_prefill(dl.struct, xd, y, K, V)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+    t0 = time.perf_counter()
+    ev[0].record(stream)
+    for i in range(args.steps):
+        ctx.rt_layer_prefill(dl.struct, xd, y, K, V)
+        ev[i + 1].record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    assert ctx.device_wait_expired() == 0, "a device-side wait expired: results invalid"
+    per_call_ms = [ev[i].elapsed_time(ev[i + 1]) for i in range(args.steps)]
+    ms_per_step = wall * 1e3 / args.steps
+    tokens = wl.B * wl.N
+    value = tokens * args.steps / wall
+    engine = ctx.engine_name()
+
+    E = 2 if wl.dtype == "bf16" else 4
+    p_min = ctx.cfg.p_min if ctx.cfg.p_min else 32
+    terms = algorithmic_bytes(wl.B, wl.N, wl.d, wl.H, wl.F, E, p_min)
+    alg_bytes = sum(terms.values())
+    dev_ms = float(np.mean(per_call_ms))
+    achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
+    roofline = {
+        "bound": "hbm", "kernel": "rt_layer_prefill (%s engine, all launches of one call)" % engine,
+        "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+        "launch_ms": dev_ms, "algorithmic_bytes": alg_bytes, "terms": terms,
+        "us_per_position": dev_ms * 1e3 / wl.N,
+    }
+    attn_flops = 2.0 * wl.N * (wl.N - 1) * wl.d * wl.B
+    out = {
+        "metric": "RT-layer prefill tokens/s at N=2048,d=1024 (1 GPU)" if args.workload == "cfg3"
+        else "RT-layer prefill tokens/s (%s)" % args.workload,
+        "value": value, "unit": "tokens/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": "%s: single RT layer, %s, B=%d, N=%d, d_model=%d, %d heads x 64, MLP hidden %d"
+                   % (wl.name, wl.dtype, wl.B, wl.N, wl.d, wl.H, wl.F), "engine": engine, "p_min": p_min,
+                   "attention_gflop_per_call": attn_flops / 1e9},
+        "roofline": roofline,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import rt_oracle
+        n_s = min(args.cpu_sample_positions, wl.N)
+        w64 = {k: v.astype(np.float64) for k, v in li.weights.items()}
+        lay = rt_oracle.Layer(w64, wl.H, alpha=wl.resid_scale, eps=1e-6)
+        xs = li.x[:, :n_s].astype(np.float64)
+        t0 = time.perf_counter()
+        ref = lay.prefill(xs)
+        dt = time.perf_counter() - t0
+        cores = min(rt_oracle.max_threads(), wl.B) if wl.B >= 4 else rt_oracle.max_threads()
+        out["cpu_baseline"] = {"value": wl.B * n_s / dt, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+                               "sample": "first %d positions of all %d sequences of the same workload (%.1f s)"
+                               % (n_s, wl.B, dt)}
+        got = tio.to_host(y[:, :n_s])
+        err = np.linalg.norm(got - ref[0], axis=-1) / np.linalg.norm(ref[0], axis=-1)
+        out["parity_sample"] = {"max_rel_err_y": float(err.max()), "positions": n_s}
+    ctx.rt_destroy()
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

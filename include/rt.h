@@ -1,0 +1,139 @@
+/*
+ * rt.h -- C ABI of the MI355X (gfx950) Recurrent Transformer layer library (librt_hip.so).
+ *
+ * One RT layer, forward only.  Per position i (paper Sec. 2.2, "The Recurrent Transformer layer"):
+ *
+ *     n_i      = RMS(x_i; g_attn)
+ *     q_i      = qkRMS(Wq n_i; g_q)     k_i^tmp = qkRMS(Wk n_i; g_k)     v_i^tmp = Wv n_i
+ *     a_i      = Wo * concat_heads Attn((k_1,v_1) ... (k_{i-1},v_{i-1}), (k_i^tmp,v_i^tmp); q_i)
+ *     h_i      = x_i + alpha a_i
+ *     z_i      = h_i + alpha W2 gelu(W1 RMS(h_i; g_mlp))                 (layer output, y)
+ *     k_i      = qkRMS(Wk RMS(z_i; g_kv); g_k)     v_i = Wv RMS(z_i; g_kv)       (persistent pair)
+ *
+ * with Attn the softmax-weighted sum over logits attn_scale*<k,q> (Sec. 2, Notation; the paper's
+ * logits are unscaled, attn_scale = 1), RMS(u) = g * u / sqrt(mean(u^2) + eps), qkRMS the same
+ * normalisation on each head's slice, exact (erf) GELU, no biases, alpha the 1/sqrt(L) residual
+ * scale of Sec. 2.  Persistent pairs of positions j < i only, plus position i's own temporary
+ * pair: that is the whole causal mask.
+ *
+ * rt_layer_prefill evaluates all N positions with the exact tiled schedule of Appendix C
+ * (Algorithms 1 and 2): when position t is finished and P is the largest power of two dividing t,
+ * the KV block [t-P+1, t] is folded into the softmax state of queries [t+1, min(t+P, N)].  Blocks
+ * smaller than the context's p_min are instead attended directly when each query is finished
+ * (Algorithm 1's free "query tile size" parameter); results do not depend on p_min beyond rounding.
+ *
+ * All pointers named "device" are device (HBM) addresses valid on rt_config.device; everything is
+ * enqueued on rt_config.stream and the calls return without synchronising.  The caller owns x, y,
+ * K, V and the weights; the context owns only scratch memory.  No exceptions cross this boundary.
+ */
+#ifndef RT_H_
+#define RT_H_
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rt_ctx rt_ctx; /* opaque */
+
+typedef enum {
+    RT_OK = 0,
+    RT_ERR_INVALID_ARG = 1, /* null pointer, size out of range, overlapping x / y, t >= kv_cap ... */
+    RT_ERR_UNSUPPORTED = 2, /* shape or dtype the kernels do not cover (head_dim != 64, ...) */
+    RT_ERR_OOM = 3,         /* scratch allocation failed */
+    RT_ERR_HIP = 4,         /* a HIP runtime call failed; see rt_last_error */
+    RT_ERR_STATE = 5        /* context unusable (earlier failure, or a bounded device-side wait expired) */
+} rt_status;
+
+typedef enum { RT_F32 = 0, RT_BF16 = 1 } rt_dtype; /* storage type of x, y, K, V, weights and gains */
+
+/* rt_config.flags */
+#define RT_FLAG_NORM_FREE 0x1u       /* every RMS / qkRMS is the identity (Appendix A's norm-free layer) */
+#define RT_FLAG_ENGINE_STEPWISE 0x2u /* drive the sequential loop as one set of kernel launches per position */
+#define RT_FLAG_ENGINE_PERSISTENT 0x4u /* require the single persistent weight-stationary kernel (error if it cannot run) */
+#define RT_FLAG_NO_MFMA 0x8u         /* use the plain-ALU kernels also for bf16 storage (cross-checks) */
+#define RT_FLAG_HIP_GRAPH 0x10u      /* stepwise engine: capture the launches of a prefill in a HIP graph and replay it */
+
+typedef struct {
+    int32_t d_model, n_heads, head_dim, d_hidden; /* n_heads * head_dim == d_model; head_dim must be 64 */
+    int32_t max_batch, max_seq;                   /* sizes the scratch (queries, temporary pairs, partial states) */
+    int32_t dtype;                                /* rt_dtype */
+    int32_t p_min;                                /* smallest KV block handled by the cross-block kernel; power of
+                                                     two in [32, 1024]; 0 = default (32) */
+    float resid_scale;                            /* alpha = 1/sqrt(L) (Sec. 2); 1 for a single layer */
+    float attn_scale;                             /* multiplies the logits; paper-literal 1 */
+    float rms_eps;                                /* paper-literal 0; 1e-6 is the usual choice */
+    uint32_t flags;
+    int32_t device;                               /* HIP device ordinal */
+    void *stream;                                 /* hipStream_t; NULL = the default stream */
+} rt_config;
+
+/* Device pointers, caller-owned, read-only.  Matrices are row-major [out, in] (y = W u).
+ * Gains: NULL = ones.  g_kv NULL = use g_attn.  g_q, g_k are [d_model] = [n_heads, head_dim]. */
+typedef struct {
+    const void *Wq, *Wk, *Wv, *Wo; /* [d, d] */
+    const void *W1;                /* [F, d] */
+    const void *W2;                /* [d, F] */
+    const void *g_attn, *g_mlp, *g_kv;
+    const void *g_q, *g_k;
+} rt_layer_weights;
+
+/* Create a context: validates cfg, allocates scratch on cfg->device.  *out is NULL on failure. */
+rt_status rt_create(const rt_config *cfg, rt_ctx **out);
+
+/* Whole-sequence forward of one layer (Appendix C, Algorithm 1: inputs x_{1:N}, outputs z_{1:N} and
+ * the persistent pairs (k_{1:N}, v_{1:N})).
+ *   x [B, N, d]  device, read-only, must not overlap y
+ *   y [B, N, d]  device, written
+ *   K, V [kv_cap, B, H, head_dim] device, position first (Sec. 6.3); rows 0..N-1 are written in place
+ *   1 <= B <= max_batch, 1 <= N <= max_seq, N <= kv_cap.
+ * Host-detectable errors are returned before anything is enqueued and leave the outputs untouched. */
+rt_status rt_layer_prefill(rt_ctx *ctx, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, void *y,
+                           void *K, void *V, int32_t kv_cap);
+
+/* One position of the same recurrence over a caller-held cache (Sec. 7.3: decoding attends over the
+ * cached persistent pairs like a Transformer).
+ *   x_t [B, d] device; t is 0-based: rows 0..t-1 of K, V are valid, row t is written; y_t [B, d].
+ *   0 <= t < kv_cap, t < max_seq.  N successive decode steps equal one prefill of length N. */
+rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t, void *y_t,
+                         void *K, void *V, int32_t kv_cap);
+
+/* Waits for nothing: the caller synchronises the stream first.  Frees scratch.  NULL is allowed. */
+rt_status rt_destroy(rt_ctx *ctx);
+
+/* Text of the last error on this context (owned by the context), or a static string for ctx == NULL. */
+const char *rt_last_error(const rt_ctx *ctx);
+
+const char *rt_status_string(rt_status s);
+
+/* Bytes of device scratch the context holds. */
+uint64_t rt_workspace_bytes(const rt_ctx *ctx);
+
+/* After the stream has been synchronised: 0 if every bounded device-side wait of the last call on
+ * this context completed, non-zero if one expired (the call's outputs are then invalid). */
+int32_t rt_device_wait_expired(rt_ctx *ctx);
+
+/* Name of the engine the last rt_layer_prefill on this context used: "stepwise", "stepwise+graph",
+ * "persistent", or "" before the first call. */
+const char *rt_engine_name(const rt_ctx *ctx);
+
+/* Host-only: the cross-block events the driver issues for a sequence of length N with threshold
+ * p_min (Appendix C, Algorithm 1, lines "P <- 2^nu2(t)" to the second UpdateTile call, restricted to
+ * P >= p_min).  Event e: out[5e+0..4] = t, P, first query u, last query v, first key s (1-based,
+ * inclusive; last key = t).  Pairs not covered by an event are covered by the direct window of
+ * query i, keys [ (i-1) - ((i-1) mod p_min) + 1, i-1 ].  Returns the number of events; writes at most
+ * cap of them (out may be NULL when cap == 0). */
+int32_t rt_schedule_events(int32_t N, int32_t p_min, int32_t *out, int32_t cap);
+
+/* Host-only: index of the partial-state slot of (level, query), or -1 if that query takes no tile at
+ * that level.  level = log2(P); query is 1-based.  Slots of one level are dense in [0, ceil(N/2)). */
+int64_t rt_partial_slot(int32_t level, int32_t query);
+
+/* Library version: major*10000 + minor*100 + patch. */
+int32_t rt_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RT_H_ */

@@ -1,0 +1,179 @@
+"""ctypes binding of librt_hip.so: the same entry points as include/rt.h, argument marshalling only.
+
+Every step of the layer runs in the library's HIP kernels; PyTorch is used by callers for device
+memory and streams.  There is no CPU fallback: if the library is missing the import of the symbols
+fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+from . import build as _build
+
+RT_OK = 0
+RT_ERR_INVALID_ARG, RT_ERR_UNSUPPORTED, RT_ERR_OOM, RT_ERR_HIP, RT_ERR_STATE = 1, 2, 3, 4, 5
+RT_F32, RT_BF16 = 0, 1
+RT_FLAG_NORM_FREE = 0x1
+RT_FLAG_ENGINE_STEPWISE = 0x2
+RT_FLAG_ENGINE_PERSISTENT = 0x4
+RT_FLAG_NO_MFMA = 0x8
+RT_FLAG_HIP_GRAPH = 0x10
+
+EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_last_error", "rt_status_string",
+           "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
+           "rt_version")
+
+
+class rt_config(C.Structure):
+    _fields_ = [
+        ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("d_hidden", C.c_int32),
+        ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("dtype", C.c_int32), ("p_min", C.c_int32),
+        ("resid_scale", C.c_float), ("attn_scale", C.c_float), ("rms_eps", C.c_float), ("flags", C.c_uint32),
+        ("device", C.c_int32), ("stream", C.c_void_p),
+    ]
+
+
+class rt_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2", "g_attn", "g_mlp", "g_kv", "g_q", "g_k")]
+
+
+class RTError(RuntimeError):
+    def __init__(self, status, msg):
+        super().__init__("%s: %s" % (status, msg))
+        self.status = status
+
+
+_lib = None
+
+
+def load():
+    """Load the built library (builds it only if no library is there at all)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB):
+        _build.build_hip(True)
+    L = C.CDLL(_build.LIB)
+    ctxp = C.c_void_p
+    L.rt_create.argtypes = [C.POINTER(rt_config), C.POINTER(ctxp)]
+    L.rt_create.restype = C.c_int
+    L.rt_layer_prefill.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                   C.c_void_p, C.c_void_p, C.c_int32]
+    L.rt_layer_prefill.restype = C.c_int
+    L.rt_decode_step.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                 C.c_void_p, C.c_void_p, C.c_int32]
+    L.rt_decode_step.restype = C.c_int
+    L.rt_destroy.argtypes = [ctxp]
+    L.rt_destroy.restype = C.c_int
+    L.rt_last_error.argtypes = [ctxp]
+    L.rt_last_error.restype = C.c_char_p
+    L.rt_status_string.argtypes = [C.c_int]
+    L.rt_status_string.restype = C.c_char_p
+    L.rt_workspace_bytes.argtypes = [ctxp]
+    L.rt_workspace_bytes.restype = C.c_uint64
+    L.rt_device_wait_expired.argtypes = [ctxp]
+    L.rt_device_wait_expired.restype = C.c_int32
+    L.rt_engine_name.argtypes = [ctxp]
+    L.rt_engine_name.restype = C.c_char_p
+    L.rt_schedule_events.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
+    L.rt_schedule_events.restype = C.c_int32
+    L.rt_partial_slot.argtypes = [C.c_int32, C.c_int32]
+    L.rt_partial_slot.restype = C.c_int64
+    L.rt_version.restype = C.c_int32
+    _lib = L
+    return L
+
+
+def _check(L, ctx, rc):
+    if rc != RT_OK:
+        msg = L.rt_last_error(ctx).decode() if ctx else ""
+        raise RTError(L.rt_status_string(rc).decode(), msg)
+
+
+def _ptr(t):
+    return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def make_weights(w: dict) -> rt_layer_weights:
+    """w maps names to device tensors (or None for the optional gains)."""
+    s = rt_layer_weights()
+    for name, _ in rt_layer_weights._fields_:
+        t = w.get(name)
+        setattr(s, name, None if t is None else t.data_ptr())
+    return s
+
+
+def rt_schedule_events(N: int, p_min: int):
+    L = load()
+    n = L.rt_schedule_events(N, p_min, None, 0)
+    if n < 0:
+        raise RTError("RT_ERR_INVALID_ARG", "rt_schedule_events")
+    buf = (C.c_int32 * (5 * max(n, 1)))()
+    L.rt_schedule_events(N, p_min, buf, n)
+    return [tuple(buf[5 * i + j] for j in range(5)) for i in range(n)]
+
+
+def rt_partial_slot(level: int, query: int) -> int:
+    return int(load().rt_partial_slot(level, query))
+
+
+class RTContext:
+    """Owns an rt_ctx.  Methods mirror the C entry points and take torch device tensors."""
+
+    def __init__(self, d_model, n_heads, d_hidden, max_batch, max_seq, dtype, *, p_min=0, resid_scale=1.0,
+                 attn_scale=1.0, rms_eps=1e-6, flags=0, device=0, stream=None):
+        L = load()
+        cfg = rt_config(d_model, n_heads, d_model // n_heads if n_heads else 0, d_hidden, max_batch, max_seq,
+                        RT_BF16 if dtype in ("bf16", RT_BF16) and dtype != 0 else RT_F32, p_min, resid_scale, attn_scale,
+                        rms_eps, flags, device, stream)
+        self.cfg = cfg
+        self._L = L
+        self._ctx = C.c_void_p()
+        rc = L.rt_create(C.byref(cfg), C.byref(self._ctx))
+        if rc != RT_OK:
+            raise RTError(L.rt_status_string(rc).decode(), "rt_create")
+
+    # -- rt_layer_prefill(ctx, w, x[B,N,d], B, N, y, K, V, kv_cap)
+    def rt_layer_prefill(self, weights: rt_layer_weights, x, y, K, V):
+        B, N, _ = x.shape
+        rc = self._L.rt_layer_prefill(self._ctx, C.byref(weights), _ptr(x), B, N, _ptr(y), _ptr(K), _ptr(V), K.shape[0])
+        _check(self._L, self._ctx, rc)
+
+    # -- rt_decode_step(ctx, w, x_t[B,d], B, t, y_t, K, V, kv_cap)
+    def rt_decode_step(self, weights: rt_layer_weights, x_t, t, y_t, K, V):
+        rc = self._L.rt_decode_step(self._ctx, C.byref(weights), _ptr(x_t), x_t.shape[0], int(t), _ptr(y_t), _ptr(K),
+                                    _ptr(V), K.shape[0])
+        _check(self._L, self._ctx, rc)
+
+    def raw_prefill(self, weights, x_ptr, B, N, y_ptr, K_ptr, V_ptr, kv_cap) -> int:
+        """Status code of rt_layer_prefill on raw addresses (error-path tests)."""
+        return self._L.rt_layer_prefill(self._ctx, C.byref(weights) if weights is not None else None, C.c_void_p(x_ptr),
+                                        B, N, C.c_void_p(y_ptr), C.c_void_p(K_ptr), C.c_void_p(V_ptr), kv_cap)
+
+    def raw_decode(self, weights, x_ptr, B, t, y_ptr, K_ptr, V_ptr, kv_cap) -> int:
+        return self._L.rt_decode_step(self._ctx, C.byref(weights) if weights is not None else None, C.c_void_p(x_ptr),
+                                      B, t, C.c_void_p(y_ptr), C.c_void_p(K_ptr), C.c_void_p(V_ptr), kv_cap)
+
+    def last_error(self) -> str:
+        return self._L.rt_last_error(self._ctx).decode()
+
+    def engine_name(self) -> str:
+        return self._L.rt_engine_name(self._ctx).decode()
+
+    def workspace_bytes(self) -> int:
+        return int(self._L.rt_workspace_bytes(self._ctx))
+
+    def device_wait_expired(self) -> int:
+        return int(self._L.rt_device_wait_expired(self._ctx))
+
+    def rt_destroy(self):
+        if self._ctx:
+            self._L.rt_destroy(self._ctx)
+            self._ctx = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.rt_destroy()
+        except Exception:
+            pass

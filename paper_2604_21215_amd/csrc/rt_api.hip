@@ -1,0 +1,388 @@
+// C ABI of the RT layer library: context, validation, and the host-side schedule driver
+// (Appendix C, Algorithm 1) that enqueues every phase on one HIP stream.
+#include "../../include/rt.h"
+#include "rt_common.h"
+#include "rt_persistent.h"
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+
+using namespace rt;
+
+struct rt_ctx {
+    rt_config cfg;
+    LayerDims base;      // B, N, kv_cap filled per call
+    Scratch S;
+    void *slab = nullptr;
+    size_t slab_bytes = 0;
+    hipStream_t stream = nullptr;
+    bool use_mfma = false;
+    bool broken = false;
+    std::string err;
+    std::string engine;
+    PersistentState persist;
+    // cached HIP graph of one stepwise prefill
+    hipGraphExec_t graph_exec = nullptr;
+    hipStream_t capture_stream = nullptr;  // the legacy default stream cannot be captured
+    struct GraphKey {
+        const void *x, *y, *K, *V;
+        rt_layer_weights w;
+        int B, N, kv_cap;
+    } graph_key;
+};
+
+static const char *kNoCtx = "no context";
+
+static rt_status fail(rt_ctx *c, rt_status s, const char *fmt, const char *detail = "")
+{
+    if (c) {
+        char buf[512];
+        snprintf(buf, sizeof(buf), fmt, detail);
+        c->err = buf;
+    }
+    return s;
+}
+static rt_status fail_hip(rt_ctx *c, hipError_t e, const char *where)
+{
+    if (c) {
+        c->err = std::string(where) + ": " + hipGetErrorString(e);
+        c->broken = true;
+    }
+    return RT_ERR_HIP;
+}
+
+static int ilog2(int v)
+{
+    int l = 0;
+    while ((1 << (l + 1)) <= v) ++l;
+    return l;
+}
+static bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+extern "C" {
+
+int32_t rt_version(void) { return 100; }
+
+const char *rt_status_string(rt_status s)
+{
+    switch (s) {
+    case RT_OK: return "RT_OK";
+    case RT_ERR_INVALID_ARG: return "RT_ERR_INVALID_ARG";
+    case RT_ERR_UNSUPPORTED: return "RT_ERR_UNSUPPORTED";
+    case RT_ERR_OOM: return "RT_ERR_OOM";
+    case RT_ERR_HIP: return "RT_ERR_HIP";
+    case RT_ERR_STATE: return "RT_ERR_STATE";
+    }
+    return "RT_ERR_?";
+}
+
+int32_t rt_schedule_events(int32_t N, int32_t p_min, int32_t *out, int32_t cap)
+{
+    if (N < 1 || !is_pow2(p_min)) return -1;
+    int32_t n = 0;
+    for (int32_t t = 1; t < N; ++t) {
+        const int32_t P = t & -t;
+        if (P < p_min) continue;
+        if (out && n < cap) {
+            int32_t *r = out + 5 * (size_t)n;
+            r[0] = t; r[1] = P; r[2] = t + 1; r[3] = (t + P < N) ? t + P : N; r[4] = t - P + 1;
+        }
+        ++n;
+    }
+    return n;
+}
+
+int64_t rt_partial_slot(int32_t level, int32_t query)
+{
+    if (level < 0 || level > 30 || query < 1) return -1;
+    const int i0 = query - 1;
+    if (!((i0 >> level) & 1)) return -1;
+    return partial_slot(level, i0);
+}
+
+rt_status rt_create(const rt_config *cfg, rt_ctx **out)
+{
+    if (out) *out = nullptr;
+    if (!cfg || !out) return RT_ERR_INVALID_ARG;
+    if (cfg->d_model <= 0 || cfg->n_heads <= 0 || cfg->head_dim <= 0 || cfg->d_hidden <= 0 || cfg->max_batch <= 0 ||
+        cfg->max_seq <= 0 || (int64_t)cfg->n_heads * cfg->head_dim != cfg->d_model)
+        return RT_ERR_INVALID_ARG;
+    if (cfg->dtype != RT_F32 && cfg->dtype != RT_BF16) return RT_ERR_INVALID_ARG;
+    if (cfg->head_dim != kHeadDim || cfg->d_hidden % 8 != 0) return RT_ERR_UNSUPPORTED;
+    if (cfg->max_seq > (1 << 20) || cfg->max_batch > 1024) return RT_ERR_UNSUPPORTED;
+    if ((cfg->flags & RT_FLAG_ENGINE_STEPWISE) && (cfg->flags & RT_FLAG_ENGINE_PERSISTENT)) return RT_ERR_INVALID_ARG;
+    const bool mfma = cfg->dtype == RT_BF16 && !(cfg->flags & RT_FLAG_NO_MFMA);
+    int p_min = cfg->p_min == 0 ? 32 : cfg->p_min;
+    if (!is_pow2(p_min) || p_min > 1024 || (mfma && p_min < 32)) return RT_ERR_INVALID_ARG;
+    if (!(cfg->rms_eps >= 0.f) || !(cfg->attn_scale == cfg->attn_scale) || !(cfg->resid_scale == cfg->resid_scale))
+        return RT_ERR_INVALID_ARG;
+
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return RT_ERR_HIP;
+    if (hipSetDevice(cfg->device) != hipSuccess) return RT_ERR_HIP;
+
+    rt_ctx *c = new (std::nothrow) rt_ctx();
+    if (!c) return RT_ERR_OOM;
+    c->cfg = *cfg;
+    c->cfg.p_min = p_min;
+    c->stream = (hipStream_t)cfg->stream;
+    c->use_mfma = mfma;
+    LayerDims &D = c->base;
+    D.B = 0; D.N = 0; D.kv_cap = 0;
+    D.d = cfg->d_model; D.H = cfg->n_heads; D.F = cfg->d_hidden;
+    D.p_min = p_min; D.log2_pmin = ilog2(p_min);
+    D.alpha = cfg->resid_scale; D.scale = cfg->attn_scale; D.eps = cfg->rms_eps;
+    D.norm_free = (cfg->flags & RT_FLAG_NORM_FREE) ? 1 : 0;
+
+    const size_t E = cfg->dtype == RT_BF16 ? 2 : 4;
+    const size_t Bm = cfg->max_batch, Nm = cfg->max_seq, d = cfg->d_model, F = cfg->d_hidden, H = cfg->n_heads;
+    Scratch &S = c->S;
+    memset(&S, 0, sizeof(S));
+    const int lvmax = Nm >= 2 ? ilog2((int)Nm - 1) : 0;
+    S.levels = lvmax - D.log2_pmin + 1;
+    if (S.levels < 1) S.levels = 1;
+    S.slots = (int)((Nm + 1) / 2);
+    if (S.slots < 64) S.slots = 64;
+    S.vt_stride = (int)align_up(Nm, 64);
+
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t oQ = carve(Nm * Bm * d * E), oKt = carve(Nm * Bm * d * E), oVt = carve(Nm * Bm * d * E);
+    const size_t oVT = mfma ? carve(Bm * H * kHeadDim * (size_t)S.vt_stride * 2) : 0;
+    const size_t np = (size_t)S.levels * S.slots * Bm * H;
+    const size_t opm = carve(np * 4), opl = carve(np * 4), opo = carve(np * kHeadDim * 4);
+    const size_t orinv = carve(Bm * Nm * 4);
+    const size_t ocat = carve(Bm * d * 4), oh = carve(Bm * d * 4), ou = carve(Bm * F * 4), oz = carve(Bm * d * 4);
+    const size_t okv = carve(Bm * 2 * d * 4);
+    c->slab_bytes = off;
+    hipError_t e = hipMalloc(&c->slab, c->slab_bytes);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        delete c;
+        return e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP;
+    }
+    char *p = (char *)c->slab;
+    S.Q = p + oQ; S.Kt = p + oKt; S.Vt = p + oVt;
+    S.VT = mfma ? (bf16_t *)(p + oVT) : nullptr;
+    S.pm = (float *)(p + opm); S.pl = (float *)(p + opl); S.po = (float *)(p + opo);
+    S.rinv = (float *)(p + orinv);
+    S.attn_cat = (float *)(p + ocat); S.h = (float *)(p + oh); S.u = (float *)(p + ou); S.z = (float *)(p + oz);
+    S.kv_raw = (float *)(p + okv);
+
+    rt_status ps = persistent_create(c->persist, c->cfg, D);
+    if (ps != RT_OK && (cfg->flags & RT_FLAG_ENGINE_PERSISTENT)) {
+        (void)hipFree(c->slab);
+        delete c;
+        return ps;
+    }
+    *out = c;
+    return RT_OK;
+}
+
+rt_status rt_destroy(rt_ctx *c)
+{
+    if (!c) return RT_OK;
+    (void)hipSetDevice(c->cfg.device);
+    if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
+    if (c->capture_stream) (void)hipStreamDestroy(c->capture_stream);
+    persistent_destroy(c->persist);
+    hipError_t e = hipFree(c->slab);
+    delete c;
+    return e == hipSuccess ? RT_OK : RT_ERR_HIP;
+}
+
+const char *rt_last_error(const rt_ctx *c) { return c ? c->err.c_str() : kNoCtx; }
+uint64_t rt_workspace_bytes(const rt_ctx *c) { return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) : 0; }
+const char *rt_engine_name(const rt_ctx *c) { return c ? c->engine.c_str() : ""; }
+
+int32_t rt_device_wait_expired(rt_ctx *c)
+{
+    if (!c) return 0;
+    const int v = persistent_wait_expired(c->persist);
+    if (v) {
+        c->broken = true;
+        c->err = "a bounded device-side wait expired in the persistent engine";
+    }
+    return v;
+}
+
+}  // extern "C"
+
+static bool ranges_overlap(const void *a, size_t na, const void *b, size_t nb)
+{
+    const char *pa = (const char *)a, *pb = (const char *)b;
+    return pa < pb + nb && pb < pa + na;
+}
+
+static rt_status check_weights(rt_ctx *c, const rt_layer_weights *w)
+{
+    if (!w || !w->Wq || !w->Wk || !w->Wv || !w->Wo || !w->W1 || !w->W2)
+        return fail(c, RT_ERR_INVALID_ARG, "null weight pointer%s");
+    return RT_OK;
+}
+
+static Weights to_weights(const rt_layer_weights *w)
+{
+    Weights W;
+    W.Wq = w->Wq; W.Wk = w->Wk; W.Wv = w->Wv; W.Wo = w->Wo; W.W1 = w->W1; W.W2 = w->W2;
+    W.g_attn = w->g_attn; W.g_mlp = w->g_mlp; W.g_kv = w->g_kv ? w->g_kv : w->g_attn; W.g_q = w->g_q; W.g_k = w->g_k;
+    return W;
+}
+
+#define RT_TRY(expr, where)                                   \
+    do {                                                      \
+        hipError_t _e = (expr);                               \
+        if (_e != hipSuccess) return fail_hip(c, _e, where);  \
+    } while (0)
+
+// One position of the sequential loop as separate launches (base case of Algorithm 1).
+template <typename T>
+static rt_status enqueue_position(rt_ctx *c, const LayerDims &D, const Weights &W, const void *x_t, size_t x_stride_b,
+                                  void *y_t, size_t y_stride_b, void *K, void *V, int t, int q_row, int n_splits,
+                                  bool write_vt)
+{
+    hipStream_t st = c->stream;
+    RT_TRY(Launch<T>::merge(D, c->S, K, V, t, q_row, n_splits, st), "merge");
+    RT_TRY(Launch<T>::gemv_wo(D, W, c->S, x_t, x_stride_b, st), "gemv_wo");
+    RT_TRY(Launch<T>::gemv_w1(D, W, c->S, st), "gemv_w1");
+    RT_TRY(Launch<T>::gemv_w2(D, W, c->S, y_t, y_stride_b, st), "gemv_w2");
+    RT_TRY(Launch<T>::gemv_kv(D, W, c->S, st), "gemv_kv");
+    RT_TRY(Launch<T>::finalize_kv(D, W, c->S, K, V, t, write_vt, st), "finalize_kv");
+    return RT_OK;
+}
+
+template <typename T>
+static rt_status enqueue_prefill_stepwise(rt_ctx *c, const LayerDims &D, const Weights &W, const void *x, void *y, void *K,
+                                          void *V)
+{
+    hipStream_t st = c->stream;
+    const size_t E = sizeof(T);
+    RT_TRY(Launch<T>::prepass(D, W, c->S, x, D.B, D.N, c->use_mfma, st), "prepass");
+    for (int t = 0; t < D.N; ++t) {
+        rt_status s = enqueue_position<T>(c, D, W, (const char *)x + (size_t)t * D.d * E, (size_t)D.N * D.d,
+                                          (char *)y + (size_t)t * D.d * E, (size_t)D.N * D.d, K, V, t, t, -1, c->use_mfma);
+        if (s != RT_OK) return s;
+        const int t1 = t + 1;
+        const int P = t1 & -t1;
+        if (P >= D.p_min && t1 < D.N) {
+            const int nq = (P < D.N - t1) ? P : D.N - t1;
+            RT_TRY(Launch<T>::cross(D, c->S, K, V, t1, P, nq, c->use_mfma, st), "cross");
+        }
+    }
+    return RT_OK;
+}
+
+template <typename T>
+static rt_status prefill_stepwise(rt_ctx *c, const LayerDims &D, const rt_layer_weights *w, const void *x, void *y, void *K,
+                                  void *V)
+{
+    const Weights W = to_weights(w);
+    if (!(c->cfg.flags & RT_FLAG_HIP_GRAPH)) {
+        c->engine = "stepwise";
+        return enqueue_prefill_stepwise<T>(c, D, W, x, y, K, V);
+    }
+    c->engine = "stepwise+graph";
+    rt_ctx::GraphKey key;
+    memset(&key, 0, sizeof(key));
+    key.x = x; key.y = y; key.K = K; key.V = V; key.w = *w; key.B = D.B; key.N = D.N; key.kv_cap = D.kv_cap;
+    if (!c->graph_exec || memcmp(&key, &c->graph_key, sizeof(key)) != 0) {
+        if (c->graph_exec) { (void)hipGraphExecDestroy(c->graph_exec); c->graph_exec = nullptr; }
+        // Record on a private stream (default priority), replay on the caller's stream.
+        if (!c->capture_stream)
+            RT_TRY(hipStreamCreateWithFlags(&c->capture_stream, hipStreamNonBlocking), "hipStreamCreateWithFlags");
+        hipStream_t user = c->stream;
+        c->stream = c->capture_stream;
+        hipError_t e = hipStreamBeginCapture(c->capture_stream, hipStreamCaptureModeThreadLocal);
+        if (e != hipSuccess) { c->stream = user; return fail_hip(c, e, "hipStreamBeginCapture"); }
+        rt_status s = enqueue_prefill_stepwise<T>(c, D, W, x, y, K, V);
+        c->stream = user;
+        hipGraph_t g = nullptr;
+        e = hipStreamEndCapture(c->capture_stream, &g);
+        if (s != RT_OK) { if (g) (void)hipGraphDestroy(g); return s; }
+        if (e != hipSuccess) return fail_hip(c, e, "hipStreamEndCapture");
+        e = hipGraphInstantiate(&c->graph_exec, g, nullptr, nullptr, 0);
+        (void)hipGraphDestroy(g);
+        if (e != hipSuccess) { c->graph_exec = nullptr; return fail_hip(c, e, "hipGraphInstantiate"); }
+        c->graph_key = key;
+    }
+    RT_TRY(hipGraphLaunch(c->graph_exec, c->stream), "hipGraphLaunch");
+    return RT_OK;
+}
+
+extern "C" rt_status rt_layer_prefill(rt_ctx *c, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, void *y,
+                                      void *K, void *V, int32_t kv_cap)
+{
+    if (!c) return RT_ERR_INVALID_ARG;
+    if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
+    rt_status s = check_weights(c, w);
+    if (s != RT_OK) return s;
+    if (!x || !y || !K || !V) return fail(c, RT_ERR_INVALID_ARG, "null tensor pointer%s");
+    if (B < 1 || B > c->cfg.max_batch) return fail(c, RT_ERR_INVALID_ARG, "B out of range [1, max_batch]%s");
+    if (N < 1 || N > c->cfg.max_seq) return fail(c, RT_ERR_INVALID_ARG, "N out of range [1, max_seq]%s");
+    if (kv_cap < N) return fail(c, RT_ERR_INVALID_ARG, "kv_cap < N%s");
+    const size_t E = c->cfg.dtype == RT_BF16 ? 2 : 4;
+    const size_t xb = (size_t)B * N * c->cfg.d_model * E, kvb = (size_t)kv_cap * B * c->cfg.d_model * E;
+    if (ranges_overlap(x, xb, y, xb)) return fail(c, RT_ERR_INVALID_ARG, "x and y overlap%s");
+    if (ranges_overlap(K, kvb, V, kvb) || ranges_overlap(K, kvb, y, xb) || ranges_overlap(V, kvb, y, xb) ||
+        ranges_overlap(K, kvb, x, xb) || ranges_overlap(V, kvb, x, xb))
+        return fail(c, RT_ERR_INVALID_ARG, "K, V, x, y must not overlap%s");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+
+    LayerDims D = c->base;
+    D.B = B; D.N = N; D.kv_cap = kv_cap;
+    const bool want_stepwise = (c->cfg.flags & RT_FLAG_ENGINE_STEPWISE) != 0;
+    if (!want_stepwise && persistent_supported(c->persist, D)) {
+        c->engine = "persistent";
+        const Weights W = to_weights(w);
+        hipError_t e;
+        if (c->cfg.dtype == RT_BF16) e = Launch<bf16_t>::prepass(D, W, c->S, x, B, N, c->use_mfma, c->stream);
+        else e = Launch<float>::prepass(D, W, c->S, x, B, N, false, c->stream);
+        if (e != hipSuccess) return fail_hip(c, e, "prepass");
+        std::string perr;
+        s = persistent_prefill(c->persist, D, W, c->S, x, y, K, V, c->stream, perr);
+        if (s != RT_OK) { c->err = perr; if (s == RT_ERR_HIP) c->broken = true; }
+        return s;
+    }
+    if (c->cfg.flags & RT_FLAG_ENGINE_PERSISTENT)
+        return fail(c, RT_ERR_UNSUPPORTED, "the persistent engine does not cover this shape%s");
+    if (c->cfg.dtype == RT_BF16) return prefill_stepwise<bf16_t>(c, D, w, x, y, K, V);
+    return prefill_stepwise<float>(c, D, w, x, y, K, V);
+}
+
+template <typename T>
+static rt_status decode_impl(rt_ctx *c, const LayerDims &D, const rt_layer_weights *w, const void *x_t, int t, void *y_t,
+                             void *K, void *V)
+{
+    const Weights W = to_weights(w);
+    hipStream_t st = c->stream;
+    RT_TRY(Launch<T>::prepass(D, W, c->S, x_t, D.B, 1, false, st), "prepass");
+    const int chunk = 256;
+    const int nsplit = (t + chunk - 1) / chunk;
+    if (nsplit > 0) RT_TRY(Launch<T>::decode_split(D, c->S, K, V, t, chunk, nsplit, st), "decode_split");
+    return enqueue_position<T>(c, D, W, x_t, (size_t)D.d, y_t, (size_t)D.d, K, V, t, 0, nsplit, false);
+}
+
+extern "C" rt_status rt_decode_step(rt_ctx *c, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t, void *y_t,
+                                    void *K, void *V, int32_t kv_cap)
+{
+    if (!c) return RT_ERR_INVALID_ARG;
+    if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
+    rt_status s = check_weights(c, w);
+    if (s != RT_OK) return s;
+    if (!x_t || !y_t || !K || !V) return fail(c, RT_ERR_INVALID_ARG, "null tensor pointer%s");
+    if (B < 1 || B > c->cfg.max_batch) return fail(c, RT_ERR_INVALID_ARG, "B out of range [1, max_batch]%s");
+    if (t < 0 || t >= kv_cap) return fail(c, RT_ERR_INVALID_ARG, "t out of range [0, kv_cap)%s");
+    if ((t + 255) / 256 > c->S.slots) return fail(c, RT_ERR_INVALID_ARG, "t too large for this context's max_seq%s");
+    const size_t E = c->cfg.dtype == RT_BF16 ? 2 : 4;
+    const size_t xb = (size_t)B * c->cfg.d_model * E;
+    if (ranges_overlap(x_t, xb, y_t, xb)) return fail(c, RT_ERR_INVALID_ARG, "x_t and y_t overlap%s");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+    LayerDims D = c->base;
+    D.B = B; D.N = 1; D.kv_cap = kv_cap;
+    c->engine = "stepwise";
+    if (c->cfg.dtype == RT_BF16) return decode_impl<bf16_t>(c, D, w, x_t, t, y_t, K, V);
+    return decode_impl<float>(c, D, w, x_t, t, y_t, K, V);
+}

@@ -1,0 +1,121 @@
+// Shared device helpers and the internal launch interface of the RT layer library (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rt {
+
+constexpr int kHeadDim = 64;   // one head = one 64-lane wavefront
+constexpr int kBatchTile = 8;  // batch rows one small-M kernel instance handles
+
+typedef uint16_t bf16_t;  // raw bits
+
+// ---------------------------------------------------------------- storage conversions
+__device__ __forceinline__ float bf16_to_f32(bf16_t v) { return __uint_as_float(((uint32_t)v) << 16); }
+__device__ __forceinline__ bf16_t f32_to_bf16(float f)
+{  // round to nearest, ties to even (inputs are finite on this path)
+    uint32_t u = __float_as_uint(f);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ float to_f32(float v) { return v; }
+__device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
+template <typename T> __device__ __forceinline__ T from_f32(float f);
+template <> __device__ __forceinline__ float from_f32<float>(float f) { return f; }
+template <> __device__ __forceinline__ bf16_t from_f32<bf16_t>(float f) { return f32_to_bf16(f); }
+
+// 8 consecutive elements -> 8 floats (16-byte aligned for bf16, 32-byte for f32)
+__device__ __forceinline__ void load8(const float *p, float *o)
+{
+    const float4 a = *reinterpret_cast<const float4 *>(p);
+    const float4 b = *reinterpret_cast<const float4 *>(p + 4);
+    o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w; o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+}
+__device__ __forceinline__ void load8(const bf16_t *p, float *o)
+{
+    const uint4 a = *reinterpret_cast<const uint4 *>(p);
+    o[0] = __uint_as_float(a.x << 16); o[1] = __uint_as_float(a.x & 0xFFFF0000u);
+    o[2] = __uint_as_float(a.y << 16); o[3] = __uint_as_float(a.y & 0xFFFF0000u);
+    o[4] = __uint_as_float(a.z << 16); o[5] = __uint_as_float(a.z & 0xFFFF0000u);
+    o[6] = __uint_as_float(a.w << 16); o[7] = __uint_as_float(a.w & 0xFFFF0000u);
+}
+
+// ---------------------------------------------------------------- wavefront (64 lanes) reductions
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+    return v;
+}
+__device__ __forceinline__ float lane_bcast(float v, int lane)
+{  // value of a wave-uniform lane index, read without going through LDS
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+__device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
+
+// ---------------------------------------------------------------- launch parameters
+struct LayerDims {
+    int B, N, d, H, F;
+    int kv_cap;
+    int p_min, log2_pmin;
+    float alpha, scale, eps;
+    int norm_free;
+};
+
+struct Weights {
+    const void *Wq, *Wk, *Wv, *Wo, *W1, *W2;
+    const void *g_attn, *g_mlp, *g_kv, *g_q, *g_k;
+};
+
+// Scratch owned by a context.  Partial softmax states are stored once per (level, query):
+//   pm, pl : [levels][slots][B*H]        po : [levels][slots][B*H][64]     (fp32)
+struct Scratch {
+    void *Q, *Kt, *Vt;   // [N][B][H][64] storage dtype: queries and temporary pairs
+    bf16_t *VT;          // [B*H][64][vt_stride] transposed copy of the persistent values (bf16 MFMA path)
+    int vt_stride;
+    float *pm, *pl, *po;
+    int levels, slots;
+    float *rinv;         // [B*N] 1/rms of the input rows
+    float *attn_cat;     // [B][d] concatenated head outputs of the current position
+    float *h;            // [B][d]
+    float *u;            // [B][F]
+    float *z;            // [B][d]
+    float *kv_raw;       // [B][2d]
+};
+
+__host__ __device__ __forceinline__ size_t partial_index(int level_rel, int slot, int slots, int BH, int bh)
+{
+    return ((size_t)level_rel * slots + slot) * BH + bh;
+}
+// compact slot of 0-based query i0 at absolute level l (bit l of i0 must be set)
+__host__ __device__ __forceinline__ int partial_slot(int l, int i0) { return ((i0 >> (l + 1)) << l) | (i0 & ((1 << l) - 1)); }
+
+// ---------------------------------------------------------------- launchers (one per kernel family)
+template <typename T> struct Launch {
+    // x [Bc][Nc][d] -> Q, Kt, Vt rows (n*Bc + b)
+    static hipError_t prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
+                              bool mfma, hipStream_t st);
+    static hipError_t merge(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int q_row,
+                            int n_decode_splits, hipStream_t st);
+    static hipError_t gemv_wo(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride_b,
+                              hipStream_t st);
+    static hipError_t gemv_w1(const LayerDims &D, const Weights &W, const Scratch &S, hipStream_t st);
+    static hipError_t gemv_w2(const LayerDims &D, const Weights &W, const Scratch &S, void *y_t, size_t y_stride_b,
+                              hipStream_t st);
+    static hipError_t gemv_kv(const LayerDims &D, const Weights &W, const Scratch &S, hipStream_t st);
+    static hipError_t finalize_kv(const LayerDims &D, const Weights &W, const Scratch &S, void *K, void *V, int t,
+                                  bool write_vt, hipStream_t st);
+    static hipError_t cross(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t1, int P, int nq,
+                            bool mfma, hipStream_t st);
+    static hipError_t decode_split(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int chunk,
+                                   int nsplit, hipStream_t st);
+};
+
+}  // namespace rt

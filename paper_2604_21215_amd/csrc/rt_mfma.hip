@@ -1,0 +1,267 @@
+// bf16 MFMA kernels (gfx950, v_mfma_f32_16x16x32_bf16): the pre-pass projection GEMM and the
+// cross-block UpdateTile (Appendix C, Algorithm 2) as a flash-style contraction.
+//
+// Operand layout of v_mfma_f32_16x16x32_bf16 (D = A*B + C, A 16x32, B 32x16, 64 lanes, g = lane/16):
+//   A: lane holds A[row = lane%16][k = 8g .. 8g+7]          (8 bf16 = 16 bytes)
+//   B: lane holds B[k = 8g .. 8g+7][col = lane%16]
+//   D: lane holds D[row = 4g + r][col = lane%16], r = 0..3   (4 fp32)
+// Both operands want the contraction index contiguous per lane, which is how x, the weights, q and k
+// rows are stored, so those fragments are loaded straight from global memory.
+#include "rt_common.h"
+
+namespace rt {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+union Frag {
+    uint4 u;
+    uint2 h[2];
+    bf16x8_t v;
+};
+
+__device__ __forceinline__ f32x4_t mfma16(const Frag &a, const Frag &b, f32x4_t c)
+{
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
+}
+
+// =============================================================================================
+// Pre-pass GEMM: C[m][c] = sum_k (x[m][k] g_attn[k]) Wqkv[c][k], rows scaled by rinv[m], then qkRMS
+// per head for the q and k_tmp parts.  Block tile 128 x 128, 4 wavefronts as 2 x 2, each 64 x 64
+// (= one head of one output).  grid (ceil(M/128), ceil(3H/2)).
+// =============================================================================================
+__global__ __launch_bounds__(256) void prepass_mfma_kernel(const bf16_t *__restrict__ x, const float *__restrict__ rinv,
+                                                           const bf16_t *__restrict__ Wq, const bf16_t *__restrict__ Wk,
+                                                           const bf16_t *__restrict__ Wv, const bf16_t *__restrict__ g_attn,
+                                                           const bf16_t *__restrict__ g_q, const bf16_t *__restrict__ g_k,
+                                                           bf16_t *__restrict__ Q, bf16_t *__restrict__ Kt,
+                                                           bf16_t *__restrict__ Vt, int Bc, int Nc, int d, int H, float eps,
+                                                           int norm_free)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l16 = lane & 15, g = lane >> 4;
+    const int M = Bc * Nc;
+    const int m0 = blockIdx.x * 128 + wm * 64;
+    const int hb = blockIdx.y * 2 + wn;  // head slot in [q heads | k heads | v heads]
+    if (hb >= 3 * H) return;             // no barriers in this kernel
+    const int which = hb / H, h = hb % H;
+    const bf16_t *W = (which == 0 ? Wq : (which == 1 ? Wk : Wv)) + (size_t)h * kHeadDim * d;
+
+    f32x4_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    const bf16_t *arow[4];
+    const bf16_t *brow[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        arow[i] = x + (size_t)min(m0 + i * 16 + l16, M - 1) * d + 8 * g;
+        brow[i] = W + (size_t)(i * 16 + l16) * d + 8 * g;
+    }
+    const bool use_gain = (g_attn != nullptr) && !norm_free;
+
+    for (int k0 = 0; k0 < d; k0 += 32) {
+        Frag a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[i].u = *reinterpret_cast<const uint4 *>(arow[i] + k0);
+            b[i].u = *reinterpret_cast<const uint4 *>(brow[i] + k0);
+        }
+        if (use_gain) {
+            float gg[8];
+            load8(g_attn + k0 + 8 * g, gg);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                float xv[8];
+                xv[0] = __uint_as_float(a[i].u.x << 16); xv[1] = __uint_as_float(a[i].u.x & 0xFFFF0000u);
+                xv[2] = __uint_as_float(a[i].u.y << 16); xv[3] = __uint_as_float(a[i].u.y & 0xFFFF0000u);
+                xv[4] = __uint_as_float(a[i].u.z << 16); xv[5] = __uint_as_float(a[i].u.z & 0xFFFF0000u);
+                xv[6] = __uint_as_float(a[i].u.w << 16); xv[7] = __uint_as_float(a[i].u.w & 0xFFFF0000u);
+                a[i].u.x = pack_bf16(xv[0] * gg[0], xv[1] * gg[1]);
+                a[i].u.y = pack_bf16(xv[2] * gg[2], xv[3] * gg[3]);
+                a[i].u.z = pack_bf16(xv[4] * gg[4], xv[5] * gg[5]);
+                a[i].u.w = pack_bf16(xv[6] * gg[6], xv[7] * gg[7]);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) acc[i][j] = mfma16(a[i], b[j], acc[i][j]);
+    }
+
+    const bf16_t *gn = which == 0 ? g_q : g_k;
+    bf16_t *dst = which == 0 ? Q : (which == 1 ? Kt : Vt);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            const int m = m0 + i * 16 + 4 * g + r;
+            const float rs = norm_free ? 1.f : rinv[min(m, M - 1)];
+            float v[4];
+            float ss = 0.f;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) { v[j] = acc[i][j][r] * rs; ss = fmaf(v[j], v[j], ss); }
+            float sc = 1.f;
+            if (which < 2 && !norm_free) {
+#pragma unroll
+                for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);  // the 16 lanes that share g
+                sc = rsqrtf(ss / (float)kHeadDim + eps);
+            }
+            if (m < M) {
+                const int b = m / Nc, n = m % Nc;
+                bf16_t *o = dst + ((size_t)n * Bc + b) * d + h * kHeadDim + l16;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    float val = v[j] * sc;
+                    if (which < 2 && !norm_free && gn) val *= bf16_to_f32(gn[h * kHeadDim + j * 16 + l16]);
+                    o[j * 16] = f32_to_bf16(val);
+                }
+            }
+        }
+    }
+}
+
+hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
+                               hipStream_t st)
+{
+    const int M = Bc * Nc;
+    hipLaunchKernelGGL(prepass_mfma_kernel, dim3((M + 127) / 128, (3 * D.H + 1) / 2), dim3(256), 0, st, (const bf16_t *)x,
+                       S.rinv, (const bf16_t *)W.Wq, (const bf16_t *)W.Wk, (const bf16_t *)W.Wv, (const bf16_t *)W.g_attn,
+                       (const bf16_t *)W.g_q, (const bf16_t *)W.g_k, (bf16_t *)S.Q, (bf16_t *)S.Kt, (bf16_t *)S.Vt, Bc, Nc,
+                       D.d, D.H, D.eps, D.norm_free);
+    return hipGetLastError();
+}
+
+// =============================================================================================
+// Cross-block UpdateTile: queries [t1, t1+nq) against keys [t1-P, t1) for every (b, h); P is a
+// multiple of 32.  The transposed products are formed so that the softmax state of a query lives in
+// one lane column:
+//     S^T[key][query] = K Q^T              (A = K rows, B = Q rows)
+//     O^T[dh][query] += V^T P^T            (A = V^T rows from the transposed value copy, B = P^T)
+// P^T comes out of the first product already in the B-operand layout once the 32 keys of a chunk
+// are assigned to contraction slots as  slot 8g+e  <->  key 4g+e (e < 4), 16+4g+(e-4) (e >= 4);
+// the V^T fragment is gathered with the same assignment (two 8-byte loads).
+// A wavefront owns 32 queries (two 16-query tiles); a block is 4 wavefronts = 128 queries.
+// grid (ceil(nq/128), B*H).
+// =============================================================================================
+__global__ __launch_bounds__(256) void cross_mfma_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                         const bf16_t *__restrict__ VT, int vt_stride,
+                                                         float *__restrict__ pm, float *__restrict__ pl,
+                                                         float *__restrict__ po, int BH, int t1, int P, int nq, int level,
+                                                         int level_rel, int slots, float scale)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+    const int bh = blockIdx.y;
+    const int q0 = blockIdx.x * 128 + wave * 32;  // first query of this wavefront, relative to t1
+    if (q0 >= nq) return;                         // no barriers in this kernel
+    const size_t rs = (size_t)BH * kHeadDim;
+
+    Frag bq[2][2];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        const int qi = min(q0 + qt * 16 + l16, nq - 1);
+        const bf16_t *qrow = Q + (size_t)(t1 + qi) * rs + (size_t)bh * kHeadDim + 8 * g;
+        bq[qt][0].u = *reinterpret_cast<const uint4 *>(qrow);
+        bq[qt][1].u = *reinterpret_cast<const uint4 *>(qrow + 32);
+    }
+    float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.f, 0.f};
+    f32x4_t O[2][4];
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt)
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk) O[qt][blk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    const bf16_t *kbase = K + (size_t)(t1 - P) * rs + (size_t)bh * kHeadDim + 8 * g;
+    const bf16_t *vbase = VT + ((size_t)bh * kHeadDim + l16) * vt_stride + (t1 - P) + 4 * g;
+
+    for (int kc = 0; kc < P; kc += 32) {
+        f32x4_t S[2][2];
+#pragma unroll
+        for (int kt = 0; kt < 2; ++kt) {
+            const bf16_t *krow = kbase + (size_t)(kc + kt * 16 + l16) * rs;
+            Frag a0, a1;
+            a0.u = *reinterpret_cast<const uint4 *>(krow);
+            a1.u = *reinterpret_cast<const uint4 *>(krow + 32);
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) {
+                f32x4_t s = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                s = mfma16(a0, bq[qt][0], s);
+                s = mfma16(a1, bq[qt][1], s);
+                S[qt][kt] = s;
+            }
+        }
+        Frag bp[2];
+#pragma unroll
+        for (int qt = 0; qt < 2; ++qt) {
+            float s[8];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) { s[r] = S[qt][0][r] * scale; s[4 + r] = S[qt][1][r] * scale; }
+            float mx = s[0];
+#pragma unroll
+            for (int e = 1; e < 8; ++e) mx = fmaxf(mx, s[e]);
+            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+            const float m_new = fmaxf(m[qt], mx);
+            const float resc = __expf(m[qt] - m_new);
+            float ps = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) { s[e] = __expf(s[e] - m_new); ps += s[e]; }
+            lsum[qt] = lsum[qt] * resc + ps;
+            m[qt] = m_new;
+#pragma unroll
+            for (int blk = 0; blk < 4; ++blk) O[qt][blk] *= resc;
+            bp[qt].u.x = pack_bf16(s[0], s[1]);
+            bp[qt].u.y = pack_bf16(s[2], s[3]);
+            bp[qt].u.z = pack_bf16(s[4], s[5]);
+            bp[qt].u.w = pack_bf16(s[6], s[7]);
+        }
+#pragma unroll
+        for (int blk = 0; blk < 4; ++blk) {
+            const bf16_t *vrow = vbase + (size_t)(blk * 16) * vt_stride + kc;
+            Frag av;
+            av.h[0] = *reinterpret_cast<const uint2 *>(vrow);
+            av.h[1] = *reinterpret_cast<const uint2 *>(vrow + 16);
+#pragma unroll
+            for (int qt = 0; qt < 2; ++qt) O[qt][blk] = mfma16(av, bp[qt], O[qt][blk]);
+        }
+    }
+
+#pragma unroll
+    for (int qt = 0; qt < 2; ++qt) {
+        float l = lsum[qt];
+        l += __shfl_xor(l, 16, 64);
+        l += __shfl_xor(l, 32, 64);
+        const int qi = q0 + qt * 16 + l16;
+        if (qi < nq) {
+            const int i0 = t1 + qi;
+            const size_t idx = partial_index(level_rel, partial_slot(level, i0), slots, BH, bh);
+            if (g == 0) { pm[idx] = m[qt]; pl[idx] = l; }
+            float *orow = po + idx * kHeadDim + 4 * g;
+#pragma unroll
+            for (int blk = 0; blk < 4; ++blk)
+                *reinterpret_cast<float4 *>(orow + blk * 16) =
+                    make_float4(O[qt][blk][0], O[qt][blk][1], O[qt][blk][2], O[qt][blk][3]);
+        }
+    }
+}
+
+hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, hipStream_t st)
+{
+    int level = 0;
+    while ((1 << level) < P) ++level;
+    hipLaunchKernelGGL(cross_mfma_kernel, dim3((nq + 127) / 128, D.B * D.H), dim3(256), 0, st, (const bf16_t *)S.Q,
+                       (const bf16_t *)K, S.VT, S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, level,
+                       level - D.log2_pmin, S.slots, D.scale);
+    return hipGetLastError();
+}
+
+}  // namespace rt

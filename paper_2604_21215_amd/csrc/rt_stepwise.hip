@@ -1,0 +1,491 @@
+// Plain-ALU kernels of the RT layer: one launch per phase of a position.
+//
+// These cover every storage dtype (fp32 and bf16, fp32 arithmetic throughout) and any sequence
+// length.  They are the per-position engine ("stepwise"), the decode step, and the fp32 path of the
+// cross-block update.  The MFMA kernels live in rt_mfma.hip, the single-launch engine in
+// rt_persistent.hip.
+#include "rt_common.h"
+
+namespace rt {
+
+// =============================================================================================
+// One query against a run of KV rows, online softmax (Appendix C, Algorithm 2, for one query row).
+// A wavefront owns one (query, batch row, head): lane c holds q[c] and o[c]; within a chunk of
+// 64 keys lane j owns key j.  m, l are wave-uniform.
+// =============================================================================================
+template <typename T>
+__device__ __forceinline__ void attend_keys(float q, const T *__restrict__ Kb, const T *__restrict__ Vb,
+                                            size_t row_stride, int nkeys, float scale, float &m, float &l, float &o)
+{
+    const int lane = threadIdx.x & 63;
+    for (int k0 = 0; k0 < nkeys; k0 += 64) {
+        const int j = k0 + lane;
+        const bool valid = j < nkeys;
+        const T *krow = Kb + (size_t)(valid ? j : nkeys - 1) * row_stride;
+        float acc = 0.f;
+#pragma unroll
+        for (int c8 = 0; c8 < 8; ++c8) {
+            float kk[8];
+            load8(krow + c8 * 8, kk);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], acc);
+        }
+        const float logit = valid ? acc * scale : -INFINITY;
+        const float m_new = fmaxf(m, wave_max(logit));
+        const float resc = expf(m - m_new);  // exp(-inf) = 0 on the first chunk
+        const float p = valid ? expf(logit - m_new) : 0.f;
+        l = l * resc + wave_sum(p);
+        float on = o * resc;
+        const int cnt = min(64, nkeys - k0);
+        for (int jj = 0; jj < cnt; ++jj) {
+            const float pj = lane_bcast(p, jj);
+            on = fmaf(pj, to_f32(Vb[(size_t)(k0 + jj) * row_stride + lane]), on);
+        }
+        o = on;
+        m = m_new;
+    }
+}
+
+// =============================================================================================
+// Cross-block update, plain-ALU form: queries [t1, t1+nq) against keys [t1-P, t1) of every (b, h);
+// the partial state (m, l, o) is written once into the slot of (level log2 P, query).
+// grid (nq, B*H), block 64.
+// =============================================================================================
+template <typename T>
+__global__ __launch_bounds__(64) void cross_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                           const T *__restrict__ V, float *__restrict__ pm,
+                                                           float *__restrict__ pl, float *__restrict__ po, int BH, int t1,
+                                                           int P, int level, int level_rel, int slots, float scale)
+{
+    const int lane = threadIdx.x;
+    const int i0 = t1 + blockIdx.x;
+    const int bh = blockIdx.y;
+    const size_t rs = (size_t)BH * kHeadDim;
+    const float q = to_f32(Q[(size_t)i0 * rs + (size_t)bh * kHeadDim + lane]);
+    float m = -INFINITY, l = 0.f, o = 0.f;
+    attend_keys<T>(q, K + (size_t)(t1 - P) * rs + (size_t)bh * kHeadDim, V + (size_t)(t1 - P) * rs + (size_t)bh * kHeadDim,
+                   rs, P, scale, m, l, o);
+    const size_t idx = partial_index(level_rel, partial_slot(level, i0), slots, BH, bh);
+    if (lane == 0) { pm[idx] = m; pl[idx] = l; }
+    po[idx * kHeadDim + lane] = o;
+}
+
+// Decode: keys [split*chunk, min(t, (split+1)*chunk)) of the cache against the single query row 0.
+// grid (nsplit, B*H), block 64; the partial goes to slot `split` of relative level 0.
+template <typename T>
+__global__ __launch_bounds__(64) void decode_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                          const T *__restrict__ V, float *__restrict__ pm,
+                                                          float *__restrict__ pl, float *__restrict__ po, int BH, int t,
+                                                          int chunk, int slots, float scale)
+{
+    const int lane = threadIdx.x;
+    const int split = blockIdx.x, bh = blockIdx.y;
+    const size_t rs = (size_t)BH * kHeadDim;
+    const int k_lo = split * chunk, k_hi = min(t, k_lo + chunk);
+    const float q = to_f32(Q[(size_t)bh * kHeadDim + lane]);
+    float m = -INFINITY, l = 0.f, o = 0.f;
+    attend_keys<T>(q, K + (size_t)k_lo * rs + (size_t)bh * kHeadDim, V + (size_t)k_lo * rs + (size_t)bh * kHeadDim, rs,
+                   k_hi - k_lo, scale, m, l, o);
+    const size_t idx = partial_index(0, split, slots, BH, bh);
+    if (lane == 0) { pm[idx] = m; pl[idx] = l; }
+    po[idx * kHeadDim + lane] = o;
+}
+
+// =============================================================================================
+// Base case, part 1: finish the attention output of position t (0-based).
+//   start from the temporary pair (Algorithm 1, "temporary self contribution"), fold in the stored
+//   partial of every level whose bit is set in t, then the direct window of the last (t mod p_min)
+//   persistent rows; a = o / l.   grid B*H, block 64.
+//   Decode mode (n_splits >= 0): the partials are slots 0..n_splits-1 of relative level 0, no window.
+// =============================================================================================
+template <typename T>
+__global__ __launch_bounds__(64) void merge_kernel(const T *__restrict__ Q, const T *__restrict__ Kt,
+                                                   const T *__restrict__ Vt, const T *__restrict__ K,
+                                                   const T *__restrict__ V, const float *__restrict__ pm,
+                                                   const float *__restrict__ pl, const float *__restrict__ po,
+                                                   float *__restrict__ attn_cat, int BH, int H, int t, int q_row,
+                                                   int p_min, int log2_pmin, int levels, int slots, int n_splits,
+                                                   float scale)
+{
+    const int lane = threadIdx.x;
+    const int bh = blockIdx.x;
+    const size_t rs = (size_t)BH * kHeadDim;
+    const size_t qoff = (size_t)q_row * rs + (size_t)bh * kHeadDim + lane;
+    const float q = to_f32(Q[qoff]);
+    float m = scale * wave_sum(q * to_f32(Kt[qoff]));
+    float l = 1.f;
+    float o = to_f32(Vt[qoff]);
+    if (n_splits >= 0) {
+        for (int s = 0; s < n_splits; ++s) {
+            const size_t idx = partial_index(0, s, slots, BH, bh);
+            const float pmv = pm[idx], plv = pl[idx], pov = po[idx * kHeadDim + lane];
+            const float m_new = fmaxf(m, pmv);
+            const float e1 = expf(m - m_new), e2 = expf(pmv - m_new);
+            l = l * e1 + plv * e2;
+            o = o * e1 + pov * e2;
+            m = m_new;
+        }
+    } else {
+        for (int lr = 0; lr < levels; ++lr) {
+            const int lv = lr + log2_pmin;
+            if ((t >> lv) & 1) {
+                const size_t idx = partial_index(lr, partial_slot(lv, t), slots, BH, bh);
+                const float pmv = pm[idx], plv = pl[idx], pov = po[idx * kHeadDim + lane];
+                const float m_new = fmaxf(m, pmv);
+                const float e1 = expf(m - m_new), e2 = expf(pmv - m_new);
+                l = l * e1 + plv * e2;
+                o = o * e1 + pov * e2;
+                m = m_new;
+            }
+        }
+        const int w = t & (p_min - 1);
+        if (w > 0) {
+            const size_t base = (size_t)(t - w) * rs + (size_t)bh * kHeadDim;
+            attend_keys<T>(q, K + base, V + base, rs, w, scale, m, l, o);
+        }
+    }
+    const int b = bh / H, h = bh % H;
+    attn_cat[(size_t)b * H * kHeadDim + h * kHeadDim + lane] = o / l;
+}
+
+// =============================================================================================
+// Small-M matrix products of the base case:  out[b][o] = epilogue( sum_k W[o][k] * in[b][k] ),
+// b < Bn <= 8.  256 threads = 4 wavefronts, each wavefront owns 4 output rows; the (optionally
+// RMS-normalised) input rows are staged in LDS in chunks of 1024 columns.
+// =============================================================================================
+enum Epi { EPI_WO = 0, EPI_W1 = 1, EPI_W2 = 2, EPI_KV = 3 };
+
+constexpr int kGemvRows = 4;      // output rows per wavefront
+constexpr int kGemvChunk = 1024;  // staged input columns
+
+template <typename T, int EPI>
+__global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, const T *__restrict__ Wb, int n_first,
+                                                   int n_out, int n_in, const float *__restrict__ in, int Bn,
+                                                   const T *__restrict__ gain, float eps, int do_norm, float alpha,
+                                                   const T *__restrict__ res_T, size_t res_stride,
+                                                   const float *__restrict__ res_f, float *__restrict__ out_f,
+                                                   T *__restrict__ out_T, size_t out_T_stride)
+{
+    __shared__ float xs[kBatchTile][kGemvChunk];
+    __shared__ float red[kBatchTile][4];
+    __shared__ float rinv_s[kBatchTile];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+
+    if (do_norm) {
+        for (int b = 0; b < kBatchTile; ++b) {
+            float ss = 0.f;
+            if (b < Bn)
+                for (int k = tid; k < n_in; k += 256) { const float v = in[(size_t)b * n_in + k]; ss = fmaf(v, v, ss); }
+            ss = wave_sum(ss);
+            if (lane == 0) red[b][wave] = ss;
+        }
+        __syncthreads();
+        if (tid < kBatchTile) rinv_s[tid] = rsqrtf((red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3]) / (float)n_in + eps);
+        __syncthreads();
+    }
+
+    const int o0 = (blockIdx.x * 4 + wave) * kGemvRows;
+    const T *wrow[kGemvRows];
+#pragma unroll
+    for (int r = 0; r < kGemvRows; ++r) {
+        const int o = min(o0 + r, n_out - 1);
+        wrow[r] = (o < n_first) ? Wa + (size_t)o * n_in : Wb + (size_t)(o - n_first) * n_in;
+    }
+    float acc[kGemvRows][kBatchTile];
+#pragma unroll
+    for (int r = 0; r < kGemvRows; ++r)
+#pragma unroll
+        for (int b = 0; b < kBatchTile; ++b) acc[r][b] = 0.f;
+
+    for (int c0 = 0; c0 < n_in; c0 += kGemvChunk) {
+        const int cn = min(kGemvChunk, n_in - c0);
+        __syncthreads();
+        for (int idx = tid; idx < kBatchTile * cn; idx += 256) {
+            const int b = idx / cn, k = idx - b * cn;
+            float v = 0.f;
+            if (b < Bn) {
+                v = in[(size_t)b * n_in + c0 + k];
+                if (do_norm) v *= rinv_s[b] * (gain ? to_f32(gain[c0 + k]) : 1.f);
+            }
+            xs[b][k] = v;
+        }
+        __syncthreads();
+        for (int k = lane * 8; k < cn; k += 512) {
+            float w[kGemvRows][8];
+#pragma unroll
+            for (int r = 0; r < kGemvRows; ++r) load8(wrow[r] + c0 + k, w[r]);
+#pragma unroll
+            for (int b = 0; b < kBatchTile; ++b) {
+                const float4 x0 = *reinterpret_cast<const float4 *>(&xs[b][k]);
+                const float4 x1 = *reinterpret_cast<const float4 *>(&xs[b][k + 4]);
+#pragma unroll
+                for (int r = 0; r < kGemvRows; ++r) {
+                    float a = acc[r][b];
+                    a = fmaf(w[r][0], x0.x, a); a = fmaf(w[r][1], x0.y, a); a = fmaf(w[r][2], x0.z, a); a = fmaf(w[r][3], x0.w, a);
+                    a = fmaf(w[r][4], x1.x, a); a = fmaf(w[r][5], x1.y, a); a = fmaf(w[r][6], x1.z, a); a = fmaf(w[r][7], x1.w, a);
+                    acc[r][b] = a;
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < kGemvRows; ++r)
+#pragma unroll
+        for (int b = 0; b < kBatchTile; ++b) acc[r][b] = wave_sum(acc[r][b]);
+
+    // lanes 0..31 each finish one (row, batch) pair
+    if (lane < kGemvRows * kBatchTile) {
+        const int r = lane / kBatchTile, b = lane % kBatchTile;
+        float v = 0.f;
+#pragma unroll
+        for (int rr = 0; rr < kGemvRows; ++rr)
+#pragma unroll
+            for (int bb = 0; bb < kBatchTile; ++bb)
+                if (rr == r && bb == b) v = acc[rr][bb];
+        const int o = o0 + r;
+        if (o < n_out && b < Bn) {
+            if (EPI == EPI_WO) {
+                out_f[(size_t)b * n_out + o] = to_f32(res_T[(size_t)b * res_stride + o]) + alpha * v;
+            } else if (EPI == EPI_W1) {
+                out_f[(size_t)b * n_out + o] = gelu_erf(v);
+            } else if (EPI == EPI_W2) {
+                const float z = res_f[(size_t)b * n_out + o] + alpha * v;
+                out_f[(size_t)b * n_out + o] = z;
+                out_T[(size_t)b * out_T_stride + o] = from_f32<T>(z);
+            } else {
+                out_f[(size_t)b * n_out + o] = v;
+            }
+        }
+    }
+}
+
+// =============================================================================================
+// Base case, last part: qkRMS of the new key, store the persistent pair of position t (and the
+// transposed bf16 copy of v used by the MFMA cross-block kernel).  grid B*H, block 64.
+// =============================================================================================
+template <typename T>
+__global__ __launch_bounds__(64) void finalize_kv_kernel(const float *__restrict__ kv_raw, const T *__restrict__ g_k,
+                                                         T *__restrict__ K, T *__restrict__ V, bf16_t *__restrict__ VT,
+                                                         int vt_stride, int BH, int H, int d, int t, float eps,
+                                                         int norm_free)
+{
+    const int lane = threadIdx.x, bh = blockIdx.x;
+    const int b = bh / H, h = bh % H;
+    float k = kv_raw[(size_t)b * 2 * d + h * kHeadDim + lane];
+    const float v = kv_raw[(size_t)b * 2 * d + d + h * kHeadDim + lane];
+    if (!norm_free) {
+        const float ss = wave_sum(k * k);
+        k = k * rsqrtf(ss / (float)kHeadDim + eps) * (g_k ? to_f32(g_k[h * kHeadDim + lane]) : 1.f);
+    }
+    const size_t off = ((size_t)t * BH + bh) * kHeadDim + lane;
+    K[off] = from_f32<T>(k);
+    V[off] = from_f32<T>(v);
+    if (VT) VT[((size_t)bh * kHeadDim + lane) * vt_stride + t] = f32_to_bf16(v);
+}
+
+// =============================================================================================
+// Pre-pass, plain-ALU form.  rinv[m] = 1/sqrt(mean(x_m^2)+eps); then for every row m = (b, n):
+//   [q | k_tmp | v_tmp] = (x_m * rinv * g_attn) [Wq | Wk | Wv]^T,  qkRMS on q and k_tmp per head.
+// Tile 64 rows x 64 columns (one head of one of the three outputs), 256 threads, 4x4 per thread.
+// =============================================================================================
+template <typename T>
+__global__ __launch_bounds__(256) void row_rinv_kernel(const T *__restrict__ x, float *__restrict__ rinv, int M, int d,
+                                                       float eps, int norm_free)
+{
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = blockIdx.x * 4 + wave;
+    if (m >= M) return;
+    float ss = 0.f;
+    for (int k = lane; k < d; k += 64) { const float v = to_f32(x[(size_t)m * d + k]); ss = fmaf(v, v, ss); }
+    ss = wave_sum(ss);
+    if (lane == 0) rinv[m] = norm_free ? 1.f : rsqrtf(ss / (float)d + eps);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void prepass_generic_kernel(const T *__restrict__ x, const float *__restrict__ rinv,
+                                                              const T *__restrict__ Wq, const T *__restrict__ Wk,
+                                                              const T *__restrict__ Wv, const T *__restrict__ g_attn,
+                                                              const T *__restrict__ g_q, const T *__restrict__ g_k,
+                                                              T *__restrict__ Q, T *__restrict__ Kt, T *__restrict__ Vt,
+                                                              int Bc, int Nc, int d, int H, float eps, int norm_free)
+{
+    __shared__ float As[16][64 + 1];
+    __shared__ float Bs[16][64 + 1];
+    const int tid = threadIdx.x, tx = tid & 15, ty = tid >> 4;
+    const int M = Bc * Nc;
+    const int m0 = blockIdx.x * 64;
+    const int which = blockIdx.y / H, h = blockIdx.y % H;  // 0 = q, 1 = k_tmp, 2 = v_tmp
+    const T *W = which == 0 ? Wq : (which == 1 ? Wk : Wv);
+    float acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = 0.f;
+
+    for (int k0 = 0; k0 < d; k0 += 16) {
+        __syncthreads();
+        for (int idx = tid; idx < 64 * 16; idx += 256) {
+            const int r = idx >> 4, kk = idx & 15;
+            const int m = min(m0 + r, M - 1);
+            const int k = k0 + kk;
+            float a = 0.f, bv = 0.f;
+            if (k < d) {
+                a = to_f32(x[(size_t)m * d + k]);
+                if (!norm_free) a *= rinv[m] * (g_attn ? to_f32(g_attn[k]) : 1.f);
+                bv = to_f32(W[(size_t)(h * kHeadDim + r) * d + k]);
+            }
+            As[kk][r] = a;
+            Bs[kk][r] = bv;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int kk = 0; kk < 16; ++kk) {
+            float a[4], bb[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { a[i] = As[kk][ty * 4 + i]; bb[i] = Bs[kk][tx * 4 + i]; }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], bb[j], acc[i][j]);
+        }
+    }
+    const T *g = which == 0 ? g_q : g_k;
+    T *dst = which == 0 ? Q : (which == 1 ? Kt : Vt);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float sc = 1.f;
+        if (which < 2 && !norm_free) {
+            float ss = acc[i][0] * acc[i][0] + acc[i][1] * acc[i][1] + acc[i][2] * acc[i][2] + acc[i][3] * acc[i][3];
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);  // the 16 threads of a row are adjacent lanes
+            sc = rsqrtf(ss / (float)kHeadDim + eps);
+        }
+        const int m = m0 + ty * 4 + i;
+        if (m < M) {
+            const int b = m / Nc, n = m % Nc;
+            T *o = dst + ((size_t)n * Bc + b) * d + h * kHeadDim + tx * 4;
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                float v = acc[i][j] * sc;
+                if (which < 2 && !norm_free && g) v *= to_f32(g[h * kHeadDim + tx * 4 + j]);
+                o[j] = from_f32<T>(v);
+            }
+        }
+    }
+}
+
+// =============================================================================================
+// Launchers
+// =============================================================================================
+hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
+                               hipStream_t st);
+hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, hipStream_t st);
+
+template <typename T>
+hipError_t Launch<T>::prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
+                              bool mfma, hipStream_t st)
+{
+    const int M = Bc * Nc;
+    hipLaunchKernelGGL(row_rinv_kernel<T>, dim3((M + 3) / 4), dim3(256), 0, st, (const T *)x, S.rinv, M, D.d, D.eps,
+                       D.norm_free);
+    if (mfma && sizeof(T) == 2) return prepass_mfma_launch(D, W, S, x, Bc, Nc, st);
+    hipLaunchKernelGGL(prepass_generic_kernel<T>, dim3((M + 63) / 64, 3 * D.H), dim3(256), 0, st, (const T *)x, S.rinv,
+                       (const T *)W.Wq, (const T *)W.Wk, (const T *)W.Wv, (const T *)W.g_attn, (const T *)W.g_q,
+                       (const T *)W.g_k, (T *)S.Q, (T *)S.Kt, (T *)S.Vt, Bc, Nc, D.d, D.H, D.eps, D.norm_free);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t Launch<T>::merge(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int q_row,
+                            int n_decode_splits, hipStream_t st)
+{
+    hipLaunchKernelGGL(merge_kernel<T>, dim3(D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)S.Kt,
+                       (const T *)S.Vt, (const T *)K, (const T *)V, S.pm, S.pl, S.po, S.attn_cat, D.B * D.H, D.H, t, q_row,
+                       D.p_min, D.log2_pmin, S.levels, S.slots, n_decode_splits, D.scale);
+    return hipGetLastError();
+}
+
+// Batch rows beyond one tile of 8 are handled by further launches of the same kernel.
+template <typename T, int EPI>
+static hipError_t gemv_launch(const T *Wa, const T *Wb, int n_first, int n_out, int n_in, const float *in, int B,
+                              const T *gain, float eps, int do_norm, float alpha, const T *res_T, size_t res_stride,
+                              const float *res_f, float *out_f, T *out_T, size_t out_T_stride, hipStream_t st)
+{
+    const int rows = 4 * kGemvRows;
+    for (int b0 = 0; b0 < B; b0 += kBatchTile) {
+        const int Bn = (B - b0 < kBatchTile) ? B - b0 : kBatchTile;
+        hipLaunchKernelGGL((gemv_kernel<T, EPI>), dim3((n_out + rows - 1) / rows), dim3(256), 0, st, Wa, Wb, n_first, n_out,
+                           n_in, in + (size_t)b0 * n_in, Bn, gain, eps, do_norm, alpha,
+                           res_T ? res_T + (size_t)b0 * res_stride : res_T, res_stride,
+                           res_f ? res_f + (size_t)b0 * n_out : res_f, out_f + (size_t)b0 * n_out,
+                           out_T ? out_T + (size_t)b0 * out_T_stride : out_T, out_T_stride);
+    }
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t Launch<T>::gemv_wo(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride_b,
+                              hipStream_t st)
+{
+    return gemv_launch<T, EPI_WO>((const T *)W.Wo, (const T *)W.Wo, D.d, D.d, D.d, S.attn_cat, D.B, (const T *)nullptr,
+                                  D.eps, 0, D.alpha, (const T *)x_t, x_stride_b, (const float *)nullptr, S.h, (T *)nullptr,
+                                  (size_t)0, st);
+}
+
+template <typename T> hipError_t Launch<T>::gemv_w1(const LayerDims &D, const Weights &W, const Scratch &S, hipStream_t st)
+{
+    return gemv_launch<T, EPI_W1>((const T *)W.W1, (const T *)W.W1, D.F, D.F, D.d, S.h, D.B, (const T *)W.g_mlp, D.eps,
+                                  D.norm_free ? 0 : 1, D.alpha, (const T *)nullptr, (size_t)0, (const float *)nullptr, S.u,
+                                  (T *)nullptr, (size_t)0, st);
+}
+
+template <typename T>
+hipError_t Launch<T>::gemv_w2(const LayerDims &D, const Weights &W, const Scratch &S, void *y_t, size_t y_stride_b,
+                              hipStream_t st)
+{
+    return gemv_launch<T, EPI_W2>((const T *)W.W2, (const T *)W.W2, D.d, D.d, D.F, S.u, D.B, (const T *)nullptr, D.eps, 0,
+                                  D.alpha, (const T *)nullptr, (size_t)0, S.h, S.z, (T *)y_t, y_stride_b, st);
+}
+
+template <typename T> hipError_t Launch<T>::gemv_kv(const LayerDims &D, const Weights &W, const Scratch &S, hipStream_t st)
+{
+    const T *g = (const T *)(W.g_kv ? W.g_kv : W.g_attn);
+    return gemv_launch<T, EPI_KV>((const T *)W.Wk, (const T *)W.Wv, D.d, 2 * D.d, D.d, S.z, D.B, g, D.eps,
+                                  D.norm_free ? 0 : 1, D.alpha, (const T *)nullptr, (size_t)0, (const float *)nullptr,
+                                  S.kv_raw, (T *)nullptr, (size_t)0, st);
+}
+
+template <typename T>
+hipError_t Launch<T>::finalize_kv(const LayerDims &D, const Weights &W, const Scratch &S, void *K, void *V, int t,
+                                  bool write_vt, hipStream_t st)
+{
+    hipLaunchKernelGGL(finalize_kv_kernel<T>, dim3(D.B * D.H), dim3(64), 0, st, S.kv_raw, (const T *)W.g_k, (T *)K, (T *)V,
+                       write_vt ? S.VT : (bf16_t *)nullptr, S.vt_stride, D.B * D.H, D.H, D.d, t, D.eps, D.norm_free);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t Launch<T>::cross(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t1, int P, int nq,
+                            bool mfma, hipStream_t st)
+{
+    int level = 0;
+    while ((1 << level) < P) ++level;
+    if (mfma && sizeof(T) == 2) return cross_mfma_launch(D, S, K, t1, P, nq, st);
+    hipLaunchKernelGGL(cross_generic_kernel<T>, dim3(nq, D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)K,
+                       (const T *)V, S.pm, S.pl, S.po, D.B * D.H, t1, P, level, level - D.log2_pmin, S.slots, D.scale);
+    return hipGetLastError();
+}
+
+template <typename T>
+hipError_t Launch<T>::decode_split(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int chunk,
+                                   int nsplit, hipStream_t st)
+{
+    hipLaunchKernelGGL(decode_split_kernel<T>, dim3(nsplit, D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)K,
+                       (const T *)V, S.pm, S.pl, S.po, D.B * D.H, t, chunk, S.slots, D.scale);
+    return hipGetLastError();
+}
+
+template struct Launch<float>;
+template struct Launch<bf16_t>;
+
+}  // namespace rt

@@ -1,0 +1,77 @@
+"""The C-ABI library loads and exports what include/rt.h declares; host-only entry points behave (no GPU)."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2604_21215_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared_symbols():
+    src = open(os.path.join(ROOT, "include", "rt.h")).read()
+    src = re.sub(r"/\*.*?\*/", "", src, flags=re.S)
+    return sorted(set(re.findall(r"\b(rt_[a-z_0-9]+)\s*\(", src)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = binding.load()
+    names = _declared_symbols()
+    assert len(names) >= 12
+    for n in names:
+        assert hasattr(L, n), n
+    assert set(names) == set(binding.EXPORTS)
+    assert L.rt_version() >= 100
+
+
+def test_status_strings_and_null_context():
+    L = binding.load()
+    assert L.rt_status_string(0) == b"RT_OK"
+    assert L.rt_status_string(2) == b"RT_ERR_UNSUPPORTED"
+    assert L.rt_last_error(None) == b"no context"
+    assert L.rt_destroy(None) == 0
+    assert L.rt_workspace_bytes(None) == 0
+    assert L.rt_create(None, None) == binding.RT_ERR_INVALID_ARG
+
+
+def test_paper_examples_in_the_driver_schedule():
+    ev = {e[0]: e for e in binding.rt_schedule_events(8, 1)}
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "schedule_examples.txt")) if l[0] != "#"]
+    for t, P, u, v, s, e in (tuple(int(a) for a in r) for r in rows):
+        assert ev[t] == (t, P, u, v, s)
+
+
+@pytest.mark.parametrize("N,p_min", [(1, 1), (2, 1), (7, 1), (100, 1), (100, 4), (257, 32), (300, 64), (1000, 32), (64, 64)])
+def test_driver_schedule_plus_direct_window_covers_every_pair_once(N, p_min):
+    ev = binding.rt_schedule_events(N, p_min)
+    cover = np.zeros((N + 1, N + 1), dtype=np.int32)
+    per_level_slots = {}
+    for (t, P, u, v, s) in ev:
+        assert P >= p_min and t % P == 0 and (t // P) % 2 == 1 and u == t + 1 and v == min(t + P, N) and s == t - P + 1
+        cover[u:v + 1, s:t + 1] += 1
+        lvl = P.bit_length() - 1
+        for q in range(u, v + 1):
+            slot = binding.rt_partial_slot(lvl, q)
+            assert 0 <= slot < (N + 1) // 2
+            assert slot not in per_level_slots.setdefault(lvl, set())      # written once
+            per_level_slots[lvl].add(slot)
+    for i in range(1, N + 1):                                               # direct window of query i
+        w = (i - 1) % p_min
+        cover[i, i - w:i] += 1
+    for i in range(1, N + 1):
+        assert (cover[i, 1:i] == 1).all() and (cover[i, i:] == 0).all()
+    # a query takes a tile at a level exactly when that bit of (i-1) is set
+    for i in range(1, N + 1):
+        for lvl in range(0, 12):
+            has = binding.rt_partial_slot(lvl, i) >= 0
+            assert has == bool(((i - 1) >> lvl) & 1)
+
+
+def test_schedule_rejects_bad_arguments():
+    L = binding.load()
+    assert L.rt_schedule_events(0, 32, None, 0) == -1
+    assert L.rt_schedule_events(16, 3, None, 0) == -1
+    assert L.rt_partial_slot(-1, 4) == -1
+    assert L.rt_partial_slot(2, 0) == -1

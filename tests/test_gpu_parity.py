@@ -1,0 +1,192 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element on the same
+seeded buffers, reported as error curves over position.
+
+Tolerance (norm-wise relative error per position, max over batch rows / heads):
+    fp32 storage 1e-4, bf16 storage 2e-2  -- for y, K and V separately.
+"""
+import numpy as np
+import pytest
+
+from paper_2604_21215_amd import inputs as gen
+from tests.parity_util import TOL, error_curves, summarize, oracle_layer
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+def _gpu():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible: the gpu-marked tests need a real MI355X")
+    from paper_2604_21215_amd import binding, torch_io
+    return binding, torch_io
+
+
+def _run_case(oracle, dtype, B, N, d, H, F, *, flags=0, p_min=0, gains="unit", seed=5, alpha=1.0, scale=1.0,
+              eps=1e-6, kv_cap=None, li=None, tol_scale=1.0, expect_engine=None):
+    binding, tio = _gpu()
+    if li is None:
+        li = gen.make_custom(seed, dtype, B, N, d, H, F, gains=gains)
+    x64 = li.x.astype(np.float64)
+    ref = oracle_layer(oracle, li, H, alpha=alpha, attn_scale=scale, eps=eps).prefill(x64)
+    ctx = binding.RTContext(d, H, F, B, N, dtype, p_min=p_min, resid_scale=alpha, attn_scale=scale, rms_eps=eps,
+                            flags=flags)
+    try:
+        dl = tio.DeviceLayer(li.weights, li.gains, dtype)
+        xd = tio.to_device(li.x, dtype)
+        y, K, V = tio.prefill(ctx, dl, xd, kv_cap=kv_cap)
+        torch.cuda.synchronize()
+        assert ctx.device_wait_expired() == 0
+        if expect_engine:
+            assert ctx.engine_name() == expect_engine
+        got = (tio.to_host(y), tio.to_host(K), tio.to_host(V))
+    finally:
+        ctx.rt_destroy()
+    cur = error_curves(x64, ref, got)
+    print("\n  [%s B=%d N=%d d=%d p_min=%d flags=%#x] %s" % (dtype, B, N, d, p_min, flags, summarize(cur)))
+    tol = TOL[dtype] * tol_scale
+    for name in ("y", "K", "V"):
+        t_bad = int(np.argmax(cur[name]))
+        assert cur[name].max() <= tol, "%s: error %.3e at position %d exceeds %.1e" % (name, cur[name].max(), t_bad, tol)
+    if kv_cap is not None and kv_cap > N:
+        assert np.all(got[1][N:] == 0) and np.all(got[2][N:] == 0)      # rows beyond N untouched
+    return cur
+
+
+def _flags():
+    from paper_2604_21215_amd import binding
+    return binding
+
+
+# ----------------------------------------------------------------------------- per-position engine
+@pytest.mark.parametrize("N", [1, 2, 3, 7, 33, 100])
+def test_stepwise_f32_small_and_ragged_lengths(oracle, N):
+    b = _flags()
+    _run_case(oracle, "f32", 2, N, 128, 2, 512, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=4, expect_engine="stepwise")
+
+
+@pytest.mark.parametrize("p_min", [1, 2, 8, 32, 256])
+def test_stepwise_f32_threshold_does_not_change_results(oracle, p_min):
+    b = _flags()
+    _run_case(oracle, "f32", 1, 150, 128, 2, 256, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=p_min)
+
+
+def test_stepwise_f32_gains_scales_and_batch_tiles(oracle):
+    b = _flags()
+    _run_case(oracle, "f32", 11, 70, 128, 2, 264, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=8, gains="random", alpha=0.7,
+              scale=0.5, kv_cap=80)
+    _run_case(oracle, "f32", 3, 40, 192, 3, 512, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=4, gains="random",
+              alpha=1.0 / np.sqrt(12.0), scale=0.125, eps=0.0)
+
+
+def test_stepwise_config1_f32(oracle):
+    """Configuration 1: fp32, B=1, N=256, d=128, 2 heads, hidden 512."""
+    b = _flags()
+    wl = gen.WORKLOADS["cfg1"]
+    li = gen.make_layer_inputs(wl)
+    cur = _run_case(oracle, "f32", wl.B, wl.N, wl.d, wl.H, wl.F, flags=b.RT_FLAG_ENGINE_STEPWISE, li=li)
+    assert cur["branch"].max() < 1e-4
+
+
+def test_stepwise_bf16_plain_alu_and_mfma_agree_with_oracle(oracle):
+    b = _flags()
+    _run_case(oracle, "bf16", 2, 200, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_STEPWISE | b.RT_FLAG_NO_MFMA, p_min=8)
+    _run_case(oracle, "bf16", 2, 200, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=32)
+    _run_case(oracle, "bf16", 3, 300, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=32, gains="random",
+              alpha=0.7, scale=0.5, kv_cap=320)
+    _run_case(oracle, "bf16", 5, 333, 320, 5, 1280, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=64)   # odd head count, ragged N
+
+
+def test_stepwise_hip_graph_replay_matches(oracle):
+    b = _flags()
+    _run_case(oracle, "bf16", 2, 130, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_STEPWISE | b.RT_FLAG_HIP_GRAPH, p_min=32,
+              expect_engine="stepwise+graph")
+
+
+# ----------------------------------------------------------------------------- prefill == decode
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_prefill_then_decode_matches_oracle_and_full_prefill(oracle, dtype):
+    binding, tio = _gpu()
+    B, N, d, H, F, n0 = 3, 300, 128, 2, 512, 270
+    li = gen.make_custom(9, dtype, B, N, d, H, F, gains="random")
+    x64 = li.x.astype(np.float64)
+    ref = oracle_layer(oracle, li, H, alpha=0.8).prefill(x64)
+    ctx = binding.RTContext(d, H, F, B, N, dtype, resid_scale=0.8, flags=binding.RT_FLAG_ENGINE_STEPWISE)
+    try:
+        dl = tio.DeviceLayer(li.weights, li.gains, dtype)
+        xd = tio.to_device(li.x, dtype)
+        y0, K, V = tio.prefill(ctx, dl, xd[:, :n0].contiguous(), kv_cap=N)
+        ys = [y0]
+        for t in range(n0, N):
+            y_t = torch.empty((B, d), dtype=xd.dtype, device=xd.device)
+            ctx.rt_decode_step(dl.struct, xd[:, t].contiguous(), t, y_t, K, V)
+            ys.append(y_t[:, None])
+        torch.cuda.synchronize()
+        got = (tio.to_host(torch.cat(ys, dim=1)), tio.to_host(K), tio.to_host(V))
+        # decode from an empty cache as well: N' successive steps equal a prefill of length N'
+        K2 = torch.zeros_like(K)
+        V2 = torch.zeros_like(V)
+        y2 = []
+        for t in range(12):
+            y_t = torch.empty((B, d), dtype=xd.dtype, device=xd.device)
+            ctx.rt_decode_step(dl.struct, xd[:, t].contiguous(), t, y_t, K2, V2)
+            y2.append(y_t[:, None])
+        torch.cuda.synchronize()
+        got2 = tio.to_host(torch.cat(y2, dim=1))
+    finally:
+        ctx.rt_destroy()
+    cur = error_curves(x64, ref, got)
+    print("\n  [prefill+decode %s] %s" % (dtype, summarize(cur)))
+    for name in ("y", "K", "V"):
+        assert cur[name].max() <= TOL[dtype]
+    from tests.parity_util import rel_err_rows
+    assert rel_err_rows(got2, ref[0][:, :12]).max() <= TOL[dtype]
+
+
+# ----------------------------------------------------------------------------- error paths (host side only)
+def test_invalid_arguments_are_rejected_before_any_launch():
+    binding, tio = _gpu()
+    with pytest.raises(binding.RTError):
+        binding.RTContext(128, 2, 512, 1, 16, "f32", p_min=3)
+    with pytest.raises(binding.RTError):
+        binding.RTContext(96, 2, 512, 1, 16, "f32")                       # head_dim 48
+    with pytest.raises(binding.RTError):
+        binding.RTContext(128, 2, 512, 1, 16, "bf16", p_min=8)            # MFMA path needs p_min >= 32
+    ctx = binding.RTContext(128, 2, 512, 2, 16, "f32", flags=binding.RT_FLAG_ENGINE_STEPWISE)
+    try:
+        li = gen.make_custom(3, "f32", 2, 16, 128, 2, 512)
+        dl = tio.DeviceLayer(li.weights, li.gains, "f32")
+        x = tio.to_device(li.x, "f32")
+        y = torch.full_like(x, 7.0)
+        K = torch.zeros((16, 2, 2, 64), device=x.device)
+        V = torch.zeros_like(K)
+        P = lambda t: t.data_ptr()
+        assert ctx.raw_prefill(dl.struct, P(x), 3, 16, P(y), P(K), P(V), 16) == binding.RT_ERR_INVALID_ARG   # B > max
+        assert ctx.raw_prefill(dl.struct, P(x), 2, 17, P(y), P(K), P(V), 17) == binding.RT_ERR_INVALID_ARG   # N > max
+        assert ctx.raw_prefill(dl.struct, P(x), 2, 16, P(y), P(K), P(V), 15) == binding.RT_ERR_INVALID_ARG   # kv_cap < N
+        assert ctx.raw_prefill(dl.struct, P(x), 2, 16, P(x), P(K), P(V), 16) == binding.RT_ERR_INVALID_ARG   # y aliases x
+        assert ctx.raw_prefill(dl.struct, 0, 2, 16, P(y), P(K), P(V), 16) == binding.RT_ERR_INVALID_ARG      # null x
+        assert ctx.raw_prefill(None, P(x), 2, 16, P(y), P(K), P(V), 16) == binding.RT_ERR_INVALID_ARG        # null weights
+        assert "overlap" in ctx.last_error() or ctx.last_error()
+        assert ctx.raw_decode(dl.struct, P(x), 2, 16, P(y), P(K), P(V), 16) == binding.RT_ERR_INVALID_ARG    # t >= kv_cap
+        assert ctx.raw_decode(dl.struct, P(x), 2, -1, P(y), P(K), P(V), 16) == binding.RT_ERR_INVALID_ARG
+        torch.cuda.synchronize()
+        assert float(y.min()) == 7.0 and float(K.abs().max()) == 0.0      # outputs untouched
+    finally:
+        ctx.rt_destroy()
+
+
+def test_two_runs_are_bit_identical(oracle):
+    binding, tio = _gpu()
+    li = gen.make_custom(4, "bf16", 2, 160, 256, 4, 1024)
+    ctx = binding.RTContext(256, 4, 1024, 2, 160, "bf16", flags=binding.RT_FLAG_ENGINE_STEPWISE)
+    try:
+        dl = tio.DeviceLayer(li.weights, li.gains, "bf16")
+        xd = tio.to_device(li.x, "bf16")
+        a = tio.prefill(ctx, dl, xd)
+        b = tio.prefill(ctx, dl, xd)
+        torch.cuda.synchronize()
+        for u, v in zip(a, b):
+            assert torch.equal(u.view(torch.int16), v.view(torch.int16))
+    finally:
+        ctx.rt_destroy()
