@@ -60,7 +60,8 @@ typedef struct {
     int32_t max_batch, max_seq;                   /* sizes the scratch (queries, temporary pairs, partial states) */
     int32_t dtype;                                /* rt_dtype */
     int32_t p_min;                                /* smallest KV block handled by the cross-block kernel; power of
-                                                     two in [32, 1024]; 0 = default (32) */
+                                                     two, at most 1024, at least 32 when the MFMA kernels are in use
+                                                     (bf16 without RT_FLAG_NO_MFMA), else at least 1; 0 = default (32) */
     float resid_scale;                            /* alpha = 1/sqrt(L) (Sec. 2); 1 for a single layer */
     float attn_scale;                             /* multiplies the logits; paper-literal 1 */
     float rms_eps;                                /* paper-literal 0; 1e-6 is the usual choice */
@@ -118,6 +119,12 @@ int32_t rt_device_wait_expired(rt_ctx *ctx);
  * "persistent", or "" before the first call. */
 const char *rt_engine_name(const rt_ctx *ctx);
 
+/* Diagnostics of the persistent engine, after the stream has been synchronised: when the environment
+ * variable RT_PERSIST_TRACE was set at rt_create, copies for each of the first `rows` positions eight
+ * 100 MHz clock stamps of workgroup 0 (start, after each of the five grid barriers, after the cross-block
+ * items) into out[rows][8] (host memory).  Returns the number of rows written, 0 if tracing is off. */
+int32_t rt_phase_trace(rt_ctx *ctx, uint64_t *out, int32_t rows);
+
 /* Host-only: the cross-block events the driver issues for a sequence of length N with threshold
  * p_min (Appendix C, Algorithm 1, lines "P <- 2^nu2(t)" to the second UpdateTile call, restricted to
  * P >= p_min).  Event e: out[5e+0..4] = t, P, first query u, last query v, first key s (1-based,
@@ -125,6 +132,14 @@ const char *rt_engine_name(const rt_ctx *ctx);
  * query i, keys [ (i-1) - ((i-1) mod p_min) + 1, i-1 ].  Returns the number of events; writes at most
  * cap of them (out may be NULL when cap == 0). */
 int32_t rt_schedule_events(int32_t N, int32_t p_min, int32_t *out, int32_t cap);
+
+/* Host-only: the events of the persistent engine, whose block decomposition is shifted by one key:
+ * query i takes key i-1 directly, and keys 1..i-2 are split by the bits of c = i-2 (1-based keys; c is
+ * the number of keys before the newest one).  Event e: out[5e+0..4] = t, P, first query u, last query v,
+ * first key s, all 1-based inclusive, where t = last key of the block (a multiple of P >= p_min), the
+ * queries are t+2 .. min(t+P+1, N), and the partial of query i is stored in the slot of (log2 P, query i-1).
+ * The direct window of query i is keys [c - (c mod p_min) + 1, c] with c = i-2, plus key i-1. */
+int32_t rt_schedule_events_shifted(int32_t N, int32_t p_min, int32_t *out, int32_t cap);
 
 /* Host-only: index of the partial-state slot of (level, query), or -1 if that query takes no tile at
  * that level.  level = log2(P); query is 1-based.  Slots of one level are dense in [0, ceil(N/2)). */

@@ -22,7 +22,7 @@ RT_FLAG_HIP_GRAPH = 0x10
 
 EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_last_error", "rt_status_string",
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
-           "rt_version")
+           "rt_version", "rt_phase_trace", "rt_schedule_events_shifted")
 
 
 class rt_config(C.Structure):
@@ -78,9 +78,13 @@ def load():
     L.rt_engine_name.restype = C.c_char_p
     L.rt_schedule_events.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
     L.rt_schedule_events.restype = C.c_int32
+    L.rt_schedule_events_shifted.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
+    L.rt_schedule_events_shifted.restype = C.c_int32
     L.rt_partial_slot.argtypes = [C.c_int32, C.c_int32]
     L.rt_partial_slot.restype = C.c_int64
     L.rt_version.restype = C.c_int32
+    L.rt_phase_trace.argtypes = [ctxp, C.POINTER(C.c_uint64), C.c_int32]
+    L.rt_phase_trace.restype = C.c_int32
     _lib = L
     return L
 
@@ -104,14 +108,21 @@ def make_weights(w: dict) -> rt_layer_weights:
     return s
 
 
-def rt_schedule_events(N: int, p_min: int):
-    L = load()
-    n = L.rt_schedule_events(N, p_min, None, 0)
+def _events(fn, N, p_min):
+    n = fn(N, p_min, None, 0)
     if n < 0:
-        raise RTError("RT_ERR_INVALID_ARG", "rt_schedule_events")
+        raise RTError("RT_ERR_INVALID_ARG", "schedule")
     buf = (C.c_int32 * (5 * max(n, 1)))()
-    L.rt_schedule_events(N, p_min, buf, n)
+    fn(N, p_min, buf, n)
     return [tuple(buf[5 * i + j] for j in range(5)) for i in range(n)]
+
+
+def rt_schedule_events(N: int, p_min: int):
+    return _events(load().rt_schedule_events, N, p_min)
+
+
+def rt_schedule_events_shifted(N: int, p_min: int):
+    return _events(load().rt_schedule_events_shifted, N, p_min)
 
 
 def rt_partial_slot(level: int, query: int) -> int:
@@ -166,6 +177,13 @@ class RTContext:
 
     def device_wait_expired(self) -> int:
         return int(self._L.rt_device_wait_expired(self._ctx))
+
+    def phase_trace(self, rows: int):
+        """[rows, 8] clock stamps (100 MHz) of the persistent engine, or None when tracing is off."""
+        import numpy as np
+        buf = np.zeros((rows, 8), dtype=np.uint64)
+        n = self._L.rt_phase_trace(self._ctx, buf.ctypes.data_as(C.POINTER(C.c_uint64)), rows)
+        return buf[:n] if n > 0 else None
 
     def rt_destroy(self):
         if self._ctx:

@@ -95,6 +95,24 @@ int32_t rt_schedule_events(int32_t N, int32_t p_min, int32_t *out, int32_t cap)
     return n;
 }
 
+int32_t rt_schedule_events_shifted(int32_t N, int32_t p_min, int32_t *out, int32_t cap)
+{
+    if (N < 1 || !is_pow2(p_min)) return -1;
+    int32_t n = 0;
+    // 0-based position t of the engine's loop: block of keys [t-P, t) serves queries c = t .. t+nq-1 (rows c+1)
+    for (int32_t t = p_min; t < N - 1; ++t) {
+        const int32_t P = t & -t;
+        if (P < p_min) continue;
+        const int32_t nq = (P < N - 1 - t) ? P : N - 1 - t;
+        if (out && n < cap) {
+            int32_t *r = out + 5 * (size_t)n;
+            r[0] = t; r[1] = P; r[2] = t + 2; r[3] = t + 1 + nq; r[4] = t - P + 1;
+        }
+        ++n;
+    }
+    return n;
+}
+
 int64_t rt_partial_slot(int32_t level, int32_t query)
 {
     if (level < 0 || level > 30 || query < 1) return -1;
@@ -207,6 +225,12 @@ int32_t rt_device_wait_expired(rt_ctx *c)
         c->err = "a bounded device-side wait expired in the persistent engine";
     }
     return v;
+}
+
+int32_t rt_phase_trace(rt_ctx *c, uint64_t *out, int32_t rows)
+{
+    if (!c || !out || rows < 1) return 0;
+    return persistent_read_trace(c->persist, (unsigned long long *)out, rows);
 }
 
 }  // extern "C"

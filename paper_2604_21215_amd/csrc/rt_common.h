@@ -60,6 +60,47 @@ __device__ __forceinline__ float lane_bcast(float v, int lane)
 
 __device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
 
+// =============================================================================================
+// One query against a run of KV rows, online softmax (Appendix C, Algorithm 2, for one query row).
+// A wavefront owns one (query, batch row, head): lane c holds q[c] and o[c]; within a chunk of
+// 64 keys lane j owns key j.  m, l are wave-uniform.
+// =============================================================================================
+template <typename T>
+__device__ __forceinline__ void attend_keys(float q, const T *__restrict__ Kb, const T *__restrict__ Vb,
+                                            size_t row_stride, int nkeys, float scale, float &m, float &l, float &o)
+{
+    const int lane = threadIdx.x & 63;
+    for (int k0 = 0; k0 < nkeys; k0 += 64) {
+        const int j = k0 + lane;
+        const bool valid = j < nkeys;
+        const T *krow = Kb + (size_t)(valid ? j : nkeys - 1) * row_stride;
+        float acc = 0.f;
+#pragma unroll
+        for (int c8 = 0; c8 < 8; ++c8) {
+            float kk[8];
+            load8(krow + c8 * 8, kk);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], acc);
+        }
+        const float logit = valid ? acc * scale : -INFINITY;
+        const float m_new = fmaxf(m, wave_max(logit));
+        const float resc = expf(m - m_new);  // exp(-inf) = 0 on the first chunk
+        const float p = valid ? expf(logit - m_new) : 0.f;
+        l = l * resc + wave_sum(p);
+        float on = o * resc;
+        const int cnt = min(64, nkeys - k0);
+        for (int j0 = 0; j0 < cnt; j0 += 8) {  // eight value rows in flight at a time
+            float vv[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) vv[e] = to_f32(Vb[(size_t)(k0 + min(j0 + e, cnt - 1)) * row_stride + lane]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) on = fmaf(j0 + e < cnt ? lane_bcast(p, min(j0 + e, 63)) : 0.f, vv[e], on);
+        }
+        o = on;
+        m = m_new;
+    }
+}
+
 // ---------------------------------------------------------------- launch parameters
 struct LayerDims {
     int B, N, d, H, F;

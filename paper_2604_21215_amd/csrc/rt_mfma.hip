@@ -7,28 +7,9 @@
 //   D: lane holds D[row = 4g + r][col = lane%16], r = 0..3   (4 fp32)
 // Both operands want the contraction index contiguous per lane, which is how x, the weights, q and k
 // rows are stored, so those fragments are loaded straight from global memory.
-#include "rt_common.h"
+#include "rt_mfma_device.h"
 
 namespace rt {
-
-typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
-typedef float f32x4_t __attribute__((ext_vector_type(4)));
-
-union Frag {
-    uint4 u;
-    uint2 h[2];
-    bf16x8_t v;
-};
-
-__device__ __forceinline__ f32x4_t mfma16(const Frag &a, const Frag &b, f32x4_t c)
-{
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a.v, b.v, c, 0, 0, 0);
-}
-
-__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
-{
-    return (uint32_t)f32_to_bf16(lo) | ((uint32_t)f32_to_bf16(hi) << 16);
-}
 
 // =============================================================================================
 // Pre-pass GEMM: C[m][c] = sum_k (x[m][k] g_attn[k]) Wqkv[c][k], rows scaled by rinv[m], then qkRMS
@@ -141,14 +122,7 @@ hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scrat
 }
 
 // =============================================================================================
-// Cross-block UpdateTile: queries [t1, t1+nq) against keys [t1-P, t1) for every (b, h); P is a
-// multiple of 32.  The transposed products are formed so that the softmax state of a query lives in
-// one lane column:
-//     S^T[key][query] = K Q^T              (A = K rows, B = Q rows)
-//     O^T[dh][query] += V^T P^T            (A = V^T rows from the transposed value copy, B = P^T)
-// P^T comes out of the first product already in the B-operand layout once the 32 keys of a chunk
-// are assigned to contraction slots as  slot 8g+e  <->  key 4g+e (e < 4), 16+4g+(e-4) (e >= 4);
-// the V^T fragment is gathered with the same assignment (two 8-byte loads).
+// Cross-block UpdateTile as a stand-alone launch: queries [t1, t1+nq) against keys [t1-P, t1).
 // A wavefront owns 32 queries (two 16-query tiles); a block is 4 wavefronts = 128 queries.
 // grid (ceil(nq/128), B*H).
 // =============================================================================================
@@ -158,100 +132,11 @@ __global__ __launch_bounds__(256) void cross_mfma_kernel(const bf16_t *__restric
                                                          float *__restrict__ po, int BH, int t1, int P, int nq, int level,
                                                          int level_rel, int slots, float scale)
 {
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int l16 = lane & 15, g = lane >> 4;
-    const int bh = blockIdx.y;
+    const int wave = threadIdx.x >> 6;
     const int q0 = blockIdx.x * 128 + wave * 32;  // first query of this wavefront, relative to t1
     if (q0 >= nq) return;                         // no barriers in this kernel
-    const size_t rs = (size_t)BH * kHeadDim;
-
-    Frag bq[2][2];
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        const int qi = min(q0 + qt * 16 + l16, nq - 1);
-        const bf16_t *qrow = Q + (size_t)(t1 + qi) * rs + (size_t)bh * kHeadDim + 8 * g;
-        bq[qt][0].u = *reinterpret_cast<const uint4 *>(qrow);
-        bq[qt][1].u = *reinterpret_cast<const uint4 *>(qrow + 32);
-    }
-    float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.f, 0.f};
-    f32x4_t O[2][4];
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt)
-#pragma unroll
-        for (int blk = 0; blk < 4; ++blk) O[qt][blk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-
-    const bf16_t *kbase = K + (size_t)(t1 - P) * rs + (size_t)bh * kHeadDim + 8 * g;
-    const bf16_t *vbase = VT + ((size_t)bh * kHeadDim + l16) * vt_stride + (t1 - P) + 4 * g;
-
-    for (int kc = 0; kc < P; kc += 32) {
-        f32x4_t S[2][2];
-#pragma unroll
-        for (int kt = 0; kt < 2; ++kt) {
-            const bf16_t *krow = kbase + (size_t)(kc + kt * 16 + l16) * rs;
-            Frag a0, a1;
-            a0.u = *reinterpret_cast<const uint4 *>(krow);
-            a1.u = *reinterpret_cast<const uint4 *>(krow + 32);
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt) {
-                f32x4_t s = f32x4_t{0.f, 0.f, 0.f, 0.f};
-                s = mfma16(a0, bq[qt][0], s);
-                s = mfma16(a1, bq[qt][1], s);
-                S[qt][kt] = s;
-            }
-        }
-        Frag bp[2];
-#pragma unroll
-        for (int qt = 0; qt < 2; ++qt) {
-            float s[8];
-#pragma unroll
-            for (int r = 0; r < 4; ++r) { s[r] = S[qt][0][r] * scale; s[4 + r] = S[qt][1][r] * scale; }
-            float mx = s[0];
-#pragma unroll
-            for (int e = 1; e < 8; ++e) mx = fmaxf(mx, s[e]);
-            mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-            mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-            const float m_new = fmaxf(m[qt], mx);
-            const float resc = __expf(m[qt] - m_new);
-            float ps = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) { s[e] = __expf(s[e] - m_new); ps += s[e]; }
-            lsum[qt] = lsum[qt] * resc + ps;
-            m[qt] = m_new;
-#pragma unroll
-            for (int blk = 0; blk < 4; ++blk) O[qt][blk] *= resc;
-            bp[qt].u.x = pack_bf16(s[0], s[1]);
-            bp[qt].u.y = pack_bf16(s[2], s[3]);
-            bp[qt].u.z = pack_bf16(s[4], s[5]);
-            bp[qt].u.w = pack_bf16(s[6], s[7]);
-        }
-#pragma unroll
-        for (int blk = 0; blk < 4; ++blk) {
-            const bf16_t *vrow = vbase + (size_t)(blk * 16) * vt_stride + kc;
-            Frag av;
-            av.h[0] = *reinterpret_cast<const uint2 *>(vrow);
-            av.h[1] = *reinterpret_cast<const uint2 *>(vrow + 16);
-#pragma unroll
-            for (int qt = 0; qt < 2; ++qt) O[qt][blk] = mfma16(av, bp[qt], O[qt][blk]);
-        }
-    }
-
-#pragma unroll
-    for (int qt = 0; qt < 2; ++qt) {
-        float l = lsum[qt];
-        l += __shfl_xor(l, 16, 64);
-        l += __shfl_xor(l, 32, 64);
-        const int qi = q0 + qt * 16 + l16;
-        if (qi < nq) {
-            const int i0 = t1 + qi;
-            const size_t idx = partial_index(level_rel, partial_slot(level, i0), slots, BH, bh);
-            if (g == 0) { pm[idx] = m[qt]; pl[idx] = l; }
-            float *orow = po + idx * kHeadDim + 4 * g;
-#pragma unroll
-            for (int blk = 0; blk < 4; ++blk)
-                *reinterpret_cast<float4 *>(orow + blk * 16) =
-                    make_float4(O[qt][blk][0], O[qt][blk][1], O[qt][blk][2], O[qt][blk][3]);
-        }
-    }
+    cross_mfma_wave(Q, K, VT, vt_stride, pm, pl, po, BH, blockIdx.y, t1, 0, t1 - P, P, q0, nq, level, level_rel, slots,
+                    scale);
 }
 
 hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, hipStream_t st)

@@ -1,23 +1,727 @@
-// Single-launch engine of the sequential loop (placeholder: reports "not available" so that the
-// per-position engine is used).
+// Single-launch ("persistent") engine of the sequential loop, bf16 storage.
+//
+// One cooperative grid of one workgroup per compute unit runs all N positions.  The five matrices
+// of the loop (Wo, W1, W2, Wk, Wv) are split by output rows over the workgroups and held in LDS for
+// the whole call (weight-stationary: 11 d^2 bf16 elements over 256 x 160 KB of LDS), so a position
+// costs no weight traffic at all.  What remains on the critical path is the exchange of the small
+// activation vectors between the phases of a position:
+//
+//   M   per (b, h) wavefront: finish the persistent pair of position t-1 (RMS scale of z, qkRMS of k,
+//       store K, V and the transposed value copy), then merge the stored partial softmax states, the
+//       direct window, the newest key and the temporary pair into a_t                    -> a
+//   O   h = x_t + alpha Wo a                       -> bf16(h * g_mlp), partial sums of squares
+//   1   u = gelu(rinv_h * W1 (h g_mlp))            -> u
+//   2   z = h + alpha W2 u   (same rows as O)      -> y, bf16(z * g_kv), partial sums of squares
+//   KV  [Wk; Wv] (z g_kv)  (RMS scale applied by M) -> raw k, v
+//
+// Exchange format: every value crosses the chip inside a self-validating 64-bit word
+// [tag:32 | payload:32] (payload = two bf16 or one fp32), written with one 8-byte agent-scope atomic
+// store and polled with 8-byte atomic loads until the tag equals the tag of (call, position).  A hop
+// therefore costs one store-to-load trip through the memory side instead of a fenced grid barrier
+// (measured on MI355X: about 3 us against about 10 us).  Buffers alternate with the parity of t; a
+// writer of position t+2 has always (transitively) gathered a full vector of position t+1, which
+// every workgroup produced after it had finished reading position t.
+//
+// K, V, the transposed value copy and the partial softmax states live in ordinary cached memory.
+// The per-position window only re-reads rows that the same wavefront wrote.  Cross-workgroup use
+// happens at the cross-block events (every p_min positions): those are bracketed by two fenced grid
+// barriers (release / acquire at agent scope).
+//
+// The RMS scale is applied after each product (the products are linear in their input), so no phase
+// waits for a norm.  Relative to the per-position engine the block decomposition is shifted by one:
+// query t takes its newest key t-1 directly (the wavefront that merges has just finished that key),
+// keys [0, t-1) are split by the bits of c = t-1 into stored partials (blocks >= p_min) and the
+// direct window.
+//
+// Every wait is bounded: a poll loop that exceeds spin_limit raises the abort word, every workgroup
+// leaves the kernel at its next wait, and the host reports it.
 #include "rt_persistent.h"
+#include "rt_mfma_device.h"
+
+#include <cstdlib>
 
 namespace rt {
 
-rt_status persistent_create(PersistentState &P, const rt_config &, const LayerDims &)
+constexpr int kPW = 8;                 // wavefronts per workgroup
+constexpr int kPThreads = kPW * 64;
+constexpr int kBMax = 16;              // batch rows (MFMA N dimension)
+constexpr int kRMax = 16;              // output rows per workgroup and matrix (MFMA M dimension)
+constexpr int kMaxLevels = 16;         // stored-partial levels a query can take (p_min 32 .. sequence 2^20)
+
+typedef unsigned long long ll_t;       // exchange word: [tag:32 | payload:32]
+
+struct PersistArgs {
+    int B, N, d, H, F, BH;
+    int p_min, log2_pmin;
+    float alpha, scale, eps;
+    int norm_free;
+    int G;
+    int R_o, R_1, R_kv;   // rows per workgroup of Wo/W2, W1, [Wk; Wv] (all even)
+    int ldw_d, ldw_F;     // LDS row strides in elements
+    const bf16_t *Wo, *W1, *W2, *Wk, *Wv, *g_mlp, *g_kv, *g_k;
+    const bf16_t *x;
+    bf16_t *y, *K, *V;
+    const bf16_t *Q, *Kt, *Vt;
+    bf16_t *VT;
+    int vt_stride;
+    float *pm, *pl, *po;
+    int levels, slots;
+    // exchange buffers, each [2 parities][kBMax][...] words
+    ll_t *a_ll, *h_ll, *z_ll;   // [..][d/2]   two bf16 per word
+    ll_t *u_ll;                 // [..][F/2]
+    ll_t *kv_ll;                // [..][2d]    one fp32 per word
+    ll_t *hss_ll, *zss_ll;      // [..][G]     one fp32 per word
+    ll_t *done_m, *done_1;      // [2][256]    "producer finished" words of phase M (per unit) and phase 1 (per workgroup)
+    int win_rows;               // p_min when the direct window is kept in LDS, else 0 (window re-read from K, V)
+    int upw;                    // merge units per workgroup = ceil(BH_max / G)
+    unsigned tag_base;          // (call nonce) << 20
+    unsigned long long *bar;    // [0] fenced-barrier counter, [8] abort word
+    unsigned long long *trace;  // optional: [N][8] wall-clock stamps of workgroup 0
+    long long spin_limit;
+};
+
+__device__ __forceinline__ ll_t ll_load(const ll_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ void ll_store(ll_t *p, unsigned tag, unsigned payload)
+{
+    __hip_atomic_store(p, ((ll_t)tag << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ bool ll_ok(ll_t w, unsigned tag) { return (unsigned)(w >> 32) == tag; }
+
+// Wave-uniform bounded poll of one word per lane (inactive lanes pass active = false).
+// Returns the word; sets fail when the bound is hit or the abort word is raised.
+__device__ __forceinline__ ll_t ll_wait(const ll_t *p, bool active, unsigned tag, const PersistArgs &A, int &fail)
+{
+    ll_t w = active ? ll_load(p) : 0;
+    bool bad = active && !ll_ok(w, tag);
+    long long spins = 0;
+    while (__any(bad)) {
+        if (bad) { w = ll_load(p); bad = !ll_ok(w, tag); }
+        if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
+    }
+    return w;
+}
+
+// Fenced grid-wide barrier on a monotonically increasing counter (used around cross-block events).
+// Returns true if the run is aborted.
+__device__ __forceinline__ bool grid_barrier(const PersistArgs &A, unsigned long long target, int *flag_s)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        __hip_atomic_fetch_add(A.bar, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int ab = 0;
+        long long spins = 0;
+        for (;;) {
+            const unsigned long long v = ll_load(A.bar);
+            if (v >= target) break;
+            if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { ab = 1; break; }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+        *flag_s = ab;
+    }
+    __syncthreads();
+    return *flag_s != 0;
+}
+
+// acc tile of one workgroup: rows of an LDS-resident weight slice times the activation rows that
+// arrive as exchange words act[b][K/2].  The contraction is split over the wavefronts; all loads of a
+// lane are issued first, then each 32-wide step is validated (re-polled if its producer is late)
+// and fed to the MFMA.  The per-wavefront 16 x 16 tiles land in red[wave][row][b].
+template <int KS>
+__device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, const ll_t *act, int B, unsigned tag,
+                                           const PersistArgs &A, float *red, int &fail)
+{
+    constexpr int K = KS * 32 * kPW;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+    constexpr int kw = K / kPW;
+    const int k0 = wave * kw + 8 * g;
+    const bf16_t *wrow = w_s + (size_t)l16 * ldw + k0;
+    const ll_t *arow = act + (size_t)l16 * (K / 2) + k0 / 2;
+    const bool has_w = l16 < R, has_a = l16 < B;
+    ll_t w[KS][4];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) w[s][j] = has_a ? ll_load(arow + s * 16 + j) : 0;
+    }
+    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+            bool bad = has_a && !(ll_ok(w[s][0], tag) && ll_ok(w[s][1], tag) && ll_ok(w[s][2], tag) && ll_ok(w[s][3], tag));
+            long long spins = 0;
+            while (__any(bad)) {
+                if (bad) {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) w[s][j] = ll_load(arow + s * 16 + j);
+                    bad = !(ll_ok(w[s][0], tag) && ll_ok(w[s][1], tag) && ll_ok(w[s][2], tag) && ll_ok(w[s][3], tag));
+                }
+                if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
+            }
+            Frag a, b;
+            a.u = has_w ? *reinterpret_cast<const uint4 *>(wrow + s * 32) : zero;
+            b.u = make_uint4((unsigned)w[s][0], (unsigned)w[s][1], (unsigned)w[s][2], (unsigned)w[s][3]);
+            acc = mfma16(a, b, acc);
+        }
+    float *r = red + ((size_t)wave * kRMax + 4 * g) * kBMax + l16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i * kBMax] = acc[i];
+}
+
+__device__ __forceinline__ float red_sum(const float *red, int row, int b)
+{
+    float v = 0.f;
+#pragma unroll
+    for (int w = 0; w < kPW; ++w) v += red[((size_t)w * kRMax + row) * kBMax + b];
+    return v;
+}
+
+__device__ __forceinline__ void copy_rows_to_lds(bf16_t *dst, int ldw, const bf16_t *src, int K, int row0, int nrows)
+{
+    const int per_row = K / 8;  // 16-byte pieces
+    for (int idx = threadIdx.x; idx < nrows * per_row; idx += kPThreads) {
+        const int r = idx / per_row, c = idx - r * per_row;
+        *reinterpret_cast<uint4 *>(dst + (size_t)r * ldw + c * 8) =
+            *reinterpret_cast<const uint4 *>(src + (size_t)(row0 + r) * K + c * 8);
+    }
+}
+
+// Bounded poll of NW words per lane, all loads issued before the first check.
+template <int NW>
+__device__ __forceinline__ void ll_wait_n(const ll_t *const (&p)[NW], const bool (&active)[NW], unsigned tag,
+                                          const PersistArgs &A, ll_t (&w)[NW], int &fail)
+{
+#pragma unroll
+    for (int i = 0; i < NW; ++i) w[i] = active[i] ? ll_load(p[i]) : 0;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) {
+        bool bad = active[i] && !ll_ok(w[i], tag);
+        long long spins = 0;
+        while (__any(bad)) {
+            if (bad) { w[i] = ll_load(p[i]); bad = !ll_ok(w[i], tag); }
+            if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
+        }
+    }
+}
+
+// Gate: wait until the first `count` words of `words` carry `tag` (thread i polls word i, i + 512, ...).
+// The bulk loads of a phase are issued only after its producers have signalled, so an early consumer
+// polls a few hundred bytes instead of re-reading whole activation vectors.
+__device__ __forceinline__ void gate_wait(const ll_t *words, int count, unsigned tag, const PersistArgs &A, int &fail)
+{
+    for (int i0 = 0; i0 < count; i0 += kPThreads) {
+        const bool act = i0 + (int)threadIdx.x < count;
+        (void)ll_wait(words + (act ? i0 + threadIdx.x : 0), act, tag, A, fail);
+    }
+}
+
+// Direct window out of LDS: query (lane c holds q[c]) against nkeys <= 64 rows kept by this wavefront.
+__device__ __forceinline__ void attend_lds(float q, const bf16_t *ks, const bf16_t *vs, int nkeys, float scale, float &m,
+                                           float &l, float &o)
+{
+    const int lane = threadIdx.x & 63;
+    const bool valid = lane < nkeys;
+    const bf16_t *krow = ks + (size_t)(valid ? lane : 0) * kHeadDim;
+    float acc = 0.f;
+#pragma unroll
+    for (int c8 = 0; c8 < 8; ++c8) {
+        float kk[8];
+        load8(krow + c8 * 8, kk);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], acc);
+    }
+    const float logit = valid ? acc * scale : -INFINITY;
+    const float m_new = fmaxf(m, wave_max(logit));
+    const float resc = __expf(m - m_new);
+    const float p = valid ? __expf(logit - m_new) : 0.f;
+    l = l * resc + wave_sum(p);
+    float on = o * resc;
+    for (int j = 0; j < nkeys; ++j) on = fmaf(lane_bcast(p, j), bf16_to_f32(vs[(size_t)j * kHeadDim + lane]), on);
+    o = on;
+    m = m_new;
+}
+
+// sum over the G producers of one fp32 exchange row per batch row: 32 threads per batch row poll
+// (up to 8 words each, i.e. G <= 256 per pass), partials go to sq[32][kBMax]; the caller syncs and
+// finishes the sum.
+__device__ __forceinline__ void gather_partial_sums(const ll_t *ss, int G, int B, unsigned tag, const PersistArgs &A, float *sq,
+                                                    int &fail)
+{
+    const int jb = threadIdx.x & 15, jg = threadIdx.x >> 4;
+    float s = 0.f;
+    for (int j0 = 0; j0 < G; j0 += 8 * (kPThreads / 16)) {
+        const ll_t *p[8];
+        bool act[8];
+        ll_t w[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const int j = j0 + i * (kPThreads / 16) + jg;
+            act[i] = jb < B && j < G;
+            p[i] = ss + (size_t)jb * G + (act[i] ? j : 0);
+        }
+        ll_wait_n<8>(p, act, tag, A, w, fail);
+#pragma unroll
+        for (int i = 0; i < 8; ++i)
+            if (act[i]) s += __uint_as_float((unsigned)w[i]);
+    }
+    sq[jg * kBMax + jb] = s;
+}
+
+#define RT_ABORT_IF(cond)                                                                                  \
+    do {                                                                                                   \
+        if (__syncthreads_or(cond)) {                                                                      \
+            if (threadIdx.x == 0) __hip_atomic_store(A.bar + 8, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); \
+            return;                                                                                        \
+        }                                                                                                  \
+    } while (0)
+
+// KSD = d / 256, KSF = F / 256: contraction steps per wavefront, fixed at compile time so that all
+// exchange loads of a phase are in flight at once without spilling.
+template <int KSD, int KSF>
+__global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wg = blockIdx.x, G = A.G;
+    const int d = A.d, F = A.F, B = A.B, BH = A.BH;
+
+    // ---- LDS carve-up
+    bf16_t *wo_s = reinterpret_cast<bf16_t *>(smem);
+    bf16_t *w1_s = wo_s + (size_t)A.R_o * A.ldw_d;
+    bf16_t *w2_s = w1_s + (size_t)A.R_1 * A.ldw_d;
+    bf16_t *wkv_s = w2_s + (size_t)A.R_o * A.ldw_F;
+    float *red = reinterpret_cast<float *>(wkv_s + (size_t)A.R_kv * A.ldw_d);  // [kPW][kRMax][kBMax]
+    float *h_loc = red + kPW * kRMax * kBMax;                                  // [kRMax][kBMax]
+    float *sq = h_loc + kRMax * kBMax;                                         // [32][kBMax]
+    float *rinv_s = sq + 32 * kBMax;                                           // [kBMax]
+    int *flag_s = reinterpret_cast<int *>(rinv_s + kBMax);
+    bf16_t *win_k = reinterpret_cast<bf16_t *>(flag_s + 4);                    // [upw][win_rows][64]
+    bf16_t *win_v = win_k + (size_t)A.upw * A.win_rows * kHeadDim;
+
+    // ---- this workgroup's rows
+    const int o_lo = min(wg * A.R_o, d), o_n = min(d, o_lo + A.R_o) - o_lo;          // Wo, W2
+    const int f_lo = min(wg * A.R_1, F), f_n = min(F, f_lo + A.R_1) - f_lo;          // W1
+    const int kv_lo = min(wg * A.R_kv, 2 * d), kv_n = min(2 * d, kv_lo + A.R_kv) - kv_lo;  // [Wk; Wv]
+
+    copy_rows_to_lds(wo_s, A.ldw_d, A.Wo, d, o_lo, o_n);
+    copy_rows_to_lds(w1_s, A.ldw_d, A.W1, d, f_lo, f_n);
+    copy_rows_to_lds(w2_s, A.ldw_F, A.W2, F, o_lo, o_n);
+    {
+        const int per_row = d / 8;
+        for (int idx = tid; idx < kv_n * per_row; idx += kPThreads) {
+            const int r = idx / per_row, c = idx - r * per_row;
+            const int o = kv_lo + r;
+            const bf16_t *src = (o < d) ? A.Wk + (size_t)o * d : A.Wv + (size_t)(o - d) * d;
+            *reinterpret_cast<uint4 *>(wkv_s + (size_t)r * A.ldw_d + c * 8) = *reinterpret_cast<const uint4 *>(src + c * 8);
+        }
+    }
+    __syncthreads();
+
+    const size_t rs = (size_t)BH * kHeadDim;
+    unsigned long long nbar = 0;
+    const int erow = tid >> 4, eb = tid & 15;  // epilogue thread -> (row, batch) for tid < 256
+    const size_t half_d = (size_t)kBMax * (d / 2), half_F = (size_t)kBMax * (F / 2);
+    const size_t sz_kv = (size_t)kBMax * 2 * d, sz_ss = (size_t)kBMax * G;
+
+    for (int t = 0; t <= A.N; ++t) {
+        const int par = t & 1, ppar = par ^ 1;
+        const unsigned tag = A.tag_base | (unsigned)(t + 1);   // words produced at position t
+        const unsigned ptag = A.tag_base | (unsigned)t;        // words produced at position t-1
+        int fail = 0;
+        if (A.trace && wg == 0 && tid == 0 && t < A.N) A.trace[(size_t)t * 8 + 0] = wall_clock64();
+        float xv = 0.f;   // residual input of this workgroup's rows, fetched ahead of phase O
+        if (t < A.N && tid < kRMax * kBMax && erow < o_n && eb < B) xv = bf16_to_f32(A.x[((size_t)eb * A.N + t) * d + o_lo + erow]);
+        // ================================================================ phase M
+        for (int u = wg + G * wave; u < BH; u += G * kPW) {
+            const int b = u / A.H, h = u - b * A.H;
+            // (1) everything that does not need the newest key: temporary pair, stored partials, window
+            float q = 0.f, m = 0.f, l = 1.f, o = 0.f;
+            if (t < A.N) {
+                const size_t qoff = (size_t)t * rs + (size_t)u * kHeadDim + lane;
+                q = bf16_to_f32(A.Q[qoff]);
+                m = A.scale * wave_sum(q * bf16_to_f32(A.Kt[qoff]));
+                o = bf16_to_f32(A.Vt[qoff]);
+                if (t >= 2) {
+                    const int c = t - 1;
+                    float pmv[kMaxLevels], plv[kMaxLevels], pov[kMaxLevels];
+#pragma unroll
+                    for (int lr = 0; lr < kMaxLevels; ++lr) {
+                        const int lv = lr + A.log2_pmin;
+                        const bool on = lr < A.levels && ((c >> lv) & 1);
+                        const size_t idx = on ? partial_index(lr, partial_slot(lv, c), A.slots, BH, u) : 0;
+                        pmv[lr] = on ? A.pm[idx] : -INFINITY;
+                        plv[lr] = on ? A.pl[idx] : 0.f;
+                        pov[lr] = on ? A.po[idx * kHeadDim + lane] : 0.f;
+                    }
+                    float mx = m;
+#pragma unroll
+                    for (int lr = 0; lr < kMaxLevels; ++lr) mx = fmaxf(mx, pmv[lr]);
+                    const float e0 = __expf(m - mx);
+                    l *= e0;
+                    o *= e0;
+#pragma unroll
+                    for (int lr = 0; lr < kMaxLevels; ++lr) {
+                        const float f = __expf(pmv[lr] - mx);   // exp(-inf) = 0 for absent levels
+                        l = fmaf(plv[lr], f, l);
+                        o = fmaf(pov[lr], f, o);
+                    }
+                    m = mx;
+                    const int w = c & (A.p_min - 1);
+                    if (w > 0) {
+                        if (A.win_rows) {
+                            const size_t wo = (size_t)(u / G) * A.win_rows * kHeadDim;
+                            attend_lds(q, win_k + wo, win_v + wo, w, A.scale, m, l, o);
+                        } else {
+                            const size_t base = (size_t)(c - w) * rs + (size_t)u * kHeadDim;
+                            attend_keys<bf16_t>(q, A.K + base, A.V + base, rs, w, A.scale, m, l, o);
+                        }
+                    }
+                }
+            }
+            // (2) the newest key: position t-1's raw k, v arrive from phase KV, are finished and stored here
+            if (t >= 1) {
+                const ll_t *p[6];
+                bool act[6];
+                ll_t w6[6];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    act[i] = i * 64 + lane < G;
+                    p[i] = A.zss_ll + ppar * sz_ss + (size_t)b * G + (act[i] ? i * 64 + lane : 0);
+                }
+                p[4] = A.kv_ll + ppar * sz_kv + (size_t)b * 2 * d + h * kHeadDim + lane;
+                p[5] = p[4] + d;
+                act[4] = act[5] = true;
+                ll_wait_n<6>(p, act, ptag, A, w6, fail);
+                float ss = 0.f;
+#pragma unroll
+                for (int i = 0; i < 4; ++i)
+                    if (act[i]) ss += __uint_as_float((unsigned)w6[i]);
+                const float rz = A.norm_free ? 1.f : rsqrtf(wave_sum(ss) / (float)d + A.eps);
+                float kr = __uint_as_float((unsigned)w6[4]) * rz;
+                const float vr = __uint_as_float((unsigned)w6[5]) * rz;
+                if (!A.norm_free) {
+                    const float s2 = wave_sum(kr * kr);
+                    kr *= rsqrtf(s2 / (float)kHeadDim + A.eps) * (A.g_k ? bf16_to_f32(A.g_k[h * kHeadDim + lane]) : 1.f);
+                }
+                const bf16_t kb = f32_to_bf16(kr), vb = f32_to_bf16(vr);
+                const size_t off = (size_t)(t - 1) * rs + (size_t)u * kHeadDim + lane;
+                A.K[off] = kb;
+                A.V[off] = vb;
+                A.VT[((size_t)u * kHeadDim + lane) * A.vt_stride + (t - 1)] = vb;
+                if (A.win_rows) {   // ring slot of key t-1; only this wavefront reads it back
+                    const size_t wo = ((size_t)(u / G) * A.win_rows + ((t - 1) & (A.win_rows - 1))) * kHeadDim + lane;
+                    win_k[wo] = kb;
+                    win_v[wo] = vb;
+                }
+                if (t < A.N) {
+                    const float sn = A.scale * wave_sum(q * bf16_to_f32(kb));
+                    const float m_new = fmaxf(m, sn);
+                    const float e1 = __expf(m - m_new), e2 = __expf(sn - m_new);
+                    l = l * e1 + e2;
+                    o = o * e1 + bf16_to_f32(vb) * e2;
+                    m = m_new;
+                }
+            }
+            if (t < A.N) {
+                const float av = o / l;
+                const float an = __shfl_down(av, 1, 64);
+                if (!(lane & 1))
+                    ll_store(A.a_ll + par * half_d + (size_t)b * (d / 2) + (h * kHeadDim + lane) / 2, tag,
+                             (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
+                if (lane == 0) ll_store(A.done_m + par * 256 + u, tag, 1u);
+            }
+        }
+        RT_ABORT_IF(fail);
+        if (t == A.N) break;
+        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 1] = wall_clock64();
+
+        // ================================================================ cross-block items of the block ending at key t-1
+        if (t >= A.p_min && t < A.N - 1 && (t & -t) >= A.p_min) {
+            const int P = t & -t;
+            if (grid_barrier(A, (++nbar) * (unsigned long long)G, flag_s)) { fail = 1; }
+            RT_ABORT_IF(fail);
+            const int nq = min(P, A.N - 1 - t);
+            const int qblocks = (nq + 31) / 32;
+            const int items = BH * qblocks;
+            int level = A.log2_pmin;
+            while ((1 << level) < P) ++level;
+            for (int it = wave * G + wg; it < items; it += G * kPW) {
+                const int bh = it % BH, qb = it / BH;
+                cross_mfma_wave(A.Q, A.K, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1, t - P, P, qb * 32, nq, level,
+                                level - A.log2_pmin, A.slots, A.scale);
+            }
+            if (grid_barrier(A, (++nbar) * (unsigned long long)G, flag_s)) { fail = 1; }
+            RT_ABORT_IF(fail);
+        }
+        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 2] = wall_clock64();
+
+        // ================================================================ phase O:  h = x_t + alpha Wo a
+        gate_wait(A.done_m + par * 256, BH, tag, A, fail);
+        RT_ABORT_IF(fail);
+        wg_gemv_ll<KSD>(wo_s, A.ldw_d, o_n, A.a_ll + par * half_d, B, tag, A, red, fail);
+        RT_ABORT_IF(fail);
+        if (tid < kRMax * kBMax) {
+            float hv = 0.f, hg = 0.f;
+            const int o = o_lo + erow;
+            if (erow < o_n && eb < B) {
+                hv = xv + A.alpha * red_sum(red, erow, eb);
+                hg = hv * (A.g_mlp && !A.norm_free ? bf16_to_f32(A.g_mlp[o]) : 1.f);
+            }
+            const float hn = __shfl_down(hg, 16, 64);
+            if (!(erow & 1) && erow < o_n && eb < B)
+                ll_store(A.h_ll + par * half_d + (size_t)eb * (d / 2) + o / 2, tag,
+                         (unsigned)f32_to_bf16(hg) | ((unsigned)f32_to_bf16(hn) << 16));
+            h_loc[erow * kBMax + eb] = hv;
+            sq[erow * kBMax + eb] = hv * hv;
+        }
+        __syncthreads();
+        if (tid < kBMax) {
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < kRMax; ++r) s += sq[r * kBMax + tid];
+            if (tid < B) ll_store(A.hss_ll + par * sz_ss + (size_t)tid * G + wg, tag, __float_as_uint(s));
+        }
+        __syncthreads();
+        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 3] = wall_clock64();
+
+        // ================================================================ phase 1:  u = gelu(rinv_h * W1 h)
+        gather_partial_sums(A.hss_ll + par * sz_ss, G, B, tag, A, sq, fail);   // doubles as the gate of this phase
+        RT_ABORT_IF(fail);
+        wg_gemv_ll<KSD>(w1_s, A.ldw_d, f_n, A.h_ll + par * half_d, B, tag, A, red, fail);
+        RT_ABORT_IF(fail);
+        if (tid < kBMax) {
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < kPThreads / 16; ++r) s += sq[r * kBMax + tid];
+            rinv_s[tid] = A.norm_free ? 1.f : rsqrtf(s / (float)d + A.eps);
+        }
+        __syncthreads();
+        if (tid < kRMax * kBMax) {
+            float uv = 0.f;
+            if (erow < f_n && eb < B) uv = gelu_erf(red_sum(red, erow, eb) * rinv_s[eb]);
+            const float un = __shfl_down(uv, 16, 64);
+            if (!(erow & 1) && erow < f_n && eb < B)
+                ll_store(A.u_ll + par * half_F + (size_t)eb * (F / 2) + (f_lo + erow) / 2, tag,
+                         (unsigned)f32_to_bf16(uv) | ((unsigned)f32_to_bf16(un) << 16));
+        }
+        __syncthreads();
+        if (tid == 0) ll_store(A.done_1 + par * 256 + wg, tag, 1u);
+        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 4] = wall_clock64();
+
+        // ================================================================ phase 2:  z = h + alpha W2 u
+        gate_wait(A.done_1 + par * 256, G, tag, A, fail);
+        RT_ABORT_IF(fail);
+        wg_gemv_ll<KSF>(w2_s, A.ldw_F, o_n, A.u_ll + par * half_F, B, tag, A, red, fail);
+        RT_ABORT_IF(fail);
+        if (tid < kRMax * kBMax) {
+            float zv = 0.f, zg = 0.f;
+            const int o = o_lo + erow;
+            if (erow < o_n && eb < B) {
+                zv = h_loc[erow * kBMax + eb] + A.alpha * red_sum(red, erow, eb);
+                A.y[((size_t)eb * A.N + t) * d + o] = f32_to_bf16(zv);
+                zg = zv * (A.g_kv && !A.norm_free ? bf16_to_f32(A.g_kv[o]) : 1.f);
+            }
+            const float zn = __shfl_down(zg, 16, 64);
+            if (!(erow & 1) && erow < o_n && eb < B)
+                ll_store(A.z_ll + par * half_d + (size_t)eb * (d / 2) + o / 2, tag,
+                         (unsigned)f32_to_bf16(zg) | ((unsigned)f32_to_bf16(zn) << 16));
+            sq[erow * kBMax + eb] = zv * zv;
+        }
+        __syncthreads();
+        if (tid < kBMax) {
+            float s = 0.f;
+#pragma unroll
+            for (int r = 0; r < kRMax; ++r) s += sq[r * kBMax + tid];
+            if (tid < B) ll_store(A.zss_ll + par * sz_ss + (size_t)tid * G + wg, tag, __float_as_uint(s));
+        }
+        __syncthreads();
+        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 5] = wall_clock64();
+
+        // ================================================================ phase KV:  [Wk; Wv] (z g_kv)
+        gate_wait(A.zss_ll + par * sz_ss, G, tag, A, fail);   // batch row 0's partial sums: one word per producer
+        RT_ABORT_IF(fail);
+        wg_gemv_ll<KSD>(wkv_s, A.ldw_d, kv_n, A.z_ll + par * half_d, B, tag, A, red, fail);
+        RT_ABORT_IF(fail);
+        if (tid < kRMax * kBMax && erow < kv_n && eb < B)
+            ll_store(A.kv_ll + par * sz_kv + (size_t)eb * 2 * d + kv_lo + erow, tag, __float_as_uint(red_sum(red, erow, eb)));
+        __syncthreads();
+        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 6] = wall_clock64();
+    }
+}
+
+// =============================================================================================
+// Host side
+// =============================================================================================
+// a captured stream must not record memset nodes: clear the counters with a kernel
+__global__ void clear_words_kernel(unsigned long long *p, int n)
+{
+    if ((int)threadIdx.x < n) p[threadIdx.x] = 0ULL;
+}
+
+typedef void (*persist_fn)(PersistArgs);
+static persist_fn pick_kernel(int d, int F)
+{
+    if (d % (32 * kPW) != 0 || F != 4 * d) return nullptr;
+    switch (d / (32 * kPW)) {
+    case 1: return persistent_kernel<1, 4>;
+    case 2: return persistent_kernel<2, 8>;
+    case 3: return persistent_kernel<3, 12>;
+    case 4: return persistent_kernel<4, 16>;
+    default: return nullptr;
+    }
+}
+
+static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+static size_t lds_bytes_for(int d, int F, int G, int win_rows, int upw, int *R_o, int *R_1, int *R_kv)
+{
+    // rows per workgroup, rounded up to even so that a bf16 pair never straddles two producers
+    *R_o = 2 * ((d + 2 * G - 1) / (2 * G));
+    *R_1 = 2 * ((F + 2 * G - 1) / (2 * G));
+    *R_kv = 2 * ((2 * d + 2 * G - 1) / (2 * G));
+    const size_t ldw_d = d + 8, ldw_F = F + 8;
+    size_t b = ((size_t)*R_o * ldw_d + (size_t)*R_1 * ldw_d + (size_t)*R_o * ldw_F + (size_t)*R_kv * ldw_d) * 2;
+    b = align_up(b, 16);
+    b += (size_t)(kPW * kRMax * kBMax + kRMax * kBMax + 32 * kBMax + kBMax) * 4 + 16;
+    b += (size_t)2 * upw * win_rows * kHeadDim * 2;   // direct-window rows of this workgroup's merge units
+    return b;
+}
+
+rt_status persistent_create(PersistentState &P, const rt_config &cfg, const LayerDims &D)
 {
     P.available = false;
-    return RT_ERR_UNSUPPORTED;
+    if (cfg.dtype != RT_BF16 || (cfg.flags & RT_FLAG_NO_MFMA)) return RT_ERR_UNSUPPORTED;
+    persist_fn fn = pick_kernel(D.d, D.F);   // d in {256, 512, 768, 1024}, F = 4 d
+    if (!fn) return RT_ERR_UNSUPPORTED;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, cfg.device) != hipSuccess) return RT_ERR_HIP;
+    if (!prop.cooperativeLaunch) return RT_ERR_UNSUPPORTED;
+    const int G = prop.multiProcessorCount;
+    if (G < 1 || G > 256) return RT_ERR_UNSUPPORTED;   // the merge wavefront gathers G partial sums, four per lane
+    int R_o, R_1, R_kv;
+    P.upw = (cfg.max_batch * D.H + G - 1) / G;
+    if (P.upw > kPW || cfg.max_batch * D.H > 256) return RT_ERR_UNSUPPORTED;
+    P.win_rows = D.p_min <= 64 ? D.p_min : 0;
+    const size_t lds = lds_bytes_for(D.d, D.F, G, P.win_rows, P.upw, &R_o, &R_1, &R_kv);
+    if (R_o > kRMax || R_1 > kRMax || R_kv > kRMax) return RT_ERR_UNSUPPORTED;
+    if (lds > (size_t)160 * 1024) return RT_ERR_UNSUPPORTED;
+    if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) !=
+        hipSuccess) {
+        (void)hipGetLastError();
+        return RT_ERR_UNSUPPORTED;
+    }
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kPThreads, lds) != hipSuccess || nb < 1) {
+        (void)hipGetLastError();
+        return RT_ERR_UNSUPPORTED;
+    }
+    P.num_cu = G;
+    P.grid = G;
+    P.lds_bytes = lds;
+
+    const bool want_trace = getenv("RT_PERSIST_TRACE") != nullptr;
+    const size_t d = D.d, F = D.F;
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t o_bar = carve(256);
+    // exchange words (8 bytes), two parities each
+    const size_t o_a = carve(2 * kBMax * (d / 2) * 8), o_h = carve(2 * kBMax * (d / 2) * 8);
+    const size_t o_u = carve(2 * kBMax * (F / 2) * 8), o_z = carve(2 * kBMax * (d / 2) * 8);
+    const size_t o_kv = carve(2 * kBMax * 2 * d * 8);
+    const size_t o_hss = carve((size_t)2 * kBMax * G * 8), o_zss = carve((size_t)2 * kBMax * G * 8);
+    const size_t o_dm = carve(2 * 256 * 8), o_d1 = carve(2 * 256 * 8);
+    const size_t o_tr = want_trace ? carve((size_t)cfg.max_seq * 8 * 8) : 0;
+    P.slab_bytes = off;
+    if (hipMalloc(&P.slab, P.slab_bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        P.slab = nullptr;
+        P.slab_bytes = 0;
+        return RT_ERR_OOM;
+    }
+    if (hipMemset(P.slab, 0, P.slab_bytes) != hipSuccess) {
+        (void)hipFree(P.slab);
+        P.slab = nullptr;
+        return RT_ERR_HIP;
+    }
+    char *p = (char *)P.slab;
+    P.bar = (unsigned long long *)(p + o_bar);
+    P.a_ll = p + o_a; P.h_ll = p + o_h; P.u_ll = p + o_u; P.z_ll = p + o_z;
+    P.kv_ll = p + o_kv; P.hss_ll = p + o_hss; P.zss_ll = p + o_zss;
+    P.done_m = p + o_dm; P.done_1 = p + o_d1;
+    P.trace = want_trace ? (unsigned long long *)(p + o_tr) : nullptr;
+    P.trace_rows = want_trace ? cfg.max_seq : 0;
+    const char *sl = getenv("RT_SPIN_LIMIT");
+    P.spin_limit = sl ? atoll(sl) : (1LL << 21);
+    if (P.spin_limit < 1) P.spin_limit = 1;
+    P.available = true;
+    return RT_OK;
 }
-void persistent_destroy(PersistentState &) {}
-size_t persistent_bytes(const PersistentState &P) { return P.slab_bytes; }
-bool persistent_supported(const PersistentState &P, const LayerDims &) { return P.available; }
-rt_status persistent_prefill(PersistentState &, const LayerDims &, const Weights &, const Scratch &, const void *, void *,
-                             void *, void *, hipStream_t, std::string &err)
+
+void persistent_destroy(PersistentState &P)
 {
-    err = "persistent engine not available";
-    return RT_ERR_UNSUPPORTED;
+    if (P.slab) (void)hipFree(P.slab);
+    P.slab = nullptr;
+    P.available = false;
 }
-int persistent_wait_expired(PersistentState &) { return 0; }
+
+size_t persistent_bytes(const PersistentState &P) { return P.slab ? P.slab_bytes : 0; }
+
+bool persistent_supported(const PersistentState &P, const LayerDims &D)
+{
+    return P.available && D.B <= kBMax && D.N >= 1 && D.N < (1 << 20) - 2 && D.p_min >= 32;
+}
+
+rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weights &W, const Scratch &S, const void *x,
+                             void *y, void *K, void *V, hipStream_t st, std::string &err)
+{
+    PersistArgs A;
+    A.B = D.B; A.N = D.N; A.d = D.d; A.H = D.H; A.F = D.F; A.BH = D.B * D.H;
+    A.p_min = D.p_min; A.log2_pmin = D.log2_pmin;
+    A.alpha = D.alpha; A.scale = D.scale; A.eps = D.eps; A.norm_free = D.norm_free;
+    A.G = P.grid;
+    (void)lds_bytes_for(D.d, D.F, P.grid, P.win_rows, P.upw, &A.R_o, &A.R_1, &A.R_kv);
+    A.win_rows = P.win_rows; A.upw = P.upw;
+    A.ldw_d = D.d + 8; A.ldw_F = D.F + 8;
+    A.Wo = (const bf16_t *)W.Wo; A.W1 = (const bf16_t *)W.W1; A.W2 = (const bf16_t *)W.W2;
+    A.Wk = (const bf16_t *)W.Wk; A.Wv = (const bf16_t *)W.Wv;
+    A.g_mlp = (const bf16_t *)W.g_mlp; A.g_kv = (const bf16_t *)W.g_kv; A.g_k = (const bf16_t *)W.g_k;
+    A.x = (const bf16_t *)x; A.y = (bf16_t *)y; A.K = (bf16_t *)K; A.V = (bf16_t *)V;
+    A.Q = (const bf16_t *)S.Q; A.Kt = (const bf16_t *)S.Kt; A.Vt = (const bf16_t *)S.Vt;
+    A.VT = S.VT; A.vt_stride = S.vt_stride;
+    A.pm = S.pm; A.pl = S.pl; A.po = S.po; A.levels = S.levels; A.slots = S.slots;
+    A.a_ll = (ll_t *)P.a_ll; A.h_ll = (ll_t *)P.h_ll; A.u_ll = (ll_t *)P.u_ll; A.z_ll = (ll_t *)P.z_ll;
+    A.kv_ll = (ll_t *)P.kv_ll; A.hss_ll = (ll_t *)P.hss_ll; A.zss_ll = (ll_t *)P.zss_ll;
+    A.done_m = (ll_t *)P.done_m; A.done_1 = (ll_t *)P.done_1;
+    A.bar = P.bar; A.trace = P.trace; A.spin_limit = P.spin_limit;
+    P.nonce = (P.nonce % 4095u) + 1u;          // 1..4095; fresh buffers hold tag 0
+    A.tag_base = P.nonce << 20;
+
+    hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, st, P.bar, 32);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) { err = std::string("clear_words_kernel: ") + hipGetErrorString(e); return RT_ERR_HIP; }
+    void *args[] = {&A};
+    e = hipLaunchCooperativeKernel((const void *)pick_kernel(D.d, D.F), dim3(P.grid), dim3(kPThreads), args,
+                                   (unsigned int)P.lds_bytes, st);
+    if (e != hipSuccess) { err = std::string("hipLaunchCooperativeKernel: ") + hipGetErrorString(e); return RT_ERR_HIP; }
+    P.launched = true;
+    return RT_OK;
+}
+
+int persistent_wait_expired(PersistentState &P)
+{
+    if (!P.slab || !P.launched) return 0;
+    unsigned long long v = 0;
+    if (hipMemcpy(&v, P.bar + 8, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return -1;
+    return v != 0 ? 1 : 0;
+}
+
+int persistent_read_trace(PersistentState &P, unsigned long long *out, int rows)
+{
+    if (!P.trace || !out) return 0;
+    const int n = rows < P.trace_rows ? rows : P.trace_rows;
+    if (hipMemcpy(out, P.trace, (size_t)n * 8 * 8, hipMemcpyDeviceToHost) != hipSuccess) return -1;
+    return n;
+}
 
 }  // namespace rt

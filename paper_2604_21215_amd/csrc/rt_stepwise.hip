@@ -9,44 +9,6 @@
 namespace rt {
 
 // =============================================================================================
-// One query against a run of KV rows, online softmax (Appendix C, Algorithm 2, for one query row).
-// A wavefront owns one (query, batch row, head): lane c holds q[c] and o[c]; within a chunk of
-// 64 keys lane j owns key j.  m, l are wave-uniform.
-// =============================================================================================
-template <typename T>
-__device__ __forceinline__ void attend_keys(float q, const T *__restrict__ Kb, const T *__restrict__ Vb,
-                                            size_t row_stride, int nkeys, float scale, float &m, float &l, float &o)
-{
-    const int lane = threadIdx.x & 63;
-    for (int k0 = 0; k0 < nkeys; k0 += 64) {
-        const int j = k0 + lane;
-        const bool valid = j < nkeys;
-        const T *krow = Kb + (size_t)(valid ? j : nkeys - 1) * row_stride;
-        float acc = 0.f;
-#pragma unroll
-        for (int c8 = 0; c8 < 8; ++c8) {
-            float kk[8];
-            load8(krow + c8 * 8, kk);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], acc);
-        }
-        const float logit = valid ? acc * scale : -INFINITY;
-        const float m_new = fmaxf(m, wave_max(logit));
-        const float resc = expf(m - m_new);  // exp(-inf) = 0 on the first chunk
-        const float p = valid ? expf(logit - m_new) : 0.f;
-        l = l * resc + wave_sum(p);
-        float on = o * resc;
-        const int cnt = min(64, nkeys - k0);
-        for (int jj = 0; jj < cnt; ++jj) {
-            const float pj = lane_bcast(p, jj);
-            on = fmaf(pj, to_f32(Vb[(size_t)(k0 + jj) * row_stride + lane]), on);
-        }
-        o = on;
-        m = m_new;
-    }
-}
-
-// =============================================================================================
 // Cross-block update, plain-ALU form: queries [t1, t1+nq) against keys [t1-P, t1) of every (b, h);
 // the partial state (m, l, o) is written once into the slot of (level log2 P, query).
 // grid (nq, B*H), block 64.

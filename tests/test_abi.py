@@ -75,3 +75,28 @@ def test_schedule_rejects_bad_arguments():
     assert L.rt_schedule_events(16, 3, None, 0) == -1
     assert L.rt_partial_slot(-1, 4) == -1
     assert L.rt_partial_slot(2, 0) == -1
+
+
+@pytest.mark.parametrize("N,p_min", [(1, 32), (2, 32), (33, 32), (34, 32), (100, 32), (257, 32), (300, 64), (1000, 32), (129, 128)])
+def test_shifted_schedule_of_the_persistent_engine_covers_every_pair_once(N, p_min):
+    """Query i: newest key i-1 directly, window and stored partials from the bits of c = i-2."""
+    ev = binding.rt_schedule_events_shifted(N, p_min)
+    cover = np.zeros((N + 2, N + 2), dtype=np.int32)
+    slots = {}
+    for (t, P, u, v, s) in ev:
+        assert P >= p_min and t % P == 0 and (t // P) % 2 == 1 and s == t - P + 1
+        assert u == t + 2 and v == min(t + P + 1, N) and u <= v
+        cover[u:v + 1, s:t + 1] += 1
+        lvl = P.bit_length() - 1
+        for q in range(u, v + 1):
+            slot = binding.rt_partial_slot(lvl, q - 1)          # stored under c + 1 = q - 1 (1-based)
+            assert 0 <= slot < (N + 1) // 2 and slot not in slots.setdefault(lvl, set())
+            slots[lvl].add(slot)
+    for i in range(1, N + 1):
+        if i >= 2:
+            cover[i, i - 1] += 1                                 # newest key
+            c = i - 2
+            w = c % p_min
+            cover[i, c - w + 1:c + 1] += 1                       # direct window
+    for i in range(1, N + 1):
+        assert (cover[i, 1:i] == 1).all() and (cover[i, i:] == 0).all(), i

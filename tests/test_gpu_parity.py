@@ -103,6 +103,65 @@ def test_stepwise_hip_graph_replay_matches(oracle):
               expect_engine="stepwise+graph")
 
 
+# ----------------------------------------------------------------------------- persistent engine
+@pytest.mark.parametrize("B,N", [(1, 1), (2, 2), (2, 5), (3, 33), (2, 34), (5, 97), (16, 130)])
+def test_persistent_small_and_ragged(oracle, B, N):
+    b = _flags()
+    _run_case(oracle, "bf16", B, N, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_PERSISTENT, expect_engine="persistent")
+
+
+def test_persistent_gains_scales_levels(oracle):
+    b = _flags()
+    _run_case(oracle, "bf16", 3, 300, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_PERSISTENT, gains="random", alpha=0.7,
+              scale=0.5, kv_cap=310, expect_engine="persistent")
+    _run_case(oracle, "bf16", 2, 200, 512, 8, 2048, flags=b.RT_FLAG_ENGINE_PERSISTENT, p_min=64, expect_engine="persistent")
+    _run_case(oracle, "bf16", 2, 300, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_PERSISTENT, p_min=128,
+              expect_engine="persistent")                       # window re-read from K, V instead of LDS
+
+
+def test_persistent_is_the_default_engine_and_repeats_bit_identically(oracle):
+    binding, tio = _gpu()
+    li = gen.make_custom(4, "bf16", 4, 161, 768, 12, 3072)
+    ctx = binding.RTContext(768, 12, 3072, 4, 200, "bf16")
+    try:
+        dl = tio.DeviceLayer(li.weights, li.gains, "bf16")
+        xd = tio.to_device(li.x, "bf16")
+        a = tio.prefill(ctx, dl, xd)
+        b2 = tio.prefill(ctx, dl, xd)
+        torch.cuda.synchronize()
+        assert ctx.engine_name() == "persistent" and ctx.device_wait_expired() == 0
+        for u, v in zip(a, b2):
+            assert torch.equal(u.view(torch.int16), v.view(torch.int16))
+        ref = oracle_layer(oracle, li, 12, eps=1e-6).prefill(li.x.astype(np.float64))
+        cur = error_curves(li.x.astype(np.float64), ref, tuple(tio.to_host(t) for t in a))
+        for name in ("y", "K", "V"):
+            assert cur[name].max() <= TOL["bf16"]
+    finally:
+        ctx.rt_destroy()
+
+
+def test_persistent_bounded_wait_expires_cleanly(monkeypatch):
+    """A spin limit of one poll forces the kernel's own bounded waits to give up: every workgroup exits,
+    the host reports it, and the context refuses further work."""
+    binding, tio = _gpu()
+    monkeypatch.setenv("RT_SPIN_LIMIT", "1")
+    li = gen.make_custom(4, "bf16", 2, 64, 256, 4, 1024)
+    ctx = binding.RTContext(256, 4, 1024, 2, 64, "bf16", flags=binding.RT_FLAG_ENGINE_PERSISTENT)
+    monkeypatch.delenv("RT_SPIN_LIMIT")
+    try:
+        dl = tio.DeviceLayer(li.weights, li.gains, "bf16")
+        xd = tio.to_device(li.x, "bf16")
+        tio.prefill(ctx, dl, xd)
+        torch.cuda.synchronize()
+        assert ctx.device_wait_expired() == 1
+        y = torch.empty_like(xd)
+        K = torch.zeros((64, 2, 4, 64), dtype=xd.dtype, device=xd.device)
+        assert ctx.raw_prefill(dl.struct, xd.data_ptr(), 2, 64, y.data_ptr(), K.data_ptr(), torch.zeros_like(K).data_ptr(),
+                               64) == binding.RT_ERR_STATE
+    finally:
+        ctx.rt_destroy()
+
+
 # ----------------------------------------------------------------------------- prefill == decode
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_prefill_then_decode_matches_oracle_and_full_prefill(oracle, dtype):
