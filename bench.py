@@ -18,11 +18,12 @@ HBM_PEAK_GBS = 8000.0
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-def algorithmic_bytes(B, N, d, H, F, E, p_min):
+def algorithmic_bytes(B, N, d, H, F, E, p_min, weights_resident):
     """Bytes one layer call must move (per-call totals), by term.
 
-    weights      : the five matrices of the sequential loop are needed at every position (11 d^2 E per
-                   position when streamed) plus the three pre-pass matrices once.
+    weights      : the five matrices of the sequential loop (11 d^2 E bytes) are read once per call when the
+                   engine keeps them on chip (persistent engine), once per position when they are streamed
+                   (per-position engine); plus the three pre-pass matrices once.
     attention    : every cross-block event reads its q, k, v tiles once and writes a partial state that is
                    read once: (3*64*E + 2*66*4) bytes per (query, level, head, batch row), plus the direct
                    window rows.
@@ -38,7 +39,7 @@ def algorithmic_bytes(B, N, d, H, F, E, p_min):
             attn += B * H * (P * 2 * 64 * E + nq * 64 * E + 2 * nq * 66 * 4)
     window = sum((t & (p_min - 1)) for t in range(N)) * B * H * 2 * 64 * E
     return {
-        "weights_seq": N * (2 * d * d + 2 * d * F + d * d) * E * 1.0,
+        "weights_seq": (1 if weights_resident else N) * (2 * d * d + 2 * d * F + d * d) * E * 1.0,
         "weights_pre": 3 * d * d * E * 1.0,
         "attention": float(attn + window),
         "activations": 11.0 * B * N * d * E,
@@ -100,15 +101,21 @@ def main():
 
     E = 2 if wl.dtype == "bf16" else 4
     p_min = ctx.cfg.p_min if ctx.cfg.p_min else 32
-    terms = algorithmic_bytes(wl.B, wl.N, wl.d, wl.H, wl.F, E, p_min)
+    resident = engine == "persistent"
+    terms = algorithmic_bytes(wl.B, wl.N, wl.d, wl.H, wl.F, E, p_min, resident)
+    streamed = algorithmic_bytes(wl.B, wl.N, wl.d, wl.H, wl.F, E, p_min, False)
     alg_bytes = sum(terms.values())
     dev_ms = float(np.mean(per_call_ms))
     achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
     roofline = {
-        "bound": "hbm", "kernel": "rt_layer_prefill (%s engine, all launches of one call)" % engine,
+        "bound": "hbm",
+        "kernel": ("persistent_kernel (one launch per call; the call's two small pre-pass kernels are inside the timed events)"
+                   if resident else "rt_layer_prefill (%s engine, all launches of one call)" % engine),
         "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
         "launch_ms": dev_ms, "algorithmic_bytes": alg_bytes, "terms": terms,
         "us_per_position": dev_ms * 1e3 / wl.N,
+        # what a design that re-streams the loop's weights at every position would have to move, for comparison
+        "weight_streaming_equivalent_GBps": sum(streamed.values()) / (dev_ms * 1e-3) / 1e9,
     }
     attn_flops = 2.0 * wl.N * (wl.N - 1) * wl.d * wl.B
     out = {

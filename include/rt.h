@@ -120,9 +120,9 @@ int32_t rt_device_wait_expired(rt_ctx *ctx);
 const char *rt_engine_name(const rt_ctx *ctx);
 
 /* Diagnostics of the persistent engine, after the stream has been synchronised: when the environment
- * variable RT_PERSIST_TRACE was set at rt_create, copies for each of the first `rows` positions eight
- * 100 MHz clock stamps of workgroup 0 (start, after each of the five grid barriers, after the cross-block
- * items) into out[rows][8] (host memory).  Returns the number of rows written, 0 if tracing is off. */
+ * variable RT_PERSIST_TRACE was set at rt_create, copies for each of the first `rows` positions sixteen
+ * 100 MHz clock stamps of workgroup 0 (slot 0 start, 1..6 end of phases M, cross-block items, O, 1, 2, KV,
+ * 7..12 points inside the phases) into out[rows][16] (host memory).  Returns the number of rows written, 0 if tracing is off. */
 int32_t rt_phase_trace(rt_ctx *ctx, uint64_t *out, int32_t rows);
 
 /* Host-only: the cross-block events the driver issues for a sequence of length N with threshold

@@ -179,9 +179,9 @@ class RTContext:
         return int(self._L.rt_device_wait_expired(self._ctx))
 
     def phase_trace(self, rows: int):
-        """[rows, 8] clock stamps (100 MHz) of the persistent engine, or None when tracing is off."""
+        """[rows, 16] clock stamps (100 MHz) of the persistent engine, or None when tracing is off."""
         import numpy as np
-        buf = np.zeros((rows, 8), dtype=np.uint64)
+        buf = np.zeros((rows, 16), dtype=np.uint64)
         n = self._L.rt_phase_trace(self._ctx, buf.ctypes.data_as(C.POINTER(C.c_uint64)), rows)
         return buf[:n] if n > 0 else None
 

@@ -50,6 +50,37 @@ constexpr int kMaxLevels = 16;         // stored-partial levels a query can take
 
 typedef unsigned long long ll_t;       // exchange word: [tag:32 | payload:32]
 
+// 64-lane all-reduce with DPP inside each row of 16 lanes (no LDS crossbar), rows combined through
+// scalar reads.  quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140.
+__device__ __forceinline__ float dpp_f(float v, int ctrl_sel)
+{
+    const int i = __float_as_int(v);
+    int r;
+    switch (ctrl_sel) {
+    case 0: r = __builtin_amdgcn_mov_dpp(i, 0xB1, 0xF, 0xF, true); break;
+    case 1: r = __builtin_amdgcn_mov_dpp(i, 0x4E, 0xF, 0xF, true); break;
+    case 2: r = __builtin_amdgcn_mov_dpp(i, 0x141, 0xF, 0xF, true); break;
+    default: r = __builtin_amdgcn_mov_dpp(i, 0x140, 0xF, 0xF, true); break;
+    }
+    return __int_as_float(r);
+}
+__device__ __forceinline__ float fast_sum(float v)
+{
+    v += dpp_f(v, 0);
+    v += dpp_f(v, 1);
+    v += dpp_f(v, 2);
+    v += dpp_f(v, 3);
+    return lane_bcast(v, 0) + lane_bcast(v, 16) + lane_bcast(v, 32) + lane_bcast(v, 48);
+}
+__device__ __forceinline__ float fast_max(float v)
+{
+    v = fmaxf(v, dpp_f(v, 0));
+    v = fmaxf(v, dpp_f(v, 1));
+    v = fmaxf(v, dpp_f(v, 2));
+    v = fmaxf(v, dpp_f(v, 3));
+    return fmaxf(fmaxf(lane_bcast(v, 0), lane_bcast(v, 16)), fmaxf(lane_bcast(v, 32), lane_bcast(v, 48)));
+}
+
 struct PersistArgs {
     int B, N, d, H, F, BH;
     int p_min, log2_pmin;
@@ -76,7 +107,7 @@ struct PersistArgs {
     int upw;                    // merge units per workgroup = ceil(BH_max / G)
     unsigned tag_base;          // (call nonce) << 20
     unsigned long long *bar;    // [0] fenced-barrier counter, [8] abort word
-    unsigned long long *trace;  // optional: [N][8] wall-clock stamps of workgroup 0
+    unsigned long long *trace;  // optional: [N][16] wall-clock stamps of workgroup 0
     long long spin_limit;
 };
 
@@ -86,6 +117,15 @@ __device__ __forceinline__ void ll_store(ll_t *p, unsigned tag, unsigned payload
     __hip_atomic_store(p, ((ll_t)tag << 32) | payload, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 __device__ __forceinline__ bool ll_ok(ll_t w, unsigned tag) { return (unsigned)(w >> 32) == tag; }
+
+// Word of elements (k, k+1) of batch row b in an exchange vector of KS*32*kPW elements per row.
+// Rows are 8-16 KB apart, so the 8-byte atomic loads of one instruction (one per lane, never merged by
+// the memory pipeline) spread over many channels; a layout that packed a wavefront's loads into one
+// contiguous run was measured 1.5x slower on the widest vector.
+template <int KS> __device__ __forceinline__ size_t frag_word(int k, int b)
+{
+    return (size_t)b * (KS * 32 * kPW / 2) + (k >> 1);
+}
 
 // Wave-uniform bounded poll of one word per lane (inactive lanes pass active = false).
 // Returns the word; sets fail when the bound is hit or the abort word is raised.
@@ -131,39 +171,46 @@ template <int KS>
 __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, const ll_t *act, int B, unsigned tag,
                                            const PersistArgs &A, float *red, int &fail)
 {
-    constexpr int K = KS * 32 * kPW;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, g = lane >> 4;
-    constexpr int kw = K / kPW;
-    const int k0 = wave * kw + 8 * g;
-    const bf16_t *wrow = w_s + (size_t)l16 * ldw + k0;
-    const ll_t *arow = act + (size_t)l16 * (K / 2) + k0 / 2;
+    constexpr int kw = KS * 32;
+    const bf16_t *wrow = w_s + (size_t)l16 * ldw + wave * kw + 8 * g;
+    // word of (step s, j) for this lane: base + s*16 + j
+    const ll_t *abase = act + (size_t)l16 * (KS * 32 * kPW / 2) + (wave * kw + 8 * g) / 2;
     const bool has_w = l16 < R, has_a = l16 < B;
     ll_t w[KS][4];
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j) w[s][j] = has_a ? ll_load(arow + s * 16 + j) : 0;
+        for (int j = 0; j < 4; ++j) w[s][j] = has_a ? ll_load(abase + s * 16 + j) : 0;
+    }
+    unsigned bad = 0;
+#pragma unroll
+    for (int s = 0; s < KS; ++s)
+        if (has_a && !(ll_ok(w[s][0], tag) && ll_ok(w[s][1], tag) && ll_ok(w[s][2], tag) && ll_ok(w[s][3], tag))) bad |= 1u << s;
+    long long spins = 0;
+    while (__any(bad != 0)) {   // late producers: re-poll every stale step in one batch
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            if (bad & (1u << s)) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) w[s][j] = ll_load(abase + s * 16 + j);
+            }
+#pragma unroll
+        for (int s = 0; s < KS; ++s)
+            if ((bad & (1u << s)) && ll_ok(w[s][0], tag) && ll_ok(w[s][1], tag) && ll_ok(w[s][2], tag) && ll_ok(w[s][3], tag))
+                bad &= ~(1u << s);
+        if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
     }
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
-            bool bad = has_a && !(ll_ok(w[s][0], tag) && ll_ok(w[s][1], tag) && ll_ok(w[s][2], tag) && ll_ok(w[s][3], tag));
-            long long spins = 0;
-            while (__any(bad)) {
-                if (bad) {
-#pragma unroll
-                    for (int j = 0; j < 4; ++j) w[s][j] = ll_load(arow + s * 16 + j);
-                    bad = !(ll_ok(w[s][0], tag) && ll_ok(w[s][1], tag) && ll_ok(w[s][2], tag) && ll_ok(w[s][3], tag));
-                }
-                if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
-            }
-            Frag a, b;
-            a.u = has_w ? *reinterpret_cast<const uint4 *>(wrow + s * 32) : zero;
-            b.u = make_uint4((unsigned)w[s][0], (unsigned)w[s][1], (unsigned)w[s][2], (unsigned)w[s][3]);
-            acc = mfma16(a, b, acc);
-        }
+        Frag a, b;
+        a.u = has_w ? *reinterpret_cast<const uint4 *>(wrow + s * 32) : zero;
+        b.u = make_uint4((unsigned)w[s][0], (unsigned)w[s][1], (unsigned)w[s][2], (unsigned)w[s][3]);
+        acc = mfma16(a, b, acc);
+    }
     float *r = red + ((size_t)wave * kRMax + 4 * g) * kBMax + l16;
 #pragma unroll
     for (int i = 0; i < 4; ++i) r[i * kBMax] = acc[i];
@@ -232,10 +279,10 @@ __device__ __forceinline__ void attend_lds(float q, const bf16_t *ks, const bf16
         for (int e = 0; e < 8; ++e) acc = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], acc);
     }
     const float logit = valid ? acc * scale : -INFINITY;
-    const float m_new = fmaxf(m, wave_max(logit));
+    const float m_new = fmaxf(m, fast_max(logit));
     const float resc = __expf(m - m_new);
     const float p = valid ? __expf(logit - m_new) : 0.f;
-    l = l * resc + wave_sum(p);
+    l = l * resc + fast_sum(p);
     float on = o * resc;
     for (int j = 0; j < nkeys; ++j) on = fmaf(lane_bcast(p, j), bf16_to_f32(vs[(size_t)j * kHeadDim + lane]), on);
     o = on;
@@ -267,6 +314,11 @@ __device__ __forceinline__ void gather_partial_sums(const ll_t *ss, int G, int B
     }
     sq[jg * kBMax + jb] = s;
 }
+
+#define RT_STAMP(k)                                                                         \
+    do {                                                                                    \
+        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 16 + (k)] = wall_clock64(); \
+    } while (0)
 
 #define RT_ABORT_IF(cond)                                                                                  \
     do {                                                                                                   \
@@ -329,7 +381,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         const unsigned tag = A.tag_base | (unsigned)(t + 1);   // words produced at position t
         const unsigned ptag = A.tag_base | (unsigned)t;        // words produced at position t-1
         int fail = 0;
-        if (A.trace && wg == 0 && tid == 0 && t < A.N) A.trace[(size_t)t * 8 + 0] = wall_clock64();
+        if (t < A.N) RT_STAMP(0);
         float xv = 0.f;   // residual input of this workgroup's rows, fetched ahead of phase O
         if (t < A.N && tid < kRMax * kBMax && erow < o_n && eb < B) xv = bf16_to_f32(A.x[((size_t)eb * A.N + t) * d + o_lo + erow]);
         // ================================================================ phase M
@@ -340,7 +392,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             if (t < A.N) {
                 const size_t qoff = (size_t)t * rs + (size_t)u * kHeadDim + lane;
                 q = bf16_to_f32(A.Q[qoff]);
-                m = A.scale * wave_sum(q * bf16_to_f32(A.Kt[qoff]));
+                m = A.scale * fast_sum(q * bf16_to_f32(A.Kt[qoff]));
                 o = bf16_to_f32(A.Vt[qoff]);
                 if (t >= 2) {
                     const int c = t - 1;
@@ -397,11 +449,11 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     if (act[i]) ss += __uint_as_float((unsigned)w6[i]);
-                const float rz = A.norm_free ? 1.f : rsqrtf(wave_sum(ss) / (float)d + A.eps);
+                const float rz = A.norm_free ? 1.f : rsqrtf(fast_sum(ss) / (float)d + A.eps);
                 float kr = __uint_as_float((unsigned)w6[4]) * rz;
                 const float vr = __uint_as_float((unsigned)w6[5]) * rz;
                 if (!A.norm_free) {
-                    const float s2 = wave_sum(kr * kr);
+                    const float s2 = fast_sum(kr * kr);
                     kr *= rsqrtf(s2 / (float)kHeadDim + A.eps) * (A.g_k ? bf16_to_f32(A.g_k[h * kHeadDim + lane]) : 1.f);
                 }
                 const bf16_t kb = f32_to_bf16(kr), vb = f32_to_bf16(vr);
@@ -415,7 +467,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                     win_v[wo] = vb;
                 }
                 if (t < A.N) {
-                    const float sn = A.scale * wave_sum(q * bf16_to_f32(kb));
+                    const float sn = A.scale * fast_sum(q * bf16_to_f32(kb));
                     const float m_new = fmaxf(m, sn);
                     const float e1 = __expf(m - m_new), e2 = __expf(sn - m_new);
                     l = l * e1 + e2;
@@ -427,14 +479,14 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 const float av = o / l;
                 const float an = __shfl_down(av, 1, 64);
                 if (!(lane & 1))
-                    ll_store(A.a_ll + par * half_d + (size_t)b * (d / 2) + (h * kHeadDim + lane) / 2, tag,
+                    ll_store(A.a_ll + par * half_d + frag_word<KSD>(h * kHeadDim + lane, b), tag,
                              (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
                 if (lane == 0) ll_store(A.done_m + par * 256 + u, tag, 1u);
             }
         }
         RT_ABORT_IF(fail);
         if (t == A.N) break;
-        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 1] = wall_clock64();
+        RT_STAMP(1);
 
         // ================================================================ cross-block items of the block ending at key t-1
         if (t >= A.p_min && t < A.N - 1 && (t & -t) >= A.p_min) {
@@ -454,13 +506,15 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             if (grid_barrier(A, (++nbar) * (unsigned long long)G, flag_s)) { fail = 1; }
             RT_ABORT_IF(fail);
         }
-        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 2] = wall_clock64();
+        RT_STAMP(2);
 
         // ================================================================ phase O:  h = x_t + alpha Wo a
         gate_wait(A.done_m + par * 256, BH, tag, A, fail);
         RT_ABORT_IF(fail);
+        RT_STAMP(7);
         wg_gemv_ll<KSD>(wo_s, A.ldw_d, o_n, A.a_ll + par * half_d, B, tag, A, red, fail);
         RT_ABORT_IF(fail);
+        RT_STAMP(8);
         if (tid < kRMax * kBMax) {
             float hv = 0.f, hg = 0.f;
             const int o = o_lo + erow;
@@ -470,7 +524,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             }
             const float hn = __shfl_down(hg, 16, 64);
             if (!(erow & 1) && erow < o_n && eb < B)
-                ll_store(A.h_ll + par * half_d + (size_t)eb * (d / 2) + o / 2, tag,
+                ll_store(A.h_ll + par * half_d + frag_word<KSD>(o, eb), tag,
                          (unsigned)f32_to_bf16(hg) | ((unsigned)f32_to_bf16(hn) << 16));
             h_loc[erow * kBMax + eb] = hv;
             sq[erow * kBMax + eb] = hv * hv;
@@ -483,7 +537,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             if (tid < B) ll_store(A.hss_ll + par * sz_ss + (size_t)tid * G + wg, tag, __float_as_uint(s));
         }
         __syncthreads();
-        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 3] = wall_clock64();
+        RT_STAMP(3);
 
         // ================================================================ phase 1:  u = gelu(rinv_h * W1 h)
         gather_partial_sums(A.hss_ll + par * sz_ss, G, B, tag, A, sq, fail);   // doubles as the gate of this phase
@@ -502,18 +556,20 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             if (erow < f_n && eb < B) uv = gelu_erf(red_sum(red, erow, eb) * rinv_s[eb]);
             const float un = __shfl_down(uv, 16, 64);
             if (!(erow & 1) && erow < f_n && eb < B)
-                ll_store(A.u_ll + par * half_F + (size_t)eb * (F / 2) + (f_lo + erow) / 2, tag,
+                ll_store(A.u_ll + par * half_F + frag_word<KSF>(f_lo + erow, eb), tag,
                          (unsigned)f32_to_bf16(uv) | ((unsigned)f32_to_bf16(un) << 16));
         }
         __syncthreads();
         if (tid == 0) ll_store(A.done_1 + par * 256 + wg, tag, 1u);
-        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 4] = wall_clock64();
+        RT_STAMP(4);
 
         // ================================================================ phase 2:  z = h + alpha W2 u
         gate_wait(A.done_1 + par * 256, G, tag, A, fail);
         RT_ABORT_IF(fail);
+        RT_STAMP(9);
         wg_gemv_ll<KSF>(w2_s, A.ldw_F, o_n, A.u_ll + par * half_F, B, tag, A, red, fail);
         RT_ABORT_IF(fail);
+        RT_STAMP(10);
         if (tid < kRMax * kBMax) {
             float zv = 0.f, zg = 0.f;
             const int o = o_lo + erow;
@@ -524,7 +580,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             }
             const float zn = __shfl_down(zg, 16, 64);
             if (!(erow & 1) && erow < o_n && eb < B)
-                ll_store(A.z_ll + par * half_d + (size_t)eb * (d / 2) + o / 2, tag,
+                ll_store(A.z_ll + par * half_d + frag_word<KSD>(o, eb), tag,
                          (unsigned)f32_to_bf16(zg) | ((unsigned)f32_to_bf16(zn) << 16));
             sq[erow * kBMax + eb] = zv * zv;
         }
@@ -536,7 +592,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             if (tid < B) ll_store(A.zss_ll + par * sz_ss + (size_t)tid * G + wg, tag, __float_as_uint(s));
         }
         __syncthreads();
-        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 5] = wall_clock64();
+        RT_STAMP(5);
 
         // ================================================================ phase KV:  [Wk; Wv] (z g_kv)
         gate_wait(A.zss_ll + par * sz_ss, G, tag, A, fail);   // batch row 0's partial sums: one word per producer
@@ -546,7 +602,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         if (tid < kRMax * kBMax && erow < kv_n && eb < B)
             ll_store(A.kv_ll + par * sz_kv + (size_t)eb * 2 * d + kv_lo + erow, tag, __float_as_uint(red_sum(red, erow, eb)));
         __syncthreads();
-        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 8 + 6] = wall_clock64();
+        RT_STAMP(6);
     }
 }
 
@@ -631,7 +687,7 @@ rt_status persistent_create(PersistentState &P, const rt_config &cfg, const Laye
     const size_t o_kv = carve(2 * kBMax * 2 * d * 8);
     const size_t o_hss = carve((size_t)2 * kBMax * G * 8), o_zss = carve((size_t)2 * kBMax * G * 8);
     const size_t o_dm = carve(2 * 256 * 8), o_d1 = carve(2 * 256 * 8);
-    const size_t o_tr = want_trace ? carve((size_t)cfg.max_seq * 8 * 8) : 0;
+    const size_t o_tr = want_trace ? carve((size_t)cfg.max_seq * 16 * 8) : 0;
     P.slab_bytes = off;
     if (hipMalloc(&P.slab, P.slab_bytes) != hipSuccess) {
         (void)hipGetLastError();
@@ -720,7 +776,7 @@ int persistent_read_trace(PersistentState &P, unsigned long long *out, int rows)
 {
     if (!P.trace || !out) return 0;
     const int n = rows < P.trace_rows ? rows : P.trace_rows;
-    if (hipMemcpy(out, P.trace, (size_t)n * 8 * 8, hipMemcpyDeviceToHost) != hipSuccess) return -1;
+    if (hipMemcpy(out, P.trace, (size_t)n * 16 * 8, hipMemcpyDeviceToHost) != hipSuccess) return -1;
     return n;
 }
 
