@@ -179,9 +179,9 @@ __device__ __forceinline__ bool grid_barrier(const PersistArgs &A, unsigned long
 typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
 constexpr int kAuxAgent = 16;   // cache-policy operand of the buffer load: sc1 (agent scope)
 
-template <int KS>
+template <int KS, bool SS = false>
 __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, const ll_t *act, int row_words, int B,
-                                           unsigned tag, const PersistArgs &A, float *red, int &fail)
+                                           unsigned tag, const PersistArgs &A, float *red, int &fail, float *ss_s = nullptr)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int l16 = lane & 15, g = lane >> 4;
@@ -208,6 +208,21 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
         }
         if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
     }
+    if (SS) {   // sum of squares of this lane's elements -> ss_s[wave][b] (the consumer's own RMS statistic)
+        float ss = 0.f;
+#pragma unroll
+        for (int i = 0; i < 2 * KS; ++i) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const float lo = __uint_as_float(v[i][2 * h] << 16), hi = __uint_as_float(v[i][2 * h] & 0xFFFF0000u);
+                ss = fmaf(lo, lo, ss);
+                ss = fmaf(hi, hi, ss);
+            }
+        }
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (g == 0) ss_s[wave * kBMax + l16] = ss;
+    }
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
 #pragma unroll
@@ -231,14 +246,25 @@ __device__ __forceinline__ float red_sum(const float *red, int row, int b)
 }
 
 // rows [row0, row0+nrows), columns [col0, col0+K) of a row-major matrix with leading dimension src_ld
+// If `gain` is given the columns are scaled by it (W diag(g), rounded to bf16 once): the RMS gain of a
+// product's input is folded into the stationary weights, so the exchanged vectors carry no gain.
 __device__ __forceinline__ void copy_rows_to_lds(bf16_t *dst, int ldw, const bf16_t *src, int src_ld, int col0, int K, int row0,
-                                                 int nrows)
+                                                 int nrows, const bf16_t *gain = nullptr)
 {
     const int per_row = K / 8;  // 16-byte pieces
     for (int idx = threadIdx.x; idx < nrows * per_row; idx += kPThreads) {
         const int r = idx / per_row, c = idx - r * per_row;
-        *reinterpret_cast<uint4 *>(dst + (size_t)r * ldw + c * 8) =
-            *reinterpret_cast<const uint4 *>(src + (size_t)(row0 + r) * src_ld + col0 + c * 8);
+        uint4 w = *reinterpret_cast<const uint4 *>(src + (size_t)(row0 + r) * src_ld + col0 + c * 8);
+        if (gain) {
+            float gg[8], ww[8];
+            load8(gain + col0 + c * 8, gg);
+            load8(reinterpret_cast<const bf16_t *>(&w), ww);
+            w.x = (unsigned)f32_to_bf16(ww[0] * gg[0]) | ((unsigned)f32_to_bf16(ww[1] * gg[1]) << 16);
+            w.y = (unsigned)f32_to_bf16(ww[2] * gg[2]) | ((unsigned)f32_to_bf16(ww[3] * gg[3]) << 16);
+            w.z = (unsigned)f32_to_bf16(ww[4] * gg[4]) | ((unsigned)f32_to_bf16(ww[5] * gg[5]) << 16);
+            w.w = (unsigned)f32_to_bf16(ww[6] * gg[6]) | ((unsigned)f32_to_bf16(ww[7] * gg[7]) << 16);
+        }
+        *reinterpret_cast<uint4 *>(dst + (size_t)r * ldw + c * 8) = w;
     }
 }
 
@@ -367,15 +393,14 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     // W2 is split in two dimensions: row block rb (RB = d/64 rows) x contraction block jb (d columns of F = 4d)
     const int rb = wg >> 2, jb = wg & 3, RB = A.R_2;
     copy_rows_to_lds(wo_s, A.ldw_d, A.Wo, d, 0, d, o_lo, o_n);
-    copy_rows_to_lds(w1_s, A.ldw_d, A.W1, d, 0, d, f_lo, f_n);
+    const bf16_t *gm = A.norm_free ? nullptr : A.g_mlp, *gkv = A.norm_free ? nullptr : A.g_kv;
+    copy_rows_to_lds(w1_s, A.ldw_d, A.W1, d, 0, d, f_lo, f_n, gm);
     copy_rows_to_lds(w2_s, A.ldw_d, A.W2, F, jb * d, d, rb * RB, RB);
-    {
-        const int per_row = d / 8;
-        for (int idx = tid; idx < kv_n * per_row; idx += kPThreads) {
-            const int r = idx / per_row, c = idx - r * per_row;
+    {   // [Wk; Wv] rows, one at a time (a row block may straddle the two matrices)
+        for (int r = 0; r < kv_n; ++r) {
             const int o = kv_lo + r;
-            const bf16_t *src = (o < d) ? A.Wk + (size_t)o * d : A.Wv + (size_t)(o - d) * d;
-            *reinterpret_cast<uint4 *>(wkv_s + (size_t)r * A.ldw_d + c * 8) = *reinterpret_cast<const uint4 *>(src + c * 8);
+            if (o < d) copy_rows_to_lds(wkv_s + (size_t)r * A.ldw_d, A.ldw_d, A.Wk, d, 0, d, o, 1, gkv);
+            else copy_rows_to_lds(wkv_s + (size_t)r * A.ldw_d, A.ldw_d, A.Wv, d, 0, d, o - d, 1, gkv);
         }
     }
     __syncthreads();
@@ -528,37 +553,25 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         RT_ABORT_IF(fail);
         RT_STAMP(8);
         if (tid < kRMax * kBMax) {
-            float hv = 0.f, hg = 0.f;
+            float hv = 0.f;
             const int o = o_lo + erow;
-            if (erow < o_n && eb < B) {
-                hv = xv + A.alpha * red_sum(red, erow, eb);
-                hg = hv * (A.g_mlp && !A.norm_free ? bf16_to_f32(A.g_mlp[o]) : 1.f);
-            }
-            const float hn = __shfl_down(hg, 16, 64);
+            if (erow < o_n && eb < B) hv = xv + A.alpha * red_sum(red, erow, eb);
+            const float hn = __shfl_down(hv, 16, 64);
             if (!(erow & 1) && erow < o_n && eb < B)
                 ll_store(A.h_ll + par * half_d + frag_word<KSD>(o, eb), tag,
-                         (unsigned)f32_to_bf16(hg) | ((unsigned)f32_to_bf16(hn) << 16));
+                         (unsigned)f32_to_bf16(hv) | ((unsigned)f32_to_bf16(hn) << 16));
             h_loc[erow * kBMax + eb] = hv;
-            sq[erow * kBMax + eb] = hv * hv;
-        }
-        __syncthreads();
-        if (tid < kBMax) {
-            float s = 0.f;
-#pragma unroll
-            for (int r = 0; r < kRMax; ++r) s += sq[r * kBMax + tid];
-            if (tid < B) ll_store(A.hss_ll + par * sz_ss + (size_t)tid * G + wg, tag, __float_as_uint(s));
         }
         __syncthreads();
         RT_STAMP(3);
 
         // ================================================================ phase 1:  u = gelu(rinv_h * W1 h)
-        wg_gemv_ll<KSD>(w1_s, A.ldw_d, f_n, A.h_ll + par * half_d, d / 2, B, tag, A, red, fail);
-        gather_partial_sums(A.hss_ll + par * sz_ss, G, B, tag, A, sq, fail);   // stored right after the h words: there by now
+        wg_gemv_ll<KSD, true>(w1_s, A.ldw_d, f_n, A.h_ll + par * half_d, d / 2, B, tag, A, red, fail, sq);
         RT_ABORT_IF(fail);
-        if (tid < kBMax) {
+        if (tid < kBMax) {   // 1/rms(h) from the values this workgroup just received
             float s = 0.f;
 #pragma unroll
-            for (int r = 0; r < kPThreads / 16; ++r) s += sq[r * kBMax + tid];
+            for (int w = 0; w < kPW; ++w) s += sq[w * kBMax + tid];
             rinv_s[tid] = A.norm_free ? 1.f : rsqrtf(s / (float)d + A.eps);
         }
         __syncthreads();
@@ -608,7 +621,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                                   (__uint_as_float((unsigned)w4[2]) + __uint_as_float((unsigned)w4[3]));
                 zv = h_loc[erow * kBMax + eb] + A.alpha * acc;
                 A.y[((size_t)eb * A.N + t) * d + o] = f32_to_bf16(zv);
-                zg = zv * (A.g_kv && !A.norm_free ? bf16_to_f32(A.g_kv[o]) : 1.f);
+                zg = zv;   // the gain of RMS(z) is folded into the stationary Wk, Wv
             }
             const float zn = __shfl_down(zg, 16, 64);
             if (!(erow & 1) && own)
