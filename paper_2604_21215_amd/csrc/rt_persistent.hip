@@ -362,6 +362,69 @@ __device__ __forceinline__ void gather_partial_sums(const ll_t *ss, int G, int B
         }                                                                                                  \
     } while (0)
 
+// Part of the merge of a position that does not need its newest key: the temporary pair, the stored
+// partial states (bits of c = t-1 at or above p_min) and the direct window.  The loads are issued one
+// phase ahead (pre_issue, at the start of phase KV of the previous position) and combined after that
+// phase's own work (pre_finish), so that phase M only waits for the raw k, v of the newest key.
+struct PreLoad {
+    float q, kt, vt;
+    float pm[kMaxLevels], pl[kMaxLevels], po[kMaxLevels];
+};
+
+__device__ __forceinline__ void pre_issue(const PersistArgs &A, int t, int u, PreLoad &L)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t rs = (size_t)A.BH * kHeadDim;
+    const size_t qoff = (size_t)t * rs + (size_t)u * kHeadDim + lane;
+    L.q = bf16_to_f32(A.Q[qoff]);
+    L.kt = bf16_to_f32(A.Kt[qoff]);
+    L.vt = bf16_to_f32(A.Vt[qoff]);
+    const int c = t - 1;
+#pragma unroll
+    for (int lr = 0; lr < kMaxLevels; ++lr) {
+        const int lv = lr + A.log2_pmin;
+        const bool on = t >= 2 && lr < A.levels && ((c >> lv) & 1);
+        const size_t idx = on ? partial_index(lr, partial_slot(lv, c), A.slots, A.BH, u) : 0;
+        L.pm[lr] = on ? A.pm[idx] : -INFINITY;
+        L.pl[lr] = on ? A.pl[idx] : 0.f;
+        L.po[lr] = on ? A.po[idx * kHeadDim + lane] : 0.f;
+    }
+}
+
+__device__ __forceinline__ void pre_finish(const PersistArgs &A, int t, int u, const PreLoad &L, const bf16_t *wk,
+                                           const bf16_t *wv, float &q, float &m, float &l, float &o)
+{
+    q = L.q;
+    m = A.scale * fast_sum(L.q * L.kt);
+    l = 1.f;
+    o = L.vt;
+    if (t < 2) return;
+    float mx = m;
+#pragma unroll
+    for (int lr = 0; lr < kMaxLevels; ++lr) mx = fmaxf(mx, L.pm[lr]);
+    const float e0 = __expf(m - mx);
+    l *= e0;
+    o *= e0;
+#pragma unroll
+    for (int lr = 0; lr < kMaxLevels; ++lr) {
+        const float f = __expf(L.pm[lr] - mx);   // exp(-inf) = 0 for absent levels
+        l = fmaf(L.pl[lr], f, l);
+        o = fmaf(L.po[lr], f, o);
+    }
+    m = mx;
+    const int c = t - 1;
+    const int w = c & (A.p_min - 1);
+    if (w > 0) {
+        if (A.win_rows) {
+            attend_lds(q, wk, wv, w, A.scale, m, l, o);
+        } else {
+            const size_t rs = (size_t)A.BH * kHeadDim;
+            const size_t base = (size_t)(c - w) * rs + (size_t)u * kHeadDim;
+            attend_keys<bf16_t>(q, A.K + base, A.V + base, rs, w, A.scale, m, l, o);
+        }
+    }
+}
+
 // KSD = d / 256, KSF = F / 256: contraction steps per wavefront, fixed at compile time so that all
 // exchange loads of a phase are in flight at once without spilling.
 template <int KSD, int KSF>
@@ -411,6 +474,17 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     const size_t half_d = (size_t)kBMax * (d / 2), half_F = (size_t)kBMax * (F / 2);
     const size_t sz_kv = (size_t)kBMax * 2 * d, sz_ss = (size_t)kBMax * G;
 
+    // this wavefront's merge unit (at most one: B*H <= G*kPW), and its pre-merged state for the next position
+    const int my_u = wg + G * wave;
+    const bool has_u = my_u < BH;
+    const bf16_t *my_wk = win_k + (size_t)wave * A.win_rows * kHeadDim, *my_wv = win_v + (size_t)wave * A.win_rows * kHeadDim;
+    float cq = 0.f, cm = 0.f, cl = 1.f, co = 0.f;
+    if (has_u) {
+        PreLoad L;
+        pre_issue(A, 0, my_u, L);
+        pre_finish(A, 0, my_u, L, my_wk, my_wv, cq, cm, cl, co);
+    }
+
     for (int t = 0; t <= A.N; ++t) {
         const int par = t & 1, ppar = par ^ 1;
         const unsigned tag = A.tag_base | (unsigned)(t + 1);   // words produced at position t
@@ -420,52 +494,10 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         float xv = 0.f;   // residual input of this workgroup's rows, fetched ahead of phase O
         if (t < A.N && tid < kRMax * kBMax && erow < o_n && eb < B) xv = bf16_to_f32(A.x[((size_t)eb * A.N + t) * d + o_lo + erow]);
         // ================================================================ phase M
-        for (int u = wg + G * wave; u < BH; u += G * kPW) {
+        if (has_u) {
+            const int u = my_u;
             const int b = u / A.H, h = u - b * A.H;
-            // (1) everything that does not need the newest key: temporary pair, stored partials, window
-            float q = 0.f, m = 0.f, l = 1.f, o = 0.f;
-            if (t < A.N) {
-                const size_t qoff = (size_t)t * rs + (size_t)u * kHeadDim + lane;
-                q = bf16_to_f32(A.Q[qoff]);
-                m = A.scale * fast_sum(q * bf16_to_f32(A.Kt[qoff]));
-                o = bf16_to_f32(A.Vt[qoff]);
-                if (t >= 2) {
-                    const int c = t - 1;
-                    float pmv[kMaxLevels], plv[kMaxLevels], pov[kMaxLevels];
-#pragma unroll
-                    for (int lr = 0; lr < kMaxLevels; ++lr) {
-                        const int lv = lr + A.log2_pmin;
-                        const bool on = lr < A.levels && ((c >> lv) & 1);
-                        const size_t idx = on ? partial_index(lr, partial_slot(lv, c), A.slots, BH, u) : 0;
-                        pmv[lr] = on ? A.pm[idx] : -INFINITY;
-                        plv[lr] = on ? A.pl[idx] : 0.f;
-                        pov[lr] = on ? A.po[idx * kHeadDim + lane] : 0.f;
-                    }
-                    float mx = m;
-#pragma unroll
-                    for (int lr = 0; lr < kMaxLevels; ++lr) mx = fmaxf(mx, pmv[lr]);
-                    const float e0 = __expf(m - mx);
-                    l *= e0;
-                    o *= e0;
-#pragma unroll
-                    for (int lr = 0; lr < kMaxLevels; ++lr) {
-                        const float f = __expf(pmv[lr] - mx);   // exp(-inf) = 0 for absent levels
-                        l = fmaf(plv[lr], f, l);
-                        o = fmaf(pov[lr], f, o);
-                    }
-                    m = mx;
-                    const int w = c & (A.p_min - 1);
-                    if (w > 0) {
-                        if (A.win_rows) {
-                            const size_t wo = (size_t)(u / G) * A.win_rows * kHeadDim;
-                            attend_lds(q, win_k + wo, win_v + wo, w, A.scale, m, l, o);
-                        } else {
-                            const size_t base = (size_t)(c - w) * rs + (size_t)u * kHeadDim;
-                            attend_keys<bf16_t>(q, A.K + base, A.V + base, rs, w, A.scale, m, l, o);
-                        }
-                    }
-                }
-            }
+            float q = cq, m = cm, l = cl, o = co;   // pre-merged one phase ahead
             // (2) the newest key: position t-1's raw k, v arrive from phase KV, are finished and stored here
             if (t >= 1) {
                 const ll_t *p[6];
@@ -644,10 +676,14 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             gate_wait(A.zss_ll + par * sz_ss, G, tag, A, fail);   // batch row 0's partial sums: one word per producer
             RT_ABORT_IF(fail);
         }
+        PreLoad L;
+        const bool pre = has_u && t + 1 < A.N;
+        if (pre) pre_issue(A, t + 1, my_u, L);   // loads fly while this phase polls and multiplies
         wg_gemv_ll<KSD>(wkv_s, A.ldw_d, kv_n, A.z_ll + par * half_d, d / 2, B, tag, A, red, fail);
         RT_ABORT_IF(fail);
         if (tid < kRMax * kBMax && erow < kv_n && eb < B)
             ll_store(A.kv_ll + par * sz_kv + (size_t)eb * 2 * d + kv_lo + erow, tag, __float_as_uint(red_sum(red, erow, eb)));
+        if (pre) pre_finish(A, t + 1, my_u, L, my_wk, my_wv, cq, cm, cl, co);   // overlaps the raw k, v crossing the chip
         __syncthreads();
         RT_STAMP(6);
     }
