@@ -21,6 +21,7 @@ struct PersistentState {
     void *kv_ll = nullptr, *hss_ll = nullptr, *zss_ll = nullptr, *done_m = nullptr, *done_1 = nullptr, *zp_ll = nullptr;
     int win_rows = 0, upw = 1;
     int gate_mask = 0;
+    int max_batch = 0;
     unsigned nonce = 0;                  // per-call tag prefix of the exchange words
     unsigned long long *trace = nullptr; // optional per-position phase clocks
     int trace_rows = 0;
