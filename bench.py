@@ -15,6 +15,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# L2<->fabric bytes of one persistent_kernel launch on workload cfg3, from two rocprofv3 --pmc runs (FETCH_SIZE, then
+# WRITE_SIZE) scaled by what the same counters read for a plain 256 MiB copy: fetch 7.31 GB + write 4.22 GB.
+MEASURED_TRAFFIC_BYTES = {("cfg3", "persistent"): 7136588 * 1024 + 4125567 * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -56,6 +59,9 @@ def main():
     ap.add_argument("--p-min", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-sample-positions", type=int, default=1024)
+    ap.add_argument("--traffic-calibration", action="store_true",
+                    help="also run one plain 256 MiB device copy, the reference the rocprofv3 FETCH_SIZE / WRITE_SIZE "
+                         "counters of the prefill kernel are scaled by")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (one process, one device); --gpus %d is not supported"
@@ -81,6 +87,12 @@ def main():
     K = torch.zeros((wl.N, wl.B, wl.H, wl.head_dim), dtype=xd.dtype, device=xd.device)
     V = torch.zeros_like(K)
 
+    if args.traffic_calibration:
+        big = torch.empty(256 * 2**20, dtype=torch.uint8, device=xd.device)
+        big.zero_()
+        big2 = big.clone()          # one copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del big, big2
     for _ in range(args.warmup):
         ctx.rt_layer_prefill(dl.struct, xd, y, K, V)
     torch.cuda.synchronize()
@@ -111,7 +123,8 @@ def main():
         "bound": "hbm",
         "kernel": ("persistent_kernel (one launch per call; the call's two small pre-pass kernels are inside the timed events)"
                    if resident else "rt_layer_prefill (%s engine, all launches of one call)" % engine),
-        "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+        "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+        "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, engine)),
         "launch_ms": dev_ms, "algorithmic_bytes": alg_bytes, "terms": terms,
         "us_per_position": dev_ms * 1e3 / wl.N,
         # what a design that re-streams the loop's weights at every position would have to move, for comparison
