@@ -1,40 +1,52 @@
 // Single-launch ("persistent") engine of the sequential loop, bf16 storage.
 //
-// One cooperative grid of one workgroup per compute unit runs all N positions.  The five matrices
-// of the loop (Wo, W1, W2, Wk, Wv) are split by output rows over the workgroups and held in LDS for
-// the whole call (weight-stationary: 11 d^2 bf16 elements over 256 x 160 KB of LDS), so a position
-// costs no weight traffic at all.  What remains on the critical path is the exchange of the small
-// activation vectors between the phases of a position:
+// One cooperative grid of 256 workgroups (one per compute unit) x 512 threads runs all N positions.
+// The five matrices of the loop (Wo, W1, W2, Wk, Wv) are split over the workgroups and held in LDS
+// for the whole call (weight-stationary: 11 d^2 bf16 elements over 256 x 160 KB of LDS), so a position
+// costs no weight traffic at all.  Wo, W1, [Wk; Wv] are split by output rows; W2 in two dimensions
+// (64 row blocks x 4 contraction blocks) so that no workgroup has to pull the 4d-wide hidden vector.
+// The RMS gains g_mlp, g_kv are folded into the stationary W1, Wk, Wv (W diag(g), rounded once), and
+// each RMS scale is applied after its product (the products are linear in their input), so the
+// exchanged vectors carry neither gain nor norm and no phase waits for a statistic.
 //
-//   M   per (b, h) wavefront: finish the persistent pair of position t-1 (RMS scale of z, qkRMS of k,
-//       store K, V and the transposed value copy), then merge the stored partial softmax states, the
-//       direct window, the newest key and the temporary pair into a_t                    -> a
-//   O   h = x_t + alpha Wo a                       -> bf16(h * g_mlp), partial sums of squares
-//   1   u = gelu(rinv_h * W1 (h g_mlp))            -> u
-//   2   z = h + alpha W2 u   (same rows as O)      -> y, bf16(z * g_kv), partial sums of squares
-//   KV  [Wk; Wv] (z g_kv)  (RMS scale applied by M) -> raw k, v
+// What remains on the critical path is the exchange of small vectors between the phases of a position:
+//
+//   M    per (b, h) wavefront: poll the raw k, v of position t-1 and the partial sums of z^2; finish
+//        that persistent pair (RMS scale of z, qkRMS of k; store K, V, the transposed value copy and
+//        the LDS window row); fold it as the newest key into the pre-merged softmax state   -> a
+//   O    h = x_t + alpha Wo a                                                                -> bf16(h)
+//   1    u = gelu(W1' h / rms(h)),  1/rms(h) from the received values themselves             -> u
+//   2a   partial W2 u over one quarter of the hidden dimension                               -> 4 partial sums
+//   2b   z = h + alpha (sum of partials), same rows as O                      -> y, bf16(z), partial sums of z^2
+//   KV   [Wk'; Wv'] z  (scale 1/rms(z) applied in M)                                         -> raw k, v
+//        and, on the wavefronts that own a (b, h): the pre-merge of position t+1 (temporary pair,
+//        stored partial states of the bits of c = t at or above p_min, direct window out of LDS),
+//        issued before and finished after this phase's own work, in the shadow of the k, v hop.
 //
 // Exchange format: every value crosses the chip inside a self-validating 64-bit word
 // [tag:32 | payload:32] (payload = two bf16 or one fp32), written with one 8-byte agent-scope atomic
-// store and polled with 8-byte atomic loads until the tag equals the tag of (call, position).  A hop
-// therefore costs one store-to-load trip through the memory side instead of a fenced grid barrier
-// (measured on MI355X: about 3 us against about 10 us).  Buffers alternate with the parity of t; a
-// writer of position t+2 has always (transitively) gathered a full vector of position t+1, which
-// every workgroup produced after it had finished reading position t.
+// store.  Consumers poll the data itself until every tag equals the tag of (call, position): a hop
+// costs one store-to-load trip through the memory side.  Measured on MI355X with 256 workgroups: a
+// fenced grid barrier (release, counter, acquire) 7.5-11 us, the fences alone 3.6-7.9 us, a counter
+// barrier without fences 4.2 us, a flag-in-data all-to-all hop 2.7-3.3 us; waiting for separate
+// "producer done" words before the bulk loads was slower than polling the data (39.8 vs 34.3 us per
+// position, kept behind gate_mask for experiments).  Bulk loads are pulled thread-linearly with 16-byte
+// agent-scope buffer loads and staged in LDS (see wg_gemv_ll).  Buffers alternate with the parity of t;
+// a writer of position t+2 has always (transitively) gathered the partial sums of z^2 of position t+1
+// from all workgroups, which each of them stored after it had finished reading position t.
 //
 // K, V, the transposed value copy and the partial softmax states live in ordinary cached memory.
-// The per-position window only re-reads rows that the same wavefront wrote.  Cross-workgroup use
-// happens at the cross-block events (every p_min positions): those are bracketed by two fenced grid
-// barriers (release / acquire at agent scope).
+// The per-position window only re-reads rows that the same wavefront wrote (kept in LDS when
+// p_min <= 64).  Cross-workgroup use happens at the cross-block events (every p_min positions): those
+// run inline on all wavefronts, bracketed by two fenced grid barriers (release / acquire, agent scope).
 //
-// The RMS scale is applied after each product (the products are linear in their input), so no phase
-// waits for a norm.  Relative to the per-position engine the block decomposition is shifted by one:
-// query t takes its newest key t-1 directly (the wavefront that merges has just finished that key),
-// keys [0, t-1) are split by the bits of c = t-1 into stored partials (blocks >= p_min) and the
-// direct window.
+// Relative to the per-position engine the block decomposition is shifted by one: query t takes its
+// newest key t-1 directly (the wavefront that merges has just finished that key), keys [0, t-1) are
+// split by the bits of c = t-1 into stored partials (blocks >= p_min) and the direct window.  The
+// UpdateTile of the block ending at key e-1 therefore has a whole position of slack.
 //
 // Every wait is bounded: a poll loop that exceeds spin_limit raises the abort word, every workgroup
-// leaves the kernel at its next wait, and the host reports it.
+// leaves the kernel at its next wait, and the host reports it (rt_device_wait_expired).
 #include "rt_persistent.h"
 #include "rt_mfma_device.h"
 
