@@ -119,6 +119,7 @@ struct PersistArgs {
     ll_t *done_m, *done_1;      // [2][256]    "producer finished" words of phase M (per unit) and phase 1 (per workgroup)
     int win_rows;               // p_min when the direct window is kept in LDS, else 0 (window re-read from K, V)
     int upw;                    // merge units per workgroup = ceil(BH_max / G)
+    int max_batch;              // rows of the LDS staging area
     unsigned tag_base;          // (call nonce) << 20
     unsigned long long *bar;    // [0] fenced-barrier counter, [8] abort word
     unsigned long long *trace;  // optional: [N][16] wall-clock stamps of workgroup 0
@@ -418,6 +419,30 @@ __device__ __forceinline__ void pre_issue(const PersistArgs &A, int t, int u, Pr
     }
 }
 
+// PreLoad <-> LDS (layout: q, kt, vt rows of 64, then pm[], pl[] as broadcast scalars, then po[][64])
+constexpr int kPreFloats = 3 * 64 + 2 * kMaxLevels + kMaxLevels * 64;
+__device__ __forceinline__ void pre_to_lds(const PreLoad &L, float *s)
+{
+    const int lane = threadIdx.x & 63;
+    s[lane] = L.q; s[64 + lane] = L.kt; s[128 + lane] = L.vt;
+#pragma unroll
+    for (int lr = 0; lr < kMaxLevels; ++lr) {
+        if (lane == 0) { s[192 + lr] = L.pm[lr]; s[192 + kMaxLevels + lr] = L.pl[lr]; }
+        s[192 + 2 * kMaxLevels + lr * 64 + lane] = L.po[lr];
+    }
+}
+__device__ __forceinline__ void pre_from_lds(const float *s, PreLoad &L)
+{
+    const int lane = threadIdx.x & 63;
+    L.q = s[lane]; L.kt = s[64 + lane]; L.vt = s[128 + lane];
+#pragma unroll
+    for (int lr = 0; lr < kMaxLevels; ++lr) {
+        L.pm[lr] = s[192 + lr];
+        L.pl[lr] = s[192 + kMaxLevels + lr];
+        L.po[lr] = s[192 + 2 * kMaxLevels + lr * 64 + lane];
+    }
+}
+
 __device__ __forceinline__ void pre_finish(const PersistArgs &A, int t, int u, const PreLoad &L, const bf16_t *wk,
                                            const bf16_t *wv, float &q, float &m, float &l, float &o)
 {
@@ -475,6 +500,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     bf16_t *win_k = reinterpret_cast<bf16_t *>(flag_s + 4);                    // [upw][win_rows][64]
     bf16_t *win_v = win_k + (size_t)A.upw * A.win_rows * kHeadDim;
     bf16_t *act_s = win_v + (size_t)A.upw * A.win_rows * kHeadDim;             // [max_batch][ldw_d] staged activations
+    float *pre_s = reinterpret_cast<float *>(act_s + (size_t)A.max_batch * A.ldw_d);   // [upw][kPreFloats] pre-fetched merge inputs
 
     // ---- this workgroup's rows
     const int o_lo = min(wg * A.R_o, d), o_n = min(d, o_lo + A.R_o) - o_lo;          // Wo, W2
@@ -507,9 +533,20 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     const bool has_u = my_u < BH;
     const bf16_t *my_wk = win_k + (size_t)wave * A.win_rows * kHeadDim, *my_wv = win_v + (size_t)wave * A.win_rows * kHeadDim;
     float cq = 0.f, cm = 0.f, cl = 1.f, co = 0.f;
+    // The loads of a pre-merge are made by an otherwise idle helper wavefront (wave 4 + slot, during
+    // phase 2b) and handed over through LDS, so that no wavefront carries them in registers across a phase.
+    const int help_slot = wave - 4;
+    const int help_u = wg + G * help_slot;
+    const bool is_helper = help_slot >= 0 && help_slot < A.upw && help_u < BH;
+    if (is_helper) {
+        PreLoad L;
+        pre_issue(A, 0, help_u, L);
+        pre_to_lds(L, pre_s + (size_t)help_slot * kPreFloats);
+    }
+    __syncthreads();
     if (has_u) {
         PreLoad L;
-        pre_issue(A, 0, my_u, L);
+        pre_from_lds(pre_s + (size_t)wave * kPreFloats, L);
         pre_finish(A, 0, my_u, L, my_wk, my_wv, cq, cm, cl, co);
     }
 
@@ -663,6 +700,11 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         RT_STAMP(13);
 
         // ================================================================ phase 2b:  z = h + alpha (sum of the four partials)
+        if (is_helper && t + 1 < A.N) {   // wavefronts 4.. are idle in this phase: fetch the next position's merge inputs
+            PreLoad L;
+            pre_issue(A, t + 1, help_u, L);
+            pre_to_lds(L, pre_s + (size_t)help_slot * kPreFloats);
+        }
         if (tid < kRMax * kBMax) {   // four full wavefronts
             float zv = 0.f, zg = 0.f;
             const int o = o_lo + erow;
@@ -704,14 +746,16 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             gate_wait(A.zss_ll + par * sz_ss, G, tag, A, fail);   // batch row 0's partial sums: one word per producer
             RT_ABORT_IF(fail);
         }
-        PreLoad L;
         const bool pre = has_u && t + 1 < A.N;
-        if (pre) pre_issue(A, t + 1, my_u, L);   // loads fly while this phase polls and multiplies
         wg_gemv_ll<KSD>(wkv_s, A.ldw_d, kv_n, A.z_ll + par * half_d, d / 2, B, tag, A, red, act_s, A.ldw_d, fail);
         RT_ABORT_IF(fail);
         if (tid < kRMax * kBMax && erow < kv_n && eb < B)
             ll_store(A.kv_ll + par * sz_kv + (size_t)eb * 2 * d + kv_lo + erow, tag, __float_as_uint(red_sum(red, erow, eb)));
-        if (pre) pre_finish(A, t + 1, my_u, L, my_wk, my_wv, cq, cm, cl, co);   // overlaps the raw k, v crossing the chip
+        if (pre) {   // overlaps the raw k, v crossing the chip
+            PreLoad L;
+            pre_from_lds(pre_s + (size_t)wave * kPreFloats, L);
+            pre_finish(A, t + 1, my_u, L, my_wk, my_wv, cq, cm, cl, co);
+        }
         __syncthreads();
         RT_STAMP(6);
     }
@@ -754,6 +798,7 @@ static size_t lds_bytes_for(int d, int F, int G, int win_rows, int upw, int max_
     b += (size_t)(kPW * kRMax * kBMax + kRMax * kBMax + 32 * kBMax + kBMax) * 4 + 16;
     b += (size_t)2 * upw * win_rows * kHeadDim * 2;   // direct-window rows of this workgroup's merge units
     b += (size_t)max_batch * ldw_d * 2;                // staged activation rows of the phase in flight
+    b += (size_t)upw * kPreFloats * 4;                 // pre-fetched merge inputs
     return b;
 }
 
@@ -771,7 +816,7 @@ rt_status persistent_create(PersistentState &P, const rt_config &cfg, const Laye
     int R_o, R_1, R_kv;
     P.upw = ((cfg.max_batch < kBMax ? cfg.max_batch : kBMax) * D.H + G - 1) / G;
     P.max_batch = cfg.max_batch < kBMax ? cfg.max_batch : kBMax;   // larger batches take the per-position engine
-    if (P.upw > kPW || (cfg.max_batch < kBMax ? cfg.max_batch : kBMax) * D.H > 256) return RT_ERR_UNSUPPORTED;
+    if (P.upw > 4 || (cfg.max_batch < kBMax ? cfg.max_batch : kBMax) * D.H > 256) return RT_ERR_UNSUPPORTED;
     P.win_rows = D.p_min <= 64 ? D.p_min : 0;
     const size_t lds = lds_bytes_for(D.d, D.F, G, P.win_rows, P.upw, P.max_batch, &R_o, &R_1, &R_kv);
     if (R_o > kRMax || R_1 > kRMax || R_kv > kRMax) return RT_ERR_UNSUPPORTED;
@@ -854,7 +899,7 @@ rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weigh
     A.alpha = D.alpha; A.scale = D.scale; A.eps = D.eps; A.norm_free = D.norm_free;
     A.G = P.grid;
     (void)lds_bytes_for(D.d, D.F, P.grid, P.win_rows, P.upw, P.max_batch, &A.R_o, &A.R_1, &A.R_kv);
-    A.win_rows = P.win_rows; A.upw = P.upw;
+    A.win_rows = P.win_rows; A.upw = P.upw; A.max_batch = P.max_batch;
     A.ldw_d = D.d + 8; A.ldw_F = D.F + 8;
     A.Wo = (const bf16_t *)W.Wo; A.W1 = (const bf16_t *)W.W1; A.W2 = (const bf16_t *)W.W2;
     A.Wk = (const bf16_t *)W.Wk; A.Wv = (const bf16_t *)W.Wv;
