@@ -170,6 +170,8 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
     auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
     const size_t oQ = carve(Nm * Bm * d * E), oKt = carve(Nm * Bm * d * E), oVt = carve(Nm * Bm * d * E);
     const size_t oVT = mfma ? carve(Bm * H * kHeadDim * (size_t)S.vt_stride * 2) : 0;
+    const size_t oQf = mfma ? carve(Nm * Bm * d * 4) : 0, oKtf = mfma ? carve(Nm * Bm * d * 4) : 0;
+    const size_t oKlo = mfma ? carve(Nm * Bm * d * 2) : 0;
     const size_t np = (size_t)S.levels * S.slots * Bm * H;
     const size_t opm = carve(np * 4), opl = carve(np * 4), opo = carve(np * kHeadDim * 4);
     const size_t orinv = carve(Bm * Nm * 4);
@@ -185,6 +187,9 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
     char *p = (char *)c->slab;
     S.Q = p + oQ; S.Kt = p + oKt; S.Vt = p + oVt;
     S.VT = mfma ? (bf16_t *)(p + oVT) : nullptr;
+    S.Qf = mfma ? (float *)(p + oQf) : nullptr;
+    S.Ktf = mfma ? (float *)(p + oKtf) : nullptr;
+    S.Klo = mfma ? (bf16_t *)(p + oKlo) : nullptr;
     S.pm = (float *)(p + opm); S.pl = (float *)(p + opl); S.po = (float *)(p + opo);
     S.rinv = (float *)(p + orinv);
     S.attn_cat = (float *)(p + ocat); S.h = (float *)(p + oh); S.u = (float *)(p + ou); S.z = (float *)(p + oz);

@@ -119,6 +119,8 @@ struct Weights {
 //   pm, pl : [levels][slots][B*H]        po : [levels][slots][B*H][64]     (fp32)
 struct Scratch {
     void *Q, *Kt, *Vt;   // [N][B][H][64] storage dtype: queries and temporary pairs
+    float *Qf, *Ktf;     // [N][B][H][64] unrounded q and k_tmp (persistent engine's high-precision logits), or null
+    bf16_t *Klo;         // [N][B][H][64] bf16 remainder k - bf16(k) of the persistent keys, or null
     bf16_t *VT;          // [B*H][64][vt_stride] transposed copy of the persistent values (bf16 MFMA path)
     int vt_stride;
     float *pm, *pl, *po;

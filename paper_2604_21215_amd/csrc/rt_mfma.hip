@@ -21,7 +21,8 @@ __global__ __launch_bounds__(256) void prepass_mfma_kernel(const bf16_t *__restr
                                                            const bf16_t *__restrict__ Wv, const bf16_t *__restrict__ g_attn,
                                                            const bf16_t *__restrict__ g_q, const bf16_t *__restrict__ g_k,
                                                            bf16_t *__restrict__ Q, bf16_t *__restrict__ Kt,
-                                                           bf16_t *__restrict__ Vt, int Bc, int Nc, int d, int H, float eps,
+                                                           bf16_t *__restrict__ Vt, float *__restrict__ Qf,
+                                                           float *__restrict__ Ktf, int Bc, int Nc, int d, int H, float eps,
                                                            int norm_free)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -80,6 +81,7 @@ __global__ __launch_bounds__(256) void prepass_mfma_kernel(const bf16_t *__restr
 
     const bf16_t *gn = which == 0 ? g_q : g_k;
     bf16_t *dst = which == 0 ? Q : (which == 1 ? Kt : Vt);
+    float *dstf = which == 0 ? Qf : (which == 1 ? Ktf : nullptr);   // optional unrounded copies of q and k_tmp
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
 #pragma unroll
@@ -98,12 +100,13 @@ __global__ __launch_bounds__(256) void prepass_mfma_kernel(const bf16_t *__restr
             }
             if (m < M) {
                 const int b = m / Nc, n = m % Nc;
-                bf16_t *o = dst + ((size_t)n * Bc + b) * d + h * kHeadDim + l16;
+                const size_t oo = ((size_t)n * Bc + b) * d + h * kHeadDim + l16;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     float val = v[j] * sc;
                     if (which < 2 && !norm_free && gn) val *= bf16_to_f32(gn[h * kHeadDim + j * 16 + l16]);
-                    o[j * 16] = f32_to_bf16(val);
+                    dst[oo + j * 16] = f32_to_bf16(val);
+                    if (dstf) dstf[oo + j * 16] = val;
                 }
             }
         }
@@ -116,8 +119,8 @@ hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scrat
     const int M = Bc * Nc;
     hipLaunchKernelGGL(prepass_mfma_kernel, dim3((M + 127) / 128, (3 * D.H + 1) / 2), dim3(256), 0, st, (const bf16_t *)x,
                        S.rinv, (const bf16_t *)W.Wq, (const bf16_t *)W.Wk, (const bf16_t *)W.Wv, (const bf16_t *)W.g_attn,
-                       (const bf16_t *)W.g_q, (const bf16_t *)W.g_k, (bf16_t *)S.Q, (bf16_t *)S.Kt, (bf16_t *)S.Vt, Bc, Nc,
-                       D.d, D.H, D.eps, D.norm_free);
+                       (const bf16_t *)W.g_q, (const bf16_t *)W.g_k, (bf16_t *)S.Q, (bf16_t *)S.Kt, (bf16_t *)S.Vt, S.Qf, S.Ktf,
+                       Bc, Nc, D.d, D.H, D.eps, D.norm_free);
     return hipGetLastError();
 }
 
@@ -135,8 +138,8 @@ __global__ __launch_bounds__(256) void cross_mfma_kernel(const bf16_t *__restric
     const int wave = threadIdx.x >> 6;
     const int q0 = blockIdx.x * 128 + wave * 32;  // first query of this wavefront, relative to t1
     if (q0 >= nq) return;                         // no barriers in this kernel
-    cross_mfma_wave(Q, K, VT, vt_stride, pm, pl, po, BH, blockIdx.y, t1, 0, t1 - P, P, q0, nq, level, level_rel, slots,
-                    scale);
+    cross_mfma_wave<false>(Q, nullptr, K, nullptr, VT, vt_stride, pm, pl, po, BH, blockIdx.y, t1, 0, t1 - P, P, q0, nq, level,
+                           level_rel, slots, scale);
 }
 
 hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, hipStream_t st)

@@ -39,22 +39,39 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 // P^T comes out of the first product already in the B-operand layout once the 32 keys of a chunk
 // are assigned to contraction slots as  slot 8g+e  <->  key 4g+e (e < 4), 16+4g+(e-4) (e >= 4);
 // the V^T fragment is gathered with the same assignment (two 8-byte loads).
-__device__ __forceinline__ void cross_mfma_wave(const bf16_t *Q, const bf16_t *K, const bf16_t *VT, int vt_stride,
-                                                float *pm, float *pl, float *po, int BH, int bh, int c_first,
-                                                int q_shift, int k_first, int P, int q0, int nq, int level,
-                                                int level_rel, int slots, float scale)
+// With HP (high-precision logits) the queries come as fp32 rows Qf and are split into a bf16 head and a
+// bf16 remainder, the keys come as head K plus remainder Klo, and S^T = Khi Qhi + Khi Qlo + Klo Qhi:
+// the logits then carry no bf16 rounding of q or k (they are sharp here: |q| = |k| = 8, and every
+// rounding of a logit input shows up as a few per cent on individual softmax weights).
+template <bool HP>
+__device__ __forceinline__ void cross_mfma_wave(const bf16_t *Q, const float *Qf, const bf16_t *K, const bf16_t *Klo,
+                                                const bf16_t *VT, int vt_stride, float *pm, float *pl, float *po, int BH,
+                                                int bh, int c_first, int q_shift, int k_first, int P, int q0, int nq,
+                                                int level, int level_rel, int slots, float scale)
 {
     const int lane = threadIdx.x & 63;
     const int l16 = lane & 15, g = lane >> 4;
     const size_t rs = (size_t)BH * kHeadDim;
 
-    Frag bq[2][2];
+    Frag bq[2][2], bql[2][2];
 #pragma unroll
     for (int qt = 0; qt < 2; ++qt) {
         const int qi = min(q0 + qt * 16 + l16, nq - 1);
-        const bf16_t *qrow = Q + (size_t)(c_first + q_shift + qi) * rs + (size_t)bh * kHeadDim + 8 * g;
-        bq[qt][0].u = *reinterpret_cast<const uint4 *>(qrow);
-        bq[qt][1].u = *reinterpret_cast<const uint4 *>(qrow + 32);
+        const size_t qo = (size_t)(c_first + q_shift + qi) * rs + (size_t)bh * kHeadDim + 8 * g;
+        if (HP) {
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) {
+                float f[8], r[8];
+                load8(Qf + qo + ks * 32, f);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) r[e] = f[e] - bf16_to_f32(f32_to_bf16(f[e]));
+                bq[qt][ks].u = make_uint4(pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3]), pack_bf16(f[4], f[5]), pack_bf16(f[6], f[7]));
+                bql[qt][ks].u = make_uint4(pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3]), pack_bf16(r[4], r[5]), pack_bf16(r[6], r[7]));
+            }
+        } else {
+            bq[qt][0].u = *reinterpret_cast<const uint4 *>(Q + qo);
+            bq[qt][1].u = *reinterpret_cast<const uint4 *>(Q + qo + 32);
+        }
     }
     float m[2] = {-INFINITY, -INFINITY}, lsum[2] = {0.f, 0.f};
     f32x4_t O[2][4];
@@ -64,18 +81,30 @@ __device__ __forceinline__ void cross_mfma_wave(const bf16_t *Q, const bf16_t *K
         for (int blk = 0; blk < 4; ++blk) O[qt][blk] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
     const bf16_t *kbase = K + (size_t)k_first * rs + (size_t)bh * kHeadDim + 8 * g;
+    const bf16_t *klbase = HP ? Klo + (size_t)k_first * rs + (size_t)bh * kHeadDim + 8 * g : nullptr;
     const bf16_t *vbase = VT + ((size_t)bh * kHeadDim + l16) * vt_stride + k_first + 4 * g;
     for (int kc = 0; kc < P; kc += 32) {
         f32x4_t S[2][2];
 #pragma unroll
         for (int kt = 0; kt < 2; ++kt) {
             const bf16_t *krow = kbase + (size_t)(kc + kt * 16 + l16) * rs;
-            Frag a0, a1;
+            Frag a0, a1, l0, l1;
             a0.u = *reinterpret_cast<const uint4 *>(krow);
             a1.u = *reinterpret_cast<const uint4 *>(krow + 32);
+            if (HP) {
+                const bf16_t *klrow = klbase + (size_t)(kc + kt * 16 + l16) * rs;
+                l0.u = *reinterpret_cast<const uint4 *>(klrow);
+                l1.u = *reinterpret_cast<const uint4 *>(klrow + 32);
+            }
 #pragma unroll
             for (int qt = 0; qt < 2; ++qt) {
                 f32x4_t s = f32x4_t{0.f, 0.f, 0.f, 0.f};
+                if (HP) {   // small terms first
+                    s = mfma16(l0, bq[qt][0], s);
+                    s = mfma16(l1, bq[qt][1], s);
+                    s = mfma16(a0, bql[qt][0], s);
+                    s = mfma16(a1, bql[qt][1], s);
+                }
                 s = mfma16(a0, bq[qt][0], s);
                 s = mfma16(a1, bq[qt][1], s);
                 S[qt][kt] = s;

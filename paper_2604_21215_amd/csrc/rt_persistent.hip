@@ -106,6 +106,8 @@ struct PersistArgs {
     const bf16_t *x;
     bf16_t *y, *K, *V;
     const bf16_t *Q, *Kt, *Vt;
+    const float *Qf, *Ktf;      // unrounded q, k_tmp
+    bf16_t *Klo;                // remainder k - bf16(k) of the persistent keys
     bf16_t *VT;
     int vt_stride;
     float *pm, *pl, *po;
@@ -326,12 +328,12 @@ __device__ __forceinline__ void gate_wait(const ll_t *words, int count, unsigned
 }
 
 // Direct window out of LDS: query (lane c holds q[c]) against nkeys <= 64 rows kept by this wavefront.
-__device__ __forceinline__ void attend_lds(float q, const bf16_t *ks, const bf16_t *vs, int nkeys, float scale, float &m,
+__device__ __forceinline__ void attend_lds(float q, const float *ks, const bf16_t *vs, int nkeys, float scale, float &m,
                                            float &l, float &o)
 {
     const int lane = threadIdx.x & 63;
     const bool valid = lane < nkeys;
-    const bf16_t *krow = ks + (size_t)(valid ? lane : 0) * kHeadDim;
+    const float *krow = ks + (size_t)(valid ? lane : 0) * (kHeadDim + 4);   // rows padded against bank conflicts
     float acc = 0.f;
 #pragma unroll
     for (int c8 = 0; c8 < 8; ++c8) {
@@ -404,8 +406,8 @@ __device__ __forceinline__ void pre_issue(const PersistArgs &A, int t, int u, Pr
     const int lane = threadIdx.x & 63;
     const size_t rs = (size_t)A.BH * kHeadDim;
     const size_t qoff = (size_t)t * rs + (size_t)u * kHeadDim + lane;
-    L.q = bf16_to_f32(A.Q[qoff]);
-    L.kt = bf16_to_f32(A.Kt[qoff]);
+    L.q = A.Qf[qoff];
+    L.kt = A.Ktf[qoff];
     L.vt = bf16_to_f32(A.Vt[qoff]);
     const int c = t - 1;
 #pragma unroll
@@ -443,7 +445,7 @@ __device__ __forceinline__ void pre_from_lds(const float *s, PreLoad &L)
     }
 }
 
-__device__ __forceinline__ void pre_finish(const PersistArgs &A, int t, int u, const PreLoad &L, const bf16_t *wk,
+__device__ __forceinline__ void pre_finish(const PersistArgs &A, int t, int u, const PreLoad &L, const float *wk,
                                            const bf16_t *wv, float &q, float &m, float &l, float &o)
 {
     q = L.q;
@@ -497,8 +499,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     float *sq = h_loc + kRMax * kBMax;                                         // [32][kBMax]
     float *rinv_s = sq + 32 * kBMax;                                           // [kBMax]
     int *flag_s = reinterpret_cast<int *>(rinv_s + kBMax);
-    bf16_t *win_k = reinterpret_cast<bf16_t *>(flag_s + 4);                    // [upw][win_rows][64]
-    bf16_t *win_v = win_k + (size_t)A.upw * A.win_rows * kHeadDim;
+    float *win_k = reinterpret_cast<float *>(flag_s + 4);                      // [upw][win_rows][64 + 4] unrounded keys
+    bf16_t *win_v = reinterpret_cast<bf16_t *>(win_k + (size_t)A.upw * A.win_rows * (kHeadDim + 4));   // [upw][win_rows][64]
     bf16_t *act_s = win_v + (size_t)A.upw * A.win_rows * kHeadDim;             // [max_batch][ldw_d] staged activations
     float *pre_s = reinterpret_cast<float *>(act_s + (size_t)A.max_batch * A.ldw_d);   // [upw][kPreFloats] pre-fetched merge inputs
 
@@ -531,7 +533,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     // this wavefront's merge unit (at most one: B*H <= G*kPW), and its pre-merged state for the next position
     const int my_u = wg + G * wave;
     const bool has_u = my_u < BH;
-    const bf16_t *my_wk = win_k + (size_t)wave * A.win_rows * kHeadDim, *my_wv = win_v + (size_t)wave * A.win_rows * kHeadDim;
+    const float *my_wk = win_k + (size_t)wave * A.win_rows * (kHeadDim + 4);
+    const bf16_t *my_wv = win_v + (size_t)wave * A.win_rows * kHeadDim;
     float cq = 0.f, cm = 0.f, cl = 1.f, co = 0.f;
     // The loads of a pre-merge are made by an otherwise idle helper wavefront (wave 4 + slot, during
     // phase 2b) and handed over through LDS, so that no wavefront carries them in registers across a phase.
@@ -593,13 +596,14 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 A.K[off] = kb;
                 A.V[off] = vb;
                 A.VT[((size_t)u * kHeadDim + lane) * A.vt_stride + (t - 1)] = vb;
+                A.Klo[off] = f32_to_bf16(kr - bf16_to_f32(kb));   // what the stored bf16 key lost; the cross-block kernel adds it back
                 if (A.win_rows) {   // ring slot of key t-1; only this wavefront reads it back
-                    const size_t wo = ((size_t)(u / G) * A.win_rows + ((t - 1) & (A.win_rows - 1))) * kHeadDim + lane;
-                    win_k[wo] = kb;
-                    win_v[wo] = vb;
+                    const size_t slot = (size_t)(u / G) * A.win_rows + ((t - 1) & (A.win_rows - 1));
+                    win_k[slot * (kHeadDim + 4) + lane] = kr;
+                    win_v[slot * kHeadDim + lane] = vb;
                 }
                 if (t < A.N) {
-                    const float sn = A.scale * fast_sum(q * bf16_to_f32(kb));
+                    const float sn = A.scale * fast_sum(q * kr);
                     const float m_new = fmaxf(m, sn);
                     const float e1 = __expf(m - m_new), e2 = __expf(sn - m_new);
                     l = l * e1 + e2;
@@ -632,8 +636,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             while ((1 << level) < P) ++level;
             for (int it = wave * G + wg; it < items; it += G * kPW) {
                 const int bh = it % BH, qb = it / BH;
-                cross_mfma_wave(A.Q, A.K, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1, t - P, P, qb * 32, nq, level,
-                                level - A.log2_pmin, A.slots, A.scale);
+                cross_mfma_wave<true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1, t - P, P, qb * 32,
+                                      nq, level, level - A.log2_pmin, A.slots, A.scale);
             }
             if (grid_barrier(A, (++nbar) * (unsigned long long)G, flag_s)) { fail = 1; }
             RT_ABORT_IF(fail);
@@ -796,7 +800,7 @@ static size_t lds_bytes_for(int d, int F, int G, int win_rows, int upw, int max_
     size_t b = ((size_t)*R_o * ldw_d + (size_t)*R_1 * ldw_d + (size_t)(d / 64) * ldw_d + (size_t)*R_kv * ldw_d) * 2;
     b = align_up(b, 16);
     b += (size_t)(kPW * kRMax * kBMax + kRMax * kBMax + 32 * kBMax + kBMax) * 4 + 16;
-    b += (size_t)2 * upw * win_rows * kHeadDim * 2;   // direct-window rows of this workgroup's merge units
+    b += (size_t)upw * win_rows * ((kHeadDim + 4) * 4 + kHeadDim * 2);   // direct-window rows (fp32 keys, bf16 values)
     b += (size_t)max_batch * ldw_d * 2;                // staged activation rows of the phase in flight
     b += (size_t)upw * kPreFloats * 4;                 // pre-fetched merge inputs
     return b;
@@ -906,6 +910,7 @@ rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weigh
     A.g_mlp = (const bf16_t *)W.g_mlp; A.g_kv = (const bf16_t *)W.g_kv; A.g_k = (const bf16_t *)W.g_k;
     A.x = (const bf16_t *)x; A.y = (bf16_t *)y; A.K = (bf16_t *)K; A.V = (bf16_t *)V;
     A.Q = (const bf16_t *)S.Q; A.Kt = (const bf16_t *)S.Kt; A.Vt = (const bf16_t *)S.Vt;
+    A.Qf = S.Qf; A.Ktf = S.Ktf; A.Klo = S.Klo;
     A.VT = S.VT; A.vt_stride = S.vt_stride;
     A.pm = S.pm; A.pl = S.pl; A.po = S.po; A.levels = S.levels; A.slots = S.slots;
     A.a_ll = (ll_t *)P.a_ll; A.h_ll = (ll_t *)P.h_ll; A.u_ll = (ll_t *)P.u_ll; A.z_ll = (ll_t *)P.z_ll;
