@@ -20,8 +20,14 @@
 //   2b   z = h + alpha (sum of partials), same rows as O                      -> y, bf16(z), partial sums of z^2
 //   KV   [Wk'; Wv'] z  (scale 1/rms(z) applied in M)                                         -> raw k, v
 //        and, on the wavefronts that own a (b, h): the pre-merge of position t+1 (temporary pair,
-//        stored partial states of the bits of c = t at or above p_min, direct window out of LDS),
-//        issued before and finished after this phase's own work, in the shadow of the k, v hop.
+//        stored partial states of the bits of c = t at or above p_min, direct window out of LDS).
+//        Its global loads are issued during phase 2b by a wavefront that has nothing else to do there
+//        and parked in LDS; the owner finishes the merge after this phase's own product, in the shadow
+//        of the k, v hop.
+//
+// Logits are formed from unrounded operands: fp32 q and temporary k from the pre-pass, fp32 keys in the
+// LDS window, and for the cross-block tiles the persistent key as bf16 head + bf16 remainder (three MFMA
+// terms).  The K the caller receives is the bf16 head.
 //
 // Exchange format: every value crosses the chip inside a self-validating 64-bit word
 // [tag:32 | payload:32] (payload = two bf16 or one fp32), written with one 8-byte agent-scope atomic
