@@ -143,6 +143,37 @@ def main():
         "roofline": roofline,
     }
 
+    # The cross-block UpdateTile kernel by itself (the path's one dense contraction): the top three levels carry
+    # 87.5 % of the attention FLOPs of a call; each event is re-run alone on the state the last call left.
+    if wl.dtype == "bf16" and wl.N >= 256:
+        levels = []
+        for lv in range(3):
+            P = wl.N >> (lv + 1)
+            evs = [(t1, min(P, wl.N - t1)) for t1 in range(P, wl.N, 2 * P)]
+            if P < 64 or not evs:
+                continue
+            reps = 10
+            for t1, nq in evs:
+                ctx.rt_cross_block_event(K, V, t1, P, nq)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(reps):
+                for t1, nq in evs:
+                    ctx.rt_cross_block_event(K, V, t1, P, nq)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            us = e0.elapsed_time(e1) * 1e3 / (reps * len(evs))
+            fl = float(np.mean([4.0 * P * nq * wl.head_dim * wl.B * wl.H for _, nq in evs]))
+            levels.append({"P": P, "events_per_call": len(evs), "us_per_event": us, "tflops": fl / us / 1e6})
+        if levels:
+            tot_fl = sum(l["tflops"] * l["us_per_event"] * l["events_per_call"] for l in levels)
+            tot_us = sum(l["us_per_event"] * l["events_per_call"] for l in levels)
+            out["cross_block_kernel"] = {
+                "bound": "mfma", "unit": "TFLOP/s", "peak": MFMA_BF16_PEAK_TFLOPS * 1e0,
+                "achieved": tot_fl / tot_us, "frac": tot_fl / tot_us / MFMA_BF16_PEAK_TFLOPS,
+                "note": "stand-alone launches of the top three levels (87.5 % of the attention FLOPs), FLOP-weighted; "
+                        "back-to-back launches, launch overhead included", "levels": levels}
+
     if not args.no_cpu_baseline:
         from oracle import rt_oracle
         n_s = min(args.cpu_sample_positions, wl.N)

@@ -100,6 +100,22 @@ rt_status rt_layer_prefill(rt_ctx *ctx, const rt_layer_weights *w, const void *x
 rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t, void *y_t,
                          void *K, void *V, int32_t kv_cap);
 
+/* Input of the first layer of a stack (Sec. 2: a sequence of token embeddings enters the first layer):
+ *   x[b, n, :] = table[ids[b * ids_stride + first + n], :]   for 0 <= b < B, 0 <= n < N.
+ *   table [vocab, d] device, storage dtype; ids device int32; x [B, N, d] device, written.
+ * An id outside [0, vocab) is clamped into the table.  B, N >= 1 (not limited by max_batch / max_seq:
+ * no scratch is used). */
+rt_status rt_embed_rows(rt_ctx *ctx, const void *table, int32_t vocab, const int32_t *ids, int64_t ids_stride, int32_t first,
+                        int32_t B, int32_t N, void *x);
+
+/* Read-out of a stack: logits[b, v] = < W_lm[v, :], RMS(z_b; g_final) >, the final normalisation being
+ * the same RMS as inside the layers (Sec. 2, Notation) and W_lm an untied [vocab, d] matrix.
+ *   z: B rows of d elements, row b at z + b * z_stride elements (so the last position of a [B, N, d]
+ *   tensor can be passed without a copy); g_final [d] or NULL = ones; logits [B, vocab] fp32 device, written.
+ *   1 <= B <= max_batch. */
+rt_status rt_lm_head(rt_ctx *ctx, const void *W_lm, const void *g_final, int32_t vocab, const void *z, int64_t z_stride,
+                     int32_t B, float *logits);
+
 /* Waits for nothing: the caller synchronises the stream first.  Frees scratch.  NULL is allowed. */
 rt_status rt_destroy(rt_ctx *ctx);
 
@@ -124,6 +140,14 @@ const char *rt_engine_name(const rt_ctx *ctx);
  * 100 MHz clock stamps of workgroup 0 (slot 0 start, 1..6 end of phases M, cross-block items, O, 1, 2, KV,
  * 7..12 points inside the phases) into out[rows][16] (host memory).  Returns the number of rows written, 0 if tracing is off. */
 int32_t rt_phase_trace(rt_ctx *ctx, uint64_t *out, int32_t rows);
+
+/* Diagnostics / measurement: run one cross-block UpdateTile (Appendix C, Algorithm 2) again, by itself, on the
+ * state the last rt_layer_prefill of this context left behind (its queries and transposed values in scratch, the
+ * caller's K, V): queries t1+1 .. t1+nq (1-based) against the keys t1-P+1 .. t1.  Rewrites those queries' partial
+ * states of level log2(P) with the values the stand-alone kernel computes; outputs of the prefill are not touched.
+ *   B = batch of that prefill; P a power of two >= p_min; t1 a positive multiple of P; 1 <= nq <= P; t1 + nq <= N.
+ * Used by the benchmark to time the cross-block kernel alone. */
+rt_status rt_cross_block_event(rt_ctx *ctx, const void *K, const void *V, int32_t B, int32_t t1, int32_t P, int32_t nq);
 
 /* Host-only: the cross-block events the driver issues for a sequence of length N with threshold
  * p_min (Appendix C, Algorithm 1, lines "P <- 2^nu2(t)" to the second UpdateTile call, restricted to

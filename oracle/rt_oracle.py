@@ -200,3 +200,52 @@ def stack_prefill(layers, x0):
         out.append((y, K, V))
         x = y
     return out
+
+
+# ------------------------------------------------------------------ a stack of layers with embedding and read-out
+def embed(table, ids):
+    """First-layer input: row ids[b, n] of the embedding table (Sec. 2: token embeddings enter layer 1)."""
+    return _f64(np.asarray(table)[np.asarray(ids)])
+
+
+def lm_head(W_lm, z, g_final=None, eps=1e-6, norm_free=False):
+    """logits = W_lm RMS(z; g_final) for rows z [B, d] (RMS as in Sec. 2, Notation; untied projection)."""
+    z = _f64(z)
+    if not norm_free:
+        z = z / np.sqrt(np.mean(z * z, axis=-1, keepdims=True) + eps)
+        if g_final is not None:
+            z = z * _f64(g_final)
+    return z @ _f64(W_lm).T
+
+
+class Stack:
+    """L RT layers (each its own parameters and key-value memory), embedding in front, read-out behind."""
+
+    def __init__(self, layers, embedding, W_lm, g_final=None, eps=1e-6, norm_free=False):
+        self.layers, self.embedding, self.W_lm, self.g_final = layers, embedding, W_lm, g_final
+        self.eps, self.norm_free = eps, norm_free
+        self.K, self.V = [], []
+
+    def prefill(self, ids, N, kv_cap, progress=None):
+        """Positions 0..N-1 of ids [B, >= N].  Returns (per-layer list of (y, K, V), logits of position N-1).
+        progress: optional callable(layer index), called after each layer (long runs report through it)."""
+        x = embed(self.embedding, np.asarray(ids)[:, :N])
+        out = []
+        self.K, self.V = [], []
+        for l, lay in enumerate(self.layers):
+            y, K, V = lay.prefill(x, kv_cap=kv_cap)
+            if progress is not None:
+                progress(l)
+            out.append((y, K, V))
+            self.K.append(K); self.V.append(V)
+            x = y
+        return out, lm_head(self.W_lm, x[:, N - 1], self.g_final, self.eps, self.norm_free)
+
+    def decode_step(self, ids, t):
+        """Position t over the caches held from prefill / earlier steps.  Returns (per-layer outputs [L, B, d], logits)."""
+        x = embed(self.embedding, np.asarray(ids)[:, t])
+        ys = []
+        for l, lay in enumerate(self.layers):
+            x = lay.decode_step(x, t, self.K[l], self.V[l])
+            ys.append(x)
+        return np.stack(ys), lm_head(self.W_lm, x, self.g_final, self.eps, self.norm_free)

@@ -22,7 +22,7 @@ RT_FLAG_HIP_GRAPH = 0x10
 
 EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_last_error", "rt_status_string",
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
-           "rt_version", "rt_phase_trace", "rt_schedule_events_shifted")
+           "rt_version", "rt_phase_trace", "rt_schedule_events_shifted", "rt_embed_rows", "rt_lm_head", "rt_cross_block_event")
 
 
 class rt_config(C.Structure):
@@ -85,6 +85,13 @@ def load():
     L.rt_version.restype = C.c_int32
     L.rt_phase_trace.argtypes = [ctxp, C.POINTER(C.c_uint64), C.c_int32]
     L.rt_phase_trace.restype = C.c_int32
+    L.rt_embed_rows.argtypes = [ctxp, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
+                                C.c_void_p]
+    L.rt_embed_rows.restype = C.c_int
+    L.rt_lm_head.argtypes = [ctxp, C.c_void_p, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_int32, C.c_void_p]
+    L.rt_lm_head.restype = C.c_int
+    L.rt_cross_block_event.argtypes = [ctxp, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    L.rt_cross_block_event.restype = C.c_int
     _lib = L
     return L
 
@@ -156,6 +163,32 @@ class RTContext:
         rc = self._L.rt_decode_step(self._ctx, C.byref(weights), _ptr(x_t), x_t.shape[0], int(t), _ptr(y_t), _ptr(K),
                                     _ptr(V), K.shape[0])
         _check(self._L, self._ctx, rc)
+
+    # -- rt_embed_rows(ctx, table[vocab,d], vocab, ids[B,ids_stride] int32, ids_stride, first, B, N, x[B,N,d])
+    def rt_embed_rows(self, table, ids, first, x):
+        B, N, _ = x.shape
+        rc = self._L.rt_embed_rows(self._ctx, _ptr(table), table.shape[0], _ptr(ids), ids.stride(0), int(first), B, N,
+                                   _ptr(x))
+        _check(self._L, self._ctx, rc)
+
+    # -- rt_lm_head(ctx, W_lm[vocab,d], g_final[d] | None, vocab, z rows (stride z_stride elements), z_stride, B, logits[B,vocab] f32)
+    def rt_lm_head(self, W_lm, g_final, z, z_stride, B, logits):
+        rc = self._L.rt_lm_head(self._ctx, _ptr(W_lm), _ptr(g_final), W_lm.shape[0], _ptr(z), int(z_stride), int(B),
+                                _ptr(logits))
+        _check(self._L, self._ctx, rc)
+
+    # -- rt_cross_block_event(ctx, K, V, B, t1, P, nq)
+    def rt_cross_block_event(self, K, V, t1, P, nq):
+        rc = self._L.rt_cross_block_event(self._ctx, _ptr(K), _ptr(V), K.shape[1], int(t1), int(P), int(nq))
+        _check(self._L, self._ctx, rc)
+
+    def raw_embed(self, table_ptr, vocab, ids_ptr, ids_stride, first, B, N, x_ptr) -> int:
+        return self._L.rt_embed_rows(self._ctx, C.c_void_p(table_ptr), vocab, C.c_void_p(ids_ptr), ids_stride, first, B, N,
+                                     C.c_void_p(x_ptr))
+
+    def raw_lm_head(self, W_ptr, g_ptr, vocab, z_ptr, z_stride, B, logits_ptr) -> int:
+        return self._L.rt_lm_head(self._ctx, C.c_void_p(W_ptr), C.c_void_p(g_ptr), vocab, C.c_void_p(z_ptr), z_stride, B,
+                                  C.c_void_p(logits_ptr))
 
     def raw_prefill(self, weights, x_ptr, B, N, y_ptr, K_ptr, V_ptr, kv_cap) -> int:
         """Status code of rt_layer_prefill on raw addresses (error-path tests)."""

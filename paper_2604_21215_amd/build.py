@@ -14,6 +14,8 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
     # keep the compiler from forming packed-fp32 instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results go to ordinary VGPRs: the softmax arithmetic reads them directly (no v_accvgpr copies)
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
 ]
 
 

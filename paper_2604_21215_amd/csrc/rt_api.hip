@@ -20,6 +20,7 @@ struct rt_ctx {
     hipStream_t stream = nullptr;
     bool use_mfma = false;
     bool broken = false;
+    int last_B = 0, last_N = 0;   // shape of the last prefill (what the scratch holds)
     std::string err;
     std::string engine;
     PersistentState persist;
@@ -362,6 +363,7 @@ extern "C" rt_status rt_layer_prefill(rt_ctx *c, const rt_layer_weights *w, cons
 
     LayerDims D = c->base;
     D.B = B; D.N = N; D.kv_cap = kv_cap;
+    c->last_B = B; c->last_N = N;
     const bool want_stepwise = (c->cfg.flags & RT_FLAG_ENGINE_STEPWISE) != 0;
     if (!want_stepwise && persistent_supported(c->persist, D)) {
         c->engine = "persistent";
@@ -414,4 +416,61 @@ extern "C" rt_status rt_decode_step(rt_ctx *c, const rt_layer_weights *w, const 
     c->engine = "stepwise";
     if (c->cfg.dtype == RT_BF16) return decode_impl<bf16_t>(c, D, w, x_t, t, y_t, K, V);
     return decode_impl<float>(c, D, w, x_t, t, y_t, K, V);
+}
+
+extern "C" rt_status rt_embed_rows(rt_ctx *c, const void *table, int32_t vocab, const int32_t *ids, int64_t ids_stride,
+                                   int32_t first, int32_t B, int32_t N, void *x)
+{
+    if (!c) return RT_ERR_INVALID_ARG;
+    if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
+    if (!table || !ids || !x) return fail(c, RT_ERR_INVALID_ARG, "null pointer%s");
+    if (vocab < 1 || B < 1 || N < 1 || first < 0 || ids_stride < (int64_t)first + N)
+        return fail(c, RT_ERR_INVALID_ARG, "vocab, B, N >= 1 and first + N <= ids_stride are required%s");
+    if ((int64_t)B * N > (int64_t)1 << 31) return fail(c, RT_ERR_INVALID_ARG, "B * N too large%s");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+    hipError_t e;
+    if (c->cfg.dtype == RT_BF16)
+        e = embed_rows_launch<bf16_t>(table, ids, x, B, N, c->cfg.d_model, vocab, ids_stride, first, c->stream);
+    else
+        e = embed_rows_launch<float>(table, ids, x, B, N, c->cfg.d_model, vocab, ids_stride, first, c->stream);
+    if (e != hipSuccess) return fail_hip(c, e, "embed_rows");
+    return RT_OK;
+}
+
+extern "C" rt_status rt_lm_head(rt_ctx *c, const void *W_lm, const void *g_final, int32_t vocab, const void *z,
+                                int64_t z_stride, int32_t B, float *logits)
+{
+    if (!c) return RT_ERR_INVALID_ARG;
+    if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
+    if (!W_lm || !z || !logits) return fail(c, RT_ERR_INVALID_ARG, "null pointer%s");
+    if (vocab < 1 || B < 1 || B > c->cfg.max_batch || z_stride < c->cfg.d_model)
+        return fail(c, RT_ERR_INVALID_ARG, "vocab >= 1, 1 <= B <= max_batch and z_stride >= d_model are required%s");
+    if (c->cfg.d_model > 12288) return fail(c, RT_ERR_UNSUPPORTED, "rt_lm_head covers d_model <= 12288%s");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+    const int nf = (c->cfg.flags & RT_FLAG_NORM_FREE) ? 1 : 0;
+    hipError_t e;
+    if (c->cfg.dtype == RT_BF16)
+        e = lm_head_launch<bf16_t>(W_lm, g_final, z, z_stride, logits, B, c->cfg.d_model, vocab, c->cfg.rms_eps, nf, c->stream);
+    else
+        e = lm_head_launch<float>(W_lm, g_final, z, z_stride, logits, B, c->cfg.d_model, vocab, c->cfg.rms_eps, nf, c->stream);
+    if (e != hipSuccess) return fail_hip(c, e, "lm_head");
+    return RT_OK;
+}
+
+extern "C" rt_status rt_cross_block_event(rt_ctx *c, const void *K, const void *V, int32_t B, int32_t t1, int32_t P, int32_t nq)
+{
+    if (!c) return RT_ERR_INVALID_ARG;
+    if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
+    if (!K || !V) return fail(c, RT_ERR_INVALID_ARG, "null tensor pointer%s");
+    if (c->last_N == 0 || B != c->last_B) return fail(c, RT_ERR_STATE, "no prefill of this batch size has run on this context%s");
+    if (!is_pow2(P) || P < c->cfg.p_min || t1 < P || t1 % P != 0 || nq < 1 || nq > P || (int64_t)t1 + nq > c->last_N)
+        return fail(c, RT_ERR_INVALID_ARG, "need P a power of two >= p_min, t1 a positive multiple of P, 1 <= nq <= P, t1 + nq <= N%s");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+    LayerDims D = c->base;
+    D.B = B; D.N = c->last_N; D.kv_cap = c->last_N;
+    hipError_t e;
+    if (c->cfg.dtype == RT_BF16) e = Launch<bf16_t>::cross(D, c->S, K, V, t1, P, nq, c->use_mfma, c->stream);
+    else e = Launch<float>::cross(D, c->S, K, V, t1, P, nq, false, c->stream);
+    if (e != hipSuccess) return fail_hip(c, e, "cross");
+    return RT_OK;
 }

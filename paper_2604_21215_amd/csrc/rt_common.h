@@ -161,4 +161,12 @@ template <typename T> struct Launch {
                                    int nsplit, hipStream_t st);
 };
 
+// embedding lookup and final-norm + output projection of a layer stack (rt_stack.hip)
+template <typename T>
+hipError_t embed_rows_launch(const void *table, const int32_t *ids, void *x, int B, int N, int d, int vocab,
+                             long long ids_stride, int first, hipStream_t st);
+template <typename T>
+hipError_t lm_head_launch(const void *W, const void *g, const void *z, long long z_stride, float *logits, int B, int d,
+                          int vocab, float eps, int norm_free, hipStream_t st);
+
 }  // namespace rt

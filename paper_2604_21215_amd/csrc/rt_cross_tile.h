@@ -1,0 +1,251 @@
+// Cross-block UpdateTile (Appendix C, Algorithm 2) with the key and value tiles staged in LDS and shared by
+// all wavefronts of a workgroup: NW wavefronts x 32 queries of one (b, h) against the P keys of the block.
+//
+// Per chunk of 64 keys the workgroup copies K[64][64] (and, for high-precision logits, the remainder
+// tile) and V^T[64][64] into LDS once (next chunk prefetched into registers while the current one is
+// being used); each wavefront then forms, with v_mfma_f32_32x32x16_bf16 (measured on MI355X: 2.1 PFLOP/s
+// against 1.2-1.3 PFLOP/s for the 16x16x32 form),
+//     S^T[key][query] = K Q^T          (A = K rows out of LDS, B = this wavefront's Q rows, registers)
+//     O^T[dh][query] += V^T P^T        (A = V^T rows out of LDS, B = P^T straight from the S^T registers)
+// Operand layout of v_mfma_f32_32x32x16_bf16 (A 32x16, B 16x32, hi = lane/32):
+//   A: lane holds A[row = lane%32][k = 8hi .. 8hi+7],  B: lane holds B[k = 8hi .. 8hi+7][col = lane%32],
+//   D: register i of a lane holds D[row = 8(i/4) + 4hi + i%4][col = lane%32], i = 0..15.
+// Eight consecutive D registers 8s .. 8s+7 of a lane are therefore the keys 16s + 4hi + (0..3) and
+// 16s + 8 + 4hi + (0..3) of one query: packed to bf16 they are the B fragment of contraction step s when
+// the V^T fragment is gathered with the same key <-> slot assignment (two 8-byte reads).
+// The softmax keeps one reference value per query (not necessarily the running maximum): it is moved up,
+// and the accumulators rescaled, only when a logit exceeds it by more than kSlack (powers of two), which
+// after the first chunk is rare.  Any reference gives the same (m, l, o) triple up to rounding (Algorithm 2
+// tracks the maximum for stability only); p <= 2^kSlack keeps everything far from overflow.  The row sums
+// l are accumulated with plain additions of the unrounded weights.  Measured on MI355X: the exponential
+// and the bf16 dot-product instructions do not run beside the matrix pipeline, multiply-add, max3, add and
+// the bf16 pair conversion do; the core clock is about 1.7 GHz while this kernel runs.
+#pragma once
+#include "rt_mfma_device.h"
+
+namespace rt {
+
+constexpr int kKC = 64;            // keys per chunk
+constexpr int kTileLd = 72;        // LDS row stride of the key tiles in bf16 elements (64 + 8: 16-byte reads of 16 rows hit distinct banks)
+constexpr int kVLd = 68;           // row stride of the V^T tile (8-byte reads of 32 rows hit distinct banks)
+constexpr float kSlack = 16.f;     // how far (log2 units) a logit may exceed the reference before it is moved
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+
+template <bool HP> constexpr int cross_tile_lds_bytes() { return (HP ? 3 : 2) * kKC * kTileLd * 2; }   // one buffer (V^T tile padded to the key tiles' size)
+
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi)
+{   // hardware round-to-nearest-even pair conversion
+    f32x2_t v = {lo, hi};
+    bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    return *reinterpret_cast<uint32_t *>(&b);
+}
+
+typedef float f32x16_t __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ f32x16_t mfma32u(const uint4 &a, const uint4 &b, f32x16_t c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+// All 64 * NW threads of the workgroup must call this together (it contains workgroup barriers).
+//   q0:       first query (relative to the block's first query) of this wavefront; wavefronts with q0 >= nq idle
+//   lds:      NBUF * cross_tile_lds_bytes<HP>() bytes, 16-byte aligned; NBUF = 2 double-buffers the tiles
+// Query j sits in row (c_first + q_shift + j) of Q / Qf and its partial goes to the slot of (level, c_first + j).
+// P is a multiple of 64.
+template <bool HP, int NW, int NBUF>
+__device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, const float *__restrict__ Qf,
+                                              const bf16_t *__restrict__ K, const bf16_t *__restrict__ Klo,
+                                              const bf16_t *__restrict__ VT, int vt_stride, float *__restrict__ pm,
+                                              float *__restrict__ pl, float *__restrict__ po, int BH, int bh, int c_first,
+                                              int q_shift, int k_first, int P, int q0, int nq, int level, int level_rel,
+                                              int slots, float scale, unsigned char *lds)
+{
+    constexpr int T = 64 * NW;
+    constexpr int kPieces = kKC * 8;              // 16-byte pieces of one 64 x 64 bf16 tile
+    constexpr int PPT = (kPieces + T - 1) / T;    // pieces per thread and tile
+    constexpr int TILE = kKC * kTileLd;           // elements of one LDS tile
+    constexpr int BUF = (HP ? 3 : 2) * TILE;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const size_t rs = (size_t)BH * kHeadDim;
+    bf16_t *tiles = reinterpret_cast<bf16_t *>(lds);
+    const bool active = q0 < nq;   // wave-uniform
+    const float c2 = scale * kLog2e;
+
+    // ---- this wavefront's 32 queries as B fragments (contraction step ks covers head dimensions 16ks .. 16ks+15)
+    uint4 bq[4], bql[4];
+    {
+        const int qi = min(q0 + l32, nq - 1);
+        const size_t qo = (size_t)(c_first + q_shift + qi) * rs + (size_t)bh * kHeadDim + 8 * hi;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            if (HP) {
+                float f[8], r[8];
+                load8(Qf + qo + ks * 16, f);
+                uint32_t h2[4];
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    h2[e] = cvt_pk_bf16(f[2 * e], f[2 * e + 1]);
+                    r[2 * e] = f[2 * e] - __uint_as_float(h2[e] << 16);
+                    r[2 * e + 1] = f[2 * e + 1] - __uint_as_float(h2[e] & 0xFFFF0000u);
+                }
+                bq[ks] = make_uint4(h2[0], h2[1], h2[2], h2[3]);
+                bql[ks] = make_uint4(cvt_pk_bf16(r[0], r[1]), cvt_pk_bf16(r[2], r[3]), cvt_pk_bf16(r[4], r[5]), cvt_pk_bf16(r[6], r[7]));
+            } else {
+                bq[ks] = *reinterpret_cast<const uint4 *>(Q + qo + ks * 16);
+            }
+        }
+    }
+
+    // The query loads are issued before any key/value load: waiting for the first chunk then also covers them, and
+    // the loop never has to wait on the memory counter for a query fragment (which would also wait for the chunk
+    // that has just been requested).
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- global -> register -> LDS staging of one chunk (thread -> 16-byte piece: 8 consecutive threads cover one row)
+    u32x4_t rk[PPT], rl[PPT], rv[PPT];   // native vectors: these must stay in registers across the chunk's work
+    const int prow = tid >> 3, pc16 = tid & 7;                    // piece i of this thread: row prow + i * (T / 8)
+    const bf16_t *gk = K + (size_t)(k_first + prow) * rs + (size_t)bh * kHeadDim + pc16 * 8;
+    const bf16_t *gl = HP ? Klo + (size_t)(k_first + prow) * rs + (size_t)bh * kHeadDim + pc16 * 8 : nullptr;
+    const bf16_t *gv = VT + ((size_t)bh * kHeadDim + prow) * vt_stride + k_first + pc16 * 8;
+    const int lds_off = prow * kTileLd + pc16 * 8, lds_off_v = prow * kVLd + pc16 * 8;
+#define RT_CT_FETCH(kc)                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < PPT; ++i)                                                                  \
+    {                                                                                                                \
+        if (kPieces % T == 0 || tid + i * T < kPieces) {                                                             \
+            rk[i] = *reinterpret_cast<const u32x4_t *>(gk + (size_t)((kc) + i * (T / 8)) * rs);                        \
+            if (HP) rl[i] = *reinterpret_cast<const u32x4_t *>(gl + (size_t)((kc) + i * (T / 8)) * rs);                \
+            rv[i] = *reinterpret_cast<const u32x4_t *>(gv + (size_t)(i * (T / 8)) * vt_stride + (kc));                 \
+        }                                                                                                            \
+    }
+#define RT_CT_STAGE(buf)                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < PPT; ++i)                                                                  \
+    {                                                                                                                \
+        if (kPieces % T == 0 || tid + i * T < kPieces) {                                                             \
+            bf16_t *dst = tiles + (size_t)(buf) * BUF + lds_off + i * (T / 8) * kTileLd;                             \
+            *reinterpret_cast<u32x4_t *>(dst) = rk[i];                                                                 \
+            {                                                                                                        \
+                bf16_t *dv = tiles + (size_t)(buf) * BUF + TILE + lds_off_v + i * (T / 8) * kVLd;                    \
+                *reinterpret_cast<uint2 *>(dv) = make_uint2(rv[i][0], rv[i][1]);                                     \
+                *reinterpret_cast<uint2 *>(dv + 4) = make_uint2(rv[i][2], rv[i][3]);                                 \
+            }                                                                                                        \
+            if (HP) *reinterpret_cast<u32x4_t *>(dst + 2 * TILE) = rl[i];                                              \
+        }                                                                                                            \
+    }
+
+    // reference value m2 (log2 units; the two lanes that share a query hold the same value), row sum l (each of
+    // the two lanes sums its own keys), accumulators O^T (2 tiles of 32 head dimensions x 32 queries)
+    float m2 = -INFINITY, lsum = 0.f;
+    f32x16_t O[2];
+#pragma unroll
+    for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) O[dt][i] = 0.f;
+
+    RT_CT_FETCH(0)
+    RT_CT_STAGE(0)
+    __syncthreads();
+    const int nchunks = P / kKC;
+    for (int c = 0; c < nchunks; ++c) {
+        const int cur = (NBUF == 2) ? (c & 1) : 0;
+        if (c + 1 < nchunks) { RT_CT_FETCH((c + 1) * kKC) }
+        if (active) {
+            const bf16_t *Ks = tiles + (size_t)cur * BUF, *Vs = Ks + TILE, *Kl = Ks + 2 * TILE;
+            // ---- S^T = K Q^T for 64 keys x 32 queries (fragments are read next to their use: the kernel runs four
+            // wavefronts per SIMD within 128 registers, and the other wavefronts cover the LDS latency)
+            f32x16_t S[2];
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                const bf16_t *krow = Ks + (kt * 32 + l32) * kTileLd + 8 * hi;
+                uint4 ka[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) ka[ks] = *reinterpret_cast<const uint4 *>(krow + ks * 16);
+                f32x16_t acc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+                if (HP) {   // small terms first
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks)
+                        acc = mfma32u(*reinterpret_cast<const uint4 *>(krow + (Kl - Ks) + ks * 16), bq[ks], acc);
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bql[ks], acc);
+                }
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bq[ks], acc);
+                S[kt] = acc;
+            }
+            // ---- move the reference where a logit runs more than kSlack ahead of it (always on the first chunk)
+            float lmax = fmaxf(fmaxf(S[0][0], S[0][1]), S[0][2]);
+#pragma unroll
+            for (int i = 3; i < 15; i += 2) lmax = fmaxf(fmaxf(lmax, S[0][i]), S[0][i + 1]);
+            lmax = fmaxf(fmaxf(lmax, S[0][15]), S[1][0]);
+#pragma unroll
+            for (int i = 1; i < 15; i += 2) lmax = fmaxf(fmaxf(lmax, S[1][i]), S[1][i + 1]);
+            lmax = fmaxf(lmax, S[1][15]) * c2;
+            const bool over = lmax > m2 + kSlack;
+            if (__any(over)) {
+                const float mx = fmaxf(lmax, __shfl_xor(lmax, 32, 64));
+                const float m_new = fmaxf(m2, mx);
+                const float resc = __builtin_amdgcn_exp2f(m2 - m_new);   // exp2(-inf) = 0 on the first chunk
+                m2 = m_new;
+                lsum *= resc;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) O[dt] *= resc;
+            }
+            // ---- P^T = exp2(S^T c2 - m2), packed: registers 8s .. 8s+7 of tile kt are the B fragment of step 2kt + s
+            uint4 bp[4];
+            const float nm = -m2;
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                float p[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const float sv = S[s4 >> 1][8 * (s4 & 1) + e];
+                    p[e] = __builtin_amdgcn_exp2f(fmaf(sv, c2, nm));
+                }
+                bp[s4] = make_uint4(cvt_pk_bf16(p[0], p[1]), cvt_pk_bf16(p[2], p[3]), cvt_pk_bf16(p[4], p[5]), cvt_pk_bf16(p[6], p[7]));
+                // plain adds: they run beside the matrix pipeline, which the dot-product and exponential instructions do not
+                lsum += ((p[0] + p[1]) + (p[2] + p[3])) + ((p[4] + p[5]) + (p[6] + p[7]));
+            }
+            // ---- O^T += V^T P^T
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const bf16_t *vrow = Vs + (dt * 32 + l32) * kVLd + s4 * 16 + 4 * hi;
+                    const uint2 v0 = *reinterpret_cast<const uint2 *>(vrow), v1 = *reinterpret_cast<const uint2 *>(vrow + 8);
+                    O[dt] = mfma32u(make_uint4(v0.x, v0.y, v1.x, v1.y), bp[s4], O[dt]);
+                }
+            }
+        }
+        if (c + 1 < nchunks) {
+            if (NBUF == 1) __syncthreads();   // everyone is done reading the single buffer
+            RT_CT_STAGE((NBUF == 2) ? (cur ^ 1) : 0)
+            __syncthreads();
+        }
+    }
+
+    if (active) {
+        const float l = lsum + __shfl_xor(lsum, 32, 64);
+        const int qi = q0 + l32;
+        if (qi < nq) {
+            const size_t idx = partial_index(level_rel, partial_slot(level, c_first + qi), slots, BH, bh);
+            if (hi == 0) { pm[idx] = m2 * kLn2; pl[idx] = l; }
+            // register i of tile dt is head dimension 32dt + 8(i/4) + 4hi + i%4
+            float *orow = po + idx * kHeadDim + 4 * hi;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<float4 *>(orow + dt * 32 + 8 * j) =
+                        make_float4(O[dt][4 * j], O[dt][4 * j + 1], O[dt][4 * j + 2], O[dt][4 * j + 3]);
+        }
+    }
+}
+
+#undef RT_CT_FETCH
+#undef RT_CT_STAGE
+
+}  // namespace rt

@@ -8,6 +8,7 @@
 // Both operands want the contraction index contiguous per lane, which is how x, the weights, q and k
 // rows are stored, so those fragments are loaded straight from global memory.
 #include "rt_mfma_device.h"
+#include "rt_cross_tile.h"
 
 namespace rt {
 
@@ -142,10 +143,36 @@ __global__ __launch_bounds__(256) void cross_mfma_kernel(const bf16_t *__restric
                            level_rel, slots, scale);
 }
 
+// Same tile with K and V^T staged in LDS for the four wavefronts (128 queries) of a workgroup, blocks of
+// 64 keys and more.  Workgroups are dealt to the 8 XCDs round-robin by the dispatcher, so the index is
+// decoded such that all query blocks of one (b, h) land on the same XCD and its key/value tiles are
+// fetched into that L2 once.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void cross_tile_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                         const bf16_t *__restrict__ VT, int vt_stride,
+                                                         float *__restrict__ pm, float *__restrict__ pl,
+                                                         float *__restrict__ po, int BH, int t1, int P, int nq, int nqb,
+                                                         int level, int level_rel, int slots, float scale)
+{
+    __shared__ __align__(16) unsigned char lds[2 * cross_tile_lds_bytes<false>()];
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int bh = (j / nqb) * 8 + xcd, qb = j % nqb;
+    if (bh >= BH) return;   // the whole workgroup leaves together
+    cross_tile_wg<false, 4, 2>(Q, nullptr, K, nullptr, VT, vt_stride, pm, pl, po, BH, bh, t1, 0, t1 - P, P,
+                               qb * 128 + (int)(threadIdx.x >> 6) * 32, nq, level, level_rel, slots, scale, lds);
+}
+
 hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, hipStream_t st)
 {
     int level = 0;
     while ((1 << level) < P) ++level;
+    if (P >= kKC) {
+        const int nqb = (nq + 127) / 128;
+        const int bh8 = (D.B * D.H + 7) / 8 * 8;
+        hipLaunchKernelGGL(cross_tile_kernel, dim3(bh8 * nqb), dim3(256), 0, st, (const bf16_t *)S.Q, (const bf16_t *)K, S.VT,
+                           S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, nqb, level, level - D.log2_pmin, S.slots,
+                           D.scale);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(cross_mfma_kernel, dim3((nq + 127) / 128, D.B * D.H), dim3(256), 0, st, (const bf16_t *)S.Q,
                        (const bf16_t *)K, S.VT, S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, level,
                        level - D.log2_pmin, S.slots, D.scale);

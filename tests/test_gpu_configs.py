@@ -50,6 +50,6 @@ def test_config3_bf16_full_headline(oracle):
     _full(oracle, "cfg3")
 
 
-@pytest.mark.parametrize("N", [1024, 2048])
+@pytest.mark.parametrize("N", [1024, 2048, 4096, 8192])
 def test_config4_sweep_prefixes(oracle, N):
     _full(oracle, "cfg4_8192", N=N)

@@ -97,6 +97,45 @@ def test_stepwise_bf16_plain_alu_and_mfma_agree_with_oracle(oracle):
     _run_case(oracle, "bf16", 5, 333, 320, 5, 1280, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=64)   # odd head count, ragged N
 
 
+def test_cross_block_tiles_with_several_query_blocks(oracle):
+    """Blocks of 256 and 512 keys: the LDS-staged tile kernel runs with two and more 128-query workgroups per
+    (b, h), a ragged last workgroup (N = 700: the 512-key block serves 188 queries) and 16 x 3 = 48 (b, h)
+    problems dealt over the 8 XCD slots."""
+    b = _flags()
+    _run_case(oracle, "bf16", 3, 700, 1024, 16, 4096, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=64, expect_engine="stepwise")
+
+
+def test_cross_block_event_rerun_and_argument_checks(oracle):
+    """rt_cross_block_event re-runs one tile on the state of the last prefill; the prefill's outputs stay as
+    they were and a following prefill gives the same bits as before."""
+    binding, tio = _gpu()
+    B, N, d, H, F = 2, 300, 256, 4, 1024
+    li = gen.make_custom(9, "bf16", B, N, d, H, F)
+    for flags in (binding.RT_FLAG_ENGINE_STEPWISE, binding.RT_FLAG_ENGINE_PERSISTENT):
+        ctx = binding.RTContext(d, H, F, B, N, "bf16", p_min=32, flags=flags)
+        try:
+            dl = tio.DeviceLayer(li.weights, li.gains, "bf16")
+            xd = tio.to_device(li.x, "bf16")
+            K0 = torch.zeros((N, B, H, 64), dtype=torch.bfloat16, device="cuda:0")
+            with pytest.raises(binding.RTError):
+                ctx.rt_cross_block_event(K0, K0, 128, 128, 128)          # nothing has run yet
+            y, K, V = tio.prefill(ctx, dl, xd)
+            torch.cuda.synchronize()
+            y0 = y.clone()
+            for t1, P, nq in ((128, 128, 128), (256, 256, 44), (64, 64, 64), (32, 32, 32)):
+                ctx.rt_cross_block_event(K, V, t1, P, nq)
+            torch.cuda.synchronize()
+            assert torch.equal(y.view(torch.int16), y0.view(torch.int16))
+            for bad in ((128, 128, 129), (100, 128, 10), (128, 96, 10), (256, 256, 45), (0, 128, 1), (128, 16, 16)):
+                with pytest.raises(binding.RTError):
+                    ctx.rt_cross_block_event(K, V, *bad)
+            y2, _, _ = tio.prefill(ctx, dl, xd)
+            torch.cuda.synchronize()
+            assert torch.equal(y2.view(torch.int16), y0.view(torch.int16))
+        finally:
+            ctx.rt_destroy()
+
+
 def test_stepwise_hip_graph_replay_matches(oracle):
     b = _flags()
     _run_case(oracle, "bf16", 2, 130, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_STEPWISE | b.RT_FLAG_HIP_GRAPH, p_min=32,

@@ -464,3 +464,73 @@ def test_thread_modes_bit_identical(oracle):
     x8 = np.concatenate([x] * 4, axis=0)
     got8 = oracle.Layer(w, 4, threads=4).prefill(x8)
     np.testing.assert_array_equal(got8[0][:2], ref[0])
+
+
+# ------------------------------------------------------------------------------------------
+# Stack helpers: embedding lookup, final norm + read-out, layers fed one into the next (Sec. 2).
+# ------------------------------------------------------------------------------------------
+def test_stack_embed_is_row_lookup(oracle):
+    rng = np.random.default_rng(5)
+    table = rng.standard_normal((11, 6))
+    ids = np.array([[3, 0, 10, 3], [7, 7, 1, 2]])
+    x = oracle.embed(table, ids)
+    assert x.shape == (2, 4, 6)
+    for b in range(2):
+        for n in range(4):
+            assert list(x[b, n]) == list(table[ids[b, n]])
+
+
+def test_stack_lm_head_closed_forms(oracle):
+    rng = np.random.default_rng(6)
+    d, vocab = 8, 5
+    W = rng.standard_normal((vocab, d))
+    signs = np.array([1, -1, 1, 1, -1, -1, 1, -1], dtype=np.float64)
+    # a vector of constant magnitude normalises to its sign pattern (eps = 0): logits are signed row sums
+    want = [sum(W[v, k] * signs[k] for k in range(d)) for v in range(vocab)]
+    got = oracle.lm_head(W, (3.7 * signs)[None, :], eps=0.0)
+    np.testing.assert_allclose(got[0], want, rtol=1e-14)
+    # scale invariance at eps = 0, and a gain equals a column scaling of the matrix
+    z = rng.standard_normal((3, d))
+    np.testing.assert_allclose(oracle.lm_head(W, 5.0 * z, eps=0.0), oracle.lm_head(W, z, eps=0.0), rtol=1e-13)
+    g = rng.uniform(0.5, 1.5, d)
+    np.testing.assert_allclose(oracle.lm_head(W, z, g_final=g, eps=1e-6), oracle.lm_head(W * g[None, :], z, eps=1e-6),
+                               rtol=1e-13)
+    # eps enters under the root next to the mean square
+    z1 = np.full((1, d), 2.0)
+    np.testing.assert_allclose(oracle.lm_head(W, z1, eps=5.0)[0], W.sum(axis=1) * 2.0 / 3.0, rtol=1e-14)
+    # norm-free: plain projection
+    np.testing.assert_allclose(oracle.lm_head(W, z, norm_free=True), np.einsum("vk,bk->bv", W, z), rtol=1e-13)
+
+
+def test_stack_composes_layers_and_decodes(oracle):
+    rng = np.random.default_rng(7)
+    d, H, F, vocab, B, N = 16, 2, 32, 19, 2, 11
+    table = rng.standard_normal((vocab, d)) * 0.5
+    W_lm = rng.standard_normal((vocab, d))
+    ids = rng.integers(0, vocab, size=(B, N))
+    lays = []
+    for l in range(3):
+        li = gen.make_custom(90 + l, "f32", 1, 1, d, H, F, w_std=0.3, gains="random")
+        lays.append(oracle.Layer({k: v.astype(np.float64) for k, v in li.weights.items()}, H,
+                                 gains={k: v.astype(np.float64) for k, v in li.gains.items()}, alpha=1 / math.sqrt(3)))
+    st = oracle.Stack(lays, table, W_lm)
+    out, logits = st.prefill(ids, N, kv_cap=N)
+    # layer l+1 reads layer l's output; layer 0 reads the looked-up rows
+    x = table[ids]
+    for l in range(3):
+        y, K, V = lays[l].prefill(x)
+        np.testing.assert_array_equal(out[l][0], y)
+        np.testing.assert_array_equal(out[l][1], K)
+        x = y
+    np.testing.assert_allclose(logits, _rms(x[:, -1], eps=1e-6) @ W_lm.T, rtol=1e-12)
+    # a shorter prefill followed by decoding steps reproduces the longer prefill (Sec. 7.3), layer by layer
+    st2 = oracle.Stack(lays, table, W_lm)
+    n0 = 6
+    out0, _ = st2.prefill(ids, n0, kv_cap=N)
+    for t in range(n0, N):
+        ys, lg = st2.decode_step(ids, t)
+        for l in range(3):
+            np.testing.assert_array_equal(ys[l], out[l][0][:, t])
+    np.testing.assert_allclose(lg, logits, rtol=1e-12)
+    for l in range(3):
+        np.testing.assert_array_equal(st2.K[l], out[l][1])
