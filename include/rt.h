@@ -138,7 +138,7 @@ const char *rt_engine_name(const rt_ctx *ctx);
 /* Diagnostics of the persistent engine, after the stream has been synchronised: when the environment
  * variable RT_PERSIST_TRACE was set at rt_create, copies for each of the first `rows` positions sixteen
  * 100 MHz clock stamps of workgroup 0 (slot 0 start, 1..6 end of phases M, cross-block items, O, 1, 2, KV,
- * 7..12 points inside the phases) into out[rows][16] (host memory).  Returns the number of rows written, 0 if tracing is off. */
+ * 7..13 points inside the phases, 14 and 15 the end of the first grid barrier and of the tile work of a cross-block event) into out[rows][16] (host memory).  Returns the number of rows written, 0 if tracing is off. */
 int32_t rt_phase_trace(rt_ctx *ctx, uint64_t *out, int32_t rows);
 
 /* Diagnostics / measurement: run one cross-block UpdateTile (Appendix C, Algorithm 2) again, by itself, on the

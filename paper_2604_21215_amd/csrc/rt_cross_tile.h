@@ -52,6 +52,8 @@ __device__ __forceinline__ f32x16_t mfma32u(const uint4 &a, const uint4 &b, f32x
 // All 64 * NW threads of the workgroup must call this together (it contains workgroup barriers).
 //   q0:       first query (relative to the block's first query) of this wavefront; wavefronts with q0 >= nq idle
 //   lds:      NBUF * cross_tile_lds_bytes<HP>() bytes, 16-byte aligned; NBUF = 2 double-buffers the tiles
+//   tid:      threadIdx.x (a caller inside a long loop may pass it through an opaque copy, so that nothing derived
+//             from it is hoisted out of that loop and kept in registers)
 // Query j sits in row (c_first + q_shift + j) of Q / Qf and its partial goes to the slot of (level, c_first + j).
 // P is a multiple of 64.
 template <bool HP, int NW, int NBUF>
@@ -60,14 +62,14 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
                                               const bf16_t *__restrict__ VT, int vt_stride, float *__restrict__ pm,
                                               float *__restrict__ pl, float *__restrict__ po, int BH, int bh, int c_first,
                                               int q_shift, int k_first, int P, int q0, int nq, int level, int level_rel,
-                                              int slots, float scale, unsigned char *lds)
+                                              int slots, float scale, unsigned char *lds, int tid)
 {
     constexpr int T = 64 * NW;
     constexpr int kPieces = kKC * 8;              // 16-byte pieces of one 64 x 64 bf16 tile
     constexpr int PPT = (kPieces + T - 1) / T;    // pieces per thread and tile
     constexpr int TILE = kKC * kTileLd;           // elements of one LDS tile
     constexpr int BUF = (HP ? 3 : 2) * TILE;
-    const int tid = threadIdx.x, lane = tid & 63;
+    const int lane = tid & 63;
     const int l32 = lane & 31, hi = lane >> 5;
     const size_t rs = (size_t)BH * kHeadDim;
     bf16_t *tiles = reinterpret_cast<bf16_t *>(lds);

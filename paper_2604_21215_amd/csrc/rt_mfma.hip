@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
     const int bh = (j / nqb) * 8 + xcd, qb = j % nqb;
     if (bh >= BH) return;   // the whole workgroup leaves together
     cross_tile_wg<false, 4, 2>(Q, nullptr, K, nullptr, VT, vt_stride, pm, pl, po, BH, bh, t1, 0, t1 - P, P,
-                               qb * 128 + (int)(threadIdx.x >> 6) * 32, nq, level, level_rel, slots, scale, lds);
+                               qb * 128 + (int)(threadIdx.x >> 6) * 32, nq, level, level_rel, slots, scale, lds, (int)threadIdx.x);
 }
 
 hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, hipStream_t st)

@@ -55,6 +55,7 @@
 // leaves the kernel at its next wait, and the host reports it (rt_device_wait_expired).
 #include "rt_persistent.h"
 #include "rt_mfma_device.h"
+#include "rt_cross_tile.h"
 
 #include <cstdlib>
 
@@ -485,6 +486,16 @@ __device__ __forceinline__ void pre_finish(const PersistArgs &A, int t, int u, c
     }
 }
 
+// One cross-block item of the whole workgroup.
+__device__ __forceinline__ void cross_tile_item(const PersistArgs &A, int bh, int t, int P, int q0, int nq, int level,
+                                             unsigned char *lds)
+{
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));   // opaque: keeps the tile's lane-derived addresses out of the registers of the per-position phases
+    cross_tile_wg<true, kPW, 1>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, A.BH, bh, t, 1, t - P, P, q0, nq,
+                                level, level - A.log2_pmin, A.slots, A.scale, lds, tid);
+}
+
 // KSD = d / 256, KSF = F / 256: contraction steps per wavefront, fixed at compile time so that all
 // exchange loads of a phase are in flight at once without spilling.
 template <int KSD, int KSF>
@@ -635,16 +646,30 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             const int P = t & -t;
             if (grid_barrier(A, (++nbar) * (unsigned long long)G, flag_s)) { fail = 1; }
             RT_ABORT_IF(fail);
+            RT_STAMP(14);
             const int nq = min(P, A.N - 1 - t);
             const int qblocks = (nq + 31) / 32;
             const int items = BH * qblocks;
             int level = A.log2_pmin;
             while ((1 << level) < P) ++level;
-            for (int it = wave * G + wg; it < items; it += G * kPW) {
-                const int bh = it % BH, qb = it / BH;
-                cross_mfma_wave<true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1, t - P, P, qb * 32,
-                                      nq, level, level - A.log2_pmin, A.slots, A.scale);
+            if (P >= kKC) {
+                // blocks of 64 keys and more: the whole workgroup takes one (b, h) and up to 256 queries at a time,
+                // with the key and value tiles staged in the LDS area that the phases use for staged activations
+                // and pre-fetched merge inputs (both idle between phase M and phase O)
+                const int qgroups = (nq + 32 * kPW - 1) / (32 * kPW);
+                for (int it = wg; it < BH * qgroups; it += G) {
+                    const int bh = it % BH, qg = it / BH;
+                    cross_tile_item(A, bh, t, P, qg * 32 * kPW + wave * 32, nq, level, reinterpret_cast<unsigned char *>(act_s));
+                    __syncthreads();   // the next item overwrites the tiles
+                }
+            } else {
+                for (int it = wave * G + wg; it < items; it += G * kPW) {
+                    const int bh = it % BH, qb = it / BH;
+                    cross_mfma_wave<true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1, t - P, P, qb * 32,
+                                          nq, level, level - A.log2_pmin, A.slots, A.scale);
+                }
             }
+            RT_STAMP(15);
             if (grid_barrier(A, (++nbar) * (unsigned long long)G, flag_s)) { fail = 1; }
             RT_ABORT_IF(fail);
         }
@@ -807,8 +832,11 @@ static size_t lds_bytes_for(int d, int F, int G, int win_rows, int upw, int max_
     b = align_up(b, 16);
     b += (size_t)(kPW * kRMax * kBMax + kRMax * kBMax + 32 * kBMax + kBMax) * 4 + 16;
     b += (size_t)upw * win_rows * ((kHeadDim + 4) * 4 + kHeadDim * 2);   // direct-window rows (fp32 keys, bf16 values)
-    b += (size_t)max_batch * ldw_d * 2;                // staged activation rows of the phase in flight
-    b += (size_t)upw * kPreFloats * 4;                 // pre-fetched merge inputs
+    b = align_up(b, 16);
+    size_t tail = (size_t)max_batch * ldw_d * 2;       // staged activation rows of the phase in flight
+    tail += (size_t)upw * kPreFloats * 4;              // pre-fetched merge inputs
+    const size_t tiles = (size_t)cross_tile_lds_bytes<true>();   // the cross-block tiles reuse the same area
+    b += tail > tiles ? tail : tiles;
     return b;
 }
 
