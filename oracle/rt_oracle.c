@@ -148,16 +148,19 @@ static int make_tw(const rto_params *p, rto_tw *w)
 /* per-row scratch */
 typedef struct {
     double *n, *q, *kt, *vt, *cat, *a, *h, *u, *hid, *mo, *r, *logit;
+    int maxpos;
 } rto_ws;
 
-static int make_ws(rto_ws *s, int d, int F, int maxpos)
+static int make_ws(rto_ws *s, int d, int F, int maxpos, int H)
 {
-    size_t tot = (size_t)d * 9 + (size_t)F + (size_t)d + (size_t)maxpos + 8;
+    /* one logit row per head, so that the heads of a position can be evaluated by different threads */
+    size_t tot = (size_t)d * 9 + (size_t)F + (size_t)d + (size_t)maxpos * (size_t)H + 8;
     double *base = (double *)calloc(tot, sizeof(double));
     if (!base) return -1;
     s->n = base; s->q = s->n + d; s->kt = s->q + d; s->vt = s->kt + d; s->cat = s->vt + d;
     s->a = s->cat + d; s->h = s->a + d; s->u = s->h + d; s->mo = s->u + d; s->r = s->mo + d;
     s->hid = s->r + d; s->logit = s->hid + F;
+    s->maxpos = maxpos;
     return 0;
 }
 static void free_ws(rto_ws *s) { free(s->n); }
@@ -204,30 +207,34 @@ static void finish_position(const rto_params *p, const rto_tw *w, const double *
 /* Attention of one position: persistent rows 0..t-1 of (K, V) for batch row b plus the
  * temporary pair (s->kt, s->vt); direct two-pass softmax.  attw (optional) gets [H][t+1] weights. */
 static void attend(const rto_params *p, rto_ws *s, const double *K, const double *V, int B, int b, int t,
-                   double *attw, int attw_stride)
+                   double *attw, int attw_stride, int par)
 {
     const int H = p->H, dh = p->dh;
+    /* heads are independent (Sec. 2, Notation); with par != 0 they are spread over the threads, each with its own
+     * logit row, in the same arithmetic order as the serial loop */
+#pragma omp parallel for schedule(static) if (par && t >= 64)
     for (int h = 0; h < H; ++h) {
         const double *q = s->q + h * dh;
+        double *logit = s->logit + (size_t)h * s->maxpos;
         double mx = -INFINITY;
         for (int j = 0; j < t; ++j) {
             const double *kj = K + (((size_t)j * B + b) * H + h) * dh;
-            s->logit[j] = p->attn_scale * dot(kj, q, dh);
-            if (s->logit[j] > mx) mx = s->logit[j];
+            logit[j] = p->attn_scale * dot(kj, q, dh);
+            if (logit[j] > mx) mx = logit[j];
         }
-        s->logit[t] = p->attn_scale * dot(s->kt + h * dh, q, dh);
-        if (s->logit[t] > mx) mx = s->logit[t];
+        logit[t] = p->attn_scale * dot(s->kt + h * dh, q, dh);
+        if (logit[t] > mx) mx = logit[t];
         double den = 0.0;
-        for (int j = 0; j <= t; ++j) { s->logit[j] = exp(s->logit[j] - mx); den += s->logit[j]; }
+        for (int j = 0; j <= t; ++j) { logit[j] = exp(logit[j] - mx); den += logit[j]; }
         double *o = s->cat + h * dh;
         for (int c = 0; c < dh; ++c) o[c] = 0.0;
         for (int j = 0; j < t; ++j) {
-            const double wj = s->logit[j] / den;
+            const double wj = logit[j] / den;
             const double *vj = V + (((size_t)j * B + b) * H + h) * dh;
             for (int c = 0; c < dh; ++c) o[c] += wj * vj[c];
             if (attw) attw[(size_t)h * attw_stride + j] = wj;
         }
-        const double wt = s->logit[t] / den;
+        const double wt = logit[t] / den;
         for (int c = 0; c < dh; ++c) o[c] += wt * s->vt[h * dh + c];
         if (attw) attw[(size_t)h * attw_stride + t] = wt;
     }
@@ -258,7 +265,7 @@ static void position(const rto_params *p, const rto_tw *w, rto_ws *s, const doub
 {
     const int H = p->H, dh = p->dh;
     project_qkv(p, w, x_row, s, par);
-    attend(p, s, K, V, B, b, t, attw, attw_stride);
+    attend(p, s, K, V, B, b, t, attw, attw_stride, par);
     double *k_out = K + (((size_t)t * B + b) * H) * dh;
     double *v_out = V + (((size_t)t * B + b) * H) * dh;
     finish_position(p, w, x_row, s, y_row, k_out, v_out, par);
@@ -278,7 +285,7 @@ int rto_layer_prefill(const rto_params *p, const double *x, int B, int N, double
     const int inner = !outer && nt > 1 && d >= 256;  /* else split matrix rows */
     rto_ws *ws = (rto_ws *)calloc((size_t)B, sizeof(rto_ws));
     int err = ws ? 0 : -2;
-    for (int b = 0; b < B && !err; ++b) if (make_ws(&ws[b], d, p->F > 0 ? p->F : 1, N + 1)) err = -2;
+    for (int b = 0; b < B && !err; ++b) if (make_ws(&ws[b], d, p->F > 0 ? p->F : 1, N + 1, H)) err = -2;
     if (!err) {
 #ifdef _OPENMP
         omp_set_num_threads(nt);
@@ -304,7 +311,7 @@ int rto_decode_step(const rto_params *p, const double *x_t, int B, int t, double
     rto_tw w;
     if (make_tw(p, &w)) return -2;
     rto_ws s;
-    if (make_ws(&s, p->d, p->F > 0 ? p->F : 1, t + 1)) { free_tw(&w); return -2; }
+    if (make_ws(&s, p->d, p->F > 0 ? p->F : 1, t + 1, p->H)) { free_tw(&w); return -2; }
     for (int b = 0; b < B; ++b)
         position(p, &w, &s, x_t + (size_t)b * p->d, B, b, t, y_t + (size_t)b * p->d, K, V, NULL, 0, 0);
     free_ws(&s);
@@ -322,7 +329,7 @@ int rto_transformer_layer(const rto_params *p, const double *x, int B, int N, do
     if (make_tw(p, &w)) return -2;
     const int d = p->d, H = p->H, dh = p->dh, F = p->F;
     rto_ws s;
-    if (make_ws(&s, d, F > 0 ? F : 1, N + 1)) { free_tw(&w); return -2; }
+    if (make_ws(&s, d, F > 0 ? F : 1, N + 1, p->H)) { free_tw(&w); return -2; }
     for (int b = 0; b < B; ++b) {
         for (int t = 0; t < N; ++t) {
             const double *xr = x + ((size_t)b * N + t) * d;
@@ -333,7 +340,7 @@ int rto_transformer_layer(const rto_params *p, const double *x, int B, int N, do
             double *v_row = V + (((size_t)t * B + b) * H) * dh;
             for (int i = 0; i < d; ++i) { k_row[i] = s.kt[i]; v_row[i] = s.vt[i]; }
             double *aw = attw ? attw + (((size_t)b * H) * N + t) * N : NULL;
-            attend(p, &s, K, V, B, b, t, aw, N * N); /* rows < t persistent + (kt, vt) == row t */
+            attend(p, &s, K, V, B, b, t, aw, N * N, 0); /* rows < t persistent + (kt, vt) == row t */
             if (w.Wo_t) matvec(w.Wo_t, d, d, s.cat, s.a, 0);
             else for (int i = 0; i < d; ++i) s.a[i] = s.cat[i];
             for (int i = 0; i < d; ++i) s.h[i] = xr[i] + p->alpha * s.a[i];
@@ -415,7 +422,7 @@ int rto_layer_prefill_tiled(const rto_params *p, const double *x, int B, int N, 
     if (make_tw(p, &w)) return -2;
     const int d = p->d, H = p->H, dh = p->dh;
     rto_ws s;
-    if (make_ws(&s, d, p->F > 0 ? p->F : 1, N + 1)) { free_tw(&w); return -2; }
+    if (make_ws(&s, d, p->F > 0 ? p->F : 1, N + 1, p->H)) { free_tw(&w); return -2; }
     double *Q = (double *)malloc(sizeof(double) * (size_t)N * d);
     double *m = (double *)malloc(sizeof(double) * (size_t)N * H);
     double *l = (double *)malloc(sizeof(double) * (size_t)N * H);
