@@ -18,9 +18,8 @@ struct PersistentState {
     // exchange buffers between the phases of a position (device)
     unsigned long long *bar = nullptr;   // [0] fenced-barrier counter, [8] abort word (non-zero once a wait expired)
     void *a_ll = nullptr, *h_ll = nullptr, *u_ll = nullptr, *z_ll = nullptr;
-    void *kv_ll = nullptr, *hss_ll = nullptr, *zss_ll = nullptr, *done_m = nullptr, *done_1 = nullptr, *zp_ll = nullptr;
+    void *kv_ll = nullptr, *zss_ll = nullptr, *zp_ll = nullptr;
     int win_rows = 0, upw = 1;
-    int gate_mask = 0;
     int max_batch = 0;
     unsigned nonce = 0;                  // per-call tag prefix of the exchange words
     unsigned long long *trace = nullptr; // optional per-position phase clocks

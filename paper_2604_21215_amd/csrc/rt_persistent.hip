@@ -36,7 +36,7 @@
 // fenced grid barrier (release, counter, acquire) 7.5-11 us, the fences alone 3.6-7.9 us, a counter
 // barrier without fences 4.2 us, a flag-in-data all-to-all hop 2.7-3.3 us; waiting for separate
 // "producer done" words before the bulk loads was slower than polling the data (39.8 vs 34.3 us per
-// position, kept behind gate_mask for experiments).  Bulk loads are pulled thread-linearly with 16-byte
+// position, so that variant is gone).  Bulk loads are pulled thread-linearly with 16-byte
 // agent-scope buffer loads and staged in LDS (see wg_gemv_ll).  Buffers alternate with the parity of t;
 // a writer of position t+2 has always (transitively) gathered the partial sums of z^2 of position t+1
 // from all workgroups, which each of them stored after it had finished reading position t.
@@ -123,9 +123,8 @@ struct PersistArgs {
     ll_t *a_ll, *h_ll, *z_ll;   // [..][d/2]   two bf16 per word
     ll_t *u_ll;                 // [..][F/2]
     ll_t *kv_ll;                // [..][2d]    one fp32 per word
-    ll_t *hss_ll, *zss_ll;      // [..][G]     one fp32 per word
+    ll_t *zss_ll;               // [..][G]     one fp32 per word
     ll_t *zp_ll;                // [2][4][kBMax][d] one fp32 per word: partial W2 products of the four contraction blocks
-    ll_t *done_m, *done_1;      // [2][256]    "producer finished" words of phase M (per unit) and phase 1 (per workgroup)
     int win_rows;               // p_min when the direct window is kept in LDS, else 0 (window re-read from K, V)
     int upw;                    // merge units per workgroup = ceil(BH_max / G)
     int max_batch;              // rows of the LDS staging area
@@ -133,7 +132,6 @@ struct PersistArgs {
     unsigned long long *bar;    // [0] fenced-barrier counter, [8] abort word
     unsigned long long *trace;  // optional: [N][16] wall-clock stamps of workgroup 0
     long long spin_limit;
-    int gate_mask;              // bit 0/1/2: wait for the producers-done words before the bulk loads of phase O / 2a / KV
 };
 
 __device__ __forceinline__ ll_t ll_load(const ll_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -323,17 +321,6 @@ __device__ __forceinline__ void ll_wait_n(const ll_t *const (&p)[NW], const bool
     }
 }
 
-// Gate: wait until the first `count` words of `words` carry `tag` (thread i polls word i, i + 512, ...).
-// The bulk loads of a phase are issued only after its producers have signalled, so an early consumer
-// polls a few hundred bytes instead of re-reading whole activation vectors.
-__device__ __forceinline__ void gate_wait(const ll_t *words, int count, unsigned tag, const PersistArgs &A, int &fail)
-{
-    for (int i0 = 0; i0 < count; i0 += kPThreads) {
-        const bool act = i0 + (int)threadIdx.x < count;
-        (void)ll_wait(words + (act ? i0 + threadIdx.x : 0), act, tag, A, fail);
-    }
-}
-
 // Direct window out of LDS: query (lane c holds q[c]) against nkeys <= 64 rows kept by this wavefront.
 __device__ __forceinline__ void attend_lds(float q, const float *ks, const bf16_t *vs, int nkeys, float scale, float &m,
                                            float &l, float &o)
@@ -358,32 +345,6 @@ __device__ __forceinline__ void attend_lds(float q, const float *ks, const bf16_
     for (int j = 0; j < nkeys; ++j) on = fmaf(lane_bcast(p, j), bf16_to_f32(vs[(size_t)j * kHeadDim + lane]), on);
     o = on;
     m = m_new;
-}
-
-// sum over the G producers of one fp32 exchange row per batch row: 32 threads per batch row poll
-// (up to 8 words each, i.e. G <= 256 per pass), partials go to sq[32][kBMax]; the caller syncs and
-// finishes the sum.
-__device__ __forceinline__ void gather_partial_sums(const ll_t *ss, int G, int B, unsigned tag, const PersistArgs &A, float *sq,
-                                                    int &fail)
-{
-    const int jb = threadIdx.x & 15, jg = threadIdx.x >> 4;
-    float s = 0.f;
-    for (int j0 = 0; j0 < G; j0 += 8 * (kPThreads / 16)) {
-        const ll_t *p[8];
-        bool act[8];
-        ll_t w[8];
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-            const int j = j0 + i * (kPThreads / 16) + jg;
-            act[i] = jb < B && j < G;
-            p[i] = ss + (size_t)jb * G + (act[i] ? j : 0);
-        }
-        ll_wait_n<8>(p, act, tag, A, w, fail);
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            if (act[i]) s += __uint_as_float((unsigned)w[i]);
-    }
-    sq[jg * kBMax + jb] = s;
 }
 
 #define RT_STAMP(k)                                                                         \
@@ -634,7 +595,6 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 if (!(lane & 1))
                     ll_store(A.a_ll + par * half_d + frag_word<KSD>(h * kHeadDim + lane, b), tag,
                              (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
-                if (lane == 0) ll_store(A.done_m + par * 256 + u, tag, 1u);
             }
         }
         RT_ABORT_IF(fail);
@@ -676,10 +636,6 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         RT_STAMP(2);
 
         // ================================================================ phase O:  h = x_t + alpha Wo a
-        if (A.gate_mask & 1) {
-            gate_wait(A.done_m + par * 256, BH, tag, A, fail);
-            RT_ABORT_IF(fail);
-        }
         RT_STAMP(7);
         wg_gemv_ll<KSD>(wo_s, A.ldw_d, o_n, A.a_ll + par * half_d, d / 2, B, tag, A, red, act_s, A.ldw_d, fail);
         RT_ABORT_IF(fail);
@@ -716,14 +672,9 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                          (unsigned)f32_to_bf16(uv) | ((unsigned)f32_to_bf16(un) << 16));
         }
         __syncthreads();
-        if (tid == 0) ll_store(A.done_1 + par * 256 + wg, tag, 1u);
         RT_STAMP(4);
 
         // ================================================================ phase 2a:  partial W2 u over contraction block jb
-        if (A.gate_mask & 2) {
-            gate_wait(A.done_1 + par * 256 + jb * 64, 64, tag, A, fail);   // the 64 producers of u[jb*d .. +d)
-            RT_ABORT_IF(fail);
-        }
         RT_STAMP(9);
         wg_gemv_ll<KSD>(w2_s, A.ldw_d, RB, A.u_ll + par * half_F + (size_t)jb * (d / 2), F / 2, B, tag, A, red, act_s, A.ldw_d, fail);
         RT_ABORT_IF(fail);
@@ -777,10 +728,6 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         RT_STAMP(5);
 
         // ================================================================ phase KV:  [Wk; Wv] (z g_kv)
-        if (A.gate_mask & 4) {
-            gate_wait(A.zss_ll + par * sz_ss, G, tag, A, fail);   // batch row 0's partial sums: one word per producer
-            RT_ABORT_IF(fail);
-        }
         const bool pre = has_u && t + 1 < A.N;
         wg_gemv_ll<KSD>(wkv_s, A.ldw_d, kv_n, A.z_ll + par * half_d, d / 2, B, tag, A, red, act_s, A.ldw_d, fail);
         RT_ABORT_IF(fail);
@@ -882,8 +829,7 @@ rt_status persistent_create(PersistentState &P, const rt_config &cfg, const Laye
     const size_t o_a = carve(2 * kBMax * (d / 2) * 8), o_h = carve(2 * kBMax * (d / 2) * 8);
     const size_t o_u = carve(2 * kBMax * (F / 2) * 8), o_z = carve(2 * kBMax * (d / 2) * 8);
     const size_t o_kv = carve(2 * kBMax * 2 * d * 8);
-    const size_t o_hss = carve((size_t)2 * kBMax * G * 8), o_zss = carve((size_t)2 * kBMax * G * 8);
-    const size_t o_dm = carve(2 * 256 * 8), o_d1 = carve(2 * 256 * 8);
+    const size_t o_zss = carve((size_t)2 * kBMax * G * 8);
     const size_t o_zp = carve((size_t)2 * 4 * kBMax * d * 8);
     const size_t o_tr = want_trace ? carve((size_t)cfg.max_seq * 16 * 8) : 0;
     P.slab_bytes = off;
@@ -901,15 +847,12 @@ rt_status persistent_create(PersistentState &P, const rt_config &cfg, const Laye
     char *p = (char *)P.slab;
     P.bar = (unsigned long long *)(p + o_bar);
     P.a_ll = p + o_a; P.h_ll = p + o_h; P.u_ll = p + o_u; P.z_ll = p + o_z;
-    P.kv_ll = p + o_kv; P.hss_ll = p + o_hss; P.zss_ll = p + o_zss;
-    P.done_m = p + o_dm; P.done_1 = p + o_d1; P.zp_ll = p + o_zp;
+    P.kv_ll = p + o_kv; P.zss_ll = p + o_zss; P.zp_ll = p + o_zp;
     P.trace = want_trace ? (unsigned long long *)(p + o_tr) : nullptr;
     P.trace_rows = want_trace ? cfg.max_seq : 0;
     const char *sl = getenv("RT_SPIN_LIMIT");
     P.spin_limit = sl ? atoll(sl) : (1LL << 21);
     if (P.spin_limit < 1) P.spin_limit = 1;
-    const char *gm = getenv("RT_GATE_MASK");
-    P.gate_mask = gm ? atoi(gm) : 0;   // measured: polling the data itself beats gate + bulk (34.3 vs 39.8 us per position)
     P.available = true;
     return RT_OK;
 }
@@ -948,11 +891,9 @@ rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weigh
     A.VT = S.VT; A.vt_stride = S.vt_stride;
     A.pm = S.pm; A.pl = S.pl; A.po = S.po; A.levels = S.levels; A.slots = S.slots;
     A.a_ll = (ll_t *)P.a_ll; A.h_ll = (ll_t *)P.h_ll; A.u_ll = (ll_t *)P.u_ll; A.z_ll = (ll_t *)P.z_ll;
-    A.kv_ll = (ll_t *)P.kv_ll; A.hss_ll = (ll_t *)P.hss_ll; A.zss_ll = (ll_t *)P.zss_ll;
-    A.done_m = (ll_t *)P.done_m; A.done_1 = (ll_t *)P.done_1; A.zp_ll = (ll_t *)P.zp_ll;
+    A.kv_ll = (ll_t *)P.kv_ll; A.zss_ll = (ll_t *)P.zss_ll; A.zp_ll = (ll_t *)P.zp_ll;
     A.R_2 = D.d / 64;
     A.bar = P.bar; A.trace = P.trace; A.spin_limit = P.spin_limit;
-    A.gate_mask = P.gate_mask;
     P.nonce = (P.nonce % 4095u) + 1u;          // 1..4095; fresh buffers hold tag 0
     A.tag_base = P.nonce << 20;
 
