@@ -58,6 +58,7 @@ def main():
     ap.add_argument("--engine", default="auto", choices=["auto", "stepwise", "graph", "persistent"])
     ap.add_argument("--p-min", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the rt_decode_step measurement")
     ap.add_argument("--cpu-sample-positions", type=int, default=1024)
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy, the reference the rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -173,6 +174,29 @@ def main():
                 "achieved": tot_fl / tot_us, "frac": tot_fl / tot_us / MFMA_BF16_PEAK_TFLOPS,
                 "note": "stand-alone launches of the top three levels (87.5 % of the attention FLOPs), FLOP-weighted; "
                         "back-to-back launches, launch overhead included", "levels": levels}
+
+    # One decoding step (rt_decode_step) over the cache the call above left: position t = N - 1 is evaluated again
+    # from rows 0 .. N-2 (row N-1 is rewritten with the same values).  Bandwidth-bound in principle: the step has to
+    # read the cache (2 t B d E bytes) and the layer's weights (12 d^2 E) once.
+    if not args.no_decode:
+        t_dec = wl.N - 1
+        x_t = xd[:, t_dec].contiguous()
+        y_t = torch.empty_like(x_t)
+        for _ in range(3):
+            ctx.rt_decode_step(dl.struct, x_t, t_dec, y_t, K, V)
+        reps = 50
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(stream)
+        for _ in range(reps):
+            ctx.rt_decode_step(dl.struct, x_t, t_dec, y_t, K, V)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        us = e0.elapsed_time(e1) * 1e3 / reps
+        dec_bytes = 2.0 * t_dec * wl.B * wl.d * E + 12.0 * wl.d * wl.d * E
+        out["decode_step"] = {"t": t_dec, "us_per_step": us, "tokens_per_s": wl.B / (us * 1e-6), "bound": "hbm",
+                              "algorithmic_bytes": dec_bytes, "achieved": dec_bytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
+                              "unit": "GB/s", "frac": dec_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                              "note": "eight launches per step on one stream"}
 
     if not args.no_cpu_baseline:
         from oracle import rt_oracle

@@ -177,7 +177,7 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
     const size_t opm = carve(np * 4), opl = carve(np * 4), opo = carve(np * kHeadDim * 4);
     const size_t orinv = carve(Bm * Nm * 4);
     const size_t ocat = carve(Bm * d * 4), oh = carve(Bm * d * 4), ou = carve(Bm * F * 4), oz = carve(Bm * d * 4);
-    const size_t okv = carve(Bm * 2 * d * 4);
+    const size_t okv = carve(Bm * 2 * d * 4), oqkv = carve(Bm * 3 * d * 4);
     c->slab_bytes = off;
     hipError_t e = hipMalloc(&c->slab, c->slab_bytes);
     if (e != hipSuccess) {
@@ -195,6 +195,7 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
     S.rinv = (float *)(p + orinv);
     S.attn_cat = (float *)(p + ocat); S.h = (float *)(p + oh); S.u = (float *)(p + ou); S.z = (float *)(p + oz);
     S.kv_raw = (float *)(p + okv);
+    S.qkv_raw = (float *)(p + oqkv);
 
     rt_status ps = persistent_create(c->persist, c->cfg, D);
     if (ps != RT_OK && (cfg->flags & RT_FLAG_ENGINE_PERSISTENT)) {
@@ -389,7 +390,7 @@ static rt_status decode_impl(rt_ctx *c, const LayerDims &D, const rt_layer_weigh
 {
     const Weights W = to_weights(w);
     hipStream_t st = c->stream;
-    RT_TRY(Launch<T>::prepass(D, W, c->S, x_t, D.B, 1, false, st), "prepass");
+    RT_TRY(Launch<T>::prepass_one(D, W, c->S, x_t, (size_t)D.d, st), "prepass_one");
     const int chunk = 256;
     const int nsplit = (t + chunk - 1) / chunk;
     if (nsplit > 0) RT_TRY(Launch<T>::decode_split(D, c->S, K, V, t, chunk, nsplit, st), "decode_split");

@@ -131,6 +131,7 @@ struct Scratch {
     float *u;            // [B][F]
     float *z;            // [B][d]
     float *kv_raw;       // [B][2d]
+    float *qkv_raw;      // [B][3d] raw q, k_tmp, v_tmp of a decoding step
 };
 
 __host__ __device__ __forceinline__ size_t partial_index(int level_rel, int slot, int slots, int BH, int bh)
@@ -145,6 +146,9 @@ template <typename T> struct Launch {
     // x [Bc][Nc][d] -> Q, Kt, Vt rows (n*Bc + b)
     static hipError_t prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
                               bool mfma, hipStream_t st);
+    // one position's q, k_tmp, v_tmp (decoding step): rows b of Q, Kt, Vt
+    static hipError_t prepass_one(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride,
+                                  hipStream_t st);
     static hipError_t merge(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int q_row,
                             int n_decode_splits, hipStream_t st);
     static hipError_t gemv_wo(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride_b,

@@ -112,98 +112,103 @@ __global__ __launch_bounds__(64) void merge_kernel(const T *__restrict__ Q, cons
 
 // =============================================================================================
 // Small-M matrix products of the base case:  out[b][o] = epilogue( sum_k W[o][k] * in[b][k] ),
-// b < Bn <= 8.  256 threads = 4 wavefronts, each wavefront owns 4 output rows; the (optionally
-// RMS-normalised) input rows are staged in LDS in chunks of 1024 columns.
+// b < Bn <= 8.  Bandwidth is the bound (every weight is used for at most 8 multiply-adds), so the
+// work is cut for memory parallelism: a workgroup of 4 wavefronts owns 4 output rows, each
+// wavefront takes every fourth 512-column slice of the contraction (16-byte weight loads, 4 rows in
+// flight), the partial sums meet in LDS in a fixed order (runs are bit-reproducible).  A workgroup
+// streams 4 rows of W once and the B input rows once (those come out of L2).  With do_norm the
+// input is RMS-normalised: the sum of squares is accumulated from the same values on the way and
+// the scale 1/rms is applied to the finished sums (the product is linear in its input); the gain
+// multiplies the input elements as they are read.
+// Rows o < n_first come from Wa, n_first <= o < 2 n_first from Wb, the rest from Wc.
 // =============================================================================================
 enum Epi { EPI_WO = 0, EPI_W1 = 1, EPI_W2 = 2, EPI_KV = 3 };
 
-constexpr int kGemvRows = 4;      // output rows per wavefront
-constexpr int kGemvChunk = 1024;  // staged input columns
+constexpr int kGemvRows = 4;      // output rows per workgroup
 
-template <typename T, int EPI>
-__global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, const T *__restrict__ Wb, int n_first,
-                                                   int n_out, int n_in, const float *__restrict__ in, int Bn,
+__device__ __forceinline__ void load8_in(const float *p, float *o) { load8(p, o); }
+__device__ __forceinline__ void load8_in(const bf16_t *p, float *o) { load8(p, o); }
+
+template <typename T, typename IN_T, int EPI>
+__global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, const T *__restrict__ Wb,
+                                                   const T *__restrict__ Wc, int n_first, int n_out, int n_in,
+                                                   const IN_T *__restrict__ in, size_t in_stride, int Bn,
                                                    const T *__restrict__ gain, float eps, int do_norm, float alpha,
                                                    const T *__restrict__ res_T, size_t res_stride,
                                                    const float *__restrict__ res_f, float *__restrict__ out_f,
                                                    T *__restrict__ out_T, size_t out_T_stride)
 {
-    __shared__ float xs[kBatchTile][kGemvChunk];
-    __shared__ float red[kBatchTile][4];
-    __shared__ float rinv_s[kBatchTile];
+    __shared__ float part[4][kGemvRows * kBatchTile + kBatchTile];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-
-    if (do_norm) {
-        for (int b = 0; b < kBatchTile; ++b) {
-            float ss = 0.f;
-            if (b < Bn)
-                for (int k = tid; k < n_in; k += 256) { const float v = in[(size_t)b * n_in + k]; ss = fmaf(v, v, ss); }
-            ss = wave_sum(ss);
-            if (lane == 0) red[b][wave] = ss;
-        }
-        __syncthreads();
-        if (tid < kBatchTile) rinv_s[tid] = rsqrtf((red[tid][0] + red[tid][1] + red[tid][2] + red[tid][3]) / (float)n_in + eps);
-        __syncthreads();
-    }
-
-    const int o0 = (blockIdx.x * 4 + wave) * kGemvRows;
+    const int o0 = blockIdx.x * kGemvRows;
     const T *wrow[kGemvRows];
 #pragma unroll
     for (int r = 0; r < kGemvRows; ++r) {
         const int o = min(o0 + r, n_out - 1);
-        wrow[r] = (o < n_first) ? Wa + (size_t)o * n_in : Wb + (size_t)(o - n_first) * n_in;
+        const int which = o / n_first;
+        wrow[r] = (which == 0 ? Wa : (which == 1 ? Wb : Wc)) + (size_t)(o - which * n_first) * n_in;
     }
-    float acc[kGemvRows][kBatchTile];
+    float acc[kGemvRows][kBatchTile], ssq[kBatchTile];
 #pragma unroll
-    for (int r = 0; r < kGemvRows; ++r)
+    for (int b = 0; b < kBatchTile; ++b) {
+        ssq[b] = 0.f;
 #pragma unroll
-        for (int b = 0; b < kBatchTile; ++b) acc[r][b] = 0.f;
-
-    for (int c0 = 0; c0 < n_in; c0 += kGemvChunk) {
-        const int cn = min(kGemvChunk, n_in - c0);
-        __syncthreads();
-        for (int idx = tid; idx < kBatchTile * cn; idx += 256) {
-            const int b = idx / cn, k = idx - b * cn;
-            float v = 0.f;
+        for (int r = 0; r < kGemvRows; ++r) acc[r][b] = 0.f;
+    }
+    for (int k = wave * 512 + lane * 8; k < n_in; k += 2048) {
+        float w[kGemvRows][8];
+#pragma unroll
+        for (int r = 0; r < kGemvRows; ++r) load8(wrow[r] + k, w[r]);
+        float g8[8];
+        const bool use_g = do_norm && gain != nullptr;
+        if (use_g) load8(gain + k, g8);
+#pragma unroll
+        for (int b = 0; b < kBatchTile; ++b) {
             if (b < Bn) {
-                v = in[(size_t)b * n_in + c0 + k];
-                if (do_norm) v *= rinv_s[b] * (gain ? to_f32(gain[c0 + k]) : 1.f);
-            }
-            xs[b][k] = v;
-        }
-        __syncthreads();
-        for (int k = lane * 8; k < cn; k += 512) {
-            float w[kGemvRows][8];
+                float x8[8];
+                load8_in(in + (size_t)b * in_stride + k, x8);
+                if (do_norm) {
 #pragma unroll
-            for (int r = 0; r < kGemvRows; ++r) load8(wrow[r] + c0 + k, w[r]);
+                    for (int e = 0; e < 8; ++e) ssq[b] = fmaf(x8[e], x8[e], ssq[b]);
+                    if (use_g) {
 #pragma unroll
-            for (int b = 0; b < kBatchTile; ++b) {
-                const float4 x0 = *reinterpret_cast<const float4 *>(&xs[b][k]);
-                const float4 x1 = *reinterpret_cast<const float4 *>(&xs[b][k + 4]);
+                        for (int e = 0; e < 8; ++e) x8[e] *= g8[e];
+                    }
+                }
 #pragma unroll
                 for (int r = 0; r < kGemvRows; ++r) {
                     float a = acc[r][b];
-                    a = fmaf(w[r][0], x0.x, a); a = fmaf(w[r][1], x0.y, a); a = fmaf(w[r][2], x0.z, a); a = fmaf(w[r][3], x0.w, a);
-                    a = fmaf(w[r][4], x1.x, a); a = fmaf(w[r][5], x1.y, a); a = fmaf(w[r][6], x1.z, a); a = fmaf(w[r][7], x1.w, a);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) a = fmaf(w[r][e], x8[e], a);
                     acc[r][b] = a;
                 }
             }
         }
     }
 #pragma unroll
-    for (int r = 0; r < kGemvRows; ++r)
+    for (int b = 0; b < kBatchTile; ++b) {
+        ssq[b] = wave_sum(ssq[b]);
 #pragma unroll
-        for (int b = 0; b < kBatchTile; ++b) acc[r][b] = wave_sum(acc[r][b]);
-
-    // lanes 0..31 each finish one (row, batch) pair
-    if (lane < kGemvRows * kBatchTile) {
-        const int r = lane / kBatchTile, b = lane % kBatchTile;
-        float v = 0.f;
+        for (int r = 0; r < kGemvRows; ++r) acc[r][b] = wave_sum(acc[r][b]);
+    }
+    if (lane == 0) {
 #pragma unroll
-        for (int rr = 0; rr < kGemvRows; ++rr)
+        for (int b = 0; b < kBatchTile; ++b) {
+            part[wave][kGemvRows * kBatchTile + b] = ssq[b];
 #pragma unroll
-            for (int bb = 0; bb < kBatchTile; ++bb)
-                if (rr == r && bb == b) v = acc[rr][bb];
+            for (int r = 0; r < kGemvRows; ++r) part[wave][r * kBatchTile + b] = acc[r][b];
+        }
+    }
+    __syncthreads();
+    // threads 0..31 each finish one (row, batch) pair
+    if (tid < kGemvRows * kBatchTile) {
+        const int r = tid / kBatchTile, b = tid % kBatchTile;
+        float v = (part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid]);
+        if (do_norm) {
+            const int si = kGemvRows * kBatchTile + b;
+            const float tot = (part[0][si] + part[1][si]) + (part[2][si] + part[3][si]);
+            v *= rsqrtf(tot / (float)n_in + eps);
+        }
         const int o = o0 + r;
         if (o < n_out && b < Bn) {
             if (EPI == EPI_WO) {
@@ -219,6 +224,28 @@ __global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, con
             }
         }
     }
+}
+
+// Decoding step, after the raw [q | k_tmp | v_tmp] product of one position: qkRMS of q and k_tmp per head and the
+// rows of Q, Kt, Vt (row index b: one position).  grid B*H, block 64.
+template <typename T>
+__global__ __launch_bounds__(64) void finalize_qkv_kernel(const float *__restrict__ raw, const T *__restrict__ g_q,
+                                                          const T *__restrict__ g_k, T *__restrict__ Q, T *__restrict__ Kt,
+                                                          T *__restrict__ Vt, int H, int d, float eps, int norm_free)
+{
+    const int lane = threadIdx.x, bh = blockIdx.x;
+    const int b = bh / H, h = bh % H;
+    const float *r = raw + (size_t)b * 3 * d + h * kHeadDim + lane;
+    float q = r[0], k = r[d];
+    const float v = r[2 * d];
+    if (!norm_free) {
+        q = q * rsqrtf(wave_sum(q * q) / (float)kHeadDim + eps) * (g_q ? to_f32(g_q[h * kHeadDim + lane]) : 1.f);
+        k = k * rsqrtf(wave_sum(k * k) / (float)kHeadDim + eps) * (g_k ? to_f32(g_k[h * kHeadDim + lane]) : 1.f);
+    }
+    const size_t off = (size_t)b * d + h * kHeadDim + lane;
+    Q[off] = from_f32<T>(q);
+    Kt[off] = from_f32<T>(k);
+    Vt[off] = from_f32<T>(v);
 }
 
 // =============================================================================================
@@ -368,16 +395,16 @@ hipError_t Launch<T>::merge(const LayerDims &D, const Scratch &S, const void *K,
 }
 
 // Batch rows beyond one tile of 8 are handled by further launches of the same kernel.
-template <typename T, int EPI>
-static hipError_t gemv_launch(const T *Wa, const T *Wb, int n_first, int n_out, int n_in, const float *in, int B,
-                              const T *gain, float eps, int do_norm, float alpha, const T *res_T, size_t res_stride,
-                              const float *res_f, float *out_f, T *out_T, size_t out_T_stride, hipStream_t st)
+template <typename T, typename IN_T, int EPI>
+static hipError_t gemv_launch(const T *Wa, const T *Wb, const T *Wc, int n_first, int n_out, int n_in, const IN_T *in,
+                              size_t in_stride, int B, const T *gain, float eps, int do_norm, float alpha, const T *res_T,
+                              size_t res_stride, const float *res_f, float *out_f, T *out_T, size_t out_T_stride,
+                              hipStream_t st)
 {
-    const int rows = 4 * kGemvRows;
     for (int b0 = 0; b0 < B; b0 += kBatchTile) {
         const int Bn = (B - b0 < kBatchTile) ? B - b0 : kBatchTile;
-        hipLaunchKernelGGL((gemv_kernel<T, EPI>), dim3((n_out + rows - 1) / rows), dim3(256), 0, st, Wa, Wb, n_first, n_out,
-                           n_in, in + (size_t)b0 * n_in, Bn, gain, eps, do_norm, alpha,
+        hipLaunchKernelGGL((gemv_kernel<T, IN_T, EPI>), dim3((n_out + kGemvRows - 1) / kGemvRows), dim3(256), 0, st, Wa, Wb, Wc,
+                           n_first, n_out, n_in, in + (size_t)b0 * in_stride, in_stride, Bn, gain, eps, do_norm, alpha,
                            res_T ? res_T + (size_t)b0 * res_stride : res_T, res_stride,
                            res_f ? res_f + (size_t)b0 * n_out : res_f, out_f + (size_t)b0 * n_out,
                            out_T ? out_T + (size_t)b0 * out_T_stride : out_T, out_T_stride);
@@ -385,18 +412,34 @@ static hipError_t gemv_launch(const T *Wa, const T *Wb, int n_first, int n_out, 
     return hipGetLastError();
 }
 
+// One position's [q | k_tmp | v_tmp] (a decoding step): the three products as one small-M launch, then the per-head
+// normalisation.  x_t rows are B apart by x_stride elements.
+template <typename T>
+hipError_t Launch<T>::prepass_one(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride,
+                                  hipStream_t st)
+{
+    hipError_t e = gemv_launch<T, T, EPI_KV>((const T *)W.Wq, (const T *)W.Wk, (const T *)W.Wv, D.d, 3 * D.d, D.d,
+                                             (const T *)x_t, x_stride, D.B, (const T *)W.g_attn, D.eps, D.norm_free ? 0 : 1,
+                                             D.alpha, (const T *)nullptr, (size_t)0, (const float *)nullptr, S.qkv_raw,
+                                             (T *)nullptr, (size_t)0, st);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(finalize_qkv_kernel<T>, dim3(D.B * D.H), dim3(64), 0, st, S.qkv_raw, (const T *)W.g_q, (const T *)W.g_k,
+                       (T *)S.Q, (T *)S.Kt, (T *)S.Vt, D.H, D.d, D.eps, D.norm_free);
+    return hipGetLastError();
+}
+
 template <typename T>
 hipError_t Launch<T>::gemv_wo(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride_b,
                               hipStream_t st)
 {
-    return gemv_launch<T, EPI_WO>((const T *)W.Wo, (const T *)W.Wo, D.d, D.d, D.d, S.attn_cat, D.B, (const T *)nullptr,
+    return gemv_launch<T, float, EPI_WO>((const T *)W.Wo, (const T *)W.Wo, (const T *)W.Wo, D.d, D.d, D.d, S.attn_cat, (size_t)D.d, D.B, (const T *)nullptr,
                                   D.eps, 0, D.alpha, (const T *)x_t, x_stride_b, (const float *)nullptr, S.h, (T *)nullptr,
                                   (size_t)0, st);
 }
 
 template <typename T> hipError_t Launch<T>::gemv_w1(const LayerDims &D, const Weights &W, const Scratch &S, hipStream_t st)
 {
-    return gemv_launch<T, EPI_W1>((const T *)W.W1, (const T *)W.W1, D.F, D.F, D.d, S.h, D.B, (const T *)W.g_mlp, D.eps,
+    return gemv_launch<T, float, EPI_W1>((const T *)W.W1, (const T *)W.W1, (const T *)W.W1, D.F, D.F, D.d, S.h, (size_t)D.d, D.B, (const T *)W.g_mlp, D.eps,
                                   D.norm_free ? 0 : 1, D.alpha, (const T *)nullptr, (size_t)0, (const float *)nullptr, S.u,
                                   (T *)nullptr, (size_t)0, st);
 }
@@ -405,14 +448,14 @@ template <typename T>
 hipError_t Launch<T>::gemv_w2(const LayerDims &D, const Weights &W, const Scratch &S, void *y_t, size_t y_stride_b,
                               hipStream_t st)
 {
-    return gemv_launch<T, EPI_W2>((const T *)W.W2, (const T *)W.W2, D.d, D.d, D.F, S.u, D.B, (const T *)nullptr, D.eps, 0,
+    return gemv_launch<T, float, EPI_W2>((const T *)W.W2, (const T *)W.W2, (const T *)W.W2, D.d, D.d, D.F, S.u, (size_t)D.F, D.B, (const T *)nullptr, D.eps, 0,
                                   D.alpha, (const T *)nullptr, (size_t)0, S.h, S.z, (T *)y_t, y_stride_b, st);
 }
 
 template <typename T> hipError_t Launch<T>::gemv_kv(const LayerDims &D, const Weights &W, const Scratch &S, hipStream_t st)
 {
     const T *g = (const T *)(W.g_kv ? W.g_kv : W.g_attn);
-    return gemv_launch<T, EPI_KV>((const T *)W.Wk, (const T *)W.Wv, D.d, 2 * D.d, D.d, S.z, D.B, g, D.eps,
+    return gemv_launch<T, float, EPI_KV>((const T *)W.Wk, (const T *)W.Wv, (const T *)W.Wv, D.d, 2 * D.d, D.d, S.z, (size_t)D.d, D.B, g, D.eps,
                                   D.norm_free ? 0 : 1, D.alpha, (const T *)nullptr, (size_t)0, (const float *)nullptr,
                                   S.kv_raw, (T *)nullptr, (size_t)0, st);
 }
