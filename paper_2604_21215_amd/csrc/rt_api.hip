@@ -391,7 +391,7 @@ static rt_status decode_impl(rt_ctx *c, const LayerDims &D, const rt_layer_weigh
     const Weights W = to_weights(w);
     hipStream_t st = c->stream;
     RT_TRY(Launch<T>::prepass_one(D, W, c->S, x_t, (size_t)D.d, st), "prepass_one");
-    const int chunk = 256;
+    const int chunk = 64;   // keys per wavefront: t / 64 wavefronts per (b, h) keep the whole chip reading the cache
     const int nsplit = (t + chunk - 1) / chunk;
     if (nsplit > 0) RT_TRY(Launch<T>::decode_split(D, c->S, K, V, t, chunk, nsplit, st), "decode_split");
     return enqueue_position<T>(c, D, W, x_t, (size_t)D.d, y_t, (size_t)D.d, K, V, t, 0, nsplit, false);
@@ -407,7 +407,7 @@ extern "C" rt_status rt_decode_step(rt_ctx *c, const rt_layer_weights *w, const 
     if (!x_t || !y_t || !K || !V) return fail(c, RT_ERR_INVALID_ARG, "null tensor pointer%s");
     if (B < 1 || B > c->cfg.max_batch) return fail(c, RT_ERR_INVALID_ARG, "B out of range [1, max_batch]%s");
     if (t < 0 || t >= kv_cap) return fail(c, RT_ERR_INVALID_ARG, "t out of range [0, kv_cap)%s");
-    if ((t + 255) / 256 > c->S.slots) return fail(c, RT_ERR_INVALID_ARG, "t too large for this context's max_seq%s");
+    if ((t + 63) / 64 > c->S.slots) return fail(c, RT_ERR_INVALID_ARG, "t too large for this context's max_seq%s");
     const size_t E = c->cfg.dtype == RT_BF16 ? 2 : 4;
     const size_t xb = (size_t)B * c->cfg.d_model * E;
     if (ranges_overlap(x_t, xb, y_t, xb)) return fail(c, RT_ERR_INVALID_ARG, "x_t and y_t overlap%s");

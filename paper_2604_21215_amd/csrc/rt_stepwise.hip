@@ -78,15 +78,31 @@ __global__ __launch_bounds__(64) void merge_kernel(const T *__restrict__ Q, cons
     float l = 1.f;
     float o = to_f32(Vt[qoff]);
     if (n_splits >= 0) {
-        for (int s = 0; s < n_splits; ++s) {
-            const size_t idx = partial_index(0, s, slots, BH, bh);
-            const float pmv = pm[idx], plv = pl[idx], pov = po[idx * kHeadDim + lane];
-            const float m_new = fmaxf(m, pmv);
-            const float e1 = expf(m - m_new), e2 = expf(pmv - m_new);
-            l = l * e1 + plv * e2;
-            o = o * e1 + pov * e2;
-            m = m_new;
+        // two passes, so that no load waits for an exponential: the overall maximum first (lanes read the splits'
+        // maxima side by side), then the weighted sums in split order
+        float mx = m;
+        for (int s0 = 0; s0 < n_splits; s0 += 64) {
+            const int sidx = s0 + lane;
+            mx = fmaxf(mx, sidx < n_splits ? pm[partial_index(0, sidx, slots, BH, bh)] : -INFINITY);
         }
+        mx = wave_max(mx);
+        const float e0 = expf(m - mx);
+        l = e0;
+        o = o * e0;
+        for (int s0 = 0; s0 < n_splits; s0 += 64) {
+            const int sidx = s0 + lane, cnt = min(64, n_splits - s0);
+            float wgt = 0.f, lw = 0.f;
+            if (sidx < n_splits) {
+                const size_t idx = partial_index(0, sidx, slots, BH, bh);
+                wgt = expf(pm[idx] - mx);
+                lw = wgt * pl[idx];
+            }
+            for (int j = 0; j < cnt; ++j) {
+                l += lane_bcast(lw, j);
+                o = fmaf(lane_bcast(wgt, j), po[partial_index(0, s0 + j, slots, BH, bh) * kHeadDim + lane], o);
+            }
+        }
+        m = mx;
     } else {
         for (int lr = 0; lr < levels; ++lr) {
             const int lv = lr + log2_pmin;
@@ -113,10 +129,11 @@ __global__ __launch_bounds__(64) void merge_kernel(const T *__restrict__ Q, cons
 // =============================================================================================
 // Small-M matrix products of the base case:  out[b][o] = epilogue( sum_k W[o][k] * in[b][k] ),
 // b < Bn <= 8.  Bandwidth is the bound (every weight is used for at most 8 multiply-adds), so the
-// work is cut for memory parallelism: a workgroup of 4 wavefronts owns 4 output rows, each
-// wavefront takes every fourth 512-column slice of the contraction (16-byte weight loads, 4 rows in
-// flight), the partial sums meet in LDS in a fixed order (runs are bit-reproducible).  A workgroup
-// streams 4 rows of W once and the B input rows once (those come out of L2).  With do_norm the
+// work is cut for memory parallelism: groups of KS wavefronts own 4 output rows each (a workgroup
+// of 4 wavefronts: 16 / KS rows), a wavefront takes every KS-th 512-column slice of the contraction
+// (16-byte weight loads, 4 rows in flight), the partial sums meet in LDS in a fixed order (runs are
+// bit-reproducible).  KS = 2 for contractions up to 1024 columns (every wavefront then has exactly
+// one slice), else 4.  The B input rows come out of L2.  With do_norm the
 // input is RMS-normalised: the sum of squares is accumulated from the same values on the way and
 // the scale 1/rms is applied to the finished sums (the product is linear in its input); the gain
 // multiplies the input elements as they are read.
@@ -129,7 +146,7 @@ constexpr int kGemvRows = 4;      // output rows per workgroup
 __device__ __forceinline__ void load8_in(const float *p, float *o) { load8(p, o); }
 __device__ __forceinline__ void load8_in(const bf16_t *p, float *o) { load8(p, o); }
 
-template <typename T, typename IN_T, int EPI>
+template <typename T, typename IN_T, int EPI, int KS>
 __global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, const T *__restrict__ Wb,
                                                    const T *__restrict__ Wc, int n_first, int n_out, int n_in,
                                                    const IN_T *__restrict__ in, size_t in_stride, int Bn,
@@ -140,7 +157,9 @@ __global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, con
 {
     __shared__ float part[4][kGemvRows * kBatchTile + kBatchTile];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int o0 = blockIdx.x * kGemvRows;
+    constexpr int kGroups = 4 / KS;   // row groups per workgroup
+    const int rg = wave / KS, kw = wave % KS;
+    const int o0 = (blockIdx.x * kGroups + rg) * kGemvRows;
     const T *wrow[kGemvRows];
 #pragma unroll
     for (int r = 0; r < kGemvRows; ++r) {
@@ -155,7 +174,7 @@ __global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, con
 #pragma unroll
         for (int r = 0; r < kGemvRows; ++r) acc[r][b] = 0.f;
     }
-    for (int k = wave * 512 + lane * 8; k < n_in; k += 2048) {
+    for (int k = kw * 512 + lane * 8; k < n_in; k += 512 * KS) {
         float w[kGemvRows][8];
 #pragma unroll
         for (int r = 0; r < kGemvRows; ++r) load8(wrow[r] + k, w[r]);
@@ -200,16 +219,16 @@ __global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, con
         }
     }
     __syncthreads();
-    // threads 0..31 each finish one (row, batch) pair
-    if (tid < kGemvRows * kBatchTile) {
-        const int r = tid / kBatchTile, b = tid % kBatchTile;
-        float v = (part[0][tid] + part[1][tid]) + (part[2][tid] + part[3][tid]);
-        if (do_norm) {
-            const int si = kGemvRows * kBatchTile + b;
-            const float tot = (part[0][si] + part[1][si]) + (part[2][si] + part[3][si]);
-            v *= rsqrtf(tot / (float)n_in + eps);
-        }
-        const int o = o0 + r;
+    // 32 threads per row group each finish one (row, batch) pair
+    if (tid < kGroups * kGemvRows * kBatchTile) {
+        const int grp = tid / (kGemvRows * kBatchTile), pi = tid % (kGemvRows * kBatchTile);
+        const int r = pi / kBatchTile, b = pi % kBatchTile;
+        const int si = kGemvRows * kBatchTile + b;
+        float v = 0.f, tot = 0.f;
+#pragma unroll
+        for (int j = 0; j < KS; ++j) { v += part[grp * KS + j][pi]; tot += part[grp * KS + j][si]; }
+        if (do_norm) v *= rsqrtf(tot / (float)n_in + eps);
+        const int o = (blockIdx.x * kGroups + grp) * kGemvRows + r;
         if (o < n_out && b < Bn) {
             if (EPI == EPI_WO) {
                 out_f[(size_t)b * n_out + o] = to_f32(res_T[(size_t)b * res_stride + o]) + alpha * v;
@@ -403,11 +422,18 @@ static hipError_t gemv_launch(const T *Wa, const T *Wb, const T *Wc, int n_first
 {
     for (int b0 = 0; b0 < B; b0 += kBatchTile) {
         const int Bn = (B - b0 < kBatchTile) ? B - b0 : kBatchTile;
-        hipLaunchKernelGGL((gemv_kernel<T, IN_T, EPI>), dim3((n_out + kGemvRows - 1) / kGemvRows), dim3(256), 0, st, Wa, Wb, Wc,
-                           n_first, n_out, n_in, in + (size_t)b0 * in_stride, in_stride, Bn, gain, eps, do_norm, alpha,
-                           res_T ? res_T + (size_t)b0 * res_stride : res_T, res_stride,
-                           res_f ? res_f + (size_t)b0 * n_out : res_f, out_f + (size_t)b0 * n_out,
-                           out_T ? out_T + (size_t)b0 * out_T_stride : out_T, out_T_stride);
+        if (n_in <= 1024)
+            hipLaunchKernelGGL((gemv_kernel<T, IN_T, EPI, 2>), dim3((n_out + 2 * kGemvRows - 1) / (2 * kGemvRows)), dim3(256), 0, st,
+                               Wa, Wb, Wc, n_first, n_out, n_in, in + (size_t)b0 * in_stride, in_stride, Bn, gain, eps, do_norm,
+                               alpha, res_T ? res_T + (size_t)b0 * res_stride : res_T, res_stride,
+                               res_f ? res_f + (size_t)b0 * n_out : res_f, out_f + (size_t)b0 * n_out,
+                               out_T ? out_T + (size_t)b0 * out_T_stride : out_T, out_T_stride);
+        else
+            hipLaunchKernelGGL((gemv_kernel<T, IN_T, EPI, 4>), dim3((n_out + kGemvRows - 1) / kGemvRows), dim3(256), 0, st, Wa, Wb,
+                               Wc, n_first, n_out, n_in, in + (size_t)b0 * in_stride, in_stride, Bn, gain, eps, do_norm, alpha,
+                               res_T ? res_T + (size_t)b0 * res_stride : res_T, res_stride,
+                               res_f ? res_f + (size_t)b0 * n_out : res_f, out_f + (size_t)b0 * n_out,
+                               out_T ? out_T + (size_t)b0 * out_T_stride : out_T, out_T_stride);
     }
     return hipGetLastError();
 }
