@@ -65,6 +65,7 @@ constexpr int kPW = 8;                 // wavefronts per workgroup
 constexpr int kPThreads = kPW * 64;
 constexpr int kBMax = 16;              // batch rows (MFMA N dimension)
 constexpr int kRMax = 16;              // output rows per workgroup and matrix (MFMA M dimension)
+constexpr int kGlobalP = 256;           // cross-block events of at least this many keys are spread over all workgroups
 constexpr int kMaxLevels = 16;         // stored-partial levels a query can take (p_min 32 .. sequence 2^20)
 
 typedef unsigned long long ll_t;       // exchange word: [tag:32 | payload:32]
@@ -604,14 +605,39 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         // ================================================================ cross-block items of the block ending at key t-1
         if (t >= A.p_min && t < A.N - 1 && (t & -t) >= A.p_min) {
             const int P = t & -t;
-            if (grid_barrier(A, (++nbar) * (unsigned long long)G, flag_s)) { fail = 1; }
-            RT_ABORT_IF(fail);
-            RT_STAMP(14);
             const int nq = min(P, A.N - 1 - t);
             const int qblocks = (nq + 31) / 32;
             const int items = BH * qblocks;
             int level = A.log2_pmin;
             while ((1 << level) < P) ++level;
+            if (P < kGlobalP) {
+                // Small blocks stay inside the workgroup that owns the (b, h): all their keys and values were stored by
+                // its merge wavefront, the partial states will be read by its own helper wavefront, so no other
+                // workgroup is involved and no grid barrier is needed (a grid barrier with its fences and the cold
+                // misses behind it costs about 30 us, the 128-key tile a few).  The other workgroups already have a_t
+                // and go on with phase O.
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __syncthreads();
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                for (int w = 0; w < A.upw; ++w) {
+                    const int bh = wg + G * w;   // workgroup-uniform
+                    if (bh >= BH) break;
+                    if (P >= kKC) {   // nq <= P < kGlobalP <= 32 kPW: one pass covers all queries
+                        cross_tile_item(A, bh, t, P, wave * 32, nq, level, reinterpret_cast<unsigned char *>(act_s));
+                        __syncthreads();
+                    } else if (wave * 32 < nq) {
+                        cross_mfma_wave<true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1, t - P, P,
+                                              wave * 32, nq, level, level - A.log2_pmin, A.slots, A.scale);
+                    }
+                }
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __syncthreads();
+                RT_STAMP(14);
+                RT_STAMP(15);
+            } else {
+            if (grid_barrier(A, (++nbar) * (unsigned long long)G, flag_s)) { fail = 1; }
+            RT_ABORT_IF(fail);
+            RT_STAMP(14);
             if (P >= kKC) {
                 // blocks of 64 keys and more: the whole workgroup takes one (b, h) and up to 256 queries at a time,
                 // with the key and value tiles staged in the LDS area that the phases use for staged activations
@@ -632,6 +658,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             RT_STAMP(15);
             if (grid_barrier(A, (++nbar) * (unsigned long long)G, flag_s)) { fail = 1; }
             RT_ABORT_IF(fail);
+            }
         }
         RT_STAMP(2);
 
