@@ -100,6 +100,23 @@ rt_status rt_layer_prefill(rt_ctx *ctx, const rt_layer_weights *w, const void *x
 rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t, void *y_t,
                          void *K, void *V, int32_t kv_cap);
 
+/* Whole-sequence forward of a stack of L layers, layer l + 1 reading layer l's output (Sec. 2: the layers of a
+ * model are stacked; Sec. 2.2: each RT layer has its own persistent key-value memory).  Same results as L
+ * successive rt_layer_prefill calls up to rounding, but the layers run concurrently, layer l working `chunk`
+ * positions behind layer l - 1 (the queries of a layer depend only on its input, Sec. 5, so a layer can start a
+ * chunk as soon as the layer below has finished it).  Inside a chunk the schedule is Appendix C, Algorithm 1;
+ * the keys before the chunk are folded into the chunk's queries by one UpdateTile (Algorithm 2) when the layer
+ * enters the chunk.
+ *   layers [L] host array of weight structs (device pointers inside); x [B, N, d] device, input of layer 0;
+ *   y, K, V: host arrays of L device pointers: y[l] [B, N, d] output of layer l (all L are written: y[l] is layer
+ *   l + 1's input), K[l], V[l] [kv_cap, B, H, head_dim] rows 0..N-1 written.  No two of these tensors may overlap.
+ *   chunk: power of two >= p_min (>= 64 with the MFMA kernels); 0 = 128.
+ * The first call allocates one scratch set per layer (RT_ERR_OOM if that fails); it is kept until rt_destroy and
+ * reused by later calls with the same chunk and at most as many layers (another shape synchronises the stream
+ * and reallocates).  rt_decode_step continues from the caches layer by layer. */
+rt_status rt_stack_prefill(rt_ctx *ctx, const rt_layer_weights *layers, int32_t L, const void *x, int32_t B, int32_t N,
+                           void *const *y, void *const *K, void *const *V, int32_t kv_cap, int32_t chunk);
+
 /* Input of the first layer of a stack (Sec. 2: a sequence of token embeddings enters the first layer):
  *   x[b, n, :] = table[ids[b * ids_stride + first + n], :]   for 0 <= b < B, 0 <= n < N.
  *   table [vocab, d] device, storage dtype; ids device int32; x [B, N, d] device, written.
@@ -131,8 +148,8 @@ uint64_t rt_workspace_bytes(const rt_ctx *ctx);
  * this context completed, non-zero if one expired (the call's outputs are then invalid). */
 int32_t rt_device_wait_expired(rt_ctx *ctx);
 
-/* Name of the engine the last rt_layer_prefill on this context used: "stepwise", "stepwise+graph",
- * "persistent", or "" before the first call. */
+/* Name of the engine the last prefill call on this context used: "stepwise", "stepwise+graph",
+ * "persistent", "wavefront" (rt_stack_prefill), or "" before the first call. */
 const char *rt_engine_name(const rt_ctx *ctx);
 
 /* Diagnostics of the persistent engine, after the stream has been synchronised: when the environment

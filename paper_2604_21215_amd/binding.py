@@ -22,7 +22,8 @@ RT_FLAG_HIP_GRAPH = 0x10
 
 EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_last_error", "rt_status_string",
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
-           "rt_version", "rt_phase_trace", "rt_schedule_events_shifted", "rt_embed_rows", "rt_lm_head", "rt_cross_block_event")
+           "rt_version", "rt_phase_trace", "rt_schedule_events_shifted", "rt_embed_rows", "rt_lm_head", "rt_cross_block_event",
+           "rt_stack_prefill")
 
 
 class rt_config(C.Structure):
@@ -92,6 +93,9 @@ def load():
     L.rt_lm_head.restype = C.c_int
     L.rt_cross_block_event.argtypes = [ctxp, C.c_void_p, C.c_void_p, C.c_int32, C.c_int32, C.c_int32, C.c_int32]
     L.rt_cross_block_event.restype = C.c_int
+    L.rt_stack_prefill.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
+                                   C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32]
+    L.rt_stack_prefill.restype = C.c_int
     _lib = L
     return L
 
@@ -157,6 +161,24 @@ class RTContext:
         B, N, _ = x.shape
         rc = self._L.rt_layer_prefill(self._ctx, C.byref(weights), _ptr(x), B, N, _ptr(y), _ptr(K), _ptr(V), K.shape[0])
         _check(self._L, self._ctx, rc)
+
+    # -- rt_stack_prefill(ctx, layers[L], L, x[B,N,d], B, N, y[L], K[L], V[L], kv_cap, chunk)
+    def rt_stack_prefill(self, weights: list, x, ys: list, Ks: list, Vs: list, chunk: int = 0):
+        B, N, _ = x.shape
+        L = len(weights)
+        warr = (rt_layer_weights * L)(*weights)
+        parr = lambda ts: (C.c_void_p * L)(*[t.data_ptr() for t in ts])
+        rc = self._L.rt_stack_prefill(self._ctx, warr, L, _ptr(x), B, N, parr(ys), parr(Ks), parr(Vs), Ks[0].shape[0],
+                                      int(chunk))
+        _check(self._L, self._ctx, rc)
+
+    def raw_stack_prefill(self, weights: list, x_ptr, B, N, y_ptrs, K_ptrs, V_ptrs, kv_cap, chunk) -> int:
+        """Status code of rt_stack_prefill on raw addresses (error-path tests)."""
+        L = len(weights)
+        warr = (rt_layer_weights * L)(*weights)
+        parr = lambda ps: (C.c_void_p * L)(*ps)
+        return self._L.rt_stack_prefill(self._ctx, warr, L, C.c_void_p(x_ptr), B, N, parr(y_ptrs), parr(K_ptrs),
+                                        parr(V_ptrs), kv_cap, chunk)
 
     # -- rt_decode_step(ctx, w, x_t[B,d], B, t, y_t, K, V, kv_cap)
     def rt_decode_step(self, weights: rt_layer_weights, x_t, t, y_t, K, V):

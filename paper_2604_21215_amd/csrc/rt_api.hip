@@ -8,6 +8,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <vector>
 
 using namespace rt;
 
@@ -24,6 +25,12 @@ struct rt_ctx {
     std::string err;
     std::string engine;
     PersistentState persist;
+    // layer-wavefront engine: one scratch set per layer and the device copy of the layer descriptors
+    void *stack_slab = nullptr;
+    size_t stack_bytes = 0;
+    int stack_L = 0, stack_chunk = 0;
+    std::vector<Scratch> stack_S;
+    WaveLayer *stack_dev = nullptr;
     // cached HIP graph of one stepwise prefill
     hipGraphExec_t graph_exec = nullptr;
     hipStream_t capture_stream = nullptr;  // the legacy default stream cannot be captured
@@ -62,6 +69,41 @@ static int ilog2(int v)
 }
 static bool is_pow2(int v) { return v > 0 && (v & (v - 1)) == 0; }
 static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Lays one scratch set out from `base` (may be null: sizes only) and returns its size in bytes.
+static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_t d, size_t F, size_t H, size_t E, bool mfma,
+                             int levels, int slots)
+{
+    memset(&S, 0, sizeof(S));
+    S.levels = levels;
+    S.slots = slots;
+    S.vt_stride = (int)align_up(Nm, 64);
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
+    const size_t oQ = carve(Nm * Bm * d * E), oKt = carve(Nm * Bm * d * E), oVt = carve(Nm * Bm * d * E);
+    const size_t oVT = mfma ? carve(Bm * H * kHeadDim * (size_t)S.vt_stride * 2) : 0;
+    const size_t oQf = mfma ? carve(Nm * Bm * d * 4) : 0, oKtf = mfma ? carve(Nm * Bm * d * 4) : 0;
+    const size_t oKlo = mfma ? carve(Nm * Bm * d * 2) : 0;
+    const size_t np = (size_t)levels * slots * Bm * H;
+    const size_t opm = carve(np * 4), opl = carve(np * 4), opo = carve(np * kHeadDim * 4);
+    const size_t orinv = carve(Bm * Nm * 4);
+    const size_t ocat = carve(Bm * d * 4), oh = carve(Bm * d * 4), ou = carve(Bm * F * 4), oz = carve(Bm * d * 4);
+    const size_t okv = carve(Bm * 2 * d * 4), oqkv = carve(Bm * 3 * d * 4);
+    if (base) {
+        char *p = base;
+        S.Q = p + oQ; S.Kt = p + oKt; S.Vt = p + oVt;
+        S.VT = mfma ? (bf16_t *)(p + oVT) : nullptr;
+        S.Qf = mfma ? (float *)(p + oQf) : nullptr;
+        S.Ktf = mfma ? (float *)(p + oKtf) : nullptr;
+        S.Klo = mfma ? (bf16_t *)(p + oKlo) : nullptr;
+        S.pm = (float *)(p + opm); S.pl = (float *)(p + opl); S.po = (float *)(p + opo);
+        S.rinv = (float *)(p + orinv);
+        S.attn_cat = (float *)(p + ocat); S.h = (float *)(p + oh); S.u = (float *)(p + ou); S.z = (float *)(p + oz);
+        S.kv_raw = (float *)(p + okv);
+        S.qkv_raw = (float *)(p + oqkv);
+    }
+    return off;
+}
 
 extern "C" {
 
@@ -159,43 +201,19 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
     const size_t E = cfg->dtype == RT_BF16 ? 2 : 4;
     const size_t Bm = cfg->max_batch, Nm = cfg->max_seq, d = cfg->d_model, F = cfg->d_hidden, H = cfg->n_heads;
     Scratch &S = c->S;
-    memset(&S, 0, sizeof(S));
     const int lvmax = Nm >= 2 ? ilog2((int)Nm - 1) : 0;
-    S.levels = lvmax - D.log2_pmin + 1;
-    if (S.levels < 1) S.levels = 1;
-    S.slots = (int)((Nm + 1) / 2);
-    if (S.slots < 64) S.slots = 64;
-    S.vt_stride = (int)align_up(Nm, 64);
-
-    size_t off = 0;
-    auto carve = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes, 256); return o; };
-    const size_t oQ = carve(Nm * Bm * d * E), oKt = carve(Nm * Bm * d * E), oVt = carve(Nm * Bm * d * E);
-    const size_t oVT = mfma ? carve(Bm * H * kHeadDim * (size_t)S.vt_stride * 2) : 0;
-    const size_t oQf = mfma ? carve(Nm * Bm * d * 4) : 0, oKtf = mfma ? carve(Nm * Bm * d * 4) : 0;
-    const size_t oKlo = mfma ? carve(Nm * Bm * d * 2) : 0;
-    const size_t np = (size_t)S.levels * S.slots * Bm * H;
-    const size_t opm = carve(np * 4), opl = carve(np * 4), opo = carve(np * kHeadDim * 4);
-    const size_t orinv = carve(Bm * Nm * 4);
-    const size_t ocat = carve(Bm * d * 4), oh = carve(Bm * d * 4), ou = carve(Bm * F * 4), oz = carve(Bm * d * 4);
-    const size_t okv = carve(Bm * 2 * d * 4), oqkv = carve(Bm * 3 * d * 4);
-    c->slab_bytes = off;
+    int levels = lvmax - D.log2_pmin + 1;
+    if (levels < 1) levels = 1;
+    int slots = (int)((Nm + 1) / 2);
+    if (slots < 64) slots = 64;
+    c->slab_bytes = layout_scratch(S, nullptr, Bm, Nm, d, F, H, E, mfma, levels, slots);
     hipError_t e = hipMalloc(&c->slab, c->slab_bytes);
     if (e != hipSuccess) {
         (void)hipGetLastError();
         delete c;
         return e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP;
     }
-    char *p = (char *)c->slab;
-    S.Q = p + oQ; S.Kt = p + oKt; S.Vt = p + oVt;
-    S.VT = mfma ? (bf16_t *)(p + oVT) : nullptr;
-    S.Qf = mfma ? (float *)(p + oQf) : nullptr;
-    S.Ktf = mfma ? (float *)(p + oKtf) : nullptr;
-    S.Klo = mfma ? (bf16_t *)(p + oKlo) : nullptr;
-    S.pm = (float *)(p + opm); S.pl = (float *)(p + opl); S.po = (float *)(p + opo);
-    S.rinv = (float *)(p + orinv);
-    S.attn_cat = (float *)(p + ocat); S.h = (float *)(p + oh); S.u = (float *)(p + ou); S.z = (float *)(p + oz);
-    S.kv_raw = (float *)(p + okv);
-    S.qkv_raw = (float *)(p + oqkv);
+    layout_scratch(S, (char *)c->slab, Bm, Nm, d, F, H, E, mfma, levels, slots);
 
     rt_status ps = persistent_create(c->persist, c->cfg, D);
     if (ps != RT_OK && (cfg->flags & RT_FLAG_ENGINE_PERSISTENT)) {
@@ -214,13 +232,18 @@ rt_status rt_destroy(rt_ctx *c)
     if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
     if (c->capture_stream) (void)hipStreamDestroy(c->capture_stream);
     persistent_destroy(c->persist);
+    if (c->stack_slab) (void)hipFree(c->stack_slab);
+    if (c->stack_dev) (void)hipFree(c->stack_dev);
     hipError_t e = hipFree(c->slab);
     delete c;
     return e == hipSuccess ? RT_OK : RT_ERR_HIP;
 }
 
 const char *rt_last_error(const rt_ctx *c) { return c ? c->err.c_str() : kNoCtx; }
-uint64_t rt_workspace_bytes(const rt_ctx *c) { return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) : 0; }
+uint64_t rt_workspace_bytes(const rt_ctx *c)
+{
+    return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) + c->stack_bytes : 0;
+}
 const char *rt_engine_name(const rt_ctx *c) { return c ? c->engine.c_str() : ""; }
 
 int32_t rt_device_wait_expired(rt_ctx *c)
@@ -473,5 +496,101 @@ extern "C" rt_status rt_cross_block_event(rt_ctx *c, const void *K, const void *
     if (c->cfg.dtype == RT_BF16) e = Launch<bf16_t>::cross(D, c->S, K, V, t1, P, nq, c->use_mfma, c->stream);
     else e = Launch<float>::cross(D, c->S, K, V, t1, P, nq, false, c->stream);
     if (e != hipSuccess) return fail_hip(c, e, "cross");
+    return RT_OK;
+}
+
+// Scratch of the layer-wavefront engine: one set per layer, sized for max_batch x max_seq; kept until the
+// context is destroyed and reused by later calls with the same chunk and at most as many layers.
+static rt_status stack_workspace(rt_ctx *c, int L, int chunk)
+{
+    if (c->stack_slab && c->stack_L >= L && c->stack_chunk == chunk) return RT_OK;
+    // a different shape: wait for whatever still uses the old sets before they go
+    if (c->stack_slab || c->stack_dev) {
+        if (hipStreamSynchronize(c->stream) != hipSuccess) return fail(c, RT_ERR_HIP, "hipStreamSynchronize failed%s");
+        if (c->stack_slab) (void)hipFree(c->stack_slab);
+        if (c->stack_dev) (void)hipFree(c->stack_dev);
+        c->stack_slab = nullptr; c->stack_dev = nullptr; c->stack_bytes = 0; c->stack_L = 0;
+    }
+    const rt_config &cfg = c->cfg;
+    const size_t E = cfg.dtype == RT_BF16 ? 2 : 4;
+    // partial states: the levels inside a chunk, then one far state per query (slots 0..N-1 of the next level on)
+    int slots = (cfg.max_seq + 1) / 2;
+    if (slots < 64) slots = 64;
+    const int levels = ilog2(chunk) - c->base.log2_pmin + (cfg.max_seq + slots - 1) / slots;
+    Scratch tmp;
+    const size_t one = align_up(layout_scratch(tmp, nullptr, cfg.max_batch, cfg.max_seq, cfg.d_model, cfg.d_hidden, cfg.n_heads, E,
+                                               c->use_mfma, levels, slots), 256);
+    hipError_t e = hipMalloc(&c->stack_slab, one * L);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        c->stack_slab = nullptr;
+        return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "scratch of the layer stack: %s", hipGetErrorString(e));
+    }
+    e = hipMalloc((void **)&c->stack_dev, sizeof(WaveLayer) * L);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        (void)hipFree(c->stack_slab);
+        c->stack_slab = nullptr; c->stack_dev = nullptr;
+        return fail(c, RT_ERR_OOM, "layer descriptors: %s", hipGetErrorString(e));
+    }
+    c->stack_S.resize(L);
+    for (int l = 0; l < L; ++l)
+        layout_scratch(c->stack_S[l], (char *)c->stack_slab + one * l, cfg.max_batch, cfg.max_seq, cfg.d_model, cfg.d_hidden,
+                       cfg.n_heads, E, c->use_mfma, levels, slots);
+    c->stack_bytes = one * L + sizeof(WaveLayer) * L;
+    c->stack_L = L;
+    c->stack_chunk = chunk;
+    return RT_OK;
+}
+
+extern "C" rt_status rt_stack_prefill(rt_ctx *c, const rt_layer_weights *layers, int32_t L, const void *x, int32_t B, int32_t N,
+                                      void *const *y, void *const *K, void *const *V, int32_t kv_cap, int32_t chunk)
+{
+    if (!c) return RT_ERR_INVALID_ARG;
+    if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
+    if (!layers || !x || !y || !K || !V) return fail(c, RT_ERR_INVALID_ARG, "null pointer%s");
+    if (L < 1 || L > 4096) return fail(c, RT_ERR_INVALID_ARG, "L out of range [1, 4096]%s");
+    if (B < 1 || B > c->cfg.max_batch) return fail(c, RT_ERR_INVALID_ARG, "B out of range [1, max_batch]%s");
+    if (N < 1 || N > c->cfg.max_seq) return fail(c, RT_ERR_INVALID_ARG, "N out of range [1, max_seq]%s");
+    if (kv_cap < N) return fail(c, RT_ERR_INVALID_ARG, "kv_cap < N%s");
+    if (chunk == 0) chunk = 128;
+    const int chunk_min = c->use_mfma ? 64 : c->cfg.p_min;
+    if (!is_pow2(chunk) || chunk < chunk_min || chunk < c->cfg.p_min || chunk > (1 << 20))
+        return fail(c, RT_ERR_INVALID_ARG, "chunk must be a power of two, at least p_min (and 64 with the MFMA kernels)%s");
+    const size_t E = c->cfg.dtype == RT_BF16 ? 2 : 4;
+    const size_t xb = (size_t)B * N * c->cfg.d_model * E, kvb = (size_t)kv_cap * B * c->cfg.d_model * E;
+    for (int l = 0; l < L; ++l) {
+        rt_status s = check_weights(c, &layers[l]);
+        if (s != RT_OK) return s;
+        if (!y[l] || !K[l] || !V[l]) return fail(c, RT_ERR_INVALID_ARG, "null tensor pointer%s");
+        const void *in = l == 0 ? x : y[l - 1];
+        if (ranges_overlap(in, xb, y[l], xb) || ranges_overlap(K[l], kvb, V[l], kvb) || ranges_overlap(K[l], kvb, y[l], xb) ||
+            ranges_overlap(V[l], kvb, y[l], xb) || ranges_overlap(K[l], kvb, in, xb) || ranges_overlap(V[l], kvb, in, xb))
+            return fail(c, RT_ERR_INVALID_ARG, "a layer's input, output, K and V must not overlap%s");
+        for (int m = 0; m < l; ++m)
+            if (ranges_overlap(y[m], xb, y[l], xb) || ranges_overlap(K[m], kvb, K[l], kvb) || ranges_overlap(V[m], kvb, V[l], kvb) ||
+                ranges_overlap(K[m], kvb, V[l], kvb) || ranges_overlap(V[m], kvb, K[l], kvb))
+                return fail(c, RT_ERR_INVALID_ARG, "tensors of different layers must not overlap%s");
+    }
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+    rt_status s = stack_workspace(c, L, chunk);
+    if (s != RT_OK) return s;
+
+    std::vector<WaveLayer> host(L);
+    for (int l = 0; l < L; ++l) {
+        host[l].W = to_weights(&layers[l]);
+        host[l].S = c->stack_S[l];
+        host[l].x = l == 0 ? x : y[l - 1];
+        host[l].y = y[l]; host[l].K = K[l]; host[l].V = V[l];
+    }
+    // pageable source: the copy has been staged when the call returns, `host` may go out of scope
+    RT_TRY(hipMemcpyAsync(c->stack_dev, host.data(), sizeof(WaveLayer) * L, hipMemcpyHostToDevice, c->stream), "descriptor copy");
+    LayerDims D = c->base;
+    D.B = B; D.N = N; D.kv_cap = kv_cap;
+    c->engine = "wavefront";
+    hipError_t e;
+    if (c->cfg.dtype == RT_BF16) e = wavefront_prefill<bf16_t>(D, c->stack_dev, host.data(), L, chunk, c->use_mfma, c->stream);
+    else e = wavefront_prefill<float>(D, c->stack_dev, host.data(), L, chunk, false, c->stream);
+    if (e != hipSuccess) return fail_hip(c, e, "wavefront_prefill");
     return RT_OK;
 }

@@ -65,9 +65,11 @@ __device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + e
 // A wavefront owns one (query, batch row, head): lane c holds q[c] and o[c]; within a chunk of
 // 64 keys lane j owns key j.  m, l are wave-uniform.
 // =============================================================================================
-template <typename T>
+// With HP the keys are Kb + Klo_b (bf16 head plus bf16 remainder, same row layout).
+template <typename T, bool HP = false>
 __device__ __forceinline__ void attend_keys(float q, const T *__restrict__ Kb, const T *__restrict__ Vb,
-                                            size_t row_stride, int nkeys, float scale, float &m, float &l, float &o)
+                                            size_t row_stride, int nkeys, float scale, float &m, float &l, float &o,
+                                            const bf16_t *__restrict__ Klo_b = nullptr)
 {
     const int lane = threadIdx.x & 63;
     for (int k0 = 0; k0 < nkeys; k0 += 64) {
@@ -79,6 +81,12 @@ __device__ __forceinline__ void attend_keys(float q, const T *__restrict__ Kb, c
         for (int c8 = 0; c8 < 8; ++c8) {
             float kk[8];
             load8(krow + c8 * 8, kk);
+            if (HP) {
+                float kl[8];
+                load8(Klo_b + (size_t)(valid ? j : nkeys - 1) * row_stride + c8 * 8, kl);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) kk[e] += kl[e];
+            }
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], acc);
         }
@@ -143,9 +151,10 @@ __host__ __device__ __forceinline__ int partial_slot(int l, int i0) { return ((i
 
 // ---------------------------------------------------------------- launchers (one per kernel family)
 template <typename T> struct Launch {
-    // x [Bc][Nc][d] -> Q, Kt, Vt rows (n*Bc + b)
+    // rows n0 .. n0+Nc-1 of every batch row of x (batch rows x_bstride elements apart; 0 = Nc * d, a dense
+    // [Bc][Nc][d] tensor) -> Q, Kt, Vt rows ((n0 + n)*Bc + b)
     static hipError_t prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
-                              bool mfma, hipStream_t st);
+                              bool mfma, hipStream_t st, size_t x_bstride = 0, int n0 = 0);
     // one position's q, k_tmp, v_tmp (decoding step): rows b of Q, Kt, Vt
     static hipError_t prepass_one(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride,
                                   hipStream_t st);
@@ -164,6 +173,20 @@ template <typename T> struct Launch {
     static hipError_t decode_split(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int chunk,
                                    int nsplit, hipStream_t st);
 };
+
+// One layer of a stack as the layer-wavefront engine's kernels see it (an array of these lives in device memory).
+struct WaveLayer {
+    Weights W;
+    Scratch S;        // this layer's own queries, temporary pairs, partial states and base-case vectors
+    const void *x;    // [B][N][d] input (the output of the layer below)
+    void *y;          // [B][N][d] output
+    void *K, *V;      // [kv_cap][B][H][64]
+};
+
+// All layers of a stack, layer l running `chunk` positions behind layer l - 1 (rt_wavefront.hip).
+template <typename T>
+hipError_t wavefront_prefill(const LayerDims &D, const WaveLayer *dev_layers, const WaveLayer *host_layers, int L, int chunk,
+                             bool mfma, hipStream_t st);
 
 // embedding lookup and final-norm + output projection of a layer stack (rt_stack.hip)
 template <typename T>

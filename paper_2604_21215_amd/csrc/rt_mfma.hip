@@ -23,8 +23,8 @@ __global__ __launch_bounds__(256) void prepass_mfma_kernel(const bf16_t *__restr
                                                            const bf16_t *__restrict__ g_q, const bf16_t *__restrict__ g_k,
                                                            bf16_t *__restrict__ Q, bf16_t *__restrict__ Kt,
                                                            bf16_t *__restrict__ Vt, float *__restrict__ Qf,
-                                                           float *__restrict__ Ktf, int Bc, int Nc, int d, int H, float eps,
-                                                           int norm_free)
+                                                           float *__restrict__ Ktf, int Bc, int Nc, size_t x_bstride,
+                                                           int n0, int d, int H, float eps, int norm_free)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
@@ -46,7 +46,8 @@ __global__ __launch_bounds__(256) void prepass_mfma_kernel(const bf16_t *__restr
     const bf16_t *brow[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        arow[i] = x + (size_t)min(m0 + i * 16 + l16, M - 1) * d + 8 * g;
+        const int mr = min(m0 + i * 16 + l16, M - 1);
+        arow[i] = x + (size_t)(mr / Nc) * x_bstride + (size_t)(n0 + mr % Nc) * d + 8 * g;
         brow[i] = W + (size_t)(i * 16 + l16) * d + 8 * g;
     }
     const bool use_gain = (g_attn != nullptr) && !norm_free;
@@ -100,7 +101,7 @@ __global__ __launch_bounds__(256) void prepass_mfma_kernel(const bf16_t *__restr
                 sc = rsqrtf(ss / (float)kHeadDim + eps);
             }
             if (m < M) {
-                const int b = m / Nc, n = m % Nc;
+                const int b = m / Nc, n = n0 + m % Nc;
                 const size_t oo = ((size_t)n * Bc + b) * d + h * kHeadDim + l16;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
@@ -115,13 +116,13 @@ __global__ __launch_bounds__(256) void prepass_mfma_kernel(const bf16_t *__restr
 }
 
 hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
-                               hipStream_t st)
+                               size_t x_bstride, int n0, hipStream_t st)
 {
     const int M = Bc * Nc;
     hipLaunchKernelGGL(prepass_mfma_kernel, dim3((M + 127) / 128, (3 * D.H + 1) / 2), dim3(256), 0, st, (const bf16_t *)x,
                        S.rinv, (const bf16_t *)W.Wq, (const bf16_t *)W.Wk, (const bf16_t *)W.Wv, (const bf16_t *)W.g_attn,
                        (const bf16_t *)W.g_q, (const bf16_t *)W.g_k, (bf16_t *)S.Q, (bf16_t *)S.Kt, (bf16_t *)S.Vt, S.Qf, S.Ktf,
-                       Bc, Nc, D.d, D.H, D.eps, D.norm_free);
+                       Bc, Nc, x_bstride, n0, D.d, D.H, D.eps, D.norm_free);
     return hipGetLastError();
 }
 
@@ -161,19 +162,59 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) voi
                                qb * 128 + (int)(threadIdx.x >> 6) * 32, nq, level, level_rel, slots, scale, lds, (int)threadIdx.x);
 }
 
-hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, hipStream_t st)
+// The same two kernels with high-precision logits: unrounded queries Qf, keys as head K plus remainder Klo
+// (three products per logit tile).  The three LDS tiles per buffer leave room for two workgroups per compute unit.
+__global__ __launch_bounds__(256) void cross_mfma_hp_kernel(const float *__restrict__ Qf, const bf16_t *__restrict__ K,
+                                                            const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT,
+                                                            int vt_stride, float *__restrict__ pm, float *__restrict__ pl,
+                                                            float *__restrict__ po, int BH, int t1, int P, int nq, int level,
+                                                            int level_rel, int slots, float scale)
+{
+    const int wave = threadIdx.x >> 6;
+    const int q0 = blockIdx.x * 128 + wave * 32;
+    if (q0 >= nq) return;                         // no barriers in this kernel
+    cross_mfma_wave<true>(nullptr, Qf, K, Klo, VT, vt_stride, pm, pl, po, BH, blockIdx.y, t1, 0, t1 - P, P, q0, nq, level,
+                          level_rel, slots, scale);
+}
+
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void cross_tile_hp_kernel(
+    const float *__restrict__ Qf, const bf16_t *__restrict__ K, const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT,
+    int vt_stride, float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ po, int BH, int t1, int P, int nq,
+    int nqb, int level, int level_rel, int slots, float scale)
+{
+    __shared__ __align__(16) unsigned char lds[2 * cross_tile_lds_bytes<true>()];
+    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int bh = (j / nqb) * 8 + xcd, qb = j % nqb;
+    if (bh >= BH) return;   // the whole workgroup leaves together
+    cross_tile_wg<true, 4, 2>(nullptr, Qf, K, Klo, VT, vt_stride, pm, pl, po, BH, bh, t1, 0, t1 - P, P,
+                              qb * 128 + (int)(threadIdx.x >> 6) * 32, nq, level, level_rel, slots, scale, lds, (int)threadIdx.x);
+}
+
+hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, bool hp,
+                             hipStream_t st)
 {
     int level = 0;
     while ((1 << level) < P) ++level;
+    const int nqb = (nq + 127) / 128;
+    const int bh8 = (D.B * D.H + 7) / 8 * 8;
+    if (hp) {
+        if (P >= kKC)
+            hipLaunchKernelGGL(cross_tile_hp_kernel, dim3(bh8 * nqb), dim3(256), 0, st, S.Qf, (const bf16_t *)K, S.Klo, S.VT,
+                               S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, nqb, level, level - D.log2_pmin, S.slots,
+                               D.scale);
+        else
+            hipLaunchKernelGGL(cross_mfma_hp_kernel, dim3(nqb, D.B * D.H), dim3(256), 0, st, S.Qf, (const bf16_t *)K, S.Klo,
+                               S.VT, S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, level, level - D.log2_pmin, S.slots,
+                               D.scale);
+        return hipGetLastError();
+    }
     if (P >= kKC) {
-        const int nqb = (nq + 127) / 128;
-        const int bh8 = (D.B * D.H + 7) / 8 * 8;
         hipLaunchKernelGGL(cross_tile_kernel, dim3(bh8 * nqb), dim3(256), 0, st, (const bf16_t *)S.Q, (const bf16_t *)K, S.VT,
                            S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, nqb, level, level - D.log2_pmin, S.slots,
                            D.scale);
         return hipGetLastError();
     }
-    hipLaunchKernelGGL(cross_mfma_kernel, dim3((nq + 127) / 128, D.B * D.H), dim3(256), 0, st, (const bf16_t *)S.Q,
+    hipLaunchKernelGGL(cross_mfma_kernel, dim3(nqb, D.B * D.H), dim3(256), 0, st, (const bf16_t *)S.Q,
                        (const bf16_t *)K, S.VT, S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, level,
                        level - D.log2_pmin, S.slots, D.scale);
     return hipGetLastError();

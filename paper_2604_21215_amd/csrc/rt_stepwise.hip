@@ -4,7 +4,7 @@
 // length.  They are the per-position engine ("stepwise"), the decode step, and the fp32 path of the
 // cross-block update.  The MFMA kernels live in rt_mfma.hip, the single-launch engine in
 // rt_persistent.hip.
-#include "rt_common.h"
+#include "rt_base_case.h"
 
 namespace rt {
 
@@ -54,11 +54,7 @@ __global__ __launch_bounds__(64) void decode_split_kernel(const T *__restrict__ 
 }
 
 // =============================================================================================
-// Base case, part 1: finish the attention output of position t (0-based).
-//   start from the temporary pair (Algorithm 1, "temporary self contribution"), fold in the stored
-//   partial of every level whose bit is set in t, then the direct window of the last (t mod p_min)
-//   persistent rows; a = o / l.   grid B*H, block 64.
-//   Decode mode (n_splits >= 0): the partials are slots 0..n_splits-1 of relative level 0, no window.
+// Base case, part 1: finish the attention output of position t (merge_body).  grid B*H, block 64.
 // =============================================================================================
 template <typename T>
 __global__ __launch_bounds__(64) void merge_kernel(const T *__restrict__ Q, const T *__restrict__ Kt,
@@ -69,82 +65,24 @@ __global__ __launch_bounds__(64) void merge_kernel(const T *__restrict__ Q, cons
                                                    int p_min, int log2_pmin, int levels, int slots, int n_splits,
                                                    float scale)
 {
-    const int lane = threadIdx.x;
-    const int bh = blockIdx.x;
-    const size_t rs = (size_t)BH * kHeadDim;
-    const size_t qoff = (size_t)q_row * rs + (size_t)bh * kHeadDim + lane;
-    const float q = to_f32(Q[qoff]);
-    float m = scale * wave_sum(q * to_f32(Kt[qoff]));
-    float l = 1.f;
-    float o = to_f32(Vt[qoff]);
-    if (n_splits >= 0) {
-        // two passes, so that no load waits for an exponential: the overall maximum first (lanes read the splits'
-        // maxima side by side), then the weighted sums in split order
-        float mx = m;
-        for (int s0 = 0; s0 < n_splits; s0 += 64) {
-            const int sidx = s0 + lane;
-            mx = fmaxf(mx, sidx < n_splits ? pm[partial_index(0, sidx, slots, BH, bh)] : -INFINITY);
-        }
-        mx = wave_max(mx);
-        const float e0 = expf(m - mx);
-        l = e0;
-        o = o * e0;
-        for (int s0 = 0; s0 < n_splits; s0 += 64) {
-            const int sidx = s0 + lane, cnt = min(64, n_splits - s0);
-            float wgt = 0.f, lw = 0.f;
-            if (sidx < n_splits) {
-                const size_t idx = partial_index(0, sidx, slots, BH, bh);
-                wgt = expf(pm[idx] - mx);
-                lw = wgt * pl[idx];
-            }
-            for (int j = 0; j < cnt; ++j) {
-                l += lane_bcast(lw, j);
-                o = fmaf(lane_bcast(wgt, j), po[partial_index(0, s0 + j, slots, BH, bh) * kHeadDim + lane], o);
-            }
-        }
-        m = mx;
-    } else {
-        for (int lr = 0; lr < levels; ++lr) {
-            const int lv = lr + log2_pmin;
-            if ((t >> lv) & 1) {
-                const size_t idx = partial_index(lr, partial_slot(lv, t), slots, BH, bh);
-                const float pmv = pm[idx], plv = pl[idx], pov = po[idx * kHeadDim + lane];
-                const float m_new = fmaxf(m, pmv);
-                const float e1 = expf(m - m_new), e2 = expf(pmv - m_new);
-                l = l * e1 + plv * e2;
-                o = o * e1 + pov * e2;
-                m = m_new;
-            }
-        }
-        const int w = t & (p_min - 1);
-        if (w > 0) {
-            const size_t base = (size_t)(t - w) * rs + (size_t)bh * kHeadDim;
-            attend_keys<T>(q, K + base, V + base, rs, w, scale, m, l, o);
-        }
-    }
-    const int b = bh / H, h = bh % H;
-    attn_cat[(size_t)b * H * kHeadDim + h * kHeadDim + lane] = o / l;
+    merge_body<T, false>(Q, nullptr, Kt, nullptr, Vt, K, nullptr, V, pm, pl, po, attn_cat, BH, H, blockIdx.x, t, q_row, p_min,
+                         log2_pmin, levels, slots, n_splits, scale);
 }
 
 // =============================================================================================
-// Small-M matrix products of the base case:  out[b][o] = epilogue( sum_k W[o][k] * in[b][k] ),
-// b < Bn <= 8.  Bandwidth is the bound (every weight is used for at most 8 multiply-adds), so the
-// work is cut for memory parallelism: groups of KS wavefronts own 4 output rows each (a workgroup
-// of 4 wavefronts: 16 / KS rows), a wavefront takes every KS-th 512-column slice of the contraction
-// (16-byte weight loads, 4 rows in flight), the partial sums meet in LDS in a fixed order (runs are
-// bit-reproducible).  KS = 2 for contractions up to 1024 columns (every wavefront then has exactly
-// one slice), else 4.  The B input rows come out of L2.  With do_norm the
-// input is RMS-normalised: the sum of squares is accumulated from the same values on the way and
-// the scale 1/rms is applied to the finished sums (the product is linear in its input); the gain
-// multiplies the input elements as they are read.
-// Rows o < n_first come from Wa, n_first <= o < 2 n_first from Wb, the rest from Wc.
+// Small-M matrix products of the base case (gemv_body) for one layer: rows o < n_first come from Wa,
+// n_first <= o < 2 n_first from Wb, the rest from Wc; one gain vector.
 // =============================================================================================
-enum Epi { EPI_WO = 0, EPI_W1 = 1, EPI_W2 = 2, EPI_KV = 3 };
-
-constexpr int kGemvRows = 4;      // output rows per workgroup
-
-__device__ __forceinline__ void load8_in(const float *p, float *o) { load8(p, o); }
-__device__ __forceinline__ void load8_in(const bf16_t *p, float *o) { load8(p, o); }
+template <typename T> struct ThreeMatrices {
+    const T *Wa, *Wb, *Wc, *g;
+    int n_first, n_in;
+    __device__ __forceinline__ const T *row(int o) const
+    {
+        const int which = o / n_first;
+        return (which == 0 ? Wa : (which == 1 ? Wb : Wc)) + (size_t)(o - which * n_first) * n_in;
+    }
+    __device__ __forceinline__ const T *gain() const { return g; }
+};
 
 template <typename T, typename IN_T, int EPI, int KS>
 __global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, const T *__restrict__ Wb,
@@ -155,94 +93,10 @@ __global__ __launch_bounds__(256) void gemv_kernel(const T *__restrict__ Wa, con
                                                    const float *__restrict__ res_f, float *__restrict__ out_f,
                                                    T *__restrict__ out_T, size_t out_T_stride)
 {
-    __shared__ float part[4][kGemvRows * kBatchTile + kBatchTile];
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    constexpr int kGroups = 4 / KS;   // row groups per workgroup
-    const int rg = wave / KS, kw = wave % KS;
-    const int o0 = (blockIdx.x * kGroups + rg) * kGemvRows;
-    const T *wrow[kGemvRows];
-#pragma unroll
-    for (int r = 0; r < kGemvRows; ++r) {
-        const int o = min(o0 + r, n_out - 1);
-        const int which = o / n_first;
-        wrow[r] = (which == 0 ? Wa : (which == 1 ? Wb : Wc)) + (size_t)(o - which * n_first) * n_in;
-    }
-    float acc[kGemvRows][kBatchTile], ssq[kBatchTile];
-#pragma unroll
-    for (int b = 0; b < kBatchTile; ++b) {
-        ssq[b] = 0.f;
-#pragma unroll
-        for (int r = 0; r < kGemvRows; ++r) acc[r][b] = 0.f;
-    }
-    for (int k = kw * 512 + lane * 8; k < n_in; k += 512 * KS) {
-        float w[kGemvRows][8];
-#pragma unroll
-        for (int r = 0; r < kGemvRows; ++r) load8(wrow[r] + k, w[r]);
-        float g8[8];
-        const bool use_g = do_norm && gain != nullptr;
-        if (use_g) load8(gain + k, g8);
-#pragma unroll
-        for (int b = 0; b < kBatchTile; ++b) {
-            if (b < Bn) {
-                float x8[8];
-                load8_in(in + (size_t)b * in_stride + k, x8);
-                if (do_norm) {
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) ssq[b] = fmaf(x8[e], x8[e], ssq[b]);
-                    if (use_g) {
-#pragma unroll
-                        for (int e = 0; e < 8; ++e) x8[e] *= g8[e];
-                    }
-                }
-#pragma unroll
-                for (int r = 0; r < kGemvRows; ++r) {
-                    float a = acc[r][b];
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) a = fmaf(w[r][e], x8[e], a);
-                    acc[r][b] = a;
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int b = 0; b < kBatchTile; ++b) {
-        ssq[b] = wave_sum(ssq[b]);
-#pragma unroll
-        for (int r = 0; r < kGemvRows; ++r) acc[r][b] = wave_sum(acc[r][b]);
-    }
-    if (lane == 0) {
-#pragma unroll
-        for (int b = 0; b < kBatchTile; ++b) {
-            part[wave][kGemvRows * kBatchTile + b] = ssq[b];
-#pragma unroll
-            for (int r = 0; r < kGemvRows; ++r) part[wave][r * kBatchTile + b] = acc[r][b];
-        }
-    }
-    __syncthreads();
-    // 32 threads per row group each finish one (row, batch) pair
-    if (tid < kGroups * kGemvRows * kBatchTile) {
-        const int grp = tid / (kGemvRows * kBatchTile), pi = tid % (kGemvRows * kBatchTile);
-        const int r = pi / kBatchTile, b = pi % kBatchTile;
-        const int si = kGemvRows * kBatchTile + b;
-        float v = 0.f, tot = 0.f;
-#pragma unroll
-        for (int j = 0; j < KS; ++j) { v += part[grp * KS + j][pi]; tot += part[grp * KS + j][si]; }
-        if (do_norm) v *= rsqrtf(tot / (float)n_in + eps);
-        const int o = (blockIdx.x * kGroups + grp) * kGemvRows + r;
-        if (o < n_out && b < Bn) {
-            if (EPI == EPI_WO) {
-                out_f[(size_t)b * n_out + o] = to_f32(res_T[(size_t)b * res_stride + o]) + alpha * v;
-            } else if (EPI == EPI_W1) {
-                out_f[(size_t)b * n_out + o] = gelu_erf(v);
-            } else if (EPI == EPI_W2) {
-                const float z = res_f[(size_t)b * n_out + o] + alpha * v;
-                out_f[(size_t)b * n_out + o] = z;
-                out_T[(size_t)b * out_T_stride + o] = from_f32<T>(z);
-            } else {
-                out_f[(size_t)b * n_out + o] = v;
-            }
-        }
-    }
+    __shared__ float part[4][kGemvPart];
+    const ThreeMatrices<T> rows{Wa, Wb, Wc, gain, n_first, n_in};
+    gemv_body<T, IN_T, EPI, KS>(rows, blockIdx.x, n_out, n_in, in, in_stride, Bn, eps, do_norm, alpha, res_T, res_stride, res_f,
+                                out_f, out_T, out_T_stride, part);
 }
 
 // Decoding step, after the raw [q | k_tmp | v_tmp] product of one position: qkRMS of q and k_tmp per head and the
@@ -297,14 +151,15 @@ __global__ __launch_bounds__(64) void finalize_kv_kernel(const float *__restrict
 // Tile 64 rows x 64 columns (one head of one of the three outputs), 256 threads, 4x4 per thread.
 // =============================================================================================
 template <typename T>
-__global__ __launch_bounds__(256) void row_rinv_kernel(const T *__restrict__ x, float *__restrict__ rinv, int M, int d,
-                                                       float eps, int norm_free)
+__global__ __launch_bounds__(256) void row_rinv_kernel(const T *__restrict__ x, float *__restrict__ rinv, int M, int Nc,
+                                                       size_t x_bstride, int n0, int d, float eps, int norm_free)
 {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = blockIdx.x * 4 + wave;
     if (m >= M) return;
+    const T *xr = x + (size_t)(m / Nc) * x_bstride + (size_t)(n0 + m % Nc) * d;
     float ss = 0.f;
-    for (int k = lane; k < d; k += 64) { const float v = to_f32(x[(size_t)m * d + k]); ss = fmaf(v, v, ss); }
+    for (int k = lane; k < d; k += 64) { const float v = to_f32(xr[k]); ss = fmaf(v, v, ss); }
     ss = wave_sum(ss);
     if (lane == 0) rinv[m] = norm_free ? 1.f : rsqrtf(ss / (float)d + eps);
 }
@@ -315,7 +170,8 @@ __global__ __launch_bounds__(256) void prepass_generic_kernel(const T *__restric
                                                               const T *__restrict__ Wv, const T *__restrict__ g_attn,
                                                               const T *__restrict__ g_q, const T *__restrict__ g_k,
                                                               T *__restrict__ Q, T *__restrict__ Kt, T *__restrict__ Vt,
-                                                              int Bc, int Nc, int d, int H, float eps, int norm_free)
+                                                              int Bc, int Nc, size_t x_bstride, int n0, int d, int H,
+                                                              float eps, int norm_free)
 {
     __shared__ float As[16][64 + 1];
     __shared__ float Bs[16][64 + 1];
@@ -338,7 +194,7 @@ __global__ __launch_bounds__(256) void prepass_generic_kernel(const T *__restric
             const int k = k0 + kk;
             float a = 0.f, bv = 0.f;
             if (k < d) {
-                a = to_f32(x[(size_t)m * d + k]);
+                a = to_f32(x[(size_t)(m / Nc) * x_bstride + (size_t)(n0 + m % Nc) * d + k]);
                 if (!norm_free) a *= rinv[m] * (g_attn ? to_f32(g_attn[k]) : 1.f);
                 bv = to_f32(W[(size_t)(h * kHeadDim + r) * d + k]);
             }
@@ -370,7 +226,7 @@ __global__ __launch_bounds__(256) void prepass_generic_kernel(const T *__restric
         }
         const int m = m0 + ty * 4 + i;
         if (m < M) {
-            const int b = m / Nc, n = m % Nc;
+            const int b = m / Nc, n = n0 + m % Nc;
             T *o = dst + ((size_t)n * Bc + b) * d + h * kHeadDim + tx * 4;
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
@@ -386,20 +242,23 @@ __global__ __launch_bounds__(256) void prepass_generic_kernel(const T *__restric
 // Launchers
 // =============================================================================================
 hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
-                               hipStream_t st);
-hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, hipStream_t st);
+                               size_t x_bstride, int n0, hipStream_t st);
+hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, bool hp,
+                             hipStream_t st);
 
 template <typename T>
 hipError_t Launch<T>::prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
-                              bool mfma, hipStream_t st)
+                              bool mfma, hipStream_t st, size_t x_bstride, int n0)
 {
     const int M = Bc * Nc;
-    hipLaunchKernelGGL(row_rinv_kernel<T>, dim3((M + 3) / 4), dim3(256), 0, st, (const T *)x, S.rinv, M, D.d, D.eps,
-                       D.norm_free);
-    if (mfma && sizeof(T) == 2) return prepass_mfma_launch(D, W, S, x, Bc, Nc, st);
+    if (x_bstride == 0) x_bstride = (size_t)Nc * D.d;
+    hipLaunchKernelGGL(row_rinv_kernel<T>, dim3((M + 3) / 4), dim3(256), 0, st, (const T *)x, S.rinv, M, Nc, x_bstride, n0,
+                       D.d, D.eps, D.norm_free);
+    if (mfma && sizeof(T) == 2) return prepass_mfma_launch(D, W, S, x, Bc, Nc, x_bstride, n0, st);
     hipLaunchKernelGGL(prepass_generic_kernel<T>, dim3((M + 63) / 64, 3 * D.H), dim3(256), 0, st, (const T *)x, S.rinv,
                        (const T *)W.Wq, (const T *)W.Wk, (const T *)W.Wv, (const T *)W.g_attn, (const T *)W.g_q,
-                       (const T *)W.g_k, (T *)S.Q, (T *)S.Kt, (T *)S.Vt, Bc, Nc, D.d, D.H, D.eps, D.norm_free);
+                       (const T *)W.g_k, (T *)S.Q, (T *)S.Kt, (T *)S.Vt, Bc, Nc, x_bstride, n0, D.d, D.H, D.eps,
+                       D.norm_free);
     return hipGetLastError();
 }
 
@@ -501,7 +360,7 @@ hipError_t Launch<T>::cross(const LayerDims &D, const Scratch &S, const void *K,
 {
     int level = 0;
     while ((1 << level) < P) ++level;
-    if (mfma && sizeof(T) == 2) return cross_mfma_launch(D, S, K, t1, P, nq, st);
+    if (mfma && sizeof(T) == 2) return cross_mfma_launch(D, S, K, t1, P, nq, false, st);
     hipLaunchKernelGGL(cross_generic_kernel<T>, dim3(nq, D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)K,
                        (const T *)V, S.pm, S.pl, S.po, D.B * D.H, t1, P, level, level - D.log2_pmin, S.slots, D.scale);
     return hipGetLastError();

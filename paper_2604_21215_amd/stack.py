@@ -21,25 +21,35 @@ class DeviceStack:
         self.H = ctx.cfg.n_heads
         self.K = self.V = self.y = None
 
-    def prefill(self, ids: torch.Tensor, N: int, kv_cap: int, keep_outputs: bool = True):
+    def prefill(self, ids: torch.Tensor, N: int, kv_cap: int, keep_outputs: bool = True, wavefront: bool = False,
+                chunk: int = 0):
         """ids [B, >= N] int32 on the device.  Runs positions 0..N-1 through every layer; returns the
         logits [B, vocab] (fp32) of position N-1.  Layer outputs stay in self.y[l] ([B, N, d]) and the
-        caches in self.K[l], self.V[l] ([kv_cap, B, H, 64])."""
+        caches in self.K[l], self.V[l] ([kv_cap, B, H, 64]).  wavefront: one rt_stack_prefill call (layers
+        run concurrently, `chunk` positions apart) instead of one rt_layer_prefill per layer."""
         B = ids.shape[0]
         td = torch_dtype(self.dtype)
         x = torch.empty((B, N, self.d), dtype=td, device=self.device)
         self.ctx.rt_embed_rows(self.embedding, ids, 0, x)
         self.x0 = x
         self.K, self.V, self.y = [], [], []
-        for lay in self.layers:
-            y = torch.empty_like(x)
-            K = torch.zeros((kv_cap, B, self.H, self.d // self.H), dtype=td, device=self.device)
-            V = torch.zeros_like(K)
-            self.ctx.rt_layer_prefill(lay.struct, x, y, K, V)
-            self.K.append(K); self.V.append(V)
-            if keep_outputs:
-                self.y.append(y)
-            x = y
+        if wavefront:
+            for _ in self.layers:
+                self.y.append(torch.empty_like(x))
+                self.K.append(torch.zeros((kv_cap, B, self.H, self.d // self.H), dtype=td, device=self.device))
+                self.V.append(torch.zeros_like(self.K[-1]))
+            self.ctx.rt_stack_prefill([lay.struct for lay in self.layers], x, self.y, self.K, self.V, chunk)
+            x = self.y[-1]
+        else:
+            for lay in self.layers:
+                y = torch.empty_like(x)
+                K = torch.zeros((kv_cap, B, self.H, self.d // self.H), dtype=td, device=self.device)
+                V = torch.zeros_like(K)
+                self.ctx.rt_layer_prefill(lay.struct, x, y, K, V)
+                self.K.append(K); self.V.append(V)
+                if keep_outputs:
+                    self.y.append(y)
+                x = y
         self.last = x
         logits = torch.empty((B, self.vocab), dtype=torch.float32, device=self.device)
         self.ctx.rt_lm_head(self.lm_head, self.g_final, x[:, N - 1], x.stride(0), B, logits)

@@ -36,7 +36,7 @@ def _ids_dev(ids):
 EMB_UNIT = 50.0
 
 
-def _make_stack(oracle, wl, B, max_seq, flags=0, emb_scale=1.0):
+def _make_stack(oracle, wl, B, max_seq, flags=0, emb_scale=1.0, p_min=0):
     """Device stack and oracle stack over the same host buffers."""
     from paper_2604_21215_amd import binding, torch_io as tio
     from paper_2604_21215_amd.stack import DeviceStack
@@ -45,7 +45,7 @@ def _make_stack(oracle, wl, B, max_seq, flags=0, emb_scale=1.0):
         e = tabs["embedding"] * np.float32(emb_scale)
         tabs["embedding"] = gen.round_to_bf16(e) if wl.dtype == "bf16" else e
     ctx = binding.RTContext(wl.d, wl.H, wl.F, B, max_seq, wl.dtype, resid_scale=wl.resid_scale, rms_eps=1e-6, flags=flags,
-                            stream=torch.cuda.current_stream().cuda_stream)
+                            p_min=p_min, stream=torch.cuda.current_stream().cuda_stream)
     dls, ols = [], []
     for l in range(wl.layers):
         w = gen.make_layer_weights(wl.seed, l, wl.d, wl.F, wl.dtype)
@@ -72,18 +72,19 @@ def _fmt(rows):
     return " | ".join("L%d y %.1e K %.1e V %.1e" % (l, r[0], r[1], r[2]) for l, r in enumerate(rows))
 
 
-def _run_elementwise(oracle, wl, B, N, n_dec, flags=0, emb_scale=1.0):
+def _run_elementwise(oracle, wl, B, N, n_dec, flags=0, emb_scale=1.0, wavefront=False, chunk=0, p_min=0):
     from paper_2604_21215_amd import torch_io as tio
     _need_gpu()
     T = N + n_dec
     ids = gen.make_token_ids(wl)[:B, :T]
-    ctx, ds, os_ = _make_stack(oracle, wl, B, T, flags, emb_scale)
+    ctx, ds, os_ = _make_stack(oracle, wl, B, T, flags, emb_scale, p_min)
     try:
         ref_layers, ref_logits = os_.prefill(ids, N, kv_cap=T)
         idd = _ids_dev(ids)
-        logits = ds.prefill(idd, N, kv_cap=T)
+        logits = ds.prefill(idd, N, kv_cap=T, wavefront=wavefront, chunk=chunk)
         torch.cuda.synchronize()
         assert ctx.device_wait_expired() == 0
+        assert (ctx.engine_name() == "wavefront") == wavefront
         tol = TOL[wl.dtype]
         rows = _layer_errors(ds, ref_layers, N)
         e_log = rel_err_rows(logits.cpu().numpy().astype(np.float64), ref_logits).max()
@@ -112,6 +113,49 @@ def test_small_fp32_stack_elementwise(oracle):
 def test_small_bf16_stack_elementwise(oracle):
     wl = gen.Workload("stack_small_bf16", "bf16", 3, 70, 256, 4, 1024, layers=4, vocab=1000, decode_steps=6, seed=992)
     _run_elementwise(oracle, wl, 3, 70, 6, emb_scale=EMB_UNIT)
+
+
+@pytest.mark.parametrize("N,chunk,p_min", [(100, 32, 0), (75, 32, 8), (40, 64, 0), (130, 16, 4)])
+def test_small_fp32_stack_wavefront(oracle, N, chunk, p_min):
+    """rt_stack_prefill (layers run concurrently, a chunk apart) against the oracle, fp32: several chunks with a
+    ragged last one, with and without blocks inside the chunk, a sequence shorter than the chunk."""
+    wl = gen.Workload("stack_small_wf", "f32", 2, N, 128, 2, 512, layers=3, vocab=257, decode_steps=4, seed=993)
+    _run_elementwise(oracle, wl, 2, N, 4, emb_scale=EMB_UNIT, wavefront=True, chunk=chunk, p_min=p_min)
+
+
+@pytest.mark.parametrize("N,chunk", [(200, 64), (300, 128)])
+def test_small_bf16_stack_wavefront(oracle, N, chunk):
+    """The same on the bf16 path (MFMA tiles with unrounded logit inputs for the blocks inside a chunk and for the
+    keys before it)."""
+    wl = gen.Workload("stack_small_bf16_wf", "bf16", 3, N, 256, 4, 1024, layers=4, vocab=1000, decode_steps=4, seed=994)
+    _run_elementwise(oracle, wl, 3, N, 4, emb_scale=EMB_UNIT, wavefront=True, chunk=chunk)
+
+
+def test_stack_prefill_argument_checks():
+    from paper_2604_21215_amd import binding, torch_io as tio
+    _need_gpu()
+    d, B, N = 128, 2, 48
+    ctx = binding.RTContext(d, 2, 4 * d, B, 64, "bf16", stream=torch.cuda.current_stream().cuda_stream)
+    try:
+        w = gen.make_layer_weights(5, 0, d, 4 * d, "bf16")
+        lay = tio.DeviceLayer(w, None, "bf16")
+        x = torch.zeros((B, N, d), dtype=torch.bfloat16, device="cuda:0")
+        ys = [torch.zeros_like(x) for _ in range(2)]
+        Ks = [torch.zeros((N, B, 2, 64), dtype=torch.bfloat16, device="cuda:0") for _ in range(2)]
+        Vs = [torch.zeros_like(k) for k in Ks]
+        ws = [lay.struct, lay.struct]
+        pt = lambda ts: [t.data_ptr() for t in ts]
+        bad = binding.RT_ERR_INVALID_ARG
+        assert ctx.raw_stack_prefill(ws, x.data_ptr(), B, N, pt(ys), pt(Ks), pt(Vs), N, 32) == bad       # chunk < 64 with MFMA
+        assert ctx.raw_stack_prefill(ws, x.data_ptr(), B, N, pt(ys), pt(Ks), pt(Vs), N, 96) == bad       # not a power of two
+        assert ctx.raw_stack_prefill(ws, x.data_ptr(), B, N, pt(ys), pt(Ks), pt(Vs), N - 1, 64) == bad   # kv_cap < N
+        assert ctx.raw_stack_prefill(ws, x.data_ptr(), B, N, [ys[0].data_ptr(), ys[0].data_ptr()], pt(Ks), pt(Vs), N, 64) == bad
+        assert ctx.raw_stack_prefill(ws, x.data_ptr(), B, N, pt(ys), [Ks[0].data_ptr(), 0], pt(Vs), N, 64) == bad
+        assert ctx.raw_stack_prefill(ws, x.data_ptr(), B + 1, N, pt(ys), pt(Ks), pt(Vs), N, 64) == bad
+        assert ctx.raw_stack_prefill(ws, x.data_ptr(), B, N, pt(ys), pt(Ks), pt(Vs), N, 64) == binding.RT_OK
+        torch.cuda.synchronize()
+    finally:
+        ctx.rt_destroy()
 
 
 def test_embed_rows_exact_and_lm_head(oracle):
@@ -150,6 +194,12 @@ def test_config5_reduced_length_elementwise(oracle):
     decoding steps: every layer's y, K, V and the read-out logits against the oracle."""
     wl = gen.WORKLOADS["cfg5"]
     _run_elementwise(oracle, wl, wl.B, 384, 16, emb_scale=EMB_UNIT)
+
+
+def test_config5_reduced_length_wavefront(oracle):
+    """The same through rt_stack_prefill with the default chunk of 128 positions."""
+    wl = gen.WORKLOADS["cfg5"]
+    _run_elementwise(oracle, wl, wl.B, 384, 16, emb_scale=EMB_UNIT, wavefront=True)
 
 
 def test_config5_literal_embedding_scale_tracks_oracle_sensitivity(oracle):
@@ -227,6 +277,29 @@ def test_config5_full_size(oracle):
             e_log = rel_err_rows(logits.cpu().numpy().astype(np.float64), ref_logits).max()
             print("  [cfg5 logits at position %d vs oracle] %.1e" % (N - 1, e_log), flush=True)
             assert e_log <= tol
+        # the layer-wavefront engine on the same inputs: against the oracle as above, and every position of every
+        # layer against the layer-by-layer run (each is within tol of the exact result)
+        y_seq, K_seq, V_seq = ds.y, ds.K, ds.V
+        logits_wf = ds.prefill(idd, N, kv_cap=T, wavefront=True)
+        torch.cuda.synchronize()
+        assert ctx.engine_name() == "wavefront"
+        rows_wf = _layer_errors(ds, ref_layers, N if full else Np)
+        print("  [cfg5 full size, wavefront engine, positions < %d vs oracle] %s" % (N if full else Np, _fmt(rows_wf)), flush=True)
+        assert rows_wf.max() <= tol
+        d_seq = np.zeros(3)
+        for l in range(wl.layers):
+            d_seq = np.maximum(d_seq, [rel_err_rows(tio.to_host(ds.y[l]), tio.to_host(y_seq[l])).max(),
+                                       rel_err_rows(tio.to_host(ds.K[l][:N]), tio.to_host(K_seq[l][:N])).max(),
+                                       rel_err_rows(tio.to_host(ds.V[l][:N]), tio.to_host(V_seq[l][:N])).max()])
+        e_lw = rel_err_rows(logits_wf.cpu().numpy().astype(np.float64), logits.cpu().numpy().astype(np.float64)).max()
+        print("  [cfg5 full size, wavefront vs layer-by-layer, all positions] y %.1e K %.1e V %.1e logits %.1e" % (*d_seq, e_lw),
+              flush=True)
+        assert d_seq.max() <= 2 * tol and e_lw <= 2 * tol
+        if full:
+            e_log = rel_err_rows(logits_wf.cpu().numpy().astype(np.float64), ref_logits).max()
+            print("  [cfg5 wavefront logits at position %d vs oracle] %.1e" % (N - 1, e_log), flush=True)
+            assert e_log <= tol
+        # decoding continues from the wavefront engine's caches
         worst = np.zeros(3)
         worst_o = np.zeros(3)
         for t in range(N, T):
