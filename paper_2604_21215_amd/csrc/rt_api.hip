@@ -89,6 +89,9 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
     const size_t orinv = carve(Bm * Nm * 4);
     const size_t ocat = carve(Bm * d * 4), oh = carve(Bm * d * 4), ou = carve(Bm * F * 4), oz = carve(Bm * d * 4);
     const size_t okv = carve(Bm * 2 * d * 4), oqkv = carve(Bm * 3 * d * 4);
+    const size_t oopa = carve(2 * Bm * d * 2), ooph = carve(2 * Bm * d * 2), oopz = carve(2 * Bm * d * 2);
+    const size_t oopu = carve(2 * Bm * F * 2);
+    const size_t osh = carve(Bm * (d / 16 + 1) * 4), osz = carve(Bm * (d / 16 + 1) * 4);
     if (base) {
         char *p = base;
         S.Q = p + oQ; S.Kt = p + oKt; S.Vt = p + oVt;
@@ -101,6 +104,9 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
         S.attn_cat = (float *)(p + ocat); S.h = (float *)(p + oh); S.u = (float *)(p + ou); S.z = (float *)(p + oz);
         S.kv_raw = (float *)(p + okv);
         S.qkv_raw = (float *)(p + oqkv);
+        S.op_a = (bf16_t *)(p + oopa); S.op_h = (bf16_t *)(p + ooph); S.op_z = (bf16_t *)(p + oopz);
+        S.op_u = (bf16_t *)(p + oopu);
+        S.ssq_h = (float *)(p + osh); S.ssq_z = (float *)(p + osz);
     }
     return off;
 }

@@ -15,6 +15,7 @@ namespace rt {
 //   far_rel >= 0 (chunked schedule of the layer-wavefront engine): `levels` covers the blocks inside the
 //   position's chunk of 2^log2_chunk positions only; all keys before the chunk were folded into one more
 //   partial state, stored at slot t of relative level far_rel.
+//   op_a: if not null, a is also written as a bf16 head row and a bf16 remainder row (rows 2b, 2b + 1 of [2B][d]).
 //   HP: the query and the temporary key come unrounded from Qf / Ktf and the window keys are head K plus
 //   remainder Klo, so that no logit carries a bf16 rounding of q or k.
 // =============================================================================================
@@ -26,7 +27,8 @@ __device__ __forceinline__ void merge_body(const T *__restrict__ Q, const float 
                                            const float *__restrict__ pm, const float *__restrict__ pl,
                                            const float *__restrict__ po, float *__restrict__ attn_cat, int BH, int H,
                                            int bh, int t, int q_row, int p_min, int log2_pmin, int levels, int slots,
-                                           int n_splits, float scale, int far_rel = -1, int log2_chunk = 0)
+                                           int n_splits, float scale, int far_rel = -1, int log2_chunk = 0,
+                                           bf16_t *__restrict__ op_a = nullptr)
 {
     const int lane = threadIdx.x & 63;
     const size_t rs = (size_t)BH * kHeadDim;
@@ -91,7 +93,14 @@ __device__ __forceinline__ void merge_body(const T *__restrict__ Q, const float 
         }
     }
     const int b = bh / H, h = bh % H;
-    attn_cat[(size_t)b * H * kHeadDim + h * kHeadDim + lane] = o / l;
+    const float a = o / l;
+    attn_cat[(size_t)b * H * kHeadDim + h * kHeadDim + lane] = a;
+    if (op_a) {   // the same value as bf16 head + remainder rows (2b, 2b + 1) for the matrix-core products
+        const size_t d = (size_t)H * kHeadDim;
+        const bf16_t hi = f32_to_bf16(a);
+        op_a[(size_t)(2 * b) * d + h * kHeadDim + lane] = hi;
+        op_a[(size_t)(2 * b + 1) * d + h * kHeadDim + lane] = f32_to_bf16(a - bf16_to_f32(hi));
+    }
 }
 
 // =============================================================================================

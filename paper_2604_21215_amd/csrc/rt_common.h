@@ -140,6 +140,11 @@ struct Scratch {
     float *z;            // [B][d]
     float *kv_raw;       // [B][2d]
     float *qkv_raw;      // [B][3d] raw q, k_tmp, v_tmp of a decoding step
+    // layer-wavefront engine, bf16: inputs of the base-case products as bf16 head + remainder rows (row 2b: head of
+    // batch row b, row 2b + 1: remainder), gains already applied; sums of squares per group of 16 elements
+    bf16_t *op_a, *op_h, *op_z;   // [2B][d]
+    bf16_t *op_u;                 // [2B][F]
+    float *ssq_h, *ssq_z;         // [B][d/16]
 };
 
 __host__ __device__ __forceinline__ size_t partial_index(int level_rel, int slot, int slots, int BH, int bh)

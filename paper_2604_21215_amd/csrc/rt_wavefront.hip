@@ -43,7 +43,7 @@ __global__ __launch_bounds__(64) void wf_merge_kernel(const WaveLayer *__restric
     const int tree_levels = log2_chunk - log2_pmin;
     merge_body<T, HP>((const T *)Y.S.Q, Y.S.Qf, (const T *)Y.S.Kt, Y.S.Ktf, (const T *)Y.S.Vt, (const T *)Y.K, Y.S.Klo,
                       (const T *)Y.V, Y.S.pm, Y.S.pl, Y.S.po, Y.S.attn_cat, BH, H, blockIdx.x, t, t, p_min, log2_pmin, tree_levels,
-                      Y.S.slots, -1, scale, tree_levels, log2_chunk);
+                      Y.S.slots, -1, scale, tree_levels, log2_chunk, HP ? Y.S.op_a : nullptr);
 }
 
 template <typename T> struct StackedRows {   // rows o < n_first from Wa, the rest from Wb
@@ -83,6 +83,156 @@ __global__ __launch_bounds__(256) void wf_gemv_kernel(const WaveLayer *__restric
         const StackedRows<T> rows{(const T *)Y.W.Wk, (const T *)Y.W.Wv, (const T *)Y.W.g_kv, d, d};
         gemv_body<T, float, EPI, KS>(rows, blockIdx.x, 2 * d, d, Y.S.z + (size_t)b0 * d, (size_t)d, Bn, eps, norm_free ? 0 : 1,
                                      alpha, nullptr, 0, nullptr, Y.S.kv_raw + (size_t)b0 * 2 * d, nullptr, 0, part);
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same four products on the matrix cores (bf16 storage).  With at most 16 batch rows the products are
+// bound by the weight bytes, and the plain-ALU form spends more instructions on the cross-lane sums than
+// on the multiply-adds; v_mfma_f32_16x16x32_bf16 does that reduction for free:
+//     D[16 weight rows][16 batch columns] += W[16 rows][32 k] * X^T[32 k][16 columns]
+// A fragments come straight from the row-major weights (lane: row lane%16, 16 bytes), and so that a lane's
+// two consecutive loads cover 32 contiguous bytes (the four lanes of a row one 128-byte line per pair of
+// steps) the contraction index of step pair p is assigned as k = 64 p + 16 g + (0..7 | 8..15), g = lane/16.
+// The input vector is not rounded: it comes as a bf16 head row plus a bf16 remainder row (written by the
+// producing kernel's epilogue with the consumer's RMS gain applied) and each weight fragment feeds two
+// instructions.  The RMS scale is applied to the finished sums (the product is linear in its input); its
+// sum of squares comes as one partial per 16 elements from the producer and is added in a fixed order.
+// KS wavefronts of a workgroup share 16 rows and split the contraction; their partial tiles meet in LDS.
+// grid (n_out / (16 * 4 / KS), layers, batch tiles of 16), block 256.
+// ---------------------------------------------------------------------------------------------
+constexpr int kMmBatch = 16;
+
+__device__ __forceinline__ void split_store4(bf16_t *__restrict__ op, size_t hi_off, size_t lo_off, const float *v)
+{
+    uint32_t h01 = pack_bf16(v[0], v[1]), h23 = pack_bf16(v[2], v[3]);
+    const float r0 = v[0] - __uint_as_float(h01 << 16), r1 = v[1] - __uint_as_float(h01 & 0xFFFF0000u);
+    const float r2 = v[2] - __uint_as_float(h23 << 16), r3 = v[3] - __uint_as_float(h23 & 0xFFFF0000u);
+    *reinterpret_cast<uint2 *>(op + hi_off) = make_uint2(h01, h23);
+    *reinterpret_cast<uint2 *>(op + lo_off) = make_uint2(pack_bf16(r0, r1), pack_bf16(r2, r3));
+}
+
+// 1 / rms of batch row `col` from the producer's partial sums of squares (ng of them); all four lanes that share
+// a column end up with the same value.
+__device__ __forceinline__ float rms_scale_from_parts(const float *__restrict__ ssq, int col, int g, int ng, int K, float eps)
+{
+    float tot = 0.f;
+    const int per = (ng + 3) / 4;
+    for (int j = g * per; j < min(ng, (g + 1) * per); ++j) tot += ssq[(size_t)col * ng + j];
+    tot += __shfl_xor(tot, 16, 64);
+    tot += __shfl_xor(tot, 32, 64);
+    return rsqrtf(tot / (float)K + eps);
+}
+
+template <int EPI, int KS>
+__global__ __launch_bounds__(256) void wf_mm_kernel(const WaveLayer *__restrict__ layers, int l_first, int s, int chunk, int B,
+                                                    int N, int d, int F, float eps, int norm_free, float alpha)
+{
+    __shared__ float part[4][16 * 16];
+    const int l = l_first + blockIdx.y, t = layer_pos(s, l, chunk);
+    const WaveLayer &Y = layers[l];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 15, g = lane >> 4;
+    constexpr int RG = 4 / KS;
+    const int rg = wave / KS, kw = wave % KS;
+    const int row0 = ((int)blockIdx.x * RG + rg) * 16;
+    const int b0 = blockIdx.z * kMmBatch;
+    const int Bn = min(kMmBatch, B - b0);
+    const int K = EPI == EPI_W2 ? F : d;
+    const bf16_t *W;        // first of this wavefront's 16 weight rows
+    const bf16_t *X;        // operand rows [2B][K]
+    if (EPI == EPI_WO) { W = (const bf16_t *)Y.W.Wo + (size_t)row0 * K; X = Y.S.op_a; }
+    else if (EPI == EPI_W1) { W = (const bf16_t *)Y.W.W1 + (size_t)row0 * K; X = Y.S.op_h; }
+    else if (EPI == EPI_W2) { W = (const bf16_t *)Y.W.W2 + (size_t)row0 * K; X = Y.S.op_u; }
+    else { W = (row0 < d ? (const bf16_t *)Y.W.Wk + (size_t)row0 * K : (const bf16_t *)Y.W.Wv + (size_t)(row0 - d) * K); X = Y.S.op_z; }
+    const int klen = K / KS, kbeg = kw * klen;
+    const bf16_t *wr = W + (size_t)col * K + kbeg + 16 * g;
+    const bf16_t *xh = X + (size_t)(2 * (b0 + min(col, Bn - 1))) * K + kbeg + 16 * g;   // columns beyond Bn repeat the last row
+    const bf16_t *xl = xh + K;
+    const bool do_norm = !norm_free && (EPI == EPI_W1 || EPI == EPI_KV);
+    float rscale = 1.f;
+    if (do_norm) rscale = rms_scale_from_parts((EPI == EPI_W1 ? Y.S.ssq_h : Y.S.ssq_z) + (size_t)b0 * (d / 16), min(col, Bn - 1), g, d / 16, d, eps);
+
+    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    // one step pair: 64 contraction indices (two weight fragments, four instructions)
+#define RT_WF_MM_PAIR(kk)                                                   \
+    {                                                                       \
+        Frag a0, a1, h0, h1, l0, l1;                                        \
+        a0.u = *reinterpret_cast<const uint4 *>(wr + (kk));                 \
+        a1.u = *reinterpret_cast<const uint4 *>(wr + (kk) + 8);             \
+        h0.u = *reinterpret_cast<const uint4 *>(xh + (kk));                 \
+        h1.u = *reinterpret_cast<const uint4 *>(xh + (kk) + 8);             \
+        l0.u = *reinterpret_cast<const uint4 *>(xl + (kk));                 \
+        l1.u = *reinterpret_cast<const uint4 *>(xl + (kk) + 8);             \
+        acc = mfma16(a0, l0, acc);                                          \
+        acc = mfma16(a1, l1, acc);                                          \
+        acc = mfma16(a0, h0, acc);                                          \
+        acc = mfma16(a1, h1, acc);                                          \
+    }
+    int k = 0;
+    for (; k + 256 <= klen; k += 256) {   // four pairs at a time: eight 16-byte weight loads in flight per lane
+        RT_WF_MM_PAIR(k) RT_WF_MM_PAIR(k + 64) RT_WF_MM_PAIR(k + 128) RT_WF_MM_PAIR(k + 192)
+    }
+    for (; k < klen; k += 64) RT_WF_MM_PAIR(k)
+#undef RT_WF_MM_PAIR
+    if (KS > 1) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) part[wave][(4 * g + r) * 16 + col] = acc[r];
+        __syncthreads();
+        if (kw != 0) return;
+#pragma unroll
+        for (int j = 1; j < KS; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) acc[r] += part[wave + j][(4 * g + r) * 16 + col];
+    }
+    // lane: outputs (rows row0 + 4g .. + 3, batch row b0 + col)
+    const bool live = col < Bn;
+    const int b = b0 + min(col, Bn - 1), o = row0 + 4 * g;
+    float v[4] = {acc[0] * rscale, acc[1] * rscale, acc[2] * rscale, acc[3] * rscale};
+    if (EPI == EPI_WO || EPI == EPI_W2) {
+        float gn[4] = {1.f, 1.f, 1.f, 1.f}, ss = 0.f;
+        const bf16_t *gp = (const bf16_t *)(EPI == EPI_WO ? Y.W.g_mlp : Y.W.g_kv);
+        if (gp && !norm_free) {
+            const uint2 gg = *reinterpret_cast<const uint2 *>(gp + o);
+            gn[0] = __uint_as_float(gg.x << 16); gn[1] = __uint_as_float(gg.x & 0xFFFF0000u);
+            gn[2] = __uint_as_float(gg.y << 16); gn[3] = __uint_as_float(gg.y & 0xFFFF0000u);
+        }
+        float res[4];
+        if (EPI == EPI_WO) {
+            const uint2 xr = *reinterpret_cast<const uint2 *>((const bf16_t *)Y.x + ((size_t)b * N + t) * d + o);
+            res[0] = __uint_as_float(xr.x << 16); res[1] = __uint_as_float(xr.x & 0xFFFF0000u);
+            res[2] = __uint_as_float(xr.y << 16); res[3] = __uint_as_float(xr.y & 0xFFFF0000u);
+        } else {
+            const float4 hr = *reinterpret_cast<const float4 *>(Y.S.h + (size_t)b * d + o);
+            res[0] = hr.x; res[1] = hr.y; res[2] = hr.z; res[3] = hr.w;
+        }
+        float gv[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { v[r] = res[r] + alpha * v[r]; ss = fmaf(v[r], v[r], ss); gv[r] = v[r] * gn[r]; }
+        if (!live) ss = 0.f;
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (live) {
+            if (EPI == EPI_WO) {
+                *reinterpret_cast<float4 *>(Y.S.h + (size_t)b * d + o) = make_float4(v[0], v[1], v[2], v[3]);
+                split_store4(Y.S.op_h, (size_t)(2 * b) * d + o, (size_t)(2 * b + 1) * d + o, gv);
+                if (g == 0) Y.S.ssq_h[(size_t)b * (d / 16) + row0 / 16] = ss;
+            } else {
+                *reinterpret_cast<uint2 *>((bf16_t *)Y.y + ((size_t)b * N + t) * d + o) =
+                    make_uint2(pack_bf16(v[0], v[1]), pack_bf16(v[2], v[3]));
+                split_store4(Y.S.op_z, (size_t)(2 * b) * d + o, (size_t)(2 * b + 1) * d + o, gv);
+                if (g == 0) Y.S.ssq_z[(size_t)b * (d / 16) + row0 / 16] = ss;
+            }
+        }
+    } else if (EPI == EPI_W1) {
+        if (live) {
+            float u[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) u[r] = gelu_erf(v[r]);
+            split_store4(Y.S.op_u, (size_t)(2 * b) * F + o, (size_t)(2 * b + 1) * F + o, u);
+        }
+    } else {
+        if (live) *reinterpret_cast<float4 *>(Y.S.kv_raw + (size_t)b * 2 * d + o) = make_float4(v[0], v[1], v[2], v[3]);
     }
 }
 
@@ -203,6 +353,32 @@ static hipError_t wf_cross_launch(const LayerDims &D, const WaveLayer *dev_layer
     return hipGetLastError();
 }
 
+// Launches one of the four matrix-core products with the contraction split over ks wavefronts.
+template <int EPI>
+static void mm_launch(int ks, int n_out, unsigned nl, unsigned bt, hipStream_t st, const WaveLayer *dev_layers, int l0, int s,
+                      int chunk, const LayerDims &D)
+{
+    const dim3 grid((unsigned)(n_out / (16 * 4 / ks)), nl, bt);
+    if (ks == 4)
+        hipLaunchKernelGGL((wf_mm_kernel<EPI, 4>), grid, dim3(256), 0, st, dev_layers, l0, s, chunk, D.B, D.N, D.d, D.F, D.eps,
+                           D.norm_free, D.alpha);
+    else if (ks == 2)
+        hipLaunchKernelGGL((wf_mm_kernel<EPI, 2>), grid, dim3(256), 0, st, dev_layers, l0, s, chunk, D.B, D.N, D.d, D.F, D.eps,
+                           D.norm_free, D.alpha);
+    else
+        hipLaunchKernelGGL((wf_mm_kernel<EPI, 1>), grid, dim3(256), 0, st, dev_layers, l0, s, chunk, D.B, D.N, D.d, D.F, D.eps,
+                           D.norm_free, D.alpha);
+}
+// largest split in {want, .., 1} such that every wavefront's share of the contraction is a multiple of 64 and the
+// workgroup's rows (16 * 4 / ks) divide n_out
+static int mm_split(int want, int K, int n_out)
+{
+    int ks = want;
+    while (ks > 1 && (K % (64 * ks) != 0)) ks >>= 1;
+    while (n_out % (16 * 4 / ks) != 0 && ks < 4 && K % (64 * ks * 2) == 0) ks <<= 1;
+    return ks;
+}
+
 template <typename T, bool HP, int KSd, int KSF>
 static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layers, const WaveLayer *host_layers, int L, int chunk,
                                   bool mfma, hipStream_t st)
@@ -213,6 +389,10 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
     const int far_rel = log2_chunk - D.log2_pmin;
     const unsigned bt = (unsigned)((B + kBatchTile - 1) / kBatchTile);
     constexpr int rows_d = (4 / KSd) * kGemvRows, rows_F = (4 / KSF) * kGemvRows;   // output rows per workgroup
+    // matrix-core products: every row count must split into workgroups of 16 * 4 / ks rows
+    const int ks_wo = mm_split(4, d, d), ks_w1 = mm_split(1, d, F), ks_w2 = mm_split(4, F, d), ks_kv = mm_split(2, d, 2 * d);
+    const bool use_mm = HP && d % 64 == 0 && F % 64 == 0 && d % (16 * 4 / ks_wo) == 0 && F % (16 * 4 / ks_w1) == 0 &&
+                        d % (16 * 4 / ks_w2) == 0 && (2 * d) % (16 * 4 / ks_kv) == 0;
     const int n_steps = N + (L - 1) * chunk;
     for (int s = 0; s < n_steps; ++s) {
         // active layers: 0 <= s - l * chunk < N
@@ -236,6 +416,13 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
         }
         hipLaunchKernelGGL((wf_merge_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, log2_chunk, BH, D.H,
                            D.p_min, D.log2_pmin, D.scale);
+        if (HP && use_mm) {
+            const unsigned bt16 = (unsigned)((B + kMmBatch - 1) / kMmBatch);
+            mm_launch<EPI_WO>(ks_wo, d, nl, bt16, st, dev_layers, l0, s, chunk, D);
+            mm_launch<EPI_W1>(ks_w1, F, nl, bt16, st, dev_layers, l0, s, chunk, D);
+            mm_launch<EPI_W2>(ks_w2, d, nl, bt16, st, dev_layers, l0, s, chunk, D);
+            mm_launch<EPI_KV>(ks_kv, 2 * d, nl, bt16, st, dev_layers, l0, s, chunk, D);
+        } else {
         hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_WO, KSd>), dim3((d + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st, dev_layers,
                            l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
         hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_W1, KSd>), dim3((F + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st, dev_layers,
@@ -244,6 +431,7 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
                            l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
         hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_KV, KSd>), dim3((2 * d + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st,
                            dev_layers, l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
+        }
         hipLaunchKernelGGL((wf_finalize_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, B, D.H, d, D.eps,
                            D.norm_free);
         e = hipGetLastError();
