@@ -124,16 +124,26 @@ __device__ __forceinline__ float rms_scale_from_parts(const float *__restrict__ 
     return rsqrtf(tot / (float)K + eps);
 }
 
-template <int EPI, int KS>
-__global__ __launch_bounds__(256) void wf_mm_kernel(const WaveLayer *__restrict__ layers, int l_first, int s, int chunk, int B,
-                                                    int N, int d, int F, float eps, int norm_free, float alpha)
+// NW wavefronts per workgroup, KS of them share 16 rows: 16 * NW / KS rows per workgroup.  XL: the operand rows of
+// the batch tile are staged in LDS once per workgroup (row stride K + 8 elements: the rows of a 16-lane group
+// then sit in different banks) instead of being fetched through the vector cache by every wavefront.
+// Weight fragments are fetched one block of 256 contraction indices ahead of the instructions that use them.
+// EPI_KV needs NW / KS = 4: a workgroup is then one head of k or of v, and the epilogue finishes the position
+// (qkRMS of the key, persistent pair of (l, t) in place, remainder keys and transposed values for the tiles).
+// Dynamic LDS: NW KB of partial tiles, 256 B of per-head sums, then the operand rows.
+template <int EPI, int KS, int NW, bool XL>
+__global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restrict__ layers, int l_first, int s, int chunk, int B,
+                                                        int N, int d, int F, int H, float eps, int norm_free, float alpha)
 {
-    __shared__ float part[4][16 * 16];
+    extern __shared__ __align__(16) unsigned char wf_mm_smem[];
+    float(*part)[16 * 16] = reinterpret_cast<float(*)[16 * 16]>(wf_mm_smem);
+    float *hss = reinterpret_cast<float *>(wf_mm_smem + NW * 1024);
+    bf16_t *xs = reinterpret_cast<bf16_t *>(wf_mm_smem + NW * 1024 + 256);
     const int l = l_first + blockIdx.y, t = layer_pos(s, l, chunk);
     const WaveLayer &Y = layers[l];
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, g = lane >> 4;
-    constexpr int RG = 4 / KS;
+    constexpr int RG = NW / KS;
     const int rg = wave / KS, kw = wave % KS;
     const int row0 = ((int)blockIdx.x * RG + rg) * 16;
     const int b0 = blockIdx.z * kMmBatch;
@@ -146,50 +156,81 @@ __global__ __launch_bounds__(256) void wf_mm_kernel(const WaveLayer *__restrict_
     else if (EPI == EPI_W2) { W = (const bf16_t *)Y.W.W2 + (size_t)row0 * K; X = Y.S.op_u; }
     else { W = (row0 < d ? (const bf16_t *)Y.W.Wk + (size_t)row0 * K : (const bf16_t *)Y.W.Wv + (size_t)(row0 - d) * K); X = Y.S.op_z; }
     const int klen = K / KS, kbeg = kw * klen;
-    const bf16_t *wr = W + (size_t)col * K + kbeg + 16 * g;
-    const bf16_t *xh = X + (size_t)(2 * (b0 + min(col, Bn - 1))) * K + kbeg + 16 * g;   // columns beyond Bn repeat the last row
-    const bf16_t *xl = xh + K;
+    // fragment of step pair p: first instruction k = 64 p + 8 g + (0..7), second 32 further: per row 64 contiguous bytes each
+    const bf16_t *wr = W + (size_t)col * K + kbeg + 8 * g;
+    const int cb = min(col, Bn - 1);   // columns beyond Bn repeat the last batch row (their results are dropped)
+    const int xld = XL ? K + 8 : K;
+    const bf16_t *xh = (XL ? xs + (size_t)(2 * cb) * xld : X + (size_t)(2 * (b0 + cb)) * K) + kbeg + 8 * g;
+    const bf16_t *xl = xh + xld;
+
+    uint4 wa[8], wb[8];
+#define RT_WF_LOADW(buf, kk)                                                                   \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j)                                              \
+    {                                                                                          \
+        buf[2 * j] = *reinterpret_cast<const uint4 *>(wr + (kk) + 64 * j);                     \
+        buf[2 * j + 1] = *reinterpret_cast<const uint4 *>(wr + (kk) + 64 * j + 32);            \
+    }
+#define RT_WF_PAIR(a0v, a1v, kk)                                                               \
+    {                                                                                          \
+        Frag a0, a1, h0, h1, l0, l1;                                                           \
+        a0.u = a0v; a1.u = a1v;                                                                \
+        h0.u = *reinterpret_cast<const uint4 *>(xh + (kk));                                    \
+        h1.u = *reinterpret_cast<const uint4 *>(xh + (kk) + 32);                               \
+        l0.u = *reinterpret_cast<const uint4 *>(xl + (kk));                                    \
+        l1.u = *reinterpret_cast<const uint4 *>(xl + (kk) + 32);                               \
+        acc = mfma16(a0, l0, acc);                                                             \
+        acc = mfma16(a1, l1, acc);                                                             \
+        acc = mfma16(a0, h0, acc);                                                             \
+        acc = mfma16(a1, h1, acc);                                                             \
+    }
+#define RT_WF_COMPUTE(buf, kk) \
+    _Pragma("unroll") for (int j = 0; j < 4; ++j) RT_WF_PAIR(buf[2 * j], buf[2 * j + 1], (kk) + 64 * j)
+
+    const int nfull = klen / 256;
+    if (nfull > 0) { RT_WF_LOADW(wa, 0) }
     const bool do_norm = !norm_free && (EPI == EPI_W1 || EPI == EPI_KV);
     float rscale = 1.f;
-    if (do_norm) rscale = rms_scale_from_parts((EPI == EPI_W1 ? Y.S.ssq_h : Y.S.ssq_z) + (size_t)b0 * (d / 16), min(col, Bn - 1), g, d / 16, d, eps);
-
+    if (do_norm) rscale = rms_scale_from_parts((EPI == EPI_W1 ? Y.S.ssq_h : Y.S.ssq_z) + (size_t)b0 * (d / 16), cb, g, d / 16, d, eps);
+    if (XL) {
+        const int ppr = K / 8;   // 16-byte pieces per operand row
+        for (int p = tid; p < 2 * Bn * ppr; p += 64 * NW) {
+            const int r = p / ppr, c = p - r * ppr;
+            *reinterpret_cast<uint4 *>(xs + (size_t)r * xld + c * 8) =
+                *reinterpret_cast<const uint4 *>(X + (size_t)(2 * b0 + r) * K + c * 8);
+        }
+        __syncthreads();
+    }
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    // one step pair: 64 contraction indices (two weight fragments, four instructions)
-#define RT_WF_MM_PAIR(kk)                                                   \
-    {                                                                       \
-        Frag a0, a1, h0, h1, l0, l1;                                        \
-        a0.u = *reinterpret_cast<const uint4 *>(wr + (kk));                 \
-        a1.u = *reinterpret_cast<const uint4 *>(wr + (kk) + 8);             \
-        h0.u = *reinterpret_cast<const uint4 *>(xh + (kk));                 \
-        h1.u = *reinterpret_cast<const uint4 *>(xh + (kk) + 8);             \
-        l0.u = *reinterpret_cast<const uint4 *>(xl + (kk));                 \
-        l1.u = *reinterpret_cast<const uint4 *>(xl + (kk) + 8);             \
-        acc = mfma16(a0, l0, acc);                                          \
-        acc = mfma16(a1, l1, acc);                                          \
-        acc = mfma16(a0, h0, acc);                                          \
-        acc = mfma16(a1, h1, acc);                                          \
+    for (int i = 0; i < nfull; i += 2) {
+        if (i + 1 < nfull) { RT_WF_LOADW(wb, (i + 1) * 256) }
+        RT_WF_COMPUTE(wa, i * 256)
+        if (i + 1 < nfull) {
+            if (i + 2 < nfull) { RT_WF_LOADW(wa, (i + 2) * 256) }
+            RT_WF_COMPUTE(wb, (i + 1) * 256)
+        }
     }
-    int k = 0;
-    for (; k + 256 <= klen; k += 256) {   // four pairs at a time: eight 16-byte weight loads in flight per lane
-        RT_WF_MM_PAIR(k) RT_WF_MM_PAIR(k + 64) RT_WF_MM_PAIR(k + 128) RT_WF_MM_PAIR(k + 192)
-    }
-    for (; k < klen; k += 64) RT_WF_MM_PAIR(k)
-#undef RT_WF_MM_PAIR
+    for (int k = nfull * 256; k < klen; k += 64)
+        RT_WF_PAIR(*reinterpret_cast<const uint4 *>(wr + k), *reinterpret_cast<const uint4 *>(wr + k + 32), k)
+#undef RT_WF_LOADW
+#undef RT_WF_PAIR
+#undef RT_WF_COMPUTE
     if (KS > 1) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) part[wave][(4 * g + r) * 16 + col] = acc[r];
         __syncthreads();
-        if (kw != 0) return;
+        if (kw == 0) {
 #pragma unroll
-        for (int j = 1; j < KS; ++j)
+            for (int j = 1; j < KS; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) acc[r] += part[wave + j][(4 * g + r) * 16 + col];
+                for (int r = 0; r < 4; ++r) acc[r] += part[wave + j][(4 * g + r) * 16 + col];
+        }
     }
-    // lane: outputs (rows row0 + 4g .. + 3, batch row b0 + col)
-    const bool live = col < Bn;
-    const int b = b0 + min(col, Bn - 1), o = row0 + 4 * g;
+    // wavefronts with kw == 0 hold the tile: lane = outputs (rows row0 + 4g .. + 3, batch row b0 + col)
+    const bool live = col < Bn && kw == 0;
+    const int b = b0 + cb, o = row0 + 4 * g;
     float v[4] = {acc[0] * rscale, acc[1] * rscale, acc[2] * rscale, acc[3] * rscale};
     if (EPI == EPI_WO || EPI == EPI_W2) {
+        if (kw != 0) return;   // no barrier below on this path
         float gn[4] = {1.f, 1.f, 1.f, 1.f}, ss = 0.f;
         const bf16_t *gp = (const bf16_t *)(EPI == EPI_WO ? Y.W.g_mlp : Y.W.g_kv);
         if (gp && !norm_free) {
@@ -232,7 +273,39 @@ __global__ __launch_bounds__(256) void wf_mm_kernel(const WaveLayer *__restrict_
             split_store4(Y.S.op_u, (size_t)(2 * b) * F + o, (size_t)(2 * b + 1) * F + o, u);
         }
     } else {
-        if (live) *reinterpret_cast<float4 *>(Y.S.kv_raw + (size_t)b * 2 * d + o) = make_float4(v[0], v[1], v[2], v[3]);
+        // the workgroup is head hh of [k heads | v heads]; this wavefront holds head dimensions 16 rg + 4g .. + 3
+        const int hh = blockIdx.x;
+        const bool is_k = hh < H;
+        if (is_k && !norm_free) {
+            float ss = live ? (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]) : 0.f;
+            ss += __shfl_xor(ss, 16, 64);
+            ss += __shfl_xor(ss, 32, 64);
+            if (kw == 0 && g == 0) hss[rg * 16 + col] = ss;
+            __syncthreads();   // is_k is uniform over the workgroup
+            const float tot = (hss[col] + hss[16 + col]) + (hss[32 + col] + hss[48 + col]);
+            const float sc = rsqrtf(tot / (float)kHeadDim + eps);
+            const bf16_t *gk = (const bf16_t *)Y.W.g_k;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[r] *= sc * (gk ? bf16_to_f32(gk[hh * kHeadDim + 16 * rg + 4 * g + r]) : 1.f);
+        }
+        if (live) {
+            const int h = is_k ? hh : hh - H, bh = b * H + h, BH = B * H;
+            const size_t off = ((size_t)t * BH + bh) * kHeadDim + 16 * rg + 4 * g;
+            const uint32_t p01 = pack_bf16(v[0], v[1]), p23 = pack_bf16(v[2], v[3]);
+            if (is_k) {
+                *reinterpret_cast<uint2 *>((bf16_t *)Y.K + off) = make_uint2(p01, p23);
+                const float r0 = v[0] - __uint_as_float(p01 << 16), r1 = v[1] - __uint_as_float(p01 & 0xFFFF0000u);
+                const float r2 = v[2] - __uint_as_float(p23 << 16), r3 = v[3] - __uint_as_float(p23 & 0xFFFF0000u);
+                *reinterpret_cast<uint2 *>(Y.S.Klo + off) = make_uint2(pack_bf16(r0, r1), pack_bf16(r2, r3));
+            } else {
+                *reinterpret_cast<uint2 *>((bf16_t *)Y.V + off) = make_uint2(p01, p23);
+                bf16_t *vt = Y.S.VT + ((size_t)bh * kHeadDim + 16 * rg + 4 * g) * Y.S.vt_stride + t;
+                vt[0] = (bf16_t)(p01 & 0xFFFFu);
+                vt[(size_t)Y.S.vt_stride] = (bf16_t)(p01 >> 16);
+                vt[2 * (size_t)Y.S.vt_stride] = (bf16_t)(p23 & 0xFFFFu);
+                vt[3 * (size_t)Y.S.vt_stride] = (bf16_t)(p23 >> 16);
+            }
+        }
     }
 }
 
@@ -353,30 +426,34 @@ static hipError_t wf_cross_launch(const LayerDims &D, const WaveLayer *dev_layer
     return hipGetLastError();
 }
 
-// Launches one of the four matrix-core products with the contraction split over ks wavefronts.
-template <int EPI>
-static void mm_launch(int ks, int n_out, unsigned nl, unsigned bt, hipStream_t st, const WaveLayer *dev_layers, int l0, int s,
-                      int chunk, const LayerDims &D)
+// Launches one of the four matrix-core products.  Shapes: WO and W2 split the contraction over the four wavefronts
+// of a workgroup (16 rows per workgroup), W1 does not (64 rows), [Wk; Wv] splits it in two with eight wavefronts (64
+// rows = one head).  The operand rows go through LDS when they fit beside two more workgroups on a compute unit.
+constexpr size_t kMmMaxLds = 72 * 1024;
+template <int EPI, int KS, int NW>
+static hipError_t mm_launch(int n_out, unsigned nl, hipStream_t st, const WaveLayer *dev_layers, int l0, int s, int chunk,
+                            const LayerDims &D)
 {
-    const dim3 grid((unsigned)(n_out / (16 * 4 / ks)), nl, bt);
-    if (ks == 4)
-        hipLaunchKernelGGL((wf_mm_kernel<EPI, 4>), grid, dim3(256), 0, st, dev_layers, l0, s, chunk, D.B, D.N, D.d, D.F, D.eps,
-                           D.norm_free, D.alpha);
-    else if (ks == 2)
-        hipLaunchKernelGGL((wf_mm_kernel<EPI, 2>), grid, dim3(256), 0, st, dev_layers, l0, s, chunk, D.B, D.N, D.d, D.F, D.eps,
-                           D.norm_free, D.alpha);
-    else
-        hipLaunchKernelGGL((wf_mm_kernel<EPI, 1>), grid, dim3(256), 0, st, dev_layers, l0, s, chunk, D.B, D.N, D.d, D.F, D.eps,
-                           D.norm_free, D.alpha);
-}
-// largest split in {want, .., 1} such that every wavefront's share of the contraction is a multiple of 64 and the
-// workgroup's rows (16 * 4 / ks) divide n_out
-static int mm_split(int want, int K, int n_out)
-{
-    int ks = want;
-    while (ks > 1 && (K % (64 * ks) != 0)) ks >>= 1;
-    while (n_out % (16 * 4 / ks) != 0 && ks < 4 && K % (64 * ks * 2) == 0) ks <<= 1;
-    return ks;
+    const int K = EPI == EPI_W2 ? D.F : D.d;
+    const unsigned bt = (unsigned)((D.B + kMmBatch - 1) / kMmBatch);
+    const int Bt = D.B < kMmBatch ? D.B : kMmBatch;
+    const size_t base = (size_t)NW * 1024 + 256, xbytes = (size_t)2 * Bt * (K + 8) * 2;
+    const dim3 grid((unsigned)(n_out / (16 * NW / KS)), nl, bt);
+    if (base + xbytes <= kMmMaxLds) {
+        static bool raised = false;   // more than the default 64 KB of dynamic LDS needs the attribute once
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute((const void *)wf_mm_kernel<EPI, KS, NW, true>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMmMaxLds);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+        hipLaunchKernelGGL((wf_mm_kernel<EPI, KS, NW, true>), grid, dim3(64 * NW), base + xbytes, st, dev_layers, l0, s, chunk,
+                           D.B, D.N, D.d, D.F, D.H, D.eps, D.norm_free, D.alpha);
+    } else {
+        hipLaunchKernelGGL((wf_mm_kernel<EPI, KS, NW, false>), grid, dim3(64 * NW), base, st, dev_layers, l0, s, chunk, D.B, D.N,
+                           D.d, D.F, D.H, D.eps, D.norm_free, D.alpha);
+    }
+    return hipSuccess;
 }
 
 template <typename T, bool HP, int KSd, int KSF>
@@ -389,10 +466,8 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
     const int far_rel = log2_chunk - D.log2_pmin;
     const unsigned bt = (unsigned)((B + kBatchTile - 1) / kBatchTile);
     constexpr int rows_d = (4 / KSd) * kGemvRows, rows_F = (4 / KSF) * kGemvRows;   // output rows per workgroup
-    // matrix-core products: every row count must split into workgroups of 16 * 4 / ks rows
-    const int ks_wo = mm_split(4, d, d), ks_w1 = mm_split(1, d, F), ks_w2 = mm_split(4, F, d), ks_kv = mm_split(2, d, 2 * d);
-    const bool use_mm = HP && d % 64 == 0 && F % 64 == 0 && d % (16 * 4 / ks_wo) == 0 && F % (16 * 4 / ks_w1) == 0 &&
-                        d % (16 * 4 / ks_w2) == 0 && (2 * d) % (16 * 4 / ks_kv) == 0;
+    // matrix-core products: every wavefront's share of a contraction must be a multiple of 64 (d and F multiples of 256)
+    const bool use_mm = HP && d % 256 == 0 && F % 256 == 0;
     const int n_steps = N + (L - 1) * chunk;
     for (int s = 0; s < n_steps; ++s) {
         // active layers: 0 <= s - l * chunk < N
@@ -417,11 +492,11 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
         hipLaunchKernelGGL((wf_merge_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, log2_chunk, BH, D.H,
                            D.p_min, D.log2_pmin, D.scale);
         if (HP && use_mm) {
-            const unsigned bt16 = (unsigned)((B + kMmBatch - 1) / kMmBatch);
-            mm_launch<EPI_WO>(ks_wo, d, nl, bt16, st, dev_layers, l0, s, chunk, D);
-            mm_launch<EPI_W1>(ks_w1, F, nl, bt16, st, dev_layers, l0, s, chunk, D);
-            mm_launch<EPI_W2>(ks_w2, d, nl, bt16, st, dev_layers, l0, s, chunk, D);
-            mm_launch<EPI_KV>(ks_kv, 2 * d, nl, bt16, st, dev_layers, l0, s, chunk, D);
+            if ((e = mm_launch<EPI_WO, 4, 4>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
+            if ((e = mm_launch<EPI_W1, 1, 4>(F, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
+            if ((e = mm_launch<EPI_W2, 4, 4>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
+            // the epilogue of this one also finishes the position (persistent pair and its copies)
+            if ((e = mm_launch<EPI_KV, 2, 8>(2 * d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
         } else {
         hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_WO, KSd>), dim3((d + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st, dev_layers,
                            l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
@@ -431,9 +506,9 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
                            l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
         hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_KV, KSd>), dim3((2 * d + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st,
                            dev_layers, l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
-        }
         hipLaunchKernelGGL((wf_finalize_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, B, D.H, d, D.eps,
                            D.norm_free);
+        }
         e = hipGetLastError();
         if (e != hipSuccess) return e;
         // a block inside the chunk closes: s + 1 positions of layer 0 are finished, every layer is at the same offset
