@@ -5,6 +5,7 @@
 #include "rt_persistent.h"
 
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <string>
@@ -31,6 +32,7 @@ struct rt_ctx {
     int stack_L = 0, stack_chunk = 0;
     std::vector<Scratch> stack_S;
     WaveLayer *stack_dev = nullptr;
+    WaveStreams wave_streams = {};   // st[1..], ev[..] created on first use
     // cached HIP graph of one stepwise prefill
     hipGraphExec_t graph_exec = nullptr;
     hipStream_t capture_stream = nullptr;  // the legacy default stream cannot be captured
@@ -72,7 +74,7 @@ static size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
 // Lays one scratch set out from `base` (may be null: sizes only) and returns its size in bytes.
 static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_t d, size_t F, size_t H, size_t E, bool mfma,
-                             int levels, int slots)
+                             int levels, int slots, bool packed_weights = false)
 {
     memset(&S, 0, sizeof(S));
     S.levels = levels;
@@ -92,6 +94,8 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
     const size_t oopa = carve(2 * Bm * d * 2), ooph = carve(2 * Bm * d * 2), oopz = carve(2 * Bm * d * 2);
     const size_t oopu = carve(2 * Bm * F * 2);
     const size_t osh = carve(Bm * (d / 16 + 1) * 4), osz = carve(Bm * (d / 16 + 1) * 4);
+    const size_t owo = packed_weights ? carve(d * d * 2) : 0, ow1 = packed_weights ? carve(F * d * 2) : 0;
+    const size_t ow2 = packed_weights ? carve(d * F * 2) : 0, owkv = packed_weights ? carve(2 * d * d * 2) : 0;
     if (base) {
         char *p = base;
         S.Q = p + oQ; S.Kt = p + oKt; S.Vt = p + oVt;
@@ -107,6 +111,10 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
         S.op_a = (bf16_t *)(p + oopa); S.op_h = (bf16_t *)(p + ooph); S.op_z = (bf16_t *)(p + oopz);
         S.op_u = (bf16_t *)(p + oopu);
         S.ssq_h = (float *)(p + osh); S.ssq_z = (float *)(p + osz);
+        if (packed_weights) {
+            S.wp_o = (bf16_t *)(p + owo); S.wp_1 = (bf16_t *)(p + ow1); S.wp_2 = (bf16_t *)(p + ow2);
+            S.wp_kv = (bf16_t *)(p + owkv);
+        }
     }
     return off;
 }
@@ -240,6 +248,10 @@ rt_status rt_destroy(rt_ctx *c)
     persistent_destroy(c->persist);
     if (c->stack_slab) (void)hipFree(c->stack_slab);
     if (c->stack_dev) (void)hipFree(c->stack_dev);
+    for (int g = 0; g < kMaxWaveStreams; ++g) {
+        if (g > 0 && c->wave_streams.st[g]) (void)hipStreamDestroy(c->wave_streams.st[g]);
+        if (c->wave_streams.ev[g]) (void)hipEventDestroy(c->wave_streams.ev[g]);
+    }
     hipError_t e = hipFree(c->slab);
     delete c;
     return e == hipSuccess ? RT_OK : RT_ERR_HIP;
@@ -524,8 +536,9 @@ static rt_status stack_workspace(rt_ctx *c, int L, int chunk)
     if (slots < 64) slots = 64;
     const int levels = ilog2(chunk) - c->base.log2_pmin + (cfg.max_seq + slots - 1) / slots;
     Scratch tmp;
+    const bool packed = wavefront_uses_matrix_cores(cfg.d_model, cfg.d_hidden, c->use_mfma);
     const size_t one = align_up(layout_scratch(tmp, nullptr, cfg.max_batch, cfg.max_seq, cfg.d_model, cfg.d_hidden, cfg.n_heads, E,
-                                               c->use_mfma, levels, slots), 256);
+                                               c->use_mfma, levels, slots, packed), 256);
     hipError_t e = hipMalloc(&c->stack_slab, one * L);
     if (e != hipSuccess) {
         (void)hipGetLastError();
@@ -542,7 +555,7 @@ static rt_status stack_workspace(rt_ctx *c, int L, int chunk)
     c->stack_S.resize(L);
     for (int l = 0; l < L; ++l)
         layout_scratch(c->stack_S[l], (char *)c->stack_slab + one * l, cfg.max_batch, cfg.max_seq, cfg.d_model, cfg.d_hidden,
-                       cfg.n_heads, E, c->use_mfma, levels, slots);
+                       cfg.n_heads, E, c->use_mfma, levels, slots, packed);
     c->stack_bytes = one * L + sizeof(WaveLayer) * L;
     c->stack_L = L;
     c->stack_chunk = chunk;
@@ -594,9 +607,21 @@ extern "C" rt_status rt_stack_prefill(rt_ctx *c, const rt_layer_weights *layers,
     LayerDims D = c->base;
     D.B = B; D.N = N; D.kv_cap = kv_cap;
     c->engine = "wavefront";
+    // groups of layers on streams of their own (RT_WAVE_STREAMS = 1..4 overrides the default of 2)
+    WaveStreams &WS = c->wave_streams;
+    int want = 2;
+    if (const char *ev = getenv("RT_WAVE_STREAMS")) want = atoi(ev);
+    if (want < 1) want = 1;
+    if (want > kMaxWaveStreams) want = kMaxWaveStreams;
+    WS.st[0] = c->stream;
+    for (int g = 0; g < want; ++g) {
+        if (g > 0 && !WS.st[g]) RT_TRY(hipStreamCreateWithFlags(&WS.st[g], hipStreamNonBlocking), "hipStreamCreateWithFlags");
+        if (!WS.ev[g]) RT_TRY(hipEventCreateWithFlags(&WS.ev[g], hipEventDisableTiming), "hipEventCreateWithFlags");
+    }
+    WS.n = want;
     hipError_t e;
-    if (c->cfg.dtype == RT_BF16) e = wavefront_prefill<bf16_t>(D, c->stack_dev, host.data(), L, chunk, c->use_mfma, c->stream);
-    else e = wavefront_prefill<float>(D, c->stack_dev, host.data(), L, chunk, false, c->stream);
+    if (c->cfg.dtype == RT_BF16) e = wavefront_prefill<bf16_t>(D, c->stack_dev, host.data(), L, chunk, c->use_mfma, WS);
+    else e = wavefront_prefill<float>(D, c->stack_dev, host.data(), L, chunk, false, WS);
     if (e != hipSuccess) return fail_hip(c, e, "wavefront_prefill");
     return RT_OK;
 }

@@ -145,6 +145,10 @@ struct Scratch {
     bf16_t *op_a, *op_h, *op_z;   // [2B][d]
     bf16_t *op_u;                 // [2B][F]
     float *ssq_h, *ssq_z;         // [B][d/16]
+    // the layer's Wo, W1, W2 and [Wk; Wv] re-laid in matrix-core fragment order (or null): for rows 16R .. 16R+15 and
+    // contraction indices 64p .. 64p+63, two fragments of 64 lanes x 16 bytes, lane (col, g) of fragment f holding
+    // W[16R + col][64p + 32f + 8g .. + 7]; a wavefront's weight stream is then one contiguous run
+    bf16_t *wp_o, *wp_1, *wp_2, *wp_kv;
 };
 
 __host__ __device__ __forceinline__ size_t partial_index(int level_rel, int slot, int slots, int BH, int bh)
@@ -188,10 +192,21 @@ struct WaveLayer {
     void *K, *V;      // [kv_cap][B][H][64]
 };
 
+// Streams of the layer-wavefront engine: st[0] is the caller's, the others belong to the context (default
+// priority); ev[g] orders group g + 1 after group g (ev[0] also starts the other streams, ev[g >= 1] joins them).
+constexpr int kMaxWaveStreams = 4;
+struct WaveStreams {
+    int n;
+    hipStream_t st[kMaxWaveStreams];
+    hipEvent_t ev[kMaxWaveStreams];
+};
+
 // All layers of a stack, layer l running `chunk` positions behind layer l - 1 (rt_wavefront.hip).
 template <typename T>
 hipError_t wavefront_prefill(const LayerDims &D, const WaveLayer *dev_layers, const WaveLayer *host_layers, int L, int chunk,
-                             bool mfma, hipStream_t st);
+                             bool mfma, const WaveStreams &W);
+// whether the engine's matrix-core products cover this shape (they need the packed weight copies in the scratch)
+bool wavefront_uses_matrix_cores(int d, int F, bool mfma_bf16);
 
 // embedding lookup and final-norm + output projection of a layer stack (rt_stack.hip)
 template <typename T>

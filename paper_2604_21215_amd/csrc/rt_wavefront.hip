@@ -149,15 +149,16 @@ __global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restr
     const int b0 = blockIdx.z * kMmBatch;
     const int Bn = min(kMmBatch, B - b0);
     const int K = EPI == EPI_W2 ? F : d;
-    const bf16_t *W;        // first of this wavefront's 16 weight rows
+    const bf16_t *Wp;       // the matrix in fragment order (Scratch::wp_*)
     const bf16_t *X;        // operand rows [2B][K]
-    if (EPI == EPI_WO) { W = (const bf16_t *)Y.W.Wo + (size_t)row0 * K; X = Y.S.op_a; }
-    else if (EPI == EPI_W1) { W = (const bf16_t *)Y.W.W1 + (size_t)row0 * K; X = Y.S.op_h; }
-    else if (EPI == EPI_W2) { W = (const bf16_t *)Y.W.W2 + (size_t)row0 * K; X = Y.S.op_u; }
-    else { W = (row0 < d ? (const bf16_t *)Y.W.Wk + (size_t)row0 * K : (const bf16_t *)Y.W.Wv + (size_t)(row0 - d) * K); X = Y.S.op_z; }
+    if (EPI == EPI_WO) { Wp = Y.S.wp_o; X = Y.S.op_a; }
+    else if (EPI == EPI_W1) { Wp = Y.S.wp_1; X = Y.S.op_h; }
+    else if (EPI == EPI_W2) { Wp = Y.S.wp_2; X = Y.S.op_u; }
+    else { Wp = Y.S.wp_kv; X = Y.S.op_z; }
     const int klen = K / KS, kbeg = kw * klen;
-    // fragment of step pair p: first instruction k = 64 p + 8 g + (0..7), second 32 further: per row 64 contiguous bytes each
-    const bf16_t *wr = W + (size_t)col * K + kbeg + 8 * g;
+    // step pair p (contraction indices 64p .. 64p+63) of this wavefront's 16 rows: fragments 2p and 2p + 1, 1 KB each,
+    // the first covering k = 64p + 8g + (0..7), the second 32 further
+    const bf16_t *wr = Wp + ((size_t)(row0 / 16) * (K / 64) + kbeg / 64) * 1024 + lane * 8;
     const int cb = min(col, Bn - 1);   // columns beyond Bn repeat the last batch row (their results are dropped)
     const int xld = XL ? K + 8 : K;
     const bf16_t *xh = (XL ? xs + (size_t)(2 * cb) * xld : X + (size_t)(2 * (b0 + cb)) * K) + kbeg + 8 * g;
@@ -167,8 +168,8 @@ __global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restr
 #define RT_WF_LOADW(buf, kk)                                                                   \
     _Pragma("unroll") for (int j = 0; j < 4; ++j)                                              \
     {                                                                                          \
-        buf[2 * j] = *reinterpret_cast<const uint4 *>(wr + (kk) + 64 * j);                     \
-        buf[2 * j + 1] = *reinterpret_cast<const uint4 *>(wr + (kk) + 64 * j + 32);            \
+        buf[2 * j] = *reinterpret_cast<const uint4 *>(wr + ((kk) / 64 + j) * 1024);             \
+        buf[2 * j + 1] = *reinterpret_cast<const uint4 *>(wr + ((kk) / 64 + j) * 1024 + 512);   \
     }
 #define RT_WF_PAIR(a0v, a1v, kk)                                                               \
     {                                                                                          \
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restr
         }
     }
     for (int k = nfull * 256; k < klen; k += 64)
-        RT_WF_PAIR(*reinterpret_cast<const uint4 *>(wr + k), *reinterpret_cast<const uint4 *>(wr + k + 32), k)
+        RT_WF_PAIR(*reinterpret_cast<const uint4 *>(wr + (k / 64) * 1024), *reinterpret_cast<const uint4 *>(wr + (k / 64) * 1024 + 512), k)
 #undef RT_WF_LOADW
 #undef RT_WF_PAIR
 #undef RT_WF_COMPUTE
@@ -426,6 +427,28 @@ static hipError_t wf_cross_launch(const LayerDims &D, const WaveLayer *dev_layer
     return hipGetLastError();
 }
 
+// Re-lays n_rows x K row-major weights in fragment order (Scratch::wp_*): one thread per 16-byte piece of the output.
+__global__ __launch_bounds__(256) void wf_pack_kernel(const bf16_t *__restrict__ W, bf16_t *__restrict__ Wp, int n_rows, int K)
+{
+    const size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= (size_t)n_rows * K / 8) return;
+    const int lane = (int)(q & 63), f = (int)((q >> 6) & 1);
+    const size_t pr = q >> 7;                       // (row group, step pair)
+    const int p = (int)(pr % (size_t)(K / 64)), R = (int)(pr / (size_t)(K / 64));
+    const int col = lane & 15, g = lane >> 4;
+    *reinterpret_cast<uint4 *>(Wp + q * 8) = *reinterpret_cast<const uint4 *>(W + (size_t)(R * 16 + col) * K + 64 * p + 32 * f + 8 * g);
+}
+static void pack_launch(const void *W, bf16_t *Wp, int n_rows, int K, hipStream_t st)
+{
+    const size_t pieces = (size_t)n_rows * K / 8;
+    hipLaunchKernelGGL(wf_pack_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, (const bf16_t *)W, Wp, n_rows, K);
+}
+
+bool wavefront_uses_matrix_cores(int d, int F, bool mfma_bf16)
+{   // every wavefront's share of a contraction must be a multiple of 64 (d and F multiples of 256)
+    return mfma_bf16 && d % 256 == 0 && F % 256 == 0;
+}
+
 // Launches one of the four matrix-core products.  Shapes: WO and W2 split the contraction over the four wavefronts
 // of a workgroup (16 rows per workgroup), W1 does not (64 rows), [Wk; Wv] splits it in two with eight wavefronts (64
 // rows = one head).  The operand rows go through LDS when they fit beside two more workgroups on a compute unit.
@@ -456,9 +479,13 @@ static hipError_t mm_launch(int n_out, unsigned nl, hipStream_t st, const WaveLa
     return hipSuccess;
 }
 
+// The steps of one prefill.  The layers are dealt to W.n groups of consecutive layers, each group enqueued on its own
+// stream: a step is a chain of dependent launches, each with a serial start-up and tail, and the chains of different
+// groups fill each other's gaps.  A group's first layer enters a chunk only after the group below has finished it:
+// one event per group, recorded after every chunk's last step, awaited before the next group's chunk entry.
 template <typename T, bool HP, int KSd, int KSF>
 static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layers, const WaveLayer *host_layers, int L, int chunk,
-                                  bool mfma, hipStream_t st)
+                                  bool mfma, const WaveStreams &W)
 {
     const int B = D.B, N = D.N, d = D.d, F = D.F, BH = D.B * D.H;
     int log2_chunk = 0;
@@ -466,72 +493,106 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
     const int far_rel = log2_chunk - D.log2_pmin;
     const unsigned bt = (unsigned)((B + kBatchTile - 1) / kBatchTile);
     constexpr int rows_d = (4 / KSd) * kGemvRows, rows_F = (4 / KSF) * kGemvRows;   // output rows per workgroup
-    // matrix-core products: every wavefront's share of a contraction must be a multiple of 64 (d and F multiples of 256)
-    const bool use_mm = HP && d % 256 == 0 && F % 256 == 0;
+    const bool use_mm = HP && wavefront_uses_matrix_cores(d, F, true);
+    const int G = W.n < L ? W.n : L;
+    const int per = (L + G - 1) / G;   // layers per group
+    hipError_t e;
+    // the other streams start after everything enqueued on the caller's stream so far (inputs, layer 0's pre-pass)
+    if (G > 1) {
+        if ((e = hipEventRecord(W.ev[0], W.st[0])) != hipSuccess) return e;
+        for (int g = 1; g < G; ++g)
+            if ((e = hipStreamWaitEvent(W.st[g], W.ev[0], 0)) != hipSuccess) return e;
+    }
     const int n_steps = N + (L - 1) * chunk;
     for (int s = 0; s < n_steps; ++s) {
         // active layers: 0 <= s - l * chunk < N
-        const int l1 = s / chunk < L - 1 ? s / chunk : L - 1;
-        int l0 = s - (N - 1) > 0 ? (s - (N - 1) + chunk - 1) / chunk : 0;
-        if (l0 > l1) continue;   // between the last position of one layer and the first of the next (N not a multiple of the chunk)
-        const unsigned nl = (unsigned)(l1 - l0 + 1);
-        hipError_t e;
-        if (s % chunk == 0) {
-            // the active layers enter a chunk: queries and temporary pairs of its rows, then the far tile
-            for (int l = l0 > 1 ? l0 : 1; l <= l1; ++l) {
-                const int t = s - l * chunk;
-                const int Nc = chunk < N - t ? chunk : N - t;
-                e = Launch<T>::prepass(D, host_layers[l].W, host_layers[l].S, host_layers[l].x, B, Nc, mfma, st, (size_t)N * d, t);
+        const int a1 = s / chunk < L - 1 ? s / chunk : L - 1;
+        const int a0 = s - (N - 1) > 0 ? (s - (N - 1) + chunk - 1) / chunk : 0;
+        for (int g = 0; g < G; ++g) {
+            const int l0 = a0 > g * per ? a0 : g * per;
+            const int l1 = a1 < (g + 1) * per - 1 ? a1 : (g + 1) * per - 1;
+            if (l0 > l1) continue;
+            hipStream_t st = W.st[g];
+            const unsigned nl = (unsigned)(l1 - l0 + 1);
+            if (s % chunk == 0) {
+                // the active layers enter a chunk: the group below has finished it
+                if (g > 0 && (e = hipStreamWaitEvent(st, W.ev[g - 1], 0)) != hipSuccess) return e;
+                // queries and temporary pairs of the chunk's rows, then the far tile
+                for (int l = l0 > 1 ? l0 : 1; l <= l1; ++l) {
+                    const int t = s - l * chunk;
+                    const int Nc = chunk < N - t ? chunk : N - t;
+                    e = Launch<T>::prepass(D, host_layers[l].W, host_layers[l].S, host_layers[l].x, B, Nc, mfma, st, (size_t)N * d, t);
+                    if (e != hipSuccess) return e;
+                }
+                if (s - l0 * chunk > 0) {
+                    e = wf_cross_launch<T, HP>(D, dev_layers, l0, (int)nl, s, chunk, 1, 0, far_rel, st);
+                    if (e != hipSuccess) return e;
+                }
+            }
+            hipLaunchKernelGGL((wf_merge_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, log2_chunk, BH,
+                               D.H, D.p_min, D.log2_pmin, D.scale);
+            if (HP && use_mm) {
+                if ((e = mm_launch<EPI_WO, 4, 4>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
+                if ((e = mm_launch<EPI_W1, 1, 4>(F, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
+                if ((e = mm_launch<EPI_W2, 4, 4>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
+                // the epilogue of this one also finishes the position (persistent pair and its copies)
+                if ((e = mm_launch<EPI_KV, 2, 8>(2 * d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
+            } else {
+                hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_WO, KSd>), dim3((d + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st,
+                                   dev_layers, l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
+                hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_W1, KSd>), dim3((F + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st,
+                                   dev_layers, l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
+                hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_W2, KSF>), dim3((d + rows_F - 1) / rows_F, nl, bt), dim3(256), 0, st,
+                                   dev_layers, l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
+                hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_KV, KSd>), dim3((2 * d + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st,
+                                   dev_layers, l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
+                hipLaunchKernelGGL((wf_finalize_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, B, D.H, d,
+                                   D.eps, D.norm_free);
+            }
+            if ((e = hipGetLastError()) != hipSuccess) return e;
+            // a block inside the chunk closes: s + 1 positions of layer 0 are finished, every layer is at the same offset
+            const int t1 = s + 1;
+            const int P = t1 & -t1;
+            if (P >= D.p_min && P < chunk) {
+                e = wf_cross_launch<T, HP>(D, dev_layers, l0, (int)nl, t1, chunk, 0, P, far_rel, st);
                 if (e != hipSuccess) return e;
             }
-            if (s - l0 * chunk > 0) {
-                e = wf_cross_launch<T, HP>(D, dev_layers, l0, (int)nl, s, chunk, 1, 0, far_rel, st);
-                if (e != hipSuccess) return e;
-            }
+            // last step of a chunk (or of the sequence): the group above may enter it
+            if (g + 1 < G && ((s + 1) % chunk == 0 || s - l1 * chunk == N - 1))
+                if ((e = hipEventRecord(W.ev[g], st)) != hipSuccess) return e;
         }
-        hipLaunchKernelGGL((wf_merge_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, log2_chunk, BH, D.H,
-                           D.p_min, D.log2_pmin, D.scale);
-        if (HP && use_mm) {
-            if ((e = mm_launch<EPI_WO, 4, 4>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
-            if ((e = mm_launch<EPI_W1, 1, 4>(F, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
-            if ((e = mm_launch<EPI_W2, 4, 4>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
-            // the epilogue of this one also finishes the position (persistent pair and its copies)
-            if ((e = mm_launch<EPI_KV, 2, 8>(2 * d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
-        } else {
-        hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_WO, KSd>), dim3((d + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st, dev_layers,
-                           l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
-        hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_W1, KSd>), dim3((F + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st, dev_layers,
-                           l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
-        hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_W2, KSF>), dim3((d + rows_F - 1) / rows_F, nl, bt), dim3(256), 0, st, dev_layers,
-                           l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
-        hipLaunchKernelGGL((wf_gemv_kernel<T, EPI_KV, KSd>), dim3((2 * d + rows_d - 1) / rows_d, nl, bt), dim3(256), 0, st,
-                           dev_layers, l0, s, chunk, B, N, d, F, D.eps, D.norm_free, D.alpha);
-        hipLaunchKernelGGL((wf_finalize_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, B, D.H, d, D.eps,
-                           D.norm_free);
-        }
-        e = hipGetLastError();
-        if (e != hipSuccess) return e;
-        // a block inside the chunk closes: s + 1 positions of layer 0 are finished, every layer is at the same offset
-        const int t1 = s + 1;
-        const int P = t1 & -t1;
-        if (P >= D.p_min && P < chunk) {
-            e = wf_cross_launch<T, HP>(D, dev_layers, l0, (int)nl, t1, chunk, 0, P, far_rel, st);
-            if (e != hipSuccess) return e;
-        }
+    }
+    // the caller's stream continues after every group
+    for (int g = 1; g < G; ++g) {
+        if ((e = hipEventRecord(W.ev[g], W.st[g])) != hipSuccess) return e;
+        if ((e = hipStreamWaitEvent(W.st[0], W.ev[g], 0)) != hipSuccess) return e;
     }
     return hipSuccess;
 }
 
 template <typename T>
 hipError_t wavefront_prefill(const LayerDims &D, const WaveLayer *dev_layers, const WaveLayer *host_layers, int L, int chunk,
-                             bool mfma, hipStream_t st)
+                             bool mfma, const WaveStreams &W)
 {
+    hipStream_t st = W.st[0];
     // layer 0: its input is known in full, all queries and temporary pairs at once
     hipError_t e = Launch<T>::prepass(D, host_layers[0].W, host_layers[0].S, host_layers[0].x, D.B, D.N, mfma, st);
     if (e != hipSuccess) return e;
     const bool hp = mfma && sizeof(T) == 2;
+    if (wavefront_uses_matrix_cores(D.d, D.F, hp)) {
+        // the weights in fragment order, once per call (they are the caller's and may have changed since the last one)
+        for (int l = 0; l < L; ++l) {
+            const WaveLayer &Y = host_layers[l];
+            pack_launch(Y.W.Wo, Y.S.wp_o, D.d, D.d, st);
+            pack_launch(Y.W.W1, Y.S.wp_1, D.F, D.d, st);
+            pack_launch(Y.W.W2, Y.S.wp_2, D.d, D.F, st);
+            pack_launch(Y.W.Wk, Y.S.wp_kv, D.d, D.d, st);
+            pack_launch(Y.W.Wv, Y.S.wp_kv + (size_t)D.d * D.d, D.d, D.d, st);
+        }
+        if ((e = hipGetLastError()) != hipSuccess) return e;
+    }
     const bool ks2_d = D.d <= 1024, ks2_F = D.F <= 1024;   // one 512-column slice per wavefront up to 1024 columns
-#define RT_WF_GO(HPv, KD, KF) return wavefront_steps<T, HPv, KD, KF>(D, dev_layers, host_layers, L, chunk, mfma, st)
+#define RT_WF_GO(HPv, KD, KF) return wavefront_steps<T, HPv, KD, KF>(D, dev_layers, host_layers, L, chunk, mfma, W)
     if (hp) {
         if (ks2_d && ks2_F) RT_WF_GO(true, 2, 2);
         if (ks2_d) RT_WF_GO(true, 2, 4);
@@ -543,7 +604,9 @@ hipError_t wavefront_prefill(const LayerDims &D, const WaveLayer *dev_layers, co
 #undef RT_WF_GO
 }
 
-template hipError_t wavefront_prefill<float>(const LayerDims &, const WaveLayer *, const WaveLayer *, int, int, bool, hipStream_t);
-template hipError_t wavefront_prefill<bf16_t>(const LayerDims &, const WaveLayer *, const WaveLayer *, int, int, bool, hipStream_t);
+template hipError_t wavefront_prefill<float>(const LayerDims &, const WaveLayer *, const WaveLayer *, int, int, bool,
+                                             const WaveStreams &);
+template hipError_t wavefront_prefill<bf16_t>(const LayerDims &, const WaveLayer *, const WaveLayer *, int, int, bool,
+                                              const WaveStreams &);
 
 }  // namespace rt
