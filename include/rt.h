@@ -110,10 +110,12 @@ rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t
  *   layers [L] host array of weight structs (device pointers inside); x [B, N, d] device, input of layer 0;
  *   y, K, V: host arrays of L device pointers: y[l] [B, N, d] output of layer l (all L are written: y[l] is layer
  *   l + 1's input), K[l], V[l] [kv_cap, B, H, head_dim] rows 0..N-1 written.  No two of these tensors may overlap.
- *   chunk: power of two >= p_min (>= 64 with the MFMA kernels); 0 = 128.
+ *   chunk: power of two >= p_min (>= 64 with the MFMA kernels); 0 = 64.
  * The first call allocates one scratch set per layer (RT_ERR_OOM if that fails); it is kept until rt_destroy and
  * reused by later calls with the same chunk and at most as many layers (another shape synchronises the stream
- * and reallocates).  rt_decode_step continues from the caches layer by layer. */
+ * and reallocates).  Half of the layers are enqueued on a second stream that the context owns (default priority;
+ * it starts after the work already enqueued on rt_config.stream and that stream continues after it).
+ * rt_decode_step continues from the caches layer by layer. */
 rt_status rt_stack_prefill(rt_ctx *ctx, const rt_layer_weights *layers, int32_t L, const void *x, int32_t B, int32_t N,
                            void *const *y, void *const *K, void *const *V, int32_t kv_cap, int32_t chunk);
 

@@ -572,7 +572,7 @@ extern "C" rt_status rt_stack_prefill(rt_ctx *c, const rt_layer_weights *layers,
     if (B < 1 || B > c->cfg.max_batch) return fail(c, RT_ERR_INVALID_ARG, "B out of range [1, max_batch]%s");
     if (N < 1 || N > c->cfg.max_seq) return fail(c, RT_ERR_INVALID_ARG, "N out of range [1, max_seq]%s");
     if (kv_cap < N) return fail(c, RT_ERR_INVALID_ARG, "kv_cap < N%s");
-    if (chunk == 0) chunk = 128;
+    if (chunk == 0) chunk = 64;
     const int chunk_min = c->use_mfma ? 64 : c->cfg.p_min;
     if (!is_pow2(chunk) || chunk < chunk_min || chunk < c->cfg.p_min || chunk > (1 << 20))
         return fail(c, RT_ERR_INVALID_ARG, "chunk must be a power of two, at least p_min (and 64 with the MFMA kernels)%s");

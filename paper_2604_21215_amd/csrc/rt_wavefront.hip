@@ -449,10 +449,10 @@ bool wavefront_uses_matrix_cores(int d, int F, bool mfma_bf16)
     return mfma_bf16 && d % 256 == 0 && F % 256 == 0;
 }
 
-// Launches one of the four matrix-core products.  Shapes: WO and W2 split the contraction over the four wavefronts
-// of a workgroup (16 rows per workgroup), W1 does not (64 rows), [Wk; Wv] splits it in two with eight wavefronts (64
-// rows = one head).  The operand rows go through LDS when they fit beside two more workgroups on a compute unit.
-constexpr size_t kMmMaxLds = 72 * 1024;
+// Launches one of the four matrix-core products.  Shapes (measured best at d = 1024, F = 4096, 12 layers): WO and W2
+// split the contraction in four with eight wavefronts (32 rows per workgroup), W1 does not split it (64 rows), [Wk; Wv]
+// splits it in two with eight wavefronts (64 rows = one head).  The operand rows go through LDS when they fit.
+constexpr size_t kMmMaxLds = 96 * 1024;
 template <int EPI, int KS, int NW>
 static hipError_t mm_launch(int n_out, unsigned nl, hipStream_t st, const WaveLayer *dev_layers, int l0, int s, int chunk,
                             const LayerDims &D)
@@ -532,9 +532,9 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
             hipLaunchKernelGGL((wf_merge_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, log2_chunk, BH,
                                D.H, D.p_min, D.log2_pmin, D.scale);
             if (HP && use_mm) {
-                if ((e = mm_launch<EPI_WO, 4, 4>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
+                if ((e = mm_launch<EPI_WO, 4, 8>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
                 if ((e = mm_launch<EPI_W1, 1, 4>(F, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
-                if ((e = mm_launch<EPI_W2, 4, 4>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
+                if ((e = mm_launch<EPI_W2, 4, 8>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
                 // the epilogue of this one also finishes the position (persistent pair and its copies)
                 if ((e = mm_launch<EPI_KV, 2, 8>(2 * d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
             } else {
