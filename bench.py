@@ -49,6 +49,52 @@ def algorithmic_bytes(B, N, d, H, F, E, p_min, weights_resident):
     }
 
 
+def stack_section(stream, layer_by_layer=True):
+    """The 12-layer stack workload (cfg5: B = 4, N = 4096) through the layer-wavefront engine (rt_stack_prefill: the
+    layers run concurrently, a chunk of positions apart) and, for comparison, layer by layer (12 x rt_layer_prefill).
+    Its bound is the weight stream: every (layer, position) reads the layer's five loop matrices once."""
+    import numpy as np
+    import torch
+    from paper_2604_21215_amd import binding, inputs as gen, torch_io as tio
+    from paper_2604_21215_amd.stack import DeviceStack
+    ws = gen.WORKLOADS["cfg5"]
+    tabs = gen.make_embedding_tables(ws)
+    sctx = binding.RTContext(ws.d, ws.H, ws.F, ws.B, ws.N, ws.dtype, resid_scale=ws.resid_scale, rms_eps=1e-6,
+                             stream=stream.cuda_stream)
+    dls = [tio.DeviceLayer(gen.make_layer_weights(ws.seed, l, ws.d, ws.F, ws.dtype), None, ws.dtype)
+           for l in range(ws.layers)]
+    # table entries ~ N(0, 1): the scale at which the stack's parity tests run
+    ds = DeviceStack(sctx, dls, gen.round_to_bf16(tabs["embedding"] * np.float32(50.0)), tabs["lm_head"], None, ws.dtype)
+    ids = torch.from_numpy(np.ascontiguousarray(gen.make_token_ids(ws)[:, :ws.N], dtype=np.int32)).to("cuda:0")
+
+    def timed(reps, **kw):
+        ds.prefill(ids, ws.N, kv_cap=ws.N, **kw)   # warm-up (allocates the engine's scratch)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            ds.prefill(ids, ws.N, kv_cap=ws.N, **kw)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    t_wf = timed(2, wavefront=True)
+    w_bytes = float(ws.N) * ws.layers * (3 * ws.d * ws.d + 2 * ws.d * ws.F) * 2
+    sec = {
+        "workload": "cfg5: 12 RT layers, bf16, B=%d, N=%d, d_model=%d, embedding + read-out included" % (ws.B, ws.N, ws.d),
+        "ms_per_prefill": t_wf * 1e3, "tokens_per_s": ws.B * ws.N / t_wf,
+        "layer_tokens_per_s": ws.B * ws.N * ws.layers / t_wf,
+        "bound": "hbm", "algorithmic_bytes": w_bytes, "achieved": w_bytes / t_wf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+        "frac": w_bytes / t_wf / 1e9 / HBM_PEAK_GBS,
+        "note": "algorithmic bytes = the loop matrices (3 d^2 + 2 d F elements) once per layer and position; "
+                "host-timed over whole calls",
+    }
+    if layer_by_layer:
+        t_seq = timed(1)
+        sec["layer_by_layer_ms"] = t_seq * 1e3
+        sec["speedup_over_layer_by_layer"] = t_seq / t_wf
+    sctx.rt_destroy()
+    return sec
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -59,6 +105,9 @@ def main():
     ap.add_argument("--p-min", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the rt_decode_step measurement")
+    ap.add_argument("--no-stack", action="store_true", help="skip the 12-layer stack measurement (rt_stack_prefill)")
+    ap.add_argument("--stack-only", action="store_true",
+                    help="only the 12-layer stack through rt_stack_prefill (for profiling): prints its section alone")
     ap.add_argument("--cpu-sample-positions", type=int, default=1024)
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy, the reference the rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -74,6 +123,9 @@ def main():
     from paper_2604_21215_amd import binding, inputs as gen, torch_io as tio
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.stack_only:
+        print(json.dumps({"stack_wavefront": stack_section(torch.cuda.current_stream(), layer_by_layer=False)}))
+        return
     wl = gen.WORKLOADS[args.workload]
     li = gen.make_layer_inputs(wl)
     flags = {"auto": 0, "stepwise": binding.RT_FLAG_ENGINE_STEPWISE,
@@ -215,6 +267,9 @@ def main():
         err = np.linalg.norm(got - ref[0], axis=-1) / np.linalg.norm(ref[0], axis=-1)
         out["parity_sample"] = {"max_rel_err_y": float(err.max()), "positions": n_s}
     ctx.rt_destroy()
+
+    if not args.no_stack and args.workload == "cfg3":
+        out["stack_wavefront"] = stack_section(stream)
     print(json.dumps(out))
 
 
