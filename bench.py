@@ -49,7 +49,7 @@ def algorithmic_bytes(B, N, d, H, F, E, p_min, weights_resident):
     }
 
 
-def stack_section(stream, layer_by_layer=True):
+def stack_section(stream, layer_by_layer=True, reps=2):
     """The 12-layer stack workload (cfg5: B = 4, N = 4096) through the layer-wavefront engine (rt_stack_prefill: the
     layers run concurrently, a chunk of positions apart) and, for comparison, layer by layer (12 x rt_layer_prefill).
     Its bound is the weight stream: every (layer, position) reads the layer's five loop matrices once."""
@@ -76,7 +76,7 @@ def stack_section(stream, layer_by_layer=True):
         torch.cuda.synchronize()
         return (time.perf_counter() - t0) / reps
 
-    t_wf = timed(2, wavefront=True)
+    t_wf = timed(reps, wavefront=True)
     w_bytes = float(ws.N) * ws.layers * (3 * ws.d * ws.d + 2 * ws.d * ws.F) * 2
     sec = {
         "workload": "cfg5: 12 RT layers, bf16, B=%d, N=%d, d_model=%d, embedding + read-out included" % (ws.B, ws.N, ws.d),
@@ -123,8 +123,15 @@ def main():
     from paper_2604_21215_amd import binding, inputs as gen, torch_io as tio
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
+    if args.traffic_calibration:
+        big = torch.empty(256 * 2**20, dtype=torch.uint8, device="cuda:0")
+        big.zero_()
+        big2 = big.clone()          # one copy kernel: reads 256 MiB, writes 256 MiB
+        torch.cuda.synchronize()
+        del big, big2
     if args.stack_only:
-        print(json.dumps({"stack_wavefront": stack_section(torch.cuda.current_stream(), layer_by_layer=False)}))
+        print(json.dumps({"stack_wavefront": stack_section(torch.cuda.current_stream(), layer_by_layer=False,
+                                                           reps=args.steps)}))
         return
     wl = gen.WORKLOADS[args.workload]
     li = gen.make_layer_inputs(wl)
@@ -140,12 +147,6 @@ def main():
     K = torch.zeros((wl.N, wl.B, wl.H, wl.head_dim), dtype=xd.dtype, device=xd.device)
     V = torch.zeros_like(K)
 
-    if args.traffic_calibration:
-        big = torch.empty(256 * 2**20, dtype=torch.uint8, device=xd.device)
-        big.zero_()
-        big2 = big.clone()          # one copy kernel: reads 256 MiB, writes 256 MiB
-        torch.cuda.synchronize()
-        del big, big2
     for _ in range(args.warmup):
         ctx.rt_layer_prefill(dl.struct, xd, y, K, V)
     torch.cuda.synchronize()

@@ -26,6 +26,7 @@
 // remainder), as in the single-launch engine.
 #include "rt_base_case.h"
 #include "rt_cross_tile.h"
+#include "rt_prepass_device.h"
 
 namespace rt {
 
@@ -427,6 +428,21 @@ static hipError_t wf_cross_launch(const LayerDims &D, const WaveLayer *dev_layer
     return hipGetLastError();
 }
 
+// Queries and temporary pairs of the chunks that layers l_first .. enter at this step, one launch: the pre-pass GEMM
+// over the chunk's rows of each layer's input, 1/rms of the rows formed on the way.
+// grid (ceil(B * chunk / 128), ceil(3H / 2), layers), block 256.
+__global__ __launch_bounds__(256) void wf_prepass_kernel(const WaveLayer *__restrict__ layers, int l_first, int s, int chunk, int B,
+                                                         int N, int d, int H, float eps, int norm_free)
+{
+    const int l = l_first + blockIdx.z, t = layer_pos(s, l, chunk);
+    const WaveLayer &Y = layers[l];
+    const int Nc = min(chunk, N - t);
+    prepass_mfma_body<true>((const bf16_t *)Y.x, nullptr, (const bf16_t *)Y.W.Wq, (const bf16_t *)Y.W.Wk, (const bf16_t *)Y.W.Wv,
+                            (const bf16_t *)Y.W.g_attn, (const bf16_t *)Y.W.g_q, (const bf16_t *)Y.W.g_k, (bf16_t *)Y.S.Q,
+                            (bf16_t *)Y.S.Kt, (bf16_t *)Y.S.Vt, Y.S.Qf, Y.S.Ktf, B, Nc, (size_t)N * d, t, d, H, eps, norm_free,
+                            blockIdx.x, blockIdx.y);
+}
+
 // Re-lays n_rows x K row-major weights in fragment order (Scratch::wp_*): one thread per 16-byte piece of the output.
 __global__ __launch_bounds__(256) void wf_pack_kernel(const bf16_t *__restrict__ W, bf16_t *__restrict__ Wp, int n_rows, int K)
 {
@@ -518,7 +534,13 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
                 // the active layers enter a chunk: the group below has finished it
                 if (g > 0 && (e = hipStreamWaitEvent(st, W.ev[g - 1], 0)) != hipSuccess) return e;
                 // queries and temporary pairs of the chunk's rows, then the far tile
-                for (int l = l0 > 1 ? l0 : 1; l <= l1; ++l) {
+                const int lp = l0 > 1 ? l0 : 1;
+                if (HP && lp <= l1) {
+                    hipLaunchKernelGGL(wf_prepass_kernel, dim3((unsigned)((B * chunk + 127) / 128), (unsigned)((3 * D.H + 1) / 2),
+                                                               (unsigned)(l1 - lp + 1)),
+                                       dim3(256), 0, st, dev_layers, lp, s, chunk, B, N, d, D.H, D.eps, D.norm_free);
+                }
+                for (int l = lp; l <= l1 && !HP; ++l) {
                     const int t = s - l * chunk;
                     const int Nc = chunk < N - t ? chunk : N - t;
                     e = Launch<T>::prepass(D, host_layers[l].W, host_layers[l].S, host_layers[l].x, B, Nc, mfma, st, (size_t)N * d, t);
