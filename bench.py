@@ -16,8 +16,8 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0
 # L2<->fabric bytes of one persistent_kernel launch on workload cfg3, from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE) scaled by what the same counters read for a plain 256 MiB copy: fetch 7.31 GB + write 4.22 GB.
-MEASURED_TRAFFIC_BYTES = {("cfg3", "persistent"): 7321870 * 1024 + 4043248 * 1024}
+# WRITE_SIZE) scaled by what the same counters read for a plain 256 MiB copy (x 2.000 and x 1.000): fetch 9.58 GB + write 5.17 GB.
+MEASURED_TRAFFIC_BYTES = {("cfg3", "persistent"): 2 * 4676919 * 1024 + 5048709 * 1024}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
