@@ -184,6 +184,13 @@ int32_t rt_schedule_events(int32_t N, int32_t p_min, int32_t *out, int32_t cap);
  * The direct window of query i is keys [c - (c mod p_min) + 1, c] with c = i-2, plus key i-1. */
 int32_t rt_schedule_events_shifted(int32_t N, int32_t p_min, int32_t *out, int32_t cap);
 
+/* Host-only: the events rt_stack_prefill issues for each layer (positions of that layer, 1-based as above): the events
+ * of rt_schedule_events with p_min <= P < chunk unchanged, and for every t that is a multiple of chunk one event with
+ * P = t, s = 1 (every key so far) and queries t+1 .. min(t+chunk, N), whose partial states are stored one per query
+ * beside the levels of the blocks.  All queries of an event lie in one chunk of `chunk` positions, the one a layer has
+ * just entered when the event is issued.  chunk: power of two >= p_min. */
+int32_t rt_schedule_events_chunked(int32_t N, int32_t p_min, int32_t chunk, int32_t *out, int32_t cap);
+
 /* Host-only: index of the partial-state slot of (level, query), or -1 if that query takes no tile at
  * that level.  level = log2(P); query is 1-based.  Slots of one level are dense in [0, ceil(N/2)). */
 int64_t rt_partial_slot(int32_t level, int32_t query);

@@ -413,11 +413,16 @@ int rto_schedule(int N, int32_t *out, int cap)
 }
 
 /* Algorithm 1 with Algorithm 2 as its update primitive; single batch loop, read-modify-write
- * running statistics initialised to (-inf, 0, 0). */
+ * running statistics initialised to (-inf, 0, 0).
+ * chunk = 0: the schedule as printed.  chunk = C > 0 (a power of two): the variant for a layer that knows its
+ * queries only one chunk of C positions ahead - the blocks P < C are served as printed (their queries lie in the
+ * block's own chunk), the blocks P >= C are not; instead, when position t = cC is finished, ONE UpdateTile folds
+ * all keys 1..t into the queries t+1..min(t+C, N).  Every (query, earlier key) pair is still covered exactly once,
+ * and UpdateTile is exact for any partition of the keys (Appendix C, online softmax), so the result is the same. */
 int rto_layer_prefill_tiled(const rto_params *p, const double *x, int B, int N, double *y, double *K, double *V,
-                            int kv_cap)
+                            int kv_cap, int chunk)
 {
-    if (check_params(p) || B <= 0 || N <= 0 || kv_cap < N) return -1;
+    if (check_params(p) || B <= 0 || N <= 0 || kv_cap < N || chunk < 0 || (chunk & (chunk - 1))) return -1;
     rto_tw w;
     if (make_tw(p, &w)) return -2;
     const int d = p->d, H = p->H, dh = p->dh;
@@ -450,9 +455,14 @@ int rto_layer_prefill_tiled(const rto_params *p, const double *x, int B, int N, 
             finish_position(p, &w, xr, &s, y + ((size_t)b * N + (t - 1)) * d, k_out, v_out, 0);
             int P = 1;
             while (t % (2 * P) == 0) P *= 2;
-            const int u = t + 1, v = (t + P < N) ? t + P : N;
+            int u = t + 1, v = (t + P < N) ? t + P : N;
+            int s0 = t - P + 1;
+            if (chunk > 0 && P >= chunk) { /* chunked variant: every key so far against the next chunk's queries */
+                v = (t + chunk < N) ? t + chunk : N;
+                s0 = 1;
+                P = t;
+            }
             if (u <= v) {
-                const int s0 = t - P + 1;
                 for (int h = 0; h < H; ++h) {
                     double *mh = m + (size_t)h * N, *lh = l + (size_t)h * N, *oh = o + (size_t)h * N * dh;
                     rto_update_tile(Q + (size_t)(u - 1) * d + h * dh, v - u + 1, d,

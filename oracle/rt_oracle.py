@@ -53,7 +53,7 @@ def lib():
         PP = C.POINTER(_Params)
         L.rto_layer_prefill.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int, _DP]
         L.rto_layer_prefill.restype = C.c_int
-        L.rto_layer_prefill_tiled.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int]
+        L.rto_layer_prefill_tiled.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int, C.c_int]
         L.rto_layer_prefill_tiled.restype = C.c_int
         L.rto_transformer_layer.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int, _DP]
         L.rto_transformer_layer.restype = C.c_int
@@ -139,10 +139,12 @@ class Layer:
             raise RuntimeError("rto_layer_prefill failed: %d" % rc)
         return (y, K, V, aw) if want_attw else (y, K, V)
 
-    def prefill_tiled(self, x, kv_cap=None):
-        """Appendix C, Algorithms 1 + 2 literally (running statistics, tiled schedule)."""
+    def prefill_tiled(self, x, kv_cap=None, chunk=0):
+        """Appendix C, Algorithms 1 + 2 literally (running statistics, tiled schedule).  chunk > 0: the variant
+        in which a layer knows its queries one chunk ahead only (blocks of `chunk` keys and more replaced by one
+        UpdateTile per chunk over all earlier keys)."""
         x, B, N, kv_cap, y, K, V = self._alloc(x, kv_cap)
-        rc = lib().rto_layer_prefill_tiled(C.byref(self.p), _ptr(x), B, N, _ptr(y), _ptr(K), _ptr(V), kv_cap)
+        rc = lib().rto_layer_prefill_tiled(C.byref(self.p), _ptr(x), B, N, _ptr(y), _ptr(K), _ptr(V), kv_cap, int(chunk))
         if rc:
             raise RuntimeError("rto_layer_prefill_tiled failed: %d" % rc)
         return y, K, V

@@ -23,7 +23,7 @@ RT_FLAG_HIP_GRAPH = 0x10
 EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_last_error", "rt_status_string",
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
            "rt_version", "rt_phase_trace", "rt_schedule_events_shifted", "rt_embed_rows", "rt_lm_head", "rt_cross_block_event",
-           "rt_stack_prefill")
+           "rt_stack_prefill", "rt_schedule_events_chunked")
 
 
 class rt_config(C.Structure):
@@ -81,6 +81,8 @@ def load():
     L.rt_schedule_events.restype = C.c_int32
     L.rt_schedule_events_shifted.argtypes = [C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
     L.rt_schedule_events_shifted.restype = C.c_int32
+    L.rt_schedule_events_chunked.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.POINTER(C.c_int32), C.c_int32]
+    L.rt_schedule_events_chunked.restype = C.c_int32
     L.rt_partial_slot.argtypes = [C.c_int32, C.c_int32]
     L.rt_partial_slot.restype = C.c_int64
     L.rt_version.restype = C.c_int32
@@ -134,6 +136,11 @@ def rt_schedule_events(N: int, p_min: int):
 
 def rt_schedule_events_shifted(N: int, p_min: int):
     return _events(load().rt_schedule_events_shifted, N, p_min)
+
+
+def rt_schedule_events_chunked(N: int, p_min: int, chunk: int):
+    fn = load().rt_schedule_events_chunked
+    return _events(lambda n, p, buf, cap: fn(n, p, chunk, buf, cap), N, p_min)
 
 
 def rt_partial_slot(level: int, query: int) -> int:

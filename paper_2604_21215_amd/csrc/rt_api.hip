@@ -170,6 +170,24 @@ int32_t rt_schedule_events_shifted(int32_t N, int32_t p_min, int32_t *out, int32
     return n;
 }
 
+int32_t rt_schedule_events_chunked(int32_t N, int32_t p_min, int32_t chunk, int32_t *out, int32_t cap)
+{
+    if (N < 1 || !is_pow2(p_min) || !is_pow2(chunk) || chunk < p_min) return -1;
+    int32_t n = 0;
+    for (int32_t t = 1; t < N; ++t) {
+        int32_t P = t & -t;
+        int32_t v = (t + P < N) ? t + P : N, s = t - P + 1;
+        if (P >= chunk) { v = (t + chunk < N) ? t + chunk : N; s = 1; P = t; }   // far tile: every key so far
+        else if (P < p_min) continue;
+        if (out && n < cap) {
+            int32_t *r = out + 5 * (size_t)n;
+            r[0] = t; r[1] = P; r[2] = t + 1; r[3] = v; r[4] = s;
+        }
+        ++n;
+    }
+    return n;
+}
+
 int64_t rt_partial_slot(int32_t level, int32_t query)
 {
     if (level < 0 || level > 30 || query < 1) return -1;

@@ -100,3 +100,31 @@ def test_shifted_schedule_of_the_persistent_engine_covers_every_pair_once(N, p_m
             cover[i, c - w + 1:c + 1] += 1                       # direct window
     for i in range(1, N + 1):
         assert (cover[i, 1:i] == 1).all() and (cover[i, i:] == 0).all(), i
+
+
+@pytest.mark.parametrize("N,p_min,chunk", [(1, 32, 64), (40, 32, 64), (100, 32, 32), (130, 4, 16), (300, 32, 64), (1000, 32, 128),
+                                           (257, 64, 64), (75, 8, 32)])
+def test_chunked_schedule_of_the_layer_wavefront_engine_covers_every_pair_once(N, p_min, chunk):
+    """Blocks below the chunk as in the driver schedule, one tile over all earlier keys per chunk, direct window below
+    p_min; every event's queries lie in the chunk that starts right after the event's last key."""
+    ev = binding.rt_schedule_events_chunked(N, p_min, chunk)
+    cover = np.zeros((N + 1, N + 1), dtype=np.int32)
+    n_far = 0
+    for (t, P, u, v, s) in ev:
+        assert u == t + 1 and u <= v <= N
+        if s == 1 and P == t and t % chunk == 0:            # far tile
+            assert v == min(t + chunk, N)
+            n_far += 1
+        else:
+            assert p_min <= P < chunk and t % P == 0 and (t // P) % 2 == 1 and v == min(t + P, N) and s == t - P + 1
+        assert (u - 1) // chunk == (v - 1) // chunk        # one chunk, known when the layer enters it
+        assert (u - 1) // chunk == t // chunk or t % chunk == 0
+        cover[u:v + 1, s:t + 1] += 1
+    assert n_far == (N - 1) // chunk
+    for i in range(1, N + 1):
+        w = (i - 1) % p_min
+        cover[i, i - w:i] += 1
+    for i in range(1, N + 1):
+        assert (cover[i, 1:i] == 1).all() and (cover[i, i:] == 0).all(), i
+    assert binding.load().rt_schedule_events_chunked(16, 32, 16, None, 0) == -1     # chunk < p_min
+    assert binding.load().rt_schedule_events_chunked(16, 4, 24, None, 0) == -1      # not a power of two

@@ -367,6 +367,20 @@ def test_p8_tiled_equals_naive(oracle, N):
     np.testing.assert_allclose(V2, V, rtol=1e-12, atol=1e-12)
 
 
+@pytest.mark.parametrize("N,chunk", [(5, 4), (37, 4), (64, 16), (70, 16), (33, 32), (20, 32)])
+def test_p8_chunked_schedule_equals_naive(oracle, N, chunk):
+    """The schedule of a layer that knows its queries one chunk ahead (blocks of `chunk` keys and more replaced by one
+    UpdateTile per chunk over all earlier keys) gives the plain recurrence's result: UpdateTile is exact for any
+    partition of the keys (Appendix C)."""
+    x, w, g = _small(43, B=2, N=N, d=24, H=3, F=40)
+    lay = oracle.Layer(w, 3, gains=g, alpha=0.9, eps=1e-6, attn_scale=1.0)
+    y, K, V = lay.prefill(x)
+    y2, K2, V2 = lay.prefill_tiled(x, chunk=chunk)
+    np.testing.assert_allclose(y2, y, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(K2, K, rtol=1e-12, atol=1e-12)
+    np.testing.assert_allclose(V2, V, rtol=1e-12, atol=1e-12)
+
+
 # ------------------------------------------------------------------------------------------
 # P9  Softmax special cases.
 # ------------------------------------------------------------------------------------------
