@@ -24,6 +24,9 @@
  *   logits = attn_scale * <k, q>   (paper: attn_scale = 1)
  *   residual scale alpha = 1/sqrt(L):  h = x + alpha a,  z = h + alpha MLP(RMS(h))
  *   norm_free != 0 turns every RMS and qkRMS into the identity (Appendix A).
+ *   alibi_max_bias = beta > 0 adds the linear positional bias the paper's trained models use (Appendix D,
+ *   experimental details: ALiBi with maximum bias 8.0): logit(i, j) -= m_h (i - j) for a persistent key of position
+ *   j < i, with head slopes m_h = 2^(-beta (h + 1) / H), h = 0..H-1; the temporary pair sits at distance 0.
  *
  * Layouts: x, y [B][N][d];  K, V [kv_cap][B][H][dh] (position first);  weights row-major [out][in].
  * Pinned by tests/test_oracle_pins.py (closed forms, invariants, Appendix A construction,
@@ -51,7 +54,13 @@ typedef struct {
     const double *g_attn, *g_mlp, *g_kv, *g_q, *g_k; /* [d] or NULL = ones */
     rto_mlp_fn mlp;               /* optional replacement for the whole MLP block */
     void *mlp_user;
+    double alibi_max_bias;        /* 0 = no positional bias */
 } rto_params;
+
+static double alibi_slope(const rto_params *p, int h)
+{
+    return p->alibi_max_bias > 0.0 ? pow(2.0, -p->alibi_max_bias * (double)(h + 1) / (double)p->H) : 0.0;
+}
 
 #if defined(__x86_64__) && defined(__GNUC__) && !defined(__clang__)
 #define RTO_CLONES __attribute__((target_clones("avx2", "default")))
@@ -216,10 +225,11 @@ static void attend(const rto_params *p, rto_ws *s, const double *K, const double
     for (int h = 0; h < H; ++h) {
         const double *q = s->q + h * dh;
         double *logit = s->logit + (size_t)h * s->maxpos;
+        const double slope = alibi_slope(p, h);
         double mx = -INFINITY;
         for (int j = 0; j < t; ++j) {
             const double *kj = K + (((size_t)j * B + b) * H + h) * dh;
-            logit[j] = p->attn_scale * dot(kj, q, dh);
+            logit[j] = p->attn_scale * dot(kj, q, dh) - slope * (double)(t - j);
             if (logit[j] > mx) mx = logit[j];
         }
         logit[t] = p->attn_scale * dot(s->kt + h * dh, q, dh);
@@ -364,16 +374,17 @@ int rto_transformer_layer(const rto_params *p, const double *x, int B, int N, do
  * ------------------------------------------------------------------------------------------ */
 
 /* Algorithm 2: fold KV rows (k[j], v[j]), j in [0, nkv), into the running (m, l, o) of nq queries.
- * q, k, v rows have `stride` doubles between consecutive positions; o rows are dense [nq][dh]. */
+ * q, k, v rows have `stride` doubles between consecutive positions; o rows are dense [nq][dh].
+ * Positional bias: query i of the tile is dist0 + i - j positions after key j, logit -= slope * that. */
 void rto_update_tile(const double *q, int nq, int q_stride, const double *k, const double *v, int nkv,
-                     int kv_stride, int dh, double scale, double *m, double *l, double *o)
+                     int kv_stride, int dh, double scale, double *m, double *l, double *o, double slope, int dist0)
 {
     double *logit = (double *)malloc(sizeof(double) * (size_t)(nkv > 0 ? nkv : 1));
     for (int i = 0; i < nq; ++i) {
         const double *qi = q + (size_t)i * q_stride;
         double m_tile = -INFINITY;
         for (int j = 0; j < nkv; ++j) {
-            logit[j] = scale * dot(k + (size_t)j * kv_stride, qi, dh);
+            logit[j] = scale * dot(k + (size_t)j * kv_stride, qi, dh) - slope * (double)(dist0 + i - j);
             if (logit[j] > m_tile) m_tile = logit[j];
         }
         const double m_new = m[i] > m_tile ? m[i] : m_tile;
@@ -447,7 +458,7 @@ int rto_layer_prefill_tiled(const rto_params *p, const double *x, int B, int N, 
             for (int h = 0; h < H; ++h) {
                 double *mh = m + (size_t)h * N, *lh = l + (size_t)h * N, *oh = o + (size_t)h * N * dh;
                 rto_update_tile(Q + (size_t)(t - 1) * d + h * dh, 1, d, s.kt + h * dh, s.vt + h * dh, 1, 0, dh,
-                                p->attn_scale, mh + (t - 1), lh + (t - 1), oh + (size_t)(t - 1) * dh);
+                                p->attn_scale, mh + (t - 1), lh + (t - 1), oh + (size_t)(t - 1) * dh, 0.0, 0);
                 for (int c = 0; c < dh; ++c) s.cat[h * dh + c] = oh[(size_t)(t - 1) * dh + c] / lh[t - 1];
             }
             double *k_out = K + (((size_t)(t - 1) * B + b) * H) * dh;
@@ -468,7 +479,7 @@ int rto_layer_prefill_tiled(const rto_params *p, const double *x, int B, int N, 
                     rto_update_tile(Q + (size_t)(u - 1) * d + h * dh, v - u + 1, d,
                                     K + (((size_t)(s0 - 1) * B + b) * H + h) * dh,
                                     V + (((size_t)(s0 - 1) * B + b) * H + h) * dh, P, kvs, dh, p->attn_scale,
-                                    mh + (u - 1), lh + (u - 1), oh + (size_t)(u - 1) * dh);
+                                    mh + (u - 1), lh + (u - 1), oh + (size_t)(u - 1) * dh, alibi_slope(p, h), u - s0);
                 }
             }
         }

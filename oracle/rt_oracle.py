@@ -28,6 +28,7 @@ class _Params(C.Structure):
         ("Wq", _DP), ("Wk", _DP), ("Wv", _DP), ("Wo", _DP), ("W1", _DP), ("W2", _DP),
         ("g_attn", _DP), ("g_mlp", _DP), ("g_kv", _DP), ("g_q", _DP), ("g_k", _DP),
         ("mlp", _MLP_FN), ("mlp_user", C.c_void_p),
+        ("alibi_max_bias", C.c_double),
     ]
 
 
@@ -60,7 +61,7 @@ def lib():
         L.rto_decode_step.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int]
         L.rto_decode_step.restype = C.c_int
         L.rto_update_tile.argtypes = [_DP, C.c_int, C.c_int, _DP, _DP, C.c_int, C.c_int, C.c_int, C.c_double,
-                                      _DP, _DP, _DP]
+                                      _DP, _DP, _DP, C.c_double, C.c_int]
         L.rto_update_tile.restype = None
         L.rto_schedule.argtypes = [C.c_int, C.POINTER(C.c_int32), C.c_int]
         L.rto_schedule.restype = C.c_int
@@ -87,7 +88,7 @@ class Layer:
     """
 
     def __init__(self, weights, H, *, gains=None, alpha=1.0, attn_scale=1.0, eps=1e-6, norm_free=False,
-                 mlp=None, threads=0):
+                 mlp=None, threads=0, alibi_max_bias=0.0):
         self._keep = []
         w = {k: (_f64(v) if v is not None else None) for k, v in weights.items()}
         d = w["Wq"].shape[0]
@@ -102,6 +103,7 @@ class Layer:
         p.d, p.H, p.dh, p.F = d, H, self.dh, self.F
         p.alpha, p.attn_scale, p.eps = float(alpha), float(attn_scale), float(eps)
         p.norm_free, p.threads = int(bool(norm_free)), int(threads)
+        p.alibi_max_bias = float(alibi_max_bias)
         for name in ("Wq", "Wk", "Wv", "Wo", "W1", "W2"):
             a = w.get(name)
             setattr(p, name, _ptr(a))
@@ -170,14 +172,16 @@ class Layer:
         return y_t
 
 
-def update_tile(q, k, v, m, l, o, scale=1.0):
-    """Algorithm 2 on dense [nq,dh] / [nkv,dh] tiles; m, l [nq], o [nq,dh] updated in place."""
+def update_tile(q, k, v, m, l, o, scale=1.0, slope=0.0, dist0=0):
+    """Algorithm 2 on dense [nq,dh] / [nkv,dh] tiles; m, l [nq], o [nq,dh] updated in place.  slope, dist0: linear
+    positional bias, query i being dist0 + i - j positions after key j."""
     q, k, v = _f64(q), _f64(k), _f64(v)
     nq, dh = q.shape
     nkv = k.shape[0]
     for a in (m, l, o):
         assert a.dtype == np.float64 and a.flags.c_contiguous
-    lib().rto_update_tile(_ptr(q), nq, dh, _ptr(k), _ptr(v), nkv, dh, dh, float(scale), _ptr(m), _ptr(l), _ptr(o))
+    lib().rto_update_tile(_ptr(q), nq, dh, _ptr(k), _ptr(v), nkv, dh, dh, float(scale), _ptr(m), _ptr(l), _ptr(o),
+                          float(slope), int(dist0))
 
 
 def schedule(N):

@@ -82,8 +82,9 @@ def test_p2_causality_bit_identical(oracle):
 # P3  Brute force: re-evaluate the whole prefix from scratch for every t, and an independent
 #     dense re-statement of the recurrence in numpy for tiny N.
 # ------------------------------------------------------------------------------------------
-def _rt_numpy(x, w, g, H, alpha=1.0, eps=0.0, scale=1.0):
-    """One sequence [N, d]; nothing cached except the outputs the definition itself refers to."""
+def _rt_numpy(x, w, g, H, alpha=1.0, eps=0.0, scale=1.0, alibi=0.0):
+    """One sequence [N, d]; nothing cached except the outputs the definition itself refers to.
+    alibi = beta: logits get -2^(-beta (h+1)/H) (i - j) for the persistent key of position j (Press et al.)."""
     N, d = x.shape
     dh = d // H
     gq, gk = g["g_q"].reshape(H, dh), g["g_k"].reshape(H, dh)
@@ -102,6 +103,8 @@ def _rt_numpy(x, w, g, H, alpha=1.0, eps=0.0, scale=1.0):
             keys = np.vstack([Kp[:, h], kt[h][None]])
             vals = np.vstack([Vp[:, h], vt[h][None]])
             s = scale * (keys @ q[h])
+            if alibi:
+                s = s - 2.0 ** (-alibi * (h + 1) / H) * (i - np.arange(i + 1))   # last entry: the temporary pair, distance 0
             p = np.exp(s - s.max())
             heads.append((p / p.sum()) @ vals)
         a = w["Wo"] @ np.concatenate(heads)
@@ -129,7 +132,7 @@ def test_p3_bruteforce_prefix_and_dense_restatement(oracle):
 #     in parallel; the result must reproduce z.  By induction on position the fixed point is
 #     unique, so zero residual means z is the layer's output.
 # ------------------------------------------------------------------------------------------
-def _parallel_recompute(x, z, w, g, H, alpha, eps, scale):
+def _parallel_recompute(x, z, w, g, H, alpha, eps, scale, alibi=0.0):
     N, d = x.shape
     dh = d // H
     gq, gk = g["g_q"].reshape(H, dh), g["g_k"].reshape(H, dh)
@@ -143,6 +146,8 @@ def _parallel_recompute(x, z, w, g, H, alpha, eps, scale):
     cat = np.zeros((N, H, dh))
     for h in range(H):
         S = scale * (Q[:, h] @ Kp[:, h].T)                      # [i, j]
+        if alibi:
+            S = S - 2.0 ** (-alibi * (h + 1) / H) * (np.arange(N)[:, None] - np.arange(N)[None, :])
         S[np.triu_indices(N, 0)] = -np.inf                      # strictly lower triangle is visible
         S[np.arange(N), np.arange(N)] = scale * np.sum(Q[:, h] * Kt[:, h], axis=1)
         P = np.exp(S - S.max(axis=1, keepdims=True))
@@ -548,3 +553,63 @@ def test_stack_composes_layers_and_decodes(oracle):
     np.testing.assert_allclose(lg, logits, rtol=1e-12)
     for l in range(3):
         np.testing.assert_array_equal(st2.K[l], out[l][1])
+
+
+# ------------------------------------------------------------------------------------------
+# P12  ALiBi (Appendix D: the trained models use ALiBi positional biases with maximum bias 8.0; Press et al.:
+#      logit(i, j) -= m_h (i - j), head slopes a geometric sequence m_h = 2^(-8 (h+1) / H)).
+# ------------------------------------------------------------------------------------------
+def test_p12_alibi_zero_queries_give_geometric_weights(oracle):
+    """Wq = 0: every content logit vanishes, so position t (0-based) spreads its attention over keys 0..t-1 and its own
+    temporary pair as r^(t-j) / sum_{i=0..t} r^i with r = exp(-m_h): checks the slopes head by head, the sign, and that
+    the temporary pair sits at distance 0 and the newest persistent key at distance 1."""
+    H, N, beta = 4, 9, 8.0
+    x, w, g = _small(61, B=1, N=N, d=32, H=H, F=16)
+    w = dict(w)
+    w["Wq"] = np.zeros_like(w["Wq"])
+    _, _, _, attw = oracle.Layer(w, H, gains=g, alibi_max_bias=beta).prefill(x, want_attw=True)
+    for h in range(H):
+        r = math.exp(-(2.0 ** (-beta * (h + 1) / H)))
+        for t in range(N):
+            ref = np.array([r ** (t - j) for j in range(t + 1)])
+            np.testing.assert_allclose(attw[0, h, t, :t + 1], ref / ref.sum(), rtol=1e-12, atol=1e-15)
+    # H = 8, beta = 8: the slopes of Press et al., 1/2, 1/4, ..., 1/256
+    H = 8
+    x, w, g = _small(62, B=1, N=3, d=32, H=H, F=16)
+    w = dict(w)
+    w["Wq"] = np.zeros_like(w["Wq"])
+    _, _, _, attw = oracle.Layer(w, H, gains=g, alibi_max_bias=8.0).prefill(x, want_attw=True)
+    for h in range(H):
+        m = 0.5 ** (h + 1)
+        np.testing.assert_allclose(attw[0, h, 1, 0] / attw[0, h, 1, 1], math.exp(-m), rtol=1e-12)
+
+
+@pytest.mark.parametrize("beta", [8.0, 3.0])
+def test_p12_alibi_dense_restatement_and_fixed_point(oracle, beta):
+    x, w, g = _small(63, B=2, N=14, d=24, H=3, F=40)
+    alpha, eps, scale = 0.7, 1e-6, 0.5
+    lay = oracle.Layer(w, 3, gains=g, alpha=alpha, eps=eps, attn_scale=scale, alibi_max_bias=beta)
+    y, K, V = lay.prefill(x)
+    y0, _, _ = oracle.Layer(w, 3, gains=g, alpha=alpha, eps=eps, attn_scale=scale).prefill(x)
+    assert np.abs(y - y0).max() > 1e-3                      # the bias matters at this size
+    for b in range(2):
+        np.testing.assert_allclose(y[b], _rt_numpy(x[b], w, g, 3, alpha=alpha, eps=eps, scale=scale, alibi=beta),
+                                   rtol=1e-11, atol=1e-12)
+        z2, Kp, Vp = _parallel_recompute(x[b], y[b], w, g, 3, alpha, eps, scale, alibi=beta)
+        np.testing.assert_allclose(z2, y[b], rtol=1e-10, atol=1e-11)
+        np.testing.assert_allclose(K[:, b], Kp, rtol=1e-10, atol=1e-11)
+    # a bias of the wrong sign is not a fixed point
+    bad, _, _ = _parallel_recompute(x[0], y[0], w, g, 3, alpha, eps, scale, alibi=-beta)
+    assert np.abs(bad - y[0]).max() > 1e-3
+    # the tiled algorithm (Appendix C) with the bias carried into every tile, and its chunked variant; decoding
+    for chunk in (0, 4):
+        y2, K2, _ = lay.prefill_tiled(x, chunk=chunk)
+        np.testing.assert_allclose(y2, y, rtol=1e-12, atol=1e-12)
+        np.testing.assert_allclose(K2, K, rtol=1e-12, atol=1e-12)
+    yp, Kp2, Vp2 = lay.prefill(x[:, :9], kv_cap=14)
+    for t in range(9, 14):
+        yt = lay.decode_step(x[:, t], t, Kp2, Vp2)
+        np.testing.assert_array_equal(yt, y[:, t])
+    # beta = 0 is the layer without positions, bit for bit
+    y3, _, _ = oracle.Layer(w, 3, gains=g, alpha=alpha, eps=eps, attn_scale=scale, alibi_max_bias=0.0).prefill(x)
+    np.testing.assert_array_equal(y3, y0)
