@@ -11,7 +11,7 @@
  *     k_i      = qkRMS(Wk RMS(z_i; g_kv); g_k)     v_i = Wv RMS(z_i; g_kv)       (persistent pair)
  *
  * with Attn the softmax-weighted sum over logits attn_scale*<k,q> (Sec. 2, Notation; the paper's
- * logits are unscaled, attn_scale = 1), RMS(u) = g * u / sqrt(mean(u^2) + eps), qkRMS the same
+ * logits are unscaled, attn_scale = 1; optionally minus an ALiBi bias, rt_config.alibi_max_bias), RMS(u) = g * u / sqrt(mean(u^2) + eps), qkRMS the same
  * normalisation on each head's slice, exact (erf) GELU, no biases, alpha the 1/sqrt(L) residual
  * scale of Sec. 2.  Persistent pairs of positions j < i only, plus position i's own temporary
  * pair: that is the whole causal mask.
@@ -68,6 +68,13 @@ typedef struct {
     uint32_t flags;
     int32_t device;                               /* HIP device ordinal */
     void *stream;                                 /* hipStream_t; NULL = the default stream */
+    float alibi_max_bias;                         /* beta >= 0: linear positional bias (ALiBi) as in the paper's trained
+                                                     models (Appendix D: maximum bias 8.0): the logit of query i and the
+                                                     persistent key of position j < i is lowered by m_h (i - j), head
+                                                     slopes m_h = 2^(-beta (h + 1) / H), h = 0..H-1; the temporary pair is
+                                                     at distance 0.  0 = none (Sec. 2.2 as it stands).  With beta > 0 the
+                                                     per-position engine (and rt_stack_prefill) run; the persistent
+                                                     engine does not cover it */
 } rt_config;
 
 /* Device pointers, caller-owned, read-only.  Matrices are row-major [out, in] (y = W u).

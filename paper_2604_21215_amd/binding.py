@@ -31,7 +31,7 @@ class rt_config(C.Structure):
         ("d_model", C.c_int32), ("n_heads", C.c_int32), ("head_dim", C.c_int32), ("d_hidden", C.c_int32),
         ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("dtype", C.c_int32), ("p_min", C.c_int32),
         ("resid_scale", C.c_float), ("attn_scale", C.c_float), ("rms_eps", C.c_float), ("flags", C.c_uint32),
-        ("device", C.c_int32), ("stream", C.c_void_p),
+        ("device", C.c_int32), ("stream", C.c_void_p), ("alibi_max_bias", C.c_float),
     ]
 
 
@@ -151,11 +151,11 @@ class RTContext:
     """Owns an rt_ctx.  Methods mirror the C entry points and take torch device tensors."""
 
     def __init__(self, d_model, n_heads, d_hidden, max_batch, max_seq, dtype, *, p_min=0, resid_scale=1.0,
-                 attn_scale=1.0, rms_eps=1e-6, flags=0, device=0, stream=None):
+                 attn_scale=1.0, rms_eps=1e-6, flags=0, device=0, stream=None, alibi_max_bias=0.0):
         L = load()
         cfg = rt_config(d_model, n_heads, d_model // n_heads if n_heads else 0, d_hidden, max_batch, max_seq,
                         RT_BF16 if dtype in ("bf16", RT_BF16) and dtype != 0 else RT_F32, p_min, resid_scale, attn_scale,
-                        rms_eps, flags, device, stream)
+                        rms_eps, flags, device, stream, alibi_max_bias)
         self.cfg = cfg
         self._L = L
         self._ctx = C.c_void_p()

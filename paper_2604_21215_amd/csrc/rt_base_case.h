@@ -16,6 +16,8 @@ namespace rt {
 //   position's chunk of 2^log2_chunk positions only; all keys before the chunk were folded into one more
 //   partial state, stored at slot t of relative level far_rel.
 //   op_a: if not null, a is also written as a bf16 head row and a bf16 remainder row (rows 2b, 2b + 1 of [2B][d]).
+//   alibi > 0: linear positional bias; the temporary pair is at distance 0 and every stored partial state was
+//   written with its maximum already expressed relative to this query's position, so only the window needs it.
 //   HP: the query and the temporary key come unrounded from Qf / Ktf and the window keys are head K plus
 //   remainder Klo, so that no logit carries a bf16 rounding of q or k.
 // =============================================================================================
@@ -28,7 +30,7 @@ __device__ __forceinline__ void merge_body(const T *__restrict__ Q, const float 
                                            const float *__restrict__ po, float *__restrict__ attn_cat, int BH, int H,
                                            int bh, int t, int q_row, int p_min, int log2_pmin, int levels, int slots,
                                            int n_splits, float scale, int far_rel = -1, int log2_chunk = 0,
-                                           bf16_t *__restrict__ op_a = nullptr)
+                                           bf16_t *__restrict__ op_a = nullptr, float alibi = 0.f)
 {
     const int lane = threadIdx.x & 63;
     const size_t rs = (size_t)BH * kHeadDim;
@@ -89,7 +91,9 @@ __device__ __forceinline__ void merge_body(const T *__restrict__ Q, const float 
         const int w = t & (p_min - 1);
         if (w > 0) {
             const size_t base = (size_t)(t - w) * rs + (size_t)bh * kHeadDim;
-            attend_keys<T, HP>(q, K + base, V + base, rs, w, scale, m, l, o, HP ? Klo + base : nullptr);
+            // window key j is w - j positions before the query; stored partial states are already in this query's frame
+            attend_keys<T, HP>(q, K + base, V + base, rs, w, scale, m, l, o, HP ? Klo + base : nullptr,
+                               alibi_slope(alibi, bh % H, H), w);
         }
     }
     const int b = bh / H, h = bh % H;

@@ -66,10 +66,13 @@ __device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + e
 // 64 keys lane j owns key j.  m, l are wave-uniform.
 // =============================================================================================
 // With HP the keys are Kb + Klo_b (bf16 head plus bf16 remainder, same row layout).
+// Linear positional bias (ALiBi): key j of the run is dist_first - j positions before the query and its logit is
+// lowered by slope times that distance (slope = 0: no bias).
 template <typename T, bool HP = false>
 __device__ __forceinline__ void attend_keys(float q, const T *__restrict__ Kb, const T *__restrict__ Vb,
                                             size_t row_stride, int nkeys, float scale, float &m, float &l, float &o,
-                                            const bf16_t *__restrict__ Klo_b = nullptr)
+                                            const bf16_t *__restrict__ Klo_b = nullptr, float slope = 0.f,
+                                            int dist_first = 0)
 {
     const int lane = threadIdx.x & 63;
     for (int k0 = 0; k0 < nkeys; k0 += 64) {
@@ -90,7 +93,7 @@ __device__ __forceinline__ void attend_keys(float q, const T *__restrict__ Kb, c
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], acc);
         }
-        const float logit = valid ? acc * scale : -INFINITY;
+        const float logit = valid ? fmaf(-slope, (float)(dist_first - j), acc * scale) : -INFINITY;
         const float m_new = fmaxf(m, wave_max(logit));
         const float resc = expf(m - m_new);  // exp(-inf) = 0 on the first chunk
         const float p = valid ? expf(logit - m_new) : 0.f;
@@ -116,7 +119,14 @@ struct LayerDims {
     int p_min, log2_pmin;
     float alpha, scale, eps;
     int norm_free;
+    float alibi;   // maximum ALiBi bias beta (head slopes 2^(-beta (h+1)/H)); 0 = no positional bias
 };
+
+// ALiBi slope of head h (Press et al.: a geometric sequence over the heads)
+__host__ __device__ __forceinline__ float alibi_slope(float beta, int h, int H)
+{
+    return beta > 0.f ? exp2f(-beta * (float)(h + 1) / (float)H) : 0.f;
+}
 
 struct Weights {
     const void *Wq, *Wk, *Wv, *Wo, *W1, *W2;

@@ -56,13 +56,16 @@ __device__ __forceinline__ f32x16_t mfma32u(const uint4 &a, const uint4 &b, f32x
 //             from it is hoisted out of that loop and kept in registers)
 // Query j sits in row (c_first + q_shift + j) of Q / Qf and its partial goes to the slot of (level, c_first + j).
 // P is a multiple of 64.
-template <bool HP, int NW, int NBUF>
+// ALIBI (linear positional bias, slope per head): inside the tile the bias is taken relative to the block's last
+// key, slope * (j - j_last) <= 0, the same for every query; the stored maximum is moved into the query's own frame
+// when it is written (m -= slope * (i_query - j_last)).  The reference value then follows the biased logits.
+template <bool HP, int NW, int NBUF, bool ALIBI = false>
 __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, const float *__restrict__ Qf,
                                               const bf16_t *__restrict__ K, const bf16_t *__restrict__ Klo,
                                               const bf16_t *__restrict__ VT, int vt_stride, float *__restrict__ pm,
                                               float *__restrict__ pl, float *__restrict__ po, int BH, int bh, int c_first,
                                               int q_shift, int k_first, int P, int q0, int nq, int level, int level_rel,
-                                              int slots, float scale, unsigned char *lds, int tid)
+                                              int slots, float scale, unsigned char *lds, int tid, float slope = 0.f)
 {
     constexpr int T = 64 * NW;
     constexpr int kPieces = kKC * 8;              // 16-byte pieces of one 64 x 64 bf16 tile
@@ -178,6 +181,18 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
                 for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bq[ks], acc);
                 S[kt] = acc;
             }
+            if (ALIBI) {
+                // register i of tile kt is key 64c + 32kt + 8(i/4) + 4hi + i%4 of the block; from here on S holds the
+                // biased logits in log2 units (c2 is applied here instead of below)
+                const float s2 = slope * kLog2e;
+                const float base = s2 * (float)(c * kKC + 4 * hi - (P - 1));
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        S[kt][i] = fmaf(S[kt][i], c2, fmaf(s2, (float)(32 * kt + 8 * (i / 4) + (i % 4)), base));
+            }
+            const float c2e = ALIBI ? 1.f : c2;   // what still multiplies S below
             // ---- move the reference where a logit runs more than kSlack ahead of it (always on the first chunk)
             float lmax = fmaxf(fmaxf(S[0][0], S[0][1]), S[0][2]);
 #pragma unroll
@@ -185,7 +200,7 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
             lmax = fmaxf(fmaxf(lmax, S[0][15]), S[1][0]);
 #pragma unroll
             for (int i = 1; i < 15; i += 2) lmax = fmaxf(fmaxf(lmax, S[1][i]), S[1][i + 1]);
-            lmax = fmaxf(lmax, S[1][15]) * c2;
+            lmax = fmaxf(lmax, S[1][15]) * c2e;
             const bool over = lmax > m2 + kSlack;
             if (__any(over)) {
                 const float mx = fmaxf(lmax, __shfl_xor(lmax, 32, 64));
@@ -205,7 +220,7 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     const float sv = S[s4 >> 1][8 * (s4 & 1) + e];
-                    p[e] = __builtin_amdgcn_exp2f(fmaf(sv, c2, nm));
+                    p[e] = __builtin_amdgcn_exp2f(fmaf(sv, c2e, nm));
                 }
                 bp[s4] = make_uint4(cvt_pk_bf16(p[0], p[1]), cvt_pk_bf16(p[2], p[3]), cvt_pk_bf16(p[4], p[5]), cvt_pk_bf16(p[6], p[7]));
                 // plain adds: they run beside the matrix pipeline, which the dot-product and exponential instructions do not
@@ -234,7 +249,10 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
         const int qi = q0 + l32;
         if (qi < nq) {
             const size_t idx = partial_index(level_rel, partial_slot(level, c_first + qi), slots, BH, bh);
-            if (hi == 0) { pm[idx] = m2 * kLn2; pl[idx] = l; }
+            if (hi == 0) {
+                pm[idx] = ALIBI ? m2 * kLn2 - slope * (float)(c_first + q_shift + qi - (k_first + P - 1)) : m2 * kLn2;
+                pl[idx] = l;
+            }
             // register i of tile dt is head dimension 32dt + 8(i/4) + 4hi + i%4
             float *orow = po + idx * kHeadDim + 4 * hi;
 #pragma unroll

@@ -43,66 +43,47 @@ hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scrat
 // =============================================================================================
 // Cross-block UpdateTile as a stand-alone launch: queries [t1, t1+nq) against keys [t1-P, t1).
 // A wavefront owns 32 queries (two 16-query tiles); a block is 4 wavefronts = 128 queries.
-// grid (ceil(nq/128), B*H).
+// grid (ceil(nq/128), B*H).  HP: unrounded queries Qf, keys as head K plus remainder Klo (three products per
+// logit tile).  ALIBI: linear positional bias with the head's slope 2^(-alibi (h+1)/H).
 // =============================================================================================
-__global__ __launch_bounds__(256) void cross_mfma_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+template <bool HP, bool ALIBI>
+__global__ __launch_bounds__(256) void cross_mfma_kernel(const bf16_t *__restrict__ Q, const float *__restrict__ Qf,
+                                                         const bf16_t *__restrict__ K, const bf16_t *__restrict__ Klo,
                                                          const bf16_t *__restrict__ VT, int vt_stride,
                                                          float *__restrict__ pm, float *__restrict__ pl,
                                                          float *__restrict__ po, int BH, int t1, int P, int nq, int level,
-                                                         int level_rel, int slots, float scale)
+                                                         int level_rel, int slots, float scale, float alibi, int H)
 {
     const int wave = threadIdx.x >> 6;
     const int q0 = blockIdx.x * 128 + wave * 32;  // first query of this wavefront, relative to t1
     if (q0 >= nq) return;                         // no barriers in this kernel
-    cross_mfma_wave<false>(Q, nullptr, K, nullptr, VT, vt_stride, pm, pl, po, BH, blockIdx.y, t1, 0, t1 - P, P, q0, nq, level,
-                           level_rel, slots, scale);
+    cross_mfma_wave<HP, ALIBI>(Q, Qf, K, Klo, VT, vt_stride, pm, pl, po, BH, blockIdx.y, t1, 0, t1 - P, P, q0, nq, level,
+                               level_rel, slots, scale, ALIBI ? alibi_slope(alibi, (int)blockIdx.y % H, H) : 0.f);
 }
 
 // Same tile with K and V^T staged in LDS for the four wavefronts (128 queries) of a workgroup, blocks of
 // 64 keys and more.  Workgroups are dealt to the 8 XCDs round-robin by the dispatcher, so the index is
 // decoded such that all query blocks of one (b, h) land on the same XCD and its key/value tiles are
-// fetched into that L2 once.
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4, 4))) void cross_tile_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
-                                                         const bf16_t *__restrict__ VT, int vt_stride,
-                                                         float *__restrict__ pm, float *__restrict__ pl,
-                                                         float *__restrict__ po, int BH, int t1, int P, int nq, int nqb,
-                                                         int level, int level_rel, int slots, float scale)
-{
-    __shared__ __align__(16) unsigned char lds[2 * cross_tile_lds_bytes<false>()];
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int bh = (j / nqb) * 8 + xcd, qb = j % nqb;
-    if (bh >= BH) return;   // the whole workgroup leaves together
-    cross_tile_wg<false, 4, 2>(Q, nullptr, K, nullptr, VT, vt_stride, pm, pl, po, BH, bh, t1, 0, t1 - P, P,
-                               qb * 128 + (int)(threadIdx.x >> 6) * 32, nq, level, level_rel, slots, scale, lds, (int)threadIdx.x);
-}
-
-// The same two kernels with high-precision logits: unrounded queries Qf, keys as head K plus remainder Klo
-// (three products per logit tile).  The three LDS tiles per buffer leave room for two workgroups per compute unit.
-__global__ __launch_bounds__(256) void cross_mfma_hp_kernel(const float *__restrict__ Qf, const bf16_t *__restrict__ K,
-                                                            const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT,
-                                                            int vt_stride, float *__restrict__ pm, float *__restrict__ pl,
-                                                            float *__restrict__ po, int BH, int t1, int P, int nq, int level,
-                                                            int level_rel, int slots, float scale)
-{
-    const int wave = threadIdx.x >> 6;
-    const int q0 = blockIdx.x * 128 + wave * 32;
-    if (q0 >= nq) return;                         // no barriers in this kernel
-    cross_mfma_wave<true>(nullptr, Qf, K, Klo, VT, vt_stride, pm, pl, po, BH, blockIdx.y, t1, 0, t1 - P, P, q0, nq, level,
-                          level_rel, slots, scale);
-}
-
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void cross_tile_hp_kernel(
-    const float *__restrict__ Qf, const bf16_t *__restrict__ K, const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT,
-    int vt_stride, float *__restrict__ pm, float *__restrict__ pl, float *__restrict__ po, int BH, int t1, int P, int nq,
-    int nqb, int level, int level_rel, int slots, float scale)
-{
-    __shared__ __align__(16) unsigned char lds[2 * cross_tile_lds_bytes<true>()];
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int bh = (j / nqb) * 8 + xcd, qb = j % nqb;
-    if (bh >= BH) return;   // the whole workgroup leaves together
-    cross_tile_wg<true, 4, 2>(nullptr, Qf, K, Klo, VT, vt_stride, pm, pl, po, BH, bh, t1, 0, t1 - P, P,
-                              qb * 128 + (int)(threadIdx.x >> 6) * 32, nq, level, level_rel, slots, scale, lds, (int)threadIdx.x);
-}
+// fetched into that L2 once.  The HP form's three LDS tiles per buffer leave room for two workgroups per compute unit.
+#define RT_CROSS_TILE_KERNEL(NAME, HPv, WAVES)                                                                              \
+    template <bool ALIBI>                                                                                                   \
+    __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES))) void NAME(                        \
+        const bf16_t *__restrict__ Q, const float *__restrict__ Qf, const bf16_t *__restrict__ K,                          \
+        const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT, int vt_stride, float *__restrict__ pm,              \
+        float *__restrict__ pl, float *__restrict__ po, int BH, int t1, int P, int nq, int nqb, int level, int level_rel,  \
+        int slots, float scale, float alibi, int H)                                                                         \
+    {                                                                                                                       \
+        __shared__ __align__(16) unsigned char lds[2 * cross_tile_lds_bytes<HPv>()];                                        \
+        const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;                                                                \
+        const int bh = (j / nqb) * 8 + xcd, qb = j % nqb;                                                                   \
+        if (bh >= BH) return; /* the whole workgroup leaves together */                                                     \
+        cross_tile_wg<HPv, 4, 2, ALIBI>(Q, Qf, K, Klo, VT, vt_stride, pm, pl, po, BH, bh, t1, 0, t1 - P, P,                 \
+                                        qb * 128 + (int)(threadIdx.x >> 6) * 32, nq, level, level_rel, slots, scale, lds,   \
+                                        (int)threadIdx.x, ALIBI ? alibi_slope(alibi, bh % H, H) : 0.f);                     \
+    }
+RT_CROSS_TILE_KERNEL(cross_tile_kernel, false, 4)
+RT_CROSS_TILE_KERNEL(cross_tile_hp_kernel, true, 2)
+#undef RT_CROSS_TILE_KERNEL
 
 hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, bool hp,
                              hipStream_t st)
@@ -110,27 +91,26 @@ hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K
     int level = 0;
     while ((1 << level) < P) ++level;
     const int nqb = (nq + 127) / 128;
-    const int bh8 = (D.B * D.H + 7) / 8 * 8;
-    if (hp) {
-        if (P >= kKC)
-            hipLaunchKernelGGL(cross_tile_hp_kernel, dim3(bh8 * nqb), dim3(256), 0, st, S.Qf, (const bf16_t *)K, S.Klo, S.VT,
-                               S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, nqb, level, level - D.log2_pmin, S.slots,
-                               D.scale);
-        else
-            hipLaunchKernelGGL(cross_mfma_hp_kernel, dim3(nqb, D.B * D.H), dim3(256), 0, st, S.Qf, (const bf16_t *)K, S.Klo,
-                               S.VT, S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, level, level - D.log2_pmin, S.slots,
-                               D.scale);
-        return hipGetLastError();
-    }
+    const int BH = D.B * D.H, bh8 = (BH + 7) / 8 * 8;
+    const bool al = D.alibi > 0.f;
+    const bf16_t *Q = (const bf16_t *)S.Q, *Kb = (const bf16_t *)K;
+#define RT_TILE_ARGS Q, S.Qf, Kb, S.Klo, S.VT, S.vt_stride, S.pm, S.pl, S.po, BH, t1, P, nq, nqb, level, level - D.log2_pmin, S.slots, D.scale, D.alibi, D.H
+#define RT_WAVE_ARGS Q, S.Qf, Kb, S.Klo, S.VT, S.vt_stride, S.pm, S.pl, S.po, BH, t1, P, nq, level, level - D.log2_pmin, S.slots, D.scale, D.alibi, D.H
     if (P >= kKC) {
-        hipLaunchKernelGGL(cross_tile_kernel, dim3(bh8 * nqb), dim3(256), 0, st, (const bf16_t *)S.Q, (const bf16_t *)K, S.VT,
-                           S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, nqb, level, level - D.log2_pmin, S.slots,
-                           D.scale);
-        return hipGetLastError();
+        const dim3 grid(bh8 * nqb);
+        if (hp && al) hipLaunchKernelGGL(cross_tile_hp_kernel<true>, grid, dim3(256), 0, st, RT_TILE_ARGS);
+        else if (hp) hipLaunchKernelGGL(cross_tile_hp_kernel<false>, grid, dim3(256), 0, st, RT_TILE_ARGS);
+        else if (al) hipLaunchKernelGGL(cross_tile_kernel<true>, grid, dim3(256), 0, st, RT_TILE_ARGS);
+        else hipLaunchKernelGGL(cross_tile_kernel<false>, grid, dim3(256), 0, st, RT_TILE_ARGS);
+    } else {
+        const dim3 grid(nqb, BH);
+        if (hp && al) hipLaunchKernelGGL((cross_mfma_kernel<true, true>), grid, dim3(256), 0, st, RT_WAVE_ARGS);
+        else if (hp) hipLaunchKernelGGL((cross_mfma_kernel<true, false>), grid, dim3(256), 0, st, RT_WAVE_ARGS);
+        else if (al) hipLaunchKernelGGL((cross_mfma_kernel<false, true>), grid, dim3(256), 0, st, RT_WAVE_ARGS);
+        else hipLaunchKernelGGL((cross_mfma_kernel<false, false>), grid, dim3(256), 0, st, RT_WAVE_ARGS);
     }
-    hipLaunchKernelGGL(cross_mfma_kernel, dim3(nqb, D.B * D.H), dim3(256), 0, st, (const bf16_t *)S.Q,
-                       (const bf16_t *)K, S.VT, S.vt_stride, S.pm, S.pl, S.po, D.B * D.H, t1, P, nq, level,
-                       level - D.log2_pmin, S.slots, D.scale);
+#undef RT_TILE_ARGS
+#undef RT_WAVE_ARGS
     return hipGetLastError();
 }
 

@@ -43,11 +43,14 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
 // bf16 remainder, the keys come as head K plus remainder Klo, and S^T = Khi Qhi + Khi Qlo + Klo Qhi:
 // the logits then carry no bf16 rounding of q or k (they are sharp here: |q| = |k| = 8, and every
 // rounding of a logit input shows up as a few per cent on individual softmax weights).
-template <bool HP>
+// ALIBI: the logit of key j is lowered by slope * (distance to the query).  Inside the tile the bias is taken
+// relative to the block's last key (slope * (j - j_last) <= 0, the same for every query), and the stored maximum
+// is moved into the query's own frame when it is written: m -= slope * (i_query - j_last).
+template <bool HP, bool ALIBI = false>
 __device__ __forceinline__ void cross_mfma_wave(const bf16_t *Q, const float *Qf, const bf16_t *K, const bf16_t *Klo,
                                                 const bf16_t *VT, int vt_stride, float *pm, float *pl, float *po, int BH,
                                                 int bh, int c_first, int q_shift, int k_first, int P, int q0, int nq,
-                                                int level, int level_rel, int slots, float scale)
+                                                int level, int level_rel, int slots, float scale, float slope = 0.f)
 {
     const int lane = threadIdx.x & 63;
     const int l16 = lane & 15, g = lane >> 4;
@@ -116,6 +119,13 @@ __device__ __forceinline__ void cross_mfma_wave(const bf16_t *Q, const float *Qf
             float s[8];
 #pragma unroll
             for (int r = 0; r < 4; ++r) { s[r] = S[qt][0][r] * scale; s[4 + r] = S[qt][1][r] * scale; }
+            if (ALIBI) {   // element r of tile kt is key kc + 16 kt + 4g + r of the block
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    s[r] = fmaf(slope, (float)(kc + 4 * g + r - (P - 1)), s[r]);
+                    s[4 + r] = fmaf(slope, (float)(kc + 16 + 4 * g + r - (P - 1)), s[4 + r]);
+                }
+            }
             float mx = s[0];
 #pragma unroll
             for (int e = 1; e < 8; ++e) mx = fmaxf(mx, s[e]);
@@ -154,7 +164,11 @@ __device__ __forceinline__ void cross_mfma_wave(const bf16_t *Q, const float *Qf
         const int qi = q0 + qt * 16 + l16;
         if (qi < nq) {
             const size_t idx = partial_index(level_rel, partial_slot(level, c_first + qi), slots, BH, bh);
-            if (g == 0) { pm[idx] = m[qt]; pl[idx] = l; }
+            if (g == 0) {
+                // ALIBI: query row c_first + q_shift + qi is that many positions after the block's last key
+                pm[idx] = ALIBI ? m[qt] - slope * (float)(c_first + q_shift + qi - (k_first + P - 1)) : m[qt];
+                pl[idx] = l;
+            }
             float *orow = po + idx * kHeadDim + 4 * g;
 #pragma unroll
             for (int blk = 0; blk < 4; ++blk)

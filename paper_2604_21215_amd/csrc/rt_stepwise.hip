@@ -17,7 +17,8 @@ template <typename T>
 __global__ __launch_bounds__(64) void cross_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                            const T *__restrict__ V, float *__restrict__ pm,
                                                            float *__restrict__ pl, float *__restrict__ po, int BH, int t1,
-                                                           int P, int level, int level_rel, int slots, float scale)
+                                                           int P, int level, int level_rel, int slots, float scale,
+                                                           float alibi, int H)
 {
     const int lane = threadIdx.x;
     const int i0 = t1 + blockIdx.x;
@@ -26,7 +27,7 @@ __global__ __launch_bounds__(64) void cross_generic_kernel(const T *__restrict__
     const float q = to_f32(Q[(size_t)i0 * rs + (size_t)bh * kHeadDim + lane]);
     float m = -INFINITY, l = 0.f, o = 0.f;
     attend_keys<T>(q, K + (size_t)(t1 - P) * rs + (size_t)bh * kHeadDim, V + (size_t)(t1 - P) * rs + (size_t)bh * kHeadDim,
-                   rs, P, scale, m, l, o);
+                   rs, P, scale, m, l, o, nullptr, alibi_slope(alibi, bh % H, H), i0 - (t1 - P));
     const size_t idx = partial_index(level_rel, partial_slot(level, i0), slots, BH, bh);
     if (lane == 0) { pm[idx] = m; pl[idx] = l; }
     po[idx * kHeadDim + lane] = o;
@@ -38,7 +39,7 @@ template <typename T>
 __global__ __launch_bounds__(64) void decode_split_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                           const T *__restrict__ V, float *__restrict__ pm,
                                                           float *__restrict__ pl, float *__restrict__ po, int BH, int t,
-                                                          int chunk, int slots, float scale)
+                                                          int chunk, int slots, float scale, float alibi, int H)
 {
     const int lane = threadIdx.x;
     const int split = blockIdx.x, bh = blockIdx.y;
@@ -47,7 +48,7 @@ __global__ __launch_bounds__(64) void decode_split_kernel(const T *__restrict__ 
     const float q = to_f32(Q[(size_t)bh * kHeadDim + lane]);
     float m = -INFINITY, l = 0.f, o = 0.f;
     attend_keys<T>(q, K + (size_t)k_lo * rs + (size_t)bh * kHeadDim, V + (size_t)k_lo * rs + (size_t)bh * kHeadDim, rs,
-                   k_hi - k_lo, scale, m, l, o);
+                   k_hi - k_lo, scale, m, l, o, nullptr, alibi_slope(alibi, bh % H, H), t - k_lo);
     const size_t idx = partial_index(0, split, slots, BH, bh);
     if (lane == 0) { pm[idx] = m; pl[idx] = l; }
     po[idx * kHeadDim + lane] = o;
@@ -63,10 +64,10 @@ __global__ __launch_bounds__(64) void merge_kernel(const T *__restrict__ Q, cons
                                                    const float *__restrict__ pl, const float *__restrict__ po,
                                                    float *__restrict__ attn_cat, int BH, int H, int t, int q_row,
                                                    int p_min, int log2_pmin, int levels, int slots, int n_splits,
-                                                   float scale)
+                                                   float scale, float alibi)
 {
     merge_body<T, false>(Q, nullptr, Kt, nullptr, Vt, K, nullptr, V, pm, pl, po, attn_cat, BH, H, blockIdx.x, t, q_row, p_min,
-                         log2_pmin, levels, slots, n_splits, scale);
+                         log2_pmin, levels, slots, n_splits, scale, -1, 0, nullptr, alibi);
 }
 
 // =============================================================================================
@@ -268,7 +269,7 @@ hipError_t Launch<T>::merge(const LayerDims &D, const Scratch &S, const void *K,
 {
     hipLaunchKernelGGL(merge_kernel<T>, dim3(D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)S.Kt,
                        (const T *)S.Vt, (const T *)K, (const T *)V, S.pm, S.pl, S.po, S.attn_cat, D.B * D.H, D.H, t, q_row,
-                       D.p_min, D.log2_pmin, S.levels, S.slots, n_decode_splits, D.scale);
+                       D.p_min, D.log2_pmin, S.levels, S.slots, n_decode_splits, D.scale, D.alibi);
     return hipGetLastError();
 }
 
@@ -362,7 +363,8 @@ hipError_t Launch<T>::cross(const LayerDims &D, const Scratch &S, const void *K,
     while ((1 << level) < P) ++level;
     if (mfma && sizeof(T) == 2) return cross_mfma_launch(D, S, K, t1, P, nq, false, st);
     hipLaunchKernelGGL(cross_generic_kernel<T>, dim3(nq, D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)K,
-                       (const T *)V, S.pm, S.pl, S.po, D.B * D.H, t1, P, level, level - D.log2_pmin, S.slots, D.scale);
+                       (const T *)V, S.pm, S.pl, S.po, D.B * D.H, t1, P, level, level - D.log2_pmin, S.slots, D.scale, D.alibi,
+                       D.H);
     return hipGetLastError();
 }
 
@@ -371,7 +373,7 @@ hipError_t Launch<T>::decode_split(const LayerDims &D, const Scratch &S, const v
                                    int nsplit, hipStream_t st)
 {
     hipLaunchKernelGGL(decode_split_kernel<T>, dim3(nsplit, D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)K,
-                       (const T *)V, S.pm, S.pl, S.po, D.B * D.H, t, chunk, S.slots, D.scale);
+                       (const T *)V, S.pm, S.pl, S.po, D.B * D.H, t, chunk, S.slots, D.scale, D.alibi, D.H);
     return hipGetLastError();
 }
 

@@ -37,14 +37,15 @@ __device__ __forceinline__ int layer_pos(int t0, int l, int chunk) { return t0 -
 
 template <typename T, bool HP>
 __global__ __launch_bounds__(64) void wf_merge_kernel(const WaveLayer *__restrict__ layers, int l_first, int s, int chunk,
-                                                      int log2_chunk, int BH, int H, int p_min, int log2_pmin, float scale)
+                                                      int log2_chunk, int BH, int H, int p_min, int log2_pmin, float scale,
+                                                      float alibi)
 {
     const int l = l_first + blockIdx.y, t = layer_pos(s, l, chunk);
     const WaveLayer &Y = layers[l];
     const int tree_levels = log2_chunk - log2_pmin;
     merge_body<T, HP>((const T *)Y.S.Q, Y.S.Qf, (const T *)Y.S.Kt, Y.S.Ktf, (const T *)Y.S.Vt, (const T *)Y.K, Y.S.Klo,
                       (const T *)Y.V, Y.S.pm, Y.S.pl, Y.S.po, Y.S.attn_cat, BH, H, blockIdx.x, t, t, p_min, log2_pmin, tree_levels,
-                      Y.S.slots, -1, scale, tree_levels, log2_chunk, HP ? Y.S.op_a : nullptr);
+                      Y.S.slots, -1, scale, tree_levels, log2_chunk, HP ? Y.S.op_a : nullptr, alibi);
 }
 
 template <typename T> struct StackedRows {   // rows o < n_first from Wa, the rest from Wb
@@ -353,9 +354,10 @@ __device__ __forceinline__ CrossJob cross_job(int t1_0, int l, int chunk, int N,
 }
 
 // blocks of 64 keys and more, LDS-staged; grid (8 * ceil(BH/8) * nqb, layers), block 256
+template <bool ALIBI>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void wf_cross_tile_kernel(
     const WaveLayer *__restrict__ layers, int l_first, int t1_0, int chunk, int N, int far, int P_tree, int far_rel,
-    int log2_pmin, int BH, int nqb, float scale)
+    int log2_pmin, int BH, int nqb, float scale, float alibi, int H)
 {
     __shared__ __align__(16) unsigned char lds[2 * cross_tile_lds_bytes<true>()];
     const int l = l_first + blockIdx.y;
@@ -364,30 +366,33 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int bh = (j / nqb) * 8 + xcd, qb = j % nqb;
     if (!J.any || bh >= BH || qb * 128 >= J.nq) return;   // the whole workgroup leaves together
     const WaveLayer &Y = layers[l];
-    cross_tile_wg<true, 4, 2>(nullptr, Y.S.Qf, (const bf16_t *)Y.K, Y.S.Klo, Y.S.VT, Y.S.vt_stride, Y.S.pm, Y.S.pl, Y.S.po, BH, bh,
-                              J.t1, 0, J.t1 - J.P, J.P, qb * 128 + (int)(threadIdx.x >> 6) * 32, J.nq, J.level, J.level_rel,
-                              Y.S.slots, scale, lds, (int)threadIdx.x);
+    cross_tile_wg<true, 4, 2, ALIBI>(nullptr, Y.S.Qf, (const bf16_t *)Y.K, Y.S.Klo, Y.S.VT, Y.S.vt_stride, Y.S.pm, Y.S.pl, Y.S.po,
+                                     BH, bh, J.t1, 0, J.t1 - J.P, J.P, qb * 128 + (int)(threadIdx.x >> 6) * 32, J.nq, J.level,
+                                     J.level_rel, Y.S.slots, scale, lds, (int)threadIdx.x,
+                                     ALIBI ? alibi_slope(alibi, bh % H, H) : 0.f);
 }
 
 // blocks of 32 keys (any multiple of 32); grid (ceil(nq/128), B*H, layers), block 256, no barriers
+template <bool ALIBI>
 __global__ __launch_bounds__(256) void wf_cross_wave_kernel(const WaveLayer *__restrict__ layers, int l_first, int t1_0, int chunk,
                                                             int N, int far, int P_tree, int far_rel, int log2_pmin, int BH,
-                                                            float scale)
+                                                            float scale, float alibi, int H)
 {
     const int l = l_first + blockIdx.z;
     const CrossJob J = cross_job(t1_0, l, chunk, N, far, P_tree, far_rel, log2_pmin);
     const int q0 = blockIdx.x * 128 + (int)(threadIdx.x >> 6) * 32;
     if (!J.any || q0 >= J.nq) return;
     const WaveLayer &Y = layers[l];
-    cross_mfma_wave<true>(nullptr, Y.S.Qf, (const bf16_t *)Y.K, Y.S.Klo, Y.S.VT, Y.S.vt_stride, Y.S.pm, Y.S.pl, Y.S.po, BH,
-                          blockIdx.y, J.t1, 0, J.t1 - J.P, J.P, q0, J.nq, J.level, J.level_rel, Y.S.slots, scale);
+    cross_mfma_wave<true, ALIBI>(nullptr, Y.S.Qf, (const bf16_t *)Y.K, Y.S.Klo, Y.S.VT, Y.S.vt_stride, Y.S.pm, Y.S.pl, Y.S.po, BH,
+                                 blockIdx.y, J.t1, 0, J.t1 - J.P, J.P, q0, J.nq, J.level, J.level_rel, Y.S.slots, scale,
+                                 ALIBI ? alibi_slope(alibi, (int)blockIdx.y % H, H) : 0.f);
 }
 
 // plain-ALU form (fp32 storage, or bf16 without the MFMA kernels); grid (max nq, B*H, layers), block 64
 template <typename T>
 __global__ __launch_bounds__(64) void wf_cross_generic_kernel(const WaveLayer *__restrict__ layers, int l_first, int t1_0,
                                                               int chunk, int N, int far, int P_tree, int far_rel, int log2_pmin,
-                                                              int BH, float scale)
+                                                              int BH, float scale, float alibi, int H)
 {
     const int lane = threadIdx.x, bh = blockIdx.y;
     const int l = l_first + blockIdx.z;
@@ -399,7 +404,8 @@ __global__ __launch_bounds__(64) void wf_cross_generic_kernel(const WaveLayer *_
     const float q = to_f32(((const T *)Y.S.Q)[(size_t)i0 * rs + (size_t)bh * kHeadDim + lane]);
     float m = -INFINITY, lsum = 0.f, o = 0.f;
     const size_t kb = (size_t)(J.t1 - J.P) * rs + (size_t)bh * kHeadDim;
-    attend_keys<T>(q, (const T *)Y.K + kb, (const T *)Y.V + kb, rs, J.P, scale, m, lsum, o);
+    attend_keys<T>(q, (const T *)Y.K + kb, (const T *)Y.V + kb, rs, J.P, scale, m, lsum, o, nullptr,
+                   alibi_slope(alibi, bh % H, H), i0 - (J.t1 - J.P));
     const size_t idx = partial_index(J.level_rel, partial_slot(J.level, i0), Y.S.slots, BH, bh);
     if (lane == 0) { Y.S.pm[idx] = m; Y.S.pl[idx] = lsum; }
     Y.S.po[idx * kHeadDim + lane] = o;
@@ -415,15 +421,23 @@ static hipError_t wf_cross_launch(const LayerDims &D, const WaveLayer *dev_layer
         // far tiles cover a multiple of the chunk (>= 64 keys); tree blocks of 64 keys and more use the same kernel
         if (far || P_tree >= kKC) {
             const int nqb = (max_nq + 127) / 128, bh8 = (BH + 7) / 8 * 8;
-            hipLaunchKernelGGL(wf_cross_tile_kernel, dim3(bh8 * nqb, nl), dim3(256), 0, st, dev_layers, l0, t1_0, chunk, D.N, far,
-                               P_tree, far_rel, D.log2_pmin, BH, nqb, D.scale);
+            if (D.alibi > 0.f)
+                hipLaunchKernelGGL(wf_cross_tile_kernel<true>, dim3(bh8 * nqb, nl), dim3(256), 0, st, dev_layers, l0, t1_0, chunk,
+                                   D.N, far, P_tree, far_rel, D.log2_pmin, BH, nqb, D.scale, D.alibi, D.H);
+            else
+                hipLaunchKernelGGL(wf_cross_tile_kernel<false>, dim3(bh8 * nqb, nl), dim3(256), 0, st, dev_layers, l0, t1_0, chunk,
+                                   D.N, far, P_tree, far_rel, D.log2_pmin, BH, nqb, D.scale, D.alibi, D.H);
         } else {
-            hipLaunchKernelGGL(wf_cross_wave_kernel, dim3((max_nq + 127) / 128, BH, nl), dim3(256), 0, st, dev_layers, l0, t1_0,
-                               chunk, D.N, far, P_tree, far_rel, D.log2_pmin, BH, D.scale);
+            if (D.alibi > 0.f)
+                hipLaunchKernelGGL(wf_cross_wave_kernel<true>, dim3((max_nq + 127) / 128, BH, nl), dim3(256), 0, st, dev_layers, l0,
+                                   t1_0, chunk, D.N, far, P_tree, far_rel, D.log2_pmin, BH, D.scale, D.alibi, D.H);
+            else
+                hipLaunchKernelGGL(wf_cross_wave_kernel<false>, dim3((max_nq + 127) / 128, BH, nl), dim3(256), 0, st, dev_layers,
+                                   l0, t1_0, chunk, D.N, far, P_tree, far_rel, D.log2_pmin, BH, D.scale, D.alibi, D.H);
         }
     } else {
         hipLaunchKernelGGL(wf_cross_generic_kernel<T>, dim3(max_nq, BH, nl), dim3(64), 0, st, dev_layers, l0, t1_0, chunk, D.N,
-                           far, P_tree, far_rel, D.log2_pmin, BH, D.scale);
+                           far, P_tree, far_rel, D.log2_pmin, BH, D.scale, D.alibi, D.H);
     }
     return hipGetLastError();
 }
@@ -552,7 +566,7 @@ static hipError_t wavefront_steps(const LayerDims &D, const WaveLayer *dev_layer
                 }
             }
             hipLaunchKernelGGL((wf_merge_kernel<T, HP>), dim3(BH, nl), dim3(64), 0, st, dev_layers, l0, s, chunk, log2_chunk, BH,
-                               D.H, D.p_min, D.log2_pmin, D.scale);
+                               D.H, D.p_min, D.log2_pmin, D.scale, D.alibi);
             if (HP && use_mm) {
                 if ((e = mm_launch<EPI_WO, 4, 8>(d, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;
                 if ((e = mm_launch<EPI_W1, 1, 4>(F, nl, st, dev_layers, l0, s, chunk, D)) != hipSuccess) return e;

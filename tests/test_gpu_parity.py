@@ -23,14 +23,14 @@ def _gpu():
 
 
 def _run_case(oracle, dtype, B, N, d, H, F, *, flags=0, p_min=0, gains="unit", seed=5, alpha=1.0, scale=1.0,
-              eps=1e-6, kv_cap=None, li=None, tol_scale=1.0, expect_engine=None):
+              eps=1e-6, kv_cap=None, li=None, tol_scale=1.0, expect_engine=None, alibi=0.0, n_decode=0):
     binding, tio = _gpu()
     if li is None:
         li = gen.make_custom(seed, dtype, B, N, d, H, F, gains=gains)
     x64 = li.x.astype(np.float64)
-    ref = oracle_layer(oracle, li, H, alpha=alpha, attn_scale=scale, eps=eps).prefill(x64)
+    ref = oracle_layer(oracle, li, H, alpha=alpha, attn_scale=scale, eps=eps, alibi_max_bias=alibi).prefill(x64)
     ctx = binding.RTContext(d, H, F, B, N, dtype, p_min=p_min, resid_scale=alpha, attn_scale=scale, rms_eps=eps,
-                            flags=flags)
+                            flags=flags, alibi_max_bias=alibi)
     try:
         dl = tio.DeviceLayer(li.weights, li.gains, dtype)
         xd = tio.to_device(li.x, dtype)
@@ -40,6 +40,13 @@ def _run_case(oracle, dtype, B, N, d, H, F, *, flags=0, p_min=0, gains="unit", s
         if expect_engine:
             assert ctx.engine_name() == expect_engine
         got = (tio.to_host(y), tio.to_host(K), tio.to_host(V))
+        # the last n_decode positions once more, one rt_decode_step each over the cache the prefill left
+        for t in range(N - n_decode, N):
+            y_t = torch.empty_like(xd[:, t])
+            ctx.rt_decode_step(dl.struct, xd[:, t].contiguous(), t, y_t, K, V)
+            torch.cuda.synchronize()
+            e = np.linalg.norm(tio.to_host(y_t) - ref[0][:, t], axis=-1) / np.linalg.norm(ref[0][:, t], axis=-1)
+            assert e.max() <= TOL[dtype] * tol_scale, "decode step %d: %.3e" % (t, e.max())
     finally:
         ctx.rt_destroy()
     cur = error_curves(x64, ref, got)
@@ -95,6 +102,33 @@ def test_stepwise_bf16_plain_alu_and_mfma_agree_with_oracle(oracle):
     _run_case(oracle, "bf16", 3, 300, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=32, gains="random",
               alpha=0.7, scale=0.5, kv_cap=320)
     _run_case(oracle, "bf16", 5, 333, 320, 5, 1280, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=64)   # odd head count, ragged N
+
+
+# ----------------------------------------------------------------------------- ALiBi
+@pytest.mark.parametrize("N,p_min", [(100, 4), (150, 32), (40, 1)])
+def test_alibi_stepwise_f32(oracle, N, p_min):
+    """Linear positional bias (maximum bias 8, slopes 2^(-8 (h+1)/H)) through every plain-ALU kernel: direct window,
+    stored partial states of several levels, the temporary pair at distance 0, and decoding steps over the cache."""
+    b = _flags()
+    _run_case(oracle, "f32", 2, N, 256, 4, 512, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=p_min, alibi=8.0, gains="random",
+              scale=0.5, n_decode=3, expect_engine="stepwise")
+
+
+def test_alibi_bf16_mfma_tiles(oracle):
+    """The matrix-core tiles with the bias: 32-key blocks (wave kernel), 64 .. 256-key blocks (LDS-staged kernel,
+    several chunks per block), a ragged tail; the default engine choice falls to the per-position engine."""
+    b = _flags()
+    _run_case(oracle, "bf16", 2, 600, 256, 4, 1024, p_min=32, alibi=8.0, n_decode=2, expect_engine="stepwise")
+    _run_case(oracle, "bf16", 3, 333, 320, 5, 1280, p_min=64, alibi=3.0, scale=0.5, gains="random", expect_engine="stepwise")
+    _run_case(oracle, "bf16", 2, 200, 256, 4, 1024, flags=b.RT_FLAG_NO_MFMA, p_min=8, alibi=8.0)
+
+
+def test_alibi_rejected_where_not_covered():
+    binding, _ = _gpu()
+    with pytest.raises(binding.RTError):
+        binding.RTContext(256, 4, 1024, 2, 64, "bf16", flags=binding.RT_FLAG_ENGINE_PERSISTENT, alibi_max_bias=8.0)
+    with pytest.raises(binding.RTError):
+        binding.RTContext(256, 4, 1024, 2, 64, "bf16", alibi_max_bias=-1.0)
 
 
 def test_cross_block_tiles_with_several_query_blocks(oracle):

@@ -36,7 +36,7 @@ def _ids_dev(ids):
 EMB_UNIT = 50.0
 
 
-def _make_stack(oracle, wl, B, max_seq, flags=0, emb_scale=1.0, p_min=0):
+def _make_stack(oracle, wl, B, max_seq, flags=0, emb_scale=1.0, p_min=0, alibi=0.0):
     """Device stack and oracle stack over the same host buffers."""
     from paper_2604_21215_amd import binding, torch_io as tio
     from paper_2604_21215_amd.stack import DeviceStack
@@ -45,12 +45,13 @@ def _make_stack(oracle, wl, B, max_seq, flags=0, emb_scale=1.0, p_min=0):
         e = tabs["embedding"] * np.float32(emb_scale)
         tabs["embedding"] = gen.round_to_bf16(e) if wl.dtype == "bf16" else e
     ctx = binding.RTContext(wl.d, wl.H, wl.F, B, max_seq, wl.dtype, resid_scale=wl.resid_scale, rms_eps=1e-6, flags=flags,
-                            p_min=p_min, stream=torch.cuda.current_stream().cuda_stream)
+                            p_min=p_min, stream=torch.cuda.current_stream().cuda_stream, alibi_max_bias=alibi)
     dls, ols = [], []
     for l in range(wl.layers):
         w = gen.make_layer_weights(wl.seed, l, wl.d, wl.F, wl.dtype)
         dls.append(tio.DeviceLayer(w, None, wl.dtype))
-        ols.append(oracle.Layer({k: v.astype(np.float64) for k, v in w.items()}, wl.H, alpha=wl.resid_scale, eps=1e-6))
+        ols.append(oracle.Layer({k: v.astype(np.float64) for k, v in w.items()}, wl.H, alpha=wl.resid_scale, eps=1e-6,
+                                alibi_max_bias=alibi))
     ds = DeviceStack(ctx, dls, tabs["embedding"], tabs["lm_head"], None, wl.dtype)
     os_ = oracle.Stack(ols, tabs["embedding"].astype(np.float64), tabs["lm_head"].astype(np.float64), None, eps=1e-6)
     return ctx, ds, os_
@@ -72,12 +73,12 @@ def _fmt(rows):
     return " | ".join("L%d y %.1e K %.1e V %.1e" % (l, r[0], r[1], r[2]) for l, r in enumerate(rows))
 
 
-def _run_elementwise(oracle, wl, B, N, n_dec, flags=0, emb_scale=1.0, wavefront=False, chunk=0, p_min=0):
+def _run_elementwise(oracle, wl, B, N, n_dec, flags=0, emb_scale=1.0, wavefront=False, chunk=0, p_min=0, alibi=0.0):
     from paper_2604_21215_amd import torch_io as tio
     _need_gpu()
     T = N + n_dec
     ids = gen.make_token_ids(wl)[:B, :T]
-    ctx, ds, os_ = _make_stack(oracle, wl, B, T, flags, emb_scale, p_min)
+    ctx, ds, os_ = _make_stack(oracle, wl, B, T, flags, emb_scale, p_min, alibi)
     try:
         ref_layers, ref_logits = os_.prefill(ids, N, kv_cap=T)
         idd = _ids_dev(ids)
@@ -129,6 +130,18 @@ def test_small_bf16_stack_wavefront(oracle, N, chunk):
     keys before it)."""
     wl = gen.Workload("stack_small_bf16_wf", "bf16", 3, N, 256, 4, 1024, layers=4, vocab=1000, decode_steps=4, seed=994)
     _run_elementwise(oracle, wl, 3, N, 4, emb_scale=EMB_UNIT, wavefront=True, chunk=chunk)
+
+
+@pytest.mark.parametrize("dtype,N,chunk,p_min", [("f32", 130, 16, 4), ("bf16", 300, 64, 0), ("bf16", 300, 128, 0)])
+def test_stack_wavefront_with_alibi(oracle, dtype, N, chunk, p_min):
+    """rt_stack_prefill with the linear positional bias (maximum bias 8): blocks inside a chunk, the far tile over
+    all earlier keys (bias relative to its last key, moved into each query's frame when stored), decoding after it."""
+    if dtype == "f32":
+        wl = gen.Workload("stack_alibi_f32", "f32", 2, N, 128, 2, 512, layers=3, vocab=257, decode_steps=4, seed=995)
+        _run_elementwise(oracle, wl, 2, N, 4, emb_scale=EMB_UNIT, wavefront=True, chunk=chunk, p_min=p_min, alibi=8.0)
+    else:
+        wl = gen.Workload("stack_alibi_bf16", "bf16", 3, N, 256, 4, 1024, layers=4, vocab=1000, decode_steps=4, seed=996)
+        _run_elementwise(oracle, wl, 3, N, 4, emb_scale=EMB_UNIT, wavefront=True, chunk=chunk, alibi=8.0)
 
 
 def test_stack_prefill_argument_checks():
