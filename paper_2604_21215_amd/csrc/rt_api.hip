@@ -94,6 +94,7 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
     const size_t oopa = carve(2 * Bm * d * 2), ooph = carve(2 * Bm * d * 2), oopz = carve(2 * Bm * d * 2);
     const size_t oopu = carve(2 * Bm * F * 2);
     const size_t osh = carve(Bm * (d / 16 + 1) * 4), osz = carve(Bm * (d / 16 + 1) * 4);
+    const size_t oopx = carve(2 * Bm * d * 2), osx = carve(Bm * (d / 16 + 1) * 4);
     const size_t owo = packed_weights ? carve(d * d * 2) : 0, ow1 = packed_weights ? carve(F * d * 2) : 0;
     const size_t ow2 = packed_weights ? carve(d * F * 2) : 0, owkv = packed_weights ? carve(2 * d * d * 2) : 0;
     if (base) {
@@ -111,6 +112,7 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
         S.op_a = (bf16_t *)(p + oopa); S.op_h = (bf16_t *)(p + ooph); S.op_z = (bf16_t *)(p + oopz);
         S.op_u = (bf16_t *)(p + oopu);
         S.ssq_h = (float *)(p + osh); S.ssq_z = (float *)(p + osz);
+        S.op_x = (bf16_t *)(p + oopx); S.ssq_x = (float *)(p + osx);
         if (packed_weights) {
             S.wp_o = (bf16_t *)(p + owo); S.wp_1 = (bf16_t *)(p + ow1); S.wp_2 = (bf16_t *)(p + ow2);
             S.wp_kv = (bf16_t *)(p + owkv);
@@ -452,11 +454,17 @@ static rt_status decode_impl(rt_ctx *c, const LayerDims &D, const rt_layer_weigh
 {
     const Weights W = to_weights(w);
     hipStream_t st = c->stream;
-    RT_TRY(Launch<T>::prepass_one(D, W, c->S, x_t, (size_t)D.d, st), "prepass_one");
+    // bf16 with d and F multiples of 256: the products run on the matrix cores
+    const bool mm = sizeof(T) == 2 && step_mm_supported(D, c->use_mfma);
+    RT_TRY(Launch<T>::prepass_one(D, W, c->S, x_t, (size_t)D.d, st, mm), "prepass_one");
     const int chunk = 64;   // keys per wavefront: t / 64 wavefronts per (b, h) keep the whole chip reading the cache
     const int nsplit = (t + chunk - 1) / chunk;
     if (nsplit > 0) RT_TRY(Launch<T>::decode_split(D, c->S, K, V, t, chunk, nsplit, st), "decode_split");
-    return enqueue_position<T>(c, D, W, x_t, (size_t)D.d, y_t, (size_t)D.d, K, V, t, 0, nsplit, false);
+    if (!mm) return enqueue_position<T>(c, D, W, x_t, (size_t)D.d, y_t, (size_t)D.d, K, V, t, 0, nsplit, false);
+    RT_TRY(Launch<T>::merge(D, c->S, K, V, t, 0, nsplit, st, true), "merge");
+    const size_t row = (size_t)t * D.B * D.d * sizeof(T);
+    RT_TRY(step_base_case_mm(D, W, c->S, x_t, y_t, (char *)K + row, (char *)V + row, st), "step_base_case_mm");
+    return RT_OK;
 }
 
 extern "C" rt_status rt_decode_step(rt_ctx *c, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t, void *y_t,

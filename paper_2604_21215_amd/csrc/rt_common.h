@@ -155,6 +155,8 @@ struct Scratch {
     bf16_t *op_a, *op_h, *op_z;   // [2B][d]
     bf16_t *op_u;                 // [2B][F]
     float *ssq_h, *ssq_z;         // [B][d/16]
+    bf16_t *op_x;                 // [2B][d] the same for a decoding step's input row (gain g_attn applied)
+    float *ssq_x;                 // [B][d/16]
     // the layer's Wo, W1, W2 and [Wk; Wv] re-laid in matrix-core fragment order (or null): for rows 16R .. 16R+15 and
     // contraction indices 64p .. 64p+63, two fragments of 64 lanes x 16 bytes, lane (col, g) of fragment f holding
     // W[16R + col][64p + 32f + 8g .. + 7]; a wavefront's weight stream is then one contiguous run
@@ -176,9 +178,10 @@ template <typename T> struct Launch {
                               bool mfma, hipStream_t st, size_t x_bstride = 0, int n0 = 0);
     // one position's q, k_tmp, v_tmp (decoding step): rows b of Q, Kt, Vt
     static hipError_t prepass_one(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride,
-                                  hipStream_t st);
+                                  hipStream_t st, bool matrix_cores = false);
+    // split_out: a is also written as operand rows (bf16 head + remainder) into S.op_a
     static hipError_t merge(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int q_row,
-                            int n_decode_splits, hipStream_t st);
+                            int n_decode_splits, hipStream_t st, bool split_out = false);
     static hipError_t gemv_wo(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride_b,
                               hipStream_t st);
     static hipError_t gemv_w1(const LayerDims &D, const Weights &W, const Scratch &S, hipStream_t st);
@@ -217,6 +220,12 @@ hipError_t wavefront_prefill(const LayerDims &D, const WaveLayer *dev_layers, co
                              bool mfma, const WaveStreams &W);
 // whether the engine's matrix-core products cover this shape (they need the packed weight copies in the scratch)
 bool wavefront_uses_matrix_cores(int d, int F, bool mfma_bf16);
+// One position of one layer with the same products from the caller's row-major weights (decoding, bf16): x_t, y_t
+// rows d apart ([B][d]); K_row, V_row the cache rows to write ([B][H][64]).
+bool step_mm_supported(const LayerDims &D, bool mfma_bf16);
+hipError_t step_qkv_mm(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride, hipStream_t st);
+hipError_t step_base_case_mm(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, void *y_t, void *K_row,
+                             void *V_row, hipStream_t st);
 
 // embedding lookup and final-norm + output projection of a layer stack (rt_stack.hip)
 template <typename T>

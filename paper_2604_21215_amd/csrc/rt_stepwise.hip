@@ -64,10 +64,10 @@ __global__ __launch_bounds__(64) void merge_kernel(const T *__restrict__ Q, cons
                                                    const float *__restrict__ pl, const float *__restrict__ po,
                                                    float *__restrict__ attn_cat, int BH, int H, int t, int q_row,
                                                    int p_min, int log2_pmin, int levels, int slots, int n_splits,
-                                                   float scale, float alibi)
+                                                   float scale, float alibi, bf16_t *__restrict__ op_a)
 {
     merge_body<T, false>(Q, nullptr, Kt, nullptr, Vt, K, nullptr, V, pm, pl, po, attn_cat, BH, H, blockIdx.x, t, q_row, p_min,
-                         log2_pmin, levels, slots, n_splits, scale, -1, 0, nullptr, alibi);
+                         log2_pmin, levels, slots, n_splits, scale, -1, 0, op_a, alibi);
 }
 
 // =============================================================================================
@@ -265,11 +265,12 @@ hipError_t Launch<T>::prepass(const LayerDims &D, const Weights &W, const Scratc
 
 template <typename T>
 hipError_t Launch<T>::merge(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int q_row,
-                            int n_decode_splits, hipStream_t st)
+                            int n_decode_splits, hipStream_t st, bool split_out)
 {
     hipLaunchKernelGGL(merge_kernel<T>, dim3(D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)S.Kt,
                        (const T *)S.Vt, (const T *)K, (const T *)V, S.pm, S.pl, S.po, S.attn_cat, D.B * D.H, D.H, t, q_row,
-                       D.p_min, D.log2_pmin, S.levels, S.slots, n_decode_splits, D.scale, D.alibi);
+                       D.p_min, D.log2_pmin, S.levels, S.slots, n_decode_splits, D.scale, D.alibi,
+                       split_out ? S.op_a : (bf16_t *)nullptr);
     return hipGetLastError();
 }
 
@@ -302,9 +303,9 @@ static hipError_t gemv_launch(const T *Wa, const T *Wb, const T *Wc, int n_first
 // normalisation.  x_t rows are B apart by x_stride elements.
 template <typename T>
 hipError_t Launch<T>::prepass_one(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride,
-                                  hipStream_t st)
+                                  hipStream_t st, bool matrix_cores)
 {
-    hipError_t e = gemv_launch<T, T, EPI_KV>((const T *)W.Wq, (const T *)W.Wk, (const T *)W.Wv, D.d, 3 * D.d, D.d,
+    hipError_t e = matrix_cores ? step_qkv_mm(D, W, S, x_t, x_stride, st) : gemv_launch<T, T, EPI_KV>((const T *)W.Wq, (const T *)W.Wk, (const T *)W.Wv, D.d, 3 * D.d, D.d,
                                              (const T *)x_t, x_stride, D.B, (const T *)W.g_attn, D.eps, D.norm_free ? 0 : 1,
                                              D.alpha, (const T *)nullptr, (size_t)0, (const float *)nullptr, S.qkv_raw,
                                              (T *)nullptr, (size_t)0, st);

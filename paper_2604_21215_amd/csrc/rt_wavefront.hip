@@ -133,34 +133,45 @@ __device__ __forceinline__ float rms_scale_from_parts(const float *__restrict__ 
 // EPI_KV needs NW / KS = 4: a workgroup is then one head of k or of v, and the epilogue finishes the position
 // (qkRMS of the key, persistent pair of (l, t) in place, remainder keys and transposed values for the tiles).
 // Dynamic LDS: NW KB of partial tiles, 256 B of per-head sums, then the operand rows.
-template <int EPI, int KS, int NW, bool XL>
-__global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restrict__ layers, int l_first, int s, int chunk, int B,
-                                                        int N, int d, int F, int H, float eps, int norm_free, float alpha)
+// PACKED: the weights come in fragment order (Scratch::wp_*); else row-major as the caller holds them (a lane's two
+// fragments of a step pair are then 64 bytes apart in its row: half a cache line per row and instruction).
+// EPI_QKV: the raw [q | k_tmp | v_tmp] of one position from [Wq; Wk; Wv] and the operand rows op_x (a decoding step).
+// Y: the layer; t: its position (row t of x / y / K / V / V^T); block_x: row block; batch_tile: which 16 batch rows.
+constexpr int EPI_QKV = 4;
+template <int EPI, int KS, int NW, bool XL, bool PACKED>
+__device__ __forceinline__ void mm_body(const WaveLayer &Y, int t, int block_x, int batch_tile, int B, int N, int d, int F, int H,
+                                        float eps, int norm_free, float alpha, unsigned char *wf_mm_smem)
 {
-    extern __shared__ __align__(16) unsigned char wf_mm_smem[];
     float(*part)[16 * 16] = reinterpret_cast<float(*)[16 * 16]>(wf_mm_smem);
     float *hss = reinterpret_cast<float *>(wf_mm_smem + NW * 1024);
     bf16_t *xs = reinterpret_cast<bf16_t *>(wf_mm_smem + NW * 1024 + 256);
-    const int l = l_first + blockIdx.y, t = layer_pos(s, l, chunk);
-    const WaveLayer &Y = layers[l];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 15, g = lane >> 4;
     constexpr int RG = NW / KS;
     const int rg = wave / KS, kw = wave % KS;
-    const int row0 = ((int)blockIdx.x * RG + rg) * 16;
-    const int b0 = blockIdx.z * kMmBatch;
+    const int row0 = (block_x * RG + rg) * 16;
+    const int b0 = batch_tile * kMmBatch;
     const int Bn = min(kMmBatch, B - b0);
     const int K = EPI == EPI_W2 ? F : d;
-    const bf16_t *Wp;       // the matrix in fragment order (Scratch::wp_*)
+    const bf16_t *Wp;       // the matrix in fragment order (Scratch::wp_*), PACKED only
+    const bf16_t *Wr;       // this wavefront's first row in the caller's row-major matrix, !PACKED only
     const bf16_t *X;        // operand rows [2B][K]
-    if (EPI == EPI_WO) { Wp = Y.S.wp_o; X = Y.S.op_a; }
-    else if (EPI == EPI_W1) { Wp = Y.S.wp_1; X = Y.S.op_h; }
-    else if (EPI == EPI_W2) { Wp = Y.S.wp_2; X = Y.S.op_u; }
-    else { Wp = Y.S.wp_kv; X = Y.S.op_z; }
+    if (EPI == EPI_WO) { Wp = Y.S.wp_o; Wr = (const bf16_t *)Y.W.Wo + (size_t)row0 * K; X = Y.S.op_a; }
+    else if (EPI == EPI_W1) { Wp = Y.S.wp_1; Wr = (const bf16_t *)Y.W.W1 + (size_t)row0 * K; X = Y.S.op_h; }
+    else if (EPI == EPI_W2) { Wp = Y.S.wp_2; Wr = (const bf16_t *)Y.W.W2 + (size_t)row0 * K; X = Y.S.op_u; }
+    else if (EPI == EPI_KV) {
+        Wp = Y.S.wp_kv; X = Y.S.op_z;
+        Wr = row0 < d ? (const bf16_t *)Y.W.Wk + (size_t)row0 * K : (const bf16_t *)Y.W.Wv + (size_t)(row0 - d) * K;
+    } else {
+        Wp = nullptr; X = Y.S.op_x;
+        Wr = (const bf16_t *)(row0 < d ? Y.W.Wq : (row0 < 2 * d ? Y.W.Wk : Y.W.Wv)) + (size_t)(row0 % d) * K;
+    }
     const int klen = K / KS, kbeg = kw * klen;
-    // step pair p (contraction indices 64p .. 64p+63) of this wavefront's 16 rows: fragments 2p and 2p + 1, 1 KB each,
-    // the first covering k = 64p + 8g + (0..7), the second 32 further
-    const bf16_t *wr = Wp + ((size_t)(row0 / 16) * (K / 64) + kbeg / 64) * 1024 + lane * 8;
+    // step pair p (contraction indices 64p .. 64p+63) of this wavefront's 16 rows: two fragments, the first covering
+    // k = 64p + 8g + (0..7), the second 32 further; PACKED: fragments 2p and 2p + 1 of the row group, 1 KB each
+    const bf16_t *wr = PACKED ? Wp + ((size_t)(row0 / 16) * (K / 64) + kbeg / 64) * 1024 + lane * 8
+                              : Wr + (size_t)col * K + kbeg + 8 * g;
+    constexpr int kPairStride = PACKED ? 1024 : 64, kFragStride = PACKED ? 512 : 32;
     const int cb = min(col, Bn - 1);   // columns beyond Bn repeat the last batch row (their results are dropped)
     const int xld = XL ? K + 8 : K;
     const bf16_t *xh = (XL ? xs + (size_t)(2 * cb) * xld : X + (size_t)(2 * (b0 + cb)) * K) + kbeg + 8 * g;
@@ -170,8 +181,8 @@ __global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restr
 #define RT_WF_LOADW(buf, kk)                                                                   \
     _Pragma("unroll") for (int j = 0; j < 4; ++j)                                              \
     {                                                                                          \
-        buf[2 * j] = *reinterpret_cast<const uint4 *>(wr + ((kk) / 64 + j) * 1024);             \
-        buf[2 * j + 1] = *reinterpret_cast<const uint4 *>(wr + ((kk) / 64 + j) * 1024 + 512);   \
+        buf[2 * j] = *reinterpret_cast<const uint4 *>(wr + ((kk) / 64 + j) * kPairStride);                \
+        buf[2 * j + 1] = *reinterpret_cast<const uint4 *>(wr + ((kk) / 64 + j) * kPairStride + kFragStride); \
     }
 #define RT_WF_PAIR(a0v, a1v, kk)                                                               \
     {                                                                                          \
@@ -191,9 +202,11 @@ __global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restr
 
     const int nfull = klen / 256;
     if (nfull > 0) { RT_WF_LOADW(wa, 0) }
-    const bool do_norm = !norm_free && (EPI == EPI_W1 || EPI == EPI_KV);
+    const bool do_norm = !norm_free && (EPI == EPI_W1 || EPI == EPI_KV || EPI == EPI_QKV);
     float rscale = 1.f;
-    if (do_norm) rscale = rms_scale_from_parts((EPI == EPI_W1 ? Y.S.ssq_h : Y.S.ssq_z) + (size_t)b0 * (d / 16), cb, g, d / 16, d, eps);
+    if (do_norm)
+        rscale = rms_scale_from_parts((EPI == EPI_W1 ? Y.S.ssq_h : (EPI == EPI_KV ? Y.S.ssq_z : Y.S.ssq_x)) + (size_t)b0 * (d / 16),
+                                      cb, g, d / 16, d, eps);
     if (XL) {
         const int ppr = K / 8;   // 16-byte pieces per operand row
         for (int p = tid; p < 2 * Bn * ppr; p += 64 * NW) {
@@ -213,7 +226,8 @@ __global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restr
         }
     }
     for (int k = nfull * 256; k < klen; k += 64)
-        RT_WF_PAIR(*reinterpret_cast<const uint4 *>(wr + (k / 64) * 1024), *reinterpret_cast<const uint4 *>(wr + (k / 64) * 1024 + 512), k)
+        RT_WF_PAIR(*reinterpret_cast<const uint4 *>(wr + (k / 64) * kPairStride),
+                   *reinterpret_cast<const uint4 *>(wr + (k / 64) * kPairStride + kFragStride), k)
 #undef RT_WF_LOADW
 #undef RT_WF_PAIR
 #undef RT_WF_COMPUTE
@@ -275,9 +289,11 @@ __global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restr
             for (int r = 0; r < 4; ++r) u[r] = gelu_erf(v[r]);
             split_store4(Y.S.op_u, (size_t)(2 * b) * F + o, (size_t)(2 * b + 1) * F + o, u);
         }
+    } else if (EPI == EPI_QKV) {
+        if (live) *reinterpret_cast<float4 *>(Y.S.qkv_raw + (size_t)b * 3 * d + o) = make_float4(v[0], v[1], v[2], v[3]);
     } else {
         // the workgroup is head hh of [k heads | v heads]; this wavefront holds head dimensions 16 rg + 4g .. + 3
-        const int hh = blockIdx.x;
+        const int hh = block_x;
         const bool is_k = hh < H;
         if (is_k && !norm_free) {
             float ss = live ? (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]) : 0.f;
@@ -299,16 +315,64 @@ __global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restr
                 *reinterpret_cast<uint2 *>((bf16_t *)Y.K + off) = make_uint2(p01, p23);
                 const float r0 = v[0] - __uint_as_float(p01 << 16), r1 = v[1] - __uint_as_float(p01 & 0xFFFF0000u);
                 const float r2 = v[2] - __uint_as_float(p23 << 16), r3 = v[3] - __uint_as_float(p23 & 0xFFFF0000u);
-                *reinterpret_cast<uint2 *>(Y.S.Klo + off) = make_uint2(pack_bf16(r0, r1), pack_bf16(r2, r3));
+                if (Y.S.Klo) *reinterpret_cast<uint2 *>(Y.S.Klo + off) = make_uint2(pack_bf16(r0, r1), pack_bf16(r2, r3));
             } else {
                 *reinterpret_cast<uint2 *>((bf16_t *)Y.V + off) = make_uint2(p01, p23);
-                bf16_t *vt = Y.S.VT + ((size_t)bh * kHeadDim + 16 * rg + 4 * g) * Y.S.vt_stride + t;
-                vt[0] = (bf16_t)(p01 & 0xFFFFu);
-                vt[(size_t)Y.S.vt_stride] = (bf16_t)(p01 >> 16);
-                vt[2 * (size_t)Y.S.vt_stride] = (bf16_t)(p23 & 0xFFFFu);
-                vt[3 * (size_t)Y.S.vt_stride] = (bf16_t)(p23 >> 16);
+                if (Y.S.VT) {
+                    bf16_t *vt = Y.S.VT + ((size_t)bh * kHeadDim + 16 * rg + 4 * g) * Y.S.vt_stride + t;
+                    vt[0] = (bf16_t)(p01 & 0xFFFFu);
+                    vt[(size_t)Y.S.vt_stride] = (bf16_t)(p01 >> 16);
+                    vt[2 * (size_t)Y.S.vt_stride] = (bf16_t)(p23 & 0xFFFFu);
+                    vt[3 * (size_t)Y.S.vt_stride] = (bf16_t)(p23 >> 16);
+                }
             }
         }
+    }
+}
+
+// the body over the active layers of a stack (layer-wavefront engine): grid (row blocks, layers, batch tiles of 16)
+template <int EPI, int KS, int NW, bool XL>
+__global__ __launch_bounds__(64 * NW) void wf_mm_kernel(const WaveLayer *__restrict__ layers, int l_first, int s, int chunk, int B,
+                                                        int N, int d, int F, int H, float eps, int norm_free, float alpha)
+{
+    extern __shared__ __align__(16) unsigned char wf_mm_smem[];
+    const int l = l_first + blockIdx.y;
+    mm_body<EPI, KS, NW, XL, true>(layers[l], layer_pos(s, l, chunk), (int)blockIdx.x, (int)blockIdx.z, B, N, d, F, H, eps, norm_free,
+                                   alpha, wf_mm_smem);
+}
+
+// the body for one layer and one position whose rows the descriptor's pointers already address (a decoding step:
+// x, y [B][d], K / V / Klo pointing at the cache row to write, V^T at its column), weights as the caller holds them:
+// grid (row blocks, 1, batch tiles of 16)
+template <int EPI, int KS, int NW, bool XL>
+__global__ __launch_bounds__(64 * NW) void step_mm_kernel(const WaveLayer Y, int B, int d, int F, int H, float eps, int norm_free,
+                                                          float alpha)
+{
+    extern __shared__ __align__(16) unsigned char wf_mm_smem[];
+    mm_body<EPI, KS, NW, XL, false>(Y, 0, (int)blockIdx.x, (int)blockIdx.z, B, 1, d, F, H, eps, norm_free, alpha, wf_mm_smem);
+}
+
+// A decoding step's input rows x_t [B][d] as operand rows: head + remainder of x * g_attn, and the sums of squares of
+// x per 16 elements.  grid (ceil(d / 1024), B), block 256: a thread takes 4 elements, 4 adjacent threads one group.
+__global__ __launch_bounds__(256) void step_prep_kernel(const bf16_t *__restrict__ x, size_t x_stride, const bf16_t *__restrict__ g,
+                                                        bf16_t *__restrict__ op_x, float *__restrict__ ssq_x, int d, int norm_free)
+{
+    const int b = blockIdx.y, e0 = ((int)blockIdx.x * 256 + (int)threadIdx.x) * 4;
+    const bool in = e0 < d;   // d is a multiple of 64: a group of 16 is all in or all out
+    float v[4] = {0.f, 0.f, 0.f, 0.f}, gv[4];
+    if (in) {
+        const uint2 xr = *reinterpret_cast<const uint2 *>(x + (size_t)b * x_stride + e0);
+        v[0] = __uint_as_float(xr.x << 16); v[1] = __uint_as_float(xr.x & 0xFFFF0000u);
+        v[2] = __uint_as_float(xr.y << 16); v[3] = __uint_as_float(xr.y & 0xFFFF0000u);
+    }
+    float ss = (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]);
+    ss += __shfl_xor(ss, 1, 64);
+    ss += __shfl_xor(ss, 2, 64);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) gv[r] = v[r] * ((g && !norm_free && in) ? bf16_to_f32(g[e0 + r]) : 1.f);
+    if (in) {
+        split_store4(op_x, (size_t)(2 * b) * d + e0, (size_t)(2 * b + 1) * d + e0, gv);
+        if ((threadIdx.x & 3) == 0) ssq_x[(size_t)b * (d / 16) + e0 / 16] = ss;
     }
 }
 
@@ -644,5 +708,70 @@ template hipError_t wavefront_prefill<float>(const LayerDims &, const WaveLayer 
                                              const WaveStreams &);
 template hipError_t wavefront_prefill<bf16_t>(const LayerDims &, const WaveLayer *, const WaveLayer *, int, int, bool,
                                               const WaveStreams &);
+
+// ---------------------------------------------------------------------------------------------
+// One position of one layer with the matrix-core products (rt_decode_step on the bf16 path): the caller's
+// row-major weights, one launch per product, smaller workgroups than in the stack engine (one layer has to
+// fill the chip by itself).
+// ---------------------------------------------------------------------------------------------
+bool step_mm_supported(const LayerDims &D, bool mfma_bf16) { return wavefront_uses_matrix_cores(D.d, D.F, mfma_bf16); }
+
+template <int EPI, int KS, int NW>
+static hipError_t step_mm_launch(const WaveLayer &Y, int n_out, const LayerDims &D, hipStream_t st)
+{
+    const int K = EPI == EPI_W2 ? D.F : D.d;
+    const unsigned bt = (unsigned)((D.B + kMmBatch - 1) / kMmBatch);
+    const int Bt = D.B < kMmBatch ? D.B : kMmBatch;
+    const size_t base = (size_t)NW * 1024 + 256, xbytes = (size_t)2 * Bt * (K + 8) * 2;
+    const dim3 grid((unsigned)(n_out / (16 * NW / KS)), 1, bt);
+    if (base + xbytes <= kMmMaxLds) {
+        static bool raised = false;
+        if (!raised) {
+            hipError_t e = hipFuncSetAttribute((const void *)step_mm_kernel<EPI, KS, NW, true>,
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMmMaxLds);
+            if (e != hipSuccess) return e;
+            raised = true;
+        }
+        hipLaunchKernelGGL((step_mm_kernel<EPI, KS, NW, true>), grid, dim3(64 * NW), base + xbytes, st, Y, D.B, D.d, D.F, D.H, D.eps,
+                           D.norm_free, D.alpha);
+    } else {
+        hipLaunchKernelGGL((step_mm_kernel<EPI, KS, NW, false>), grid, dim3(64 * NW), base, st, Y, D.B, D.d, D.F, D.H, D.eps,
+                           D.norm_free, D.alpha);
+    }
+    return hipSuccess;
+}
+
+static WaveLayer step_layer(const Weights &W, const Scratch &S, const void *x_t, void *y_t, void *K_row, void *V_row)
+{
+    WaveLayer Y;
+    Y.W = W;
+    Y.S = S;
+    Y.S.Klo = nullptr;   // a decoding step writes the caller's cache rows only
+    Y.S.VT = nullptr;
+    Y.x = x_t; Y.y = y_t; Y.K = K_row; Y.V = V_row;
+    return Y;
+}
+
+// raw [q | k_tmp | v_tmp] of the rows x_t [B][d] into S.qkv_raw
+hipError_t step_qkv_mm(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride, hipStream_t st)
+{
+    hipLaunchKernelGGL(step_prep_kernel, dim3((unsigned)((D.d + 1023) / 1024), (unsigned)D.B), dim3(256), 0, st, (const bf16_t *)x_t,
+                       x_stride, (const bf16_t *)W.g_attn, S.op_x, S.ssq_x, D.d, D.norm_free);
+    const WaveLayer Y = step_layer(W, S, x_t, nullptr, nullptr, nullptr);
+    return step_mm_launch<EPI_QKV, 4, 4>(Y, 3 * D.d, D, st);
+}
+
+// h = x_t + alpha Wo a (a as operand rows in S.op_a), MLP, y_t, and the persistent pair into K_row, V_row ([B][H][64])
+hipError_t step_base_case_mm(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, void *y_t, void *K_row,
+                             void *V_row, hipStream_t st)
+{
+    const WaveLayer Y = step_layer(W, S, x_t, y_t, K_row, V_row);
+    hipError_t e;
+    if ((e = step_mm_launch<EPI_WO, 4, 4>(Y, D.d, D, st)) != hipSuccess) return e;
+    if ((e = step_mm_launch<EPI_W1, 4, 4>(Y, D.F, D, st)) != hipSuccess) return e;
+    if ((e = step_mm_launch<EPI_W2, 4, 4>(Y, D.d, D, st)) != hipSuccess) return e;
+    if ((e = step_mm_launch<EPI_KV, 2, 8>(Y, 2 * D.d, D, st)) != hipSuccess) return e;
+    return hipGetLastError();
+}
 
 }  // namespace rt
