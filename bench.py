@@ -49,7 +49,7 @@ def algorithmic_bytes(B, N, d, H, F, E, p_min, weights_resident):
     }
 
 
-def stack_section(stream, layer_by_layer=True, reps=2):
+def stack_section(stream, layer_by_layer=True, reps=2, alibi=0.0):
     """The 12-layer stack workload (cfg5: B = 4, N = 4096) through the layer-wavefront engine (rt_stack_prefill: the
     layers run concurrently, a chunk of positions apart) and, for comparison, layer by layer (12 x rt_layer_prefill).
     Its bound is the weight stream: every (layer, position) reads the layer's five loop matrices once."""
@@ -60,7 +60,7 @@ def stack_section(stream, layer_by_layer=True, reps=2):
     ws = gen.WORKLOADS["cfg5"]
     tabs = gen.make_embedding_tables(ws)
     sctx = binding.RTContext(ws.d, ws.H, ws.F, ws.B, ws.N, ws.dtype, resid_scale=ws.resid_scale, rms_eps=1e-6,
-                             stream=stream.cuda_stream)
+                             stream=stream.cuda_stream, alibi_max_bias=alibi)
     dls = [tio.DeviceLayer(gen.make_layer_weights(ws.seed, l, ws.d, ws.F, ws.dtype), None, ws.dtype)
            for l in range(ws.layers)]
     # table entries ~ N(0, 1): the scale at which the stack's parity tests run
@@ -103,6 +103,8 @@ def main():
     ap.add_argument("--workload", default="cfg3")
     ap.add_argument("--engine", default="auto", choices=["auto", "stepwise", "graph", "persistent"])
     ap.add_argument("--p-min", type=int, default=0)
+    ap.add_argument("--alibi", type=float, default=0.0,
+                    help="maximum ALiBi bias (the paper's trained models: 8.0); 0 = the layer of Sec. 2.2 as it stands")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the rt_decode_step measurement")
     ap.add_argument("--no-stack", action="store_true", help="skip the 12-layer stack measurement (rt_stack_prefill)")
@@ -131,7 +133,7 @@ def main():
         del big, big2
     if args.stack_only:
         print(json.dumps({"stack_wavefront": stack_section(torch.cuda.current_stream(), layer_by_layer=False,
-                                                           reps=args.steps)}))
+                                                           reps=args.steps, alibi=args.alibi)}))
         return
     wl = gen.WORKLOADS[args.workload]
     li = gen.make_layer_inputs(wl)
@@ -140,7 +142,7 @@ def main():
              "persistent": binding.RT_FLAG_ENGINE_PERSISTENT}[args.engine]
     stream = torch.cuda.current_stream()
     ctx = binding.RTContext(wl.d, wl.H, wl.F, wl.B, wl.N, wl.dtype, p_min=args.p_min, resid_scale=wl.resid_scale,
-                            attn_scale=1.0, rms_eps=1e-6, flags=flags, stream=stream.cuda_stream)
+                            attn_scale=1.0, rms_eps=1e-6, flags=flags, stream=stream.cuda_stream, alibi_max_bias=args.alibi)
     dl = tio.DeviceLayer(li.weights, li.gains, wl.dtype)
     xd = tio.to_device(li.x, wl.dtype)
     y = torch.empty_like(xd)
@@ -193,6 +195,7 @@ def main():
         "dtype": wl.dtype, "data": "synthetic",
         "config": {"workload": "%s: single RT layer, %s, B=%d, N=%d, d_model=%d, %d heads x 64, MLP hidden %d"
                    % (wl.name, wl.dtype, wl.B, wl.N, wl.d, wl.H, wl.F), "engine": engine, "p_min": p_min,
+                   "alibi_max_bias": args.alibi,
                    "attention_gflop_per_call": attn_flops / 1e9},
         "roofline": roofline,
     }
@@ -249,13 +252,13 @@ def main():
         out["decode_step"] = {"t": t_dec, "us_per_step": us, "tokens_per_s": wl.B / (us * 1e-6), "bound": "hbm",
                               "algorithmic_bytes": dec_bytes, "achieved": dec_bytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": dec_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                              "note": "eight launches per step on one stream"}
+                              "note": "nine launches per step on one stream (bf16: products on the matrix cores)"}
 
     if not args.no_cpu_baseline:
         from oracle import rt_oracle
         n_s = min(args.cpu_sample_positions, wl.N)
         w64 = {k: v.astype(np.float64) for k, v in li.weights.items()}
-        lay = rt_oracle.Layer(w64, wl.H, alpha=wl.resid_scale, eps=1e-6)
+        lay = rt_oracle.Layer(w64, wl.H, alpha=wl.resid_scale, eps=1e-6, alibi_max_bias=args.alibi)
         xs = li.x[:, :n_s].astype(np.float64)
         t0 = time.perf_counter()
         ref = lay.prefill(xs)
@@ -270,7 +273,7 @@ def main():
     ctx.rt_destroy()
 
     if not args.no_stack and args.workload == "cfg3":
-        out["stack_wavefront"] = stack_section(stream)
+        out["stack_wavefront"] = stack_section(stream, alibi=args.alibi)
     print(json.dumps(out))
 
 

@@ -121,7 +121,8 @@ rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t
  * The first call allocates one scratch set per layer (RT_ERR_OOM if that fails); it is kept until rt_destroy and
  * reused by later calls with the same chunk and at most as many layers (another shape synchronises the stream
  * and reallocates).  Half of the layers are enqueued on a second stream that the context owns (default priority;
- * it starts after the work already enqueued on rt_config.stream and that stream continues after it).
+ * it starts after the work already enqueued on rt_config.stream and that stream continues after it; the
+ * environment variable RT_WAVE_STREAMS = 1..4 sets the number of layer groups / streams, default 2).
  * rt_decode_step continues from the caches layer by layer. */
 rt_status rt_stack_prefill(rt_ctx *ctx, const rt_layer_weights *layers, int32_t L, const void *x, int32_t B, int32_t N,
                            void *const *y, void *const *K, void *const *V, int32_t kv_cap, int32_t chunk);

@@ -55,6 +55,12 @@ def load():
         return _lib
     if not os.path.exists(_build.LIB):
         _build.build_hip(True)
+    try:
+        # callers hold their device memory in torch tensors: load torch's HIP runtime first so that the library binds
+        # to the same one whatever the import order (two runtimes in one process do not share a device context)
+        import torch  # noqa: F401
+    except ImportError:
+        pass
     L = C.CDLL(_build.LIB)
     ctxp = C.c_void_p
     L.rt_create.argtypes = [C.POINTER(rt_config), C.POINTER(ctxp)]

@@ -144,6 +144,13 @@ def test_stack_wavefront_with_alibi(oracle, dtype, N, chunk, p_min):
         _run_elementwise(oracle, wl, 3, N, 4, emb_scale=EMB_UNIT, wavefront=True, chunk=chunk, alibi=8.0)
 
 
+def test_stack_wavefront_width_768(oracle):
+    """Two layers of the 150M-like shape (d = 768, 12 heads, hidden 3072): the contraction shares of the matrix-core
+    products are then 192 and 768 columns (step pairs outside the blocks of four), batch of 8."""
+    wl = gen.Workload("stack_768_wf", "bf16", 8, 200, 768, 12, 3072, layers=2, vocab=500, decode_steps=3, seed=997)
+    _run_elementwise(oracle, wl, 8, 200, 3, emb_scale=EMB_UNIT, wavefront=True)
+
+
 def test_stack_prefill_argument_checks():
     from paper_2604_21215_amd import binding, torch_io as tio
     _need_gpu()
