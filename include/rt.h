@@ -72,9 +72,7 @@ typedef struct {
                                                      models (Appendix D: maximum bias 8.0): the logit of query i and the
                                                      persistent key of position j < i is lowered by m_h (i - j), head
                                                      slopes m_h = 2^(-beta (h + 1) / H), h = 0..H-1; the temporary pair is
-                                                     at distance 0.  0 = none (Sec. 2.2 as it stands).  With beta > 0 the
-                                                     per-position engine (and rt_stack_prefill) run; the persistent
-                                                     engine does not cover it */
+                                                     at distance 0.  0 = none (Sec. 2.2 as it stands) */
 } rt_config;
 
 /* Device pointers, caller-owned, read-only.  Matrices are row-major [out, in] (y = W u).

@@ -215,7 +215,6 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
     if (!(cfg->rms_eps >= 0.f) || !(cfg->attn_scale == cfg->attn_scale) || !(cfg->resid_scale == cfg->resid_scale))
         return RT_ERR_INVALID_ARG;
     if (!(cfg->alibi_max_bias >= 0.f) || !(cfg->alibi_max_bias <= 1024.f)) return RT_ERR_INVALID_ARG;
-    if (cfg->alibi_max_bias > 0.f && (cfg->flags & RT_FLAG_ENGINE_PERSISTENT)) return RT_ERR_UNSUPPORTED;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return RT_ERR_HIP;
@@ -430,7 +429,7 @@ extern "C" rt_status rt_layer_prefill(rt_ctx *c, const rt_layer_weights *w, cons
     D.B = B; D.N = N; D.kv_cap = kv_cap;
     c->last_B = B; c->last_N = N;
     const bool want_stepwise = (c->cfg.flags & RT_FLAG_ENGINE_STEPWISE) != 0;
-    if (!want_stepwise && D.alibi == 0.f && persistent_supported(c->persist, D)) {
+    if (!want_stepwise && persistent_supported(c->persist, D)) {
         c->engine = "persistent";
         const Weights W = to_weights(w);
         hipError_t e;

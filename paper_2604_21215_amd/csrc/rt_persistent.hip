@@ -133,6 +133,7 @@ struct PersistArgs {
     unsigned long long *bar;    // [0] fenced-barrier counter, [8] abort word
     unsigned long long *trace;  // optional: [N][16] wall-clock stamps of workgroup 0
     long long spin_limit;
+    float alibi;                // maximum ALiBi bias (kernels instantiated with ALIBI only)
 };
 
 __device__ __forceinline__ ll_t ll_load(const ll_t *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -323,8 +324,10 @@ __device__ __forceinline__ void ll_wait_n(const ll_t *const (&p)[NW], const bool
 }
 
 // Direct window out of LDS: query (lane c holds q[c]) against nkeys <= 64 rows kept by this wavefront.
+// ALIBI: key j of the window is dist_first - j positions before the query, its logit lowered by slope times that.
+template <bool ALIBI>
 __device__ __forceinline__ void attend_lds(float q, const float *ks, const bf16_t *vs, int nkeys, float scale, float &m,
-                                           float &l, float &o)
+                                           float &l, float &o, float slope, int dist_first)
 {
     const int lane = threadIdx.x & 63;
     const bool valid = lane < nkeys;
@@ -337,7 +340,7 @@ __device__ __forceinline__ void attend_lds(float q, const float *ks, const bf16_
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], acc);
     }
-    const float logit = valid ? acc * scale : -INFINITY;
+    const float logit = valid ? (ALIBI ? fmaf(-slope, (float)(dist_first - lane), acc * scale) : acc * scale) : -INFINITY;
     const float m_new = fmaxf(m, fast_max(logit));
     const float resc = __expf(m - m_new);
     const float p = valid ? __expf(logit - m_new) : 0.f;
@@ -414,6 +417,9 @@ __device__ __forceinline__ void pre_from_lds(const float *s, PreLoad &L)
     }
 }
 
+// ALIBI: the stored partial states are already in this query's frame; the window key c - w + j is w + 1 - j
+// positions before query t = c + 1.
+template <bool ALIBI>
 __device__ __forceinline__ void pre_finish(const PersistArgs &A, int t, int u, const PreLoad &L, const float *wk,
                                            const bf16_t *wv, float &q, float &m, float &l, float &o)
 {
@@ -438,29 +444,38 @@ __device__ __forceinline__ void pre_finish(const PersistArgs &A, int t, int u, c
     const int c = t - 1;
     const int w = c & (A.p_min - 1);
     if (w > 0) {
+        const float slope = ALIBI ? alibi_slope(A.alibi, u % A.H, A.H) : 0.f;
         if (A.win_rows) {
-            attend_lds(q, wk, wv, w, A.scale, m, l, o);
+            attend_lds<ALIBI>(q, wk, wv, w, A.scale, m, l, o, slope, w + 1);
         } else {
             const size_t rs = (size_t)A.BH * kHeadDim;
             const size_t base = (size_t)(c - w) * rs + (size_t)u * kHeadDim;
-            attend_keys<bf16_t>(q, A.K + base, A.V + base, rs, w, A.scale, m, l, o);
+            if (ALIBI) attend_keys<bf16_t>(q, A.K + base, A.V + base, rs, w, A.scale, m, l, o, nullptr, slope, w + 1);
+            else attend_keys<bf16_t>(q, A.K + base, A.V + base, rs, w, A.scale, m, l, o);
         }
     }
 }
 
 // One cross-block item of the whole workgroup.
+template <bool ALIBI>
 __device__ __forceinline__ void cross_tile_item(const PersistArgs &A, int bh, int t, int P, int q0, int nq, int level,
                                              unsigned char *lds)
 {
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));   // opaque: keeps the tile's lane-derived addresses out of the registers of the per-position phases
-    cross_tile_wg<true, kPW, 1>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, A.BH, bh, t, 1, t - P, P, q0, nq,
-                                level, level - A.log2_pmin, A.slots, A.scale, lds, tid);
+    if (ALIBI)
+        cross_tile_wg<true, kPW, 1, true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, A.BH, bh, t, 1, t - P, P, q0,
+                                          nq, level, level - A.log2_pmin, A.slots, A.scale, lds, tid,
+                                          alibi_slope(A.alibi, bh % A.H, A.H));
+    else
+        cross_tile_wg<true, kPW, 1>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, A.BH, bh, t, 1, t - P, P, q0, nq,
+                                    level, level - A.log2_pmin, A.slots, A.scale, lds, tid);
 }
 
 // KSD = d / 256, KSF = F / 256: contraction steps per wavefront, fixed at compile time so that all
 // exchange loads of a phase are in flight at once without spilling.
-template <int KSD, int KSF>
+// ALIBI: linear positional bias (PersistArgs::alibi); a separate instantiation, the plain kernel is unchanged.
+template <int KSD, int KSF, bool ALIBI = false>
 __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 {
     extern __shared__ __align__(16) unsigned char smem[];
@@ -529,7 +544,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     if (has_u) {
         PreLoad L;
         pre_from_lds(pre_s + (size_t)wave * kPreFloats, L);
-        pre_finish(A, 0, my_u, L, my_wk, my_wv, cq, cm, cl, co);
+        pre_finish<ALIBI>(A, 0, my_u, L, my_wk, my_wv, cq, cm, cl, co);
     }
 
     for (int t = 0; t <= A.N; ++t) {
@@ -582,7 +597,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                     win_v[slot * kHeadDim + lane] = vb;
                 }
                 if (t < A.N) {
-                    const float sn = A.scale * fast_sum(q * kr);
+                    // the newest key is one position before the query
+                    const float sn = ALIBI ? A.scale * fast_sum(q * kr) - alibi_slope(A.alibi, h, A.H) : A.scale * fast_sum(q * kr);
                     const float m_new = fmaxf(m, sn);
                     const float e1 = __expf(m - m_new), e2 = __expf(sn - m_new);
                     l = l * e1 + e2;
@@ -623,9 +639,14 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                     const int bh = wg + G * w;   // workgroup-uniform
                     if (bh >= BH) break;
                     if (P >= kKC) {   // nq <= P < kGlobalP <= 32 kPW: one pass covers all queries
-                        cross_tile_item(A, bh, t, P, wave * 32, nq, level, reinterpret_cast<unsigned char *>(act_s));
+                        cross_tile_item<ALIBI>(A, bh, t, P, wave * 32, nq, level, reinterpret_cast<unsigned char *>(act_s));
                         __syncthreads();
                     } else if (wave * 32 < nq) {
+                        if (ALIBI)
+                            cross_mfma_wave<true, true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1,
+                                                        t - P, P, wave * 32, nq, level, level - A.log2_pmin, A.slots, A.scale,
+                                                        alibi_slope(A.alibi, bh % A.H, A.H));
+                        else
                         cross_mfma_wave<true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1, t - P, P,
                                               wave * 32, nq, level, level - A.log2_pmin, A.slots, A.scale);
                     }
@@ -645,12 +666,17 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 const int qgroups = (nq + 32 * kPW - 1) / (32 * kPW);
                 for (int it = wg; it < BH * qgroups; it += G) {
                     const int bh = it % BH, qg = it / BH;
-                    cross_tile_item(A, bh, t, P, qg * 32 * kPW + wave * 32, nq, level, reinterpret_cast<unsigned char *>(act_s));
+                    cross_tile_item<ALIBI>(A, bh, t, P, qg * 32 * kPW + wave * 32, nq, level, reinterpret_cast<unsigned char *>(act_s));
                     __syncthreads();   // the next item overwrites the tiles
                 }
             } else {
                 for (int it = wave * G + wg; it < items; it += G * kPW) {
                     const int bh = it % BH, qb = it / BH;
+                    if (ALIBI)
+                        cross_mfma_wave<true, true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1, t - P, P,
+                                                    qb * 32, nq, level, level - A.log2_pmin, A.slots, A.scale,
+                                                    alibi_slope(A.alibi, bh % A.H, A.H));
+                    else
                     cross_mfma_wave<true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, BH, bh, t, 1, t - P, P, qb * 32,
                                           nq, level, level - A.log2_pmin, A.slots, A.scale);
                 }
@@ -763,7 +789,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         if (pre) {   // overlaps the raw k, v crossing the chip
             PreLoad L;
             pre_from_lds(pre_s + (size_t)wave * kPreFloats, L);
-            pre_finish(A, t + 1, my_u, L, my_wk, my_wv, cq, cm, cl, co);
+            pre_finish<ALIBI>(A, t + 1, my_u, L, my_wk, my_wv, cq, cm, cl, co);
         }
         __syncthreads();
         RT_STAMP(6);
@@ -780,14 +806,14 @@ __global__ void clear_words_kernel(unsigned long long *p, int n)
 }
 
 typedef void (*persist_fn)(PersistArgs);
-static persist_fn pick_kernel(int d, int F)
+static persist_fn pick_kernel(int d, int F, bool alibi)
 {
     if (d % (32 * kPW) != 0 || F != 4 * d) return nullptr;
     switch (d / (32 * kPW)) {
-    case 1: return persistent_kernel<1, 4>;
-    case 2: return persistent_kernel<2, 8>;
-    case 3: return persistent_kernel<3, 12>;
-    case 4: return persistent_kernel<4, 16>;
+    case 1: return alibi ? persistent_kernel<1, 4, true> : persistent_kernel<1, 4>;
+    case 2: return alibi ? persistent_kernel<2, 8, true> : persistent_kernel<2, 8>;
+    case 3: return alibi ? persistent_kernel<3, 12, true> : persistent_kernel<3, 12>;
+    case 4: return alibi ? persistent_kernel<4, 16, true> : persistent_kernel<4, 16>;
     default: return nullptr;
     }
 }
@@ -818,7 +844,7 @@ rt_status persistent_create(PersistentState &P, const rt_config &cfg, const Laye
 {
     P.available = false;
     if (cfg.dtype != RT_BF16 || (cfg.flags & RT_FLAG_NO_MFMA)) return RT_ERR_UNSUPPORTED;
-    persist_fn fn = pick_kernel(D.d, D.F);   // d in {256, 512, 768, 1024}, F = 4 d
+    persist_fn fn = pick_kernel(D.d, D.F, D.alibi > 0.f);   // d in {256, 512, 768, 1024}, F = 4 d
     if (!fn) return RT_ERR_UNSUPPORTED;
     hipDeviceProp_t prop;
     if (hipGetDeviceProperties(&prop, cfg.device) != hipSuccess) return RT_ERR_HIP;
@@ -928,7 +954,8 @@ rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weigh
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) { err = std::string("clear_words_kernel: ") + hipGetErrorString(e); return RT_ERR_HIP; }
     void *args[] = {&A};
-    e = hipLaunchCooperativeKernel((const void *)pick_kernel(D.d, D.F), dim3(P.grid), dim3(kPThreads), args,
+    A.alibi = D.alibi;
+    e = hipLaunchCooperativeKernel((const void *)pick_kernel(D.d, D.F, D.alibi > 0.f), dim3(P.grid), dim3(kPThreads), args,
                                    (unsigned int)P.lds_bytes, st);
     if (e != hipSuccess) { err = std::string("hipLaunchCooperativeKernel: ") + hipGetErrorString(e); return RT_ERR_HIP; }
     P.launched = true;

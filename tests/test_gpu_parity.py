@@ -115,18 +115,26 @@ def test_alibi_stepwise_f32(oracle, N, p_min):
 
 
 def test_alibi_bf16_mfma_tiles(oracle):
-    """The matrix-core tiles with the bias: 32-key blocks (wave kernel), 64 .. 256-key blocks (LDS-staged kernel,
-    several chunks per block), a ragged tail; the default engine choice falls to the per-position engine."""
+    """The matrix-core tiles of the per-position engine with the bias: 32-key blocks (wave kernel), 64 .. 256-key
+    blocks (LDS-staged kernel, several chunks per block), a ragged tail."""
     b = _flags()
-    _run_case(oracle, "bf16", 2, 600, 256, 4, 1024, p_min=32, alibi=8.0, n_decode=2, expect_engine="stepwise")
+    _run_case(oracle, "bf16", 2, 600, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_STEPWISE, p_min=32, alibi=8.0, n_decode=2,
+              expect_engine="stepwise")
     _run_case(oracle, "bf16", 3, 333, 320, 5, 1280, p_min=64, alibi=3.0, scale=0.5, gains="random", expect_engine="stepwise")
-    _run_case(oracle, "bf16", 2, 200, 256, 4, 1024, flags=b.RT_FLAG_NO_MFMA, p_min=8, alibi=8.0)
+    _run_case(oracle, "bf16", 2, 200, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_STEPWISE | b.RT_FLAG_NO_MFMA, p_min=8, alibi=8.0)
 
 
-def test_alibi_rejected_where_not_covered():
+def test_alibi_persistent_engine(oracle):
+    """The single-launch engine with the bias: LDS window (newest key at distance 1), stored partial states from the
+    in-workgroup tiles (32 .. 128 keys) and from the grid-wide tiles (256 and 512 keys), several heads per workgroup
+    slot, gains and a logit scale."""
+    _run_case(oracle, "bf16", 2, 600, 256, 4, 1024, alibi=8.0, n_decode=2, expect_engine="persistent")
+    _run_case(oracle, "bf16", 3, 700, 1024, 16, 4096, alibi=8.0, expect_engine="persistent")
+    _run_case(oracle, "bf16", 8, 300, 512, 8, 2048, alibi=3.0, scale=0.5, gains="random", alpha=0.7, expect_engine="persistent")
+
+
+def test_alibi_rejects_a_negative_bias():
     binding, _ = _gpu()
-    with pytest.raises(binding.RTError):
-        binding.RTContext(256, 4, 1024, 2, 64, "bf16", flags=binding.RT_FLAG_ENGINE_PERSISTENT, alibi_max_bias=8.0)
     with pytest.raises(binding.RTError):
         binding.RTContext(256, 4, 1024, 2, 64, "bf16", alibi_max_bias=-1.0)
 
