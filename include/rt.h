@@ -125,6 +125,26 @@ rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t
 rt_status rt_stack_prefill(rt_ctx *ctx, const rt_layer_weights *layers, int32_t L, const void *x, int32_t B, int32_t N,
                            void *const *y, void *const *K, void *const *V, int32_t kv_cap, int32_t chunk);
 
+/* The same layer evaluated without the sequential loop, given its output (Sec. 6.1, "Activation checkpointing": with
+ * z known, all persistent pairs k_i, v_i = proj(RMS(z_i)) can be rebuilt at once and every intermediate recomputed in
+ * parallel): K, V rows 0..N-1 are written from z, then y_i = the layer's output at position i computed from x_i, the
+ * temporary pair of i and the persistent pairs of positions < i - one causal attention (all of Algorithm 1's tiles at
+ * once) and three GEMMs.  If z is the layer's true output for x, y reproduces it up to rounding (by induction over
+ * the positions z is the only fixed point).  This is the forward half of a training step's recompute; no backward
+ * pass is provided.
+ *   x, z [B, N, d] device, read-only; y [B, N, d] written; K, V [kv_cap, B, H, head_dim] rows 0..N-1 written.
+ *   bf16 storage with the MFMA kernels only (else RT_ERR_UNSUPPORTED); d_hidden a multiple of 64.
+ * The first call allocates activation scratch for max_batch x max_seq rows (kept until rt_destroy). */
+rt_status rt_layer_recompute(rt_ctx *ctx, const rt_layer_weights *w, const void *x, const void *z, int32_t B, int32_t N,
+                             void *y, void *K, void *V, int32_t kv_cap);
+
+/* The standard Transformer layer of Sec. 2.1 on the same kernels (the comparison layer of the paper's Figure 4): keys
+ * and values of every position come from the layer input, k_i = qkRMS(Wk RMS(x_i)), v_i = Wv RMS(x_i), attention over
+ * positions <= i, then the same output projection, residuals and MLP.  Same arguments and limits as
+ * rt_layer_recompute (K, V receive the pairs). */
+rt_status rt_transformer_layer(rt_ctx *ctx, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, void *y,
+                               void *K, void *V, int32_t kv_cap);
+
 /* Input of the first layer of a stack (Sec. 2: a sequence of token embeddings enters the first layer):
  *   x[b, n, :] = table[ids[b * ids_stride + first + n], :]   for 0 <= b < B, 0 <= n < N.
  *   table [vocab, d] device, storage dtype; ids device int32; x [B, N, d] device, written.
@@ -157,7 +177,7 @@ uint64_t rt_workspace_bytes(const rt_ctx *ctx);
 int32_t rt_device_wait_expired(rt_ctx *ctx);
 
 /* Name of the engine the last prefill call on this context used: "stepwise", "stepwise+graph",
- * "persistent", "wavefront" (rt_stack_prefill), or "" before the first call. */
+ * "persistent", "wavefront" (rt_stack_prefill), "recompute", "transformer", or "" before the first call. */
 const char *rt_engine_name(const rt_ctx *ctx);
 
 /* Diagnostics of the persistent engine, after the stream has been synchronised: when the environment

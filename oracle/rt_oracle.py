@@ -104,6 +104,7 @@ class Layer:
         p.alpha, p.attn_scale, p.eps = float(alpha), float(attn_scale), float(eps)
         p.norm_free, p.threads = int(bool(norm_free)), int(threads)
         p.alibi_max_bias = float(alibi_max_bias)
+        self._w, self._g, self._mlp = w, g, mlp
         for name in ("Wq", "Wk", "Wv", "Wo", "W1", "W2"):
             a = w.get(name)
             setattr(p, name, _ptr(a))
@@ -150,6 +151,62 @@ class Layer:
         if rc:
             raise RuntimeError("rto_layer_prefill_tiled failed: %d" % rc)
         return y, K, V
+
+    def recompute(self, x, z):
+        """Sec. 6.1 ("Activation checkpointing"): the layer evaluated with its output z given.  All persistent pairs are
+        projected from RMS(z) at once; position i then attends the persistent pairs of positions < i and its own
+        temporary pair, and the output projection, residuals and MLP follow row by row - no sequential loop.  Dense
+        numpy algebra, one (N x N) logit matrix per head.  Returns (y, K, V) in the layouts of prefill(); y equals z
+        when z is the layer's output for x."""
+        x, z = _f64(x), _f64(z)
+        B, N, d = x.shape
+        H, dh, p, w, g = self.H, self.dh, self.p, self._w, self._g
+        eps, nf = p.eps, bool(p.norm_free)
+
+        def rms(v, gain):
+            if nf:
+                return v
+            r = v / np.sqrt(np.mean(v * v, axis=-1, keepdims=True) + eps)
+            return r if gain is None else r * gain
+
+        def heads(v, gain):      # per-head normalisation of [.., d] rows
+            vh = v.reshape(v.shape[:-1] + (H, dh))
+            return rms(vh, None if gain is None else gain.reshape(H, dh))
+
+        n = rms(x, g.get("g_attn"))
+        q = heads(n @ w["Wq"].T, g.get("g_q"))
+        kt = heads(n @ w["Wk"].T, g.get("g_k"))
+        vt = (n @ w["Wv"].T).reshape(B, N, H, dh)
+        r = rms(z, g.get("g_kv"))
+        Kp = heads(r @ w["Wk"].T, g.get("g_k"))
+        Vp = (r @ w["Wv"].T).reshape(B, N, H, dh)
+        dist = np.arange(N)[:, None] - np.arange(N)[None, :]          # i - j
+        cat = np.zeros((B, N, H, dh))
+        for b in range(B):
+            for h in range(H):
+                S = p.attn_scale * (q[b, :, h] @ Kp[b, :, h].T)
+                if p.alibi_max_bias > 0:
+                    S = S - 2.0 ** (-p.alibi_max_bias * (h + 1) / H) * dist
+                S = np.where(dist > 0, S, -np.inf)                     # persistent pairs of earlier positions only
+                own = p.attn_scale * np.sum(q[b, :, h] * kt[b, :, h], axis=-1)
+                m = np.maximum(S.max(axis=1), own)
+                E, e_own = np.exp(S - m[:, None]), np.exp(own - m)
+                den = E.sum(axis=1) + e_own
+                cat[b, :, h] = (E @ Vp[b, :, h] + e_own[:, None] * vt[b, :, h]) / den[:, None]
+        a = cat.reshape(B, N, d)
+        if w.get("Wo") is not None:
+            a = a @ w["Wo"].T
+        hdd = x + p.alpha * a
+        u = rms(hdd, g.get("g_mlp"))
+        if self._mlp is not None:
+            mo = np.stack([[np.asarray(self._mlp(u[b, i]), dtype=np.float64) for i in range(N)] for b in range(B)])
+        else:
+            t = u @ w["W1"].T
+            from math import sqrt
+            from scipy.special import erf
+            mo = (0.5 * t * (1.0 + erf(t / sqrt(2.0)))) @ w["W2"].T
+        y = hdd + p.alpha * mo
+        return y, np.ascontiguousarray(Kp.transpose(1, 0, 2, 3)), np.ascontiguousarray(Vp.transpose(1, 0, 2, 3))
 
     def transformer(self, x, want_attw=False):
         """Standard causal Transformer layer with the same parameters (Sec. 2.1)."""

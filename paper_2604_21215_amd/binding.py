@@ -23,7 +23,7 @@ RT_FLAG_HIP_GRAPH = 0x10
 EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_last_error", "rt_status_string",
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
            "rt_version", "rt_phase_trace", "rt_schedule_events_shifted", "rt_embed_rows", "rt_lm_head", "rt_cross_block_event",
-           "rt_stack_prefill", "rt_schedule_events_chunked")
+           "rt_stack_prefill", "rt_schedule_events_chunked", "rt_layer_recompute", "rt_transformer_layer")
 
 
 class rt_config(C.Structure):
@@ -104,6 +104,12 @@ def load():
     L.rt_stack_prefill.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_int32, C.c_void_p, C.c_int32, C.c_int32,
                                    C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.POINTER(C.c_void_p), C.c_int32, C.c_int32]
     L.rt_stack_prefill.restype = C.c_int
+    L.rt_layer_recompute.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_void_p, C.c_void_p, C.c_int32, C.c_int32,
+                                     C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+    L.rt_layer_recompute.restype = C.c_int
+    L.rt_transformer_layer.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
+                                       C.c_void_p, C.c_void_p, C.c_int32]
+    L.rt_transformer_layer.restype = C.c_int
     _lib = L
     return L
 
@@ -192,6 +198,19 @@ class RTContext:
         parr = lambda ps: (C.c_void_p * L)(*ps)
         return self._L.rt_stack_prefill(self._ctx, warr, L, C.c_void_p(x_ptr), B, N, parr(y_ptrs), parr(K_ptrs),
                                         parr(V_ptrs), kv_cap, chunk)
+
+    # -- rt_layer_recompute(ctx, w, x[B,N,d], z[B,N,d], B, N, y, K, V, kv_cap)
+    def rt_layer_recompute(self, weights: rt_layer_weights, x, z, y, K, V):
+        B, N, _ = x.shape
+        rc = self._L.rt_layer_recompute(self._ctx, C.byref(weights), _ptr(x), _ptr(z), B, N, _ptr(y), _ptr(K), _ptr(V),
+                                        K.shape[0])
+        _check(self._L, self._ctx, rc)
+
+    # -- rt_transformer_layer(ctx, w, x[B,N,d], B, N, y, K, V, kv_cap)
+    def rt_transformer_layer(self, weights: rt_layer_weights, x, y, K, V):
+        B, N, _ = x.shape
+        rc = self._L.rt_transformer_layer(self._ctx, C.byref(weights), _ptr(x), B, N, _ptr(y), _ptr(K), _ptr(V), K.shape[0])
+        _check(self._L, self._ctx, rc)
 
     # -- rt_decode_step(ctx, w, x_t[B,d], B, t, y_t, K, V, kv_cap)
     def rt_decode_step(self, weights: rt_layer_weights, x_t, t, y_t, K, V):

@@ -33,6 +33,8 @@ struct rt_ctx {
     std::vector<Scratch> stack_S;
     WaveLayer *stack_dev = nullptr;
     WaveStreams wave_streams = {};   // st[1..], ev[..] created on first use
+    void *par_slab = nullptr;        // activations of the loop-free evaluations (rt_layer_recompute, rt_transformer_layer)
+    size_t par_bytes = 0;
     // cached HIP graph of one stepwise prefill
     hipGraphExec_t graph_exec = nullptr;
     hipStream_t capture_stream = nullptr;  // the legacy default stream cannot be captured
@@ -270,6 +272,7 @@ rt_status rt_destroy(rt_ctx *c)
     persistent_destroy(c->persist);
     if (c->stack_slab) (void)hipFree(c->stack_slab);
     if (c->stack_dev) (void)hipFree(c->stack_dev);
+    if (c->par_slab) (void)hipFree(c->par_slab);
     for (int g = 0; g < kMaxWaveStreams; ++g) {
         if (g > 0 && c->wave_streams.st[g]) (void)hipStreamDestroy(c->wave_streams.st[g]);
         if (c->wave_streams.ev[g]) (void)hipEventDestroy(c->wave_streams.ev[g]);
@@ -282,7 +285,7 @@ rt_status rt_destroy(rt_ctx *c)
 const char *rt_last_error(const rt_ctx *c) { return c ? c->err.c_str() : kNoCtx; }
 uint64_t rt_workspace_bytes(const rt_ctx *c)
 {
-    return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) + c->stack_bytes : 0;
+    return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) + c->stack_bytes + c->par_bytes : 0;
 }
 const char *rt_engine_name(const rt_ctx *c) { return c ? c->engine.c_str() : ""; }
 
@@ -652,4 +655,59 @@ extern "C" rt_status rt_stack_prefill(rt_ctx *c, const rt_layer_weights *layers,
     else e = wavefront_prefill<float>(D, c->stack_dev, host.data(), L, chunk, false, WS);
     if (e != hipSuccess) return fail_hip(c, e, "wavefront_prefill");
     return RT_OK;
+}
+
+// Loop-free evaluation of a whole sequence (rt_parallel.hip); pairs_src = z (recompute) or x (Transformer layer).
+static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void *x, const void *pairs_src, bool transformer,
+                                int32_t B, int32_t N, void *y, void *K, void *V, int32_t kv_cap)
+{
+    if (!c) return RT_ERR_INVALID_ARG;
+    if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
+    rt_status s = check_weights(c, w);
+    if (s != RT_OK) return s;
+    if (!x || !pairs_src || !y || !K || !V) return fail(c, RT_ERR_INVALID_ARG, "null tensor pointer%s");
+    if (B < 1 || B > c->cfg.max_batch) return fail(c, RT_ERR_INVALID_ARG, "B out of range [1, max_batch]%s");
+    if (N < 1 || N > c->cfg.max_seq) return fail(c, RT_ERR_INVALID_ARG, "N out of range [1, max_seq]%s");
+    if (kv_cap < N) return fail(c, RT_ERR_INVALID_ARG, "kv_cap < N%s");
+    const size_t E = 2;
+    const size_t xb = (size_t)B * N * c->cfg.d_model * E, kvb = (size_t)kv_cap * B * c->cfg.d_model * E;
+    if (ranges_overlap(x, xb, y, xb) || (pairs_src != x && ranges_overlap(pairs_src, xb, y, xb)))
+        return fail(c, RT_ERR_INVALID_ARG, "the output must not overlap an input%s");
+    if (ranges_overlap(K, kvb, V, kvb) || ranges_overlap(K, kvb, y, xb) || ranges_overlap(V, kvb, y, xb) ||
+        ranges_overlap(K, kvb, x, xb) || ranges_overlap(V, kvb, x, xb) || ranges_overlap(K, kvb, pairs_src, xb) ||
+        ranges_overlap(V, kvb, pairs_src, xb))
+        return fail(c, RT_ERR_INVALID_ARG, "K, V and the other tensors must not overlap%s");
+    LayerDims D = c->base;
+    D.B = B; D.N = N; D.kv_cap = kv_cap;
+    if (c->cfg.dtype != RT_BF16 || !parallel_supported(D, c->use_mfma))
+        return fail(c, RT_ERR_UNSUPPORTED, "the loop-free evaluations need bf16 storage, the MFMA kernels and d_hidden a multiple of 64%s");
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+    if (!c->par_slab) {
+        const size_t bytes = parallel_scratch_bytes((size_t)c->cfg.max_batch * c->cfg.max_seq, c->cfg.d_model, c->cfg.d_hidden);
+        hipError_t e = hipMalloc(&c->par_slab, bytes);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            c->par_slab = nullptr;
+            return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "activation scratch: %s", hipGetErrorString(e));
+        }
+        c->par_bytes = bytes;
+    }
+    c->last_B = B; c->last_N = N;
+    c->engine = transformer ? "transformer" : "recompute";
+    const Weights W = to_weights(w);
+    hipError_t e = parallel_layer(D, W, c->S, x, pairs_src, transformer, y, K, V, c->par_slab, c->stream);
+    if (e != hipSuccess) return fail_hip(c, e, "parallel_layer");
+    return RT_OK;
+}
+
+extern "C" rt_status rt_layer_recompute(rt_ctx *c, const rt_layer_weights *w, const void *x, const void *z, int32_t B, int32_t N,
+                                        void *y, void *K, void *V, int32_t kv_cap)
+{
+    return parallel_entry(c, w, x, z, false, B, N, y, K, V, kv_cap);
+}
+
+extern "C" rt_status rt_transformer_layer(rt_ctx *c, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, void *y,
+                                          void *K, void *V, int32_t kv_cap)
+{
+    return parallel_entry(c, w, x, x, true, B, N, y, K, V, kv_cap);
 }

@@ -21,8 +21,9 @@ namespace rt {
 //   HP: the query and the temporary key come unrounded from Qf / Ktf and the window keys are head K plus
 //   remainder Klo, so that no logit carries a bf16 rounding of q or k.
 // =============================================================================================
+// Returns a (lane = head dimension); attn_cat may be null when the caller stores it elsewhere.
 template <typename T, bool HP>
-__device__ __forceinline__ void merge_body(const T *__restrict__ Q, const float *__restrict__ Qf,
+__device__ __forceinline__ float merge_body(const T *__restrict__ Q, const float *__restrict__ Qf,
                                            const T *__restrict__ Kt, const float *__restrict__ Ktf,
                                            const T *__restrict__ Vt, const T *__restrict__ K,
                                            const bf16_t *__restrict__ Klo, const T *__restrict__ V,
@@ -98,13 +99,14 @@ __device__ __forceinline__ void merge_body(const T *__restrict__ Q, const float 
     }
     const int b = bh / H, h = bh % H;
     const float a = o / l;
-    attn_cat[(size_t)b * H * kHeadDim + h * kHeadDim + lane] = a;
+    if (attn_cat) attn_cat[(size_t)b * H * kHeadDim + h * kHeadDim + lane] = a;
     if (op_a) {   // the same value as bf16 head + remainder rows (2b, 2b + 1) for the matrix-core products
         const size_t d = (size_t)H * kHeadDim;
         const bf16_t hi = f32_to_bf16(a);
         op_a[(size_t)(2 * b) * d + h * kHeadDim + lane] = hi;
         op_a[(size_t)(2 * b + 1) * d + h * kHeadDim + lane] = f32_to_bf16(a - bf16_to_f32(hi));
     }
+    return a;
 }
 
 // =============================================================================================

@@ -227,6 +227,13 @@ hipError_t step_qkv_mm(const LayerDims &D, const Weights &W, const Scratch &S, c
 hipError_t step_base_case_mm(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, void *y_t, void *K_row,
                              void *V_row, hipStream_t st);
 
+// Whole-sequence evaluation when every key-value pair is known in advance (rt_parallel.hip): the recompute of a
+// layer from its input and output (Sec. 6.1) and the standard Transformer layer (Sec. 2.1).  bf16 + matrix cores.
+bool parallel_supported(const LayerDims &D, bool mfma_bf16);
+size_t parallel_scratch_bytes(size_t M, size_t d, size_t F);
+hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, const void *pairs_src,
+                          bool pairs_are_temporary, void *y, void *K, void *V, void *par, hipStream_t st);
+
 // embedding lookup and final-norm + output projection of a layer stack (rt_stack.hip)
 template <typename T>
 hipError_t embed_rows_launch(const void *table, const int32_t *ids, void *x, int B, int N, int d, int vocab,

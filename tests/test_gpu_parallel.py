@@ -1,0 +1,116 @@
+"""GPU parity of the loop-free evaluations against the CPU oracle: rt_layer_recompute (the layer with its output
+given, Sec. 6.1) and rt_transformer_layer (Sec. 2.1), bf16 storage, element by element as error curves over position
+(tolerance 2e-2 per position for y, K, V)."""
+import numpy as np
+import pytest
+
+from paper_2604_21215_amd import inputs as gen
+from tests.parity_util import TOL, error_curves, summarize, oracle_layer
+
+pytestmark = pytest.mark.gpu
+torch = pytest.importorskip("torch")
+
+
+def _setup(li, B, N, d, H, F, **kw):
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible")
+    from paper_2604_21215_amd import binding, torch_io as tio
+    ctx = binding.RTContext(d, H, F, B, N, "bf16", stream=torch.cuda.current_stream().cuda_stream, **kw)
+    dl = tio.DeviceLayer(li.weights, li.gains, "bf16")
+    xd = tio.to_device(li.x, "bf16")
+    y = torch.empty_like(xd)
+    K = torch.zeros((N, B, H, d // H), dtype=xd.dtype, device=xd.device)
+    V = torch.zeros_like(K)
+    return ctx, tio, dl, xd, y, K, V
+
+
+def _check(name, x64, ref, got, tol):
+    cur = error_curves(x64, ref, got)
+    print("\n  [%s] %s" % (name, summarize(cur)))
+    for k in ("y", "K", "V"):
+        assert cur[k].max() <= tol, "%s %s: %.3e at position %d" % (name, k, cur[k].max(), int(np.argmax(cur[k])))
+
+
+@pytest.mark.parametrize("B,N,d,H,F,alibi,gains,alpha,scale", [
+    (2, 200, 256, 4, 1024, 0.0, "unit", 1.0, 1.0),
+    (3, 333, 320, 5, 1280, 8.0, "random", 0.7, 0.5),       # odd head count, ragged N, bias, gains
+    (2, 700, 1024, 16, 4096, 0.0, "unit", 1.0, 1.0),       # blocks up to 512 keys, several query workgroups
+    (1, 33, 256, 4, 1024, 0.0, "unit", 1.0, 1.0),
+])
+def test_recompute_from_exact_output(oracle, B, N, d, H, F, alibi, gains, alpha, scale):
+    """z = the oracle's output (rounded to bf16): the recompute must reproduce the oracle's y, K, V."""
+    li = gen.make_custom(21, "bf16", B, N, d, H, F, gains=gains)
+    x64 = li.x.astype(np.float64)
+    lay = oracle_layer(oracle, li, H, alpha=alpha, attn_scale=scale, eps=1e-6, alibi_max_bias=alibi)
+    ref = lay.prefill(x64)
+    ctx, tio, dl, xd, y, K, V = _setup(li, B, N, d, H, F, resid_scale=alpha, attn_scale=scale, rms_eps=1e-6, alibi_max_bias=alibi)
+    try:
+        zd = tio.to_device(gen.round_to_bf16(ref[0].astype(np.float32)), "bf16")
+        ctx.rt_layer_recompute(dl.struct, xd, zd, y, K, V)
+        torch.cuda.synchronize()
+        assert ctx.engine_name() == "recompute"
+        _check("recompute B=%d N=%d d=%d alibi=%g" % (B, N, d, alibi), x64, ref, (tio.to_host(y), tio.to_host(K), tio.to_host(V)),
+               TOL["bf16"])
+    finally:
+        ctx.rt_destroy()
+
+
+def test_recompute_of_an_arbitrary_z_and_of_the_prefill_output(oracle):
+    """(1) z that is NOT the layer's output: the recompute is still a defined map (K, V from z, y from x and those) and must
+    match the oracle's recompute of the same z; (2) z = what rt_layer_prefill produced on the GPU: y reproduces it and
+    K, V equal the prefill's up to rounding."""
+    B, N, d, H, F = 2, 300, 256, 4, 1024
+    li = gen.make_custom(22, "bf16", B, N, d, H, F)
+    x64 = li.x.astype(np.float64)
+    lay = oracle_layer(oracle, li, H, eps=1e-6)
+    z = gen.round_to_bf16((li.x + 0.5 * gen.make_custom(23, "bf16", B, N, d, H, F).x).astype(np.float32))
+    ref = lay.recompute(x64, z.astype(np.float64))
+    ctx, tio, dl, xd, y, K, V = _setup(li, B, N, d, H, F, rms_eps=1e-6)
+    try:
+        ctx.rt_layer_recompute(dl.struct, xd, tio.to_device(z, "bf16"), y, K, V)
+        torch.cuda.synchronize()
+        _check("recompute of an arbitrary z", x64, ref, (tio.to_host(y), tio.to_host(K), tio.to_host(V)), TOL["bf16"])
+        y1, K1, V1 = tio.prefill(ctx, dl, xd)
+        torch.cuda.synchronize()
+        y2, K2, V2 = torch.empty_like(y1), torch.zeros_like(K1), torch.zeros_like(V1)
+        ctx.rt_layer_recompute(dl.struct, xd, y1, y2, K2, V2)
+        torch.cuda.synchronize()
+        _check("recompute of the prefill's own output", x64, (tio.to_host(y1), tio.to_host(K1), tio.to_host(V1)),
+               (tio.to_host(y2), tio.to_host(K2), tio.to_host(V2)), TOL["bf16"])
+    finally:
+        ctx.rt_destroy()
+
+
+@pytest.mark.parametrize("B,N,d,H,F,alibi", [(2, 200, 256, 4, 1024, 0.0), (3, 333, 320, 5, 1280, 8.0), (2, 600, 1024, 16, 4096, 0.0)])
+def test_transformer_layer(oracle, B, N, d, H, F, alibi):
+    li = gen.make_custom(24, "bf16", B, N, d, H, F, gains="random")
+    x64 = li.x.astype(np.float64)
+    ref = oracle_layer(oracle, li, H, alpha=0.8, eps=1e-6, alibi_max_bias=alibi).transformer(x64)
+    ctx, tio, dl, xd, y, K, V = _setup(li, B, N, d, H, F, resid_scale=0.8, rms_eps=1e-6, alibi_max_bias=alibi)
+    try:
+        ctx.rt_transformer_layer(dl.struct, xd, y, K, V)
+        torch.cuda.synchronize()
+        assert ctx.engine_name() == "transformer"
+        _check("transformer layer B=%d N=%d d=%d alibi=%g" % (B, N, d, alibi), x64, ref[:3],
+               (tio.to_host(y), tio.to_host(K), tio.to_host(V)), TOL["bf16"])
+    finally:
+        ctx.rt_destroy()
+
+
+def test_parallel_entry_points_reject_what_they_do_not_cover():
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible")
+    from paper_2604_21215_amd import binding, torch_io as tio
+    li = gen.make_custom(25, "f32", 1, 16, 128, 2, 512)
+    ctx = binding.RTContext(128, 2, 512, 1, 16, "f32")
+    try:
+        dl = tio.DeviceLayer(li.weights, li.gains, "f32")
+        xd = tio.to_device(li.x, "f32")
+        y, K, V = torch.empty_like(xd), torch.zeros((16, 1, 2, 64), device=xd.device), torch.zeros((16, 1, 2, 64), device=xd.device)
+        with pytest.raises(binding.RTError) as ei:
+            ctx.rt_transformer_layer(dl.struct, xd, y, K, V)
+        assert ei.value.status == "RT_ERR_UNSUPPORTED"
+        with pytest.raises(binding.RTError):
+            ctx.rt_layer_recompute(dl.struct, xd, xd, xd, K, V)          # output overlaps an input (checked first)
+    finally:
+        ctx.rt_destroy()

@@ -172,6 +172,29 @@ def test_p4_fixed_point_parallel_recompute(oracle, N, scale):
         np.testing.assert_allclose(V[:, b], Vp, rtol=1e-10, atol=1e-11)
 
 
+@pytest.mark.parametrize("beta", [0.0, 8.0])
+def test_p4_oracle_recompute(oracle, beta):
+    """oracle.Layer.recompute (the layer with its output given, Sec. 6.1): (1) the output of the token-by-token recurrence
+    is its fixed point, with the same persistent pairs; (2) for an arbitrary z (not a fixed point) it agrees with the
+    independent dense restatement above; (3) a perturbed z does not reproduce itself."""
+    x, w, g = _small(16, B=2, N=21, d=24, H=3, F=40)
+    alpha, eps, scale = 0.6, 1e-5, 0.5
+    lay = oracle.Layer(w, 3, gains=g, alpha=alpha, eps=eps, attn_scale=scale, alibi_max_bias=beta)
+    y, K, V = lay.prefill(x)
+    y2, K2, V2 = lay.recompute(x, y)
+    np.testing.assert_allclose(y2, y, rtol=1e-10, atol=1e-11)
+    np.testing.assert_allclose(K2, K, rtol=1e-10, atol=1e-11)
+    np.testing.assert_allclose(V2, V, rtol=1e-10, atol=1e-11)
+    z = y + 0.3 * gen.normal(16, 9, y.shape, 1.0).astype(np.float64)
+    y3, K3, V3 = lay.recompute(x, z)
+    assert np.abs(y3 - z).max() > 1e-2
+    for b in range(2):
+        ref, Kp, Vp = _parallel_recompute(x[b], z[b], w, g, 3, alpha, eps, scale, alibi=beta)
+        np.testing.assert_allclose(y3[b], ref, rtol=1e-10, atol=1e-11)
+        np.testing.assert_allclose(K3[:, b], Kp, rtol=1e-10, atol=1e-11)
+        np.testing.assert_allclose(V3[:, b], Vp, rtol=1e-10, atol=1e-11)
+
+
 def test_p4_fixed_point_detects_planted_mistakes(oracle):
     """The residual is not vacuous: a wrong sign / dropped term / transposed matrix shows up."""
     x, w, g = _small(15, B=1, N=12)
