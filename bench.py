@@ -107,6 +107,7 @@ def main():
                     help="maximum ALiBi bias (the paper's trained models: 8.0); 0 = the layer of Sec. 2.2 as it stands")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the rt_decode_step measurement")
+    ap.add_argument("--no-parallel", action="store_true", help="skip rt_transformer_layer / rt_layer_recompute")
     ap.add_argument("--no-stack", action="store_true", help="skip the 12-layer stack measurement (rt_stack_prefill)")
     ap.add_argument("--stack-only", action="store_true",
                     help="only the 12-layer stack through rt_stack_prefill (for profiling): prints its section alone")
@@ -253,6 +254,34 @@ def main():
                               "algorithmic_bytes": dec_bytes, "achieved": dec_bytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": dec_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                               "note": "nine launches per step on one stream (bf16: products on the matrix cores)"}
+
+    # The same layer without its sequential loop (every key-value pair known in advance): the recompute from a given
+    # output (Sec. 6.1) and the standard Transformer layer (Sec. 2.1) - the paper's Figure 4 compares the tiled RT layer
+    # with the latter.  GEMM-bound: 2 M (d^2 + 2 d F) FLOPs of the block + 2 M 3 d^2 per pre-pass + the attention.
+    if wl.dtype == "bf16" and not args.no_parallel:
+        y2, K2, V2 = torch.empty_like(y), torch.zeros_like(K), torch.zeros_like(V)
+        Mrows = wl.B * wl.N
+        blk = 2.0 * Mrows * (wl.d * wl.d + 2.0 * wl.d * wl.F)
+        pre = 2.0 * Mrows * 3.0 * wl.d * wl.d
+        sec = {}
+        for name, fn, fl in (("transformer_layer", lambda: ctx.rt_transformer_layer(dl.struct, xd, y2, K2, V2), blk + pre + attn_flops),
+                             ("recompute", lambda: ctx.rt_layer_recompute(dl.struct, xd, y, y2, K2, V2), blk + 2 * pre + attn_flops)):
+            fn()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            reps = 5
+            e0.record(stream)
+            for _ in range(reps):
+                fn()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            sec[name] = {"ms_per_call": ms, "tokens_per_s": tokens / (ms * 1e-3), "gflop": fl / 1e9, "bound": "mfma",
+                         "achieved": fl / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        sec["rt_layer_prefill_ms"] = dev_ms
+        sec["rt_over_transformer"] = dev_ms / sec["transformer_layer"]["ms_per_call"]
+        out["loop_free_layers"] = sec
 
     if not args.no_cpu_baseline:
         from oracle import rt_oracle
