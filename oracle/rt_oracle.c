@@ -16,6 +16,7 @@
  *                          query, read-modify-write); exists to check the exactness claim.
  *   rto_update_tile        Appendix C, Algorithm 2 on one (query tile, KV tile).
  *   rto_schedule           the (t, P, u, v, s, e) events of Algorithm 1.
+ *   rto_layer_prefill_blocked  the blocked-recurrence extension of Sec. 8 (reading stated at the function).
  *
  * Readings taken where the paper is silent (all configurable, see rto_params):
  *   RMS(x) = g * x / sqrt(mean(x^2) + eps)   (paper: sqrt(D) x / |x|, i.e. eps = 0, g = 1)
@@ -310,6 +311,52 @@ int rto_layer_prefill(const rto_params *p, const double *x, int B, int N, double
         }
     }
     if (ws) { for (int b = 0; b < B; ++b) if (ws[b].n) free_ws(&ws[b]); free(ws); }
+    free_tw(&w);
+    return err;
+}
+
+/* Blocked recurrence (Sec. 8, Discussion: "recurrence executed over blocks of steps", given as an extension in
+ * one sentence).  Reading: the positions are cut into blocks of S; a position attends the PERSISTENT pairs of all
+ * positions in earlier blocks, and the TEMPORARY pairs (from the layer input) of the positions of its own block up to
+ * and including itself - inside a block the layer is the Transformer layer of Sec. 2.1, across blocks the RT layer of
+ * Sec. 2.2, so the outputs of a block do not depend on each other and the recurrent depth is ceil(N / S).  S = 1 is
+ * the RT layer, S >= N the Transformer layer.  K, V receive the persistent pairs.  Serial (a test oracle). */
+int rto_layer_prefill_blocked(const rto_params *p, const double *x, int B, int N, int S, double *y, double *K, double *V,
+                              int kv_cap)
+{
+    if (check_params(p) || B <= 0 || N <= 0 || kv_cap < N || S <= 0) return -1;
+    rto_tw w;
+    if (make_tw(p, &w)) return -2;
+    const int d = p->d, H = p->H, dh = p->dh;
+    rto_ws s;
+    if (make_ws(&s, d, p->F > 0 ? p->F : 1, N + 1, H)) { free_tw(&w); return -2; }
+    const int Sb = S < N ? S : N;
+    double *Kp = (double *)malloc(sizeof(double) * (size_t)Sb * d), *Vp = (double *)malloc(sizeof(double) * (size_t)Sb * d);
+    int err = (Kp && Vp) ? 0 : -2;
+    for (int b = 0; b < B && !err; ++b) {
+        for (int t0 = 0; t0 < N; t0 += S) {
+            const int t1 = t0 + S < N ? t0 + S : N;
+            /* rows t0..t1-1 of K, V hold the temporary pairs while the block is evaluated */
+            for (int t = t0; t < t1; ++t) {
+                project_qkv(p, &w, x + ((size_t)b * N + t) * d, &s, 0);
+                memcpy(K + (((size_t)t * B + b) * H) * dh, s.kt, sizeof(double) * d);
+                memcpy(V + (((size_t)t * B + b) * H) * dh, s.vt, sizeof(double) * d);
+            }
+            for (int t = t0; t < t1; ++t) {
+                const double *xr = x + ((size_t)b * N + t) * d;
+                project_qkv(p, &w, xr, &s, 0);
+                attend(p, &s, K, V, B, b, t, NULL, 0, 0); /* rows < t0 persistent, rows t0..t-1 temporary, own pair */
+                finish_position(p, &w, xr, &s, y + ((size_t)b * N + t) * d, Kp + (size_t)(t - t0) * d,
+                                Vp + (size_t)(t - t0) * d, 0);
+            }
+            for (int t = t0; t < t1; ++t) {
+                memcpy(K + (((size_t)t * B + b) * H) * dh, Kp + (size_t)(t - t0) * d, sizeof(double) * d);
+                memcpy(V + (((size_t)t * B + b) * H) * dh, Vp + (size_t)(t - t0) * d, sizeof(double) * d);
+            }
+        }
+    }
+    free(Kp); free(Vp);
+    free_ws(&s);
     free_tw(&w);
     return err;
 }

@@ -60,6 +60,8 @@ def lib():
         L.rto_transformer_layer.restype = C.c_int
         L.rto_decode_step.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int]
         L.rto_decode_step.restype = C.c_int
+        L.rto_layer_prefill_blocked.argtypes = [PP, _DP, C.c_int, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int]
+        L.rto_layer_prefill_blocked.restype = C.c_int
         L.rto_update_tile.argtypes = [_DP, C.c_int, C.c_int, _DP, _DP, C.c_int, C.c_int, C.c_int, C.c_double,
                                       _DP, _DP, _DP, C.c_double, C.c_int]
         L.rto_update_tile.restype = None
@@ -150,6 +152,15 @@ class Layer:
         rc = lib().rto_layer_prefill_tiled(C.byref(self.p), _ptr(x), B, N, _ptr(y), _ptr(K), _ptr(V), kv_cap, int(chunk))
         if rc:
             raise RuntimeError("rto_layer_prefill_tiled failed: %d" % rc)
+        return y, K, V
+
+    def prefill_blocked(self, x, S, kv_cap=None):
+        """Blocked recurrence (Sec. 8, one sentence; reading: persistent pairs across blocks of S positions, temporary
+        pairs inside a block).  S = 1: the RT layer; S >= N: the Transformer layer.  Returns (y, K, V)."""
+        x, B, N, kv_cap, y, K, V = self._alloc(x, kv_cap)
+        rc = lib().rto_layer_prefill_blocked(C.byref(self.p), _ptr(x), B, N, int(S), _ptr(y), _ptr(K), _ptr(V), kv_cap)
+        if rc:
+            raise RuntimeError("rto_layer_prefill_blocked failed: %d" % rc)
         return y, K, V
 
     def recompute(self, x, z):

@@ -636,3 +636,62 @@ def test_p12_alibi_dense_restatement_and_fixed_point(oracle, beta):
     # beta = 0 is the layer without positions, bit for bit
     y3, _, _ = oracle.Layer(w, 3, gains=g, alpha=alpha, eps=eps, attn_scale=scale, alibi_max_bias=0.0).prefill(x)
     np.testing.assert_array_equal(y3, y0)
+
+
+# ------------------------------------------------------------------------------------------
+# P13  Blocked recurrence (Sec. 8: "recurrence executed over blocks of steps"; reading: persistent pairs across blocks,
+#      temporary pairs inside a block).
+# ------------------------------------------------------------------------------------------
+def _blocked_fixed_point(x, z, w, g, H, S, alpha, eps, scale, alibi=0.0):
+    """Dense restatement for one sequence: with z given, key j of query i is the persistent pair (from z_j) when j lies
+    in an earlier block and the temporary pair (from x_j) when it lies in i's own block, j <= i."""
+    N, d = x.shape
+    dh = d // H
+    gq, gk = g["g_q"].reshape(H, dh), g["g_k"].reshape(H, dh)
+    n = _rms(x, g["g_attn"], eps)
+    Q = _rms((n @ w["Wq"].T).reshape(N, H, dh), gq, eps)
+    Kt = _rms((n @ w["Wk"].T).reshape(N, H, dh), gk, eps)
+    Vt = (n @ w["Wv"].T).reshape(N, H, dh)
+    r = _rms(z, g["g_kv"], eps)
+    Kp = _rms((r @ w["Wk"].T).reshape(N, H, dh), gk, eps)
+    Vp = (r @ w["Wv"].T).reshape(N, H, dh)
+    i, j = np.arange(N)[:, None], np.arange(N)[None, :]
+    same = (i // S) == (j // S)
+    cat = np.zeros((N, H, dh))
+    for h in range(H):
+        Sm = scale * np.where(same, Q[:, h] @ Kt[:, h].T, Q[:, h] @ Kp[:, h].T)
+        if alibi:
+            Sm = Sm - 2.0 ** (-alibi * (h + 1) / H) * (i - j)
+        Sm = np.where(j <= i, Sm, -np.inf)
+        P = np.exp(Sm - Sm.max(axis=1, keepdims=True))
+        P /= P.sum(axis=1, keepdims=True)
+        cat[:, h] = (P * same) @ Vt[:, h] + (P * ~same) @ Vp[:, h]
+    a = cat.reshape(N, d) @ w["Wo"].T
+    hdd = x + alpha * a
+    return hdd + alpha * (_gelu(_rms(hdd, g["g_mlp"], eps) @ w["W1"].T) @ w["W2"].T), Kp, Vp
+
+
+@pytest.mark.parametrize("S,beta", [(4, 0.0), (8, 8.0), (5, 0.0)])
+def test_p13_blocked_recurrence(oracle, S, beta):
+    x, w, g = _small(71, B=2, N=22, d=24, H=3, F=40)
+    alpha, eps, scale = 0.6, 1e-5, 0.5
+    lay = oracle.Layer(w, 3, gains=g, alpha=alpha, eps=eps, attn_scale=scale, alibi_max_bias=beta)
+    y, K, V = lay.prefill_blocked(x, S)
+    # the two ends of the family: one position per block is the RT layer, one block is the Transformer layer
+    y1, K1, V1 = lay.prefill_blocked(x, 1)
+    yr, Kr, Vr = lay.prefill(x)
+    np.testing.assert_array_equal(y1, yr)
+    np.testing.assert_array_equal(K1, Kr)
+    yN, KN, VN = lay.prefill_blocked(x, 64)
+    yT, KT, VT = lay.transformer(x)
+    np.testing.assert_allclose(yN, yT, rtol=1e-12, atol=1e-13)
+    # in between it is neither ...
+    assert np.abs(y - yr).max() > 1e-3 and np.abs(y - yT).max() > 1e-3
+    # ... but the fixed point of the dense restatement with the block mask, with persistent pairs projected from its output
+    for b in range(2):
+        z2, Kp, Vp = _blocked_fixed_point(x[b], y[b], w, g, 3, S, alpha, eps, scale, alibi=beta)
+        np.testing.assert_allclose(z2, y[b], rtol=1e-10, atol=1e-11)
+        np.testing.assert_allclose(K[:, b], Kp, rtol=1e-10, atol=1e-11)
+        np.testing.assert_allclose(V[:, b], Vp, rtol=1e-10, atol=1e-11)
+    # the first block sees no persistent pair at all: it is the Transformer layer on those positions
+    np.testing.assert_allclose(y[:, :S], yT[:, :S], rtol=1e-12, atol=1e-13)
