@@ -145,6 +145,18 @@ rt_status rt_layer_recompute(rt_ctx *ctx, const rt_layer_weights *w, const void 
 rt_status rt_transformer_layer(rt_ctx *ctx, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, void *y,
                                void *K, void *V, int32_t kv_cap);
 
+/* Blocked recurrence, the extension the paper's Discussion (Sec. 8) names in one sentence ("recurrence executed over
+ * blocks of steps, yielding a controllable trade-off between recurrent depth and training speed").  Reading taken: the
+ * positions are cut into blocks of `block`; position i attends the persistent pairs k_j, v_j = proj(RMS(z_j)) of the
+ * positions j in EARLIER blocks and the temporary pairs (from the layer input) of the positions of its OWN block up
+ * to and including itself.  Inside a block this is the Transformer layer of Sec. 2.1, across blocks the RT layer of
+ * Sec. 2.2; the sequential loop runs over ceil(N / block) blocks whose `block` x B rows go through the matrix
+ * products together.  block = 1 is rt_layer_prefill's layer (a different, slower evaluation of it), block >= N would
+ * be rt_transformer_layer's.  K, V receive the persistent pairs.
+ *   block: power of two, 1 <= block <= p_min.  Other arguments and limits as rt_layer_recompute. */
+rt_status rt_layer_prefill_blocked(rt_ctx *ctx, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, int32_t block,
+                                   void *y, void *K, void *V, int32_t kv_cap);
+
 /* Input of the first layer of a stack (Sec. 2: a sequence of token embeddings enters the first layer):
  *   x[b, n, :] = table[ids[b * ids_stride + first + n], :]   for 0 <= b < B, 0 <= n < N.
  *   table [vocab, d] device, storage dtype; ids device int32; x [B, N, d] device, written.
@@ -177,7 +189,7 @@ uint64_t rt_workspace_bytes(const rt_ctx *ctx);
 int32_t rt_device_wait_expired(rt_ctx *ctx);
 
 /* Name of the engine the last prefill call on this context used: "stepwise", "stepwise+graph",
- * "persistent", "wavefront" (rt_stack_prefill), "recompute", "transformer", or "" before the first call. */
+ * "persistent", "wavefront" (rt_stack_prefill), "recompute", "transformer", "blocked", or "" before the first call. */
 const char *rt_engine_name(const rt_ctx *ctx);
 
 /* Diagnostics of the persistent engine, after the stream has been synchronised: when the environment

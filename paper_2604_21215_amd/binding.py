@@ -23,7 +23,8 @@ RT_FLAG_HIP_GRAPH = 0x10
 EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_last_error", "rt_status_string",
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
            "rt_version", "rt_phase_trace", "rt_schedule_events_shifted", "rt_embed_rows", "rt_lm_head", "rt_cross_block_event",
-           "rt_stack_prefill", "rt_schedule_events_chunked", "rt_layer_recompute", "rt_transformer_layer")
+           "rt_stack_prefill", "rt_schedule_events_chunked", "rt_layer_recompute", "rt_transformer_layer",
+           "rt_layer_prefill_blocked")
 
 
 class rt_config(C.Structure):
@@ -110,6 +111,9 @@ def load():
     L.rt_transformer_layer.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_void_p, C.c_int32, C.c_int32, C.c_void_p,
                                        C.c_void_p, C.c_void_p, C.c_int32]
     L.rt_transformer_layer.restype = C.c_int
+    L.rt_layer_prefill_blocked.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
+                                           C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+    L.rt_layer_prefill_blocked.restype = C.c_int
     _lib = L
     return L
 
@@ -204,6 +208,13 @@ class RTContext:
         B, N, _ = x.shape
         rc = self._L.rt_layer_recompute(self._ctx, C.byref(weights), _ptr(x), _ptr(z), B, N, _ptr(y), _ptr(K), _ptr(V),
                                         K.shape[0])
+        _check(self._L, self._ctx, rc)
+
+    # -- rt_layer_prefill_blocked(ctx, w, x[B,N,d], B, N, block, y, K, V, kv_cap)
+    def rt_layer_prefill_blocked(self, weights: rt_layer_weights, x, block, y, K, V):
+        B, N, _ = x.shape
+        rc = self._L.rt_layer_prefill_blocked(self._ctx, C.byref(weights), _ptr(x), B, N, int(block), _ptr(y), _ptr(K),
+                                              _ptr(V), K.shape[0])
         _check(self._L, self._ctx, rc)
 
     # -- rt_transformer_layer(ctx, w, x[B,N,d], B, N, y, K, V, kv_cap)

@@ -658,8 +658,9 @@ extern "C" rt_status rt_stack_prefill(rt_ctx *c, const rt_layer_weights *layers,
 }
 
 // Loop-free evaluation of a whole sequence (rt_parallel.hip); pairs_src = z (recompute) or x (Transformer layer).
+// block > 0: blocked recurrence over blocks of that many positions instead (pairs_src = x).
 static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void *x, const void *pairs_src, bool transformer,
-                                int32_t B, int32_t N, void *y, void *K, void *V, int32_t kv_cap)
+                                int32_t B, int32_t N, void *y, void *K, void *V, int32_t kv_cap, int32_t block = 0)
 {
     if (!c) return RT_ERR_INVALID_ARG;
     if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
@@ -669,6 +670,8 @@ static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void
     if (B < 1 || B > c->cfg.max_batch) return fail(c, RT_ERR_INVALID_ARG, "B out of range [1, max_batch]%s");
     if (N < 1 || N > c->cfg.max_seq) return fail(c, RT_ERR_INVALID_ARG, "N out of range [1, max_seq]%s");
     if (kv_cap < N) return fail(c, RT_ERR_INVALID_ARG, "kv_cap < N%s");
+    if (block != 0 && (!is_pow2(block) || block > c->cfg.p_min))
+        return fail(c, RT_ERR_INVALID_ARG, "block must be a power of two, at most p_min%s");
     const size_t E = 2;
     const size_t xb = (size_t)B * N * c->cfg.d_model * E, kvb = (size_t)kv_cap * B * c->cfg.d_model * E;
     if (ranges_overlap(x, xb, y, xb) || (pairs_src != x && ranges_overlap(pairs_src, xb, y, xb)))
@@ -693,11 +696,19 @@ static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void
         c->par_bytes = bytes;
     }
     c->last_B = B; c->last_N = N;
-    c->engine = transformer ? "transformer" : "recompute";
+    c->engine = block ? "blocked" : (transformer ? "transformer" : "recompute");
     const Weights W = to_weights(w);
-    hipError_t e = parallel_layer(D, W, c->S, x, pairs_src, transformer, y, K, V, c->par_slab, c->stream);
+    hipError_t e = block ? blocked_layer(D, W, c->S, x, block, y, K, V, c->par_slab, c->stream)
+                         : parallel_layer(D, W, c->S, x, pairs_src, transformer, y, K, V, c->par_slab, c->stream);
     if (e != hipSuccess) return fail_hip(c, e, "parallel_layer");
     return RT_OK;
+}
+
+extern "C" rt_status rt_layer_prefill_blocked(rt_ctx *c, const rt_layer_weights *w, const void *x, int32_t B, int32_t N,
+                                              int32_t block, void *y, void *K, void *V, int32_t kv_cap)
+{
+    if (block < 1) return c ? fail(c, RT_ERR_INVALID_ARG, "block must be a power of two, at most p_min%s") : RT_ERR_INVALID_ARG;
+    return parallel_entry(c, w, x, x, true, B, N, y, K, V, kv_cap, block);
 }
 
 extern "C" rt_status rt_layer_recompute(rt_ctx *c, const rt_layer_weights *w, const void *x, const void *z, int32_t B, int32_t N,

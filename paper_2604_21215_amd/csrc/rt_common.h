@@ -233,6 +233,9 @@ bool parallel_supported(const LayerDims &D, bool mfma_bf16);
 size_t parallel_scratch_bytes(size_t M, size_t d, size_t F);
 hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, const void *pairs_src,
                           bool pairs_are_temporary, void *y, void *K, void *V, void *par, hipStream_t st);
+// blocked recurrence over blocks of Sblk positions (a power of two dividing p_min); same scratch
+hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Sblk, void *y, void *K, void *V,
+                         void *par, hipStream_t st);
 
 // embedding lookup and final-norm + output projection of a layer stack (rt_stack.hip)
 template <typename T>

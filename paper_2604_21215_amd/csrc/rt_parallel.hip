@@ -27,13 +27,16 @@ hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K
 //   PG_W1: out_b = gelu(rinv_m * C), A rows multiplied by `gain` on the way, rinv_m = 1/rms of the raw A row,
 //          formed from the fragments (u = gelu(W1 RMS(h; g_mlp)))
 //   PG_W2: out_b = res_f + alpha C                               (y = h + alpha W2 u)
+// Rows: the M rows are positions n0 .. n0 + Nc - 1 of every batch row of [B][N][*] tensors (A, res, out alike):
+// row m lives at tensor row (m / Nc) * N + n0 + m % Nc  (Nc = N, n0 = 0: the whole tensor).
 // grid (ceil(M / 128), Nn / 128 rounded up), Nn a multiple of 64.
 // ---------------------------------------------------------------------------------------------
 enum { PG_WO = 0, PG_W1 = 1, PG_W2 = 2 };
 
 template <int EPI>
 __global__ __launch_bounds__(256) void par_gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int M, int Nn,
-                                                       int K, const bf16_t *__restrict__ gain, float eps, int norm_free,
+                                                       int K, int Nc, int N, int n0, const bf16_t *__restrict__ gain, float eps,
+                                                       int norm_free,
                                                        float alpha, const bf16_t *__restrict__ res_b,
                                                        const float *__restrict__ res_f, float *__restrict__ out_f,
                                                        bf16_t *__restrict__ out_b)
@@ -41,8 +44,8 @@ __global__ __launch_bounds__(256) void par_gemm_kernel(const bf16_t *__restrict_
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int l16 = lane & 15, g = lane >> 4;
-    const int m0 = blockIdx.x * 128 + wm * 64, n0 = blockIdx.y * 128 + wn * 64;
-    if (m0 >= M || n0 >= Nn) return;   // no barriers in this kernel
+    const int m0 = blockIdx.x * 128 + wm * 64, nb0 = blockIdx.y * 128 + wn * 64;
+    if (m0 >= M || nb0 >= Nn) return;   // no barriers in this kernel
 
     f32x4_t acc[4][4];
 #pragma unroll
@@ -52,8 +55,9 @@ __global__ __launch_bounds__(256) void par_gemm_kernel(const bf16_t *__restrict_
     const bf16_t *arow[4], *brow[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        arow[i] = A + (size_t)min(m0 + i * 16 + l16, M - 1) * K + 8 * g;
-        brow[i] = W + (size_t)(n0 + i * 16 + l16) * K + 8 * g;
+        const int mr = min(m0 + i * 16 + l16, M - 1);
+        arow[i] = A + ((size_t)(mr / Nc) * N + n0 + mr % Nc) * K + 8 * g;
+        brow[i] = W + (size_t)(nb0 + i * 16 + l16) * K + 8 * g;
     }
     const bool normed = EPI == PG_W1 && !norm_free;
     const bool use_gain = normed && gain != nullptr;
@@ -103,9 +107,10 @@ __global__ __launch_bounds__(256) void par_gemm_kernel(const bf16_t *__restrict_
             // this lane's output rows are 16 i + 4 g + r; their scale sits in the lanes whose l16 is 4 g + r
             const float rs = normed ? __shfl(ssq[i], 4 * g + r, 64) : 1.f;
             if (m < M) {
+                const size_t row = (size_t)(m / Nc) * N + n0 + m % Nc;
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
-                    const size_t o = (size_t)m * Nn + n0 + j * 16 + l16;
+                    const size_t o = row * Nn + nb0 + j * 16 + l16;
                     const float c = acc[i][j][r];
                     if (EPI == PG_WO) {
                         const float h = bf16_to_f32(res_b[o]) + alpha * c;
@@ -122,14 +127,14 @@ __global__ __launch_bounds__(256) void par_gemm_kernel(const bf16_t *__restrict_
     }
 }
 
-// K, V of every position from the pre-pass outputs (rows (t, b, h)): the caller's cache rows, the bf16 remainder
+// K, V of positions t0 .. t0 + gridDim.y - 1 from the pre-pass outputs (rows (t, b, h)): the caller's cache rows, the bf16 remainder
 // of the keys and the transposed values for the tiles.  grid (B*H, N), block 64.
 __global__ __launch_bounds__(64) void par_export_kernel(const bf16_t *__restrict__ Ks, const float *__restrict__ Kf,
                                                         const bf16_t *__restrict__ Vs, bf16_t *__restrict__ K,
                                                         bf16_t *__restrict__ V, bf16_t *__restrict__ Klo,
-                                                        bf16_t *__restrict__ VT, int vt_stride, int BH)
+                                                        bf16_t *__restrict__ VT, int vt_stride, int BH, int t0)
 {
-    const int lane = threadIdx.x, bh = blockIdx.x, t = blockIdx.y;
+    const int lane = threadIdx.x, bh = blockIdx.x, t = t0 + blockIdx.y;
     const size_t off = ((size_t)t * BH + bh) * kHeadDim + lane;
     const bf16_t k = Ks[off], v = Vs[off];
     K[off] = k;
@@ -138,7 +143,7 @@ __global__ __launch_bounds__(64) void par_export_kernel(const bf16_t *__restrict
     VT[((size_t)bh * kHeadDim + lane) * vt_stride + t] = v;
 }
 
-// a_t of every position (merge_body) as bf16 rows [B][N][d].  grid (B*H, N), block 64.
+// a_t of positions t0 .. t0 + gridDim.y - 1 (merge_body) as bf16 rows of [B][N][d].  grid (B*H, positions), block 64.
 __global__ __launch_bounds__(64) void par_merge_kernel(const bf16_t *__restrict__ Q, const float *__restrict__ Qf,
                                                        const bf16_t *__restrict__ Kt, const float *__restrict__ Ktf,
                                                        const bf16_t *__restrict__ Vt, const bf16_t *__restrict__ K,
@@ -146,13 +151,30 @@ __global__ __launch_bounds__(64) void par_merge_kernel(const bf16_t *__restrict_
                                                        const float *__restrict__ pm, const float *__restrict__ pl,
                                                        const float *__restrict__ po, bf16_t *__restrict__ a_out, int BH, int H,
                                                        int N, int p_min, int log2_pmin, int levels, int slots, float scale,
-                                                       float alibi)
+                                                       float alibi, int t0)
 {
-    const int bh = blockIdx.x, t = blockIdx.y;
+    const int bh = blockIdx.x, t = t0 + blockIdx.y;
     const float a = merge_body<bf16_t, true>(Q, Qf, Kt, Ktf, Vt, K, Klo, V, pm, pl, po, nullptr, BH, H, bh, t, t, p_min, log2_pmin,
                                              levels, slots, -1, scale, -1, 0, nullptr, alibi);
     const int b = bh / H, h = bh % H;
     a_out[((size_t)b * N + t) * ((size_t)H * kHeadDim) + h * kHeadDim + threadIdx.x] = f32_to_bf16(a);
+}
+
+// h = x + alpha Wo a;  u = gelu(W1 RMS(h));  y = h + alpha W2 u  for positions n0 .. n0 + Nc - 1 of every batch row
+static void block_gemms(const LayerDims &D, const Weights &W, const void *x, void *y, bf16_t *a_b, float *h_f, bf16_t *h_b,
+                        bf16_t *u_b, int n0, int Nc, hipStream_t st)
+{
+    const int d = D.d, F = D.F, M = D.B * Nc;
+    const unsigned gm = (unsigned)((M + 127) / 128);
+    hipLaunchKernelGGL(par_gemm_kernel<PG_WO>, dim3(gm, (unsigned)((d + 127) / 128)), dim3(256), 0, st, a_b, (const bf16_t *)W.Wo, M, d,
+                       d, Nc, D.N, n0, (const bf16_t *)nullptr, D.eps, D.norm_free, D.alpha, (const bf16_t *)x,
+                       (const float *)nullptr, h_f, h_b);
+    hipLaunchKernelGGL(par_gemm_kernel<PG_W1>, dim3(gm, (unsigned)((F + 127) / 128)), dim3(256), 0, st, h_b, (const bf16_t *)W.W1, M, F,
+                       d, Nc, D.N, n0, (const bf16_t *)W.g_mlp, D.eps, D.norm_free, D.alpha, (const bf16_t *)nullptr,
+                       (const float *)nullptr, (float *)nullptr, u_b);
+    hipLaunchKernelGGL(par_gemm_kernel<PG_W2>, dim3(gm, (unsigned)((d + 127) / 128)), dim3(256), 0, st, u_b, (const bf16_t *)W.W2, M, d,
+                       F, Nc, D.N, n0, (const bf16_t *)nullptr, D.eps, D.norm_free, D.alpha, (const bf16_t *)nullptr, h_f,
+                       (float *)nullptr, (bf16_t *)y);
 }
 
 bool parallel_supported(const LayerDims &D, bool mfma_bf16) { return mfma_bf16 && D.d % 64 == 0 && D.F % 64 == 0; }
@@ -177,7 +199,7 @@ hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S
     hipError_t e = Launch<bf16_t>::prepass(D, Wp, S, pairs_src, B, N, true, st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(par_export_kernel, dim3(BH, N), dim3(64), 0, st, (const bf16_t *)S.Kt, S.Ktf, (const bf16_t *)S.Vt,
-                       (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH);
+                       (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, 0);
     if (!pairs_are_temporary) {
         e = Launch<bf16_t>::prepass(D, W, S, x, B, N, true, st);
         if (e != hipSuccess) return e;
@@ -192,16 +214,53 @@ hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S
     }
     hipLaunchKernelGGL(par_merge_kernel, dim3(BH, N), dim3(64), 0, st, (const bf16_t *)S.Q, S.Qf, (const bf16_t *)S.Kt, S.Ktf,
                        (const bf16_t *)S.Vt, (const bf16_t *)K, S.Klo, (const bf16_t *)V, S.pm, S.pl, S.po, a_b, BH, D.H, N, D.p_min,
-                       D.log2_pmin, S.levels, S.slots, D.scale, D.alibi);
-    const unsigned gm = (unsigned)((M + 127) / 128);
-    hipLaunchKernelGGL(par_gemm_kernel<PG_WO>, dim3(gm, (unsigned)((d + 127) / 128)), dim3(256), 0, st, a_b, (const bf16_t *)W.Wo, M, d,
-                       d, (const bf16_t *)nullptr, D.eps, D.norm_free, D.alpha, (const bf16_t *)x, (const float *)nullptr, h_f, h_b);
-    hipLaunchKernelGGL(par_gemm_kernel<PG_W1>, dim3(gm, (unsigned)((F + 127) / 128)), dim3(256), 0, st, h_b, (const bf16_t *)W.W1, M, F,
-                       d, (const bf16_t *)W.g_mlp, D.eps, D.norm_free, D.alpha, (const bf16_t *)nullptr, (const float *)nullptr,
-                       (float *)nullptr, u_b);
-    hipLaunchKernelGGL(par_gemm_kernel<PG_W2>, dim3(gm, (unsigned)((d + 127) / 128)), dim3(256), 0, st, u_b, (const bf16_t *)W.W2, M, d,
-                       F, (const bf16_t *)nullptr, D.eps, D.norm_free, D.alpha, (const bf16_t *)nullptr, h_f, (float *)nullptr,
-                       (bf16_t *)y);
+                       D.log2_pmin, S.levels, S.slots, D.scale, D.alibi, 0);
+    block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, 0, N, st);
+    return hipGetLastError();
+}
+
+// Blocked recurrence (Sec. 8, Discussion; the reading is stated at rt_layer_prefill_blocked in rt.h): blocks of Sblk
+// positions, a power of two that divides p_min, so that every event of Algorithm 1 falls on a block boundary.  While
+// a block is evaluated its rows of K, V hold the TEMPORARY pairs (the direct window of merge_body then reads
+// persistent pairs of earlier blocks and temporary pairs of the own block without knowing the difference); after the
+// block's outputs are there they are overwritten with the persistent pairs projected from those outputs.
+hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Sblk, void *y, void *K, void *V,
+                         void *par, hipStream_t st)
+{
+    const int B = D.B, N = D.N, d = D.d, F = D.F, BH = B * D.H;
+    const size_t Mmax = (size_t)B * N;
+    char *p = (char *)par;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    bf16_t *a_b = (bf16_t *)p; p += up(Mmax * d * 2);
+    float *h_f = (float *)p; p += up(Mmax * d * 4);
+    bf16_t *h_b = (bf16_t *)p; p += up(Mmax * d * 2);
+    bf16_t *u_b = (bf16_t *)p;
+    (void)F;
+    Weights Wp = W;
+    Wp.g_attn = W.g_kv;
+    hipError_t e = Launch<bf16_t>::prepass(D, W, S, x, B, N, true, st);   // q and temporary pairs of every position
+    if (e != hipSuccess) return e;
+    for (int t0 = 0; t0 < N; t0 += Sblk) {
+        const int nr = Sblk < N - t0 ? Sblk : N - t0;
+        hipLaunchKernelGGL(par_export_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Kt, S.Ktf, (const bf16_t *)S.Vt,
+                           (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, t0);
+        hipLaunchKernelGGL(par_merge_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Q, S.Qf, (const bf16_t *)S.Kt, S.Ktf,
+                           (const bf16_t *)S.Vt, (const bf16_t *)K, S.Klo, (const bf16_t *)V, S.pm, S.pl, S.po, a_b, BH, D.H, N,
+                           D.p_min, D.log2_pmin, S.levels, S.slots, D.scale, D.alibi, t0);
+        block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, t0, nr, st);
+        // persistent pairs of the block from its outputs (rows t0.. of the pre-pass buffers are free again)
+        e = Launch<bf16_t>::prepass(D, Wp, S, y, B, nr, true, st, (size_t)N * d, t0);
+        if (e != hipSuccess) return e;
+        hipLaunchKernelGGL(par_export_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Kt, S.Ktf, (const bf16_t *)S.Vt,
+                           (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, t0);
+        const int t1 = t0 + nr;
+        const int P = t1 & -t1;
+        if (P >= D.p_min && t1 < N) {
+            const int nq = (P < N - t1) ? P : N - t1;
+            e = cross_mfma_launch(D, S, K, t1, P, nq, true, st);
+            if (e != hipSuccess) return e;
+        }
+    }
     return hipGetLastError();
 }
 

@@ -97,6 +97,40 @@ def test_transformer_layer(oracle, B, N, d, H, F, alibi):
         ctx.rt_destroy()
 
 
+@pytest.mark.parametrize("B,N,d,H,F,block,p_min,alibi", [
+    (2, 200, 256, 4, 1024, 8, 32, 0.0),
+    (3, 333, 320, 5, 1280, 32, 32, 8.0),      # block = p_min, ragged last block, bias
+    (2, 300, 256, 4, 1024, 1, 32, 0.0),       # one position per block: the RT layer itself
+    (8, 400, 1024, 16, 4096, 16, 64, 0.0),
+])
+def test_blocked_recurrence(oracle, B, N, d, H, F, block, p_min, alibi):
+    """rt_layer_prefill_blocked against the oracle's blocked recurrence (persistent pairs across blocks, temporary pairs
+    inside a block)."""
+    li = gen.make_custom(26, "bf16", B, N, d, H, F, gains="random")
+    x64 = li.x.astype(np.float64)
+    lay = oracle_layer(oracle, li, H, alpha=0.8, eps=1e-6, alibi_max_bias=alibi)
+    ref = lay.prefill_blocked(x64, block)
+    ctx, tio, dl, xd, y, K, V = _setup(li, B, N, d, H, F, resid_scale=0.8, rms_eps=1e-6, alibi_max_bias=alibi, p_min=p_min)
+    try:
+        ctx.rt_layer_prefill_blocked(dl.struct, xd, block, y, K, V)
+        torch.cuda.synchronize()
+        assert ctx.engine_name() == "blocked"
+        _check("blocked recurrence B=%d N=%d d=%d block=%d" % (B, N, d, block), x64, ref,
+               (tio.to_host(y), tio.to_host(K), tio.to_host(V)), TOL["bf16"])
+        if block == 1:       # the same layer as rt_layer_prefill evaluates
+            y1, K1, V1 = tio.prefill(ctx, dl, xd)
+            torch.cuda.synchronize()
+            _check("block = 1 against rt_layer_prefill", x64, (tio.to_host(y1), tio.to_host(K1), tio.to_host(V1)),
+                   (tio.to_host(y), tio.to_host(K), tio.to_host(V)), TOL["bf16"])
+        from paper_2604_21215_amd import binding
+        with pytest.raises(binding.RTError):
+            ctx.rt_layer_prefill_blocked(dl.struct, xd, 2 * p_min, y, K, V)      # block > p_min
+        with pytest.raises(binding.RTError):
+            ctx.rt_layer_prefill_blocked(dl.struct, xd, 3, y, K, V)              # not a power of two
+    finally:
+        ctx.rt_destroy()
+
+
 def test_parallel_entry_points_reject_what_they_do_not_cover():
     if not torch.cuda.is_available():
         pytest.fail("no GPU visible")
