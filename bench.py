@@ -279,6 +279,21 @@ def main():
             sec[name] = {"ms_per_call": ms, "tokens_per_s": tokens / (ms * 1e-3), "gflop": fl / 1e9, "bound": "mfma",
                          "achieved": fl / (ms * 1e-3) / 1e12, "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
                          "frac": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
+        # blocked recurrence (Sec. 8): the sequential loop over blocks of S positions, S x B rows per matrix product
+        blocked = {}
+        for S in (4, 16, 32):
+            fnb = lambda: ctx.rt_layer_prefill_blocked(dl.struct, xd, S, y2, K2, V2)
+            fnb()
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(2):
+                fnb()
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 2
+            blocked["block_%d" % S] = {"ms_per_call": ms, "tokens_per_s": tokens / (ms * 1e-3)}
+        sec["blocked_recurrence"] = blocked
         sec["rt_layer_prefill_ms"] = dev_ms
         sec["rt_over_transformer"] = dev_ms / sec["transformer_layer"]["ms_per_call"]
         out["loop_free_layers"] = sec

@@ -127,6 +127,194 @@ __global__ __launch_bounds__(256) void par_gemm_kernel(const bf16_t *__restrict_
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The same products for FEW rows (a block of the blocked recurrence: M = block x B, tens to a few hundred rows),
+// where the kernel above is latency-bound: few workgroups, and every wavefront walks the whole contraction in
+// dependent steps.  Here a workgroup owns a 64 x 64 output tile and its four wavefronts split the contraction
+// (each the full tile over K / 4); a wavefront issues the loads of four steps (128 indices: 32 fragments) before
+// their 64 matrix instructions; the four partial tiles and the partial row statistics meet in LDS, then thread
+// (row, quarter) finishes 16 consecutive outputs of one row.
+//   PG_PRE: the pre-pass projection: W = [Wq; Wk; Wv] by column block (one head each), A rows RMS-normalised with
+//           `gain`, then qkRMS per head for q and k_tmp; rows go to Q / Kt / Vt (and fp32 Qf / Ktf) position-first.
+// grid (ceil(M / 64), Nn / 64), block 256, 69 KB of LDS.
+// ---------------------------------------------------------------------------------------------
+constexpr int PG_PRE = 3;
+constexpr int kSkLd = 68;   // row stride of a partial tile in floats
+
+struct PreOut {   // PG_PRE only
+    const bf16_t *Wq, *Wk, *Wv, *g_q, *g_k;
+    bf16_t *Q, *Kt, *Vt;
+    float *Qf, *Ktf;
+    int H, Bc;
+};
+
+template <int EPI>
+__global__ __launch_bounds__(256) void blk_gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int M, int Nn,
+                                                       int K, int Nc, int N, int n0, const bf16_t *__restrict__ gain, float eps,
+                                                       int norm_free, float alpha, const bf16_t *__restrict__ res_b,
+                                                       const float *__restrict__ res_f, float *__restrict__ out_f,
+                                                       bf16_t *__restrict__ out_b, PreOut po)
+{
+    extern __shared__ __align__(16) unsigned char blk_smem[];
+    float *part = reinterpret_cast<float *>(blk_smem);               // [4][64][kSkLd]
+    float *ssq_s = part + 4 * 64 * kSkLd;                             // [4][64]
+    const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+    const int m0 = blockIdx.x * 64, nb0 = blockIdx.y * 64;
+    const bf16_t *Wt = W;
+    if (EPI == PG_PRE) {
+        const int which = (int)blockIdx.y / po.H, h = (int)blockIdx.y % po.H;
+        Wt = (which == 0 ? po.Wq : (which == 1 ? po.Wk : po.Wv)) + (size_t)h * kHeadDim * K - (size_t)nb0 * K;
+    }
+    const int klen = K / 4, kbeg = kw * klen;
+    f32x4_t acc[4][4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const bf16_t *arow[4], *brow[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        const int mr = min(m0 + i * 16 + l16, M - 1);
+        arow[i] = A + ((size_t)(mr / Nc) * N + n0 + mr % Nc) * K + kbeg + 8 * g;
+        brow[i] = Wt + (size_t)(nb0 + i * 16 + l16) * K + kbeg + 8 * g;
+    }
+    const bool normed = (EPI == PG_W1 || EPI == PG_PRE) && !norm_free;
+    const bool use_gain = normed && gain != nullptr;
+    float ssq[4] = {0.f, 0.f, 0.f, 0.f};
+
+#define RT_SK_STEP(av, bv, kk)                                                                                  \
+    {                                                                                                           \
+        if (normed) {                                                                                           \
+            float gg[8] = {1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f, 1.f};                                             \
+            if (use_gain) load8(gain + kbeg + (kk) + 8 * g, gg);                                                \
+            _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                       \
+            {                                                                                                   \
+                const uint32_t w4[4] = {av[i].u.x, av[i].u.y, av[i].u.z, av[i].u.w};                            \
+                uint32_t o4[4];                                                                                 \
+                _Pragma("unroll") for (int e = 0; e < 4; ++e)                                                   \
+                {                                                                                               \
+                    const float lo = __uint_as_float(w4[e] << 16), hi = __uint_as_float(w4[e] & 0xFFFF0000u);   \
+                    ssq[i] = fmaf(lo, lo, fmaf(hi, hi, ssq[i]));                                                \
+                    o4[e] = pack_bf16(lo * gg[2 * e], hi * gg[2 * e + 1]);                                      \
+                }                                                                                               \
+                if (use_gain) av[i].u = make_uint4(o4[0], o4[1], o4[2], o4[3]);                                 \
+            }                                                                                                   \
+        }                                                                                                       \
+        _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                           \
+            _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma16(av[i], bv[j], acc[i][j]);          \
+    }
+    int k = 0;
+    for (; k + 128 <= klen; k += 128) {   // four steps: 32 fragment loads in flight, then their 64 matrix instructions
+        Frag a[4][4], b[4][4];
+#pragma unroll
+        for (int st = 0; st < 4; ++st)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                a[st][i].u = *reinterpret_cast<const uint4 *>(arow[i] + k + 32 * st);
+                b[st][i].u = *reinterpret_cast<const uint4 *>(brow[i] + k + 32 * st);
+            }
+#pragma unroll
+        for (int st = 0; st < 4; ++st) RT_SK_STEP(a[st], b[st], k + 32 * st)
+    }
+    for (; k < klen; k += 32) {
+        Frag a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            a[i].u = *reinterpret_cast<const uint4 *>(arow[i] + k);
+            b[i].u = *reinterpret_cast<const uint4 *>(brow[i] + k);
+        }
+        RT_SK_STEP(a, b, k)
+    }
+#undef RT_SK_STEP
+    // partial tile and partial row statistics of this wavefront
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        if (normed) {
+            ssq[i] += __shfl_xor(ssq[i], 16, 64);
+            ssq[i] += __shfl_xor(ssq[i], 32, 64);
+            if (g == 0) ssq_s[kw * 64 + i * 16 + l16] = ssq[i];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) part[(kw * 64 + i * 16 + 4 * g + r) * kSkLd + j * 16 + l16] = acc[i][j][r];
+    }
+    __syncthreads();
+    // thread (row, quarter): 16 consecutive outputs of one row
+    const int row = tid >> 2, qc = (tid & 3) * 16;
+    const int m = m0 + row;
+    float v[16];
+#pragma unroll
+    for (int c4 = 0; c4 < 4; ++c4) {
+        float4 s4 = *reinterpret_cast<const float4 *>(part + (size_t)row * kSkLd + qc + 4 * c4);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) {
+            const float4 t4 = *reinterpret_cast<const float4 *>(part + (size_t)(w * 64 + row) * kSkLd + qc + 4 * c4);
+            s4.x += t4.x; s4.y += t4.y; s4.z += t4.z; s4.w += t4.w;
+        }
+        v[4 * c4] = s4.x; v[4 * c4 + 1] = s4.y; v[4 * c4 + 2] = s4.z; v[4 * c4 + 3] = s4.w;
+    }
+    float rs = 1.f;
+    if (normed) rs = rsqrtf(((ssq_s[row] + ssq_s[64 + row]) + (ssq_s[128 + row] + ssq_s[192 + row])) / (float)K + eps);
+    if (EPI == PG_PRE) {
+        const int which = (int)blockIdx.y / po.H, h = (int)blockIdx.y % po.H;
+        float ss = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) { v[e] *= rs; ss = fmaf(v[e], v[e], ss); }
+        ss += __shfl_xor(ss, 1, 64);   // the four threads of a row are adjacent lanes
+        ss += __shfl_xor(ss, 2, 64);
+        const bool qk = which < 2 && !norm_free;
+        const float sc = qk ? rsqrtf(ss / (float)kHeadDim + eps) : 1.f;
+        const bf16_t *gn = which == 0 ? po.g_q : po.g_k;
+        if (m < M) {
+            const int bb = m / Nc, n = n0 + m % Nc;
+            const size_t oo = ((size_t)n * po.Bc + bb) * K + h * kHeadDim + qc;   // the projection is square: row length = K = d
+            bf16_t *dst = which == 0 ? po.Q : (which == 1 ? po.Kt : po.Vt);
+            float *dstf = which == 0 ? po.Qf : (which == 1 ? po.Ktf : nullptr);
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                float val = v[e] * sc;
+                if (qk && gn) val *= bf16_to_f32(gn[h * kHeadDim + qc + e]);
+                dst[oo + e] = f32_to_bf16(val);
+                if (dstf) dstf[oo + e] = val;
+            }
+        }
+        return;
+    }
+    if (m >= M) return;
+    const size_t o = ((size_t)(m / Nc) * N + n0 + m % Nc) * Nn + nb0 + qc;
+#pragma unroll
+    for (int e = 0; e < 16; ++e) {
+        if (EPI == PG_WO) {
+            const float h = bf16_to_f32(res_b[o + e]) + alpha * v[e];
+            out_f[o + e] = h;
+            out_b[o + e] = f32_to_bf16(h);
+        } else if (EPI == PG_W1) {
+            out_b[o + e] = f32_to_bf16(gelu_erf(v[e] * rs));
+        } else {
+            out_b[o + e] = f32_to_bf16(res_f[o + e] + alpha * v[e]);
+        }
+    }
+}
+
+constexpr size_t kBlkLds = (size_t)(4 * 64 * kSkLd + 4 * 64) * 4;
+template <int EPI>
+static hipError_t blk_gemm_launch(dim3 grid, hipStream_t st, const bf16_t *A, const bf16_t *W, int M, int Nn, int K, int Nc, int N,
+                                  int n0, const bf16_t *gain, float eps, int norm_free, float alpha, const bf16_t *res_b,
+                                  const float *res_f, float *out_f, bf16_t *out_b, const PreOut &po)
+{
+    static bool raised = false;   // more than the default 64 KB of dynamic LDS
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute((const void *)blk_gemm_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBlkLds);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL(blk_gemm_kernel<EPI>, grid, dim3(256), kBlkLds, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free, alpha,
+                       res_b, res_f, out_f, out_b, po);
+    return hipSuccess;
+}
+
 // K, V of positions t0 .. t0 + gridDim.y - 1 from the pre-pass outputs (rows (t, b, h)): the caller's cache rows, the bf16 remainder
 // of the keys and the transposed values for the tiles.  grid (B*H, N), block 64.
 __global__ __launch_bounds__(64) void par_export_kernel(const bf16_t *__restrict__ Ks, const float *__restrict__ Kf,
@@ -160,11 +348,38 @@ __global__ __launch_bounds__(64) void par_merge_kernel(const bf16_t *__restrict_
     a_out[((size_t)b * N + t) * ((size_t)H * kHeadDim) + h * kHeadDim + threadIdx.x] = f32_to_bf16(a);
 }
 
+constexpr int kSmallM = 2048;   // up to this many rows the split-contraction kernel is used
+
+// the pre-pass projection of positions n0 .. n0 + Nc - 1 of every batch row of `src` with the split-contraction kernel
+static hipError_t small_prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *src, int n0, int Nc, hipStream_t st)
+{
+    PreOut po;
+    po.Wq = (const bf16_t *)W.Wq; po.Wk = (const bf16_t *)W.Wk; po.Wv = (const bf16_t *)W.Wv;
+    po.g_q = (const bf16_t *)W.g_q; po.g_k = (const bf16_t *)W.g_k;
+    po.Q = (bf16_t *)S.Q; po.Kt = (bf16_t *)S.Kt; po.Vt = (bf16_t *)S.Vt; po.Qf = S.Qf; po.Ktf = S.Ktf;
+    po.H = D.H; po.Bc = D.B;
+    const int M = D.B * Nc;
+    return blk_gemm_launch<PG_PRE>(dim3((unsigned)((M + 63) / 64), (unsigned)(3 * D.H)), st, (const bf16_t *)src, nullptr, M, 3 * D.d,
+                                   D.d, Nc, D.N, n0, (const bf16_t *)W.g_attn, D.eps, D.norm_free, D.alpha, nullptr, nullptr,
+                                   nullptr, nullptr, po);
+}
+
 // h = x + alpha Wo a;  u = gelu(W1 RMS(h));  y = h + alpha W2 u  for positions n0 .. n0 + Nc - 1 of every batch row
 static void block_gemms(const LayerDims &D, const Weights &W, const void *x, void *y, bf16_t *a_b, float *h_f, bf16_t *h_b,
                         bf16_t *u_b, int n0, int Nc, hipStream_t st)
 {
     const int d = D.d, F = D.F, M = D.B * Nc;
+    if (M <= kSmallM && d % 128 == 0 && F % 128 == 0) {   // few rows: the split-contraction kernel
+        const unsigned gs = (unsigned)((M + 63) / 64);
+        const PreOut none = {};
+        (void)blk_gemm_launch<PG_WO>(dim3(gs, (unsigned)(d / 64)), st, a_b, (const bf16_t *)W.Wo, M, d, d, Nc, D.N, n0, nullptr, D.eps,
+                                     D.norm_free, D.alpha, (const bf16_t *)x, nullptr, h_f, h_b, none);
+        (void)blk_gemm_launch<PG_W1>(dim3(gs, (unsigned)(F / 64)), st, h_b, (const bf16_t *)W.W1, M, F, d, Nc, D.N, n0,
+                                     (const bf16_t *)W.g_mlp, D.eps, D.norm_free, D.alpha, nullptr, nullptr, nullptr, u_b, none);
+        (void)blk_gemm_launch<PG_W2>(dim3(gs, (unsigned)(d / 64)), st, u_b, (const bf16_t *)W.W2, M, d, F, Nc, D.N, n0, nullptr, D.eps,
+                                     D.norm_free, D.alpha, nullptr, h_f, nullptr, (bf16_t *)y, none);
+        return;
+    }
     const unsigned gm = (unsigned)((M + 127) / 128);
     hipLaunchKernelGGL(par_gemm_kernel<PG_WO>, dim3(gm, (unsigned)((d + 127) / 128)), dim3(256), 0, st, a_b, (const bf16_t *)W.Wo, M, d,
                        d, Nc, D.N, n0, (const bf16_t *)nullptr, D.eps, D.norm_free, D.alpha, (const bf16_t *)x,
@@ -249,7 +464,8 @@ hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S,
                            D.p_min, D.log2_pmin, S.levels, S.slots, D.scale, D.alibi, t0);
         block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, t0, nr, st);
         // persistent pairs of the block from its outputs (rows t0.. of the pre-pass buffers are free again)
-        e = Launch<bf16_t>::prepass(D, Wp, S, y, B, nr, true, st, (size_t)N * d, t0);
+        if (B * nr <= kSmallM && d % 128 == 0) e = small_prepass(D, Wp, S, y, t0, nr, st);
+        else e = Launch<bf16_t>::prepass(D, Wp, S, y, B, nr, true, st, (size_t)N * d, t0);
         if (e != hipSuccess) return e;
         hipLaunchKernelGGL(par_export_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Kt, S.Ktf, (const bf16_t *)S.Vt,
                            (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, t0);
