@@ -144,6 +144,13 @@ def test_stack_wavefront_with_alibi(oracle, dtype, N, chunk, p_min):
         _run_elementwise(oracle, wl, 3, N, 4, emb_scale=EMB_UNIT, wavefront=True, chunk=chunk, alibi=8.0)
 
 
+def test_stack_wavefront_batch_tiles(oracle):
+    """18 sequences: the matrix-core products then run two batch tiles (16 + a ragged 2), in the stack engine and in the
+    decoding steps that follow."""
+    wl = gen.Workload("stack_b18_wf", "bf16", 18, 130, 256, 4, 1024, layers=2, vocab=500, decode_steps=2, seed=998)
+    _run_elementwise(oracle, wl, 18, 130, 2, emb_scale=EMB_UNIT, wavefront=True)
+
+
 def test_stack_wavefront_width_768(oracle):
     """Two layers of the 150M-like shape (d = 768, 12 heads, hidden 3072): the contraction shares of the matrix-core
     products are then 192 and 768 columns (step pairs outside the blocks of four), batch of 8."""
