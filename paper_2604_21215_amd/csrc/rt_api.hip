@@ -576,6 +576,14 @@ static rt_status stack_workspace(rt_ctx *c, int L, int chunk)
         c->stack_slab = nullptr;
         return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "scratch of the layer stack: %s", hipGetErrorString(e));
     }
+    // the engine reads whole 32-position groups of the transposed values and gives the positions not written yet the
+    // weight 0: they must hold finite numbers
+    e = hipMemsetAsync(c->stack_slab, 0, one * L, c->stream);
+    if (e != hipSuccess) {
+        (void)hipFree(c->stack_slab);
+        c->stack_slab = nullptr;
+        return fail(c, RT_ERR_HIP, "clearing the scratch of the layer stack: %s", hipGetErrorString(e));
+    }
     e = hipMalloc((void **)&c->stack_dev, sizeof(WaveLayer) * L);
     if (e != hipSuccess) {
         (void)hipGetLastError();

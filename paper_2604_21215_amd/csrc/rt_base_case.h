@@ -110,6 +110,91 @@ __device__ __forceinline__ float merge_body(const T *__restrict__ Q, const float
 }
 
 // =============================================================================================
+// The same merge for the layer-wavefront engine's bf16 path with p_min = 32, written for latency: one wavefront per
+// (b, h) is all the parallelism there is, so every load is issued before anything is computed - the query and the
+// temporary pair, up to kFastLevels stored partial states and the far state (absent ones read slot 0 and get weight
+// 0), the window keys (lanes 0..31: head rows, lanes 32..63: remainder rows of the same keys) and the window values
+// out of the transposed copy (lane = head dimension, 32 consecutive positions = 64 contiguous bytes) - and the
+// softmax over all terms is taken in one pass.  Same value as merge_body up to the order of the sums.
+// =============================================================================================
+constexpr int kFastLevels = 3;
+
+__device__ __forceinline__ float merge_window32_hp(const float *__restrict__ Qf, const float *__restrict__ Ktf,
+                                                   const bf16_t *__restrict__ Vt, const bf16_t *__restrict__ K,
+                                                   const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT,
+                                                   int vt_stride, const float *__restrict__ pm, const float *__restrict__ pl,
+                                                   const float *__restrict__ po, int BH, int H, int bh, int t, int levels,
+                                                   int slots, float scale, int far_rel, int log2_chunk, float alibi)
+{
+    const int lane = threadIdx.x & 63;
+    const size_t rs = (size_t)BH * kHeadDim;
+    const size_t qoff = (size_t)t * rs + (size_t)bh * kHeadDim + lane;
+    const float q = Qf[qoff], kt = Ktf[qoff], vt = bf16_to_f32(Vt[qoff]);
+    // stored states: levels 5 .. 5 + levels - 1 (bits of t), then the far state
+    float sm[kFastLevels + 1], sl[kFastLevels + 1], so[kFastLevels + 1];
+#pragma unroll
+    for (int lr = 0; lr <= kFastLevels; ++lr) {
+        const bool far = lr == kFastLevels;
+        const bool on = far ? (far_rel >= 0 && (t >> log2_chunk) > 0) : (lr < levels && ((t >> (lr + 5)) & 1));
+        const size_t idx = on ? (far ? partial_index(far_rel, t, slots, BH, bh) : partial_index(lr, partial_slot(lr + 5, t), slots, BH, bh))
+                              : (size_t)bh;
+        const float m_ = pm[idx], l_ = pl[idx], o_ = po[idx * kHeadDim + lane];
+        sm[lr] = on ? m_ : -INFINITY;
+        sl[lr] = on ? l_ : 0.f;
+        so[lr] = on ? o_ : 0.f;
+    }
+    // window: keys t - w .. t - 1, w = t mod 32
+    const int w = t & 31, j = lane & 31;
+    const size_t kbase = (size_t)(t - w + min(j, max(w - 1, 0))) * rs + (size_t)bh * kHeadDim;
+    const bf16_t *krow = (lane < 32 ? K : Klo) + kbase;
+    uint4 kr[8];
+#pragma unroll
+    for (int c = 0; c < 8; ++c) kr[c] = *reinterpret_cast<const uint4 *>(krow + 8 * c);
+    const bf16_t *vrow = VT + ((size_t)bh * kHeadDim + lane) * vt_stride + (t - w);
+    uint4 vr[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) vr[c] = *reinterpret_cast<const uint4 *>(vrow + 8 * c);
+
+    const float m0 = scale * wave_sum(q * kt);
+    float acc = 0.f;
+#pragma unroll
+    for (int c = 0; c < 8; ++c) {
+        const uint32_t u4[4] = {kr[c].x, kr[c].y, kr[c].z, kr[c].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            acc = fmaf(lane_bcast(q, 8 * c + 2 * e), __uint_as_float(u4[e] << 16), acc);
+            acc = fmaf(lane_bcast(q, 8 * c + 2 * e + 1), __uint_as_float(u4[e] & 0xFFFF0000u), acc);
+        }
+    }
+    acc += __shfl_xor(acc, 32, 64);   // head + remainder
+    const float slope = alibi_slope(alibi, bh % H, H);
+    const float logit = j < w ? fmaf(-slope, (float)(w - j), acc * scale) : -INFINITY;
+    float mx = fmaxf(m0, wave_max(logit));
+#pragma unroll
+    for (int lr = 0; lr <= kFastLevels; ++lr) mx = fmaxf(mx, sm[lr]);
+    const float e0 = expf(m0 - mx);
+    float l = e0, o = e0 * vt;
+#pragma unroll
+    for (int lr = 0; lr <= kFastLevels; ++lr) {
+        const float f = expf(sm[lr] - mx);   // exp(-inf) = 0 for absent states
+        l = fmaf(sl[lr], f, l);
+        o = fmaf(so[lr], f, o);
+    }
+    const float p = expf(logit - mx);        // 0 beyond the window; lanes 32..63 mirror lanes 0..31
+    l += 0.5f * wave_sum(p);
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+        const uint32_t u4[4] = {vr[c].x, vr[c].y, vr[c].z, vr[c].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o = fmaf(lane_bcast(p, 8 * c + 2 * e), __uint_as_float(u4[e] << 16), o);
+            o = fmaf(lane_bcast(p, 8 * c + 2 * e + 1), __uint_as_float(u4[e] & 0xFFFF0000u), o);
+        }
+    }
+    return o / l;
+}
+
+// =============================================================================================
 // Small-M matrix products of the base case:  out[b][o] = epilogue( sum_k W[o][k] * in[b][k] ),
 // b < Bn <= 8.  Bandwidth is the bound (every weight is used for at most 8 multiply-adds), so the
 // work is cut for memory parallelism: groups of KS wavefronts own 4 output rows each (a workgroup

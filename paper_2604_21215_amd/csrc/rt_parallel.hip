@@ -348,7 +348,7 @@ __global__ __launch_bounds__(64) void par_merge_kernel(const bf16_t *__restrict_
     a_out[((size_t)b * N + t) * ((size_t)H * kHeadDim) + h * kHeadDim + threadIdx.x] = f32_to_bf16(a);
 }
 
-constexpr int kSmallM = 2048;   // up to this many rows the split-contraction kernel is used
+constexpr int kSmallM = 2048;   // up to this many rows the split-contraction kernel is used (it is 1.4x slower at 16384 rows)
 
 // the pre-pass projection of positions n0 .. n0 + Nc - 1 of every batch row of `src` with the split-contraction kernel
 static hipError_t small_prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *src, int n0, int Nc, hipStream_t st)

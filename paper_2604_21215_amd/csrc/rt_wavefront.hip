@@ -43,6 +43,19 @@ __global__ __launch_bounds__(64) void wf_merge_kernel(const WaveLayer *__restric
     const int l = l_first + blockIdx.y, t = layer_pos(s, l, chunk);
     const WaveLayer &Y = layers[l];
     const int tree_levels = log2_chunk - log2_pmin;
+    if (HP && p_min == 32 && tree_levels <= kFastLevels) {
+        const int bh = blockIdx.x, lane = threadIdx.x;
+        const float a = merge_window32_hp(Y.S.Qf, Y.S.Ktf, (const bf16_t *)Y.S.Vt, (const bf16_t *)Y.K, Y.S.Klo, Y.S.VT, Y.S.vt_stride,
+                                          Y.S.pm, Y.S.pl, Y.S.po, BH, H, bh, t, tree_levels, Y.S.slots, scale, tree_levels, log2_chunk,
+                                          alibi);
+        const int b = bh / H, h = bh % H;
+        const size_t d = (size_t)H * kHeadDim;
+        Y.S.attn_cat[(size_t)b * d + h * kHeadDim + lane] = a;
+        const bf16_t hi = f32_to_bf16(a);
+        Y.S.op_a[(size_t)(2 * b) * d + h * kHeadDim + lane] = hi;
+        Y.S.op_a[(size_t)(2 * b + 1) * d + h * kHeadDim + lane] = f32_to_bf16(a - bf16_to_f32(hi));
+        return;
+    }
     merge_body<T, HP>((const T *)Y.S.Q, Y.S.Qf, (const T *)Y.S.Kt, Y.S.Ktf, (const T *)Y.S.Vt, (const T *)Y.K, Y.S.Klo,
                       (const T *)Y.V, Y.S.pm, Y.S.pl, Y.S.po, Y.S.attn_cat, BH, H, blockIdx.x, t, t, p_min, log2_pmin, tree_levels,
                       Y.S.slots, -1, scale, tree_levels, log2_chunk, HP ? Y.S.op_a : nullptr, alibi);
