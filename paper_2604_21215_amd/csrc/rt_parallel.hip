@@ -130,13 +130,14 @@ __global__ __launch_bounds__(256) void par_gemm_kernel(const bf16_t *__restrict_
 // ---------------------------------------------------------------------------------------------
 // The same products for FEW rows (a block of the blocked recurrence: M = block x B, tens to a few hundred rows),
 // where the kernel above is latency-bound: few workgroups, and every wavefront walks the whole contraction in
-// dependent steps.  Here a workgroup owns a 64 x 64 output tile and its four wavefronts split the contraction
-// (each the full tile over K / 4); a wavefront issues the loads of four steps (128 indices: 32 fragments) before
-// their 64 matrix instructions; the four partial tiles and the partial row statistics meet in LDS, then thread
-// (row, quarter) finishes 16 consecutive outputs of one row.
+// dependent steps.  Here a workgroup owns a 64 x 64 output tile and its NWV = 4 or 8 wavefronts split the contraction
+// (each the full tile over K / NWV); a wavefront issues the loads of four steps (128 indices: 32 fragments) before
+// their 64 matrix instructions; the partial tiles and the partial row statistics meet in LDS (four tile slots:
+// wavefronts 4..7 add theirs onto the slots of wavefronts 0..3), then thread (row, quarter) of the first 256
+// finishes 16 consecutive outputs of one row.
 //   PG_PRE: the pre-pass projection: W = [Wq; Wk; Wv] by column block (one head each), A rows RMS-normalised with
 //           `gain`, then qkRMS per head for q and k_tmp; rows go to Q / Kt / Vt (and fp32 Qf / Ktf) position-first.
-// grid (ceil(M / 64), Nn / 64), block 256, 69 KB of LDS.
+// grid (ceil(M / 64), Nn / 64), block 64 NWV, 70 KB of LDS.
 // ---------------------------------------------------------------------------------------------
 constexpr int PG_PRE = 3;
 constexpr int kSkLd = 68;   // row stride of a partial tile in floats
@@ -148,8 +149,8 @@ struct PreOut {   // PG_PRE only
     int H, Bc;
 };
 
-template <int EPI>
-__global__ __launch_bounds__(256) void blk_gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int M, int Nn,
+template <int EPI, int NWV>
+__global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int M, int Nn,
                                                        int K, int Nc, int N, int n0, const bf16_t *__restrict__ gain, float eps,
                                                        int norm_free, float alpha, const bf16_t *__restrict__ res_b,
                                                        const float *__restrict__ res_f, float *__restrict__ out_f,
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(256) void blk_gemm_kernel(const bf16_t *__restrict_
 {
     extern __shared__ __align__(16) unsigned char blk_smem[];
     float *part = reinterpret_cast<float *>(blk_smem);               // [4][64][kSkLd]
-    float *ssq_s = part + 4 * 64 * kSkLd;                             // [4][64]
+    float *ssq_s = part + 4 * 64 * kSkLd;                             // [8][64]
     const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
     const int m0 = blockIdx.x * 64, nb0 = blockIdx.y * 64;
@@ -166,7 +167,7 @@ __global__ __launch_bounds__(256) void blk_gemm_kernel(const bf16_t *__restrict_
         const int which = (int)blockIdx.y / po.H, h = (int)blockIdx.y % po.H;
         Wt = (which == 0 ? po.Wq : (which == 1 ? po.Wk : po.Wv)) + (size_t)h * kHeadDim * K - (size_t)nb0 * K;
     }
-    const int klen = K / 4, kbeg = kw * klen;
+    const int klen = K / NWV, kbeg = kw * klen;
     f32x4_t acc[4][4];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
@@ -235,12 +236,26 @@ __global__ __launch_bounds__(256) void blk_gemm_kernel(const bf16_t *__restrict_
             ssq[i] += __shfl_xor(ssq[i], 32, 64);
             if (g == 0) ssq_s[kw * 64 + i * 16 + l16] = ssq[i];
         }
+        if (kw < 4) {
 #pragma unroll
-        for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < 4; ++j)
 #pragma unroll
-            for (int r = 0; r < 4; ++r) part[(kw * 64 + i * 16 + 4 * g + r) * kSkLd + j * 16 + l16] = acc[i][j][r];
+                for (int r = 0; r < 4; ++r) part[(kw * 64 + i * 16 + 4 * g + r) * kSkLd + j * 16 + l16] = acc[i][j][r];
+        }
     }
     __syncthreads();
+    if (NWV == 8) {
+        if (kw >= 4) {   // onto the slot of wavefront kw - 4: every element has one writer
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) part[((kw - 4) * 64 + i * 16 + 4 * g + r) * kSkLd + j * 16 + l16] += acc[i][j][r];
+        }
+        __syncthreads();
+        if (kw >= 4) return;   // no barrier below
+    }
     // thread (row, quarter): 16 consecutive outputs of one row
     const int row = tid >> 2, qc = (tid & 3) * 16;
     const int m = m0 + row;
@@ -256,7 +271,11 @@ __global__ __launch_bounds__(256) void blk_gemm_kernel(const bf16_t *__restrict_
         v[4 * c4] = s4.x; v[4 * c4 + 1] = s4.y; v[4 * c4 + 2] = s4.z; v[4 * c4 + 3] = s4.w;
     }
     float rs = 1.f;
-    if (normed) rs = rsqrtf(((ssq_s[row] + ssq_s[64 + row]) + (ssq_s[128 + row] + ssq_s[192 + row])) / (float)K + eps);
+    if (normed) {
+        float tot = (ssq_s[row] + ssq_s[64 + row]) + (ssq_s[128 + row] + ssq_s[192 + row]);
+        if (NWV == 8) tot += (ssq_s[256 + row] + ssq_s[320 + row]) + (ssq_s[384 + row] + ssq_s[448 + row]);
+        rs = rsqrtf(tot / (float)K + eps);
+    }
     if (EPI == PG_PRE) {
         const int which = (int)blockIdx.y / po.H, h = (int)blockIdx.y % po.H;
         float ss = 0.f;
@@ -298,21 +317,32 @@ __global__ __launch_bounds__(256) void blk_gemm_kernel(const bf16_t *__restrict_
     }
 }
 
-constexpr size_t kBlkLds = (size_t)(4 * 64 * kSkLd + 4 * 64) * 4;
+constexpr size_t kBlkLds = (size_t)(4 * 64 * kSkLd + 8 * 64) * 4;
+template <int EPI, int NWV>
+static hipError_t blk_gemm_launch_n(dim3 grid, hipStream_t st, const bf16_t *A, const bf16_t *W, int M, int Nn, int K, int Nc, int N,
+                                    int n0, const bf16_t *gain, float eps, int norm_free, float alpha, const bf16_t *res_b,
+                                    const float *res_f, float *out_f, bf16_t *out_b, const PreOut &po)
+{
+    static bool raised = false;   // more than the default 64 KB of dynamic LDS
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute((const void *)blk_gemm_kernel<EPI, NWV>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)kBlkLds);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    hipLaunchKernelGGL((blk_gemm_kernel<EPI, NWV>), grid, dim3(64 * NWV), kBlkLds, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free,
+                       alpha, res_b, res_f, out_f, out_b, po);
+    return hipSuccess;
+}
+// eight wavefronts when every share of the contraction is still a whole number of 32-index steps
 template <int EPI>
 static hipError_t blk_gemm_launch(dim3 grid, hipStream_t st, const bf16_t *A, const bf16_t *W, int M, int Nn, int K, int Nc, int N,
                                   int n0, const bf16_t *gain, float eps, int norm_free, float alpha, const bf16_t *res_b,
                                   const float *res_f, float *out_f, bf16_t *out_b, const PreOut &po)
 {
-    static bool raised = false;   // more than the default 64 KB of dynamic LDS
-    if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void *)blk_gemm_kernel<EPI>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)kBlkLds);
-        if (e != hipSuccess) return e;
-        raised = true;
-    }
-    hipLaunchKernelGGL(blk_gemm_kernel<EPI>, grid, dim3(256), kBlkLds, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free, alpha,
-                       res_b, res_f, out_f, out_b, po);
-    return hipSuccess;
+    if (K % 256 == 0)
+        return blk_gemm_launch_n<EPI, 8>(grid, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free, alpha, res_b, res_f, out_f, out_b, po);
+    return blk_gemm_launch_n<EPI, 4>(grid, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free, alpha, res_b, res_f, out_f, out_b, po);
 }
 
 // K, V of positions t0 .. t0 + gridDim.y - 1 from the pre-pass outputs (rows (t, b, h)): the caller's cache rows, the bf16 remainder
