@@ -61,9 +61,17 @@ __device__ __forceinline__ float merge_body(const T *__restrict__ Q, const float
                 wgt = expf(pm[idx] - mx);
                 lw = wgt * pl[idx];
             }
-            for (int j = 0; j < cnt; ++j) {
-                l += lane_bcast(lw, j);
-                o = fmaf(lane_bcast(wgt, j), po[partial_index(0, s0 + j, slots, BH, bh) * kHeadDim + lane], o);
+            for (int j0 = 0; j0 < cnt; j0 += 8) {   // eight state rows in flight at a time
+                float pv[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    pv[e] = po[partial_index(0, s0 + min(j0 + e, cnt - 1), slots, BH, bh) * kHeadDim + lane];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const bool in = j0 + e < cnt;
+                    l += in ? lane_bcast(lw, min(j0 + e, 63)) : 0.f;
+                    o = fmaf(in ? lane_bcast(wgt, min(j0 + e, 63)) : 0.f, pv[e], o);
+                }
             }
         }
         m = mx;

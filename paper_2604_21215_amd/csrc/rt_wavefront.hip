@@ -737,11 +737,12 @@ static hipError_t step_mm_launch(const WaveLayer &Y, int n_out, const LayerDims 
     const int Bt = D.B < kMmBatch ? D.B : kMmBatch;
     const size_t base = (size_t)NW * 1024 + 256, xbytes = (size_t)2 * Bt * (K + 8) * 2;
     const dim3 grid((unsigned)(n_out / (16 * NW / KS)), 1, bt);
-    if (base + xbytes <= kMmMaxLds) {
+    constexpr size_t kStepMaxLds = 144 * 1024;   // one layer never has more than one workgroup per compute unit here
+    if (base + xbytes <= kStepMaxLds) {
         static bool raised = false;
         if (!raised) {
             hipError_t e = hipFuncSetAttribute((const void *)step_mm_kernel<EPI, KS, NW, true>,
-                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kMmMaxLds);
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)kStepMaxLds);
             if (e != hipSuccess) return e;
             raised = true;
         }
