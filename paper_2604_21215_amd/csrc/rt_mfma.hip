@@ -10,6 +10,7 @@
 #include "rt_mfma_device.h"
 #include "rt_cross_tile.h"
 #include "rt_prepass_device.h"
+#include "rt_gemm_tiled.h"
 
 namespace rt {
 
@@ -29,10 +30,90 @@ __global__ __launch_bounds__(256) void prepass_mfma_kernel(const bf16_t *__restr
                              blockIdx.x, blockIdx.y);
 }
 
+// The same projection with both operands staged in LDS (tiled_mainloop), for many rows and d a multiple of 128: a
+// wavefront's 64 columns are one head of q, k_tmp or v_tmp, so the qkRMS of a row is a sum over its two column
+// tiles and the 32 lanes of its half of the wavefront.  grid (ceil(M / 256), 3 d / 128), block 256.
+__global__ __launch_bounds__(256) void prepass_tiled_kernel(const bf16_t *__restrict__ x, const float *__restrict__ rinv,
+                                                            const bf16_t *__restrict__ Wq, const bf16_t *__restrict__ Wk,
+                                                            const bf16_t *__restrict__ Wv, const bf16_t *__restrict__ g_attn,
+                                                            const bf16_t *__restrict__ g_q, const bf16_t *__restrict__ g_k,
+                                                            bf16_t *__restrict__ Q, bf16_t *__restrict__ Kt,
+                                                            bf16_t *__restrict__ Vt, float *__restrict__ Qf,
+                                                            float *__restrict__ Ktf, int Bc, int Nc, size_t x_bstride,
+                                                            int n0, int d, int H, float eps, int norm_free)
+{
+    __shared__ __align__(16) bf16_t As[kGtRows * kGtLd];
+    __shared__ __align__(16) bf16_t Bs[kGtCols * kGtLd];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int M = Bc * Nc;
+    const int m0 = blockIdx.x * kGtRows;
+    const int c0 = blockIdx.y * kGtCols;          // first of the block's columns of [q | k_tmp | v_tmp]
+    const int bw = c0 / d;                         // d is a multiple of 128: a block lies within one of the three
+    const bf16_t *Wb = (bw == 0 ? Wq : (bw == 1 ? Wk : Wv)) + (size_t)(c0 - bw * d) * d;
+    const int prow = tid >> 3, pc = tid & 7;
+    const bf16_t *ga[8], *gb[4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int mr = min(m0 + prow + 32 * i, M - 1);
+        ga[i] = x + (size_t)(mr / Nc) * x_bstride + (size_t)(n0 + mr % Nc) * d + pc * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) gb[i] = Wb + (size_t)(prow + 32 * i) * d + pc * 8;
+
+    f32x16_t acc[4][2];
+    tiled_mainloop(ga, gb, (g_attn != nullptr && !norm_free) ? g_attn : nullptr, d, As, Bs, acc);
+
+    const int hcol = c0 - bw * d + wn * 64;        // first column of this wavefront's head within its output
+    const bool normed = bw < 2 && !norm_free;
+    const bf16_t *gn = bw == 0 ? g_q : g_k;
+    bf16_t *dst = bw == 0 ? Q : (bw == 1 ? Kt : Vt);
+    float *dstf = bw == 0 ? Qf : (bw == 1 ? Ktf : nullptr);   // optional unrounded copies of q and k_tmp
+    float gc[2] = {1.f, 1.f};
+    if (normed && gn) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) gc[nt] = bf16_to_f32(gn[hcol + nt * 32 + l32]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = m0 + wm * 128 + mt * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
+            const float rs = norm_free ? 1.f : rinv[min(m, M - 1)];
+            const float v0 = acc[mt][0][i] * rs, v1 = acc[mt][1][i] * rs;
+            float sc = 1.f;
+            if (normed) {
+                float ss = fmaf(v0, v0, v1 * v1);
+#pragma unroll
+                for (int o = 16; o > 0; o >>= 1) ss += __shfl_xor(ss, o, 64);   // the 32 lanes that share hi
+                sc = rsqrtf(ss / (float)kHeadDim + eps);
+            }
+            if (m < M) {
+                const int b = m / Nc, n = n0 + m % Nc;
+                const size_t oo = ((size_t)n * Bc + b) * d + hcol + l32;
+                const float o0 = v0 * sc * gc[0], o1 = v1 * sc * gc[1];
+                dst[oo] = f32_to_bf16(o0);
+                dst[oo + 32] = f32_to_bf16(o1);
+                if (dstf) { dstf[oo] = o0; dstf[oo + 32] = o1; }
+            }
+        }
+    }
+}
+
+constexpr int kTiledMinRows = 2048;   // below this the untiled kernel's smaller block tiles fill the chip better
+
 hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
                                size_t x_bstride, int n0, hipStream_t st)
 {
     const int M = Bc * Nc;
+    if (M >= kTiledMinRows && D.d % 128 == 0) {
+        hipLaunchKernelGGL(prepass_tiled_kernel, dim3((M + kGtRows - 1) / kGtRows, 3 * D.d / kGtCols), dim3(256), 0, st,
+                           (const bf16_t *)x, S.rinv, (const bf16_t *)W.Wq, (const bf16_t *)W.Wk, (const bf16_t *)W.Wv,
+                           (const bf16_t *)W.g_attn, (const bf16_t *)W.g_q, (const bf16_t *)W.g_k, (bf16_t *)S.Q, (bf16_t *)S.Kt,
+                           (bf16_t *)S.Vt, S.Qf, S.Ktf, Bc, Nc, x_bstride, n0, D.d, D.H, D.eps, D.norm_free);
+        return hipGetLastError();
+    }
     hipLaunchKernelGGL(prepass_mfma_kernel, dim3((M + 127) / 128, (3 * D.H + 1) / 2), dim3(256), 0, st, (const bf16_t *)x,
                        S.rinv, (const bf16_t *)W.Wq, (const bf16_t *)W.Wk, (const bf16_t *)W.Wv, (const bf16_t *)W.g_attn,
                        (const bf16_t *)W.g_q, (const bf16_t *)W.g_k, (bf16_t *)S.Q, (bf16_t *)S.Kt, (bf16_t *)S.Vt, S.Qf, S.Ktf,

@@ -13,6 +13,7 @@
 //   h = x + alpha Wo a;  u = gelu(W1 RMS(h));  y = h + alpha W2 u   as three GEMMs with fused epilogues.
 #include "rt_base_case.h"
 #include "rt_mfma_device.h"
+#include "rt_gemm_tiled.h"
 
 namespace rt {
 
@@ -125,6 +126,89 @@ __global__ __launch_bounds__(256) void par_gemm_kernel(const bf16_t *__restrict_
             }
         }
     }
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same products with both operands staged in LDS (tiled_mainloop), for many rows and Nn a multiple of 128, K of 64.
+//   PG_WO: h = res_b + alpha C -> out_f (fp32) and out_b = bf16(h * gain): the A operand of the next product with its
+//          RMS gain already applied (gain may be null)
+//   PG_W1: out_b = gelu(rinv_m C); rinv_m = 1/rms of row m of h (par_rinv_kernel on the fp32 copy)
+//   PG_W2: out_b = res_f + alpha C
+// grid (ceil(M / 256), Nn / 128), block 256.
+// ---------------------------------------------------------------------------------------------
+template <int EPI>
+__global__ __launch_bounds__(256) void tiled_gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int M, int Nn,
+                                                         int K, int Nc, int N, int n0, const bf16_t *__restrict__ gain,
+                                                         const float *__restrict__ rinv, int norm_free, float alpha,
+                                                         const bf16_t *__restrict__ res_b, const float *__restrict__ res_f,
+                                                         float *__restrict__ out_f, bf16_t *__restrict__ out_b)
+{
+    __shared__ __align__(16) bf16_t As[kGtRows * kGtLd];
+    __shared__ __align__(16) bf16_t Bs[kGtCols * kGtLd];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int m0 = blockIdx.x * kGtRows, nb0 = blockIdx.y * kGtCols;
+    const int prow = tid >> 3, pc = tid & 7;
+    const bf16_t *ga[8], *gb[4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const int mr = min(m0 + prow + 32 * i, M - 1);
+        ga[i] = A + ((size_t)(mr / Nc) * N + n0 + mr % Nc) * K + pc * 8;
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) gb[i] = W + (size_t)(nb0 + prow + 32 * i) * K + pc * 8;
+
+    f32x16_t acc[4][2];
+    tiled_mainloop(ga, gb, nullptr, K, As, Bs, acc);
+
+    float gcol[2] = {1.f, 1.f};
+    if (EPI == PG_WO && gain != nullptr && !norm_free) {
+#pragma unroll
+        for (int nt = 0; nt < 2; ++nt) gcol[nt] = bf16_to_f32(gain[nb0 + wn * 64 + nt * 32 + l32]);
+    }
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt) {
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = m0 + wm * 128 + mt * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
+            if (m < M) {
+                const size_t row = (size_t)(m / Nc) * N + n0 + m % Nc;
+                const float rs = (EPI == PG_W1 && !norm_free) ? rinv[m] : 1.f;
+#pragma unroll
+                for (int nt = 0; nt < 2; ++nt) {
+                    const size_t o = row * Nn + nb0 + wn * 64 + nt * 32 + l32;
+                    const float c = acc[mt][nt][i];
+                    if (EPI == PG_WO) {
+                        const float h = bf16_to_f32(res_b[o]) + alpha * c;
+                        out_f[o] = h;
+                        out_b[o] = f32_to_bf16(h * gcol[nt]);
+                    } else if (EPI == PG_W1) {
+                        out_b[o] = f32_to_bf16(gelu_bf16_out(c * rs));
+                    } else {
+                        out_b[o] = f32_to_bf16(res_f[o] + alpha * c);
+                    }
+                }
+            }
+        }
+    }
+}
+
+// 1 / rms of rows n0 .. n0 + Nc - 1 of every batch row of a [B][N][d] fp32 tensor, rinv[m] for m = b Nc + n.
+// grid ceil(M / 4), block 256: one wavefront per row.  d is a multiple of 4.
+__global__ __launch_bounds__(256) void par_rinv_kernel(const float *__restrict__ x, float *__restrict__ rinv, int M, int Nc, int N,
+                                                       int n0, int d, float eps)
+{
+    const int lane = threadIdx.x & 63, m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (m >= M) return;
+    const float *xr = x + ((size_t)(m / Nc) * N + n0 + m % Nc) * d;
+    float ss = 0.f;
+    for (int k = lane * 4; k < d; k += 256) {
+        const float4 v = *reinterpret_cast<const float4 *>(xr + k);
+        ss = fmaf(v.x, v.x, fmaf(v.y, v.y, fmaf(v.z, v.z, fmaf(v.w, v.w, ss))));
+    }
+    ss = wave_sum(ss);
+    if (lane == 0) rinv[m] = rsqrtf(ss / (float)d + eps);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -396,7 +480,7 @@ static hipError_t small_prepass(const LayerDims &D, const Weights &W, const Scra
 
 // h = x + alpha Wo a;  u = gelu(W1 RMS(h));  y = h + alpha W2 u  for positions n0 .. n0 + Nc - 1 of every batch row
 static void block_gemms(const LayerDims &D, const Weights &W, const void *x, void *y, bf16_t *a_b, float *h_f, bf16_t *h_b,
-                        bf16_t *u_b, int n0, int Nc, hipStream_t st)
+                        bf16_t *u_b, float *rinv, int n0, int Nc, hipStream_t st)
 {
     const int d = D.d, F = D.F, M = D.B * Nc;
     if (M <= kSmallM && d % 128 == 0 && F % 128 == 0) {   // few rows: the split-contraction kernel
@@ -408,6 +492,21 @@ static void block_gemms(const LayerDims &D, const Weights &W, const void *x, voi
                                      (const bf16_t *)W.g_mlp, D.eps, D.norm_free, D.alpha, nullptr, nullptr, nullptr, u_b, none);
         (void)blk_gemm_launch<PG_W2>(dim3(gs, (unsigned)(d / 64)), st, u_b, (const bf16_t *)W.W2, M, d, F, Nc, D.N, n0, nullptr, D.eps,
                                      D.norm_free, D.alpha, nullptr, h_f, nullptr, (bf16_t *)y, none);
+        return;
+    }
+    if (d % 128 == 0 && F % 128 == 0) {   // both operands through LDS
+        const unsigned gt = (unsigned)((M + 255) / 256);
+        hipLaunchKernelGGL(tiled_gemm_kernel<PG_WO>, dim3(gt, (unsigned)(d / 128)), dim3(256), 0, st, a_b, (const bf16_t *)W.Wo, M, d, d,
+                           Nc, D.N, n0, (const bf16_t *)W.g_mlp, (const float *)nullptr, D.norm_free, D.alpha, (const bf16_t *)x,
+                           (const float *)nullptr, h_f, h_b);
+        if (!D.norm_free)
+            hipLaunchKernelGGL(par_rinv_kernel, dim3((unsigned)((M + 3) / 4)), dim3(256), 0, st, h_f, rinv, M, Nc, D.N, n0, d, D.eps);
+        hipLaunchKernelGGL(tiled_gemm_kernel<PG_W1>, dim3(gt, (unsigned)(F / 128)), dim3(256), 0, st, h_b, (const bf16_t *)W.W1, M, F, d,
+                           Nc, D.N, n0, (const bf16_t *)nullptr, rinv, D.norm_free, D.alpha, (const bf16_t *)nullptr,
+                           (const float *)nullptr, (float *)nullptr, u_b);
+        hipLaunchKernelGGL(tiled_gemm_kernel<PG_W2>, dim3(gt, (unsigned)(d / 128)), dim3(256), 0, st, u_b, (const bf16_t *)W.W2, M, d, F,
+                           Nc, D.N, n0, (const bf16_t *)nullptr, (const float *)nullptr, D.norm_free, D.alpha,
+                           (const bf16_t *)nullptr, h_f, (float *)nullptr, (bf16_t *)y);
         return;
     }
     const unsigned gm = (unsigned)((M + 127) / 128);
@@ -460,7 +559,7 @@ hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S
     hipLaunchKernelGGL(par_merge_kernel, dim3(BH, N), dim3(64), 0, st, (const bf16_t *)S.Q, S.Qf, (const bf16_t *)S.Kt, S.Ktf,
                        (const bf16_t *)S.Vt, (const bf16_t *)K, S.Klo, (const bf16_t *)V, S.pm, S.pl, S.po, a_b, BH, D.H, N, D.p_min,
                        D.log2_pmin, S.levels, S.slots, D.scale, D.alibi, 0);
-    block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, 0, N, st);
+    block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, S.rinv, 0, N, st);
     return hipGetLastError();
 }
 
@@ -492,7 +591,7 @@ hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S,
         hipLaunchKernelGGL(par_merge_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Q, S.Qf, (const bf16_t *)S.Kt, S.Ktf,
                            (const bf16_t *)S.Vt, (const bf16_t *)K, S.Klo, (const bf16_t *)V, S.pm, S.pl, S.po, a_b, BH, D.H, N,
                            D.p_min, D.log2_pmin, S.levels, S.slots, D.scale, D.alibi, t0);
-        block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, t0, nr, st);
+        block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, S.rinv, t0, nr, st);
         // persistent pairs of the block from its outputs (rows t0.. of the pre-pass buffers are free again)
         if (B * nr <= kSmallM && d % 128 == 0) e = small_prepass(D, Wp, S, y, t0, nr, st);
         else e = Launch<bf16_t>::prepass(D, Wp, S, y, B, nr, true, st, (size_t)N * d, t0);

@@ -36,6 +36,7 @@ def _check(name, x64, ref, got, tol):
     (3, 333, 320, 5, 1280, 8.0, "random", 0.7, 0.5),       # odd head count, ragged N, bias, gains
     (2, 700, 1024, 16, 4096, 0.0, "unit", 1.0, 1.0),       # blocks up to 512 keys, several query workgroups
     (1, 33, 256, 4, 1024, 0.0, "unit", 1.0, 1.0),
+    (5, 600, 256, 4, 1024, 0.0, "random", 0.7, 1.0),       # 3000 rows: the LDS-tiled products, ragged last row tile
 ])
 def test_recompute_from_exact_output(oracle, B, N, d, H, F, alibi, gains, alpha, scale):
     """z = the oracle's output (rounded to bf16): the recompute must reproduce the oracle's y, K, V."""
@@ -81,7 +82,8 @@ def test_recompute_of_an_arbitrary_z_and_of_the_prefill_output(oracle):
         ctx.rt_destroy()
 
 
-@pytest.mark.parametrize("B,N,d,H,F,alibi", [(2, 200, 256, 4, 1024, 0.0), (3, 333, 320, 5, 1280, 8.0), (2, 600, 1024, 16, 4096, 0.0)])
+@pytest.mark.parametrize("B,N,d,H,F,alibi", [(2, 200, 256, 4, 1024, 0.0), (3, 333, 320, 5, 1280, 8.0), (2, 600, 1024, 16, 4096, 0.0),
+                                               (6, 450, 384, 6, 1536, 0.0)])   # 2700 rows: the LDS-tiled products
 def test_transformer_layer(oracle, B, N, d, H, F, alibi):
     li = gen.make_custom(24, "bf16", B, N, d, H, F, gains="random")
     x64 = li.x.astype(np.float64)
