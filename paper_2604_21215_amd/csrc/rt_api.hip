@@ -252,6 +252,15 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
         return e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP;
     }
     layout_scratch(S, (char *)c->slab, Bm, Nm, d, F, H, E, mfma, levels, slots);
+    if (S.VT) {   // tiles read whole 64-position chunks of the transposed values: positions never written must hold finite values
+        e = hipMemset(S.VT, 0, Bm * H * kHeadDim * (size_t)S.vt_stride * 2);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            (void)hipFree(c->slab);
+            delete c;
+            return RT_ERR_HIP;
+        }
+    }
 
     rt_status ps = persistent_create(c->persist, c->cfg, D);
     if (ps != RT_OK && (cfg->flags & RT_FLAG_ENGINE_PERSISTENT)) {

@@ -445,6 +445,55 @@ __global__ __launch_bounds__(64) void par_export_kernel(const bf16_t *__restrict
     VT[((size_t)bh * kHeadDim + lane) * vt_stride + t] = v;
 }
 
+// The same export for all N positions, 64 positions of one (b, h) per workgroup: every global access is a run of
+// 32 bytes or more (the kernel above writes V^T two bytes at a time); the values are transposed through LDS.
+// V^T columns N .. 64 ceil(N / 64) - 1 are written as zeros.  grid (B*H, ceil(N / 64)), block 256.
+__global__ __launch_bounds__(256) void par_export_tile_kernel(const bf16_t *__restrict__ Ks, const float *__restrict__ Kf,
+                                                              const bf16_t *__restrict__ Vs, bf16_t *__restrict__ K,
+                                                              bf16_t *__restrict__ V, bf16_t *__restrict__ Klo,
+                                                              bf16_t *__restrict__ VT, int vt_stride, int BH, int N)
+{
+    constexpr int kLd = 72;
+    __shared__ __align__(16) bf16_t tile[64 * kLd];
+    const int tid = threadIdx.x, r = tid >> 2, c = tid & 3, bh = blockIdx.x, t0 = blockIdx.y * 64;
+    const int t = t0 + r;
+    uint4 v0 = make_uint4(0u, 0u, 0u, 0u), v1 = v0;
+    if (t < N) {
+        const size_t off = ((size_t)t * BH + bh) * kHeadDim + 16 * c;
+        const uint4 k0 = *reinterpret_cast<const uint4 *>(Ks + off), k1 = *reinterpret_cast<const uint4 *>(Ks + off + 8);
+        v0 = *reinterpret_cast<const uint4 *>(Vs + off);
+        v1 = *reinterpret_cast<const uint4 *>(Vs + off + 8);
+        float kf[16];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float4 f = *reinterpret_cast<const float4 *>(Kf + off + 4 * j);
+            kf[4 * j] = f.x; kf[4 * j + 1] = f.y; kf[4 * j + 2] = f.z; kf[4 * j + 3] = f.w;
+        }
+        const uint32_t kw[8] = {k0.x, k0.y, k0.z, k0.w, k1.x, k1.y, k1.z, k1.w};
+        uint32_t lo[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            lo[j] = pack_bf16(kf[2 * j] - __uint_as_float(kw[j] << 16), kf[2 * j + 1] - __uint_as_float(kw[j] & 0xFFFF0000u));
+        *reinterpret_cast<uint4 *>(K + off) = k0;
+        *reinterpret_cast<uint4 *>(K + off + 8) = k1;
+        *reinterpret_cast<uint4 *>(V + off) = v0;
+        *reinterpret_cast<uint4 *>(V + off + 8) = v1;
+        *reinterpret_cast<uint4 *>(Klo + off) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
+        *reinterpret_cast<uint4 *>(Klo + off + 8) = make_uint4(lo[4], lo[5], lo[6], lo[7]);
+    }
+    *reinterpret_cast<uint4 *>(tile + r * kLd + 16 * c) = v0;
+    *reinterpret_cast<uint4 *>(tile + r * kLd + 16 * c + 8) = v1;
+    __syncthreads();
+    // row r of V^T (head dimension r), positions t0 + 16 c .. + 15
+    uint32_t w[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+        w[j] = (uint32_t)tile[(16 * c + 2 * j) * kLd + r] | ((uint32_t)tile[(16 * c + 2 * j + 1) * kLd + r] << 16);
+    bf16_t *dst = VT + ((size_t)bh * kHeadDim + r) * vt_stride + t0 + 16 * c;
+    *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+    *reinterpret_cast<uint4 *>(dst + 8) = make_uint4(w[4], w[5], w[6], w[7]);
+}
+
 // a_t of positions t0 .. t0 + gridDim.y - 1 (merge_body) as bf16 rows of [B][N][d].  grid (B*H, positions), block 64.
 __global__ __launch_bounds__(64) void par_merge_kernel(const bf16_t *__restrict__ Q, const float *__restrict__ Qf,
                                                        const bf16_t *__restrict__ Kt, const float *__restrict__ Ktf,
@@ -460,6 +509,224 @@ __global__ __launch_bounds__(64) void par_merge_kernel(const bf16_t *__restrict_
                                              levels, slots, -1, scale, -1, 0, nullptr, alibi);
     const int b = bh / H, h = bh % H;
     a_out[((size_t)b * N + t) * ((size_t)H * kHeadDim) + h * kHeadDim + threadIdx.x] = f32_to_bf16(a);
+}
+
+// ---------------------------------------------------------------------------------------------
+// Attention of ALL positions in one launch when every key-value pair is known in advance (Sec. 6.1 recompute,
+// Sec. 2.1 Transformer layer): query i against the cache rows j < i plus its own temporary pair, as one masked
+// flash-style pass instead of Algorithm 1's blocks (no partial states to write and merge).  The inner loop is the one
+// of cross_tile_wg (K, K remainder and V^T chunks of 64 keys staged in LDS and shared by four wavefronts of 32
+// queries; high-precision logits: three products per tile); additionally
+//   - the state of a query starts from its temporary pair (m = its logit from the unrounded q and k_tmp, l = 1,
+//     o = v_tmp), so that every query has a finite reference before the first key,
+//   - chunks that reach a wavefront's own positions mask keys j >= i with -inf,
+//   - with ALIBI the bias slope (j - i) is applied per (key, query),
+//   - the result is normalised and written as bf16 rows of a [B][N][d].
+// One workgroup per (128 queries, b, h).  grid ceil(N / 128) * B*H, block 256, LDS 2 x 27 KB.  When B*H is a multiple of
+// 8 the workgroups are numbered so that all query tiles of one (b, h) run on the same XCD one after the other (their
+// keys and values then come out of that XCD's L2), the longest first.
+// ---------------------------------------------------------------------------------------------
+template <bool ALIBI>
+__global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict__ Qf, const float *__restrict__ Ktf,
+                                                        const bf16_t *__restrict__ Vt, const bf16_t *__restrict__ K,
+                                                        const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT,
+                                                        int vt_stride, bf16_t *__restrict__ a_out, int BH, int H, int N,
+                                                        int ntiles, float scale, float alibi)
+{
+    extern __shared__ __align__(16) unsigned char flash_lds[];
+    constexpr int T = 256, PPT = 2;
+    constexpr int TILE = kKC * kTileLd, BUF = 3 * TILE;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l32 = lane & 31, hi = lane >> 5;
+    int bh, qt;
+    {
+        const int L = blockIdx.x;
+        if (BH % 8 == 0) {
+            const int xcd = L & 7, idx = L >> 3;
+            bh = xcd + 8 * (idx / ntiles);
+            qt = ntiles - 1 - idx % ntiles;
+        } else {
+            bh = L / ntiles;
+            qt = ntiles - 1 - L % ntiles;
+        }
+    }
+    const int q0w = qt * 128 + 32 * wave;          // first query of this wavefront
+    const bool active = q0w < N;                    // wave-uniform
+    const int qpos = q0w + l32;                     // this lane's query (its partner lane hi ^ 1 holds the same one)
+    const int qi = min(qpos, N - 1);
+    const size_t rs = (size_t)BH * kHeadDim;
+    bf16_t *tiles = reinterpret_cast<bf16_t *>(flash_lds);
+    const float c2 = scale * kLog2e;
+    const float s2 = ALIBI ? alibi_slope(alibi, bh % H, H) * kLog2e : 0.f;
+
+    // ---- queries as B fragments (head + remainder), and the temporary pair's logit
+    uint4 bq[4], bql[4];
+    float m2, lsum = hi == 0 ? 1.f : 0.f;
+    f32x16_t O[2];
+    {
+        const size_t qo = (size_t)qi * rs + (size_t)bh * kHeadDim;
+        float dot = 0.f;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) {
+            float f[8], r[8], kf[8];
+            load8(Qf + qo + 8 * hi + ks * 16, f);
+            load8(Ktf + qo + 8 * hi + ks * 16, kf);
+            uint32_t h2[4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                h2[e] = cvt_pk_bf16(f[2 * e], f[2 * e + 1]);
+                r[2 * e] = f[2 * e] - __uint_as_float(h2[e] << 16);
+                r[2 * e + 1] = f[2 * e + 1] - __uint_as_float(h2[e] & 0xFFFF0000u);
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot = fmaf(f[e], kf[e], dot);
+            bq[ks] = make_uint4(h2[0], h2[1], h2[2], h2[3]);
+            bql[ks] = make_uint4(cvt_pk_bf16(r[0], r[1]), cvt_pk_bf16(r[2], r[3]), cvt_pk_bf16(r[4], r[5]), cvt_pk_bf16(r[6], r[7]));
+        }
+        dot += __shfl_xor(dot, 32, 64);
+        m2 = dot * c2;                              // distance 0: no bias
+        // register i of tile dt is head dimension 32dt + 8(i/4) + 4hi + i%4
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const uint2 v = *reinterpret_cast<const uint2 *>(Vt + qo + 32 * dt + 8 * j + 4 * hi);
+                O[dt][4 * j] = __uint_as_float(v.x << 16);
+                O[dt][4 * j + 1] = __uint_as_float(v.x & 0xFFFF0000u);
+                O[dt][4 * j + 2] = __uint_as_float(v.y << 16);
+                O[dt][4 * j + 3] = __uint_as_float(v.y & 0xFFFF0000u);
+            }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- staging of one chunk: thread -> 16-byte piece, 8 consecutive threads cover one row; key rows past the last
+    // position are read from the last one (they are masked), V^T columns up to vt_stride exist and hold finite values
+    u32x4_t rk[PPT], rl[PPT], rv[PPT];
+    const int prow = tid >> 3, pc16 = tid & 7;
+    const bf16_t *gv = VT + ((size_t)bh * kHeadDim + prow) * vt_stride + pc16 * 8;
+    const int lds_off = prow * kTileLd + pc16 * 8, lds_off_v = prow * kVLd + pc16 * 8;
+#define RT_FL_FETCH(kc)                                                                                               \
+    _Pragma("unroll") for (int i = 0; i < PPT; ++i)                                                                   \
+    {                                                                                                                 \
+        const size_t ro = (size_t)min((kc) + prow + i * (T / 8), N - 1) * rs + (size_t)bh * kHeadDim + pc16 * 8;      \
+        rk[i] = *reinterpret_cast<const u32x4_t *>(K + ro);                                                           \
+        rl[i] = *reinterpret_cast<const u32x4_t *>(Klo + ro);                                                         \
+        rv[i] = *reinterpret_cast<const u32x4_t *>(gv + (size_t)(i * (T / 8)) * vt_stride + (kc));                    \
+    }
+#define RT_FL_STAGE(buf)                                                                                              \
+    _Pragma("unroll") for (int i = 0; i < PPT; ++i)                                                                   \
+    {                                                                                                                 \
+        bf16_t *dst = tiles + (size_t)(buf) * BUF + lds_off + i * (T / 8) * kTileLd;                                  \
+        *reinterpret_cast<u32x4_t *>(dst) = rk[i];                                                                    \
+        bf16_t *dv = tiles + (size_t)(buf) * BUF + TILE + lds_off_v + i * (T / 8) * kVLd;                             \
+        *reinterpret_cast<uint2 *>(dv) = make_uint2(rv[i][0], rv[i][1]);                                              \
+        *reinterpret_cast<uint2 *>(dv + 4) = make_uint2(rv[i][2], rv[i][3]);                                          \
+        *reinterpret_cast<u32x4_t *>(dst + 2 * TILE) = rl[i];                                                         \
+    }
+
+    const int kend = min(qt * 128 + 128, N);        // keys 0 .. kend - 2 are needed by some query of the tile
+    const int nchunks = (kend - 1 + kKC - 1) / kKC; // workgroup-uniform; 0 for the single position 0
+    if (nchunks > 0) {
+        RT_FL_FETCH(0)
+        RT_FL_STAGE(0)
+    }
+    __syncthreads();
+    for (int c = 0; c < nchunks; ++c) {
+        const int cur = c & 1;
+        if (c + 1 < nchunks) { RT_FL_FETCH((c + 1) * kKC) }
+        if (active && c * kKC < q0w + 31) {          // some key of the chunk precedes some query of the wavefront
+            const bf16_t *Ks = tiles + (size_t)cur * BUF, *Vs = Ks + TILE;
+            f32x16_t S[2];
+#pragma unroll
+            for (int kt = 0; kt < 2; ++kt) {
+                const bf16_t *krow = Ks + (kt * 32 + l32) * kTileLd + 8 * hi;
+                uint4 ka[4];
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) ka[ks] = *reinterpret_cast<const uint4 *>(krow + ks * 16);
+                f32x16_t acc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks)      // small terms first
+                    acc = mfma32u(*reinterpret_cast<const uint4 *>(krow + 2 * TILE + ks * 16), bq[ks], acc);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bql[ks], acc);
+#pragma unroll
+                for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bq[ks], acc);
+                S[kt] = acc;
+            }
+            // register i of tile kt is key 64c + 32kt + 8(i/4) + 4hi + i%4; from here on S is in log2 units
+            {
+                const float base = ALIBI ? s2 * (float)(c * kKC + 4 * hi - qpos) : 0.f;
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        S[kt][i] = ALIBI ? fmaf(S[kt][i], c2, fmaf(s2, (float)(32 * kt + 8 * (i / 4) + (i % 4)), base)) : S[kt][i] * c2;
+            }
+            if (c * kKC + kKC > q0w) {               // the chunk reaches this wavefront's own positions: keys j >= i out
+                const int lim = qpos - (c * kKC + 4 * hi);   // valid iff 32kt + 8(i/4) + i%4 < lim
+#pragma unroll
+                for (int kt = 0; kt < 2; ++kt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i)
+                        if (32 * kt + 8 * (i / 4) + (i % 4) >= lim) S[kt][i] = -INFINITY;
+            }
+            float lmax = fmaxf(fmaxf(S[0][0], S[0][1]), S[0][2]);
+#pragma unroll
+            for (int i = 3; i < 15; i += 2) lmax = fmaxf(fmaxf(lmax, S[0][i]), S[0][i + 1]);
+            lmax = fmaxf(fmaxf(lmax, S[0][15]), S[1][0]);
+#pragma unroll
+            for (int i = 1; i < 15; i += 2) lmax = fmaxf(fmaxf(lmax, S[1][i]), S[1][i + 1]);
+            lmax = fmaxf(lmax, S[1][15]);
+            const bool over = lmax > m2 + kSlack;
+            if (__any(over)) {
+                const float mx = fmaxf(lmax, __shfl_xor(lmax, 32, 64));
+                const float m_new = fmaxf(m2, mx);
+                const float resc = __builtin_amdgcn_exp2f(m2 - m_new);   // m2 is finite from the start
+                m2 = m_new;
+                lsum *= resc;
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) O[dt] *= resc;
+            }
+            uint4 bp[4];
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+                float pw[8];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pw[e] = __builtin_amdgcn_exp2f(S[s4 >> 1][8 * (s4 & 1) + e] - m2);
+                bp[s4] = make_uint4(cvt_pk_bf16(pw[0], pw[1]), cvt_pk_bf16(pw[2], pw[3]), cvt_pk_bf16(pw[4], pw[5]), cvt_pk_bf16(pw[6], pw[7]));
+                lsum += ((pw[0] + pw[1]) + (pw[2] + pw[3])) + ((pw[4] + pw[5]) + (pw[6] + pw[7]));
+            }
+#pragma unroll
+            for (int s4 = 0; s4 < 4; ++s4) {
+#pragma unroll
+                for (int dt = 0; dt < 2; ++dt) {
+                    const bf16_t *vrow = Vs + (dt * 32 + l32) * kVLd + s4 * 16 + 4 * hi;
+                    const uint2 v0 = *reinterpret_cast<const uint2 *>(vrow), v1 = *reinterpret_cast<const uint2 *>(vrow + 8);
+                    O[dt] = mfma32u(make_uint4(v0.x, v0.y, v1.x, v1.y), bp[s4], O[dt]);
+                }
+            }
+        }
+        if (c + 1 < nchunks) {
+            RT_FL_STAGE(cur ^ 1)
+            __syncthreads();
+        }
+    }
+#undef RT_FL_FETCH
+#undef RT_FL_STAGE
+
+    if (active && qpos < N) {
+        const float inv = 1.f / (lsum + __shfl_xor(lsum, 32, 64));
+        const int b = bh / H, h = bh % H;
+        bf16_t *arow = a_out + ((size_t)b * N + qpos) * ((size_t)H * kHeadDim) + h * kHeadDim + 4 * hi;
+#pragma unroll
+        for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                *reinterpret_cast<uint2 *>(arow + dt * 32 + 8 * j) =
+                    make_uint2(cvt_pk_bf16(O[dt][4 * j] * inv, O[dt][4 * j + 1] * inv), cvt_pk_bf16(O[dt][4 * j + 2] * inv, O[dt][4 * j + 3] * inv));
+    }
 }
 
 constexpr int kSmallM = 2048;   // up to this many rows the split-contraction kernel is used (it is 1.4x slower at 16384 rows)
@@ -542,23 +809,23 @@ hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S
     if (!pairs_are_temporary) Wp.g_attn = W.g_kv;
     hipError_t e = Launch<bf16_t>::prepass(D, Wp, S, pairs_src, B, N, true, st);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(par_export_kernel, dim3(BH, N), dim3(64), 0, st, (const bf16_t *)S.Kt, S.Ktf, (const bf16_t *)S.Vt,
-                       (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, 0);
+    hipLaunchKernelGGL(par_export_tile_kernel, dim3(BH, (N + 63) / 64), dim3(256), 0, st, (const bf16_t *)S.Kt, S.Ktf,
+                       (const bf16_t *)S.Vt, (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, N);
     if (!pairs_are_temporary) {
         e = Launch<bf16_t>::prepass(D, W, S, x, B, N, true, st);
         if (e != hipSuccess) return e;
     }
-    // Algorithm 1's events; none depends on another here
-    for (int t1 = 1; t1 < N; ++t1) {
-        const int P = t1 & -t1;
-        if (P < D.p_min) continue;
-        const int nq = (P < N - t1) ? P : N - t1;
-        e = cross_mfma_launch(D, S, K, t1, P, nq, true, st);
-        if (e != hipSuccess) return e;
+    {   // attention of all positions: one masked pass over the cache rows plus the temporary pair
+        const int ntiles = (N + 127) / 128;
+        const size_t lds = 2 * (size_t)cross_tile_lds_bytes<true>();
+        const dim3 grid((unsigned)(ntiles * BH));
+        if (D.alibi > 0.f)
+            hipLaunchKernelGGL(par_flash_kernel<true>, grid, dim3(256), lds, st, S.Qf, S.Ktf, (const bf16_t *)S.Vt, (const bf16_t *)K,
+                               S.Klo, S.VT, S.vt_stride, a_b, BH, D.H, N, ntiles, D.scale, D.alibi);
+        else
+            hipLaunchKernelGGL(par_flash_kernel<false>, grid, dim3(256), lds, st, S.Qf, S.Ktf, (const bf16_t *)S.Vt, (const bf16_t *)K,
+                               S.Klo, S.VT, S.vt_stride, a_b, BH, D.H, N, ntiles, D.scale, D.alibi);
     }
-    hipLaunchKernelGGL(par_merge_kernel, dim3(BH, N), dim3(64), 0, st, (const bf16_t *)S.Q, S.Qf, (const bf16_t *)S.Kt, S.Ktf,
-                       (const bf16_t *)S.Vt, (const bf16_t *)K, S.Klo, (const bf16_t *)V, S.pm, S.pl, S.po, a_b, BH, D.H, N, D.p_min,
-                       D.log2_pmin, S.levels, S.slots, D.scale, D.alibi, 0);
     block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, S.rinv, 0, N, st);
     return hipGetLastError();
 }

@@ -83,7 +83,10 @@ def test_recompute_of_an_arbitrary_z_and_of_the_prefill_output(oracle):
 
 
 @pytest.mark.parametrize("B,N,d,H,F,alibi", [(2, 200, 256, 4, 1024, 0.0), (3, 333, 320, 5, 1280, 8.0), (2, 600, 1024, 16, 4096, 0.0),
-                                               (6, 450, 384, 6, 1536, 0.0)])   # 2700 rows: the LDS-tiled products
+                                               (6, 450, 384, 6, 1536, 0.0),    # 2700 rows: the LDS-tiled products
+                                               (2, 1, 256, 4, 1024, 0.0),      # a single position: only the temporary pair
+                                               (2, 128, 256, 4, 1024, 8.0),    # exactly one query tile of the masked pass
+                                               (2, 129, 256, 4, 1024, 8.0)])   # ... and one position more
 def test_transformer_layer(oracle, B, N, d, H, F, alibi):
     li = gen.make_custom(24, "bf16", B, N, d, H, F, gains="random")
     x64 = li.x.astype(np.float64)
