@@ -128,8 +128,8 @@ rt_status rt_stack_prefill(rt_ctx *ctx, const rt_layer_weights *layers, int32_t 
 /* The same layer evaluated without the sequential loop, given its output (Sec. 6.1, "Activation checkpointing": with
  * z known, all persistent pairs k_i, v_i = proj(RMS(z_i)) can be rebuilt at once and every intermediate recomputed in
  * parallel): K, V rows 0..N-1 are written from z, then y_i = the layer's output at position i computed from x_i, the
- * temporary pair of i and the persistent pairs of positions < i - one causal attention (all of Algorithm 1's tiles at
- * once) and three GEMMs.  If z is the layer's true output for x, y reproduces it up to rounding (by induction over
+ * temporary pair of i and the persistent pairs of positions < i - one masked causal attention over all positions
+ * (a single flash-style pass; Algorithm 1's blocks are not needed once every pair is known) and three GEMMs.  If z is the layer's true output for x, y reproduces it up to rounding (by induction over
  * the positions z is the only fixed point).  This is the forward half of a training step's recompute; no backward
  * pass is provided.
  *   x, z [B, N, d] device, read-only; y [B, N, d] written; K, V [kv_cap, B, H, head_dim] rows 0..N-1 written.

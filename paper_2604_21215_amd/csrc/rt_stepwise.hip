@@ -54,6 +54,84 @@ __global__ __launch_bounds__(64) void decode_split_kernel(const T *__restrict__ 
     po[idx * kHeadDim + lane] = o;
 }
 
+// The same for bf16 caches and splits of 64 keys with every load of the split issued at once (the generic kernel
+// walks the value rows eight at a time behind the softmax: nine dependent round trips; here the split's 8 KB of keys and
+// 8 KB of values are requested before anything is computed).  Keys and values alike: piece i of a lane is row
+// 8 i + lane / 8, columns 8 (lane % 8) .. + 7 (eight lanes cover one 128-byte row); the logits are summed over the
+// eight lanes of a row and moved to lane = key, the weights reach the value rows by a shuffle and the eight lanes
+// that share columns are summed at the end.  Rows past the split's end are read from its last row with weight zero.
+// One split per wavefront: grid (ceil(nsplit / 4), B*H), block 256.
+__global__ __launch_bounds__(256) void decode_split64_bf16_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
+                                                                 const bf16_t *__restrict__ V, float *__restrict__ pm,
+                                                                 float *__restrict__ pl, float *__restrict__ po, int BH, int t,
+                                                                 int slots, float scale, float alibi, int H)
+{
+    const int lane = threadIdx.x & 63;
+    const int split = blockIdx.x * 4 + (threadIdx.x >> 6), bh = blockIdx.y;   // one split per wavefront
+    const size_t rs = (size_t)BH * kHeadDim;
+    const int k_lo = split * 64, cnt = min(t - k_lo, 64);
+    if (cnt <= 0) return;   // no barriers in this kernel
+    uint4 kr[8], vr[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const size_t off = (size_t)(k_lo + min(8 * i + (lane >> 3), cnt - 1)) * rs + (size_t)bh * kHeadDim + (lane & 7) * 8;
+        kr[i] = *reinterpret_cast<const uint4 *>(K + off);
+        vr[i] = *reinterpret_cast<const uint4 *>(V + off);
+    }
+    const float qv = bf16_to_f32(Q[(size_t)bh * kHeadDim + lane]);
+    float q8[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) q8[e] = __shfl(qv, (lane & 7) * 8 + e, 64);
+    // the dot product of row 8 i + lane / 8 over this lane's eight columns, summed over the eight lanes of the row; the
+    // logit of key j is then moved to lane j (it sits, complete, in the lanes 8 (j % 8) .. + 7 of piece j / 8)
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t w[4] = {kr[i].x, kr[i].y, kr[i].z, kr[i].w};
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            d = fmaf(q8[2 * e], __uint_as_float(w[e] << 16), d);
+            d = fmaf(q8[2 * e + 1], __uint_as_float(w[e] & 0xFFFF0000u), d);
+        }
+        d += __shfl_xor(d, 1, 64);
+        d += __shfl_xor(d, 2, 64);
+        d += __shfl_xor(d, 4, 64);
+        const float mine = __shfl(d, (lane & 7) * 8, 64);   // row 8 i + lane % 8
+        if ((lane >> 3) == i) acc = mine;
+    }
+    const bool valid = lane < cnt;
+    const float slope = alibi_slope(alibi, bh % H, H);
+    const float logit = valid ? fmaf(-slope, (float)(t - k_lo - lane), acc * scale) : -INFINITY;
+    const float m = wave_max(logit);
+    const float p = valid ? expf(logit - m) : 0.f;
+    const float l = wave_sum(p);
+    float o8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float pr = __shfl(p, 8 * i + (lane >> 3), 64);
+        const uint32_t w[4] = {vr[i].x, vr[i].y, vr[i].z, vr[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o8[2 * e] = fmaf(pr, __uint_as_float(w[e] << 16), o8[2 * e]);
+            o8[2 * e + 1] = fmaf(pr, __uint_as_float(w[e] & 0xFFFF0000u), o8[2 * e + 1]);
+        }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        o8[e] += __shfl_xor(o8[e], 8, 64);
+        o8[e] += __shfl_xor(o8[e], 16, 64);
+        o8[e] += __shfl_xor(o8[e], 32, 64);
+    }
+    const size_t idx = partial_index(0, split, slots, BH, bh);
+    if (lane == 0) { pm[idx] = m; pl[idx] = l; }
+    if (lane < 8) {
+        float *dst = po + idx * kHeadDim + lane * 8;
+        *reinterpret_cast<float4 *>(dst) = make_float4(o8[0], o8[1], o8[2], o8[3]);
+        *reinterpret_cast<float4 *>(dst + 4) = make_float4(o8[4], o8[5], o8[6], o8[7]);
+    }
+}
+
 // =============================================================================================
 // Base case, part 1: finish the attention output of position t (merge_body).  grid B*H, block 64.
 // =============================================================================================
@@ -373,8 +451,12 @@ template <typename T>
 hipError_t Launch<T>::decode_split(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int chunk,
                                    int nsplit, hipStream_t st)
 {
-    hipLaunchKernelGGL(decode_split_kernel<T>, dim3(nsplit, D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)K,
-                       (const T *)V, S.pm, S.pl, S.po, D.B * D.H, t, chunk, S.slots, D.scale, D.alibi, D.H);
+    if (sizeof(T) == 2 && chunk == 64)
+        hipLaunchKernelGGL(decode_split64_bf16_kernel, dim3((nsplit + 3) / 4, D.B * D.H), dim3(256), 0, st, (const bf16_t *)S.Q,
+                           (const bf16_t *)K, (const bf16_t *)V, S.pm, S.pl, S.po, D.B * D.H, t, S.slots, D.scale, D.alibi, D.H);
+    else
+        hipLaunchKernelGGL(decode_split_kernel<T>, dim3(nsplit, D.B * D.H), dim3(64), 0, st, (const T *)S.Q, (const T *)K,
+                           (const T *)V, S.pm, S.pl, S.po, D.B * D.H, t, chunk, S.slots, D.scale, D.alibi, D.H);
     return hipGetLastError();
 }
 

@@ -781,9 +781,13 @@ hipError_t step_base_case_mm(const LayerDims &D, const Weights &W, const Scratch
 {
     const WaveLayer Y = step_layer(W, S, x_t, y_t, K_row, V_row);
     hipError_t e;
-    if ((e = step_mm_launch<EPI_WO, 4, 4>(Y, D.d, D, st)) != hipSuccess) return e;
+    // Wo and W2 have d / 16 row groups only: eight wavefronts share each group's contraction (shorter dependent chains)
+    // when every wavefront still gets whole 64-index step pairs
+    e = D.d % 512 == 0 ? step_mm_launch<EPI_WO, 8, 8>(Y, D.d, D, st) : step_mm_launch<EPI_WO, 4, 4>(Y, D.d, D, st);
+    if (e != hipSuccess) return e;
     if ((e = step_mm_launch<EPI_W1, 4, 4>(Y, D.F, D, st)) != hipSuccess) return e;
-    if ((e = step_mm_launch<EPI_W2, 4, 4>(Y, D.d, D, st)) != hipSuccess) return e;
+    e = D.F % 512 == 0 ? step_mm_launch<EPI_W2, 8, 8>(Y, D.d, D, st) : step_mm_launch<EPI_W2, 4, 4>(Y, D.d, D, st);
+    if (e != hipSuccess) return e;
     if ((e = step_mm_launch<EPI_KV, 2, 8>(Y, 2 * D.d, D, st)) != hipSuccess) return e;
     return hipGetLastError();
 }
