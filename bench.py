@@ -111,7 +111,7 @@ def main():
     ap.add_argument("--no-stack", action="store_true", help="skip the 12-layer stack measurement (rt_stack_prefill)")
     ap.add_argument("--stack-only", action="store_true",
                     help="only the 12-layer stack through rt_stack_prefill (for profiling): prints its section alone")
-    ap.add_argument("--cpu-sample-positions", type=int, default=1024)
+    ap.add_argument("--cpu-sample-positions", type=int, default=2048)
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy, the reference the rocprofv3 FETCH_SIZE / WRITE_SIZE "
                          "counters of the prefill kernel are scaled by")
