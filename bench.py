@@ -226,11 +226,17 @@ def main():
         if levels:
             tot_fl = sum(l["tflops"] * l["us_per_event"] * l["events_per_call"] for l in levels)
             tot_us = sum(l["us_per_event"] * l["events_per_call"] for l in levels)
+            hp = engine == "persistent"   # the tile then forms every logit tile from three bf16 products
             out["cross_block_kernel"] = {
                 "bound": "mfma", "unit": "TFLOP/s", "peak": MFMA_BF16_PEAK_TFLOPS * 1e0,
                 "achieved": tot_fl / tot_us, "frac": tot_fl / tot_us / MFMA_BF16_PEAK_TFLOPS,
-                "note": "stand-alone launches of the top three levels (87.5 % of the attention FLOPs), FLOP-weighted; "
-                        "back-to-back launches, launch overhead included", "levels": levels}
+                "logits": "high precision (three products per logit tile)" if hp else "bf16",
+                "matrix_instruction_tflops": tot_fl / tot_us * (2.0 if hp else 1.0),
+                "note": "stand-alone launches of the top three levels (87.5 % of the attention FLOPs), FLOP-weighted, in the "
+                        "form the engine of the timed call uses; achieved counts the algorithmic 4 P nq 64 FLOPs per "
+                        "(b, h) event, matrix_instruction_tflops what the matrix pipeline executes (twice that with "
+                        "high-precision logits: 32 instead of 16 instructions per 64-key chunk); back-to-back launches, "
+                        "launch overhead included", "levels": levels}
 
     # One decoding step (rt_decode_step) over the cache the call above left: position t = N - 1 is evaluated again
     # from rows 0 .. N-2 (row N-1 is rewritten with the same values).  Bandwidth-bound in principle: the step has to

@@ -23,6 +23,7 @@ struct rt_ctx {
     bool use_mfma = false;
     bool broken = false;
     int last_B = 0, last_N = 0;   // shape of the last prefill (what the scratch holds)
+    bool last_hp = false;         // that prefill formed high-precision logits (scratch holds unrounded queries and key remainders)
     std::string err;
     std::string engine;
     PersistentState persist;
@@ -440,9 +441,11 @@ extern "C" rt_status rt_layer_prefill(rt_ctx *c, const rt_layer_weights *w, cons
     LayerDims D = c->base;
     D.B = B; D.N = N; D.kv_cap = kv_cap;
     c->last_B = B; c->last_N = N;
+    c->last_hp = false;
     const bool want_stepwise = (c->cfg.flags & RT_FLAG_ENGINE_STEPWISE) != 0;
     if (!want_stepwise && persistent_supported(c->persist, D)) {
         c->engine = "persistent";
+        c->last_hp = true;
         const Weights W = to_weights(w);
         hipError_t e;
         if (c->cfg.dtype == RT_BF16) e = Launch<bf16_t>::prepass(D, W, c->S, x, B, N, c->use_mfma, c->stream);
@@ -551,7 +554,9 @@ extern "C" rt_status rt_cross_block_event(rt_ctx *c, const void *K, const void *
     LayerDims D = c->base;
     D.B = B; D.N = c->last_N; D.kv_cap = c->last_N;
     hipError_t e;
-    if (c->cfg.dtype == RT_BF16) e = Launch<bf16_t>::cross(D, c->S, K, V, t1, P, nq, c->use_mfma, c->stream);
+    // the tile in the form the engine of that prefill uses: after the persistent engine with high-precision logits
+    if (c->cfg.dtype == RT_BF16 && c->use_mfma && c->last_hp) e = cross_mfma_launch(D, c->S, K, t1, P, nq, true, c->stream);
+    else if (c->cfg.dtype == RT_BF16) e = Launch<bf16_t>::cross(D, c->S, K, V, t1, P, nq, c->use_mfma, c->stream);
     else e = Launch<float>::cross(D, c->S, K, V, t1, P, nq, false, c->stream);
     if (e != hipSuccess) return fail_hip(c, e, "cross");
     return RT_OK;
@@ -713,6 +718,7 @@ static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void
         c->par_bytes = bytes;
     }
     c->last_B = B; c->last_N = N;
+    c->last_hp = true;
     c->engine = block ? "blocked" : (transformer ? "transformer" : "recompute");
     const Weights W = to_weights(w);
     hipError_t e = block ? blocked_layer(D, W, c->S, x, block, y, K, V, c->par_slab, c->stream)

@@ -219,6 +219,9 @@ template <typename T>
 hipError_t wavefront_prefill(const LayerDims &D, const WaveLayer *dev_layers, const WaveLayer *host_layers, int L, int chunk,
                              bool mfma, const WaveStreams &W);
 // whether the engine's matrix-core products cover this shape (they need the packed weight copies in the scratch)
+// one cross-block UpdateTile on the matrix cores (bf16), queries t1+1 .. t1+nq against keys t1-P+1 .. t1 (1-based);
+// hp: high-precision logits from the unrounded queries (S.Qf) and the key remainders (S.Klo)
+hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, bool hp, hipStream_t st);
 bool wavefront_uses_matrix_cores(int d, int F, bool mfma_bf16);
 // One position of one layer with the same products from the caller's row-major weights (decoding, bf16): x_t, y_t
 // rows d apart ([B][d]); K_row, V_row the cache rows to write ([B][H][64]).

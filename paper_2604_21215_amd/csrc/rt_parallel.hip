@@ -8,17 +8,13 @@
 // Steps, all on one stream, bf16 storage with matrix-core kernels throughout:
 //   pre-pass GEMM over the source of the pairs -> export K, V (+ key remainder and V^T for the tiles)
 //   pre-pass GEMM over x -> q, temporary pairs (recompute only; for the Transformer layer they are the same rows)
-//   every cross-block UpdateTile of Algorithm 1 (all independent now), then one merge launch over all positions
-//   (stored partial states + direct window + temporary pair)
+//   one masked flash-style launch for the attention of all positions (cache rows j < i plus the temporary pair)
 //   h = x + alpha Wo a;  u = gelu(W1 RMS(h));  y = h + alpha W2 u   as three GEMMs with fused epilogues.
 #include "rt_base_case.h"
 #include "rt_mfma_device.h"
 #include "rt_gemm_tiled.h"
 
 namespace rt {
-
-hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, bool hp,
-                             hipStream_t st);
 
 // ---------------------------------------------------------------------------------------------
 // C[m][n] = sum_k A[m][k] W[n][k], A [M][K] and W [Nn][K] bf16 row-major, fp32 accumulation.
