@@ -108,6 +108,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the rt_decode_step measurement")
     ap.add_argument("--no-parallel", action="store_true", help="skip rt_transformer_layer / rt_layer_recompute")
+    ap.add_argument("--no-blocked", action="store_true",
+                    help="skip rt_layer_prefill_blocked (thousands of launches: slow under a counter-collecting profiler)")
     ap.add_argument("--no-stack", action="store_true", help="skip the 12-layer stack measurement (rt_stack_prefill)")
     ap.add_argument("--stack-only", action="store_true",
                     help="only the 12-layer stack through rt_stack_prefill (for profiling): prints its section alone")
@@ -287,7 +289,7 @@ def main():
                          "frac": fl / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS}
         # blocked recurrence (Sec. 8): the sequential loop over blocks of S positions, S x B rows per matrix product
         blocked = {}
-        for S in (4, 16, 32):
+        for S in (() if args.no_blocked else (4, 16, 32)):
             fnb = lambda: ctx.rt_layer_prefill_blocked(dl.struct, xd, S, y2, K2, V2)
             fnb()
             torch.cuda.synchronize()
@@ -299,7 +301,8 @@ def main():
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / 2
             blocked["block_%d" % S] = {"ms_per_call": ms, "tokens_per_s": tokens / (ms * 1e-3)}
-        sec["blocked_recurrence"] = blocked
+        if blocked:
+            sec["blocked_recurrence"] = blocked
         sec["rt_layer_prefill_ms"] = dev_ms
         sec["rt_over_transformer"] = dev_ms / sec["transformer_layer"]["ms_per_call"]
         out["loop_free_layers"] = sec
