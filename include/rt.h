@@ -133,7 +133,10 @@ rt_status rt_stack_prefill(rt_ctx *ctx, const rt_layer_weights *layers, int32_t 
  * the positions z is the only fixed point).  This is the forward half of a training step's recompute; no backward
  * pass is provided.
  *   x, z [B, N, d] device, read-only; y [B, N, d] written; K, V [kv_cap, B, H, head_dim] rows 0..N-1 written.
- *   bf16 storage with the MFMA kernels only (else RT_ERR_UNSUPPORTED); d_hidden a multiple of 64.
+ *   bf16 storage with the MFMA kernels and d_hidden a multiple of 64: matrix-core GEMMs and one masked attention pass.
+ *   Any other context (fp32 storage, RT_FLAG_NO_MFMA, another hidden width): the same results from the plain-ALU
+ *   kernels (one wavefront per (b, h, position) for the attention, the products in tiles of eight rows) - for checking
+ *   at fp32 tolerance, not for speed.
  * The first call allocates activation scratch for max_batch x max_seq rows (kept until rt_destroy). */
 rt_status rt_layer_recompute(rt_ctx *ctx, const rt_layer_weights *w, const void *x, const void *z, int32_t B, int32_t N,
                              void *y, void *K, void *V, int32_t kv_cap);
@@ -153,7 +156,8 @@ rt_status rt_transformer_layer(rt_ctx *ctx, const rt_layer_weights *w, const voi
  * Sec. 2.2; the sequential loop runs over ceil(N / block) blocks whose `block` x B rows go through the matrix
  * products together.  block = 1 is rt_layer_prefill's layer (a different, slower evaluation of it), block >= N would
  * be rt_transformer_layer's.  K, V receive the persistent pairs.
- *   block: power of two, 1 <= block <= p_min.  Other arguments and limits as rt_layer_recompute. */
+ *   block: power of two, 1 <= block <= p_min.  Other arguments as rt_layer_recompute; bf16 storage with the MFMA
+ *   kernels and d_hidden a multiple of 64 only (else RT_ERR_UNSUPPORTED). */
 rt_status rt_layer_prefill_blocked(rt_ctx *ctx, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, int32_t block,
                                    void *y, void *K, void *V, int32_t kv_cap);
 

@@ -694,7 +694,7 @@ static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void
     if (kv_cap < N) return fail(c, RT_ERR_INVALID_ARG, "kv_cap < N%s");
     if (block != 0 && (!is_pow2(block) || block > c->cfg.p_min))
         return fail(c, RT_ERR_INVALID_ARG, "block must be a power of two, at most p_min%s");
-    const size_t E = 2;
+    const size_t E = c->cfg.dtype == RT_BF16 ? 2 : 4;
     const size_t xb = (size_t)B * N * c->cfg.d_model * E, kvb = (size_t)kv_cap * B * c->cfg.d_model * E;
     if (ranges_overlap(x, xb, y, xb) || (pairs_src != x && ranges_overlap(pairs_src, xb, y, xb)))
         return fail(c, RT_ERR_INVALID_ARG, "the output must not overlap an input%s");
@@ -704,18 +704,34 @@ static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void
         return fail(c, RT_ERR_INVALID_ARG, "K, V and the other tensors must not overlap%s");
     LayerDims D = c->base;
     D.B = B; D.N = N; D.kv_cap = kv_cap;
-    if (c->cfg.dtype != RT_BF16 || !parallel_supported(D, c->use_mfma))
-        return fail(c, RT_ERR_UNSUPPORTED, "the loop-free evaluations need bf16 storage, the MFMA kernels and d_hidden a multiple of 64%s");
+    // bf16 with the matrix-core kernels: GEMMs and one masked attention pass; anything else (fp32 storage, no MFMA, odd
+    // hidden width): the plain-ALU kernels, which cover the recompute and the Transformer layer but not the blocked form
+    const bool fast = c->cfg.dtype == RT_BF16 && parallel_supported(D, c->use_mfma);
+    if (!fast && block != 0)
+        return fail(c, RT_ERR_UNSUPPORTED, "the blocked recurrence needs bf16 storage, the MFMA kernels and d_hidden a multiple of 64%s");
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+    const size_t Mmax = (size_t)c->cfg.max_batch * c->cfg.max_seq;
+    const size_t need = fast ? parallel_scratch_bytes(Mmax, c->cfg.d_model, c->cfg.d_hidden)
+                             : Launch<float>::loop_free_scratch_bytes(Mmax, c->cfg.d_model, c->cfg.d_hidden);
     if (!c->par_slab) {
-        const size_t bytes = parallel_scratch_bytes((size_t)c->cfg.max_batch * c->cfg.max_seq, c->cfg.d_model, c->cfg.d_hidden);
-        hipError_t e = hipMalloc(&c->par_slab, bytes);
+        hipError_t e = hipMalloc(&c->par_slab, need);
         if (e != hipSuccess) {
             (void)hipGetLastError();
             c->par_slab = nullptr;
             return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "activation scratch: %s", hipGetErrorString(e));
         }
-        c->par_bytes = bytes;
+        c->par_bytes = need;
+    }
+    if (!fast) {
+        c->last_B = B; c->last_N = N;
+        c->last_hp = false;
+        c->engine = transformer ? "transformer" : "recompute";
+        const Weights Wg = to_weights(w);
+        hipError_t e = c->cfg.dtype == RT_BF16
+                           ? Launch<bf16_t>::loop_free(D, Wg, c->S, x, pairs_src, transformer, y, K, V, c->par_slab, c->stream)
+                           : Launch<float>::loop_free(D, Wg, c->S, x, pairs_src, transformer, y, K, V, c->par_slab, c->stream);
+        if (e != hipSuccess) return fail_hip(c, e, "loop_free");
+        return RT_OK;
     }
     c->last_B = B; c->last_N = N;
     c->last_hp = true;

@@ -194,6 +194,13 @@ template <typename T> struct Launch {
                             bool mfma, hipStream_t st);
     static hipError_t decode_split(const LayerDims &D, const Scratch &S, const void *K, const void *V, int t, int chunk,
                                    int nsplit, hipStream_t st);
+    // The layer without its sequential loop (recompute from a given output, Sec. 6.1; Transformer layer, Sec. 2.1) on the
+    // plain-ALU kernels, any storage type: pre-pass over pairs_src -> K, V rows; pre-pass over x unless the pairs are the
+    // temporary ones; one wavefront per (b, h, position) for the attention; the three products in tiles of eight rows.
+    // par: loop_free_scratch_bytes(B * N, d, F) bytes.
+    static hipError_t loop_free(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, const void *pairs_src,
+                                bool pairs_are_temporary, void *y, void *K, void *V, void *par, hipStream_t st);
+    static size_t loop_free_scratch_bytes(size_t M, size_t d, size_t F) { return M * (3 * d + F) * 4 + 1024; }
 };
 
 // One layer of a stack as the layer-wavefront engine's kernels see it (an array of these lives in device memory).

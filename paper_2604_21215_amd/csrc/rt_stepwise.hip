@@ -460,6 +460,54 @@ hipError_t Launch<T>::decode_split(const LayerDims &D, const Scratch &S, const v
     return hipGetLastError();
 }
 
+// Attention output of EVERY position when all key-value pairs are known (loop-free layers): one wavefront per (b, h, i);
+// the state starts from the temporary pair of i and runs over the cache rows j < i.  a_out: fp32 rows [B][N][d].
+// grid (B*H, N), block 64.
+template <typename T>
+__global__ __launch_bounds__(64) void attend_all_kernel(const T *__restrict__ Q, const T *__restrict__ Kt, const T *__restrict__ Vt,
+                                                        const T *__restrict__ K, const T *__restrict__ V, float *__restrict__ a_out,
+                                                        int BH, int H, int N, float scale, float alibi)
+{
+    const int lane = threadIdx.x, bh = blockIdx.x, i = blockIdx.y;
+    const size_t rs = (size_t)BH * kHeadDim;
+    const size_t qo = (size_t)i * rs + (size_t)bh * kHeadDim + lane;
+    const float q = to_f32(Q[qo]);
+    float m = wave_sum(q * to_f32(Kt[qo])) * scale, l = 1.f, o = to_f32(Vt[qo]);   // distance 0: no positional bias
+    if (i > 0)
+        attend_keys<T>(q, K + (size_t)bh * kHeadDim, V + (size_t)bh * kHeadDim, rs, i, scale, m, l, o, nullptr,
+                       alibi_slope(alibi, bh % H, H), i);
+    const int b = bh / H, h = bh % H;
+    a_out[((size_t)b * N + i) * ((size_t)H * kHeadDim) + h * kHeadDim + lane] = o / l;
+}
+
+template <typename T>
+hipError_t Launch<T>::loop_free(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, const void *pairs_src,
+                                bool pairs_are_temporary, void *y, void *K, void *V, void *par, hipStream_t st)
+{
+    const int B = D.B, N = D.N, d = D.d, F = D.F, M = B * N;
+    float *a_f = (float *)par, *h_f = a_f + (size_t)M * d, *z_f = h_f + (size_t)M * d, *u_f = z_f + (size_t)M * d;
+    Weights Wp = W;
+    if (!pairs_are_temporary) Wp.g_attn = W.g_kv;
+    hipError_t e = prepass(D, Wp, S, pairs_src, B, N, false, st);
+    if (e != hipSuccess) return e;
+    // the pre-pass rows (position, b, h) are laid out like the cache rows
+    const size_t kv_bytes = (size_t)N * B * d * sizeof(T);
+    if ((e = hipMemcpyAsync(K, S.Kt, kv_bytes, hipMemcpyDeviceToDevice, st)) != hipSuccess) return e;
+    if ((e = hipMemcpyAsync(V, S.Vt, kv_bytes, hipMemcpyDeviceToDevice, st)) != hipSuccess) return e;
+    if (!pairs_are_temporary && (e = prepass(D, W, S, x, B, N, false, st)) != hipSuccess) return e;
+    hipLaunchKernelGGL(attend_all_kernel<T>, dim3(B * D.H, N), dim3(64), 0, st, (const T *)S.Q, (const T *)S.Kt, (const T *)S.Vt,
+                       (const T *)K, (const T *)V, a_f, B * D.H, D.H, N, D.scale, D.alibi);
+    e = gemv_launch<T, float, EPI_WO>((const T *)W.Wo, (const T *)W.Wo, (const T *)W.Wo, d, d, d, a_f, (size_t)d, M, (const T *)nullptr,
+                                      D.eps, 0, D.alpha, (const T *)x, (size_t)d, (const float *)nullptr, h_f, (T *)nullptr, (size_t)0, st);
+    if (e != hipSuccess) return e;
+    e = gemv_launch<T, float, EPI_W1>((const T *)W.W1, (const T *)W.W1, (const T *)W.W1, F, F, d, h_f, (size_t)d, M, (const T *)W.g_mlp,
+                                      D.eps, D.norm_free ? 0 : 1, D.alpha, (const T *)nullptr, (size_t)0, (const float *)nullptr, u_f,
+                                      (T *)nullptr, (size_t)0, st);
+    if (e != hipSuccess) return e;
+    return gemv_launch<T, float, EPI_W2>((const T *)W.W2, (const T *)W.W2, (const T *)W.W2, d, d, F, u_f, (size_t)F, M, (const T *)nullptr,
+                                         D.eps, 0, D.alpha, (const T *)nullptr, (size_t)0, h_f, z_f, (T *)y, (size_t)d, st);
+}
+
 template struct Launch<float>;
 template struct Launch<bf16_t>;
 

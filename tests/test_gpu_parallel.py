@@ -147,9 +147,58 @@ def test_parallel_entry_points_reject_what_they_do_not_cover():
         xd = tio.to_device(li.x, "f32")
         y, K, V = torch.empty_like(xd), torch.zeros((16, 1, 2, 64), device=xd.device), torch.zeros((16, 1, 2, 64), device=xd.device)
         with pytest.raises(binding.RTError) as ei:
-            ctx.rt_transformer_layer(dl.struct, xd, y, K, V)
+            ctx.rt_layer_prefill_blocked(dl.struct, xd, 4, y, K, V)       # the blocked form has matrix-core kernels only
         assert ei.value.status == "RT_ERR_UNSUPPORTED"
         with pytest.raises(binding.RTError):
             ctx.rt_layer_recompute(dl.struct, xd, xd, xd, K, V)          # output overlaps an input (checked first)
+    finally:
+        ctx.rt_destroy()
+
+
+@pytest.mark.parametrize("dtype,B,N,d,H,F,alibi,flags", [
+    ("f32", 1, 256, 128, 2, 512, 0.0, 0),            # the fp32 benchmark configuration's shape
+    ("f32", 3, 77, 192, 3, 768, 8.0, 0),             # ragged, odd head count, bias
+    ("bf16", 2, 150, 256, 4, 1024, 0.0, "no_mfma"),  # bf16 storage without the matrix-core kernels
+])
+def test_loop_free_layers_on_the_plain_alu_kernels(oracle, dtype, B, N, d, H, F, alibi, flags):
+    """fp32 storage (tolerance 1e-4) and bf16 without the MFMA kernels: rt_transformer_layer against the oracle's
+    Transformer layer; rt_layer_recompute fed with the oracle's output (rounded to the storage type) against the
+    oracle's prefill, and fed with an arbitrary z against the oracle's recompute of the same z."""
+    if not torch.cuda.is_available():
+        pytest.fail("no GPU visible")
+    from paper_2604_21215_amd import binding, torch_io as tio
+    li = gen.make_custom(31, dtype, B, N, d, H, F, gains="random")
+    x64 = li.x.astype(np.float64)
+    lay = oracle_layer(oracle, li, H, alpha=0.9, eps=1e-6, alibi_max_bias=alibi)
+    kw = dict(resid_scale=0.9, rms_eps=1e-6, alibi_max_bias=alibi, stream=torch.cuda.current_stream().cuda_stream)
+    if flags == "no_mfma":
+        kw["flags"] = binding.RT_FLAG_NO_MFMA
+    ctx = binding.RTContext(d, H, F, B, N, dtype, **kw)
+    tol = TOL[dtype]
+    try:
+        dl = tio.DeviceLayer(li.weights, li.gains, dtype)
+        xd = tio.to_device(li.x, dtype)
+        y = torch.empty_like(xd)
+        K = torch.zeros((N, B, H, d // H), dtype=xd.dtype, device=xd.device)
+        V = torch.zeros_like(K)
+        got = lambda: (tio.to_host(y), tio.to_host(K), tio.to_host(V))
+        ctx.rt_transformer_layer(dl.struct, xd, y, K, V)
+        torch.cuda.synchronize()
+        assert ctx.engine_name() == "transformer"
+        _check("plain-ALU Transformer layer %s B=%d N=%d" % (dtype, B, N), x64, lay.transformer(x64), got(), tol)
+        ref = lay.prefill(x64)
+        z = ref[0].astype(np.float32)
+        if dtype == "bf16":
+            z = gen.round_to_bf16(z)
+        ctx.rt_layer_recompute(dl.struct, xd, tio.to_device(z, dtype), y, K, V)
+        torch.cuda.synchronize()
+        assert ctx.engine_name() == "recompute"
+        _check("plain-ALU recompute from the exact output %s" % dtype, x64, ref, got(), tol)
+        z2 = (li.x + 0.5 * gen.make_custom(32, dtype, B, N, d, H, F).x).astype(np.float32)
+        if dtype == "bf16":
+            z2 = gen.round_to_bf16(z2)
+        ctx.rt_layer_recompute(dl.struct, xd, tio.to_device(z2, dtype), y, K, V)
+        torch.cuda.synchronize()
+        _check("plain-ALU recompute of an arbitrary z %s" % dtype, x64, lay.recompute(x64, z2.astype(np.float64)), got(), tol)
     finally:
         ctx.rt_destroy()
