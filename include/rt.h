@@ -156,8 +156,7 @@ rt_status rt_transformer_layer(rt_ctx *ctx, const rt_layer_weights *w, const voi
  * Sec. 2.2; the sequential loop runs over ceil(N / block) blocks whose `block` x B rows go through the matrix
  * products together.  block = 1 is rt_layer_prefill's layer (a different, slower evaluation of it), block >= N would
  * be rt_transformer_layer's.  K, V receive the persistent pairs.
- *   block: power of two, 1 <= block <= p_min.  Other arguments as rt_layer_recompute; bf16 storage with the MFMA
- *   kernels and d_hidden a multiple of 64 only (else RT_ERR_UNSUPPORTED). */
+ *   block: power of two, 1 <= block <= p_min.  Other arguments and the two kernel paths as rt_layer_recompute. */
 rt_status rt_layer_prefill_blocked(rt_ctx *ctx, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, int32_t block,
                                    void *y, void *K, void *V, int32_t kv_cap);
 

@@ -705,10 +705,8 @@ static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void
     LayerDims D = c->base;
     D.B = B; D.N = N; D.kv_cap = kv_cap;
     // bf16 with the matrix-core kernels: GEMMs and one masked attention pass; anything else (fp32 storage, no MFMA, odd
-    // hidden width): the plain-ALU kernels, which cover the recompute and the Transformer layer but not the blocked form
+    // hidden width): the plain-ALU kernels
     const bool fast = c->cfg.dtype == RT_BF16 && parallel_supported(D, c->use_mfma);
-    if (!fast && block != 0)
-        return fail(c, RT_ERR_UNSUPPORTED, "the blocked recurrence needs bf16 storage, the MFMA kernels and d_hidden a multiple of 64%s");
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
     const size_t Mmax = (size_t)c->cfg.max_batch * c->cfg.max_seq;
     const size_t need = fast ? parallel_scratch_bytes(Mmax, c->cfg.d_model, c->cfg.d_hidden)
@@ -725,11 +723,16 @@ static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void
     if (!fast) {
         c->last_B = B; c->last_N = N;
         c->last_hp = false;
-        c->engine = transformer ? "transformer" : "recompute";
+        c->engine = block ? "blocked" : (transformer ? "transformer" : "recompute");
         const Weights Wg = to_weights(w);
-        hipError_t e = c->cfg.dtype == RT_BF16
-                           ? Launch<bf16_t>::loop_free(D, Wg, c->S, x, pairs_src, transformer, y, K, V, c->par_slab, c->stream)
-                           : Launch<float>::loop_free(D, Wg, c->S, x, pairs_src, transformer, y, K, V, c->par_slab, c->stream);
+        hipError_t e;
+        if (block)
+            e = c->cfg.dtype == RT_BF16 ? Launch<bf16_t>::blocked_generic(D, Wg, c->S, x, block, y, K, V, c->par_slab, c->stream)
+                                        : Launch<float>::blocked_generic(D, Wg, c->S, x, block, y, K, V, c->par_slab, c->stream);
+        else
+            e = c->cfg.dtype == RT_BF16
+                    ? Launch<bf16_t>::loop_free(D, Wg, c->S, x, pairs_src, transformer, y, K, V, c->par_slab, c->stream)
+                    : Launch<float>::loop_free(D, Wg, c->S, x, pairs_src, transformer, y, K, V, c->par_slab, c->stream);
         if (e != hipSuccess) return fail_hip(c, e, "loop_free");
         return RT_OK;
     }

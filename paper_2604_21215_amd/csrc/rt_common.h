@@ -201,6 +201,10 @@ template <typename T> struct Launch {
     static hipError_t loop_free(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, const void *pairs_src,
                                 bool pairs_are_temporary, void *y, void *K, void *V, void *par, hipStream_t st);
     static size_t loop_free_scratch_bytes(size_t M, size_t d, size_t F) { return M * (3 * d + F) * 4 + 1024; }
+    // The blocked recurrence (blocks of Sblk positions: persistent pairs across blocks, temporary pairs inside a block) on
+    // the same plain-ALU kernels; same scratch.
+    static hipError_t blocked_generic(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Sblk, void *y,
+                                      void *K, void *V, void *par, hipStream_t st);
 };
 
 // One layer of a stack as the layer-wavefront engine's kernels see it (an array of these lives in device memory).

@@ -462,13 +462,13 @@ hipError_t Launch<T>::decode_split(const LayerDims &D, const Scratch &S, const v
 
 // Attention output of EVERY position when all key-value pairs are known (loop-free layers): one wavefront per (b, h, i);
 // the state starts from the temporary pair of i and runs over the cache rows j < i.  a_out: fp32 rows [B][N][d].
-// grid (B*H, N), block 64.
+// grid (B*H, positions), block 64: positions t0 .. t0 + gridDim.y - 1.
 template <typename T>
 __global__ __launch_bounds__(64) void attend_all_kernel(const T *__restrict__ Q, const T *__restrict__ Kt, const T *__restrict__ Vt,
                                                         const T *__restrict__ K, const T *__restrict__ V, float *__restrict__ a_out,
-                                                        int BH, int H, int N, float scale, float alibi)
+                                                        int BH, int H, int N, float scale, float alibi, int t0)
 {
-    const int lane = threadIdx.x, bh = blockIdx.x, i = blockIdx.y;
+    const int lane = threadIdx.x, bh = blockIdx.x, i = t0 + blockIdx.y;
     const size_t rs = (size_t)BH * kHeadDim;
     const size_t qo = (size_t)i * rs + (size_t)bh * kHeadDim + lane;
     const float q = to_f32(Q[qo]);
@@ -496,7 +496,7 @@ hipError_t Launch<T>::loop_free(const LayerDims &D, const Weights &W, const Scra
     if ((e = hipMemcpyAsync(V, S.Vt, kv_bytes, hipMemcpyDeviceToDevice, st)) != hipSuccess) return e;
     if (!pairs_are_temporary && (e = prepass(D, W, S, x, B, N, false, st)) != hipSuccess) return e;
     hipLaunchKernelGGL(attend_all_kernel<T>, dim3(B * D.H, N), dim3(64), 0, st, (const T *)S.Q, (const T *)S.Kt, (const T *)S.Vt,
-                       (const T *)K, (const T *)V, a_f, B * D.H, D.H, N, D.scale, D.alibi);
+                       (const T *)K, (const T *)V, a_f, B * D.H, D.H, N, D.scale, D.alibi, 0);
     e = gemv_launch<T, float, EPI_WO>((const T *)W.Wo, (const T *)W.Wo, (const T *)W.Wo, d, d, d, a_f, (size_t)d, M, (const T *)nullptr,
                                       D.eps, 0, D.alpha, (const T *)x, (size_t)d, (const float *)nullptr, h_f, (T *)nullptr, (size_t)0, st);
     if (e != hipSuccess) return e;
@@ -506,6 +506,51 @@ hipError_t Launch<T>::loop_free(const LayerDims &D, const Weights &W, const Scra
     if (e != hipSuccess) return e;
     return gemv_launch<T, float, EPI_W2>((const T *)W.W2, (const T *)W.W2, (const T *)W.W2, d, d, F, u_f, (size_t)F, M, (const T *)nullptr,
                                          D.eps, 0, D.alpha, (const T *)nullptr, (size_t)0, h_f, z_f, (T *)y, (size_t)d, st);
+}
+
+template <typename T>
+hipError_t Launch<T>::blocked_generic(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Sblk, void *y,
+                                      void *K, void *V, void *par, hipStream_t st)
+{
+    const int B = D.B, N = D.N, d = D.d, F = D.F, M = B * N;
+    float *a_f = (float *)par, *h_f = a_f + (size_t)M * d, *z_f = h_f + (size_t)M * d, *u_f = z_f + (size_t)M * d;
+    Weights Wp = W;
+    Wp.g_attn = W.g_kv;
+    hipError_t e = prepass(D, W, S, x, B, N, false, st);   // q and temporary pairs of every position
+    if (e != hipSuccess) return e;
+    const size_t row_bytes = (size_t)B * d * sizeof(T);    // one position of the pre-pass buffers and of the cache alike
+    for (int t0 = 0; t0 < N; t0 += Sblk) {
+        const int nr = Sblk < N - t0 ? Sblk : N - t0;
+        // while the block is evaluated its cache rows hold its temporary pairs
+        if ((e = hipMemcpyAsync((char *)K + t0 * row_bytes, (const char *)S.Kt + t0 * row_bytes, nr * row_bytes,
+                                hipMemcpyDeviceToDevice, st)) != hipSuccess) return e;
+        if ((e = hipMemcpyAsync((char *)V + t0 * row_bytes, (const char *)S.Vt + t0 * row_bytes, nr * row_bytes,
+                                hipMemcpyDeviceToDevice, st)) != hipSuccess) return e;
+        hipLaunchKernelGGL(attend_all_kernel<T>, dim3(B * D.H, nr), dim3(64), 0, st, (const T *)S.Q, (const T *)S.Kt, (const T *)S.Vt,
+                           (const T *)K, (const T *)V, a_f, B * D.H, D.H, N, D.scale, D.alibi, t0);
+        for (int b = 0; b < B; ++b) {   // the block's rows of one batch row are contiguous
+            const size_t r0 = (size_t)b * N + t0;
+            e = gemv_launch<T, float, EPI_WO>((const T *)W.Wo, (const T *)W.Wo, (const T *)W.Wo, d, d, d, a_f + r0 * d, (size_t)d, nr,
+                                              (const T *)nullptr, D.eps, 0, D.alpha, (const T *)x + r0 * d, (size_t)d,
+                                              (const float *)nullptr, h_f + r0 * d, (T *)nullptr, (size_t)0, st);
+            if (e != hipSuccess) return e;
+            e = gemv_launch<T, float, EPI_W1>((const T *)W.W1, (const T *)W.W1, (const T *)W.W1, F, F, d, h_f + r0 * d, (size_t)d, nr,
+                                              (const T *)W.g_mlp, D.eps, D.norm_free ? 0 : 1, D.alpha, (const T *)nullptr, (size_t)0,
+                                              (const float *)nullptr, u_f + r0 * F, (T *)nullptr, (size_t)0, st);
+            if (e != hipSuccess) return e;
+            e = gemv_launch<T, float, EPI_W2>((const T *)W.W2, (const T *)W.W2, (const T *)W.W2, d, d, F, u_f + r0 * F, (size_t)F, nr,
+                                              (const T *)nullptr, D.eps, 0, D.alpha, (const T *)nullptr, (size_t)0, h_f + r0 * d,
+                                              z_f + r0 * d, (T *)y + r0 * d, (size_t)d, st);
+            if (e != hipSuccess) return e;
+        }
+        // persistent pairs of the block from its outputs, over the temporary ones
+        if ((e = prepass(D, Wp, S, y, B, nr, false, st, (size_t)N * d, t0)) != hipSuccess) return e;
+        if ((e = hipMemcpyAsync((char *)K + t0 * row_bytes, (const char *)S.Kt + t0 * row_bytes, nr * row_bytes,
+                                hipMemcpyDeviceToDevice, st)) != hipSuccess) return e;
+        if ((e = hipMemcpyAsync((char *)V + t0 * row_bytes, (const char *)S.Vt + t0 * row_bytes, nr * row_bytes,
+                                hipMemcpyDeviceToDevice, st)) != hipSuccess) return e;
+    }
+    return hipSuccess;
 }
 
 template struct Launch<float>;

@@ -147,10 +147,12 @@ def test_parallel_entry_points_reject_what_they_do_not_cover():
         xd = tio.to_device(li.x, "f32")
         y, K, V = torch.empty_like(xd), torch.zeros((16, 1, 2, 64), device=xd.device), torch.zeros((16, 1, 2, 64), device=xd.device)
         with pytest.raises(binding.RTError) as ei:
-            ctx.rt_layer_prefill_blocked(dl.struct, xd, 4, y, K, V)       # the blocked form has matrix-core kernels only
-        assert ei.value.status == "RT_ERR_UNSUPPORTED"
+            ctx.rt_layer_prefill_blocked(dl.struct, xd, 3, y, K, V)       # not a power of two
+        assert ei.value.status == "RT_ERR_INVALID_ARG"
         with pytest.raises(binding.RTError):
-            ctx.rt_layer_recompute(dl.struct, xd, xd, xd, K, V)          # output overlaps an input (checked first)
+            ctx.rt_layer_recompute(dl.struct, xd, xd, xd, K, V)          # output overlaps an input
+        with pytest.raises(binding.RTError):
+            ctx.rt_transformer_layer(dl.struct, xd, y, K, K)             # K and V overlap
     finally:
         ctx.rt_destroy()
 
@@ -163,7 +165,8 @@ def test_parallel_entry_points_reject_what_they_do_not_cover():
 def test_loop_free_layers_on_the_plain_alu_kernels(oracle, dtype, B, N, d, H, F, alibi, flags):
     """fp32 storage (tolerance 1e-4) and bf16 without the MFMA kernels: rt_transformer_layer against the oracle's
     Transformer layer; rt_layer_recompute fed with the oracle's output (rounded to the storage type) against the
-    oracle's prefill, and fed with an arbitrary z against the oracle's recompute of the same z."""
+    oracle's prefill, and fed with an arbitrary z against the oracle's recompute of the same z; rt_layer_prefill_blocked
+    against the oracle's blocked recurrence (blocks of 1, the RT layer itself, and of 8)."""
     if not torch.cuda.is_available():
         pytest.fail("no GPU visible")
     from paper_2604_21215_amd import binding, torch_io as tio
@@ -200,5 +203,10 @@ def test_loop_free_layers_on_the_plain_alu_kernels(oracle, dtype, B, N, d, H, F,
         ctx.rt_layer_recompute(dl.struct, xd, tio.to_device(z2, dtype), y, K, V)
         torch.cuda.synchronize()
         _check("plain-ALU recompute of an arbitrary z %s" % dtype, x64, lay.recompute(x64, z2.astype(np.float64)), got(), tol)
+        for block in (1, 8):
+            ctx.rt_layer_prefill_blocked(dl.struct, xd, block, y, K, V)
+            torch.cuda.synchronize()
+            assert ctx.engine_name() == "blocked"
+            _check("plain-ALU blocked recurrence (%d) %s" % (block, dtype), x64, lay.prefill_blocked(x64, block), got(), tol)
     finally:
         ctx.rt_destroy()
