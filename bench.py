@@ -17,7 +17,9 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # L2<->fabric bytes of one persistent_kernel launch on workload cfg3, from two rocprofv3 --pmc runs (FETCH_SIZE, then
 # WRITE_SIZE) scaled by what the same counters read for a plain 256 MiB copy (x 2.000 and x 1.000): fetch 9.58 GB + write 5.17 GB.
-MEASURED_TRAFFIC_BYTES = {("cfg3", "persistent"): 2 * 4676919 * 1024 + 5048709 * 1024}
+MEASURED_TRAFFIC_BYTES = {("cfg3", "persistent"): 2 * 4676919 * 1024 + 5048709 * 1024,
+                          # one decoding step at t = 2047 (its nine kernels summed): fetch 101.0 MB + write 1.6 MB
+                          ("cfg3", "decode"): int((2 * 49301.2 + 1602.0) * 1024)}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -261,6 +263,7 @@ def main():
         out["decode_step"] = {"t": t_dec, "us_per_step": us, "tokens_per_s": wl.B / (us * 1e-6), "bound": "hbm",
                               "algorithmic_bytes": dec_bytes, "achieved": dec_bytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": dec_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                              "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "decode")) if t_dec == 2047 else None,
                               "note": "nine launches per step on one stream (bf16: products on the matrix cores)"}
 
     # The same layer without its sequential loop (every key-value pair known in advance): the recompute from a given
