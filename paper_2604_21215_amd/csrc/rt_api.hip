@@ -98,6 +98,7 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
     const size_t oopu = carve(2 * Bm * F * 2);
     const size_t osh = carve(Bm * (d / 16 + 1) * 4), osz = carve(Bm * (d / 16 + 1) * 4);
     const size_t oopx = carve(2 * Bm * d * 2), osx = carve(Bm * (d / 16 + 1) * 4);
+    const size_t owg = mfma ? carve(3 * d * d * 2) : 0;
     const size_t owo = packed_weights ? carve(d * d * 2) : 0, ow1 = packed_weights ? carve(F * d * 2) : 0;
     const size_t ow2 = packed_weights ? carve(d * F * 2) : 0, owkv = packed_weights ? carve(2 * d * d * 2) : 0;
     if (base) {
@@ -116,6 +117,7 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
         S.op_u = (bf16_t *)(p + oopu);
         S.ssq_h = (float *)(p + osh); S.ssq_z = (float *)(p + osz);
         S.op_x = (bf16_t *)(p + oopx); S.ssq_x = (float *)(p + osx);
+        S.wg_qkv = mfma ? (bf16_t *)(p + owg) : nullptr;
         if (packed_weights) {
             S.wp_o = (bf16_t *)(p + owo); S.wp_1 = (bf16_t *)(p + ow1); S.wp_2 = (bf16_t *)(p + ow2);
             S.wp_kv = (bf16_t *)(p + owkv);

@@ -161,6 +161,7 @@ struct Scratch {
     // contraction indices 64p .. 64p+63, two fragments of 64 lanes x 16 bytes, lane (col, g) of fragment f holding
     // W[16R + col][64p + 32f + 8g .. + 7]; a wavefront's weight stream is then one contiguous run
     bf16_t *wp_o, *wp_1, *wp_2, *wp_kv;
+    bf16_t *wg_qkv;      // [3d][d] [Wq; Wk; Wv] with the columns multiplied by the attention RMS gain (tiled pre-pass), MFMA path only
 };
 
 __host__ __device__ __forceinline__ size_t partial_index(int level_rel, int slot, int slots, int BH, int bh)

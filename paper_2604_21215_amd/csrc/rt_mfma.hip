@@ -101,6 +101,27 @@ __global__ __launch_bounds__(256) void prepass_tiled_kernel(const bf16_t *__rest
     }
 }
 
+// out[r][k] = bf16(W[r][k] * g[k]) for the three d x d projection matrices stacked: the tiled pre-pass then stages its input
+// rows as they are (vector work in the staging step is on that kernel's critical path).  grid ceil(3 d d / 8 / 256), block 256.
+__global__ __launch_bounds__(256) void scale_qkv_columns_kernel(const bf16_t *__restrict__ Wq, const bf16_t *__restrict__ Wk,
+                                                                const bf16_t *__restrict__ Wv, const bf16_t *__restrict__ g,
+                                                                bf16_t *__restrict__ out, int d)
+{
+    const size_t per = (size_t)d * d / 8;           // 16-byte pieces per matrix
+    const size_t q = (size_t)blockIdx.x * 256 + threadIdx.x;
+    if (q >= 3 * per) return;
+    const int which = (int)(q / per);
+    const size_t e = (q - which * per) * 8;         // element offset within the matrix
+    const int k = (int)(e % (size_t)d);
+    const bf16_t *W = which == 0 ? Wq : (which == 1 ? Wk : Wv);
+    float w[8], gg[8];
+    load8(W + e, w);
+    load8(g + k, gg);
+    *reinterpret_cast<uint4 *>(out + (size_t)which * d * d + e) =
+        make_uint4(pack_bf16(w[0] * gg[0], w[1] * gg[1]), pack_bf16(w[2] * gg[2], w[3] * gg[3]),
+                   pack_bf16(w[4] * gg[4], w[5] * gg[5]), pack_bf16(w[6] * gg[6], w[7] * gg[7]));
+}
+
 constexpr int kTiledMinRows = 2048;   // below this the untiled kernel's smaller block tiles fill the chip better
 
 hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Bc, int Nc,
@@ -108,10 +129,16 @@ hipError_t prepass_mfma_launch(const LayerDims &D, const Weights &W, const Scrat
 {
     const int M = Bc * Nc;
     if (M >= kTiledMinRows && D.d % 128 == 0) {
+        const bf16_t *wq = (const bf16_t *)W.Wq, *wk = (const bf16_t *)W.Wk, *wv = (const bf16_t *)W.Wv, *ga = (const bf16_t *)W.g_attn;
+        if (ga && !D.norm_free && S.wg_qkv) {   // the gain goes into the matrices' columns
+            const size_t pieces = 3 * (size_t)D.d * D.d / 8;
+            hipLaunchKernelGGL(scale_qkv_columns_kernel, dim3((unsigned)((pieces + 255) / 256)), dim3(256), 0, st, wq, wk, wv, ga,
+                               S.wg_qkv, D.d);
+            wq = S.wg_qkv; wk = wq + (size_t)D.d * D.d; wv = wk + (size_t)D.d * D.d; ga = nullptr;
+        }
         hipLaunchKernelGGL(prepass_tiled_kernel, dim3((M + kGtRows - 1) / kGtRows, 3 * D.d / kGtCols), dim3(256), 0, st,
-                           (const bf16_t *)x, S.rinv, (const bf16_t *)W.Wq, (const bf16_t *)W.Wk, (const bf16_t *)W.Wv,
-                           (const bf16_t *)W.g_attn, (const bf16_t *)W.g_q, (const bf16_t *)W.g_k, (bf16_t *)S.Q, (bf16_t *)S.Kt,
-                           (bf16_t *)S.Vt, S.Qf, S.Ktf, Bc, Nc, x_bstride, n0, D.d, D.H, D.eps, D.norm_free);
+                           (const bf16_t *)x, S.rinv, wq, wk, wv, ga, (const bf16_t *)W.g_q, (const bf16_t *)W.g_k, (bf16_t *)S.Q,
+                           (bf16_t *)S.Kt, (bf16_t *)S.Vt, S.Qf, S.Ktf, Bc, Nc, x_bstride, n0, D.d, D.H, D.eps, D.norm_free);
         return hipGetLastError();
     }
     hipLaunchKernelGGL(prepass_mfma_kernel, dim3((M + 127) / 128, (3 * D.H + 1) / 2), dim3(256), 0, st, (const bf16_t *)x,
