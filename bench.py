@@ -51,7 +51,7 @@ def algorithmic_bytes(B, N, d, H, F, E, p_min, weights_resident):
     }
 
 
-def stack_section(stream, layer_by_layer=True, reps=2, alibi=0.0):
+def stack_section(stream, layer_by_layer=True, reps=2, alibi=0.0, layers=0, positions=0):
     """The 12-layer stack workload (cfg5: B = 4, N = 4096) through the layer-wavefront engine (rt_stack_prefill: the
     layers run concurrently, a chunk of positions apart) and, for comparison, layer by layer (12 x rt_layer_prefill).
     Its bound is the weight stream: every (layer, position) reads the layer's five loop matrices once."""
@@ -60,6 +60,9 @@ def stack_section(stream, layer_by_layer=True, reps=2, alibi=0.0):
     from paper_2604_21215_amd import binding, inputs as gen, torch_io as tio
     from paper_2604_21215_amd.stack import DeviceStack
     ws = gen.WORKLOADS["cfg5"]
+    if layers or positions:   # a reduced or enlarged variant of the workload (sweeps; not the benchmark line)
+        import dataclasses
+        ws = dataclasses.replace(ws, layers=layers or ws.layers, N=positions or ws.N)
     tabs = gen.make_embedding_tables(ws)
     sctx = binding.RTContext(ws.d, ws.H, ws.F, ws.B, ws.N, ws.dtype, resid_scale=ws.resid_scale, rms_eps=1e-6,
                              stream=stream.cuda_stream, alibi_max_bias=alibi)
@@ -81,7 +84,9 @@ def stack_section(stream, layer_by_layer=True, reps=2, alibi=0.0):
     t_wf = timed(reps, wavefront=True)
     w_bytes = float(ws.N) * ws.layers * (3 * ws.d * ws.d + 2 * ws.d * ws.F) * 2
     sec = {
-        "workload": "cfg5: 12 RT layers, bf16, B=%d, N=%d, d_model=%d, embedding + read-out included" % (ws.B, ws.N, ws.d),
+        "workload": "cfg5: %d RT layers, bf16, B=%d, N=%d, d_model=%d, embedding + read-out included"
+                    % (ws.layers, ws.B, ws.N, ws.d),
+        "us_per_step": t_wf * 1e6 / (ws.N + (ws.layers - 1) * 64),
         "ms_per_prefill": t_wf * 1e3, "tokens_per_s": ws.B * ws.N / t_wf,
         "layer_tokens_per_s": ws.B * ws.N * ws.layers / t_wf,
         "bound": "hbm", "algorithmic_bytes": w_bytes, "achieved": w_bytes / t_wf / 1e9, "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -115,6 +120,8 @@ def main():
     ap.add_argument("--no-stack", action="store_true", help="skip the 12-layer stack measurement (rt_stack_prefill)")
     ap.add_argument("--stack-only", action="store_true",
                     help="only the 12-layer stack through rt_stack_prefill (for profiling): prints its section alone")
+    ap.add_argument("--stack-layers", type=int, default=0, help="with --stack-only: number of layers (default: the workload's 12)")
+    ap.add_argument("--stack-positions", type=int, default=0, help="with --stack-only: sequence length (default: the workload's 4096)")
     ap.add_argument("--cpu-sample-positions", type=int, default=2048)
     ap.add_argument("--traffic-calibration", action="store_true",
                     help="also run one plain 256 MiB device copy, the reference the rocprofv3 FETCH_SIZE / WRITE_SIZE "
@@ -138,7 +145,8 @@ def main():
         del big, big2
     if args.stack_only:
         print(json.dumps({"stack_wavefront": stack_section(torch.cuda.current_stream(), layer_by_layer=False,
-                                                           reps=args.steps, alibi=args.alibi)}))
+                                                           reps=args.steps, alibi=args.alibi, layers=args.stack_layers,
+                                                           positions=args.stack_positions)}))
         return
     wl = gen.WORKLOADS[args.workload]
     li = gen.make_layer_inputs(wl)
