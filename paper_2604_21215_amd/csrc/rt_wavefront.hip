@@ -217,10 +217,33 @@ __device__ __forceinline__ void mm_body(const WaveLayer &Y, int t, int block_x, 
     if (nfull > 0) { RT_WF_LOADW(wa, 0) }
     const bool do_norm = !norm_free && (EPI == EPI_W1 || EPI == EPI_KV || EPI == EPI_QKV);
     float rscale = 1.f;
-    if (do_norm)
+    if (do_norm && !(XL && EPI == EPI_QKV))
         rscale = rms_scale_from_parts((EPI == EPI_W1 ? Y.S.ssq_h : (EPI == EPI_KV ? Y.S.ssq_z : Y.S.ssq_x)) + (size_t)b0 * (d / 16),
                                       cb, g, d / 16, d, eps);
-    if (XL) {
+    if (XL && EPI == EPI_QKV) {
+        // a decoding step's input rows x_t [B][d] (Y.x, rows d apart) become the operand rows right here: head + remainder of
+        // x * g_attn, and the 1/rms of x from sums that meet in LDS (no separate preparation launch)
+        if (tid < 16) hss[tid] = 0.f;
+        __syncthreads();
+        const bf16_t *xin = (const bf16_t *)Y.x;
+        const bf16_t *ga = (const bf16_t *)Y.W.g_attn;
+        const int ppr = K / 4;   // 4-element pieces per row
+        for (int p = tid; p < Bn * ppr; p += 64 * NW) {
+            const int r = p / ppr, e0 = (p - r * ppr) * 4;
+            const uint2 xr = *reinterpret_cast<const uint2 *>(xin + (size_t)(b0 + r) * d + e0);
+            float v[4] = {__uint_as_float(xr.x << 16), __uint_as_float(xr.x & 0xFFFF0000u), __uint_as_float(xr.y << 16),
+                          __uint_as_float(xr.y & 0xFFFF0000u)};
+            atomicAdd(&hss[r], (v[0] * v[0] + v[1] * v[1]) + (v[2] * v[2] + v[3] * v[3]));
+            if (ga && !norm_free) {
+                const uint2 gr = *reinterpret_cast<const uint2 *>(ga + e0);
+                v[0] *= __uint_as_float(gr.x << 16); v[1] *= __uint_as_float(gr.x & 0xFFFF0000u);
+                v[2] *= __uint_as_float(gr.y << 16); v[3] *= __uint_as_float(gr.y & 0xFFFF0000u);
+            }
+            split_store4(xs, (size_t)(2 * r) * xld + e0, (size_t)(2 * r + 1) * xld + e0, v);
+        }
+        __syncthreads();
+        if (do_norm) rscale = rsqrtf(hss[cb] / (float)d + eps);
+    } else if (XL) {
         const int ppr = K / 8;   // 16-byte pieces per operand row
         for (int p = tid; p < 2 * Bn * ppr; p += 64 * NW) {
             const int r = p / ppr, c = p - r * ppr;
@@ -729,6 +752,14 @@ template hipError_t wavefront_prefill<bf16_t>(const LayerDims &, const WaveLayer
 // ---------------------------------------------------------------------------------------------
 bool step_mm_supported(const LayerDims &D, bool mfma_bf16) { return wavefront_uses_matrix_cores(D.d, D.F, mfma_bf16); }
 
+// whether step_mm_launch<EPI, ., NW> stages the operand rows in LDS for these dimensions
+template <int EPI, int NW> static bool step_mm_stages(const LayerDims &D)
+{
+    const int K = EPI == EPI_W2 ? D.F : D.d;
+    const int Bt = D.B < kMmBatch ? D.B : kMmBatch;
+    return (size_t)NW * 1024 + 256 + (size_t)2 * Bt * (K + 8) * 2 <= (size_t)144 * 1024;
+}
+
 template <int EPI, int KS, int NW>
 static hipError_t step_mm_launch(const WaveLayer &Y, int n_out, const LayerDims &D, hipStream_t st)
 {
@@ -769,8 +800,11 @@ static WaveLayer step_layer(const Weights &W, const Scratch &S, const void *x_t,
 // raw [q | k_tmp | v_tmp] of the rows x_t [B][d] into S.qkv_raw
 hipError_t step_qkv_mm(const LayerDims &D, const Weights &W, const Scratch &S, const void *x_t, size_t x_stride, hipStream_t st)
 {
-    hipLaunchKernelGGL(step_prep_kernel, dim3((unsigned)((D.d + 1023) / 1024), (unsigned)D.B), dim3(256), 0, st, (const bf16_t *)x_t,
-                       x_stride, (const bf16_t *)W.g_attn, S.op_x, S.ssq_x, D.d, D.norm_free);
+    if (x_stride != (size_t)D.d) return hipErrorInvalidValue;   // the products address the rows of x_t d apart
+    // operand rows that fit LDS: the product's workgroups prepare their operand rows themselves
+    if (!step_mm_stages<EPI_QKV, 4>(D))
+        hipLaunchKernelGGL(step_prep_kernel, dim3((unsigned)((D.d + 1023) / 1024), (unsigned)D.B), dim3(256), 0, st, (const bf16_t *)x_t,
+                           x_stride, (const bf16_t *)W.g_attn, S.op_x, S.ssq_x, D.d, D.norm_free);
     const WaveLayer Y = step_layer(W, S, x_t, nullptr, nullptr, nullptr);
     return step_mm_launch<EPI_QKV, 4, 4>(Y, 3 * D.d, D, st);
 }
