@@ -847,10 +847,12 @@ hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S,
     Wp.g_attn = W.g_kv;
     hipError_t e = Launch<bf16_t>::prepass(D, W, S, x, B, N, true, st);   // q and temporary pairs of every position
     if (e != hipSuccess) return e;
+    // the temporary pairs of ALL positions go into the cache rows at once: a block reads rows below its own end only, and its
+    // rows receive the persistent pairs when it is done
+    hipLaunchKernelGGL(par_export_tile_kernel, dim3(BH, (N + 63) / 64), dim3(256), 0, st, (const bf16_t *)S.Kt, S.Ktf,
+                       (const bf16_t *)S.Vt, (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, N);
     for (int t0 = 0; t0 < N; t0 += Sblk) {
         const int nr = Sblk < N - t0 ? Sblk : N - t0;
-        hipLaunchKernelGGL(par_export_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Kt, S.Ktf, (const bf16_t *)S.Vt,
-                           (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, t0);
         hipLaunchKernelGGL(par_merge_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Q, S.Qf, (const bf16_t *)S.Kt, S.Ktf,
                            (const bf16_t *)S.Vt, (const bf16_t *)K, S.Klo, (const bf16_t *)V, S.pm, S.pl, S.po, a_b, BH, D.H, N,
                            D.p_min, D.log2_pmin, S.levels, S.slots, D.scale, D.alibi, t0);
