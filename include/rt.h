@@ -148,8 +148,8 @@ rt_status rt_layer_recompute(rt_ctx *ctx, const rt_layer_weights *w, const void 
 rt_status rt_transformer_layer(rt_ctx *ctx, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, void *y,
                                void *K, void *V, int32_t kv_cap);
 
-/* Blocked recurrence, the extension the paper's Discussion (Sec. 8) names in one sentence ("recurrence executed over
- * blocks of steps, yielding a controllable trade-off between recurrent depth and training speed").  Reading taken: the
+/* Blocked recurrence, the extension the paper's Discussion (Sec. 8) names in one sentence: the recurrence advances by
+ * blocks of positions instead of single positions, so that the block length trades depth in time for speed.  Reading taken: the
  * positions are cut into blocks of `block`; position i attends the persistent pairs k_j, v_j = proj(RMS(z_j)) of the
  * positions j in EARLIER blocks and the temporary pairs (from the layer input) of the positions of its OWN block up
  * to and including itself.  Inside a block this is the Transformer layer of Sec. 2.1, across blocks the RT layer of

@@ -227,6 +227,11 @@ struct PreOut {   // PG_PRE only
     bf16_t *Q, *Kt, *Vt;
     float *Qf, *Ktf;
     int H, Bc;
+    // y0: first column block ([q heads | k heads | v heads]): H skips the queries.  With K set the pairs go straight into the
+    // cache rows (K, its bf16 remainder Klo, V and the transposed copy VT) instead of the pre-pass buffers.
+    int y0;
+    bf16_t *K, *Klo, *V, *VT;
+    int vt_stride;
 };
 
 template <int EPI, int NWV>
@@ -244,7 +249,8 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
     const int m0 = blockIdx.x * 64, nb0 = blockIdx.y * 64;
     const bf16_t *Wt = W;
     if (EPI == PG_PRE) {
-        const int which = (int)blockIdx.y / po.H, h = (int)blockIdx.y % po.H;
+        const int by = (int)blockIdx.y + po.y0;
+        const int which = by / po.H, h = by % po.H;
         Wt = (which == 0 ? po.Wq : (which == 1 ? po.Wk : po.Wv)) + (size_t)h * kHeadDim * K - (size_t)nb0 * K;
     }
     const int klen = K / NWV, kbeg = kw * klen;
@@ -357,7 +363,8 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
         rs = rsqrtf(tot / (float)K + eps);
     }
     if (EPI == PG_PRE) {
-        const int which = (int)blockIdx.y / po.H, h = (int)blockIdx.y % po.H;
+        const int by = (int)blockIdx.y + po.y0;
+        const int which = by / po.H, h = by % po.H;
         float ss = 0.f;
 #pragma unroll
         for (int e = 0; e < 16; ++e) { v[e] *= rs; ss = fmaf(v[e], v[e], ss); }
@@ -369,6 +376,23 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
         if (m < M) {
             const int bb = m / Nc, n = n0 + m % Nc;
             const size_t oo = ((size_t)n * po.Bc + bb) * K + h * kHeadDim + qc;   // the projection is square: row length = K = d
+            if (po.K != nullptr && which > 0) {   // straight into the cache: the rows of the pre-pass buffers are laid out like it
+                bf16_t *vt = po.VT + ((size_t)(bb * po.H + h) * kHeadDim + qc) * po.vt_stride + n;
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    float val = v[e] * sc;
+                    if (qk && gn) val *= bf16_to_f32(gn[h * kHeadDim + qc + e]);
+                    const bf16_t r = f32_to_bf16(val);
+                    if (which == 1) {
+                        po.K[oo + e] = r;
+                        po.Klo[oo + e] = f32_to_bf16(val - bf16_to_f32(r));
+                    } else {
+                        po.V[oo + e] = r;
+                        vt[(size_t)e * po.vt_stride] = r;
+                    }
+                }
+                return;
+            }
             bf16_t *dst = which == 0 ? po.Q : (which == 1 ? po.Kt : po.Vt);
             float *dstf = which == 0 ? po.Qf : (which == 1 ? po.Ktf : nullptr);
 #pragma unroll
@@ -728,15 +752,21 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
 constexpr int kSmallM = 2048;   // up to this many rows the split-contraction kernel is used (it is 1.4x slower at 16384 rows)
 
 // the pre-pass projection of positions n0 .. n0 + Nc - 1 of every batch row of `src` with the split-contraction kernel
-static hipError_t small_prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *src, int n0, int Nc, hipStream_t st)
+// pairs_to: the caller's K (with V): only the pairs are projected and they go straight into the cache rows and their copies
+static hipError_t small_prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *src, int n0, int Nc, hipStream_t st,
+                                void *pairs_K = nullptr, void *pairs_V = nullptr)
 {
-    PreOut po;
+    PreOut po = {};
     po.Wq = (const bf16_t *)W.Wq; po.Wk = (const bf16_t *)W.Wk; po.Wv = (const bf16_t *)W.Wv;
     po.g_q = (const bf16_t *)W.g_q; po.g_k = (const bf16_t *)W.g_k;
     po.Q = (bf16_t *)S.Q; po.Kt = (bf16_t *)S.Kt; po.Vt = (bf16_t *)S.Vt; po.Qf = S.Qf; po.Ktf = S.Ktf;
     po.H = D.H; po.Bc = D.B;
+    if (pairs_K) {
+        po.y0 = D.H;
+        po.K = (bf16_t *)pairs_K; po.V = (bf16_t *)pairs_V; po.Klo = S.Klo; po.VT = S.VT; po.vt_stride = S.vt_stride;
+    }
     const int M = D.B * Nc;
-    return blk_gemm_launch<PG_PRE>(dim3((unsigned)((M + 63) / 64), (unsigned)(3 * D.H)), st, (const bf16_t *)src, nullptr, M, 3 * D.d,
+    return blk_gemm_launch<PG_PRE>(dim3((unsigned)((M + 63) / 64), (unsigned)((pairs_K ? 2 : 3) * D.H)), st, (const bf16_t *)src, nullptr, M, 3 * D.d,
                                    D.d, Nc, D.N, n0, (const bf16_t *)W.g_attn, D.eps, D.norm_free, D.alpha, nullptr, nullptr,
                                    nullptr, nullptr, po);
 }
@@ -858,11 +888,15 @@ hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S,
                            D.p_min, D.log2_pmin, S.levels, S.slots, D.scale, D.alibi, t0);
         block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, S.rinv, t0, nr, st);
         // persistent pairs of the block from its outputs (rows t0.. of the pre-pass buffers are free again)
-        if (B * nr <= kSmallM && d % 128 == 0) e = small_prepass(D, Wp, S, y, t0, nr, st);
-        else e = Launch<bf16_t>::prepass(D, Wp, S, y, B, nr, true, st, (size_t)N * d, t0);
-        if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(par_export_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Kt, S.Ktf, (const bf16_t *)S.Vt,
-                           (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, t0);
+        if (B * nr <= kSmallM && d % 128 == 0) {
+            e = small_prepass(D, Wp, S, y, t0, nr, st, K, V);   // pairs only, written into the cache by the product's epilogue
+            if (e != hipSuccess) return e;
+        } else {
+            e = Launch<bf16_t>::prepass(D, Wp, S, y, B, nr, true, st, (size_t)N * d, t0);
+            if (e != hipSuccess) return e;
+            hipLaunchKernelGGL(par_export_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Kt, S.Ktf, (const bf16_t *)S.Vt,
+                               (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, t0);
+        }
         const int t1 = t0 + nr;
         const int P = t1 & -t1;
         if (P >= D.p_min && t1 < N) {
