@@ -128,3 +128,16 @@ def test_chunked_schedule_of_the_layer_wavefront_engine_covers_every_pair_once(N
         assert (cover[i, 1:i] == 1).all() and (cover[i, i:] == 0).all(), i
     assert binding.load().rt_schedule_events_chunked(16, 32, 16, None, 0) == -1     # chunk < p_min
     assert binding.load().rt_schedule_events_chunked(16, 4, 24, None, 0) == -1      # not a power of two
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py runs on exactly one GPU: --gpus N with N > 1 ends with a message and a non-zero status before anything
+    touches a device."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], stdout=subprocess.PIPE,
+                       stderr=subprocess.PIPE, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr and r.stdout.strip() == ""
