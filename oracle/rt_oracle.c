@@ -292,7 +292,7 @@ int rto_layer_prefill(const rto_params *p, const double *x, int B, int N, double
     if (make_tw(p, &w)) return -2;
     const int d = p->d, H = p->H;
     const int nt = pick_threads(p);
-    const int outer = (B >= nt || B >= 4) && nt > 1; /* batch rows in parallel */
+    const int outer = B >= 2 && nt > 1;              /* batch rows in parallel (one thread per sequence) */
     const int inner = !outer && nt > 1 && d >= 256;  /* else split matrix rows */
     rto_ws *ws = (rto_ws *)calloc((size_t)B, sizeof(rto_ws));
     int err = ws ? 0 : -2;

@@ -506,6 +506,10 @@ def test_thread_modes_bit_identical(oracle):
     x8 = np.concatenate([x] * 4, axis=0)
     got8 = oracle.Layer(w, 4, threads=4).prefill(x8)
     np.testing.assert_array_equal(got8[0][:2], ref[0])
+    # a single sequence: the matrix rows are split over the threads instead of the batch rows
+    got1 = oracle.Layer(w, 4, threads=4).prefill(x[:1])
+    np.testing.assert_array_equal(got1[0], ref[0][:1])
+    np.testing.assert_array_equal(got1[1], ref[1][:, :1])
 
 
 # ------------------------------------------------------------------------------------------
@@ -695,3 +699,36 @@ def test_p13_blocked_recurrence(oracle, S, beta):
         np.testing.assert_allclose(V[:, b], Vp, rtol=1e-10, atol=1e-11)
     # the first block sees no persistent pair at all: it is the Transformer layer on those positions
     np.testing.assert_allclose(y[:, :S], yT[:, :S], rtol=1e-12, atol=1e-13)
+
+
+# ------------------------------------------------------------------------------------------
+# Conditioning of the exact map on the stack workload's first-layer input (a property of the definition of
+# Sec. 2.2, measured on the oracle alone).  With embedding entries ~ N(0, 0.02^2) fed to the layer as they are and the
+# paper's unscaled logits, z = x + branch is dominated by the branch, every persistent key is a normalised copy of
+# it, the softmax over logits of standard deviation 8 is sharp, and a relative input perturbation of one bf16
+# rounding (2^-9) comes out amplified far beyond the 2e-2 the GPU path is held to - so no finite-precision
+# evaluation can be compared with the oracle at a tolerance there.  The same table with logits scaled by 1/8, and
+# the table multiplied by 50 (entries ~ N(0, 1), like x in the single-layer workloads), are benign.  The GPU parity
+# tests of the stack run on the two benign variants for this reason.
+# ------------------------------------------------------------------------------------------
+def test_stack_workload_conditioning_literal_table_vs_benign_variants(oracle):
+    wl = gen.WORKLOADS["cfg5"]
+    B, N = 2, 64
+    ids = gen.make_token_ids(wl)[:B, :N]
+    table = gen.make_embedding_tables(wl)["embedding"].astype(np.float64)
+    w = {k: v.astype(np.float64) for k, v in gen.make_layer_weights(wl.seed, 0, wl.d, wl.F, wl.dtype).items()}
+    rel = 2.0 ** -9
+    noise = 1.0 + np.random.default_rng(11).uniform(-rel, rel, (B, N, wl.d))
+
+    def amplification(mult, attn_scale):
+        lay = oracle.Layer(w, wl.H, alpha=wl.resid_scale, eps=1e-6, attn_scale=attn_scale)
+        x = oracle.embed(table * mult, ids)
+        y0, y1 = lay.prefill(x)[0], lay.prefill(x * noise)[0]
+        err = np.linalg.norm(y1 - y0, axis=-1) / np.linalg.norm(y0, axis=-1)
+        return err.max(axis=0) / rel          # curve over the position
+
+    literal = amplification(1.0, 1.0)
+    assert literal[0] < 3.0                    # a single position: one softmax weight, nothing to amplify
+    assert literal[32:].max() > 10.0, literal[32:].max()
+    assert amplification(50.0, 1.0).max() < 3.0
+    assert amplification(1.0, 0.125).max() < 3.0
