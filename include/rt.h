@@ -22,9 +22,13 @@
  * smaller than the context's p_min are instead attended directly when each query is finished
  * (Algorithm 1's free "query tile size" parameter); results do not depend on p_min beyond rounding.
  *
- * All pointers named "device" are device (HBM) addresses valid on rt_config.device; everything is
- * enqueued on rt_config.stream and the calls return without synchronising.  The caller owns x, y,
- * K, V and the weights; the context owns only scratch memory.  No exceptions cross this boundary.
+ * All pointers named "device" are device (HBM) addresses valid on rt_config.device.  The calls return
+ * without synchronising, and their work is ordered on rt_config.stream: it starts after everything
+ * enqueued there before the call, and whatever is enqueued there after the call sees its outputs.
+ * Every entry point enqueues on that stream alone except rt_stack_prefill, which may put half of its
+ * layers on a second stream the context owns, forked from and joined back into rt_config.stream by
+ * events inside the call (see there).  The caller owns x, y, K, V and the weights; the context owns
+ * only scratch memory.  No exceptions cross this boundary.
  */
 #ifndef RT_H_
 #define RT_H_
@@ -101,9 +105,27 @@ rt_status rt_layer_prefill(rt_ctx *ctx, const rt_layer_weights *w, const void *x
 /* One position of the same recurrence over a caller-held cache (Sec. 7.3: decoding attends over the
  * cached persistent pairs like a Transformer).
  *   x_t [B, d] device; t is 0-based: rows 0..t-1 of K, V are valid, row t is written; y_t [B, d].
- *   0 <= t < kv_cap, t < max_seq.  N successive decode steps equal one prefill of length N. */
+ *   0 <= t < kv_cap, t < max_seq.  N successive decode steps equal one prefill of length N.
+ *   x_t, y_t, K and V must not overlap one another (RT_ERR_INVALID_ARG, nothing enqueued). */
 rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t, void *y_t,
                          void *K, void *V, int32_t kv_cap);
+
+/* rt_decode_step for callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  No context is needed and nothing is allocated or freed, on the device or through any
+ * allocating library routine: the step's scratch (the position's query and temporary pair, one partial softmax state per
+ * 64 cached keys, the vectors between the base case's products) is a static device array of RT_STATIC_SCRATCH_BYTES that
+ * every device the library runs on holds until the process ends.  Same kernels, same arguments, same results as
+ * rt_decode_step on a context created from *cfg (cfg->max_batch and cfg->max_seq still bound B and t; cfg->stream is the
+ * stream the step is enqueued on).
+ *   Limit: the scratch of the call, about B (66 n_heads ceil(t / 64) + 11 d_model + 3 d_hidden) 4 bytes, must fit the
+ *   array (d_model 1024, d_hidden 4096, B = 8: t < 16000); a larger call returns RT_ERR_INVALID_ARG and enqueues
+ *   nothing.  rt_last_error(NULL) gives the reason of the calling thread's last failed call.
+ *   All calls on one device share the one array, which keeps the previous call's contents (every word a step reads it
+ *   has written before, so nothing is cleared): two steps that overlap in time on one device - different streams,
+ *   different threads - race.  Steps enqueued on one stream are ordered and safe. */
+#define RT_STATIC_SCRATCH_BYTES (8u << 20)
+rt_status rt_decode_step_static(const rt_config *cfg, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t,
+                                void *y_t, void *K, void *V, int32_t kv_cap);
 
 /* Whole-sequence forward of a stack of L layers, layer l + 1 reading layer l's output (Sec. 2: the layers of a
  * model are stacked; Sec. 2.2: each RT layer has its own persistent key-value memory).  Same results as L
@@ -179,7 +201,8 @@ rt_status rt_lm_head(rt_ctx *ctx, const void *W_lm, const void *g_final, int32_t
 /* Waits for nothing: the caller synchronises the stream first.  Frees scratch.  NULL is allowed. */
 rt_status rt_destroy(rt_ctx *ctx);
 
-/* Text of the last error on this context (owned by the context), or a static string for ctx == NULL. */
+/* Text of the last error on this context (owned by the context).  ctx == NULL: the reason of the calling thread's last
+ * failed rt_decode_step_static call, or a static string if there was none. */
 const char *rt_last_error(const rt_ctx *ctx);
 
 const char *rt_status_string(rt_status s);

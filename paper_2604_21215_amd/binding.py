@@ -24,7 +24,7 @@ EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
            "rt_version", "rt_phase_trace", "rt_schedule_events_shifted", "rt_embed_rows", "rt_lm_head", "rt_cross_block_event",
            "rt_stack_prefill", "rt_schedule_events_chunked", "rt_layer_recompute", "rt_transformer_layer",
-           "rt_layer_prefill_blocked")
+           "rt_layer_prefill_blocked", "rt_decode_step_static")
 
 
 class rt_config(C.Structure):
@@ -114,6 +114,9 @@ def load():
     L.rt_layer_prefill_blocked.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_void_p, C.c_int32, C.c_int32, C.c_int32,
                                            C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
     L.rt_layer_prefill_blocked.restype = C.c_int
+    L.rt_decode_step_static.argtypes = [C.POINTER(rt_config), C.POINTER(rt_layer_weights), C.c_void_p, C.c_int32, C.c_int32,
+                                        C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
+    L.rt_decode_step_static.restype = C.c_int
     _lib = L
     return L
 
@@ -126,6 +129,21 @@ def _check(L, ctx, rc):
 
 def _ptr(t):
     return C.c_void_p(0 if t is None else t.data_ptr())
+
+
+def rt_decode_step_static(cfg: rt_config, weights: rt_layer_weights, x_t, t, y_t, K, V):
+    """rt_decode_step_static(cfg, w, x_t[B,d], B, t, y_t, K, V, kv_cap): the decoding step without a context."""
+    L = load()
+    rc = L.rt_decode_step_static(C.byref(cfg), C.byref(weights), _ptr(x_t), x_t.shape[0], int(t), _ptr(y_t), _ptr(K), _ptr(V),
+                                 K.shape[0])
+    if rc != RT_OK:
+        raise RTError(L.rt_status_string(rc).decode(), L.rt_last_error(None).decode())
+
+
+def raw_decode_static(cfg, weights, x_ptr, B, t, y_ptr, K_ptr, V_ptr, kv_cap) -> int:
+    """Status code of rt_decode_step_static on raw addresses (error-path tests)."""
+    return load().rt_decode_step_static(C.byref(cfg), C.byref(weights), C.c_void_p(x_ptr), B, t, C.c_void_p(y_ptr),
+                                        C.c_void_p(K_ptr), C.c_void_p(V_ptr), kv_cap)
 
 
 def make_weights(w: dict) -> rt_layer_weights:

@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -126,6 +127,37 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
     return off;
 }
 
+// Checks every field of a configuration that does not need the device; p_min and the kernel family it selects are returned.
+static rt_status validate_config(const rt_config *cfg, int *p_min_out, bool *mfma_out)
+{
+    if (cfg->d_model <= 0 || cfg->n_heads <= 0 || cfg->head_dim <= 0 || cfg->d_hidden <= 0 || cfg->max_batch <= 0 ||
+        cfg->max_seq <= 0 || (int64_t)cfg->n_heads * cfg->head_dim != cfg->d_model)
+        return RT_ERR_INVALID_ARG;
+    if (cfg->dtype != RT_F32 && cfg->dtype != RT_BF16) return RT_ERR_INVALID_ARG;
+    if (cfg->head_dim != kHeadDim || cfg->d_hidden % 8 != 0) return RT_ERR_UNSUPPORTED;
+    if (cfg->max_seq > (1 << 20) || cfg->max_batch > 1024) return RT_ERR_UNSUPPORTED;
+    if ((cfg->flags & RT_FLAG_ENGINE_STEPWISE) && (cfg->flags & RT_FLAG_ENGINE_PERSISTENT)) return RT_ERR_INVALID_ARG;
+    const bool mfma = cfg->dtype == RT_BF16 && !(cfg->flags & RT_FLAG_NO_MFMA);
+    const int p_min = cfg->p_min == 0 ? 32 : cfg->p_min;
+    if (!is_pow2(p_min) || p_min > 1024 || (mfma && p_min < 32)) return RT_ERR_INVALID_ARG;
+    if (!(cfg->rms_eps >= 0.f) || !(cfg->attn_scale == cfg->attn_scale) || !(cfg->resid_scale == cfg->resid_scale))
+        return RT_ERR_INVALID_ARG;
+    if (!(cfg->alibi_max_bias >= 0.f) || !(cfg->alibi_max_bias <= 1024.f)) return RT_ERR_INVALID_ARG;
+    *p_min_out = p_min;
+    *mfma_out = mfma;
+    return RT_OK;
+}
+
+static void fill_dims(LayerDims &D, const rt_config &cfg, int p_min)
+{
+    D.B = 0; D.N = 0; D.kv_cap = 0;
+    D.d = cfg.d_model; D.H = cfg.n_heads; D.F = cfg.d_hidden;
+    D.p_min = p_min; D.log2_pmin = ilog2(p_min);
+    D.alpha = cfg.resid_scale; D.scale = cfg.attn_scale; D.eps = cfg.rms_eps;
+    D.norm_free = (cfg.flags & RT_FLAG_NORM_FREE) ? 1 : 0;
+    D.alibi = cfg.alibi_max_bias;
+}
+
 extern "C" {
 
 int32_t rt_version(void) { return 100; }
@@ -207,19 +239,10 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
 {
     if (out) *out = nullptr;
     if (!cfg || !out) return RT_ERR_INVALID_ARG;
-    if (cfg->d_model <= 0 || cfg->n_heads <= 0 || cfg->head_dim <= 0 || cfg->d_hidden <= 0 || cfg->max_batch <= 0 ||
-        cfg->max_seq <= 0 || (int64_t)cfg->n_heads * cfg->head_dim != cfg->d_model)
-        return RT_ERR_INVALID_ARG;
-    if (cfg->dtype != RT_F32 && cfg->dtype != RT_BF16) return RT_ERR_INVALID_ARG;
-    if (cfg->head_dim != kHeadDim || cfg->d_hidden % 8 != 0) return RT_ERR_UNSUPPORTED;
-    if (cfg->max_seq > (1 << 20) || cfg->max_batch > 1024) return RT_ERR_UNSUPPORTED;
-    if ((cfg->flags & RT_FLAG_ENGINE_STEPWISE) && (cfg->flags & RT_FLAG_ENGINE_PERSISTENT)) return RT_ERR_INVALID_ARG;
-    const bool mfma = cfg->dtype == RT_BF16 && !(cfg->flags & RT_FLAG_NO_MFMA);
-    int p_min = cfg->p_min == 0 ? 32 : cfg->p_min;
-    if (!is_pow2(p_min) || p_min > 1024 || (mfma && p_min < 32)) return RT_ERR_INVALID_ARG;
-    if (!(cfg->rms_eps >= 0.f) || !(cfg->attn_scale == cfg->attn_scale) || !(cfg->resid_scale == cfg->resid_scale))
-        return RT_ERR_INVALID_ARG;
-    if (!(cfg->alibi_max_bias >= 0.f) || !(cfg->alibi_max_bias <= 1024.f)) return RT_ERR_INVALID_ARG;
+    int p_min = 0;
+    bool mfma = false;
+    const rt_status vs = validate_config(cfg, &p_min, &mfma);
+    if (vs != RT_OK) return vs;
 
     int ndev = 0;
     if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return RT_ERR_HIP;
@@ -232,12 +255,7 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
     c->stream = (hipStream_t)cfg->stream;
     c->use_mfma = mfma;
     LayerDims &D = c->base;
-    D.B = 0; D.N = 0; D.kv_cap = 0;
-    D.d = cfg->d_model; D.H = cfg->n_heads; D.F = cfg->d_hidden;
-    D.p_min = p_min; D.log2_pmin = ilog2(p_min);
-    D.alpha = cfg->resid_scale; D.scale = cfg->attn_scale; D.eps = cfg->rms_eps;
-    D.norm_free = (cfg->flags & RT_FLAG_NORM_FREE) ? 1 : 0;
-    D.alibi = cfg->alibi_max_bias;
+    fill_dims(D, c->cfg, p_min);
 
     const size_t E = cfg->dtype == RT_BF16 ? 2 : 4;
     const size_t Bm = cfg->max_batch, Nm = cfg->max_seq, d = cfg->d_model, F = cfg->d_hidden, H = cfg->n_heads;
@@ -294,7 +312,8 @@ rt_status rt_destroy(rt_ctx *c)
     return e == hipSuccess ? RT_OK : RT_ERR_HIP;
 }
 
-const char *rt_last_error(const rt_ctx *c) { return c ? c->err.c_str() : kNoCtx; }
+static const char *static_last_error();
+const char *rt_last_error(const rt_ctx *c) { return c ? c->err.c_str() : static_last_error(); }
 uint64_t rt_workspace_bytes(const rt_ctx *c)
 {
     return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) + c->stack_bytes + c->par_bytes : 0;
@@ -483,26 +502,129 @@ static rt_status decode_impl(rt_ctx *c, const LayerDims &D, const rt_layer_weigh
     return RT_OK;
 }
 
+// Host-side argument checks of a decoding step (both entry points); msg receives the reason.
+static rt_status check_decode_args(const rt_config &cfg, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t,
+                                   const void *y_t, const void *K, const void *V, int32_t kv_cap, const char **msg)
+{
+    *msg = "";
+    if (!w || !w->Wq || !w->Wk || !w->Wv || !w->Wo || !w->W1 || !w->W2) { *msg = "null weight pointer"; return RT_ERR_INVALID_ARG; }
+    if (!x_t || !y_t || !K || !V) { *msg = "null tensor pointer"; return RT_ERR_INVALID_ARG; }
+    if (B < 1 || B > cfg.max_batch) { *msg = "B out of range [1, max_batch]"; return RT_ERR_INVALID_ARG; }
+    if (t < 0 || t >= kv_cap) { *msg = "t out of range [0, kv_cap)"; return RT_ERR_INVALID_ARG; }
+    if (t >= cfg.max_seq) { *msg = "t out of range [0, max_seq)"; return RT_ERR_INVALID_ARG; }
+    const size_t E = cfg.dtype == RT_BF16 ? 2 : 4;
+    const size_t xb = (size_t)B * cfg.d_model * E, kvb = (size_t)kv_cap * B * cfg.d_model * E;
+    if (ranges_overlap(x_t, xb, y_t, xb)) { *msg = "x_t and y_t overlap"; return RT_ERR_INVALID_ARG; }
+    if (ranges_overlap(K, kvb, V, kvb) || ranges_overlap(K, kvb, y_t, xb) || ranges_overlap(V, kvb, y_t, xb) ||
+        ranges_overlap(K, kvb, x_t, xb) || ranges_overlap(V, kvb, x_t, xb)) {
+        *msg = "K, V, x_t, y_t must not overlap";
+        return RT_ERR_INVALID_ARG;
+    }
+    return RT_OK;
+}
+
 extern "C" rt_status rt_decode_step(rt_ctx *c, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t, void *y_t,
                                     void *K, void *V, int32_t kv_cap)
 {
     if (!c) return RT_ERR_INVALID_ARG;
     if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
-    rt_status s = check_weights(c, w);
-    if (s != RT_OK) return s;
-    if (!x_t || !y_t || !K || !V) return fail(c, RT_ERR_INVALID_ARG, "null tensor pointer%s");
-    if (B < 1 || B > c->cfg.max_batch) return fail(c, RT_ERR_INVALID_ARG, "B out of range [1, max_batch]%s");
-    if (t < 0 || t >= kv_cap) return fail(c, RT_ERR_INVALID_ARG, "t out of range [0, kv_cap)%s");
+    const char *msg;
+    rt_status s = check_decode_args(c->cfg, w, x_t, B, t, y_t, K, V, kv_cap, &msg);
+    if (s != RT_OK) return fail(c, s, "%s", msg);
     if ((t + 63) / 64 > c->S.slots) return fail(c, RT_ERR_INVALID_ARG, "t too large for this context's max_seq%s");
-    const size_t E = c->cfg.dtype == RT_BF16 ? 2 : 4;
-    const size_t xb = (size_t)B * c->cfg.d_model * E;
-    if (ranges_overlap(x_t, xb, y_t, xb)) return fail(c, RT_ERR_INVALID_ARG, "x_t and y_t overlap%s");
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
     LayerDims D = c->base;
     D.B = B; D.N = 1; D.kv_cap = kv_cap;
     c->engine = "stepwise";
     if (c->cfg.dtype == RT_BF16) return decode_impl<bf16_t>(c, D, w, x_t, t, y_t, K, V);
     return decode_impl<float>(c, D, w, x_t, t, y_t, K, V);
+}
+
+// ------------------------------------------------------------------------------------------------------------
+// The decoding step for callers that cannot allocate (rt_decode_step_static): no context, no hipMalloc.  Its
+// scratch - the position's q and temporary pair, the split-attention partial states, the vectors between the base
+// case's products - lives in this file-scope device array; each device holds its own copy at its own address,
+// looked up once per device and kept.  The array's name is only a host-side handle: host code passes the looked-up
+// address, never the name.
+// ------------------------------------------------------------------------------------------------------------
+constexpr size_t kStaticScratchBytes = RT_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kStaticMaxDevices = 64;
+static std::mutex g_static_mu;
+static void *g_static_ptr[kStaticMaxDevices];   // device address of `scratch` on device i, or null before its first use
+static thread_local char g_static_err[256];      // reason of the last failed context-free call on this thread
+
+// Device address of the static scratch on `device` (made current by the caller).
+static rt_status static_scratch_address(int device, void **out)
+{
+    if (device < 0 || device >= kStaticMaxDevices) return RT_ERR_UNSUPPORTED;
+    std::lock_guard<std::mutex> lock(g_static_mu);
+    if (!g_static_ptr[device]) {
+        void *p = nullptr;
+        const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) {
+            (void)hipGetLastError();
+            snprintf(g_static_err, sizeof(g_static_err), "hipGetSymbolAddress: %s", hipGetErrorString(e));
+            return RT_ERR_HIP;
+        }
+        g_static_ptr[device] = p;
+    }
+    *out = g_static_ptr[device];
+    return RT_OK;
+}
+
+static const char *static_last_error() { return g_static_err[0] ? g_static_err : kNoCtx; }
+
+static rt_status static_fail(rt_status s, const char *msg)
+{
+    snprintf(g_static_err, sizeof(g_static_err), "%s", msg);
+    return s;
+}
+
+extern "C" rt_status rt_decode_step_static(const rt_config *cfg, const rt_layer_weights *w, const void *x_t, int32_t B,
+                                           int32_t t, void *y_t, void *K, void *V, int32_t kv_cap)
+{
+    g_static_err[0] = 0;
+    if (!cfg) return static_fail(RT_ERR_INVALID_ARG, "null configuration");
+    int p_min = 0;
+    bool mfma = false;
+    rt_status s = validate_config(cfg, &p_min, &mfma);
+    if (s != RT_OK) return static_fail(s, "invalid or unsupported configuration");
+    const char *msg;
+    s = check_decode_args(*cfg, w, x_t, B, t, y_t, K, V, kv_cap, &msg);
+    if (s != RT_OK) return static_fail(s, msg);
+    // the scratch of this call: one position's rows for B sequences and one partial state per split of 64 keys
+    const size_t E = cfg->dtype == RT_BF16 ? 2 : 4;
+    const int nsplit = (t + 63) / 64;
+    Scratch S;
+    const size_t need = layout_scratch(S, nullptr, (size_t)B, 1, (size_t)cfg->d_model, (size_t)cfg->d_hidden, (size_t)cfg->n_heads, E,
+                                       false, 1, nsplit > 0 ? nsplit : 1);
+    if (need > kStaticScratchBytes) {
+        snprintf(g_static_err, sizeof(g_static_err),
+                 "B, t, d_model, d_hidden need %zu bytes of scratch, the static scratch holds %zu", need, kStaticScratchBytes);
+        return RT_ERR_INVALID_ARG;
+    }
+    int ndev = 0;
+    if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev)
+        return static_fail(RT_ERR_HIP, "no such device");
+    if (hipSetDevice(cfg->device) != hipSuccess) return static_fail(RT_ERR_HIP, "hipSetDevice failed");
+    void *base = nullptr;
+    s = static_scratch_address(cfg->device, &base);
+    if (s != RT_OK) return s;
+    rt_ctx tmp;   // a context on the stack: configuration, stream and the scratch pointers, nothing owned
+    tmp.cfg = *cfg;
+    tmp.cfg.p_min = p_min;
+    tmp.stream = (hipStream_t)cfg->stream;
+    tmp.use_mfma = mfma;
+    fill_dims(tmp.base, tmp.cfg, p_min);
+    layout_scratch(tmp.S, (char *)base, (size_t)B, 1, (size_t)cfg->d_model, (size_t)cfg->d_hidden, (size_t)cfg->n_heads, E, false, 1,
+                   nsplit > 0 ? nsplit : 1);
+    LayerDims D = tmp.base;
+    D.B = B; D.N = 1; D.kv_cap = kv_cap;
+    s = cfg->dtype == RT_BF16 ? decode_impl<bf16_t>(&tmp, D, w, x_t, t, y_t, K, V) : decode_impl<float>(&tmp, D, w, x_t, t, y_t, K, V);
+    if (s != RT_OK) snprintf(g_static_err, sizeof(g_static_err), "%s", tmp.err.c_str());
+    return s;
 }
 
 extern "C" rt_status rt_embed_rows(rt_ctx *c, const void *table, int32_t vocab, const int32_t *ids, int64_t ids_stride,
