@@ -11,6 +11,7 @@ struct PersistentState {
     bool launched = false;
     void *slab = nullptr;
     size_t slab_bytes = 0;
+    size_t exchange_bytes = 0;           // leading part of the slab that holds the counters and the exchange words
     int num_cu = 0;
     int grid = 0;
     size_t lds_bytes = 0;

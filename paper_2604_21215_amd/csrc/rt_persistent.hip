@@ -131,7 +131,9 @@ struct PersistArgs {
     int max_batch;              // rows of the LDS staging area
     unsigned tag_base;          // (call nonce) << 20
     unsigned long long *bar;    // [0] fenced-barrier counter, [8] abort word
-    unsigned long long *trace;  // optional: [N][16] wall-clock stamps of workgroup 0
+    unsigned long long *trace;  // optional: [2][trace_rows][16] wall-clock stamps of workgroup 0 and of workgroup trace_wg
+    int trace_wg, trace_rows;
+    int pre_sleep;              // units of 8 x 64 clocks a bulk pull waits before its first poll
     long long spin_limit;
     float alibi;                // maximum ALiBi bias (kernels instantiated with ALIBI only)
 };
@@ -143,13 +145,21 @@ __device__ __forceinline__ void ll_store(ll_t *p, unsigned tag, unsigned payload
 }
 __device__ __forceinline__ bool ll_ok(ll_t w, unsigned tag) { return (unsigned)(w >> 32) == tag; }
 
-// Word of elements (k, k+1) of batch row b in an exchange vector of KS*32*kPW elements per row.
-// Rows are 8-16 KB apart, so the 8-byte atomic loads of one instruction (one per lane, never merged by
-// the memory pipeline) spread over many channels; a layout that packed a wavefront's loads into one
-// contiguous run was measured 1.5x slower on the widest vector.
-template <int KS> __device__ __forceinline__ size_t frag_word(int k, int b)
+// Layout of an exchange vector whose words hold element pairs (k, k+1) of kBMax batch rows: the words one producer
+// writes - GW per batch row, all batch rows of its GW*2 elements - are contiguous,
+//     word(k, b) = ((k / (2 GW)) * kBMax + b) * GW + (k / 2) % GW,
+// so that every 64- or 128-byte line of the vector is written by ONE workgroup.  Measured on MI355X (cfg3, phase
+// trace): with rows [b][k], where a line is assembled from the 16-byte pieces of eight workgroups, the h and z
+// exchanges took 4.5 us from store to staged operand, against 3.1-3.5 us for the vectors whose producers write 64
+// bytes and more in one piece.
+template <int GW> __device__ __forceinline__ size_t pair_word(int k, int b)
 {
-    return (size_t)b * (KS * 32 * kPW / 2) + (k >> 1);   // KS*32*kPW = elements per row
+    return ((size_t)(k / (2 * GW)) * kBMax + b) * GW + ((k >> 1) % GW);
+}
+// the same for vectors of one fp32 per word whose producers own R consecutive elements
+template <int R> __device__ __forceinline__ size_t single_word(int o, int b)
+{
+    return ((size_t)(o / R) * kBMax + b) * R + (o % R);
 }
 
 // Wave-uniform bounded poll of one word per lane (inactive lanes pass active = false).
@@ -198,45 +208,66 @@ __device__ __forceinline__ bool grid_barrier(const PersistArgs &A, unsigned long
 //     step s of lane (b, g) of wave w  <->  k = w*KS*32 + s*32 + 8g .. +7
 // The per-wavefront 16 x 16 tiles land in red[wave][row][b].  With SS the sum of squares of every
 // received row goes to ss_s[wave][b] (the consumer's own RMS statistic).
+// 16 bytes out of LDS through a pointer the compiler only knows as generic.  The weight slices and staged rows are
+// addressed through pointers computed once before the position loop; the compiler kept them as 64-bit generic
+// addresses and emitted flat loads (each waited for on both memory counters before its matrix instruction:
+// four dependent round trips of about 0.3 us per product).  The low 32 bits of a generic LDS address are the LDS
+// offset, so the cast below turns the access into ds_read_b128.
 typedef unsigned v4u_t __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) const v4u_t *lds_v4u_ptr_t;
+__device__ __forceinline__ uint4 lds_load16(const void *p)
+{
+    const v4u_t v = *(lds_v4u_ptr_t)(uintptr_t)p;
+    return make_uint4(v[0], v[1], v[2], v[3]);
+}
+
 constexpr int kAuxAgent = 16;   // cache-policy operand of the buffer load: sc1 (agent scope)
 
-template <int KS, bool SS = false>
-__device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, const ll_t *act, int row_words, int B,
+template <int KS, int GW, bool SS = false>
+__device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, const ll_t *act, int B,
                                            unsigned tag, const PersistArgs &A, float *red, bf16_t *act_s, int lda, int &fail,
                                            float *ss_s = nullptr)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
     constexpr int K = KS * 32 * kPW;
-    constexpr int kChunksPerRow = K / 4;            // 16-byte chunks (4 elements) per batch row
-    constexpr int kMaxChunks = kBMax * kChunksPerRow / kPThreads;   // per thread, at B = 16  (= 2 KS)
-    const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<ll_t *>(act), 0, kBMax * row_words * 8, 0x00020000);
-    const int total = B * kChunksPerRow;
+    constexpr int kWords = kBMax * K / 2;                   // words of the vector, unused batch rows included
+    constexpr int kMaxChunks = kWords / 2 / kPThreads;      // 16-byte chunks per thread  (= 2 KS)
+    const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<ll_t *>(act), 0, kWords * 8, 0x00020000);
     v4u_t v[kMaxChunks];
     unsigned need = 0;
+    // chunk c = words 2c, 2c + 1 of the layout above: batch rows b0, b1 (equal unless GW is odd) and first elements k0, k1
 #pragma unroll
     for (int i = 0; i < kMaxChunks; ++i) {
         v[i] = v4u_t{0u, 0u, 0u, 0u};
-        if (i * kPThreads + tid < total) need |= 1u << i;
+        const int w0 = 2 * (i * kPThreads + tid);
+        const int b0 = (w0 % (kBMax * GW)) / GW, b1 = ((w0 + 1) % (kBMax * GW)) / GW;
+        if (b0 < B || b1 < B) need |= 1u << i;
     }
     long long spins = 0;
+    // A poll that leaves before the producers' stores have landed costs a whole extra trip (about 1.2 us); measured,
+    // a quarter of a microsecond of waiting first brings the average number of rounds from 1.5 to 1.1.
+    for (int i = 0; i < A.pre_sleep; ++i) __builtin_amdgcn_s_sleep(8);
     while (__any(need != 0)) {
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i)
-            if (need & (1u << i)) {
-                const int c = i * kPThreads + tid;
-                const int row = c / kChunksPerRow, col = c - row * kChunksPerRow;
-                v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (row * row_words + col * 2) * 8, 0, kAuxAgent);
-            }
+            if (need & (1u << i)) v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (i * kPThreads + tid) * 16, 0, kAuxAgent);
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i)
-            if ((need & (1u << i)) && v[i][1] == tag && v[i][3] == tag) {
-                const int c = i * kPThreads + tid;
-                const int row = c / kChunksPerRow, col = c - row * kChunksPerRow;
-                *reinterpret_cast<uint2 *>(act_s + (size_t)row * lda + col * 4) = make_uint2(v[i][0], v[i][2]);
-                need &= ~(1u << i);
+            if (need & (1u << i)) {
+                const int w0 = 2 * (i * kPThreads + tid), w1 = w0 + 1;
+                const int b0 = (w0 % (kBMax * GW)) / GW, b1 = (w1 % (kBMax * GW)) / GW;
+                const int k0 = 2 * ((w0 / (kBMax * GW)) * GW + w0 % GW), k1 = 2 * ((w1 / (kBMax * GW)) * GW + w1 % GW);
+                const bool u0 = b0 < B, u1 = b1 < B;
+                if ((!u0 || v[i][1] == tag) && (!u1 || v[i][3] == tag)) {
+                    if (GW % 2 == 0) {   // both words belong to one batch row, four consecutive elements
+                        *reinterpret_cast<uint2 *>(act_s + (size_t)b0 * lda + k0) = make_uint2(v[i][0], v[i][2]);
+                    } else {
+                        if (u0) *reinterpret_cast<unsigned *>(act_s + (size_t)b0 * lda + k0) = v[i][0];
+                        if (u1) *reinterpret_cast<unsigned *>(act_s + (size_t)b1 * lda + k1) = v[i][2];
+                    }
+                    need &= ~(1u << i);
+                }
             }
         if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
     }
@@ -251,8 +282,8 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         Frag a, b;
-        a.u = has_w ? *reinterpret_cast<const uint4 *>(wrow + s * 32) : zero;
-        b.u = has_a ? *reinterpret_cast<const uint4 *>(arow + s * 32) : zero;
+        a.u = has_w ? lds_load16(wrow + s * 32) : zero;
+        b.u = has_a ? lds_load16(arow + s * 32) : zero;
         if (SS) {
             const unsigned w4[4] = {b.u.x, b.u.y, b.u.z, b.u.w};
 #pragma unroll
@@ -305,21 +336,34 @@ __device__ __forceinline__ void copy_rows_to_lds(bf16_t *dst, int ldw, const bf1
     }
 }
 
-// Bounded poll of NW words per lane, all loads issued before the first check.
+// Bounded poll of NW words per lane.  Every round re-issues all words that are still stale together and checks
+// them together, so a round costs one trip to memory however many words are late (re-polling them one after the
+// other cost one trip per late word: measured 2.3 us for the two words of a new key-value pair).
 template <int NW>
 __device__ __forceinline__ void ll_wait_n(const ll_t *const (&p)[NW], const bool (&active)[NW], unsigned tag,
                                           const PersistArgs &A, ll_t (&w)[NW], int &fail)
 {
+    bool bad[NW];
+    bool any_bad = false;
 #pragma unroll
     for (int i = 0; i < NW; ++i) w[i] = active[i] ? ll_load(p[i]) : 0;
 #pragma unroll
     for (int i = 0; i < NW; ++i) {
-        bool bad = active[i] && !ll_ok(w[i], tag);
-        long long spins = 0;
-        while (__any(bad)) {
-            if (bad) { w[i] = ll_load(p[i]); bad = !ll_ok(w[i], tag); }
-            if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
+        bad[i] = active[i] && !ll_ok(w[i], tag);
+        any_bad |= bad[i];
+    }
+    long long spins = 0;
+    while (__any(any_bad)) {
+#pragma unroll
+        for (int i = 0; i < NW; ++i)
+            if (bad[i]) w[i] = ll_load(p[i]);
+        any_bad = false;
+#pragma unroll
+        for (int i = 0; i < NW; ++i) {
+            if (bad[i]) bad[i] = !ll_ok(w[i], tag);
+            any_bad |= bad[i];
         }
+        if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
     }
 }
 
@@ -353,7 +397,8 @@ __device__ __forceinline__ void attend_lds(float q, const float *ks, const bf16_
 
 #define RT_STAMP(k)                                                                         \
     do {                                                                                    \
-        if (A.trace && wg == 0 && tid == 0) A.trace[(size_t)t * 16 + (k)] = wall_clock64(); \
+        if (A.trace && tid == 0 && (wg == 0 || wg == A.trace_wg))                            \
+            A.trace[((size_t)(wg == 0 ? 0 : A.trace_rows) + t) * 16 + (k)] = wall_clock64(); \
     } while (0)
 
 #define RT_ABORT_IF(cond)                                                                                  \
@@ -482,6 +527,9 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wg = blockIdx.x, G = A.G;
     const int d = A.d, F = A.F, B = A.B, BH = A.BH;
+    // rows per workgroup of Wo (and of the z rows it finishes), W1 and [Wk; Wv] for d = 256 KSD over 256 workgroups
+    // (the host computes the same numbers into A.R_o, A.R_1, A.R_kv)
+    constexpr int RO = 2 * ((KSD + 1) / 2), R1 = 4 * KSD, RKV = 2 * KSD;
 
     // ---- LDS carve-up
     bf16_t *wo_s = reinterpret_cast<bf16_t *>(smem);
@@ -568,10 +616,10 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     act[i] = i * 64 + lane < G;
-                    p[i] = A.zss_ll + ppar * sz_ss + (size_t)b * G + (act[i] ? i * 64 + lane : 0);
+                    p[i] = A.zss_ll + ppar * sz_ss + (size_t)(act[i] ? i * 64 + lane : 0) * kBMax + b;
                 }
-                p[4] = A.kv_ll + ppar * sz_kv + (size_t)b * 2 * d + h * kHeadDim + lane;
-                p[5] = p[4] + d;
+                p[4] = A.kv_ll + ppar * sz_kv + single_word<RKV>(h * kHeadDim + lane, b);
+                p[5] = A.kv_ll + ppar * sz_kv + single_word<RKV>(d + h * kHeadDim + lane, b);
                 act[4] = act[5] = true;
                 ll_wait_n<6>(p, act, ptag, A, w6, fail);
                 float ss = 0.f;
@@ -610,7 +658,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 const float av = o / l;
                 const float an = __shfl_down(av, 1, 64);
                 if (!(lane & 1))
-                    ll_store(A.a_ll + par * half_d + frag_word<KSD>(h * kHeadDim + lane, b), tag,
+                    ll_store(A.a_ll + par * half_d + pair_word<32>(h * kHeadDim + lane, b), tag,
                              (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
             }
         }
@@ -690,7 +738,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 
         // ================================================================ phase O:  h = x_t + alpha Wo a
         RT_STAMP(7);
-        wg_gemv_ll<KSD>(wo_s, A.ldw_d, o_n, A.a_ll + par * half_d, d / 2, B, tag, A, red, act_s, A.ldw_d, fail);
+        wg_gemv_ll<KSD, 32>(wo_s, A.ldw_d, o_n, A.a_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail);
         RT_ABORT_IF(fail);
         RT_STAMP(8);
         if (tid < kRMax * kBMax) {
@@ -699,7 +747,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             if (erow < o_n && eb < B) hv = xv + A.alpha * red_sum(red, erow, eb);
             const float hn = __shfl_down(hv, 16, 64);
             if (!(erow & 1) && erow < o_n && eb < B)
-                ll_store(A.h_ll + par * half_d + frag_word<KSD>(o, eb), tag,
+                ll_store(A.h_ll + par * half_d + pair_word<RO / 2>(o, eb), tag,
                          (unsigned)f32_to_bf16(hv) | ((unsigned)f32_to_bf16(hn) << 16));
             h_loc[erow * kBMax + eb] = hv;
         }
@@ -707,8 +755,9 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         RT_STAMP(3);
 
         // ================================================================ phase 1:  u = gelu(rinv_h * W1 h)
-        wg_gemv_ll<KSD, true>(w1_s, A.ldw_d, f_n, A.h_ll + par * half_d, d / 2, B, tag, A, red, act_s, A.ldw_d, fail, sq);
+        wg_gemv_ll<KSD, RO / 2, true>(w1_s, A.ldw_d, f_n, A.h_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail, sq);
         RT_ABORT_IF(fail);
+        RT_STAMP(11);
         if (tid < kBMax) {   // 1/rms(h) from the values this workgroup just received
             float s = 0.f;
 #pragma unroll
@@ -716,12 +765,13 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             rinv_s[tid] = A.norm_free ? 1.f : rsqrtf(s / (float)d + A.eps);
         }
         __syncthreads();
+        RT_STAMP(12);
         if (tid < kRMax * kBMax) {
             float uv = 0.f;
             if (erow < f_n && eb < B) uv = gelu_erf(red_sum(red, erow, eb) * rinv_s[eb]);
             const float un = __shfl_down(uv, 16, 64);
             if (!(erow & 1) && erow < f_n && eb < B)
-                ll_store(A.u_ll + par * half_F + frag_word<KSF>(f_lo + erow, eb), tag,
+                ll_store(A.u_ll + par * half_F + pair_word<R1 / 2>(f_lo + erow, eb), tag,
                          (unsigned)f32_to_bf16(uv) | ((unsigned)f32_to_bf16(un) << 16));
         }
         __syncthreads();
@@ -729,7 +779,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 
         // ================================================================ phase 2a:  partial W2 u over contraction block jb
         RT_STAMP(9);
-        wg_gemv_ll<KSD>(w2_s, A.ldw_d, RB, A.u_ll + par * half_F + (size_t)jb * (d / 2), F / 2, B, tag, A, red, act_s, A.ldw_d, fail);
+        wg_gemv_ll<KSD, R1 / 2>(w2_s, A.ldw_d, RB, A.u_ll + par * half_F + (size_t)jb * (kBMax * (d / 2)), B, tag, A, red, act_s,
+                                A.ldw_d, fail);
         RT_ABORT_IF(fail);
         RT_STAMP(10);
         if (tid < kRMax * kBMax && erow < RB && eb < B)
@@ -766,7 +817,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             }
             const float zn = __shfl_down(zg, 16, 64);
             if (!(erow & 1) && own)
-                ll_store(A.z_ll + par * half_d + frag_word<KSD>(o, eb), tag,
+                ll_store(A.z_ll + par * half_d + pair_word<RO / 2>(o, eb), tag,
                          (unsigned)f32_to_bf16(zg) | ((unsigned)f32_to_bf16(zn) << 16));
             sq[erow * kBMax + eb] = zv * zv;
         }
@@ -775,17 +826,17 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             float s = 0.f;
 #pragma unroll
             for (int r = 0; r < kRMax; ++r) s += sq[r * kBMax + tid];
-            if (tid < B) ll_store(A.zss_ll + par * sz_ss + (size_t)tid * G + wg, tag, __float_as_uint(s));
+            if (tid < B) ll_store(A.zss_ll + par * sz_ss + (size_t)wg * kBMax + tid, tag, __float_as_uint(s));
         }
         __syncthreads();
         RT_STAMP(5);
 
         // ================================================================ phase KV:  [Wk; Wv] (z g_kv)
         const bool pre = has_u && t + 1 < A.N;
-        wg_gemv_ll<KSD>(wkv_s, A.ldw_d, kv_n, A.z_ll + par * half_d, d / 2, B, tag, A, red, act_s, A.ldw_d, fail);
+        wg_gemv_ll<KSD, RO / 2>(wkv_s, A.ldw_d, kv_n, A.z_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail);
         RT_ABORT_IF(fail);
         if (tid < kRMax * kBMax && erow < kv_n && eb < B)
-            ll_store(A.kv_ll + par * sz_kv + (size_t)eb * 2 * d + kv_lo + erow, tag, __float_as_uint(red_sum(red, erow, eb)));
+            ll_store(A.kv_ll + par * sz_kv + single_word<RKV>(kv_lo + erow, eb), tag, __float_as_uint(red_sum(red, erow, eb)));
         if (pre) {   // overlaps the raw k, v crossing the chip
             PreLoad L;
             pre_from_lds(pre_s + (size_t)wave * kPreFloats, L);
@@ -803,6 +854,11 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 __global__ void clear_words_kernel(unsigned long long *p, int n)
 {
     if ((int)threadIdx.x < n) p[threadIdx.x] = 0ULL;
+}
+
+__global__ void clear_slab_kernel(unsigned long long *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ULL;
 }
 
 typedef void (*persist_fn)(PersistArgs);
@@ -884,7 +940,8 @@ rt_status persistent_create(PersistentState &P, const rt_config &cfg, const Laye
     const size_t o_kv = carve(2 * kBMax * 2 * d * 8);
     const size_t o_zss = carve((size_t)2 * kBMax * G * 8);
     const size_t o_zp = carve((size_t)2 * 4 * kBMax * d * 8);
-    const size_t o_tr = want_trace ? carve((size_t)cfg.max_seq * 16 * 8) : 0;
+    P.exchange_bytes = off;   // counters and exchange words; the trace follows
+    const size_t o_tr = want_trace ? carve((size_t)2 * cfg.max_seq * 16 * 8) : 0;
     P.slab_bytes = off;
     if (hipMalloc(&P.slab, P.slab_bytes) != hipSuccess) {
         (void)hipGetLastError();
@@ -947,8 +1004,21 @@ rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weigh
     A.kv_ll = (ll_t *)P.kv_ll; A.zss_ll = (ll_t *)P.zss_ll; A.zp_ll = (ll_t *)P.zp_ll;
     A.R_2 = D.d / 64;
     A.bar = P.bar; A.trace = P.trace; A.spin_limit = P.spin_limit;
+    A.trace_rows = P.trace_rows;
+    A.pre_sleep = getenv("RT_PRE_SLEEP") ? atoi(getenv("RT_PRE_SLEEP")) : 1;
+    {
+        const char *tw = getenv("RT_PERSIST_TRACE_WG");
+        A.trace_wg = tw ? atoi(tw) : P.grid - 1;
+    }
     P.nonce = (P.nonce % 4095u) + 1u;          // 1..4095; fresh buffers hold tag 0
     A.tag_base = P.nonce << 20;
+    if (P.nonce == 1u && P.launched) {
+        // the nonce has wrapped: words left by a call 4095 calls ago (rows of a larger batch, positions of a longer
+        // sequence) could carry this call's tags.  Start over from cleared buffers.
+        hipLaunchKernelGGL(clear_slab_kernel, dim3(256), dim3(256), 0, st, (unsigned long long *)P.slab, P.exchange_bytes / 8);
+        hipError_t ce = hipGetLastError();
+        if (ce != hipSuccess) { err = std::string("clear_slab_kernel: ") + hipGetErrorString(ce); return RT_ERR_HIP; }
+    }
 
     hipLaunchKernelGGL(clear_words_kernel, dim3(1), dim3(64), 0, st, P.bar, 32);
     hipError_t e = hipGetLastError();
@@ -973,7 +1043,7 @@ int persistent_wait_expired(PersistentState &P)
 int persistent_read_trace(PersistentState &P, unsigned long long *out, int rows)
 {
     if (!P.trace || !out) return 0;
-    const int n = rows < P.trace_rows ? rows : P.trace_rows;
+    const int n = rows < 2 * P.trace_rows ? rows : 2 * P.trace_rows;
     if (hipMemcpy(out, P.trace, (size_t)n * 16 * 8, hipMemcpyDeviceToHost) != hipSuccess) return -1;
     return n;
 }
