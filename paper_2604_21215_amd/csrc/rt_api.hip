@@ -90,6 +90,7 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
     const size_t oVT = mfma ? carve(Bm * H * kHeadDim * (size_t)S.vt_stride * 2) : 0;
     const size_t oQf = mfma ? carve(Nm * Bm * d * 4) : 0, oKtf = mfma ? carve(Nm * Bm * d * 4) : 0;
     const size_t oKlo = mfma ? carve(Nm * Bm * d * 2) : 0;
+    const size_t oKh = mfma ? carve(Nm * Bm * d * 2) : 0;
     const size_t np = (size_t)levels * slots * Bm * H;
     const size_t opm = carve(np * 4), opl = carve(np * 4), opo = carve(np * kHeadDim * 4);
     const size_t orinv = carve(Bm * Nm * 4);
@@ -109,6 +110,7 @@ static size_t layout_scratch(Scratch &S, char *base, size_t Bm, size_t Nm, size_
         S.Qf = mfma ? (float *)(p + oQf) : nullptr;
         S.Ktf = mfma ? (float *)(p + oKtf) : nullptr;
         S.Klo = mfma ? (bf16_t *)(p + oKlo) : nullptr;
+        S.Kh = mfma ? (uint16_t *)(p + oKh) : nullptr;
         S.pm = (float *)(p + opm); S.pl = (float *)(p + opl); S.po = (float *)(p + opo);
         S.rinv = (float *)(p + orinv);
         S.attn_cat = (float *)(p + ocat); S.h = (float *)(p + oh); S.u = (float *)(p + ou); S.z = (float *)(p + oz);

@@ -18,6 +18,15 @@ __device__ __forceinline__ bf16_t f32_to_bf16(float f)
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (bf16_t)(u >> 16);
 }
+__device__ __forceinline__ uint16_t f32_to_f16_bits(float f)
+{   // round to nearest, ties to even
+    const _Float16 h = (_Float16)f;
+    return __builtin_bit_cast(uint16_t, h);
+}
+__device__ __forceinline__ uint32_t pack_f16(float lo, float hi)
+{
+    return (uint32_t)f32_to_f16_bits(lo) | ((uint32_t)f32_to_f16_bits(hi) << 16);
+}
 __device__ __forceinline__ float to_f32(float v) { return v; }
 __device__ __forceinline__ float to_f32(bf16_t v) { return bf16_to_f32(v); }
 template <typename T> __device__ __forceinline__ T from_f32(float f);
@@ -56,6 +65,16 @@ __device__ __forceinline__ float wave_max(float v)
 __device__ __forceinline__ float lane_bcast(float v, int lane)
 {  // value of a wave-uniform lane index, read without going through LDS
     return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// 16 bytes from an address known to be global memory (a pointer that was itself loaded from memory is a generic address
+// to the compiler, and accesses through it become flat instructions that also count on the LDS counter, so that every
+// wait for an LDS operand waits for them as well; this load stays on the vector-memory counter alone)
+typedef unsigned rt_v4u_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 global_load16(const void *p)
+{
+    const rt_v4u_t v = *(const __attribute__((address_space(1))) rt_v4u_t *)(uintptr_t)p;
+    return make_uint4(v[0], v[1], v[2], v[3]);
 }
 
 __device__ __forceinline__ float gelu_erf(float u) { return 0.5f * u * (1.0f + erff(u * 0.70710678118654752440f)); }
@@ -139,6 +158,8 @@ struct Scratch {
     void *Q, *Kt, *Vt;   // [N][B][H][64] storage dtype: queries and temporary pairs
     float *Qf, *Ktf;     // [N][B][H][64] unrounded q and k_tmp (persistent engine's high-precision logits), or null
     bf16_t *Klo;         // [N][B][H][64] bf16 remainder k - bf16(k) of the persistent keys, or null
+    uint16_t *Kh;        // [N][B][H][64] the persistent keys rounded once to fp16 (11 significant bits): what the LDS-staged
+                         // cross-block tiles multiply with the fp16 queries; written wherever Klo is
     bf16_t *VT;          // [B*H][64][vt_stride] transposed copy of the persistent values (bf16 MFMA path)
     int vt_stride;
     float *pm, *pl, *po;

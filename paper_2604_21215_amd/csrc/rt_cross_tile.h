@@ -32,7 +32,8 @@ constexpr float kSlack = 16.f;     // how far (log2 units) a logit may exceed th
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 
-template <bool HP> constexpr int cross_tile_lds_bytes() { return (HP ? 3 : 2) * kKC * kTileLd * 2; }   // one buffer (V^T tile padded to the key tiles' size)
+// one buffer (V^T tile padded to the key tiles' size); F16: the key tile holds fp16(head + remainder), no remainder tile
+template <bool HP, bool F16 = HP> constexpr int cross_tile_lds_bytes() { return (HP && !F16 ? 3 : 2) * kKC * kTileLd * 2; }
 
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float f32x2_t __attribute__((ext_vector_type(2)));
@@ -44,7 +45,20 @@ __device__ __forceinline__ uint32_t cvt_pk_bf16(float lo, float hi)
     return *reinterpret_cast<uint32_t *>(&b);
 }
 
+typedef _Float16 f16x2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8_t __attribute__((ext_vector_type(8)));
+__device__ __forceinline__ uint32_t cvt_pk_f16(float lo, float hi)
+{   // round-to-nearest-even pair conversion to fp16
+    f32x2_t v = {lo, hi};
+    f16x2_t h = __builtin_convertvector(v, f16x2_t);
+    return __builtin_bit_cast(uint32_t, h);
+}
+
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ f32x16_t mfma32h(const uint4 &a, const uint4 &b, f32x16_t c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(f16x8_t, a), __builtin_bit_cast(f16x8_t, b), c, 0, 0, 0);
+}
 __device__ __forceinline__ f32x16_t mfma32u(const uint4 &a, const uint4 &b, f32x16_t c)
 {
     return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
@@ -59,7 +73,13 @@ __device__ __forceinline__ f32x16_t mfma32u(const uint4 &a, const uint4 &b, f32x
 // ALIBI (linear positional bias, slope per head): inside the tile the bias is taken relative to the block's last
 // key, slope * (j - j_last) <= 0, the same for every query; the stored maximum is moved into the query's own frame
 // when it is written (m -= slope * (i_query - j_last)).  The reference value then follows the biased logits.
-template <bool HP, int NW, int NBUF, bool ALIBI = false>
+// HP: logits from unrounded operands.  With F16 (the default for HP) queries (Qf, fp32) and keys are rounded ONCE to
+// fp16 - 11 significant bits against bf16's 8; elements of unit-RMS heads are far inside fp16's range - and S^T is one
+// v_mfma_f32_32x32x16_f16 product: the matrix work and the memory traffic of the plain bf16 tile with an eighth of its
+// logit rounding.  The fp16 keys are then passed in the Klo argument ([N][B][H][64], Scratch::Kh) and K is not read.
+// Without F16 the keys come as bf16 head K plus bf16 remainder Klo and go through three bf16 products
+// (K_lo Q_hi + K_hi Q_lo + K_hi Q_hi, 16 significant bits, twice the matrix instructions of the whole chunk).
+template <bool HP, int NW, int NBUF, bool ALIBI = false, bool F16 = HP>
 __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, const float *__restrict__ Qf,
                                               const bf16_t *__restrict__ K, const bf16_t *__restrict__ Klo,
                                               const bf16_t *__restrict__ VT, int vt_stride, float *__restrict__ pm,
@@ -71,7 +91,7 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
     constexpr int kPieces = kKC * 8;              // 16-byte pieces of one 64 x 64 bf16 tile
     constexpr int PPT = (kPieces + T - 1) / T;    // pieces per thread and tile
     constexpr int TILE = kKC * kTileLd;           // elements of one LDS tile
-    constexpr int BUF = (HP ? 3 : 2) * TILE;
+    constexpr int BUF = (HP && !F16 ? 3 : 2) * TILE;
     const int lane = tid & 63;
     const int l32 = lane & 31, hi = lane >> 5;
     const size_t rs = (size_t)BH * kHeadDim;
@@ -86,7 +106,11 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
         const size_t qo = (size_t)(c_first + q_shift + qi) * rs + (size_t)bh * kHeadDim + 8 * hi;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) {
-            if (HP) {
+            if (HP && F16) {
+                float f[8];
+                load8(Qf + qo + ks * 16, f);
+                bq[ks] = make_uint4(cvt_pk_f16(f[0], f[1]), cvt_pk_f16(f[2], f[3]), cvt_pk_f16(f[4], f[5]), cvt_pk_f16(f[6], f[7]));
+            } else if (HP) {
                 float f[8], r[8];
                 load8(Qf + qo + ks * 16, f);
                 uint32_t h2[4];
@@ -120,8 +144,9 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
     _Pragma("unroll") for (int i = 0; i < PPT; ++i)                                                                  \
     {                                                                                                                \
         if (kPieces % T == 0 || tid + i * T < kPieces) {                                                             \
-            rk[i] = *reinterpret_cast<const u32x4_t *>(gk + (size_t)((kc) + i * (T / 8)) * rs);                        \
-            if (HP) rl[i] = *reinterpret_cast<const u32x4_t *>(gl + (size_t)((kc) + i * (T / 8)) * rs);                \
+            if (HP && F16) rk[i] = *reinterpret_cast<const u32x4_t *>(gl + (size_t)((kc) + i * (T / 8)) * rs);       \
+            else rk[i] = *reinterpret_cast<const u32x4_t *>(gk + (size_t)((kc) + i * (T / 8)) * rs);                  \
+            if (HP && !F16) rl[i] = *reinterpret_cast<const u32x4_t *>(gl + (size_t)((kc) + i * (T / 8)) * rs);       \
             rv[i] = *reinterpret_cast<const u32x4_t *>(gv + (size_t)(i * (T / 8)) * vt_stride + (kc));                 \
         }                                                                                                            \
     }
@@ -130,13 +155,13 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
     {                                                                                                                \
         if (kPieces % T == 0 || tid + i * T < kPieces) {                                                             \
             bf16_t *dst = tiles + (size_t)(buf) * BUF + lds_off + i * (T / 8) * kTileLd;                             \
-            *reinterpret_cast<u32x4_t *>(dst) = rk[i];                                                                 \
+            *reinterpret_cast<u32x4_t *>(dst) = rk[i];                                                               \
             {                                                                                                        \
                 bf16_t *dv = tiles + (size_t)(buf) * BUF + TILE + lds_off_v + i * (T / 8) * kVLd;                    \
                 *reinterpret_cast<uint2 *>(dv) = make_uint2(rv[i][0], rv[i][1]);                                     \
                 *reinterpret_cast<uint2 *>(dv + 4) = make_uint2(rv[i][2], rv[i][3]);                                 \
             }                                                                                                        \
-            if (HP) *reinterpret_cast<u32x4_t *>(dst + 2 * TILE) = rl[i];                                              \
+            if (HP && !F16) *reinterpret_cast<u32x4_t *>(dst + 2 * TILE) = rl[i];                                    \
         }                                                                                                            \
     }
 
@@ -170,6 +195,10 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
                 f32x16_t acc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+                if (HP && F16) {
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) acc = mfma32h(ka[ks], bq[ks], acc);
+                } else {
                 if (HP) {   // small terms first
 #pragma unroll
                     for (int ks = 0; ks < 4; ++ks)
@@ -179,6 +208,7 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
                 }
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bq[ks], acc);
+                }
                 S[kt] = acc;
             }
             if (ALIBI) {

@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void cross_mfma_kernel(const bf16_t *__restric
                                         (int)threadIdx.x, ALIBI ? alibi_slope(alibi, bh % H, H) : 0.f);                     \
     }
 RT_CROSS_TILE_KERNEL(cross_tile_kernel, false, 4)
-RT_CROSS_TILE_KERNEL(cross_tile_hp_kernel, true, 2)
+RT_CROSS_TILE_KERNEL(cross_tile_hp_kernel, true, 4)
 #undef RT_CROSS_TILE_KERNEL
 
 hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K, int t1, int P, int nq, bool hp,
@@ -202,7 +202,7 @@ hipError_t cross_mfma_launch(const LayerDims &D, const Scratch &S, const void *K
     const int BH = D.B * D.H, bh8 = (BH + 7) / 8 * 8;
     const bool al = D.alibi > 0.f;
     const bf16_t *Q = (const bf16_t *)S.Q, *Kb = (const bf16_t *)K;
-#define RT_TILE_ARGS Q, S.Qf, Kb, S.Klo, S.VT, S.vt_stride, S.pm, S.pl, S.po, BH, t1, P, nq, nqb, level, level - D.log2_pmin, S.slots, D.scale, D.alibi, D.H
+#define RT_TILE_ARGS Q, S.Qf, Kb, (hp ? reinterpret_cast<const bf16_t *>(S.Kh) : S.Klo), S.VT, S.vt_stride, S.pm, S.pl, S.po, BH, t1, P, nq, nqb, level, level - D.log2_pmin, S.slots, D.scale, D.alibi, D.H
 #define RT_WAVE_ARGS Q, S.Qf, Kb, S.Klo, S.VT, S.vt_stride, S.pm, S.pl, S.po, BH, t1, P, nq, level, level - D.log2_pmin, S.slots, D.scale, D.alibi, D.H
     if (P >= kKC) {
         const dim3 grid(bh8 * nqb);

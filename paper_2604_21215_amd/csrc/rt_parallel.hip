@@ -231,6 +231,7 @@ struct PreOut {   // PG_PRE only
     // cache rows (K, its bf16 remainder Klo, V and the transposed copy VT) instead of the pre-pass buffers.
     int y0;
     bf16_t *K, *Klo, *V, *VT;
+    uint16_t *Kh;
     int vt_stride;
 };
 
@@ -386,6 +387,7 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
                     if (which == 1) {
                         po.K[oo + e] = r;
                         po.Klo[oo + e] = f32_to_bf16(val - bf16_to_f32(r));
+                        po.Kh[oo + e] = f32_to_f16_bits(val);
                     } else {
                         po.V[oo + e] = r;
                         vt[(size_t)e * po.vt_stride] = r;
@@ -453,7 +455,7 @@ static hipError_t blk_gemm_launch(dim3 grid, hipStream_t st, const bf16_t *A, co
 // of the keys and the transposed values for the tiles.  grid (B*H, N), block 64.
 __global__ __launch_bounds__(64) void par_export_kernel(const bf16_t *__restrict__ Ks, const float *__restrict__ Kf,
                                                         const bf16_t *__restrict__ Vs, bf16_t *__restrict__ K,
-                                                        bf16_t *__restrict__ V, bf16_t *__restrict__ Klo,
+                                                        bf16_t *__restrict__ V, bf16_t *__restrict__ Klo, uint16_t *__restrict__ Kh,
                                                         bf16_t *__restrict__ VT, int vt_stride, int BH, int t0)
 {
     const int lane = threadIdx.x, bh = blockIdx.x, t = t0 + blockIdx.y;
@@ -462,6 +464,7 @@ __global__ __launch_bounds__(64) void par_export_kernel(const bf16_t *__restrict
     K[off] = k;
     V[off] = v;
     Klo[off] = f32_to_bf16(Kf[off] - bf16_to_f32(k));
+    Kh[off] = f32_to_f16_bits(Kf[off]);
     VT[((size_t)bh * kHeadDim + lane) * vt_stride + t] = v;
 }
 
@@ -470,7 +473,7 @@ __global__ __launch_bounds__(64) void par_export_kernel(const bf16_t *__restrict
 // V^T columns N .. 64 ceil(N / 64) - 1 are written as zeros.  grid (B*H, ceil(N / 64)), block 256.
 __global__ __launch_bounds__(256) void par_export_tile_kernel(const bf16_t *__restrict__ Ks, const float *__restrict__ Kf,
                                                               const bf16_t *__restrict__ Vs, bf16_t *__restrict__ K,
-                                                              bf16_t *__restrict__ V, bf16_t *__restrict__ Klo,
+                                                              bf16_t *__restrict__ V, bf16_t *__restrict__ Klo, uint16_t *__restrict__ Kh,
                                                               bf16_t *__restrict__ VT, int vt_stride, int BH, int N)
 {
     constexpr int kLd = 72;
@@ -500,6 +503,11 @@ __global__ __launch_bounds__(256) void par_export_tile_kernel(const bf16_t *__re
         *reinterpret_cast<uint4 *>(V + off + 8) = v1;
         *reinterpret_cast<uint4 *>(Klo + off) = make_uint4(lo[0], lo[1], lo[2], lo[3]);
         *reinterpret_cast<uint4 *>(Klo + off + 8) = make_uint4(lo[4], lo[5], lo[6], lo[7]);
+        uint32_t kh[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) kh[j] = pack_f16(kf[2 * j], kf[2 * j + 1]);
+        *reinterpret_cast<uint4 *>(Kh + off) = make_uint4(kh[0], kh[1], kh[2], kh[3]);
+        *reinterpret_cast<uint4 *>(Kh + off + 8) = make_uint4(kh[4], kh[5], kh[6], kh[7]);
     }
     *reinterpret_cast<uint4 *>(tile + r * kLd + 16 * c) = v0;
     *reinterpret_cast<uint4 *>(tile + r * kLd + 16 * c + 8) = v1;
@@ -763,7 +771,7 @@ static hipError_t small_prepass(const LayerDims &D, const Weights &W, const Scra
     po.H = D.H; po.Bc = D.B;
     if (pairs_K) {
         po.y0 = D.H;
-        po.K = (bf16_t *)pairs_K; po.V = (bf16_t *)pairs_V; po.Klo = S.Klo; po.VT = S.VT; po.vt_stride = S.vt_stride;
+        po.K = (bf16_t *)pairs_K; po.V = (bf16_t *)pairs_V; po.Klo = S.Klo; po.Kh = S.Kh; po.VT = S.VT; po.vt_stride = S.vt_stride;
     }
     const int M = D.B * Nc;
     return blk_gemm_launch<PG_PRE>(dim3((unsigned)((M + 63) / 64), (unsigned)((pairs_K ? 2 : 3) * D.H)), st, (const bf16_t *)src, nullptr, M, 3 * D.d,
@@ -836,14 +844,14 @@ hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S
     hipError_t e = Launch<bf16_t>::prepass(D, Wp, S, pairs_src, B, N, true, st);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(par_export_tile_kernel, dim3(BH, (N + 63) / 64), dim3(256), 0, st, (const bf16_t *)S.Kt, S.Ktf,
-                       (const bf16_t *)S.Vt, (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, N);
+                       (const bf16_t *)S.Vt, (bf16_t *)K, (bf16_t *)V, S.Klo, S.Kh, S.VT, S.vt_stride, BH, N);
     if (!pairs_are_temporary) {
         e = Launch<bf16_t>::prepass(D, W, S, x, B, N, true, st);
         if (e != hipSuccess) return e;
     }
     {   // attention of all positions: one masked pass over the cache rows plus the temporary pair
         const int ntiles = (N + 127) / 128;
-        const size_t lds = 2 * (size_t)cross_tile_lds_bytes<true>();
+        const size_t lds = 2 * (size_t)cross_tile_lds_bytes<true, false>();   // three tiles per buffer: head, V^T, remainder
         const dim3 grid((unsigned)(ntiles * BH));
         if (D.alibi > 0.f)
             hipLaunchKernelGGL(par_flash_kernel<true>, grid, dim3(256), lds, st, S.Qf, S.Ktf, (const bf16_t *)S.Vt, (const bf16_t *)K,
@@ -880,7 +888,7 @@ hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S,
     // the temporary pairs of ALL positions go into the cache rows at once: a block reads rows below its own end only, and its
     // rows receive the persistent pairs when it is done
     hipLaunchKernelGGL(par_export_tile_kernel, dim3(BH, (N + 63) / 64), dim3(256), 0, st, (const bf16_t *)S.Kt, S.Ktf,
-                       (const bf16_t *)S.Vt, (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, N);
+                       (const bf16_t *)S.Vt, (bf16_t *)K, (bf16_t *)V, S.Klo, S.Kh, S.VT, S.vt_stride, BH, N);
     for (int t0 = 0; t0 < N; t0 += Sblk) {
         const int nr = Sblk < N - t0 ? Sblk : N - t0;
         hipLaunchKernelGGL(par_merge_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Q, S.Qf, (const bf16_t *)S.Kt, S.Ktf,
@@ -895,7 +903,7 @@ hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S,
             e = Launch<bf16_t>::prepass(D, Wp, S, y, B, nr, true, st, (size_t)N * d, t0);
             if (e != hipSuccess) return e;
             hipLaunchKernelGGL(par_export_kernel, dim3(BH, nr), dim3(64), 0, st, (const bf16_t *)S.Kt, S.Ktf, (const bf16_t *)S.Vt,
-                               (bf16_t *)K, (bf16_t *)V, S.Klo, S.VT, S.vt_stride, BH, t0);
+                               (bf16_t *)K, (bf16_t *)V, S.Klo, S.Kh, S.VT, S.vt_stride, BH, t0);
         }
         const int t1 = t0 + nr;
         const int P = t1 & -t1;

@@ -116,6 +116,7 @@ struct PersistArgs {
     const bf16_t *Q, *Kt, *Vt;
     const float *Qf, *Ktf;      // unrounded q, k_tmp
     bf16_t *Klo;                // remainder k - bf16(k) of the persistent keys
+    uint16_t *Kh;               // the persistent keys in fp16 (operands of the LDS-staged cross-block tiles)
     bf16_t *VT;
     int vt_stride;
     float *pm, *pl, *po;
@@ -509,11 +510,11 @@ __device__ __forceinline__ void cross_tile_item(const PersistArgs &A, int bh, in
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));   // opaque: keeps the tile's lane-derived addresses out of the registers of the per-position phases
     if (ALIBI)
-        cross_tile_wg<true, kPW, 1, true>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, A.BH, bh, t, 1, t - P, P, q0,
+        cross_tile_wg<true, kPW, 1, true>(A.Q, A.Qf, A.K, reinterpret_cast<const bf16_t *>(A.Kh), A.VT, A.vt_stride, A.pm, A.pl, A.po, A.BH, bh, t, 1, t - P, P, q0,
                                           nq, level, level - A.log2_pmin, A.slots, A.scale, lds, tid,
                                           alibi_slope(A.alibi, bh % A.H, A.H));
     else
-        cross_tile_wg<true, kPW, 1>(A.Q, A.Qf, A.K, A.Klo, A.VT, A.vt_stride, A.pm, A.pl, A.po, A.BH, bh, t, 1, t - P, P, q0, nq,
+        cross_tile_wg<true, kPW, 1>(A.Q, A.Qf, A.K, reinterpret_cast<const bf16_t *>(A.Kh), A.VT, A.vt_stride, A.pm, A.pl, A.po, A.BH, bh, t, 1, t - P, P, q0, nq,
                                     level, level - A.log2_pmin, A.slots, A.scale, lds, tid);
 }
 
@@ -638,7 +639,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 A.K[off] = kb;
                 A.V[off] = vb;
                 A.VT[((size_t)u * kHeadDim + lane) * A.vt_stride + (t - 1)] = vb;
-                A.Klo[off] = f32_to_bf16(kr - bf16_to_f32(kb));   // what the stored bf16 key lost; the cross-block kernel adds it back
+                A.Klo[off] = f32_to_bf16(kr - bf16_to_f32(kb));   // what the stored bf16 key lost; the 32-key tiles add it back
+                A.Kh[off] = f32_to_f16_bits(kr);
                 if (A.win_rows) {   // ring slot of key t-1; only this wavefront reads it back
                     const size_t slot = (size_t)(u / G) * A.win_rows + ((t - 1) & (A.win_rows - 1));
                     win_k[slot * (kHeadDim + 4) + lane] = kr;
@@ -997,7 +999,7 @@ rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weigh
     A.g_mlp = (const bf16_t *)W.g_mlp; A.g_kv = (const bf16_t *)W.g_kv; A.g_k = (const bf16_t *)W.g_k;
     A.x = (const bf16_t *)x; A.y = (bf16_t *)y; A.K = (bf16_t *)K; A.V = (bf16_t *)V;
     A.Q = (const bf16_t *)S.Q; A.Kt = (const bf16_t *)S.Kt; A.Vt = (const bf16_t *)S.Vt;
-    A.Qf = S.Qf; A.Ktf = S.Ktf; A.Klo = S.Klo;
+    A.Qf = S.Qf; A.Ktf = S.Ktf; A.Klo = S.Klo; A.Kh = S.Kh;
     A.VT = S.VT; A.vt_stride = S.vt_stride;
     A.pm = S.pm; A.pl = S.pl; A.po = S.po; A.levels = S.levels; A.slots = S.slots;
     A.a_ll = (ll_t *)P.a_ll; A.h_ll = (ll_t *)P.h_ll; A.u_ll = (ll_t *)P.u_ll; A.z_ll = (ll_t *)P.z_ll;

@@ -194,8 +194,8 @@ __device__ __forceinline__ void mm_body(const WaveLayer &Y, int t, int block_x, 
 #define RT_WF_LOADW(buf, kk)                                                                   \
     _Pragma("unroll") for (int j = 0; j < 4; ++j)                                              \
     {                                                                                          \
-        buf[2 * j] = *reinterpret_cast<const uint4 *>(wr + ((kk) / 64 + j) * kPairStride);                \
-        buf[2 * j + 1] = *reinterpret_cast<const uint4 *>(wr + ((kk) / 64 + j) * kPairStride + kFragStride); \
+        buf[2 * j] = global_load16(wr + ((kk) / 64 + j) * kPairStride);                \
+        buf[2 * j + 1] = global_load16(wr + ((kk) / 64 + j) * kPairStride + kFragStride); \
     }
 #define RT_WF_PAIR(a0v, a1v, kk)                                                               \
     {                                                                                          \
@@ -262,8 +262,7 @@ __device__ __forceinline__ void mm_body(const WaveLayer &Y, int t, int block_x, 
         }
     }
     for (int k = nfull * 256; k < klen; k += 64)
-        RT_WF_PAIR(*reinterpret_cast<const uint4 *>(wr + (k / 64) * kPairStride),
-                   *reinterpret_cast<const uint4 *>(wr + (k / 64) * kPairStride + kFragStride), k)
+        RT_WF_PAIR(global_load16(wr + (k / 64) * kPairStride), global_load16(wr + (k / 64) * kPairStride + kFragStride), k)
 #undef RT_WF_LOADW
 #undef RT_WF_PAIR
 #undef RT_WF_COMPUTE
@@ -352,6 +351,7 @@ __device__ __forceinline__ void mm_body(const WaveLayer &Y, int t, int block_x, 
                 const float r0 = v[0] - __uint_as_float(p01 << 16), r1 = v[1] - __uint_as_float(p01 & 0xFFFF0000u);
                 const float r2 = v[2] - __uint_as_float(p23 << 16), r3 = v[3] - __uint_as_float(p23 & 0xFFFF0000u);
                 if (Y.S.Klo) *reinterpret_cast<uint2 *>(Y.S.Klo + off) = make_uint2(pack_bf16(r0, r1), pack_bf16(r2, r3));
+                if (Y.S.Kh) *reinterpret_cast<uint2 *>(Y.S.Kh + off) = make_uint2(pack_f16(v[0], v[1]), pack_f16(v[2], v[3]));
             } else {
                 *reinterpret_cast<uint2 *>((bf16_t *)Y.V + off) = make_uint2(p01, p23);
                 if (Y.S.VT) {
@@ -429,6 +429,7 @@ __global__ __launch_bounds__(64) void wf_finalize_kernel(const WaveLayer *__rest
     ((T *)Y.K)[off] = kr;
     ((T *)Y.V)[off] = from_f32<T>(v);
     if (HP) Y.S.Klo[off] = f32_to_bf16(k - to_f32(kr));
+    if (HP) Y.S.Kh[off] = f32_to_f16_bits(k);
     if (Y.S.VT) Y.S.VT[((size_t)bh * kHeadDim + lane) * Y.S.vt_stride + t] = f32_to_bf16(v);
 }
 
@@ -466,7 +467,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int bh = (j / nqb) * 8 + xcd, qb = j % nqb;
     if (!J.any || bh >= BH || qb * 128 >= J.nq) return;   // the whole workgroup leaves together
     const WaveLayer &Y = layers[l];
-    cross_tile_wg<true, 4, 2, ALIBI>(nullptr, Y.S.Qf, (const bf16_t *)Y.K, Y.S.Klo, Y.S.VT, Y.S.vt_stride, Y.S.pm, Y.S.pl, Y.S.po,
+    cross_tile_wg<true, 4, 2, ALIBI>(nullptr, Y.S.Qf, (const bf16_t *)Y.K, reinterpret_cast<const bf16_t *>(Y.S.Kh), Y.S.VT, Y.S.vt_stride, Y.S.pm, Y.S.pl, Y.S.po,
                                      BH, bh, J.t1, 0, J.t1 - J.P, J.P, qb * 128 + (int)(threadIdx.x >> 6) * 32, J.nq, J.level,
                                      J.level_rel, Y.S.slots, scale, lds, (int)threadIdx.x,
                                      ALIBI ? alibi_slope(alibi, bh % H, H) : 0.f);
@@ -792,6 +793,7 @@ static WaveLayer step_layer(const Weights &W, const Scratch &S, const void *x_t,
     Y.W = W;
     Y.S = S;
     Y.S.Klo = nullptr;   // a decoding step writes the caller's cache rows only
+    Y.S.Kh = nullptr;
     Y.S.VT = nullptr;
     Y.x = x_t; Y.y = y_t; Y.K = K_row; Y.V = V_row;
     return Y;
