@@ -1,7 +1,7 @@
 /*
  * rt.h -- C ABI of the MI355X (gfx950) Recurrent Transformer layer library (librt_hip.so).
  *
- * One RT layer, forward only.  Per position i (paper Sec. 2.2, "The Recurrent Transformer layer"):
+ * One RT layer: forward (prefill, decoding step) and backward (rt_layer_backward).  Per position i (paper Sec. 2.2, "The Recurrent Transformer layer"):
  *
  *     n_i      = RMS(x_i; g_attn)
  *     q_i      = qkRMS(Wq n_i; g_q)     k_i^tmp = qkRMS(Wk n_i; g_k)     v_i^tmp = Wv n_i
@@ -152,8 +152,8 @@ rt_status rt_stack_prefill(rt_ctx *ctx, const rt_layer_weights *layers, int32_t 
  * parallel): K, V rows 0..N-1 are written from z, then y_i = the layer's output at position i computed from x_i, the
  * temporary pair of i and the persistent pairs of positions < i - one masked causal attention over all positions
  * (a single flash-style pass; Algorithm 1's blocks are not needed once every pair is known) and three GEMMs.  If z is the layer's true output for x, y reproduces it up to rounding (by induction over
- * the positions z is the only fixed point).  This is the forward half of a training step's recompute; no backward
- * pass is provided.
+ * the positions z is the only fixed point).  This is the forward half of a training step's recompute; rt_layer_backward
+ * does its own recompute.
  *   x, z [B, N, d] device, read-only; y [B, N, d] written; K, V [kv_cap, B, H, head_dim] rows 0..N-1 written.
  *   bf16 storage with the MFMA kernels and d_hidden a multiple of 64: matrix-core GEMMs and one masked attention pass.
  *   Any other context (fp32 storage, RT_FLAG_NO_MFMA, another hidden width): the same results from the plain-ALU
@@ -181,6 +181,36 @@ rt_status rt_transformer_layer(rt_ctx *ctx, const rt_layer_weights *w, const voi
  *   block: power of two, 1 <= block <= p_min.  Other arguments and the two kernel paths as rt_layer_recompute. */
 rt_status rt_layer_prefill_blocked(rt_ctx *ctx, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, int32_t block,
                                    void *y, void *K, void *V, int32_t kv_cap);
+
+/* Where rt_layer_backward writes the gradients of the parameters: device, fp32, same shapes as the parameters
+ * (matrices [out, in] row-major, gains [d_model]); written, not accumulated.  A null pointer skips that tensor. */
+typedef struct {
+    float *Wq, *Wk, *Wv, *Wo; /* [d, d] */
+    float *W1;                /* [F, d] */
+    float *W2;                /* [d, F] */
+    float *g_attn, *g_mlp, *g_kv;
+    float *g_q, *g_k;
+} rt_layer_grads;
+
+/* Backward pass of one RT layer (Sec. 6.4, "The backward pass"), with the forward intermediates recomputed from the
+ * layer's input and output (Sec. 6.1, "Activation checkpointing": given z, all persistent pairs are rebuilt at once and
+ * the remaining intermediates follow in parallel).  For the map (x, parameters) -> (y, K, V) of rt_layer_prefill and
+ *     L = <gy, y> + <gK, K> + <gV, V>
+ * it returns dL/dx and dL/d(parameter).  As Sec. 6.4 lays out, only the gradients of the persistent pairs are carried
+ * through the reverse loop over positions (position i needs the complete gradient of its z_i, which depends on k_i, v_i,
+ * before its attention can pass gradient to earlier pairs); the gradients of x, q, the temporary pairs and every parameter
+ * are batched products after the loop.  Earlier pairs are reached in Algorithm 1's blocks run backwards (Appendix C).
+ *   x, z [B, N, d] device, storage dtype, read-only: z must be the layer's output for x (from rt_layer_prefill).
+ *   gy [B, N, d] storage dtype: gradient arriving at y.  gK, gV [N, B, H, head_dim] storage dtype or NULL (zero):
+ *   gradients arriving at the returned persistent pairs (e.g. from decoding steps that read the cache).
+ *   dx [B, N, d] fp32, written.  grads: see rt_layer_grads.  When rt_layer_weights.g_kv is NULL (RMS(z) shares g_attn)
+ *   that share is added into grads->g_attn and grads->g_kv, if given, is zero-filled; gradients are also produced for
+ *   gains that were passed as NULL (implicit ones).  With RT_FLAG_NORM_FREE the gain gradients are zero.
+ *   1 <= B <= max_batch, 1 <= N <= min(max_seq, 65535).  dx and the gradient tensors must not overlap anything else.
+ * All arithmetic is fp32 whatever the storage dtype.  The first call allocates scratch for max_batch x max_seq positions
+ * (about (33 d + 3 F) 4 bytes per position; RT_ERR_OOM if that fails), kept until rt_destroy. */
+rt_status rt_layer_backward(rt_ctx *ctx, const rt_layer_weights *w, const void *x, const void *z, const void *gy,
+                            const void *gK, const void *gV, int32_t B, int32_t N, float *dx, const rt_layer_grads *grads);
 
 /* Input of the first layer of a stack (Sec. 2: a sequence of token embeddings enters the first layer):
  *   x[b, n, :] = table[ids[b * ids_stride + first + n], :]   for 0 <= b < B, 0 <= n < N.
@@ -215,7 +245,7 @@ uint64_t rt_workspace_bytes(const rt_ctx *ctx);
 int32_t rt_device_wait_expired(rt_ctx *ctx);
 
 /* Name of the engine the last prefill call on this context used: "stepwise", "stepwise+graph",
- * "persistent", "wavefront" (rt_stack_prefill), "recompute", "transformer", "blocked", or "" before the first call. */
+ * "persistent", "wavefront" (rt_stack_prefill), "recompute", "transformer", "blocked", "backward", or "" before the first call. */
 const char *rt_engine_name(const rt_ctx *ctx);
 
 /* Diagnostics of the persistent engine, after the stream has been synchronised: when the environment

@@ -24,7 +24,7 @@ EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
            "rt_version", "rt_phase_trace", "rt_schedule_events_shifted", "rt_embed_rows", "rt_lm_head", "rt_cross_block_event",
            "rt_stack_prefill", "rt_schedule_events_chunked", "rt_layer_recompute", "rt_transformer_layer",
-           "rt_layer_prefill_blocked", "rt_decode_step_static")
+           "rt_layer_prefill_blocked", "rt_decode_step_static", "rt_layer_backward")
 
 
 class rt_config(C.Structure):
@@ -37,6 +37,10 @@ class rt_config(C.Structure):
 
 
 class rt_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2", "g_attn", "g_mlp", "g_kv", "g_q", "g_k")]
+
+
+class rt_layer_grads(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("Wq", "Wk", "Wv", "Wo", "W1", "W2", "g_attn", "g_mlp", "g_kv", "g_q", "g_k")]
 
 
@@ -117,6 +121,9 @@ def load():
     L.rt_decode_step_static.argtypes = [C.POINTER(rt_config), C.POINTER(rt_layer_weights), C.c_void_p, C.c_int32, C.c_int32,
                                         C.c_void_p, C.c_void_p, C.c_void_p, C.c_int32]
     L.rt_decode_step_static.restype = C.c_int
+    L.rt_layer_backward.argtypes = [ctxp, C.POINTER(rt_layer_weights), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                                    C.c_void_p, C.c_int32, C.c_int32, C.c_void_p, C.POINTER(rt_layer_grads)]
+    L.rt_layer_backward.restype = C.c_int
     _lib = L
     return L
 
@@ -226,6 +233,18 @@ class RTContext:
         B, N, _ = x.shape
         rc = self._L.rt_layer_recompute(self._ctx, C.byref(weights), _ptr(x), _ptr(z), B, N, _ptr(y), _ptr(K), _ptr(V),
                                         K.shape[0])
+        _check(self._L, self._ctx, rc)
+
+    # -- rt_layer_backward(ctx, w, x[B,N,d], z[B,N,d], gy[B,N,d], gK | None, gV | None, B, N, dx[B,N,d] f32, grads)
+    def rt_layer_backward(self, weights: rt_layer_weights, x, z, gy, gK, gV, dx, grads: dict):
+        """grads: name -> fp32 device tensor (any subset of the six matrices and five gains)."""
+        B, N, _ = x.shape
+        g = rt_layer_grads()
+        for name, _t in rt_layer_grads._fields_:
+            t = grads.get(name)
+            setattr(g, name, None if t is None else t.data_ptr())
+        rc = self._L.rt_layer_backward(self._ctx, C.byref(weights), _ptr(x), _ptr(z), _ptr(gy), _ptr(gK), _ptr(gV), B, N,
+                                       _ptr(dx), C.byref(g))
         _check(self._L, self._ctx, rc)
 
     # -- rt_layer_prefill_blocked(ctx, w, x[B,N,d], B, N, block, y, K, V, kv_cap)

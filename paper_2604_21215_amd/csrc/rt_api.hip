@@ -3,6 +3,7 @@
 #include "../../include/rt.h"
 #include "rt_common.h"
 #include "rt_persistent.h"
+#include "rt_backward.h"
 
 #include <cstdio>
 #include <cstdlib>
@@ -37,6 +38,8 @@ struct rt_ctx {
     WaveStreams wave_streams = {};   // st[1..], ev[..] created on first use
     void *par_slab = nullptr;        // activations of the loop-free evaluations (rt_layer_recompute, rt_transformer_layer)
     size_t par_bytes = 0;
+    void *bw_slab = nullptr;         // scratch of rt_layer_backward
+    size_t bw_bytes = 0;
     // cached HIP graph of one stepwise prefill
     hipGraphExec_t graph_exec = nullptr;
     hipStream_t capture_stream = nullptr;  // the legacy default stream cannot be captured
@@ -305,6 +308,7 @@ rt_status rt_destroy(rt_ctx *c)
     if (c->stack_slab) (void)hipFree(c->stack_slab);
     if (c->stack_dev) (void)hipFree(c->stack_dev);
     if (c->par_slab) (void)hipFree(c->par_slab);
+    if (c->bw_slab) (void)hipFree(c->bw_slab);
     for (int g = 0; g < kMaxWaveStreams; ++g) {
         if (g > 0 && c->wave_streams.st[g]) (void)hipStreamDestroy(c->wave_streams.st[g]);
         if (c->wave_streams.ev[g]) (void)hipEventDestroy(c->wave_streams.ev[g]);
@@ -889,4 +893,58 @@ extern "C" rt_status rt_transformer_layer(rt_ctx *c, const rt_layer_weights *w, 
                                           void *K, void *V, int32_t kv_cap)
 {
     return parallel_entry(c, w, x, x, true, B, N, y, K, V, kv_cap);
+}
+
+// Backward pass of one layer (rt_backward.hip).
+extern "C" rt_status rt_layer_backward(rt_ctx *c, const rt_layer_weights *w, const void *x, const void *z, const void *gy,
+                                       const void *gK, const void *gV, int32_t B, int32_t N, float *dx, const rt_layer_grads *grads)
+{
+    if (!c) return RT_ERR_INVALID_ARG;
+    if (c->broken) return fail(c, RT_ERR_STATE, "context is unusable after an earlier failure%s");
+    rt_status s = check_weights(c, w);
+    if (s != RT_OK) return s;
+    if (!x || !z || !gy || !dx || !grads) return fail(c, RT_ERR_INVALID_ARG, "null tensor pointer%s");
+    if (B < 1 || B > c->cfg.max_batch) return fail(c, RT_ERR_INVALID_ARG, "B out of range [1, max_batch]%s");
+    if (N < 1 || N > c->cfg.max_seq) return fail(c, RT_ERR_INVALID_ARG, "N out of range [1, max_seq]%s");
+    if (N > 65535) return fail(c, RT_ERR_UNSUPPORTED, "rt_layer_backward covers sequences of at most 65535 positions%s");
+    const size_t E = c->cfg.dtype == RT_BF16 ? 2 : 4;
+    const size_t d = (size_t)c->cfg.d_model, F = (size_t)c->cfg.d_hidden;
+    const size_t xb = (size_t)B * N * d * E, dxb = (size_t)B * N * d * 4;
+    if (ranges_overlap(dx, dxb, x, xb) || ranges_overlap(dx, dxb, z, xb) || ranges_overlap(dx, dxb, gy, xb) ||
+        (gK && ranges_overlap(dx, dxb, gK, xb)) || (gV && ranges_overlap(dx, dxb, gV, xb)))
+        return fail(c, RT_ERR_INVALID_ARG, "dx must not overlap an input%s");
+    {   // no gradient tensor may overlap dx or another gradient tensor
+        const float *gp[11] = {grads->Wq, grads->Wk, grads->Wv, grads->Wo, grads->W1, grads->W2,
+                               grads->g_attn, grads->g_mlp, grads->g_kv, grads->g_q, grads->g_k};
+        const size_t gb[11] = {d * d * 4, d * d * 4, d * d * 4, d * d * 4, F * d * 4, F * d * 4, d * 4, d * 4, d * 4, d * 4, d * 4};
+        for (int i = 0; i < 11; ++i) {
+            if (!gp[i]) continue;
+            if (ranges_overlap(gp[i], gb[i], dx, dxb)) return fail(c, RT_ERR_INVALID_ARG, "a gradient tensor overlaps dx%s");
+            for (int j = i + 1; j < 11; ++j)
+                if (gp[j] && ranges_overlap(gp[i], gb[i], gp[j], gb[j]))
+                    return fail(c, RT_ERR_INVALID_ARG, "two gradient tensors overlap%s");
+        }
+    }
+    if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+    const size_t need = backward_scratch_bytes((size_t)c->cfg.max_batch, (size_t)c->cfg.max_seq, d, F, (size_t)c->cfg.n_heads, E);
+    if (!c->bw_slab) {
+        hipError_t e = hipMalloc(&c->bw_slab, need);
+        if (e != hipSuccess) {
+            (void)hipGetLastError();
+            c->bw_slab = nullptr;
+            return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "backward scratch: %s", hipGetErrorString(e));
+        }
+        c->bw_bytes = need;
+    }
+    LayerDims D = c->base;
+    D.B = B; D.N = N; D.kv_cap = N;
+    Weights W = to_weights(w);
+    W.g_kv = w->g_kv;   // null = RMS(z) shares g_attn: that share of the gradient goes into grads->g_attn
+    BwGrads G = {grads->Wq, grads->Wk, grads->Wv, grads->Wo, grads->W1, grads->W2,
+                 grads->g_attn, grads->g_mlp, grads->g_kv, grads->g_q, grads->g_k};
+    c->engine = "backward";
+    hipError_t e = c->cfg.dtype == RT_BF16 ? backward_layer<bf16_t>(D, W, x, z, gy, gK, gV, dx, G, c->bw_slab, c->stream)
+                                           : backward_layer<float>(D, W, x, z, gy, gK, gV, dx, G, c->bw_slab, c->stream);
+    if (e != hipSuccess) return fail_hip(c, e, "backward_layer");
+    return RT_OK;
 }

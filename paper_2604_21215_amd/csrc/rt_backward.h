@@ -1,0 +1,21 @@
+// Internal interface of the backward pass (rt_backward.hip), paper Sec. 6.4.
+#pragma once
+#include "rt_common.h"
+
+namespace rt {
+
+// Where the parameter gradients go (device, fp32, written not accumulated; null = not wanted).
+struct BwGrads {
+    float *Wq, *Wk, *Wv, *Wo, *W1, *W2;
+    float *g_attn, *g_mlp, *g_kv, *g_q, *g_k;
+};
+
+// bytes of scratch for sequences of B x N positions (E = bytes per element of the storage type)
+size_t backward_scratch_bytes(size_t B, size_t N, size_t d, size_t F, size_t H, size_t E);
+
+// x, z, gy [B][N][d]; gK, gV [N][B][H][64] or null (storage type T); dx [B][N][d] fp32.
+template <typename T>
+hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x, const void *z, const void *gy, const void *gK,
+                          const void *gV, float *dx, const BwGrads &G, void *ws, hipStream_t st);
+
+}  // namespace rt

@@ -216,7 +216,7 @@ __device__ __forceinline__ float merge_window32_hp(const float *__restrict__ Qf,
 // Where the rows come from is the caller's: rows.row(o) is the weight row of output o, rows.gain()
 // the gain vector (or null).
 // =============================================================================================
-enum Epi { EPI_WO = 0, EPI_W1 = 1, EPI_W2 = 2, EPI_KV = 3 };
+enum Epi { EPI_WO = 0, EPI_W1 = 1, EPI_W2 = 2, EPI_KV = 3, EPI_MUL = 5 };   // EPI_MUL: out_f = v * res_f (backward pass)
 
 constexpr int kGemvRows = 4;      // output rows per group of wavefronts
 constexpr int kGemvPart = kGemvRows * kBatchTile + kBatchTile;   // floats one wavefront leaves in LDS
@@ -310,6 +310,8 @@ __device__ __forceinline__ void gemv_body(const Rows &rows, int block, int n_out
                 const float z = res_f[(size_t)b * n_out + o] + alpha * v;
                 out_f[(size_t)b * n_out + o] = z;
                 out_T[(size_t)b * out_T_stride + o] = from_f32<T>(z);
+            } else if (EPI == EPI_MUL) {
+                out_f[(size_t)b * n_out + o] = v * res_f[(size_t)b * n_out + o];
             } else {
                 out_f[(size_t)b * n_out + o] = v;
             }
