@@ -15,12 +15,34 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# L2<->fabric bytes of one persistent_kernel launch on workload cfg3, from two rocprofv3 --pmc runs (FETCH_SIZE, then
-# WRITE_SIZE) scaled by what the same counters read for a plain 256 MiB copy (x 2.000 and x 1.000): fetch 9.58 GB + write 5.17 GB.
-MEASURED_TRAFFIC_BYTES = {("cfg3", "persistent"): 2 * 4676919 * 1024 + 5048709 * 1024,
-                          # one decoding step at t = 2047 (its nine kernels summed): fetch 101.0 MB + write 1.6 MB
-                          ("cfg3", "decode"): int((2 * 49301.2 + 1602.0) * 1024)}
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def measured_traffic(workload, what):
+    """L2<->fabric bytes per launch from profiles/traffic.json: the rocprofv3 FETCH_SIZE / WRITE_SIZE counter runs,
+    already scaled by the copy-kernel calibration, each entry naming the commit it was measured on.  None if absent."""
+    try:
+        with open(os.path.join(ROOT, "profiles", "traffic.json")) as f:
+            ent = json.load(f)["%s/%s" % (workload, what)]
+        return {"bytes": ent["bytes"], "measured_on": ent["commit"], "source": ent["source"]}
+    except (OSError, KeyError, ValueError):
+        return None
+
+
+def method_bytes(B, N, d, H, F, E):
+    """Bytes the METHOD has to move per layer call, by the per-token model of the tiled algorithm (Appendix C; footnote
+    of Sec. 5 for the tile's reads): every level of Algorithm 1 reads q, k, v of a tile once and writes / reads each
+    query's partial state once: 456 H ceil(log2 N) bytes per token at bf16; activations 11 d E per token (x twice,
+    q / temporary pairs written and read, y, K, V written); the loop's five matrices and the three pre-pass matrices once
+    (weights kept on chip)."""
+    import math
+    tokens = B * N
+    # per level half of the positions are queries of a tile: q, k, v rows of one head read once and a partial state
+    # (m, l, o[64], fp32) written once and read once = (3 * 64 E + 2 * 66 * 4) / 2 = 456 bytes per token and head at bf16
+    per_level = (3 * 64 * E + 2 * 66 * 4) / 2.0
+    return {"attention": float(per_level * H * math.ceil(math.log2(max(N, 2))) * tokens),
+            "activations": 11.0 * d * E * tokens,
+            "weights": float((11 + 3) * d * d * E) if F == 4 * d else float((3 * d * d + 2 * d * F + 3 * d * d) * E)}
 
 
 def algorithmic_bytes(B, N, d, H, F, E, p_min, weights_resident):
@@ -117,6 +139,7 @@ def main():
     ap.add_argument("--no-parallel", action="store_true", help="skip rt_transformer_layer / rt_layer_recompute")
     ap.add_argument("--no-blocked", action="store_true",
                     help="skip rt_layer_prefill_blocked (thousands of launches: slow under a counter-collecting profiler)")
+    ap.add_argument("--no-backward", action="store_true", help="skip rt_layer_backward")
     ap.add_argument("--no-stack", action="store_true", help="skip the 12-layer stack measurement (rt_stack_prefill)")
     ap.add_argument("--stack-only", action="store_true",
                     help="only the 12-layer stack through rt_stack_prefill (for profiling): prints its section alone")
@@ -185,16 +208,22 @@ def main():
     resident = engine == "persistent"
     terms = algorithmic_bytes(wl.B, wl.N, wl.d, wl.H, wl.F, E, p_min, resident)
     streamed = algorithmic_bytes(wl.B, wl.N, wl.d, wl.H, wl.F, E, p_min, False)
-    alg_bytes = sum(terms.values())
+    design_bytes = sum(terms.values())
+    mterms = method_bytes(wl.B, wl.N, wl.d, wl.H, wl.F, E)
+    alg_bytes = sum(mterms.values()) if resident else design_bytes
     dev_ms = float(np.mean(per_call_ms))
     achieved = alg_bytes / (dev_ms * 1e-3) / 1e9
+    traffic = measured_traffic(args.workload, engine)
     roofline = {
         "bound": "hbm",
         "kernel": ("persistent_kernel (one launch per call; the call's two small pre-pass kernels are inside the timed events)"
                    if resident else "rt_layer_prefill (%s engine, all launches of one call)" % engine),
         "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-        "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, engine)),
-        "launch_ms": dev_ms, "algorithmic_bytes": alg_bytes, "terms": terms,
+        "traffic": traffic["bytes"] if traffic else None, "traffic_source": traffic,
+        "traffic_over_algorithmic": (traffic["bytes"] / alg_bytes) if traffic else None,
+        "launch_ms": dev_ms, "algorithmic_bytes": alg_bytes, "algorithmic_terms": mterms if resident else terms,
+        # the same count with this build's own choices added (blocks below p_min read directly by each query: the window)
+        "design_bytes": design_bytes, "design_terms": terms,
         "us_per_position": dev_ms * 1e3 / wl.N,
         # what a design that re-streams the loop's weights at every position would have to move, for comparison
         "weight_streaming_equivalent_GBps": sum(streamed.values()) / (dev_ms * 1e-3) / 1e9,
@@ -238,17 +267,15 @@ def main():
         if levels:
             tot_fl = sum(l["tflops"] * l["us_per_event"] * l["events_per_call"] for l in levels)
             tot_us = sum(l["us_per_event"] * l["events_per_call"] for l in levels)
-            hp = engine == "persistent"   # the tile then forms every logit tile from three bf16 products
+            hp = engine == "persistent"   # the tile then takes fp16 copies of the unrounded queries and keys
             out["cross_block_kernel"] = {
                 "bound": "mfma", "unit": "TFLOP/s", "peak": MFMA_BF16_PEAK_TFLOPS * 1e0,
                 "achieved": tot_fl / tot_us, "frac": tot_fl / tot_us / MFMA_BF16_PEAK_TFLOPS,
-                "logits": "high precision (three products per logit tile)" if hp else "bf16",
-                "matrix_instruction_tflops": tot_fl / tot_us * (2.0 if hp else 1.0),
+                "logits": "one fp16 product from unrounded queries and keys" if hp else "bf16",
                 "note": "stand-alone launches of the top three levels (87.5 % of the attention FLOPs), FLOP-weighted, in the "
                         "form the engine of the timed call uses; achieved counts the algorithmic 4 P nq 64 FLOPs per "
-                        "(b, h) event, matrix_instruction_tflops what the matrix pipeline executes (twice that with "
-                        "high-precision logits: 32 instead of 16 instructions per 64-key chunk); back-to-back launches, "
-                        "launch overhead included", "levels": levels}
+                        "(b, h) event = what the matrix pipeline executes; back-to-back launches, launch overhead included",
+                "levels": levels}
 
     # One decoding step (rt_decode_step) over the cache the call above left: position t = N - 1 is evaluated again
     # from rows 0 .. N-2 (row N-1 is rewritten with the same values).  Bandwidth-bound in principle: the step has to
@@ -271,7 +298,7 @@ def main():
         out["decode_step"] = {"t": t_dec, "us_per_step": us, "tokens_per_s": wl.B / (us * 1e-6), "bound": "hbm",
                               "algorithmic_bytes": dec_bytes, "achieved": dec_bytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": dec_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                              "traffic": MEASURED_TRAFFIC_BYTES.get((args.workload, "decode")) if t_dec == 2047 else None,
+                              "traffic": (measured_traffic(args.workload, "decode") or {}).get("bytes") if t_dec == 2047 else None,
                               "note": "eight launches per step on one stream (bf16: products on the matrix cores)"}
 
     # The same layer without its sequential loop (every key-value pair known in advance): the recompute from a given
@@ -318,6 +345,30 @@ def main():
         sec["rt_over_transformer"] = dev_ms / sec["transformer_layer"]["ms_per_call"]
         out["loop_free_layers"] = sec
 
+    # Backward pass of the same layer (Sec. 6.4) from the output the timed calls left in y: recompute from (x, z), the
+    # reverse loop over positions (it carries the gradients of the persistent pairs only), batched parameter sums.
+    if not args.no_backward:
+        gen_t = torch.Generator(device="cuda:0")
+        gen_t.manual_seed(wl.seed)
+        gy = torch.randn(xd.shape, generator=gen_t, device="cuda:0", dtype=torch.float32).to(xd.dtype)
+        dx = torch.empty(xd.shape, dtype=torch.float32, device="cuda:0")
+        grads = {k: torch.empty(tuple(li.weights[k].shape), dtype=torch.float32, device="cuda:0")
+                 for k in ("Wq", "Wk", "Wv", "Wo", "W1", "W2")}
+        ctx.rt_layer_backward(dl.struct, xd, y, gy, None, None, dx, grads)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 2
+        e0.record(stream)
+        for _ in range(reps):
+            ctx.rt_layer_backward(dl.struct, xd, y, gy, None, None, dx, grads)
+        e1.record(stream)
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / reps
+        out["backward"] = {"ms_per_call": ms, "tokens_per_s": tokens / (ms * 1e-3), "us_per_position": ms * 1e3 / wl.N,
+                           "over_forward": ms / dev_ms, "dtype": "f32 arithmetic, %s storage" % wl.dtype,
+                           "finite": bool(torch.isfinite(dx).all().item())}
+        del gy, dx, grads
+
     if not args.no_cpu_baseline:
         from oracle import rt_oracle
         n_s = min(args.cpu_sample_positions, wl.N)
@@ -332,8 +383,20 @@ def main():
                                "sample": "first %d positions of all %d sequences of the same workload (%.1f s)"
                                % (n_s, wl.B, dt)}
         got = tio.to_host(y[:, :n_s])
-        err = np.linalg.norm(got - ref[0], axis=-1) / np.linalg.norm(ref[0], axis=-1)
-        out["parity_sample"] = {"max_rel_err_y": float(err.max()), "positions": n_s}
+        err = (np.linalg.norm(got - ref[0], axis=-1) / np.linalg.norm(ref[0], axis=-1)).max(axis=0)
+        br_ref, br_got = ref[0] - xs, got - xs     # the attention + MLP branch alone (y = x + branch hides its error)
+        ebr = (np.linalg.norm(br_got - br_ref, axis=-1) / np.linalg.norm(br_ref, axis=-1)).max(axis=0)
+        gK, gV = tio.to_host(K[:n_s]), tio.to_host(V[:n_s])
+        eK = (np.linalg.norm(gK - ref[1][:n_s], axis=-1) / np.linalg.norm(ref[1][:n_s], axis=-1)).reshape(n_s, -1).max(axis=1)
+        eV = (np.linalg.norm(gV - ref[2][:n_s], axis=-1) / np.linalg.norm(ref[2][:n_s], axis=-1)).reshape(n_s, -1).max(axis=1)
+        qs = [slice(i * n_s // 4, max((i + 1) * n_s // 4, i * n_s // 4 + 1)) for i in range(4)]
+        out["parity_sample"] = {"max_rel_err_y": float(err.max()), "max_rel_err_K": float(eK.max()),
+                                "max_rel_err_V": float(eV.max()), "max_rel_err_branch": float(ebr.max()),
+                                "by_quarter_of_the_sequence": {"y": [float(err[q].max()) for q in qs],
+                                                               "K": [float(eK[q].max()) for q in qs],
+                                                               "V": [float(eV[q].max()) for q in qs],
+                                                               "branch": [float(ebr[q].max()) for q in qs]},
+                                "positions": n_s, "tolerance": 2e-2 if wl.dtype == "bf16" else 1e-4}
     ctx.rt_destroy()
 
     if not args.no_stack and args.workload == "cfg3":

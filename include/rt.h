@@ -58,6 +58,9 @@ typedef enum { RT_F32 = 0, RT_BF16 = 1 } rt_dtype; /* storage type of x, y, K, V
 #define RT_FLAG_ENGINE_PERSISTENT 0x4u /* require the single persistent weight-stationary kernel (error if it cannot run) */
 #define RT_FLAG_NO_MFMA 0x8u         /* use the plain-ALU kernels also for bf16 storage (cross-checks) */
 #define RT_FLAG_HIP_GRAPH 0x10u      /* stepwise engine: capture the launches of a prefill in a HIP graph and replay it */
+#define RT_FLAG_DEBUG_POISON 0x20u   /* debugging: before every prefill (any engine, stacks, blocked recurrence) all stored
+                                        partial softmax states are set to NaN, so that a state read before this call has
+                                        written it - a slip in one of the schedules - reaches the outputs as NaN */
 
 typedef struct {
     int32_t d_model, n_heads, head_dim, d_hidden; /* n_heads * head_dim == d_model; head_dim must be 64 */

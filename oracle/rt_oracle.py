@@ -43,14 +43,25 @@ def build(force: bool = False) -> str:
     return _LIB
 
 
+def build_sanitized(out: str) -> str:
+    """The same source with AddressSanitizer and UndefinedBehaviorSanitizer (gcc, -O1, frame pointers kept) into `out`;
+    a process that loads it needs gcc's libasan preloaded (tests/test_oracle_sanitized.py does that in a child)."""
+    cmd = ["gcc", "-O1", "-g", "-fno-omit-frame-pointer", "-fsanitize=address,undefined", "-fno-sanitize-recover=undefined",
+           "-fopenmp", "-fPIC", "-shared", "-std=c11", "-Wall", "-fno-fast-math", "-ffp-contract=off", _SRC, "-o", out, "-lm"]
+    subprocess.run(cmd, check=True)
+    return out
+
+
 _lib = None
 
 
 def lib():
     global _lib
     if _lib is None:
-        build()
-        L = C.CDLL(_LIB)
+        path = os.environ.get("RT_ORACLE_LIB")   # an already built variant of the same source (the sanitizer build)
+        if not path:
+            path = build()
+        L = C.CDLL(path)
         PP = C.POINTER(_Params)
         L.rto_layer_prefill.argtypes = [PP, _DP, C.c_int, C.c_int, _DP, _DP, _DP, C.c_int, _DP]
         L.rto_layer_prefill.restype = C.c_int

@@ -19,6 +19,7 @@ RT_FLAG_ENGINE_STEPWISE = 0x2
 RT_FLAG_ENGINE_PERSISTENT = 0x4
 RT_FLAG_NO_MFMA = 0x8
 RT_FLAG_HIP_GRAPH = 0x10
+RT_FLAG_DEBUG_POISON = 0x20
 
 EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_last_error", "rt_status_string",
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",

@@ -70,6 +70,22 @@ static rt_status fail_hip(rt_ctx *c, hipError_t e, const char *where)
     return RT_ERR_HIP;
 }
 
+// RT_FLAG_DEBUG_POISON: every partial softmax state (m, l, o) of a scratch set becomes NaN before a call, so that a state
+// that is read before the call has written it shows up in the outputs.
+__global__ __launch_bounds__(256) void poison_f32_kernel(float *__restrict__ p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (size_t)gridDim.x * 256) p[i] = __uint_as_float(0x7FC00000u);
+}
+static void poison_partials(const rt_ctx *c, const Scratch &S)
+{
+    if (!(c->cfg.flags & RT_FLAG_DEBUG_POISON) || !S.pm) return;
+    const size_t np = (size_t)S.levels * S.slots * c->cfg.max_batch * c->cfg.n_heads;
+    auto grid = [](size_t n) { return dim3((unsigned)((n + 255) / 256 < 2048 ? (n + 255) / 256 : 2048)); };
+    hipLaunchKernelGGL(poison_f32_kernel, grid(np), dim3(256), 0, c->stream, S.pm, np);
+    hipLaunchKernelGGL(poison_f32_kernel, grid(np), dim3(256), 0, c->stream, S.pl, np);
+    hipLaunchKernelGGL(poison_f32_kernel, grid(np * kHeadDim), dim3(256), 0, c->stream, S.po, np * kHeadDim);
+}
+
 static int ilog2(int v)
 {
     int l = 0;
@@ -469,6 +485,7 @@ extern "C" rt_status rt_layer_prefill(rt_ctx *c, const rt_layer_weights *w, cons
     D.B = B; D.N = N; D.kv_cap = kv_cap;
     c->last_B = B; c->last_N = N;
     c->last_hp = false;
+    poison_partials(c, c->S);
     const bool want_stepwise = (c->cfg.flags & RT_FLAG_ENGINE_STEPWISE) != 0;
     if (!want_stepwise && persistent_supported(c->persist, D)) {
         c->engine = "persistent";
@@ -784,6 +801,7 @@ extern "C" rt_status rt_stack_prefill(rt_ctx *c, const rt_layer_weights *layers,
         host[l].S = c->stack_S[l];
         host[l].x = l == 0 ? x : y[l - 1];
         host[l].y = y[l]; host[l].K = K[l]; host[l].V = V[l];
+        poison_partials(c, c->stack_S[l]);
     }
     // pageable source: the copy has been staged when the call returns, `host` may go out of scope
     RT_TRY(hipMemcpyAsync(c->stack_dev, host.data(), sizeof(WaveLayer) * L, hipMemcpyHostToDevice, c->stream), "descriptor copy");
@@ -838,6 +856,7 @@ static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void
     // hidden width): the plain-ALU kernels
     const bool fast = c->cfg.dtype == RT_BF16 && parallel_supported(D, c->use_mfma);
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
+    poison_partials(c, c->S);
     const size_t Mmax = (size_t)c->cfg.max_batch * c->cfg.max_seq;
     const size_t need = fast ? parallel_scratch_bytes(Mmax, c->cfg.d_model, c->cfg.d_hidden)
                              : Launch<float>::loop_free_scratch_bytes(Mmax, c->cfg.d_model, c->cfg.d_hidden);
