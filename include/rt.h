@@ -80,7 +80,15 @@ typedef struct {
                                                      persistent key of position j < i is lowered by m_h (i - j), head
                                                      slopes m_h = 2^(-beta (h + 1) / H), h = 0..H-1; the temporary pair is
                                                      at distance 0.  0 = none (Sec. 2.2 as it stands) */
+    /* Scratch that would otherwise be allocated by the first call that needs it; reserved at rt_create instead, so that
+     * no later call allocates (all zero = allocate on first use): */
+    int32_t reserve_stack_layers;                 /* rt_stack_prefill: scratch sets for this many layers ... */
+    int32_t reserve_stack_chunk;                  /* ... at this chunk (0 = 64); a call with more layers or another chunk
+                                                     still reallocates */
+    uint32_t reserve;                             /* RT_RESERVE_* bits */
 } rt_config;
+#define RT_RESERVE_LOOP_FREE 0x1u /* rt_layer_recompute, rt_transformer_layer, rt_layer_prefill_blocked */
+#define RT_RESERVE_BACKWARD 0x2u  /* rt_layer_backward */
 
 /* Device pointers, caller-owned, read-only.  Matrices are row-major [out, in] (y = W u).
  * Gains: NULL = ones.  g_kv NULL = use g_attn.  g_q, g_k are [d_model] = [n_heads, head_dim]. */
@@ -141,7 +149,8 @@ rt_status rt_decode_step_static(const rt_config *cfg, const rt_layer_weights *w,
  *   y, K, V: host arrays of L device pointers: y[l] [B, N, d] output of layer l (all L are written: y[l] is layer
  *   l + 1's input), K[l], V[l] [kv_cap, B, H, head_dim] rows 0..N-1 written.  No two of these tensors may overlap.
  *   chunk: power of two >= p_min (>= 64 with the MFMA kernels); 0 = 64.
- * The first call allocates one scratch set per layer (RT_ERR_OOM if that fails); it is kept until rt_destroy and
+ * Unless rt_config.reserve_stack_layers reserved them at rt_create, the first call allocates one scratch set per layer
+ * (RT_ERR_OOM if that fails); it is kept until rt_destroy and
  * reused by later calls with the same chunk and at most as many layers (another shape synchronises the stream
  * and reallocates).  Half of the layers are enqueued on a second stream that the context owns (default priority;
  * it starts after the work already enqueued on rt_config.stream and that stream continues after it; the
@@ -162,7 +171,8 @@ rt_status rt_stack_prefill(rt_ctx *ctx, const rt_layer_weights *layers, int32_t 
  *   Any other context (fp32 storage, RT_FLAG_NO_MFMA, another hidden width): the same results from the plain-ALU
  *   kernels (one wavefront per (b, h, position) for the attention, the products in tiles of eight rows) - for checking
  *   at fp32 tolerance, not for speed.
- * The first call allocates activation scratch for max_batch x max_seq rows (kept until rt_destroy). */
+ * The first call allocates activation scratch for max_batch x max_seq rows (kept until rt_destroy) unless
+ * RT_RESERVE_LOOP_FREE reserved it at rt_create. */
 rt_status rt_layer_recompute(rt_ctx *ctx, const rt_layer_weights *w, const void *x, const void *z, int32_t B, int32_t N,
                              void *y, void *K, void *V, int32_t kv_cap);
 
@@ -211,7 +221,8 @@ typedef struct {
  *   gains that were passed as NULL (implicit ones).  With RT_FLAG_NORM_FREE the gain gradients are zero.
  *   1 <= B <= max_batch, 1 <= N <= min(max_seq, 65535).  dx and the gradient tensors must not overlap anything else.
  * All arithmetic is fp32 whatever the storage dtype.  The first call allocates scratch for max_batch x max_seq positions
- * (about (33 d + 3 F) 4 bytes per position; RT_ERR_OOM if that fails), kept until rt_destroy. */
+ * (about (33 d + 3 F) 4 bytes per position; RT_ERR_OOM if that fails), kept until rt_destroy, unless RT_RESERVE_BACKWARD
+ * reserved it at rt_create. */
 rt_status rt_layer_backward(rt_ctx *ctx, const rt_layer_weights *w, const void *x, const void *z, const void *gy,
                             const void *gK, const void *gV, int32_t B, int32_t N, float *dx, const rt_layer_grads *grads);
 

@@ -20,6 +20,7 @@ RT_FLAG_ENGINE_PERSISTENT = 0x4
 RT_FLAG_NO_MFMA = 0x8
 RT_FLAG_HIP_GRAPH = 0x10
 RT_FLAG_DEBUG_POISON = 0x20
+RT_RESERVE_LOOP_FREE, RT_RESERVE_BACKWARD = 0x1, 0x2
 
 EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_last_error", "rt_status_string",
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
@@ -34,6 +35,7 @@ class rt_config(C.Structure):
         ("max_batch", C.c_int32), ("max_seq", C.c_int32), ("dtype", C.c_int32), ("p_min", C.c_int32),
         ("resid_scale", C.c_float), ("attn_scale", C.c_float), ("rms_eps", C.c_float), ("flags", C.c_uint32),
         ("device", C.c_int32), ("stream", C.c_void_p), ("alibi_max_bias", C.c_float),
+        ("reserve_stack_layers", C.c_int32), ("reserve_stack_chunk", C.c_int32), ("reserve", C.c_uint32),
     ]
 
 
@@ -193,11 +195,12 @@ class RTContext:
     """Owns an rt_ctx.  Methods mirror the C entry points and take torch device tensors."""
 
     def __init__(self, d_model, n_heads, d_hidden, max_batch, max_seq, dtype, *, p_min=0, resid_scale=1.0,
-                 attn_scale=1.0, rms_eps=1e-6, flags=0, device=0, stream=None, alibi_max_bias=0.0):
+                 attn_scale=1.0, rms_eps=1e-6, flags=0, device=0, stream=None, alibi_max_bias=0.0, reserve_stack_layers=0,
+                 reserve_stack_chunk=0, reserve=0):
         L = load()
         cfg = rt_config(d_model, n_heads, d_model // n_heads if n_heads else 0, d_hidden, max_batch, max_seq,
                         RT_BF16 if dtype in ("bf16", RT_BF16) and dtype != 0 else RT_F32, p_min, resid_scale, attn_scale,
-                        rms_eps, flags, device, stream, alibi_max_bias)
+                        rms_eps, flags, device, stream, alibi_max_bias, reserve_stack_layers, reserve_stack_chunk, reserve)
         self.cfg = cfg
         self._L = L
         self._ctx = C.c_void_p()
@@ -327,6 +330,9 @@ class RTContext:
             self._ctx = C.c_void_p()
 
     def __del__(self):
+        import sys
+        if sys is None or sys.is_finalizing():   # no HIP calls while the interpreter (and the runtimes behind it) shut down
+            return
         try:
             self.rt_destroy()
         except Exception:

@@ -179,6 +179,43 @@ static void fill_dims(LayerDims &D, const rt_config &cfg, int p_min)
     D.alibi = cfg.alibi_max_bias;
 }
 
+static rt_status stack_workspace(rt_ctx *c, int L, int chunk);
+
+// Scratch of the loop-free evaluations / of the backward pass for max_batch x max_seq positions: allocated once, at
+// rt_create when rt_config.reserve asks for it, else by the first call that needs it.
+static rt_status ensure_loop_free_scratch(rt_ctx *c)
+{
+    if (c->par_slab) return RT_OK;
+    const size_t Mmax = (size_t)c->cfg.max_batch * c->cfg.max_seq;
+    LayerDims D = c->base;
+    const bool fast = c->cfg.dtype == RT_BF16 && parallel_supported(D, c->use_mfma);
+    const size_t need = fast ? parallel_scratch_bytes(Mmax, c->cfg.d_model, c->cfg.d_hidden)
+                             : Launch<float>::loop_free_scratch_bytes(Mmax, c->cfg.d_model, c->cfg.d_hidden);
+    hipError_t e = hipMalloc(&c->par_slab, need);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        c->par_slab = nullptr;
+        return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "activation scratch: %s", hipGetErrorString(e));
+    }
+    c->par_bytes = need;
+    return RT_OK;
+}
+static rt_status ensure_backward_scratch(rt_ctx *c)
+{
+    if (c->bw_slab) return RT_OK;
+    const size_t E = c->cfg.dtype == RT_BF16 ? 2 : 4;
+    const size_t need = backward_scratch_bytes((size_t)c->cfg.max_batch, (size_t)c->cfg.max_seq, (size_t)c->cfg.d_model,
+                                               (size_t)c->cfg.d_hidden, (size_t)c->cfg.n_heads, E);
+    hipError_t e = hipMalloc(&c->bw_slab, need);
+    if (e != hipSuccess) {
+        (void)hipGetLastError();
+        c->bw_slab = nullptr;
+        return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "backward scratch: %s", hipGetErrorString(e));
+    }
+    c->bw_bytes = need;
+    return RT_OK;
+}
+
 extern "C" {
 
 int32_t rt_version(void) { return 100; }
@@ -310,6 +347,22 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
         delete c;
         return ps;
     }
+    // scratch of the other entry points, when the caller wants no allocation inside a later call
+    rt_status rs = RT_OK;
+    if (cfg->reserve_stack_layers > 0) {
+        const int chunk = cfg->reserve_stack_chunk == 0 ? 64 : cfg->reserve_stack_chunk;
+        const int chunk_min = mfma ? 64 : p_min;
+        if (cfg->reserve_stack_layers > 4096 || !is_pow2(chunk) || chunk < chunk_min || chunk < p_min || chunk > (1 << 20))
+            rs = RT_ERR_INVALID_ARG;
+        else
+            rs = stack_workspace(c, cfg->reserve_stack_layers, chunk);
+    }
+    if (rs == RT_OK && (cfg->reserve & RT_RESERVE_LOOP_FREE)) rs = ensure_loop_free_scratch(c);
+    if (rs == RT_OK && (cfg->reserve & RT_RESERVE_BACKWARD)) rs = ensure_backward_scratch(c);
+    if (rs != RT_OK) {
+        (void)rt_destroy(c);
+        return rs;
+    }
     *out = c;
     return RT_OK;
 }
@@ -338,7 +391,7 @@ static const char *static_last_error();
 const char *rt_last_error(const rt_ctx *c) { return c ? c->err.c_str() : static_last_error(); }
 uint64_t rt_workspace_bytes(const rt_ctx *c)
 {
-    return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) + c->stack_bytes + c->par_bytes : 0;
+    return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) + c->stack_bytes + c->par_bytes + c->bw_bytes : 0;
 }
 const char *rt_engine_name(const rt_ctx *c) { return c ? c->engine.c_str() : ""; }
 
@@ -857,18 +910,8 @@ static rt_status parallel_entry(rt_ctx *c, const rt_layer_weights *w, const void
     const bool fast = c->cfg.dtype == RT_BF16 && parallel_supported(D, c->use_mfma);
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
     poison_partials(c, c->S);
-    const size_t Mmax = (size_t)c->cfg.max_batch * c->cfg.max_seq;
-    const size_t need = fast ? parallel_scratch_bytes(Mmax, c->cfg.d_model, c->cfg.d_hidden)
-                             : Launch<float>::loop_free_scratch_bytes(Mmax, c->cfg.d_model, c->cfg.d_hidden);
-    if (!c->par_slab) {
-        hipError_t e = hipMalloc(&c->par_slab, need);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            c->par_slab = nullptr;
-            return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "activation scratch: %s", hipGetErrorString(e));
-        }
-        c->par_bytes = need;
-    }
+    s = ensure_loop_free_scratch(c);
+    if (s != RT_OK) return s;
     if (!fast) {
         c->last_B = B; c->last_N = N;
         c->last_hp = false;
@@ -945,16 +988,8 @@ extern "C" rt_status rt_layer_backward(rt_ctx *c, const rt_layer_weights *w, con
         }
     }
     if (hipSetDevice(c->cfg.device) != hipSuccess) return fail(c, RT_ERR_HIP, "hipSetDevice failed%s");
-    const size_t need = backward_scratch_bytes((size_t)c->cfg.max_batch, (size_t)c->cfg.max_seq, d, F, (size_t)c->cfg.n_heads, E);
-    if (!c->bw_slab) {
-        hipError_t e = hipMalloc(&c->bw_slab, need);
-        if (e != hipSuccess) {
-            (void)hipGetLastError();
-            c->bw_slab = nullptr;
-            return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "backward scratch: %s", hipGetErrorString(e));
-        }
-        c->bw_bytes = need;
-    }
+    s = ensure_backward_scratch(c);
+    if (s != RT_OK) return s;
     LayerDims D = c->base;
     D.B = B; D.N = N; D.kv_cap = N;
     Weights W = to_weights(w);

@@ -401,3 +401,59 @@ def test_config5_full_size(variant, emb_scale, attn_scale):
         assert worst_o.max() <= tol and rows_dec[:, 1:].max() <= tol
     finally:
         ctx.rt_destroy()
+
+
+def test_stack_prefill_is_ordered_on_the_callers_stream_and_reserved_scratch_is_not_reallocated(oracle):
+    """(1) Work enqueued on rt_config.stream right after rt_stack_prefill sees its outputs without any device-wide
+    synchronisation in between, although half of the layers run on a second stream inside the call: copies of the last
+    layer's y, K, V enqueued on the same (non-default) stream directly after the call equal the tensors read back after a
+    full synchronisation, and those meet the oracle.  (2) With rt_config.reserve_stack_layers / reserve the scratch of
+    rt_stack_prefill, the loop-free layers and the backward pass is allocated by rt_create: the context's workspace size
+    does not change when those entry points are called afterwards."""
+    _need_gpu()
+    from paper_2604_21215_amd import binding, torch_io as tio
+    from paper_2604_21215_amd.stack import DeviceStack
+    wl = gen.Workload("stack_order", "bf16", 3, 200, 256, 4, 1024, layers=4, vocab=500, decode_steps=0, seed=997)
+    tabs = gen.make_embedding_tables(wl)
+    emb = gen.round_to_bf16(tabs["embedding"] * np.float32(EMB_UNIT))
+    side = torch.cuda.Stream()   # default priority
+    ctx = binding.RTContext(wl.d, wl.H, wl.F, wl.B, wl.N, wl.dtype, resid_scale=wl.resid_scale, rms_eps=1e-6,
+                            stream=side.cuda_stream, reserve_stack_layers=wl.layers, reserve_stack_chunk=64,
+                            reserve=binding.RT_RESERVE_LOOP_FREE | binding.RT_RESERVE_BACKWARD)
+    try:
+        ws0 = ctx.workspace_bytes()
+        dls, ols = [], []
+        for l in range(wl.layers):
+            w = gen.make_layer_weights(wl.seed, l, wl.d, wl.F, wl.dtype)
+            dls.append(tio.DeviceLayer(w, None, wl.dtype))
+            ols.append(oracle.Layer({k: v.astype(np.float64) for k, v in w.items()}, wl.H, alpha=wl.resid_scale, eps=1e-6))
+        ds = DeviceStack(ctx, dls, emb, tabs["lm_head"], None, wl.dtype)
+        os_ = oracle.Stack(ols, emb.astype(np.float64), tabs["lm_head"].astype(np.float64), None, eps=1e-6)
+        ids = gen.make_token_ids(wl)[:wl.B, :wl.N]
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            ds.prefill(_ids_dev(ids), wl.N, kv_cap=wl.N, wavefront=True, chunk=64)
+            y_c, K_c, V_c = ds.y[-1].clone(), ds.K[-1].clone(), ds.V[-1].clone()   # same stream, no synchronisation before
+        side.synchronize()
+        snap = [tio.to_host(t) for t in (y_c, K_c, V_c)]
+        torch.cuda.synchronize()
+        assert ctx.engine_name() == "wavefront"
+        full = [tio.to_host(t) for t in (ds.y[-1], ds.K[-1], ds.V[-1])]
+        for a, b in zip(snap, full):
+            assert np.array_equal(a, b)
+        ref_layers, _ = os_.prefill(ids, wl.N, kv_cap=wl.N)
+        rows = _layer_errors(ds, ref_layers, wl.N)
+        print("\n  [stack on a side stream] %s" % _fmt(rows))
+        assert rows.max() <= TOL[wl.dtype]
+        # the other reserved entry points
+        with torch.cuda.stream(side):
+            xd = ds.y[0]
+            y2, K2, V2 = torch.empty_like(xd), torch.zeros_like(ds.K[1]), torch.zeros_like(ds.V[1])
+            ctx.rt_layer_recompute(dls[1].struct, xd, ds.y[1], y2, K2, V2)
+            dx = torch.empty(xd.shape, dtype=torch.float32, device=xd.device)
+            ctx.rt_layer_backward(dls[1].struct, xd, ds.y[1], ds.y[1], None, None, dx, {})
+        side.synchronize()
+        assert ctx.workspace_bytes() == ws0, (ws0, ctx.workspace_bytes())
+        assert bool(torch.isfinite(dx).all())
+    finally:
+        ctx.rt_destroy()
