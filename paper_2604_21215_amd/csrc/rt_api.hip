@@ -997,8 +997,8 @@ extern "C" rt_status rt_layer_backward(rt_ctx *c, const rt_layer_weights *w, con
     BwGrads G = {grads->Wq, grads->Wk, grads->Wv, grads->Wo, grads->W1, grads->W2,
                  grads->g_attn, grads->g_mlp, grads->g_kv, grads->g_q, grads->g_k};
     c->engine = "backward";
-    hipError_t e = c->cfg.dtype == RT_BF16 ? backward_layer<bf16_t>(D, W, x, z, gy, gK, gV, dx, G, c->bw_slab, c->stream)
-                                           : backward_layer<float>(D, W, x, z, gy, gK, gV, dx, G, c->bw_slab, c->stream);
+    hipError_t e = c->cfg.dtype == RT_BF16 ? backward_layer<bf16_t>(D, W, x, z, gy, gK, gV, dx, G, c->bw_slab, c->use_mfma, c->stream)
+                                           : backward_layer<float>(D, W, x, z, gy, gK, gV, dx, G, c->bw_slab, false, c->stream);
     if (e != hipSuccess) return fail_hip(c, e, "backward_layer");
     return RT_OK;
 }

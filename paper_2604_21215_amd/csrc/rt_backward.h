@@ -14,8 +14,9 @@ struct BwGrads {
 size_t backward_scratch_bytes(size_t B, size_t N, size_t d, size_t F, size_t H, size_t E);
 
 // x, z, gy [B][N][d]; gK, gV [N][B][H][64] or null (storage type T); dx [B][N][d] fp32.
+// matrix_cores: with bf16 storage the batched products run on the matrix cores from bf16 copies of their operands.
 template <typename T>
 hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x, const void *z, const void *gy, const void *gK,
-                          const void *gV, float *dx, const BwGrads &G, void *ws, hipStream_t st);
+                          const void *gV, float *dx, const BwGrads &G, void *ws, bool matrix_cores, hipStream_t st);
 
 }  // namespace rt

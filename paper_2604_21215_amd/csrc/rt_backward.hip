@@ -14,9 +14,14 @@
 //       visited; blocks below kBwPmin keys are handled directly by each query (its "window");
 //   (C) after the loop, batched: dq over all (query, key) pairs, the gradients of the temporary pairs, x through the
 //       three projections and RMS, and every parameter sum as one product over all B N rows.
-// All arithmetic is fp32 on the vector ALUs (products in LDS-tiled kernels); the storage type T only decides how x, z,
-// gy, gK, gV and the weights are read.  Internal tensors are position-first: row r = n B + b.
+// Everything outside the batched products is fp32 on the vector ALUs; the storage type T decides how x, z, gy, gK, gV and
+// the weights are read.  The batched products are fp32 LDS-tiled kernels for fp32 storage; for bf16 storage (the
+// configurations' "bf16 compute with fp32 accumulation") they run on the matrix cores from bf16 copies of their
+// operands - the recompute's activations as bf16 head + bf16 remainder (two products: no rounding of q, k, h or the
+// MLP pre-activations that the forward engines avoid either), gradients rounded once.  Internal tensors are
+// position-first: row r = n B + b.
 #include "rt_base_case.h"
+#include "rt_gemm_tiled.h"
 #include "rt_backward.h"
 
 namespace rt {
@@ -217,6 +222,97 @@ static void gemm(hipStream_t st, const float *A, long a_rs, long a_cs, const flo
 {
     hipLaunchKernelGGL(bw_gemm_kernel, dim3((unsigned)((Nn + 63) / 64), (unsigned)((M + 63) / 64)), dim3(256), 0, st, A, a_rs, a_cs,
                        Bm, b_rs, b_cs, C, c_rs, M, Nn, K, alpha, accumulate ? 1 : 0);
+}
+
+
+// ------------------------------------------------------------------------------------------------ matrix-core products
+// C[m][n] (+)= alpha sum_k A[m][k] W[n][k] with A, W bf16 and the contraction index contiguous in both (rows lda, ldb
+// apart, K a multiple of 64), fp32 C, on the LDS-tiled main loop of the loop-free layers (256 x 128 block tile).
+// blockIdx.z = contraction slice (the parameter gradients contract over all B N rows but have few outputs): slice z
+// covers k in [z Ks, (z + 1) Ks) and, when gridDim.z > 1, writes its tile to part + z * M * Nn (dense, reduced afterwards).
+__global__ __launch_bounds__(256) void bw_mm_kernel(const bf16_t *__restrict__ A, size_t lda, const bf16_t *__restrict__ W, size_t ldb,
+                                                    float *__restrict__ C, size_t ldc, float *__restrict__ part, int M, int Nn, int Ks,
+                                                    float alpha, int accumulate)
+{
+    __shared__ __align__(16) bf16_t As[kGtRows * kGtLd];
+    __shared__ __align__(16) bf16_t Bs[kGtCols * kGtLd];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave >> 1, wn = wave & 1;
+    const int l32 = lane & 31, hi = lane >> 5;
+    const int m0 = blockIdx.x * kGtRows, nb0 = blockIdx.y * kGtCols;
+    const size_t k0 = (size_t)blockIdx.z * Ks;
+    const int prow = tid >> 3, pc = tid & 7;
+    const bf16_t *ga[8], *gb[4];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ga[i] = A + (size_t)min(m0 + prow + 32 * i, M - 1) * lda + k0 + pc * 8;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) gb[i] = W + (size_t)min(nb0 + prow + 32 * i, Nn - 1) * ldb + k0 + pc * 8;
+    f32x16_t acc[4][2];
+    tiled_mainloop(ga, gb, nullptr, Ks, As, Bs, acc);
+    const bool split = gridDim.z > 1;
+    float *out = split ? part + (size_t)blockIdx.z * M * Nn : C;
+    const size_t ldo = split ? (size_t)Nn : ldc;
+#pragma unroll
+    for (int mt = 0; mt < 4; ++mt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int m = m0 + wm * 128 + mt * 32 + 8 * (i / 4) + 4 * hi + (i % 4);
+            if (m >= M) continue;
+#pragma unroll
+            for (int nt = 0; nt < 2; ++nt) {
+                const int n = nb0 + wn * 64 + nt * 32 + l32;
+                if (n >= Nn) continue;
+                float *p = out + (size_t)m * ldo + n;
+                if (split) *p = acc[mt][nt][i];
+                else *p = accumulate ? *p + alpha * acc[mt][nt][i] : alpha * acc[mt][nt][i];
+            }
+        }
+}
+
+// C[m][n] (+)= alpha sum_z part[z][m][n]  (fixed order: runs are bit-reproducible)
+__global__ __launch_bounds__(256) void bw_mm_reduce_kernel(const float *__restrict__ part, int S, float *__restrict__ C, size_t ldc,
+                                                           int M, int Nn, float alpha, int accumulate)
+{
+    const size_t n_el = (size_t)M * Nn;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n_el; e += (size_t)gridDim.x * 256) {
+        float s = 0.f;
+        for (int z = 0; z < S; ++z) s += part[(size_t)z * n_el + e];
+        float *p = C + (e / Nn) * ldc + e % Nn;
+        *p = accumulate ? *p + alpha * s : alpha * s;
+    }
+}
+
+// fp32 rows -> bf16 head (and, if lo is given, the bf16 remainder v - head): in [R][ldi], out [R][ldo]
+__global__ __launch_bounds__(256) void bw_split_rows_kernel(const float *__restrict__ in, size_t ldi, bf16_t *__restrict__ hi_out,
+                                                            bf16_t *__restrict__ lo_out, size_t ldo, int R, int Cn)
+{
+    const size_t n_el = (size_t)R * Cn;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n_el; e += (size_t)gridDim.x * 256) {
+        const size_t r = e / Cn, c = e % Cn;
+        const float v = in[r * ldi + c];
+        const bf16_t h = f32_to_bf16(v);
+        hi_out[r * ldo + c] = h;
+        if (lo_out) lo_out[r * ldo + c] = f32_to_bf16(v - bf16_to_f32(h));
+    }
+}
+
+// fp32 [R][ldi] (columns c0 .. c0 + Cn - 1) -> bf16 transposed [Cn][ldo], columns R .. Rp - 1 of the output zero.
+// grid (ceil(Rp / 64), ceil(Cn / 64)), block 256.
+__global__ __launch_bounds__(256) void bw_transpose_bf16_kernel(const float *__restrict__ in, size_t ldi, int c0, bf16_t *__restrict__ out,
+                                                                size_t ldo, int R, int Rp, int Cn)
+{
+    __shared__ float tile[64][65];
+    const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+    const int r0 = blockIdx.x * 64, cb = blockIdx.y * 64;
+    for (int j = ty; j < 64; j += 4) {
+        const int r = r0 + j, c = cb + tx;
+        tile[j][tx] = (r < R && c < Cn) ? in[(size_t)r * ldi + c0 + c] : 0.f;
+    }
+    __syncthreads();
+    for (int j = ty; j < 64; j += 4) {
+        const int c = cb + j, r = r0 + tx;
+        if (c < Cn && r < Rp) out[(size_t)c * ldo + r] = f32_to_bf16(tile[tx][j]);
+    }
 }
 
 // small-M product of the reverse loop: out[b][o] = epilogue(sum_k W[o][k] in[b][k]) with the forward's gemv_body
@@ -655,7 +751,21 @@ struct BwBufs {
     float *c, *lse, *a, *unit_h, *hg, *rinv_h, *gp, *act;
     float *dK, *dV, *in_kv, *dkraw, *d_rz, *Gz, *dmo, *dpre, *t1, *d_h, *da, *dc, *Ds, *dq, *dkt, *dvt;
     float *G3, *dn;
+    // matrix-core path (bf16 storage): bf16 copies of the products' operands
+    bf16_t *op_hi, *op_lo;   // [M][d] head and remainder of the recompute's activations, one product at a time
+    bf16_t *G3_b;            // [M][3d]
+    bf16_t *WqkvT_b;         // [d][3d]
+    bf16_t *tA, *tB;         // transposed operands of the parameter sums, [rows][Mp]
+    float *part;             // contraction slices of a parameter sum
 };
+
+// contraction slices of the parameter sums over M rows: as many as keep 512 rows and more per slice, at most 16
+int bw_slices(size_t M)
+{
+    int S = 1;
+    while (S < 16 && M / (2 * (size_t)S) >= 512) S *= 2;
+    return S;
+}
 
 size_t carve_bufs(BwBufs &Bf, char *base, size_t B, size_t N, size_t d, size_t F, size_t H, size_t E, bool gains)
 {
@@ -676,6 +786,11 @@ size_t carve_bufs(BwBufs &Bf, char *base, size_t B, size_t N, size_t d, size_t F
     Bf.t1 = cv.take<float>(M * d); Bf.d_h = cv.take<float>(M * d); Bf.da = cv.take<float>(B * d); Bf.dc = cv.take<float>(M * d);
     Bf.Ds = cv.take<float>(M * H); Bf.dq = cv.take<float>(M * d); Bf.dkt = cv.take<float>(M * d); Bf.dvt = cv.take<float>(M * d);
     Bf.G3 = cv.take<float>(M * 3 * d); Bf.dn = cv.take<float>(M * d);
+    const size_t Mp = M + 64 * 16, wide = 3 * d > F ? 3 * d : F;
+    Bf.op_hi = cv.take<bf16_t>(M * d); Bf.op_lo = cv.take<bf16_t>(M * d);
+    Bf.G3_b = cv.take<bf16_t>(M * 3 * d); Bf.WqkvT_b = cv.take<bf16_t>(3 * d * d);
+    Bf.tA = cv.take<bf16_t>(wide * Mp); Bf.tB = cv.take<bf16_t>((F > d ? F : d) * Mp);
+    Bf.part = cv.take<float>(16 * d * d > 4 * F * d ? 16 * d * d : 4 * F * d);
     return cv.off;
 }
 
@@ -700,7 +815,7 @@ size_t backward_scratch_bytes(size_t B, size_t N, size_t d, size_t F, size_t H, 
 
 template <typename T>
 hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, const void *z_, const void *gy_, const void *gK_,
-                          const void *gV_, float *dx, const BwGrads &G, void *ws, hipStream_t st)
+                          const void *gV_, float *dx, const BwGrads &G, void *ws, bool matrix_cores, hipStream_t st)
 {
     const int B = D.B, N = D.N, d = D.d, F = D.F, H = D.H, M = B * N, BH = B * H, nf = D.norm_free;
     const T *x = (const T *)x_, *z = (const T *)z_, *gy = (const T *)gy_;
@@ -716,14 +831,37 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
     const dim3 blk(256);
     auto grid1 = [](size_t n) { return dim3((unsigned)((n + 255) / 256 < 4096 ? (n + 255) / 256 : 4096)); };
     const size_t dd = (size_t)d * d, dF = (size_t)d * F;
+    // bf16 storage: the batched products on the matrix cores
+    const bool mm = matrix_cores && sizeof(T) == 2 && F % 64 == 0;
+    // C[M][Nn] = A_bf16 [M][K] (rows lda) times W_bf16 [Nn][K]^T (rows ldb), optionally sliced over the contraction
+    auto mm_nt = [&](const bf16_t *A, size_t lda, const bf16_t *Wb, size_t ldb, float *C, size_t ldc, int Mo, int Nn, int K, float alpha,
+                     bool accumulate, int slices) {
+        const dim3 g((unsigned)((Mo + kGtRows - 1) / kGtRows), (unsigned)((Nn + kGtCols - 1) / kGtCols), (unsigned)slices);
+        hipLaunchKernelGGL(bw_mm_kernel, g, blk, 0, st, A, lda, Wb, ldb, C, ldc, Bf.part, Mo, Nn, K / slices, alpha, accumulate ? 1 : 0);
+        if (slices > 1)
+            hipLaunchKernelGGL(bw_mm_reduce_kernel, grid1((size_t)Mo * Nn), blk, 0, st, Bf.part, slices, C, ldc, Mo, Nn, alpha,
+                               accumulate ? 1 : 0);
+    };
+    // recompute product C[M][Nn] = Act [M][d] Wt^T with the activation as bf16 head + remainder (Wt: the caller's bf16 matrix)
+    auto act_times_w = [&](const float *Act, const void *Wt, const float *Wf, float *C, size_t ldc, int Nn) {
+        if (mm) {
+            hipLaunchKernelGGL(bw_split_rows_kernel, grid1((size_t)M * d), blk, 0, st, Act, (size_t)d, Bf.op_hi, Bf.op_lo, (size_t)d, M, d);
+            mm_nt(Bf.op_lo, d, (const bf16_t *)Wt, d, C, ldc, M, Nn, d, 1.f, false, 1);
+            mm_nt(Bf.op_hi, d, (const bf16_t *)Wt, d, C, ldc, M, Nn, d, 1.f, true, 1);
+        } else {
+            gemm(st, Act, d, 1, Wf, d, 1, C, (long)ldc, M, Nn, d, 1.f, false);
+        }
+    };
 
     // ---- weights: fp32 copies for the products, transposed copies (storage type) for the loop's small-M products
-    hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dd), blk, 0, st, (const T *)W.Wq, Bf.Wqkv_f, dd);
-    hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dd), blk, 0, st, (const T *)W.Wk, Bf.Wqkv_f + dd, dd);
-    hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dd), blk, 0, st, (const T *)W.Wv, Bf.Wqkv_f + 2 * dd, dd);
-    hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dd), blk, 0, st, (const T *)W.Wo, Bf.Wo_f, dd);
-    hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dF), blk, 0, st, (const T *)W.W1, Bf.W1_f, dF);
-    hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dF), blk, 0, st, (const T *)W.W2, Bf.W2_f, dF);
+    if (!mm) {
+        hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dd), blk, 0, st, (const T *)W.Wq, Bf.Wqkv_f, dd);
+        hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dd), blk, 0, st, (const T *)W.Wk, Bf.Wqkv_f + dd, dd);
+        hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dd), blk, 0, st, (const T *)W.Wv, Bf.Wqkv_f + 2 * dd, dd);
+        hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dd), blk, 0, st, (const T *)W.Wo, Bf.Wo_f, dd);
+        hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dF), blk, 0, st, (const T *)W.W1, Bf.W1_f, dF);
+        hipLaunchKernelGGL(bw_to_f32_kernel<T>, grid1(dF), blk, 0, st, (const T *)W.W2, Bf.W2_f, dF);
+    }
     auto transpose = [&](const void *in, void *out, int rows, int cols, size_t ldo, int col0) {
         hipLaunchKernelGGL(bw_transpose_kernel<T>, dim3((unsigned)((cols + 31) / 32), (unsigned)((rows + 31) / 32)), blk, 0, st,
                            (const T *)in, (T *)out, rows, cols, ldo, col0);
@@ -733,27 +871,50 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
     transpose(W.W2, Bf.W2T, d, F, (size_t)d, 0);         // W2 [d][F] -> [F][d]
     transpose(W.W1, Bf.W1T, F, d, (size_t)F, 0);         // W1 [F][d] -> [d][F]
     transpose(W.Wo, Bf.WoT, d, d, (size_t)d, 0);
+    if (mm) {   // [Wq; Wk; Wv]^T as [d][3d]
+        transpose(W.Wq, Bf.WqkvT_b, d, d, 3 * (size_t)d, 0);
+        transpose(W.Wk, Bf.WqkvT_b, d, d, 3 * (size_t)d, d);
+        transpose(W.Wv, Bf.WqkvT_b, d, d, 3 * (size_t)d, 2 * d);
+    }
 
     // ---- (A) recompute
     hipLaunchKernelGGL(bw_rows_norm_kernel<T>, dim3(M), blk, 0, st, x, (const float *)nullptr, 0.f, g_attn, Bf.unit_x, Bf.nxg, Bf.rinv_x,
                        B, N, d, D.eps, nf);
-    gemm(st, Bf.nxg, d, 1, Bf.Wqkv_f, d, 1, Bf.qkv, 3 * d, M, 3 * d, d, 1.f, false);
+    if (mm) {
+        hipLaunchKernelGGL(bw_split_rows_kernel, grid1((size_t)M * d), blk, 0, st, Bf.nxg, (size_t)d, Bf.op_hi, Bf.op_lo, (size_t)d, M, d);
+        const void *w3[3] = {W.Wq, W.Wk, W.Wv};
+        for (int j = 0; j < 3; ++j) {
+            mm_nt(Bf.op_lo, d, (const bf16_t *)w3[j], d, Bf.qkv + (size_t)j * d, 3 * (size_t)d, M, d, d, 1.f, false, 1);
+            mm_nt(Bf.op_hi, d, (const bf16_t *)w3[j], d, Bf.qkv + (size_t)j * d, 3 * (size_t)d, M, d, d, 1.f, true, 1);
+        }
+    } else {
+        gemm(st, Bf.nxg, d, 1, Bf.Wqkv_f, d, 1, Bf.qkv, 3 * d, M, 3 * d, d, 1.f, false);
+    }
     hipLaunchKernelGGL(bw_head_norm_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.qkv, 3 * d, 0, g_q, Bf.Qn, Bf.rq, H, D.eps, nf);
     hipLaunchKernelGGL(bw_head_norm_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.qkv, 3 * d, d, g_k, Bf.Ktn, Bf.rkt, H, D.eps, nf);
     hipLaunchKernelGGL(bw_head_norm_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.qkv, 3 * d, 2 * d, (const T *)nullptr, Bf.Vt,
                        (float *)nullptr, H, D.eps, nf);
     hipLaunchKernelGGL(bw_rows_norm_kernel<T>, dim3(M), blk, 0, st, z, (const float *)nullptr, 0.f, g_kv, Bf.unit_z, Bf.nzg, Bf.rinv_z,
                        B, N, d, D.eps, nf);
-    gemm(st, Bf.nzg, d, 1, Bf.Wqkv_f + dd, d, 1, Bf.kv, 2 * d, M, 2 * d, d, 1.f, false);
+    if (mm) {
+        hipLaunchKernelGGL(bw_split_rows_kernel, grid1((size_t)M * d), blk, 0, st, Bf.nzg, (size_t)d, Bf.op_hi, Bf.op_lo, (size_t)d, M, d);
+        const void *w2[2] = {W.Wk, W.Wv};
+        for (int j = 0; j < 2; ++j) {
+            mm_nt(Bf.op_lo, d, (const bf16_t *)w2[j], d, Bf.kv + (size_t)j * d, 2 * (size_t)d, M, d, d, 1.f, false, 1);
+            mm_nt(Bf.op_hi, d, (const bf16_t *)w2[j], d, Bf.kv + (size_t)j * d, 2 * (size_t)d, M, d, d, 1.f, true, 1);
+        }
+    } else {
+        gemm(st, Bf.nzg, d, 1, Bf.Wqkv_f + dd, d, 1, Bf.kv, 2 * d, M, 2 * d, d, 1.f, false);
+    }
     hipLaunchKernelGGL(bw_head_norm_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.kv, 2 * d, 0, g_k, Bf.Kp, Bf.rk, H, D.eps, nf);
     hipLaunchKernelGGL(bw_head_norm_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.kv, 2 * d, d, (const T *)nullptr, Bf.Vp,
                        (float *)nullptr, H, D.eps, nf);
     hipLaunchKernelGGL(bw_attn_fwd_kernel, dim3(BH, N), dim3(64), 0, st, Bf.Qn, Bf.Ktn, Bf.Vt, Bf.Kp, Bf.Vp, Bf.c, Bf.lse, B, H, D.scale,
                        D.alibi);
-    gemm(st, Bf.c, d, 1, Bf.Wo_f, d, 1, Bf.a, d, M, d, d, 1.f, false);
+    act_times_w(Bf.c, W.Wo, Bf.Wo_f, Bf.a, (size_t)d, d);
     hipLaunchKernelGGL(bw_rows_norm_kernel<T>, dim3(M), blk, 0, st, x, Bf.a, D.alpha, g_mlp, Bf.unit_h, Bf.hg, Bf.rinv_h, B, N, d, D.eps,
                        nf);
-    gemm(st, Bf.hg, d, 1, Bf.W1_f, d, 1, Bf.gp, F, M, F, d, 1.f, false);
+    act_times_w(Bf.hg, W.W1, Bf.W1_f, Bf.gp, (size_t)F, F);
     hipLaunchKernelGGL(bw_gelu_kernel, grid1((size_t)M * F), blk, 0, st, Bf.gp, Bf.act, Bf.gp, (size_t)M * F);
 
     // ---- (B) the reverse loop
@@ -795,9 +956,42 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
     hipLaunchKernelGGL(bw_head_norm_bw_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.dvt, Bf.qkv, 3 * d, 0, (const float *)nullptr,
                        (const T *)nullptr, Bf.G3, 3 * d, 2 * d, H, nf);
     // dn = [dq_raw | dkt_raw | dvt] [Wq; Wk; Wv]
-    gemm(st, Bf.G3, 3 * d, 1, Bf.Wqkv_f, 1, d, Bf.dn, d, M, d, 3 * d, 1.f, false);
+    if (mm) {
+        hipLaunchKernelGGL(bw_split_rows_kernel, grid1((size_t)M * 3 * d), blk, 0, st, Bf.G3, 3 * (size_t)d, Bf.G3_b, (bf16_t *)nullptr,
+                           3 * (size_t)d, M, 3 * d);
+        mm_nt(Bf.G3_b, 3 * (size_t)d, Bf.WqkvT_b, 3 * (size_t)d, Bf.dn, (size_t)d, M, d, 3 * d, 1.f, false, 1);
+    } else {
+        gemm(st, Bf.G3, 3 * d, 1, Bf.Wqkv_f, 1, d, Bf.dn, d, M, d, 3 * d, 1.f, false);
+    }
     hipLaunchKernelGGL(bw_dx_kernel<T>, dim3(M), blk, 0, st, Bf.dn, Bf.unit_x, Bf.rinv_x, g_attn, Bf.d_h, dx, B, N, d, nf);
     // parameter sums over all rows:  dW[n][k] = sum_r G[r][n] In[r][k]
+    if (mm) {
+        const int S = bw_slices((size_t)M), SF = S >= 4 ? S / 4 : 1;
+        const int Ks = (int)((((size_t)M + S - 1) / S + 63) / 64 * 64), Mp = S * Ks;
+        // transposed bf16 copy [Cn][Mp] of columns c0.. of a [M][ld] tensor (the tail M..Mp is zero)
+        auto tr = [&](const float *in, size_t ld, int c0, int Cn, bf16_t *out) {
+            hipLaunchKernelGGL(bw_transpose_bf16_kernel, dim3((unsigned)((Mp + 63) / 64), (unsigned)((Cn + 63) / 64)), blk, 0, st, in, ld, c0,
+                               out, (size_t)Mp, M, Mp, Cn);
+        };
+        auto wsum = [&](int rowsA, int rowA0, int rowsB, float *C, float alpha, bool acc, int slices) {
+            mm_nt(Bf.tA + (size_t)rowA0 * Mp, (size_t)Mp, Bf.tB, (size_t)Mp, C, (size_t)rowsB, rowsA, rowsB, Mp, alpha, acc, slices);
+        };
+        if (G.Wq || G.Wk || G.Wv) {
+            tr(Bf.G3, 3 * (size_t)d, 0, 3 * d, Bf.tA);
+            tr(Bf.nxg, (size_t)d, 0, d, Bf.tB);
+            if (G.Wq) wsum(d, 0, d, G.Wq, 1.f, false, S);
+            if (G.Wk) wsum(d, d, d, G.Wk, 1.f, false, S);
+            if (G.Wv) wsum(d, 2 * d, d, G.Wv, 1.f, false, S);
+        }
+        if (G.Wk || G.Wv) {
+            tr(Bf.nzg, (size_t)d, 0, d, Bf.tB);
+            if (G.Wk) { tr(Bf.dkraw, (size_t)d, 0, d, Bf.tA); wsum(d, 0, d, G.Wk, 1.f, true, S); }
+            if (G.Wv) { tr(Bf.dV, (size_t)d, 0, d, Bf.tA); wsum(d, 0, d, G.Wv, 1.f, true, S); }
+        }
+        if (G.Wo) { tr(Bf.d_h, (size_t)d, 0, d, Bf.tA); tr(Bf.c, (size_t)d, 0, d, Bf.tB); wsum(d, 0, d, G.Wo, D.alpha, false, S); }
+        if (G.W1) { tr(Bf.dpre, (size_t)F, 0, F, Bf.tA); tr(Bf.hg, (size_t)d, 0, d, Bf.tB); wsum(F, 0, d, G.W1, 1.f, false, SF); }
+        if (G.W2) { tr(Bf.Gz, (size_t)d, 0, d, Bf.tA); tr(Bf.act, (size_t)F, 0, F, Bf.tB); wsum(d, 0, F, G.W2, D.alpha, false, SF); }
+    } else {
     if (G.Wq) gemm(st, Bf.G3, 1, 3 * d, Bf.nxg, 1, d, G.Wq, d, d, d, M, 1.f, false);
     if (G.Wk) {
         gemm(st, Bf.G3 + d, 1, 3 * d, Bf.nxg, 1, d, G.Wk, d, d, d, M, 1.f, false);
@@ -810,6 +1004,7 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
     if (G.Wo) gemm(st, Bf.d_h, 1, d, Bf.c, 1, d, G.Wo, d, d, d, M, D.alpha, false);
     if (G.W1) gemm(st, Bf.dpre, 1, F, Bf.hg, 1, d, G.W1, d, F, d, M, 1.f, false);
     if (G.W2) gemm(st, Bf.Gz, 1, d, Bf.act, 1, F, G.W2, F, d, F, M, D.alpha, false);
+    }
     // gains
     if (nf) {
         float *gs[5] = {G.g_attn, G.g_mlp, G.g_kv, G.g_q, G.g_k};
@@ -834,8 +1029,8 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
 }
 
 template hipError_t backward_layer<float>(const LayerDims &, const Weights &, const void *, const void *, const void *, const void *,
-                                          const void *, float *, const BwGrads &, void *, hipStream_t);
+                                          const void *, float *, const BwGrads &, void *, bool, hipStream_t);
 template hipError_t backward_layer<bf16_t>(const LayerDims &, const Weights &, const void *, const void *, const void *, const void *,
-                                           const void *, float *, const BwGrads &, void *, hipStream_t);
+                                           const void *, float *, const BwGrads &, void *, bool, hipStream_t);
 
 }  // namespace rt

@@ -174,7 +174,7 @@ __global__ __launch_bounds__(256) void cross_mfma_kernel(const bf16_t *__restric
 // decoded such that all query blocks of one (b, h) land on the same XCD and its key/value tiles are
 // fetched into that L2 once.  The HP form's three LDS tiles per buffer leave room for two workgroups per compute unit.
 #define RT_CROSS_TILE_KERNEL(NAME, HPv, WAVES)                                                                              \
-    template <bool ALIBI>                                                                                                   \
+    template <bool ALIBI, int VAR = kCtVarDefault>                                                                          \
     __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(WAVES, WAVES))) void NAME(                        \
         const bf16_t *__restrict__ Q, const float *__restrict__ Qf, const bf16_t *__restrict__ K,                          \
         const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT, int vt_stride, float *__restrict__ pm,              \
@@ -185,7 +185,7 @@ __global__ __launch_bounds__(256) void cross_mfma_kernel(const bf16_t *__restric
         const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;                                                                \
         const int bh = (j / nqb) * 8 + xcd, qb = j % nqb;                                                                   \
         if (bh >= BH) return; /* the whole workgroup leaves together */                                                     \
-        cross_tile_wg<HPv, 4, 2, ALIBI>(Q, Qf, K, Klo, VT, vt_stride, pm, pl, po, BH, bh, t1, 0, t1 - P, P,                 \
+        cross_tile_wg<HPv, 4, 2, ALIBI, HPv, VAR>(Q, Qf, K, Klo, VT, vt_stride, pm, pl, po, BH, bh, t1, 0, t1 - P, P,       \
                                         qb * 128 + (int)(threadIdx.x >> 6) * 32, nq, level, level_rel, slots, scale, lds,   \
                                         (int)threadIdx.x, ALIBI ? alibi_slope(alibi, bh % H, H) : 0.f);                     \
     }

@@ -15,7 +15,7 @@ GAINS = ("g_attn", "g_mlp", "g_kv", "g_q", "g_k")
 
 
 def _run(oracle, dtype, B, N, d, H, F, *, gains="random", alpha=1.0, scale=1.0, alibi=0.0, seed=31, shared_kv_gain=False,
-         norm_free=False, with_pair_grads=True, z_from_gpu=False, tol=None):
+         norm_free=False, with_pair_grads=True, z_from_gpu=False, tol=None, no_mfma=False):
     if not torch.cuda.is_available():
         pytest.fail("no GPU visible")
     from oracle import rt_backward as bwd
@@ -36,7 +36,7 @@ def _run(oracle, dtype, B, N, d, H, F, *, gains="random", alpha=1.0, scale=1.0, 
     gK = store(rng.standard_normal((N, B, H, d // H))) if with_pair_grads else None
     gV = store(rng.standard_normal((N, B, H, d // H))) if with_pair_grads else None
 
-    flags = binding.RT_FLAG_NORM_FREE if norm_free else 0
+    flags = (binding.RT_FLAG_NORM_FREE if norm_free else 0) | (binding.RT_FLAG_NO_MFMA if no_mfma else 0)
     ctx = binding.RTContext(d, H, F, B, N, dtype, resid_scale=alpha, attn_scale=scale, rms_eps=1e-6, alibi_max_bias=alibi,
                             flags=flags, stream=torch.cuda.current_stream().cuda_stream)
     try:
@@ -101,9 +101,14 @@ def test_backward_fp32_without_pair_gradients(oracle):
     _run(oracle, "f32", 2, 50, 128, 2, 256, scale=0.5, with_pair_grads=False, gains="unit")
 
 
-@pytest.mark.parametrize("B,N,d,H,F,scale", [(3, 200, 256, 4, 1024, 0.25), (8, 130, 512, 8, 2048, 0.125)])
-def test_backward_bf16_storage(oracle, B, N, d, H, F, scale):
-    _run(oracle, "bf16", B, N, d, H, F, scale=scale, alpha=0.7)
+@pytest.mark.parametrize("B,N,d,H,F,scale,no_mfma", [(3, 200, 256, 4, 1024, 0.25, False), (8, 130, 512, 8, 2048, 0.125, False),
+                                                     (2, 300, 1024, 16, 4096, 1.0, False),   # the headline width, unscaled logits
+                                                     (5, 333, 192, 3, 448, 0.25, False),     # ragged tiles of the products
+                                                     (3, 200, 256, 4, 1024, 0.25, True)])    # fp32 products on bf16 storage
+def test_backward_bf16_storage(oracle, B, N, d, H, F, scale, no_mfma):
+    """bf16 storage: the batched products run on the matrix cores from bf16 copies of their operands (the recompute's
+    activations as head + remainder), everything else in fp32; with RT_FLAG_NO_MFMA all of it is fp32."""
+    _run(oracle, "bf16", B, N, d, H, F, scale=scale, alpha=0.7, no_mfma=no_mfma)
 
 
 def test_backward_bf16_from_the_gpu_forward(oracle):
