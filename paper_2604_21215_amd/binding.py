@@ -8,6 +8,7 @@ from __future__ import annotations
 
 import ctypes as C
 import os
+import sys as _sys
 
 from . import build as _build
 
@@ -330,8 +331,7 @@ class RTContext:
             self._ctx = C.c_void_p()
 
     def __del__(self):
-        import sys
-        if sys is None or sys.is_finalizing():   # no HIP calls while the interpreter (and the runtimes behind it) shut down
+        if _sys is None or _sys.is_finalizing():   # no HIP calls while the interpreter (and the runtimes behind it) shut down
             return
         try:
             self.rt_destroy()

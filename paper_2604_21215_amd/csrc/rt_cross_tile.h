@@ -84,9 +84,15 @@ __device__ __forceinline__ f32x16_t mfma32u(const uint4 &a, const uint4 &b, f32x
 // per-logit multiply-add before the exponential disappears (the reference moves rarely; then S is corrected by the
 // difference).  2 = DOT: the row sums are taken from the bf16 weights that also multiply V (pairs through
 // v_dot2c_f32_bf16 against (1, 1): 16 instead of 32 additions per chunk, and o / l then uses one set of weights).
-// Measured on MI355X (P = 1024 event, 128 (b, h)): 51.0 us without, 49.8 us with FOLD, 51.2 us with DOT, 49.9 us with both:
-// the instruction count of the softmax is not what bounds the tile.  FOLD is on.
-constexpr int kCtVarDefault = 1;
+// 4 = PRIO: a wavefront lowers its issue priority by one step per quarter of its chunks (see the chunk loop).
+// Measured on MI355X (P = 1024 event, 128 (b, h), stand-alone launches): 51.0 us without, 49.8 us with FOLD, 51.2 us
+// with DOT, 49.9 us with both: the instruction count of the softmax is not what bounds the tile.  Stamps at the start
+// and end of every workgroup (all 1024 start within 0.6 us): lifetimes 22.6 .. 46.1 us, median 34.7 - the four
+// wavefronts of a SIMD finish one after the other; with PRIO 33.7 .. 43.7 us and the launch ends at 43.9 instead of
+// 46.3 us (512 keys: 16.2 instead of 17.2 us; no gain below 8 chunks).  One wavefront alone on a SIMD needs 1.55 us
+// per chunk, two 1.69 us each, four 2.2 us each.  A whole cfg3 prefill of the persistent engine, whose tiles run inline:
+// 35.88 ms without, 35.63 ms with FOLD, 36.68 ms with FOLD and PRIO.  FOLD is on everywhere, PRIO in stand-alone launches.
+constexpr int kCtVarDefault = 5;
 template <bool HP, int NW, int NBUF, bool ALIBI = false, bool F16 = HP, int VAR = kCtVarDefault>
 __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, const float *__restrict__ Qf,
                                               const bf16_t *__restrict__ K, const bf16_t *__restrict__ Klo,
@@ -108,6 +114,7 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
     const float c2 = scale * kLog2e;
     constexpr bool FOLD = (VAR & 1) && HP && F16 && !ALIBI;
     constexpr bool DOT = (VAR & 2) != 0;
+    constexpr bool PRIO = (VAR & 4) != 0 && NBUF == 2;   // stand-alone launches only: inside the persistent kernel it cost 3 % of a call
 
     // ---- this wavefront's 32 queries as B fragments (contraction step ks covers head dimensions 16ks .. 16ks+15)
     uint4 bq[4], bql[4];
@@ -194,6 +201,17 @@ __device__ __forceinline__ void cross_tile_wg(const bf16_t *__restrict__ Q, cons
     const int nchunks = P / kKC;
     for (int c = 0; c < nchunks; ++c) {
         const int cur = (NBUF == 2) ? (c & 1) : 0;
+        if (PRIO && nchunks >= 8 && (4 * c) % nchunks == 0) {
+            // The issue arbiter of a SIMD prefers its oldest wavefront, which then runs at its solo speed and leaves early
+            // while the youngest takes twice as long, and the SIMD spends the second half of the launch with one to three
+            // wavefronts instead of four.  A wavefront lowers its own priority as it gets ahead: those behind catch up.
+            switch ((4 * c) / nchunks) {
+            case 0: __builtin_amdgcn_s_setprio(3); break;
+            case 1: __builtin_amdgcn_s_setprio(2); break;
+            case 2: __builtin_amdgcn_s_setprio(1); break;
+            default: __builtin_amdgcn_s_setprio(0); break;
+            }
+        }
         if (c + 1 < nchunks) { RT_CT_FETCH((c + 1) * kKC) }
         if (active) {
             const bf16_t *Ks = tiles + (size_t)cur * BUF, *Vs = Ks + TILE, *Kl = Ks + 2 * TILE;
