@@ -387,17 +387,46 @@ __global__ __launch_bounds__(256) void bw_norm_bw_row_kernel(const float *__rest
                                                              float alpha, int i, int B, int d, int norm_free)
 {
     __shared__ float red[4];
+    constexpr int kPer = 8;   // elements per thread held in registers: every load of the row is issued before the reduction
     const int b = blockIdx.x;
     const size_t r = (size_t)i * B + b;
     const float *gi = g_in + r * d, *un = unit + r * d;
     const BASE_T *bs = base + (size_t)b * base_bstride;
     const bool use_g = gain != nullptr && !norm_free;
+    const float ri = rinv[r];
+    if (d <= 256 * kPer) {
+        float w[kPer], u[kPer], bv[kPer];
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) {
+            const int k = threadIdx.x + 256 * e;
+            const bool in = k < d;
+            const float g = in ? gi[k] : 0.f;
+            w[e] = (use_g && in) ? g * to_f32(gain[k]) : g;
+            u[e] = in ? un[k] : 0.f;
+            bv[e] = in ? to_f32(bs[k]) : 0.f;
+        }
+        float dot = 0.f;
+        if (!norm_free) {
+#pragma unroll
+            for (int e = 0; e < kPer; ++e) dot = fmaf(u[e], w[e], dot);
+            dot = block_sum_256(dot, red) / (float)d;
+        }
+#pragma unroll
+        for (int e = 0; e < kPer; ++e) {
+            const int k = threadIdx.x + 256 * e;
+            if (k < d) {
+                const float v = bv[e] + (norm_free ? w[e] : ri * (w[e] - u[e] * dot));
+                out_row[r * d + k] = v;
+                out_scaled[(size_t)b * d + k] = alpha * v;
+            }
+        }
+        return;
+    }
     float dot = 0.f;
     if (!norm_free) {
         for (int k = threadIdx.x; k < d; k += 256) dot = fmaf(un[k], use_g ? gi[k] * to_f32(gain[k]) : gi[k], dot);
         dot = block_sum_256(dot, red) / (float)d;
     }
-    const float ri = rinv[r];
     for (int k = threadIdx.x; k < d; k += 256) {
         const float w = use_g ? gi[k] * to_f32(gain[k]) : gi[k];
         const float v = to_f32(bs[k]) + (norm_free ? w : ri * (w - un[k] * dot));
@@ -411,13 +440,20 @@ __global__ __launch_bounds__(256) void bw_norm_bw_row_kernel(const float *__rest
 //   Dsum = <dc, c>;  p = exp(logit - lse);  dp = <dc, v>;  ds = p (dp - Dsum);
 //   dV_j += p_j dc,  dK_j += scale ds_j q   (window keys);   dvt_i = p_own dc,  dkt_i = scale ds_own q,
 //   dq_i = scale ds_own kt_i (the keys' share of dq_i is added after the loop).  grid B H, block 64.
+template <typename T>
 __global__ __launch_bounds__(64) void bw_attn_row_kernel(const float *__restrict__ Qn, const float *__restrict__ Ktn,
                                                          const float *__restrict__ Vt, const float *__restrict__ Kp,
                                                          const float *__restrict__ Vp, const float *__restrict__ cbuf,
                                                          const float *__restrict__ dc, const float *__restrict__ lse,
-                                                         float *__restrict__ Ds, float *__restrict__ dK, float *__restrict__ dV,
+                                                         float *__restrict__ Ds, float *dK, float *dV,
                                                          float *__restrict__ dq, float *__restrict__ dkt, float *__restrict__ dvt,
-                                                         int i, int B, int H, float scale, float alibi)
+                                                         int i, int B, int H, float scale, float alibi,
+                                                         // when fuse_pair: the per-head normalisation backward of position i - 1
+                                                         // (bw_pair_grad_kernel's work) by the same wavefront, whose own window
+                                                         // update was the last contribution to dK, dV of that position
+                                                         int fuse_pair, const float *__restrict__ unit_k, const float *__restrict__ rk,
+                                                         const T *__restrict__ g_k, float *__restrict__ dkraw, float *__restrict__ in_kv,
+                                                         int norm_free)
 {
     const int bh = blockIdx.x, lane = threadIdx.x;
     const size_t rs = (size_t)B * H * kHeadDim;
@@ -432,28 +468,61 @@ __global__ __launch_bounds__(64) void bw_attn_row_kernel(const float *__restrict
     dq[off] = scale * ds_own * kt;
     if (lane == 0) Ds[(size_t)i * B * H + bh] = Dsum;
     const int w = i & (kBwPmin - 1);
-    if (w == 0) return;
-    const int j0 = i - w;
-    const size_t kb = (size_t)(j0 + min(lane, w - 1)) * rs + (size_t)bh * kHeadDim;   // lane j < w owns key j0 + j
-    float s = 0.f, dp = 0.f;
+    float dk_prev = 0.f, dv_prev = 0.f;   // dK, dV of position i - 1 after this query's update (fuse_pair needs w > 0)
+    if (w > 0) {
+        const int j0 = i - w;
+        const size_t kb = (size_t)(j0 + min(lane, w - 1)) * rs + (size_t)bh * kHeadDim;   // lane j < w owns key j0 + j
+        float s = 0.f, dp = 0.f;
 #pragma unroll
-    for (int c8 = 0; c8 < 8; ++c8) {
-        float kk[8], vv[8];
-        load8(Kp + kb + c8 * 8, kk);
-        load8(Vp + kb + c8 * 8, vv);
+        for (int c8 = 0; c8 < 8; ++c8) {
+            float kk[8], vv[8];
+            load8(Kp + kb + c8 * 8, kk);
+            load8(Vp + kb + c8 * 8, vv);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            s = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], s);
-            dp = fmaf(lane_bcast(g, c8 * 8 + e), vv[e], dp);
+            for (int e = 0; e < 8; ++e) {
+                s = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], s);
+                dp = fmaf(lane_bcast(g, c8 * 8 + e), vv[e], dp);
+            }
+        }
+        const float slope = alibi_slope(alibi, bh % H, H);
+        const float p = lane < w ? expf(fmaf(-slope, (float)(w - lane), s * scale) - L) : 0.f;
+        const float ds = p * (dp - Dsum);
+        // eight rows at a time: all their loads are issued before the first store (the rows are distinct)
+        for (int jb = 0; jb < w; jb += 8) {
+            float av[8], ak[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const size_t o = (size_t)(j0 + min(jb + e, w - 1)) * rs + (size_t)bh * kHeadDim + lane;
+                av[e] = dV[o];
+                ak[e] = dK[o];
+            }
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int j = jb + e;
+                if (j < w) {   // wave-uniform
+                    const size_t o = (size_t)(j0 + j) * rs + (size_t)bh * kHeadDim + lane;
+                    const float nv = fmaf(lane_bcast(p, j), g, av[e]);
+                    const float nk = fmaf(scale * lane_bcast(ds, j), q, ak[e]);
+                    dV[o] = nv;
+                    dK[o] = nk;
+                    if (j == w - 1) { dv_prev = nv; dk_prev = nk; }
+                }
+            }
         }
     }
-    const float slope = alibi_slope(alibi, bh % H, H);
-    const float p = lane < w ? expf(fmaf(-slope, (float)(w - lane), s * scale) - L) : 0.f;
-    const float ds = p * (dp - Dsum);
-    for (int j = 0; j < w; ++j) {
-        const size_t o = (size_t)(j0 + j) * rs + (size_t)bh * kHeadDim + lane;
-        dV[o] = fmaf(lane_bcast(p, j), g, dV[o]);
-        dK[o] = fmaf(scale * lane_bcast(ds, j), q, dK[o]);
+    if (fuse_pair && w > 0) {
+        const int b = bh / H, h = bh % H, d = H * kHeadDim;
+        const size_t r = (size_t)(i - 1) * B + b;
+        const size_t po = r * d + h * kHeadDim + lane;
+        float du = dk_prev;
+        if (!norm_free) {
+            const float wv = g_k ? dk_prev * to_f32(g_k[h * kHeadDim + lane]) : dk_prev;
+            const float u = unit_k[r * 2 * d + h * kHeadDim + lane];
+            du = rk[r * H + h] * (wv - u * (wave_sum(u * wv) / (float)kHeadDim));
+        }
+        dkraw[po] = du;
+        in_kv[(size_t)b * 2 * d + h * kHeadDim + lane] = du;
+        in_kv[(size_t)b * 2 * d + d + h * kHeadDim + lane] = dv_prev;
     }
 }
 
@@ -920,10 +989,12 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
     // ---- (B) the reverse loop
     hipLaunchKernelGGL(bw_init_pairs_kernel<T>, grid1((size_t)M * d), blk, 0, st, (const T *)gK_, (const T *)gV_, Bf.dK, Bf.dV,
                        (size_t)M * d);
+    bool pair_done = false;   // [dkraw | dV] of position i was already prepared by the query after it
     for (int i = N - 1; i >= 0; --i) {
         const size_t ro = (size_t)i * B;
-        hipLaunchKernelGGL(bw_pair_grad_kernel<T>, dim3(BH), dim3(64), 0, st, Bf.dK, Bf.dV, Bf.kv, Bf.rk, g_k, Bf.dkraw, Bf.in_kv, i, B, H,
-                           nf);
+        if (!pair_done)
+            hipLaunchKernelGGL(bw_pair_grad_kernel<T>, dim3(BH), dim3(64), 0, st, Bf.dK, Bf.dV, Bf.kv, Bf.rk, g_k, Bf.dkraw, Bf.in_kv, i, B,
+                               H, nf);
         gemv<T, EPI_KV>(st, (const T *)Bf.WkvT, d, 2 * d, Bf.in_kv, 2 * (size_t)d, B, nullptr, Bf.d_rz + ro * d);
         hipLaunchKernelGGL((bw_norm_bw_row_kernel<T, T>), dim3(B), blk, 0, st, Bf.d_rz, Bf.unit_z, Bf.rinv_z, g_kv, gy + (size_t)i * d,
                            (size_t)N * d, Bf.Gz, Bf.dmo, D.alpha, i, B, d, nf);
@@ -932,8 +1003,12 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
         hipLaunchKernelGGL((bw_norm_bw_row_kernel<T, float>), dim3(B), blk, 0, st, Bf.t1, Bf.unit_h, Bf.rinv_h, g_mlp, Bf.Gz + ro * d,
                            (size_t)d, Bf.d_h, Bf.da, D.alpha, i, B, d, nf);
         gemv<T, EPI_KV>(st, (const T *)Bf.WoT, d, d, Bf.da, (size_t)d, B, nullptr, Bf.dc + ro * d);
-        hipLaunchKernelGGL(bw_attn_row_kernel, dim3(BH), dim3(64), 0, st, Bf.Qn, Bf.Ktn, Bf.Vt, Bf.Kp, Bf.Vp, Bf.c, Bf.dc, Bf.lse, Bf.Ds,
-                           Bf.dK, Bf.dV, Bf.dq, Bf.dkt, Bf.dvt, i, B, H, D.scale, D.alibi);
+        // position i - 1 lies in this query's window unless i opens a block of kBwPmin positions (then a tile follows below,
+        // or i = 0): its pair gradient is complete after this query's update and is finished by the same wavefront
+        const int fuse = (i & (kBwPmin - 1)) != 0 ? 1 : 0;
+        hipLaunchKernelGGL(bw_attn_row_kernel<T>, dim3(BH), dim3(64), 0, st, Bf.Qn, Bf.Ktn, Bf.Vt, Bf.Kp, Bf.Vp, Bf.c, Bf.dc, Bf.lse, Bf.Ds,
+                           Bf.dK, Bf.dV, Bf.dq, Bf.dkt, Bf.dvt, i, B, H, D.scale, D.alibi, fuse, Bf.kv, Bf.rk, g_k, Bf.dkraw, Bf.in_kv, nf);
+        pair_done = fuse != 0;
         const int P = i & -i;   // Algorithm 1's block that ends with key i - 1 (0-based): keys [i - P, i), queries [i, i + P)
         if (i > 0 && P >= kBwPmin) {
             const int nq = P < N - i ? P : N - i;
