@@ -268,6 +268,14 @@ const char *rt_engine_name(const rt_ctx *ctx);
  * 7..13 points inside the phases, 14 and 15 the end of the first grid barrier and of the tile work of a cross-block event) into out[rows][16] (host memory).  Returns the number of rows written, 0 if tracing is off. */
 int32_t rt_phase_trace(rt_ctx *ctx, uint64_t *out, int32_t rows);
 
+/* Diagnostics of the single-launch decoding step, after the stream has been synchronised: when the environment variable
+ * RT_DECODE_TRACE was set at rt_create, copies for each of the first `workgroups` workgroups of the last step thirteen
+ * 100 MHz clock stamps (0 start, 1 input rows and [Wq; Wk; Wv] rows staged, 2 raw q, k, v sent, 3 the other weight
+ * slices staged, 4 this workgroup's cache chunks folded, 5 its wavefronts' states combined, 6 partial state or attention
+ * output sent, 7..11 end of the base case's products Wo, W1, W2 (partial), W2 (sum), [Wk; Wv], 12 end) into
+ * out[workgroups][16] (host memory).  Returns the number of rows written, 0 if tracing is off. */
+int32_t rt_decode_phase_trace(rt_ctx *ctx, uint64_t *out, int32_t workgroups);
+
 /* Diagnostics / measurement: run one cross-block UpdateTile (Appendix C, Algorithm 2) again, by itself, on the
  * state the last rt_layer_prefill of this context left behind (its queries and transposed values in scratch, the
  * caller's K, V): queries t1+1 .. t1+nq (1-based) against the keys t1-P+1 .. t1.  Rewrites those queries' partial

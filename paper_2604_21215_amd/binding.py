@@ -27,7 +27,7 @@ EXPORTS = ("rt_create", "rt_layer_prefill", "rt_decode_step", "rt_destroy", "rt_
            "rt_workspace_bytes", "rt_device_wait_expired", "rt_engine_name", "rt_schedule_events", "rt_partial_slot",
            "rt_version", "rt_phase_trace", "rt_schedule_events_shifted", "rt_embed_rows", "rt_lm_head", "rt_cross_block_event",
            "rt_stack_prefill", "rt_schedule_events_chunked", "rt_layer_recompute", "rt_transformer_layer",
-           "rt_layer_prefill_blocked", "rt_decode_step_static", "rt_layer_backward")
+           "rt_layer_prefill_blocked", "rt_decode_step_static", "rt_layer_backward", "rt_decode_phase_trace")
 
 
 class rt_config(C.Structure):
@@ -103,6 +103,8 @@ def load():
     L.rt_version.restype = C.c_int32
     L.rt_phase_trace.argtypes = [ctxp, C.POINTER(C.c_uint64), C.c_int32]
     L.rt_phase_trace.restype = C.c_int32
+    L.rt_decode_phase_trace.argtypes = [ctxp, C.POINTER(C.c_uint64), C.c_int32]
+    L.rt_decode_phase_trace.restype = C.c_int32
     L.rt_embed_rows.argtypes = [ctxp, C.c_void_p, C.c_int32, C.c_void_p, C.c_int64, C.c_int32, C.c_int32, C.c_int32,
                                 C.c_void_p]
     L.rt_embed_rows.restype = C.c_int
@@ -323,6 +325,13 @@ class RTContext:
         import numpy as np
         buf = np.zeros((rows, 16), dtype=np.uint64)
         n = self._L.rt_phase_trace(self._ctx, buf.ctypes.data_as(C.POINTER(C.c_uint64)), rows)
+        return buf[:n] if n > 0 else None
+
+    def decode_phase_trace(self, workgroups: int = 256):
+        """[workgroups, 16] clock stamps (100 MHz) of the last single-launch decoding step, or None when tracing is off."""
+        import numpy as np
+        buf = np.zeros((workgroups, 16), dtype=np.uint64)
+        n = self._L.rt_decode_phase_trace(self._ctx, buf.ctypes.data_as(C.POINTER(C.c_uint64)), workgroups)
         return buf[:n] if n > 0 else None
 
     def rt_destroy(self):

@@ -3,6 +3,7 @@
 #include "../../include/rt.h"
 #include "rt_common.h"
 #include "rt_persistent.h"
+#include "rt_decode_persistent.h"
 #include "rt_backward.h"
 
 #include <cstdio>
@@ -29,6 +30,7 @@ struct rt_ctx {
     std::string err;
     std::string engine;
     PersistentState persist;
+    DecodeCoopState dec;             // single-launch decoding step
     // layer-wavefront engine: one scratch set per layer and the device copy of the layer descriptors
     void *stack_slab = nullptr;
     size_t stack_bytes = 0;
@@ -347,6 +349,7 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
         delete c;
         return ps;
     }
+    (void)decode_coop_create(c->dec, c->cfg, D);   // shapes it does not cover keep the multi-launch step
     // scratch of the other entry points, when the caller wants no allocation inside a later call
     rt_status rs = RT_OK;
     if (cfg->reserve_stack_layers > 0) {
@@ -374,6 +377,7 @@ rt_status rt_destroy(rt_ctx *c)
     if (c->graph_exec) (void)hipGraphExecDestroy(c->graph_exec);
     if (c->capture_stream) (void)hipStreamDestroy(c->capture_stream);
     persistent_destroy(c->persist);
+    decode_coop_destroy(c->dec);
     if (c->stack_slab) (void)hipFree(c->stack_slab);
     if (c->stack_dev) (void)hipFree(c->stack_dev);
     if (c->par_slab) (void)hipFree(c->par_slab);
@@ -391,7 +395,7 @@ static const char *static_last_error();
 const char *rt_last_error(const rt_ctx *c) { return c ? c->err.c_str() : static_last_error(); }
 uint64_t rt_workspace_bytes(const rt_ctx *c)
 {
-    return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) + c->stack_bytes + c->par_bytes + c->bw_bytes : 0;
+    return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) + decode_coop_bytes(c->dec) + c->stack_bytes + c->par_bytes + c->bw_bytes : 0;
 }
 const char *rt_engine_name(const rt_ctx *c) { return c ? c->engine.c_str() : ""; }
 
@@ -402,14 +406,26 @@ int32_t rt_device_wait_expired(rt_ctx *c)
     if (v) {
         c->broken = true;
         c->err = "a bounded device-side wait expired in the persistent engine";
+        return v;
     }
-    return v;
+    const int w = decode_coop_wait_expired(c->dec);
+    if (w) {
+        c->broken = true;
+        c->err = "a bounded device-side wait expired in the single-launch decoding step";
+    }
+    return w;
 }
 
 int32_t rt_phase_trace(rt_ctx *c, uint64_t *out, int32_t rows)
 {
     if (!c || !out || rows < 1) return 0;
     return persistent_read_trace(c->persist, (unsigned long long *)out, rows);
+}
+
+int32_t rt_decode_phase_trace(rt_ctx *c, uint64_t *out, int32_t workgroups)
+{
+    if (!c || !out || workgroups < 1) return 0;
+    return decode_coop_read_trace(c->dec, (unsigned long long *)out, workgroups);
 }
 
 }  // extern "C"
@@ -565,6 +581,13 @@ static rt_status decode_impl(rt_ctx *c, const LayerDims &D, const rt_layer_weigh
 {
     const Weights W = to_weights(w);
     hipStream_t st = c->stream;
+    if (sizeof(T) == 2 && decode_coop_supported(c->dec, D)) {   // the whole step as one cooperative launch
+        c->engine = "decode-single-launch";
+        std::string derr;
+        const rt_status ds = decode_coop_step(c->dec, D, W, x_t, t, y_t, K, V, st, derr);
+        if (ds != RT_OK) { c->err = derr; if (ds == RT_ERR_HIP) c->broken = true; }
+        return ds;
+    }
     // bf16 with d and F multiples of 256: the products run on the matrix cores
     const bool mm = sizeof(T) == 2 && step_mm_supported(D, c->use_mfma);
     RT_TRY(Launch<T>::prepass_one(D, W, c->S, x_t, (size_t)D.d, st, mm), "prepass_one");

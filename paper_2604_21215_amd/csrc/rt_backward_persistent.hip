@@ -72,31 +72,6 @@ struct BwpArgs {
         }                                                                                                                  \
     } while (0)
 
-// rows of an LDS-resident weight slice times the activation rows already staged in LDS by the preceding pull
-// (the product half of wg_gemv_ll): the per-wavefront 16 x 16 tiles land in red[wave][row][b].
-template <int KS>
-__device__ __forceinline__ void wg_product_staged(const bf16_t *w_s, int ldw, int R, int B, float *red, const bf16_t *act_s, int lda)
-{
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int l16 = lane & 15, g = lane >> 4;
-    const bool has_w = l16 < R, has_a = l16 < B;
-    constexpr int kw = KS * 32;
-    const bf16_t *wrow = w_s + (size_t)l16 * ldw + wave * kw + 8 * g;
-    const bf16_t *arow = act_s + (size_t)l16 * lda + wave * kw + 8 * g;
-    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-#pragma unroll
-    for (int s = 0; s < KS; ++s) {
-        Frag a, b;
-        a.u = has_w ? lds_load16(wrow + s * 32) : zero;
-        b.u = has_a ? lds_load16(arow + s * 32) : zero;
-        acc = mfma16(a, b, acc);
-    }
-    float *r = red + ((size_t)wave * kRMax + 4 * g) * kBMax + l16;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) r[i * kBMax] = acc[i];
-}
-
 // <unit row, staged bf16 vector> of batch row `wave` (B <= 8: one wavefront per batch row), u16 = this lane's 16
 // elements of the unit row (elements 16 lane .. 16 lane + 15 of each 1024-element stripe are not used: the lane owns
 // elements lane * PER .. + PER - 1 with PER = d / 64)

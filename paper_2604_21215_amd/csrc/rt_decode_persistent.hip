@@ -1,0 +1,697 @@
+// Single-launch decoding step (paper Sec. 7.3: one position of the recurrence of Sec. 2.2 over a cache of persistent
+// pairs), bf16 storage.
+//
+// One cooperative grid of 256 workgroups (one per compute unit) x 512 threads evaluates the whole position:
+//
+//   Q    raw [q | k_tmp | v_tmp] = [Wq; Wk; Wv]' x_t / rms(x_t): 3d / 256 rows per workgroup                  -> raw q, k, v
+//   A    attention over the cache rows 0 .. t-1: the 64-key chunks of one (b, h) are dealt to the wavefronts of the
+//        S = 256 / (B H) workgroups that share it; every wavefront keeps a running softmax state (Appendix C,
+//        Algorithm 2 for one query row), the eight states of a workgroup are combined in LDS                   -> S partial states
+//   M    one wavefront per (b, h): the partial states and the temporary pair                                   -> a
+//   O, 1, 2a, 2b, KV   the base case exactly as in the single-launch prefill engine (rt_persistent.hip): every
+//        workgroup holds its rows of Wo, W1, [Wk; Wv] and its block of W2 in LDS, the vectors between the products
+//        cross the chip in self-validating words (rt_ll.h)                                                     -> y_t, raw k, v
+//   F    one wavefront per (b, h): RMS scale of z, qkRMS of k, the cache row t of K and V
+//
+// The multi-launch step spends most of its time in the start-up and tail of eight dependent kernels that move 2-8 MB
+// each.  Here every byte the step needs - the cache rows (2 t B d elements) and all six matrices (12 d^2) - is requested
+// in the first microseconds of the launch by the workgroup that will use it, none of it depends on a result of
+// the step, and the dependent part that follows is seven exchanges of small vectors.
+// RMS gains are folded into the rows as they are copied to LDS (W diag(g), rounded once), as in the prefill engine.
+// Every wait is bounded (spin limit -> abort word -> every workgroup leaves).
+#include "rt_decode_persistent.h"
+#include "rt_ll.h"
+
+#include <cstdlib>
+
+namespace rt {
+
+constexpr int kDecMaxSplit = 16;   // workgroups that can share the cache rows of one (b, h)
+constexpr int kPartWords = 72;     // words of an exchanged partial state: o[64], m, l, padded to whole 64-byte lines
+constexpr int kPartLds = 68;       // floats of a wavefront's state in LDS
+
+struct DecArgs {
+    int B, d, H, F, BH, G, t;
+    int S;                         // workgroups per (b, h) in the attention phase
+    float alpha, scale, eps, alibi;
+    int norm_free;
+    int R_q, R_o, R_1, R_kv, R_2, ldw, max_batch;
+    const bf16_t *Wq, *Wk, *Wv, *Wo, *W1, *W2, *g_attn, *g_mlp, *g_kv, *g_q, *g_k;
+    const bf16_t *x;               // [B][d]
+    bf16_t *y;                     // [B][d]
+    bf16_t *K, *V;                 // [kv_cap][B][H][64]: rows 0 .. t-1 read, row t written
+    ll_t *qkv_ll;                  // [3d] x kBMax, one fp32 per word
+    ll_t *part_ll;                 // [B H][kDecMaxSplit][kPartWords]
+    ll_t *a_ll, *h_ll, *z_ll;      // [kBMax][d/2]   two bf16 per word
+    ll_t *u_ll;                    // [kBMax][F/2]
+    ll_t *kv_ll;                   // [kBMax][2d]    one fp32 per word
+    ll_t *zss_ll;                  // [G][kBMax]
+    ll_t *zp_ll;                   // [4][kBMax][d]
+    unsigned tag;
+    unsigned long long *bar;       // [0] unused, [8] abort word
+    long long spin_limit;
+    int pre_sleep;
+    unsigned long long *trace;     // optional: [G][16] 100 MHz clock stamps of every workgroup's phases
+};
+
+#define RT_DEC_STAMP(k)                                                              \
+    do {                                                                             \
+        if (A.trace && threadIdx.x == 0) A.trace[(size_t)blockIdx.x * 16 + (k)] = wall_clock64(); \
+    } while (0)
+
+#define RT_DEC_ABORT_IF(cond)                                                                                           \
+    do {                                                                                                                \
+        if (__syncthreads_or(cond)) {                                                                                   \
+            if (threadIdx.x == 0) __hip_atomic_store(A.bar + 8, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     \
+            return;                                                                                                     \
+        }                                                                                                               \
+    } while (0)
+
+struct RowSrc {
+    const bf16_t *row;    // first of the row's K elements, or null: no such row in this workgroup
+    const bf16_t *gain;   // gain of those K columns, or null
+};
+
+// nrows rows of PER 16-byte pieces each into LDS rows ldw elements apart; src(r) names row r.  NB pieces per thread
+// are requested before the first is stored.
+template <int NB, int PER, typename SRC>
+__device__ __forceinline__ void copy_rows_batched(bf16_t *dst, int ldw, int nrows, SRC src)
+{
+    const int total = nrows * PER;
+    for (int i0 = 0; i0 < total; i0 += NB * kPThreads) {
+        uint4 w[NB], gq[NB];
+        bool on[NB], hg[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            const int idx = i0 + j * kPThreads + (int)threadIdx.x;
+            on[j] = hg[j] = false;
+            w[j] = gq[j] = make_uint4(0u, 0u, 0u, 0u);
+            if (idx < total) {
+                const int r = idx / PER, c = idx - r * PER;
+                const RowSrc s = src(r);
+                if (s.row) {
+                    on[j] = true;
+                    w[j] = global_load16(s.row + c * 8);
+                    if (s.gain) {
+                        hg[j] = true;
+                        gq[j] = global_load16(s.gain + c * 8);
+                    }
+                }
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < NB; ++j) {
+            if (!on[j]) continue;
+            const int idx = i0 + j * kPThreads + (int)threadIdx.x;
+            const int r = idx / PER, c = idx - r * PER;
+            uint4 v = w[j];
+            if (hg[j]) {
+                float gg[8], ww[8];
+                load8(reinterpret_cast<const bf16_t *>(&gq[j]), gg);
+                load8(reinterpret_cast<const bf16_t *>(&v), ww);
+                v.x = pack_bf16(ww[0] * gg[0], ww[1] * gg[1]);
+                v.y = pack_bf16(ww[2] * gg[2], ww[3] * gg[3]);
+                v.z = pack_bf16(ww[4] * gg[4], ww[5] * gg[5]);
+                v.w = pack_bf16(ww[6] * gg[6], ww[7] * gg[7]);
+            }
+            *reinterpret_cast<uint4 *>(dst + (size_t)r * ldw + c * 8) = v;
+        }
+    }
+}
+
+// The 64 cache rows k_lo .. k_lo + cnt - 1 of one (b, h): 16 KB requested at once.  Piece i of a lane is row
+// 8 i + lane / 8, columns 8 (lane % 8) .. + 7 (eight lanes cover one 128-byte row); rows past the end repeat the last.
+__device__ __forceinline__ void dec_load_chunk(const bf16_t *K, const bf16_t *V, size_t rs, int u, int k_lo, int cnt, uint4 (&kr)[8],
+                                               uint4 (&vr)[8])
+{
+    const int lane = threadIdx.x & 63;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const size_t off = (size_t)(k_lo + min(8 * i + (lane >> 3), cnt - 1)) * rs + (size_t)u * kHeadDim + (lane & 7) * 8;
+        kr[i] = global_load16(K + off);
+        vr[i] = global_load16(V + off);
+    }
+}
+
+// One chunk folded into a wavefront's running state (Appendix C, Algorithm 2, one query row): m, l wave-uniform,
+// o8 this lane's share of the output (its eight columns over the rows it holds; the lanes that share columns are
+// summed once, after the last chunk).  q8: the query's elements at this lane's columns.  dist_first: distance of the
+// chunk's first key from the query (ALiBi).
+__device__ __forceinline__ void dec_attend_chunk(const uint4 (&kr)[8], const uint4 (&vr)[8], const float (&q8)[8], int cnt,
+                                                 int dist_first, float scale, float slope, float &m, float &l, float (&o8)[8])
+{
+    const int lane = threadIdx.x & 63;
+    float acc = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const uint32_t w[4] = {kr[i].x, kr[i].y, kr[i].z, kr[i].w};
+        float dsum = 0.f;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            dsum = fmaf(q8[2 * e], __uint_as_float(w[e] << 16), dsum);
+            dsum = fmaf(q8[2 * e + 1], __uint_as_float(w[e] & 0xFFFF0000u), dsum);
+        }
+        dsum += __shfl_xor(dsum, 1, 64);
+        dsum += __shfl_xor(dsum, 2, 64);
+        dsum += __shfl_xor(dsum, 4, 64);
+        const float mine = __shfl(dsum, (lane & 7) * 8, 64);   // row 8 i + lane % 8
+        if ((lane >> 3) == i) acc = mine;
+    }
+    const bool valid = lane < cnt;
+    const float logit = valid ? fmaf(-slope, (float)(dist_first - lane), acc * scale) : -INFINITY;
+    const float m_new = fmaxf(m, fast_max(logit));
+    const float resc = __expf(m - m_new);   // exp(-inf) = 0 on the first chunk
+    const float p = valid ? __expf(logit - m_new) : 0.f;
+    l = l * resc + fast_sum(p);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) o8[e] *= resc;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+        const float pr = __shfl(p, 8 * i + (lane >> 3), 64);
+        const uint32_t w[4] = {vr[i].x, vr[i].y, vr[i].z, vr[i].w};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            o8[2 * e] = fmaf(pr, __uint_as_float(w[e] << 16), o8[2 * e]);
+            o8[2 * e + 1] = fmaf(pr, __uint_as_float(w[e] & 0xFFFF0000u), o8[2 * e + 1]);
+        }
+    }
+    m = m_new;
+}
+
+// two softmax states into one; an empty state has m = -inf, l = 0
+__device__ __forceinline__ void dec_combine(float &m, float &l, float &o, float m2, float l2, float o2)
+{
+    if (m2 == -INFINITY) return;   // wave-uniform
+    const float m_new = fmaxf(m, m2);
+    const float e1 = __expf(m - m_new), e2 = __expf(m2 - m_new);
+    l = l * e1 + l2 * e2;
+    o = o * e1 + o2 * e2;
+    m = m_new;
+}
+
+// KSD = d / 256.
+template <int KSD>
+__global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
+{
+    extern __shared__ __align__(16) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wg = blockIdx.x, G = A.G;
+    const int d = A.d, F = A.F, B = A.B, BH = A.BH, H = A.H, t = A.t;
+    constexpr int RQ = 3 * KSD, RO = 2 * ((KSD + 1) / 2), R1 = 4 * KSD, RKV = 2 * KSD;
+    constexpr int PER = 32 * KSD;   // 16-byte pieces of a d-long bf16 row
+    const unsigned tag = A.tag;
+
+    // ---- LDS carve-up (the five weight slices are contiguous: one copy loop fills the last four)
+    bf16_t *wq_s = reinterpret_cast<bf16_t *>(smem);
+    bf16_t *wo_s = wq_s + (size_t)A.R_q * A.ldw;
+    bf16_t *w1_s = wo_s + (size_t)A.R_o * A.ldw;
+    bf16_t *w2_s = w1_s + (size_t)A.R_1 * A.ldw;
+    bf16_t *wkv_s = w2_s + (size_t)A.R_2 * A.ldw;
+    float *red = reinterpret_cast<float *>(wkv_s + (size_t)A.R_kv * A.ldw);   // [kPW][kRMax][kBMax]
+    float *h_loc = red + kPW * kRMax * kBMax;                                 // [kRMax][kBMax]
+    float *sq = h_loc + kRMax * kBMax;                                        // [32][kBMax]
+    float *rinv_s = sq + 32 * kBMax;                                          // [kBMax]
+    float *part_s = rinv_s + kBMax;                                           // [kPW][kPartLds]
+    bf16_t *act_s = reinterpret_cast<bf16_t *>(part_s + kPW * kPartLds);      // [max_batch][ldw]
+
+    // ---- this workgroup's rows
+    const int q_lo = wg * RQ;                                                          // rows of [Wq; Wk; Wv] (3 d = 256 RQ)
+    const int o_lo = min(wg * A.R_o, d), o_n = min(d, o_lo + A.R_o) - o_lo;            // Wo, and the z rows it finishes
+    const int f_lo = min(wg * A.R_1, F), f_n = min(F, f_lo + A.R_1) - f_lo;            // W1
+    const int kv_lo = min(wg * A.R_kv, 2 * d), kv_n = min(2 * d, kv_lo + A.R_kv) - kv_lo;   // [Wk; Wv]
+    const int rb = wg >> 2, jb = wg & 3, RB = A.R_2;                                   // W2: row block x contraction block
+
+    // ---- this wavefront's share of the cache
+    const int S = A.S;
+    const int u = wg / S, s = wg - u * S;     // (b, h) and split of this workgroup
+    const bool att = u < BH;
+    const int ub = att ? u / H : 0, uh = att ? u - ub * H : 0;
+    const int nch = (t + 63) >> 6;            // chunks of 64 cached keys
+    const int nworkers = kPW * S;
+    const size_t rs = (size_t)BH * kHeadDim;
+    const bool is_merger = att && s == 0 && wave == 0;
+
+    RT_DEC_STAMP(0);
+    // ================================================================ input rows and the rows of [Wq; Wk; Wv]
+    for (int idx = tid; idx < B * PER; idx += kPThreads) {
+        const int r = idx / PER, c = idx - r * PER;
+        *reinterpret_cast<uint4 *>(act_s + (size_t)r * A.ldw + c * 8) = global_load16(A.x + (size_t)r * d + c * 8);
+    }
+    const bf16_t *g_in = A.norm_free ? nullptr : A.g_attn;
+    copy_rows_batched<3, PER>(wq_s, A.ldw, RQ, [&](int r) {
+        const int o = q_lo + r, which = o / d, row = o - which * d;
+        const bf16_t *Wm = which == 0 ? A.Wq : (which == 1 ? A.Wk : A.Wv);
+        return RowSrc{Wm + (size_t)row * d, g_in};
+    });
+
+    // ---- the first two chunks of this wavefront: requested now, used after phase Q
+    uint4 krA[8], vrA[8], krB[8], vrB[8];
+    int cA = wave * S + s, cB = cA + nworkers;
+    if (att && cA < nch) dec_load_chunk(A.K, A.V, rs, u, cA * 64, min(64, t - cA * 64), krA, vrA);
+    if (att && cB < nch) dec_load_chunk(A.K, A.V, rs, u, cB * 64, min(64, t - cB * 64), krB, vrB);
+    __syncthreads();
+    RT_DEC_STAMP(1);
+
+    // ================================================================ phase Q
+    const int erow = tid >> 4, eb = tid & 15;   // epilogue thread -> (row, batch row) for tid < 256
+    wg_product_staged<KSD, true>(wq_s, A.ldw, RQ, B, red, act_s, A.ldw, sq);
+    __syncthreads();
+    if (tid < kBMax) {
+        float ssum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kPW; ++w) ssum += sq[w * kBMax + tid];
+        rinv_s[tid] = A.norm_free ? 1.f : rsqrtf(ssum / (float)d + A.eps);
+    }
+    __syncthreads();
+    if (tid < kRMax * kBMax && erow < RQ && eb < B)
+        ll_store(A.qkv_ll + single_word<RQ>(q_lo + erow, eb), tag, __float_as_uint(red_sum(red, erow, eb) * rinv_s[eb]));
+    float xv = 0.f;   // residual input of this workgroup's rows
+    if (tid < kRMax * kBMax && erow < o_n && eb < B) xv = bf16_to_f32(A.x[(size_t)eb * d + o_lo + erow]);
+    __syncthreads();   // red, sq and the staged rows are reused
+    RT_DEC_STAMP(2);
+
+    // ================================================================ the other four weight slices
+    {
+        const bf16_t *gm = A.norm_free ? nullptr : A.g_mlp, *gkv = A.norm_free ? nullptr : A.g_kv;
+        const int n1 = A.R_o, n2 = n1 + A.R_1, n3 = n2 + A.R_2, n4 = n3 + A.R_kv;
+        copy_rows_batched<6, PER>(wo_s, A.ldw, n4, [&](int r) {
+            if (r < n1) return r < o_n ? RowSrc{A.Wo + (size_t)(o_lo + r) * d, nullptr} : RowSrc{nullptr, nullptr};
+            if (r < n2) return r - n1 < f_n ? RowSrc{A.W1 + (size_t)(f_lo + r - n1) * d, gm} : RowSrc{nullptr, nullptr};
+            if (r < n3) return RowSrc{A.W2 + (size_t)(rb * RB + r - n2) * F + (size_t)jb * d, nullptr};
+            const int rr = r - n3, o = kv_lo + rr;
+            if (rr >= kv_n) return RowSrc{nullptr, nullptr};
+            return o < d ? RowSrc{A.Wk + (size_t)o * d, gkv} : RowSrc{A.Wv + (size_t)(o - d) * d, gkv};
+        });
+    }
+
+    RT_DEC_STAMP(3);
+    // ================================================================ phase A: this wavefront's chunks
+    int fail = 0;
+    float qn = 0.f;
+    if (att) {
+        const ll_t wq = ll_wait(A.qkv_ll + single_word<RQ>(uh * kHeadDim + lane, ub), true, tag, A, fail);
+        qn = __uint_as_float((unsigned)wq);
+        if (!A.norm_free)
+            qn *= rsqrtf(fast_sum(qn * qn) / (float)kHeadDim + A.eps) * (A.g_q ? bf16_to_f32(A.g_q[uh * kHeadDim + lane]) : 1.f);
+        float q8[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) q8[e] = __shfl(qn, (lane & 7) * 8 + e, 64);
+        const float slope = alibi_slope(A.alibi, uh, H);
+        float m = -INFINITY, l = 0.f, o8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+        for (;;) {
+            if (cA >= nch) break;
+            dec_attend_chunk(krA, vrA, q8, min(64, t - cA * 64), t - cA * 64, A.scale, slope, m, l, o8);
+            cA += 2 * nworkers;
+            if (cA < nch) dec_load_chunk(A.K, A.V, rs, u, cA * 64, min(64, t - cA * 64), krA, vrA);
+            if (cB >= nch) break;
+            dec_attend_chunk(krB, vrB, q8, min(64, t - cB * 64), t - cB * 64, A.scale, slope, m, l, o8);
+            cB += 2 * nworkers;
+            if (cB < nch) dec_load_chunk(A.K, A.V, rs, u, cB * 64, min(64, t - cB * 64), krB, vrB);
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            o8[e] += __shfl_xor(o8[e], 8, 64);
+            o8[e] += __shfl_xor(o8[e], 16, 64);
+            o8[e] += __shfl_xor(o8[e], 32, 64);
+        }
+        float *ps = part_s + wave * kPartLds;
+        if (lane < 8) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ps[lane * 8 + e] = o8[e];
+        }
+        if (lane == 0) { ps[64] = m; ps[65] = l; }
+    }
+    RT_DEC_STAMP(4);
+    RT_DEC_ABORT_IF(fail);   // also orders the eight states in LDS before wavefront 0 reads them
+    RT_DEC_STAMP(5);
+
+    // ================================================================ phase M: partial states -> a
+    if (att && wave == 0) {
+        float M = -INFINITY, L = 0.f, O = 0.f;
+#pragma unroll
+        for (int w = 0; w < kPW; ++w) {
+            const float *ps = part_s + w * kPartLds;
+            dec_combine(M, L, O, ps[64], ps[65], ps[lane]);
+        }
+        ll_t *mine = A.part_ll + ((size_t)u * kDecMaxSplit + s) * kPartWords;
+        if (s != 0) {
+            ll_store(mine + lane, tag, __float_as_uint(O));
+            if (lane < 2) ll_store(mine + 64 + lane, tag, __float_as_uint(lane == 0 ? M : L));
+        } else {
+            // the temporary pair of this position (distance 0: no positional bias)
+            const ll_t *p2[2] = {A.qkv_ll + single_word<RQ>(d + uh * kHeadDim + lane, ub),
+                                 A.qkv_ll + single_word<RQ>(2 * d + uh * kHeadDim + lane, ub)};
+            const bool on2[2] = {true, true};
+            ll_t w2[2];
+            ll_wait_n<2>(p2, on2, tag, A, w2, fail);
+            float kt = __uint_as_float((unsigned)w2[0]);
+            const float vt = bf16_to_f32(f32_to_bf16(__uint_as_float((unsigned)w2[1])));
+            if (!A.norm_free)
+                kt *= rsqrtf(fast_sum(kt * kt) / (float)kHeadDim + A.eps) * (A.g_k ? bf16_to_f32(A.g_k[uh * kHeadDim + lane]) : 1.f);
+            dec_combine(M, L, O, A.scale * fast_sum(qn * kt), 1.f, vt);
+            for (int sp = 1; sp < S; ++sp) {
+                const ll_t *src = A.part_ll + ((size_t)u * kDecMaxSplit + sp) * kPartWords;
+                const ll_t *pp[2] = {src + lane, src + 64 + (lane & 1)};
+                ll_t wp[2];
+                ll_wait_n<2>(pp, on2, tag, A, wp, fail);
+                const float ml = __uint_as_float((unsigned)wp[1]);
+                dec_combine(M, L, O, lane_bcast(ml, 0), lane_bcast(ml, 1), __uint_as_float((unsigned)wp[0]));
+            }
+            const float av = O / L;
+            const float an = __shfl_down(av, 1, 64);
+            if (!(lane & 1))
+                ll_store(A.a_ll + pair_word<32>(uh * kHeadDim + lane, ub), tag,
+                         (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
+        }
+    }
+    RT_DEC_ABORT_IF(fail);
+    RT_DEC_STAMP(6);
+
+    // ================================================================ phase O:  h = x_t + alpha Wo a
+    wg_gemv_ll<KSD, 32>(wo_s, A.ldw, o_n, A.a_ll, B, tag, A, red, act_s, A.ldw, fail);
+    RT_DEC_ABORT_IF(fail);
+    if (tid < kRMax * kBMax) {
+        float hv = 0.f;
+        const int o = o_lo + erow;
+        if (erow < o_n && eb < B) hv = xv + A.alpha * red_sum(red, erow, eb);
+        const float hn = __shfl_down(hv, 16, 64);
+        if (!(erow & 1) && erow < o_n && eb < B)
+            ll_store(A.h_ll + pair_word<RO / 2>(o, eb), tag, (unsigned)f32_to_bf16(hv) | ((unsigned)f32_to_bf16(hn) << 16));
+        h_loc[erow * kBMax + eb] = hv;
+    }
+    __syncthreads();
+    RT_DEC_STAMP(7);
+
+    // ================================================================ phase 1:  u = gelu(W1' h / rms(h))
+    wg_gemv_ll<KSD, RO / 2, true>(w1_s, A.ldw, f_n, A.h_ll, B, tag, A, red, act_s, A.ldw, fail, sq);
+    RT_DEC_ABORT_IF(fail);
+    if (tid < kBMax) {
+        float ssum = 0.f;
+#pragma unroll
+        for (int w = 0; w < kPW; ++w) ssum += sq[w * kBMax + tid];
+        rinv_s[tid] = A.norm_free ? 1.f : rsqrtf(ssum / (float)d + A.eps);
+    }
+    __syncthreads();
+    if (tid < kRMax * kBMax) {
+        float uv = 0.f;
+        if (erow < f_n && eb < B) uv = gelu_erf(red_sum(red, erow, eb) * rinv_s[eb]);
+        const float un = __shfl_down(uv, 16, 64);
+        if (!(erow & 1) && erow < f_n && eb < B)
+            ll_store(A.u_ll + pair_word<R1 / 2>(f_lo + erow, eb), tag, (unsigned)f32_to_bf16(uv) | ((unsigned)f32_to_bf16(un) << 16));
+    }
+    __syncthreads();
+    RT_DEC_STAMP(8);
+
+    // ================================================================ phase 2a:  partial W2 u over contraction block jb
+    wg_gemv_ll<KSD, R1 / 2>(w2_s, A.ldw, RB, A.u_ll + (size_t)jb * (kBMax * (d / 2)), B, tag, A, red, act_s, A.ldw, fail);
+    RT_DEC_ABORT_IF(fail);
+    if (tid < kRMax * kBMax && erow < RB && eb < B)
+        ll_store(A.zp_ll + ((size_t)jb * kBMax + eb) * d + rb * RB + erow, tag, __float_as_uint(red_sum(red, erow, eb)));
+    __syncthreads();
+    RT_DEC_STAMP(9);
+
+    // ================================================================ phase 2b:  z = h + alpha (sum of the four partials)
+    if (tid < kRMax * kBMax) {
+        float zv = 0.f;
+        const int o = o_lo + erow;
+        const bool own = erow < o_n && eb < B;
+        const ll_t *pp[4];
+        bool on4[4];
+        ll_t w4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            on4[j] = own;
+            pp[j] = A.zp_ll + ((size_t)j * kBMax + (own ? eb : 0)) * d + (own ? o : 0);
+        }
+        ll_wait_n<4>(pp, on4, tag, A, w4, fail);
+        if (own) {
+            const float acc = (__uint_as_float((unsigned)w4[0]) + __uint_as_float((unsigned)w4[1])) +
+                              (__uint_as_float((unsigned)w4[2]) + __uint_as_float((unsigned)w4[3]));
+            zv = h_loc[erow * kBMax + eb] + A.alpha * acc;
+            A.y[(size_t)eb * d + o] = f32_to_bf16(zv);
+        }
+        const float zn = __shfl_down(zv, 16, 64);
+        if (!(erow & 1) && own)
+            ll_store(A.z_ll + pair_word<RO / 2>(o, eb), tag, (unsigned)f32_to_bf16(zv) | ((unsigned)f32_to_bf16(zn) << 16));
+        sq[erow * kBMax + eb] = zv * zv;
+    }
+    RT_DEC_ABORT_IF(fail);
+    if (tid < kBMax) {
+        float ssum = 0.f;
+#pragma unroll
+        for (int r = 0; r < kRMax; ++r) ssum += sq[r * kBMax + tid];
+        if (tid < B) ll_store(A.zss_ll + (size_t)wg * kBMax + tid, tag, __float_as_uint(ssum));
+    }
+    __syncthreads();
+    RT_DEC_STAMP(10);
+
+    // ================================================================ phase KV:  [Wk'; Wv'] z  (1 / rms(z) applied in F)
+    wg_gemv_ll<KSD, RO / 2>(wkv_s, A.ldw, kv_n, A.z_ll, B, tag, A, red, act_s, A.ldw, fail);
+    RT_DEC_ABORT_IF(fail);
+    if (tid < kRMax * kBMax && erow < kv_n && eb < B)
+        ll_store(A.kv_ll + single_word<RKV>(kv_lo + erow, eb), tag, __float_as_uint(red_sum(red, erow, eb)));
+
+    RT_DEC_STAMP(11);
+    // ================================================================ phase F: the persistent pair of position t
+    if (is_merger) {
+        const ll_t *p[6];
+        bool on6[6];
+        ll_t w6[6];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            on6[i] = i * 64 + lane < G;
+            p[i] = A.zss_ll + (size_t)(on6[i] ? i * 64 + lane : 0) * kBMax + ub;
+        }
+        p[4] = A.kv_ll + single_word<RKV>(uh * kHeadDim + lane, ub);
+        p[5] = A.kv_ll + single_word<RKV>(d + uh * kHeadDim + lane, ub);
+        on6[4] = on6[5] = true;
+        ll_wait_n<6>(p, on6, tag, A, w6, fail);
+        float ssum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            if (on6[i]) ssum += __uint_as_float((unsigned)w6[i]);
+        const float rz = A.norm_free ? 1.f : rsqrtf(fast_sum(ssum) / (float)d + A.eps);
+        float kr = __uint_as_float((unsigned)w6[4]) * rz;
+        const float vr = __uint_as_float((unsigned)w6[5]) * rz;
+        if (!A.norm_free)
+            kr *= rsqrtf(fast_sum(kr * kr) / (float)kHeadDim + A.eps) * (A.g_k ? bf16_to_f32(A.g_k[uh * kHeadDim + lane]) : 1.f);
+        if (!fail) {
+            const size_t off = (size_t)t * rs + (size_t)u * kHeadDim + lane;
+            A.K[off] = f32_to_bf16(kr);
+            A.V[off] = f32_to_bf16(vr);
+        }
+    }
+    RT_DEC_ABORT_IF(fail);
+    RT_DEC_STAMP(12);
+}
+
+// =============================================================================================
+// Host side
+// =============================================================================================
+namespace {
+
+typedef void (*dec_fn)(DecArgs);
+dec_fn pick(int d, int F)
+{
+    if (d % (32 * kPW) != 0 || F != 4 * d) return nullptr;
+    switch (d / (32 * kPW)) {
+    case 1: return decode_coop_kernel<1>;
+    case 2: return decode_coop_kernel<2>;
+    case 3: return decode_coop_kernel<3>;
+    case 4: return decode_coop_kernel<4>;
+    default: return nullptr;
+    }
+}
+
+size_t up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+struct Rows {
+    int R_q, R_o, R_1, R_kv, R_2;
+};
+Rows rows_for(int d, int F, int G)
+{
+    Rows r;
+    r.R_q = (3 * d + G - 1) / G;
+    r.R_o = 2 * ((d + 2 * G - 1) / (2 * G));
+    r.R_1 = 2 * ((F + 2 * G - 1) / (2 * G));
+    r.R_kv = 2 * ((2 * d + 2 * G - 1) / (2 * G));
+    r.R_2 = d / 64;
+    return r;
+}
+size_t lds_bytes_for(int d, int F, int G, int max_batch)
+{
+    const Rows r = rows_for(d, F, G);
+    const size_t ldw = d + 8;
+    size_t b = (size_t)(r.R_q + r.R_o + r.R_1 + r.R_2 + r.R_kv) * ldw * 2;
+    b = up(b, 16);
+    b += (size_t)(kPW * kRMax * kBMax + kRMax * kBMax + 32 * kBMax + kBMax + kPW * kPartLds) * 4;
+    b = up(b, 16);
+    b += (size_t)max_batch * ldw * 2;
+    return b;
+}
+
+// layout of the exchange slab (offsets in bytes)
+struct Slab {
+    size_t bar, qkv, part, a, h, z, u, kv, zss, zp, trace, total;
+};
+Slab slab_for(int d, int F, int G)
+{
+    Slab s;
+    size_t off = 0;
+    auto carve = [&](size_t bytes) { size_t o = off; off = up(off + bytes, 256); return o; };
+    s.bar = carve(256);
+    s.qkv = carve((size_t)kBMax * 3 * d * 8);
+    s.part = carve((size_t)256 * kDecMaxSplit * kPartWords * 8);
+    s.a = carve((size_t)kBMax * (d / 2) * 8);
+    s.h = carve((size_t)kBMax * (d / 2) * 8);
+    s.z = carve((size_t)kBMax * (d / 2) * 8);
+    s.u = carve((size_t)kBMax * (F / 2) * 8);
+    s.kv = carve((size_t)kBMax * 2 * d * 8);
+    s.zss = carve((size_t)kBMax * G * 8);
+    s.zp = carve((size_t)4 * kBMax * d * 8);
+    s.trace = carve((size_t)G * 16 * 8);
+    s.total = off;
+    return s;
+}
+
+__global__ void dec_clear_kernel(unsigned long long *p, size_t n)
+{
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (size_t)gridDim.x * blockDim.x) p[i] = 0ULL;
+}
+
+}  // namespace
+
+rt_status decode_coop_create(DecodeCoopState &P, const rt_config &cfg, const LayerDims &D)
+{
+    P.available = false;
+    if (cfg.dtype != RT_BF16 || (cfg.flags & (RT_FLAG_NO_MFMA | RT_FLAG_ENGINE_STEPWISE)) || getenv("RT_DECODE_MULTI_LAUNCH"))
+        return RT_ERR_UNSUPPORTED;
+    dec_fn fn = pick(D.d, D.F);   // d in {256, 512, 768, 1024}, F = 4 d
+    if (!fn) return RT_ERR_UNSUPPORTED;
+    hipDeviceProp_t prop;
+    if (hipGetDeviceProperties(&prop, cfg.device) != hipSuccess) return RT_ERR_HIP;
+    if (!prop.cooperativeLaunch || prop.multiProcessorCount != 256) return RT_ERR_UNSUPPORTED;   // W2: 64 x 4 workgroups
+    const int G = 256;
+    P.max_batch = cfg.max_batch < kBMax ? cfg.max_batch : kBMax;
+    if (P.max_batch * D.H > G) P.max_batch = G / D.H;
+    if (P.max_batch < 1) return RT_ERR_UNSUPPORTED;
+    const Rows r = rows_for(D.d, D.F, G);
+    if (r.R_q > kRMax || r.R_o > kRMax || r.R_1 > kRMax || r.R_kv > kRMax || r.R_2 > kRMax) return RT_ERR_UNSUPPORTED;
+    const size_t lds = lds_bytes_for(D.d, D.F, G, P.max_batch);
+    if (lds > (size_t)160 * 1024) return RT_ERR_UNSUPPORTED;
+    if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
+        (void)hipGetLastError();
+        return RT_ERR_UNSUPPORTED;
+    }
+    int nb = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&nb, fn, kPThreads, lds) != hipSuccess || nb < 1) {
+        (void)hipGetLastError();
+        return RT_ERR_UNSUPPORTED;
+    }
+    const Slab s = slab_for(D.d, D.F, G);
+    if (hipMalloc(&P.slab, s.total) != hipSuccess) {
+        (void)hipGetLastError();
+        P.slab = nullptr;
+        return RT_ERR_OOM;
+    }
+    if (hipMemset(P.slab, 0, s.total) != hipSuccess) {
+        (void)hipFree(P.slab);
+        P.slab = nullptr;
+        return RT_ERR_HIP;
+    }
+    P.slab_bytes = s.total;
+    P.d = D.d;
+    P.F = D.F;
+    P.grid = G;
+    P.lds_bytes = lds;
+    const char *sl = getenv("RT_SPIN_LIMIT");
+    P.spin_limit = sl ? atoll(sl) : (1LL << 21);
+    if (P.spin_limit < 1) P.spin_limit = 1;
+    P.nonce = 0;
+    P.want_trace = getenv("RT_DECODE_TRACE") != nullptr;
+    P.cooperative = getenv("RT_DECODE_COOPERATIVE") != nullptr;
+    P.available = true;
+    return RT_OK;
+}
+
+void decode_coop_destroy(DecodeCoopState &P)
+{
+    if (P.slab) (void)hipFree(P.slab);
+    P.slab = nullptr;
+    P.available = false;
+}
+
+size_t decode_coop_bytes(const DecodeCoopState &P) { return P.slab ? P.slab_bytes : 0; }
+
+bool decode_coop_supported(const DecodeCoopState &P, const LayerDims &D) { return P.available && D.B <= P.max_batch; }
+
+rt_status decode_coop_step(DecodeCoopState &P, const LayerDims &D, const Weights &W, const void *x_t, int t, void *y_t, void *K,
+                           void *V, hipStream_t st, std::string &err)
+{
+    DecArgs A;
+    A.B = D.B; A.d = D.d; A.H = D.H; A.F = D.F; A.BH = D.B * D.H; A.G = P.grid; A.t = t;
+    A.S = P.grid / A.BH < kDecMaxSplit ? P.grid / A.BH : kDecMaxSplit;
+    A.alpha = D.alpha; A.scale = D.scale; A.eps = D.eps; A.alibi = D.alibi; A.norm_free = D.norm_free;
+    const Rows r = rows_for(D.d, D.F, P.grid);
+    A.R_q = r.R_q; A.R_o = r.R_o; A.R_1 = r.R_1; A.R_kv = r.R_kv; A.R_2 = r.R_2;
+    A.ldw = D.d + 8; A.max_batch = P.max_batch;
+    A.Wq = (const bf16_t *)W.Wq; A.Wk = (const bf16_t *)W.Wk; A.Wv = (const bf16_t *)W.Wv; A.Wo = (const bf16_t *)W.Wo;
+    A.W1 = (const bf16_t *)W.W1; A.W2 = (const bf16_t *)W.W2;
+    A.g_attn = (const bf16_t *)W.g_attn; A.g_mlp = (const bf16_t *)W.g_mlp; A.g_kv = (const bf16_t *)W.g_kv;
+    A.g_q = (const bf16_t *)W.g_q; A.g_k = (const bf16_t *)W.g_k;
+    A.x = (const bf16_t *)x_t; A.y = (bf16_t *)y_t; A.K = (bf16_t *)K; A.V = (bf16_t *)V;
+    const Slab s = slab_for(D.d, D.F, P.grid);
+    char *p = (char *)P.slab;
+    A.bar = (unsigned long long *)(p + s.bar);
+    A.qkv_ll = (ll_t *)(p + s.qkv); A.part_ll = (ll_t *)(p + s.part);
+    A.a_ll = (ll_t *)(p + s.a); A.h_ll = (ll_t *)(p + s.h); A.z_ll = (ll_t *)(p + s.z); A.u_ll = (ll_t *)(p + s.u);
+    A.kv_ll = (ll_t *)(p + s.kv); A.zss_ll = (ll_t *)(p + s.zss); A.zp_ll = (ll_t *)(p + s.zp);
+    A.spin_limit = P.spin_limit;
+    A.pre_sleep = 1;
+    A.trace = P.want_trace ? (unsigned long long *)(p + s.trace) : nullptr;
+    // every word of the slab is written at most once per call and carries the call's number; when the numbers start
+    // over, no word of an earlier call may survive (the abort word at bar[8] is only ever set, never cleared here)
+    if (P.nonce == 0xFFFFFFFFu) {
+        hipLaunchKernelGGL(dec_clear_kernel, dim3(256), dim3(256), 0, st, (unsigned long long *)(p + s.qkv), (s.trace - s.qkv) / 8);
+        hipError_t ce = hipGetLastError();
+        if (ce != hipSuccess) { err = std::string("dec_clear_kernel: ") + hipGetErrorString(ce); return RT_ERR_HIP; }
+        P.nonce = 0;
+    }
+    P.nonce += 1;
+    A.tag = P.nonce;
+    // An ordinary launch: one workgroup fills a compute unit (LDS), the grid is one workgroup per compute unit, so every
+    // workgroup becomes resident as soon as the kernels before it on the stream have drained.  (A cooperative launch
+    // guarantees the same, but goes through the device's cooperative queue, which measured 19 us per step between
+    // two launches against 39 us of kernel.)  Two such launches on different streams at the same time could each
+    // hold a part of the chip and wait for the rest: their bounded waits then expire (rt_device_wait_expired).
+    hipError_t e;
+    if (P.cooperative) {
+        void *args[] = {&A};
+        e = hipLaunchCooperativeKernel((const void *)pick(D.d, D.F), dim3(P.grid), dim3(kPThreads), args, (unsigned int)P.lds_bytes, st);
+    } else {
+        hipLaunchKernelGGL(pick(D.d, D.F), dim3(P.grid), dim3(kPThreads), (unsigned int)P.lds_bytes, st, A);
+        e = hipGetLastError();
+    }
+    if (e != hipSuccess) { err = std::string("decode_coop_kernel launch: ") + hipGetErrorString(e); return RT_ERR_HIP; }
+    P.launched = true;
+    return RT_OK;
+}
+
+int decode_coop_wait_expired(DecodeCoopState &P)
+{
+    if (!P.slab || !P.launched) return 0;
+    unsigned long long v = 0;
+    if (hipMemcpy(&v, (char *)P.slab + 64, sizeof(v), hipMemcpyDeviceToHost) != hipSuccess) return -1;
+    return v != 0 ? 1 : 0;
+}
+
+int decode_coop_read_trace(DecodeCoopState &P, unsigned long long *out, int workgroups)
+{
+    if (!P.slab || !P.want_trace || !out) return 0;
+    const int n = workgroups < P.grid ? workgroups : P.grid;
+    const Slab s = slab_for(P.d, P.F, P.grid);
+    if (hipMemcpy(out, (char *)P.slab + s.trace, (size_t)n * 16 * 8, hipMemcpyDeviceToHost) != hipSuccess) return -1;
+    return n;
+}
+
+}  // namespace rt

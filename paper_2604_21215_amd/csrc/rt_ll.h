@@ -216,6 +216,48 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
     for (int i = 0; i < 4; ++i) r[i * kBMax] = acc[i];
 }
 
+// The product half of wg_gemv_ll alone: rows of an LDS-resident weight slice times activation rows that are already
+// staged in LDS as bf16 rows act_s[b][lda] (the caller has synchronised).  The per-wavefront 16 x 16 tiles land in
+// red[wave][row][b]; with SS the sum of squares of the staged rows goes to ss_s[wave][b].
+template <int KS, bool SS = false>
+__device__ __forceinline__ void wg_product_staged(const bf16_t *w_s, int ldw, int R, int B, float *red, const bf16_t *act_s, int lda,
+                                                  float *ss_s = nullptr)
+{
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+    const bool has_w = l16 < R, has_a = l16 < B;
+    constexpr int kw = KS * 32;
+    const bf16_t *wrow = w_s + (size_t)l16 * ldw + wave * kw + 8 * g;
+    const bf16_t *arow = act_s + (size_t)l16 * lda + wave * kw + 8 * g;
+    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    float ss = 0.f;
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+        Frag a, b;
+        a.u = has_w ? lds_load16(wrow + s * 32) : zero;
+        b.u = has_a ? lds_load16(arow + s * 32) : zero;
+        if (SS) {
+            const unsigned w4[4] = {b.u.x, b.u.y, b.u.z, b.u.w};
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                const float lo = __uint_as_float(w4[h] << 16), hi = __uint_as_float(w4[h] & 0xFFFF0000u);
+                ss = fmaf(lo, lo, ss);
+                ss = fmaf(hi, hi, ss);
+            }
+        }
+        acc = mfma16(a, b, acc);
+    }
+    if (SS) {
+        ss += __shfl_xor(ss, 16, 64);
+        ss += __shfl_xor(ss, 32, 64);
+        if (g == 0) ss_s[wave * kBMax + l16] = ss;
+    }
+    float *r = red + ((size_t)wave * kRMax + 4 * g) * kBMax + l16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i * kBMax] = acc[i];
+}
+
 __device__ __forceinline__ float red_sum(const float *red, int row, int b)
 {
     float v = 0.f;

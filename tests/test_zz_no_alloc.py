@@ -22,7 +22,8 @@ def test_static_decode_matches_context_decode(dtype, d, H, F):
     Bmax, N, cap = 3, 150, 160
     li = gen.make_custom(4242, dtype, Bmax, N + 1, d, H, F, gains="random")
     stream = torch.cuda.current_stream().cuda_stream
-    ctx = binding.RTContext(d, H, F, Bmax, cap, dtype, rms_eps=1e-6, attn_scale=0.5, stream=stream)
+    ctx = binding.RTContext(d, H, F, Bmax, cap, dtype, rms_eps=1e-6, attn_scale=0.5, stream=stream,
+                            flags=binding.RT_FLAG_ENGINE_STEPWISE)   # the multi-launch step: the kernels the context-free call runs
     try:
         dl = tio.DeviceLayer(li.weights, li.gains, dtype)
         xd = tio.to_device(li.x, dtype)
