@@ -299,7 +299,10 @@ def main():
                               "algorithmic_bytes": dec_bytes, "achieved": dec_bytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": dec_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
                               "traffic": (measured_traffic(args.workload, "decode") or {}).get("bytes") if t_dec == 2047 else None,
-                              "note": "eight launches per step on one stream (bf16: products on the matrix cores)"}
+                              "engine": ctx.engine_name(),
+                              "note": "one launch per step (256 workgroups, weight slices in LDS, cache rows and matrices requested at "
+                                      "its start)" if ctx.engine_name() == "decode-single-launch" else
+                                      "eight launches per step on one stream (bf16: products on the matrix cores)"}
 
     # The same layer without its sequential loop (every key-value pair known in advance): the recompute from a given
     # output (Sec. 6.1) and the standard Transformer layer (Sec. 2.1) - the paper's Figure 4 compares the tiled RT layer

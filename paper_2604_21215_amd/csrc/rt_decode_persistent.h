@@ -18,6 +18,7 @@ struct DecodeCoopState {
     unsigned nonce = 0;               // tag of the exchange words of the last call
     int d = 0, F = 0;
     bool cooperative = false;         // RT_DECODE_COOPERATIVE was set at rt_create: launch through the cooperative queue
+    int split_override = 0;           // RT_DECODE_SPLIT: at most this many workgroups share the cache rows of one (b, h)
     bool want_trace = false;          // RT_DECODE_TRACE was set at rt_create: the kernel stamps its phases
 };
 

@@ -119,6 +119,47 @@ __device__ __forceinline__ void copy_rows_batched(bf16_t *dst, int ldw, int nrow
     }
 }
 
+// The same copy in two halves, so that the rows can be in flight while the wavefront does something else: rows_issue
+// requests this thread's NB pieces (src(r): first element of row r, or null), rows_commit stores them to LDS,
+// multiplied by gain(r) (an LDS row of K gains, or null).
+template <int NB, int PER, typename SRC>
+__device__ __forceinline__ void rows_issue(uint4 (&w)[NB], int nrows, SRC src)
+{
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int idx = j * kPThreads + (int)threadIdx.x;
+        w[j] = make_uint4(0u, 0u, 0u, 0u);
+        if (idx < nrows * PER) {
+            const int r = idx / PER, c = idx - r * PER;
+            const bf16_t *row = src(r);
+            if (row) w[j] = global_load16(row + c * 8);
+        }
+    }
+}
+template <int NB, int PER, typename GAIN>
+__device__ __forceinline__ void rows_commit(const uint4 (&w)[NB], bf16_t *dst, int ldw, int nrows, GAIN gain)
+{
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int idx = j * kPThreads + (int)threadIdx.x;
+        if (idx >= nrows * PER) continue;
+        const int r = idx / PER, c = idx - r * PER;
+        uint4 v = w[j];
+        const bf16_t *g = gain(r);
+        if (g) {
+            const uint4 gq = lds_load16(g + c * 8);
+            float gg[8], ww[8];
+            load8(reinterpret_cast<const bf16_t *>(&gq), gg);
+            load8(reinterpret_cast<const bf16_t *>(&v), ww);
+            v.x = pack_bf16(ww[0] * gg[0], ww[1] * gg[1]);
+            v.y = pack_bf16(ww[2] * gg[2], ww[3] * gg[3]);
+            v.z = pack_bf16(ww[4] * gg[4], ww[5] * gg[5]);
+            v.w = pack_bf16(ww[6] * gg[6], ww[7] * gg[7]);
+        }
+        *reinterpret_cast<uint4 *>(dst + (size_t)r * ldw + c * 8) = v;
+    }
+}
+
 // The 64 cache rows k_lo .. k_lo + cnt - 1 of one (b, h): 16 KB requested at once.  Piece i of a lane is row
 // 8 i + lane / 8, columns 8 (lane % 8) .. + 7 (eight lanes cover one 128-byte row); rows past the end repeat the last.
 __device__ __forceinline__ void dec_load_chunk(const bf16_t *K, const bf16_t *V, size_t rs, int u, int k_lo, int cnt, uint4 (&kr)[8],
@@ -137,11 +178,17 @@ __device__ __forceinline__ void dec_load_chunk(const bf16_t *K, const bf16_t *V,
 // o8 this lane's share of the output (its eight columns over the rows it holds; the lanes that share columns are
 // summed once, after the last chunk).  q8: the query's elements at this lane's columns.  dist_first: distance of the
 // chunk's first key from the query (ALiBi).
+// The logit of row 8 i + lane / 8 is summed over the eight lanes of the row with three DPP steps and stays in all
+// eight of them (register i), which is where the softmax weight is needed for the value rows: no value crosses the
+// LDS crossbar.  (With the logits gathered to one key per lane - four dependent ds_bpermute per piece and one more
+// per value piece - a chunk took 2 us of a wavefront's time.)  Every weight is computed by the eight lanes of its
+// row, so the row sum over all lanes counts it eight times.
 __device__ __forceinline__ void dec_attend_chunk(const uint4 (&kr)[8], const uint4 (&vr)[8], const float (&q8)[8], int cnt,
                                                  int dist_first, float scale, float slope, float &m, float &l, float (&o8)[8])
 {
-    const int lane = threadIdx.x & 63;
-    float acc = 0.f;
+    const int lane = threadIdx.x & 63, r8 = lane >> 3;
+    float sc[8];
+    float mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const uint32_t w[4] = {kr[i].x, kr[i].y, kr[i].z, kr[i].w};
@@ -151,23 +198,22 @@ __device__ __forceinline__ void dec_attend_chunk(const uint4 (&kr)[8], const uin
             dsum = fmaf(q8[2 * e], __uint_as_float(w[e] << 16), dsum);
             dsum = fmaf(q8[2 * e + 1], __uint_as_float(w[e] & 0xFFFF0000u), dsum);
         }
-        dsum += __shfl_xor(dsum, 1, 64);
-        dsum += __shfl_xor(dsum, 2, 64);
-        dsum += __shfl_xor(dsum, 4, 64);
-        const float mine = __shfl(dsum, (lane & 7) * 8, 64);   // row 8 i + lane % 8
-        if ((lane >> 3) == i) acc = mine;
+        dsum += dpp_f(dsum, 0);
+        dsum += dpp_f(dsum, 1);
+        dsum += dpp_f(dsum, 2);   // all eight lanes of the row hold its sum
+        const int j = 8 * i + r8;
+        sc[i] = j < cnt ? fmaf(-slope, (float)(dist_first - j), dsum * scale) : -INFINITY;
+        mx = fmaxf(mx, sc[i]);
     }
-    const bool valid = lane < cnt;
-    const float logit = valid ? fmaf(-slope, (float)(dist_first - lane), acc * scale) : -INFINITY;
-    const float m_new = fmaxf(m, fast_max(logit));
+    const float m_new = fmaxf(m, fast_max(mx));
     const float resc = __expf(m - m_new);   // exp(-inf) = 0 on the first chunk
-    const float p = valid ? __expf(logit - m_new) : 0.f;
-    l = l * resc + fast_sum(p);
+    float psum = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) o8[e] *= resc;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const float pr = __shfl(p, 8 * i + (lane >> 3), 64);
+        const float pr = __expf(sc[i] - m_new);   // exp(-inf) = 0 for rows past the end
+        psum += pr;
         const uint32_t w[4] = {vr[i].x, vr[i].y, vr[i].z, vr[i].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -175,6 +221,7 @@ __device__ __forceinline__ void dec_attend_chunk(const uint4 (&kr)[8], const uin
             o8[2 * e + 1] = fmaf(pr, __uint_as_float(w[e] & 0xFFFF0000u), o8[2 * e + 1]);
         }
     }
+    l = l * resc + fast_sum(psum) * 0.125f;
     m = m_new;
 }
 
@@ -232,6 +279,12 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
     const bool is_merger = att && s == 0 && wave == 0;
 
     RT_DEC_STAMP(0);
+    // ---- the first two chunks of this wavefront: requested before anything else, used after phase Q.  The cache rows
+    // are most of the step's bytes (2 t B d of 2 t B d + 12 d^2); with them in flight from the first instruction the
+    // memory system is busy for the whole first part of the launch and phase Q hides in their shadow.
+    uint4 krA[8], vrA[8], krB[8], vrB[8];
+    int cA = wave * S + s, cB = cA + nworkers;
+    if (att && cA < nch) dec_load_chunk(A.K, A.V, rs, u, cA * 64, min(64, t - cA * 64), krA, vrA);
     // ================================================================ input rows and the rows of [Wq; Wk; Wv]
     for (int idx = tid; idx < B * PER; idx += kPThreads) {
         const int r = idx / PER, c = idx - r * PER;
@@ -244,11 +297,6 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
         return RowSrc{Wm + (size_t)row * d, g_in};
     });
 
-    // ---- the first two chunks of this wavefront: requested now, used after phase Q
-    uint4 krA[8], vrA[8], krB[8], vrB[8];
-    int cA = wave * S + s, cB = cA + nworkers;
-    if (att && cA < nch) dec_load_chunk(A.K, A.V, rs, u, cA * 64, min(64, t - cA * 64), krA, vrA);
-    if (att && cB < nch) dec_load_chunk(A.K, A.V, rs, u, cB * 64, min(64, t - cB * 64), krB, vrB);
     __syncthreads();
     RT_DEC_STAMP(1);
 
@@ -269,20 +317,35 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
     if (tid < kRMax * kBMax && erow < o_n && eb < B) xv = bf16_to_f32(A.x[(size_t)eb * d + o_lo + erow]);
     __syncthreads();   // red, sq and the staged rows are reused
     RT_DEC_STAMP(2);
+    if (att && cB < nch) dec_load_chunk(A.K, A.V, rs, u, cB * 64, min(64, t - cB * 64), krB, vrB);
 
     // ================================================================ the other four weight slices
-    {
-        const bf16_t *gm = A.norm_free ? nullptr : A.g_mlp, *gkv = A.norm_free ? nullptr : A.g_kv;
-        const int n1 = A.R_o, n2 = n1 + A.R_1, n3 = n2 + A.R_2, n4 = n3 + A.R_kv;
-        copy_rows_batched<6, PER>(wo_s, A.ldw, n4, [&](int r) {
-            if (r < n1) return r < o_n ? RowSrc{A.Wo + (size_t)(o_lo + r) * d, nullptr} : RowSrc{nullptr, nullptr};
-            if (r < n2) return r - n1 < f_n ? RowSrc{A.W1 + (size_t)(f_lo + r - n1) * d, gm} : RowSrc{nullptr, nullptr};
-            if (r < n3) return RowSrc{A.W2 + (size_t)(rb * RB + r - n2) * F + (size_t)jb * d, nullptr};
-            const int rr = r - n3, o = kv_lo + rr;
-            if (rr >= kv_n) return RowSrc{nullptr, nullptr};
-            return o < d ? RowSrc{A.Wk + (size_t)o * d, gkv} : RowSrc{A.Wv + (size_t)(o - d) * d, gkv};
-        });
+    // Requested (into registers) after this wavefront's first chunk, so that the cache rows, which the step needs first,
+    // are served first; stored to LDS before phase O.  The gains of W1's and [Wk; Wv]'s columns wait in the LDS rows
+    // that held [Wq; Wk; Wv].
+    constexpr int WROWS = RO + R1 + 4 * KSD + RKV;
+    constexpr int NBW = (WROWS * PER + kPThreads - 1) / kPThreads;
+    const int n1 = A.R_o, n2 = n1 + A.R_1, n3 = n2 + A.R_2, n4 = n3 + A.R_kv;
+    const bf16_t *gm = A.norm_free ? nullptr : A.g_mlp, *gkv = A.norm_free ? nullptr : A.g_kv;
+    bf16_t *gm_s = wq_s, *gkv_s = wq_s + A.ldw;
+    if (tid < 2 * PER) {
+        const bf16_t *g = tid < PER ? gm : gkv;
+        if (g) *reinterpret_cast<uint4 *>((tid < PER ? gm_s : gkv_s) + (tid % PER) * 8) = global_load16(g + (tid % PER) * 8);
     }
+    uint4 wreg[NBW];
+    auto weight_row = [&](int r) -> const bf16_t * {
+        if (r < n1) return r < o_n ? A.Wo + (size_t)(o_lo + r) * d : nullptr;
+        if (r < n2) return r - n1 < f_n ? A.W1 + (size_t)(f_lo + r - n1) * d : nullptr;
+        if (r < n3) return A.W2 + (size_t)(rb * RB + r - n2) * F + (size_t)jb * d;
+        const int rr = r - n3, o = kv_lo + rr;
+        if (rr >= kv_n) return nullptr;
+        return o < d ? A.Wk + (size_t)o * d : A.Wv + (size_t)(o - d) * d;
+    };
+    auto weight_gain = [&](int r) -> const bf16_t * {
+        if (r >= n1 && r < n2) return gm ? gm_s : nullptr;
+        if (r >= n3) return gkv ? gkv_s : nullptr;
+        return nullptr;
+    };
 
     RT_DEC_STAMP(3);
     // ================================================================ phase A: this wavefront's chunks
@@ -298,16 +361,20 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
         for (int e = 0; e < 8; ++e) q8[e] = __shfl(qn, (lane & 7) * 8 + e, 64);
         const float slope = alibi_slope(A.alibi, uh, H);
         float m = -INFINITY, l = 0.f, o8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (;;) {
-            if (cA >= nch) break;
-            dec_attend_chunk(krA, vrA, q8, min(64, t - cA * 64), t - cA * 64, A.scale, slope, m, l, o8);
+        while (cA + 2 * nworkers < nch) {   // both chunks in hand have a successor or are followed by one
+            dec_attend_chunk(krA, vrA, q8, 64, t - cA * 64, A.scale, slope, m, l, o8);
             cA += 2 * nworkers;
-            if (cA < nch) dec_load_chunk(A.K, A.V, rs, u, cA * 64, min(64, t - cA * 64), krA, vrA);
-            if (cB >= nch) break;
-            dec_attend_chunk(krB, vrB, q8, min(64, t - cB * 64), t - cB * 64, A.scale, slope, m, l, o8);
+            dec_load_chunk(A.K, A.V, rs, u, cA * 64, min(64, t - cA * 64), krA, vrA);
+            dec_attend_chunk(krB, vrB, q8, 64, t - cB * 64, A.scale, slope, m, l, o8);
             cB += 2 * nworkers;
             if (cB < nch) dec_load_chunk(A.K, A.V, rs, u, cB * 64, min(64, t - cB * 64), krB, vrB);
         }
+        // the last one or two chunks; the weight rows are requested between them (into the registers of the first)
+        if (cA < nch) dec_attend_chunk(krA, vrA, q8, min(64, t - cA * 64), t - cA * 64, A.scale, slope, m, l, o8);
+        __builtin_amdgcn_sched_barrier(0);   // the requests below must not move up: their registers are the first chunk's
+        rows_issue<NBW, PER>(wreg, n4, weight_row);
+        __builtin_amdgcn_sched_barrier(0);
+        if (cB < nch) dec_attend_chunk(krB, vrB, q8, min(64, t - cB * 64), t - cB * 64, A.scale, slope, m, l, o8);
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             o8[e] += __shfl_xor(o8[e], 8, 64);
@@ -320,6 +387,8 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
             for (int e = 0; e < 8; ++e) ps[lane * 8 + e] = o8[e];
         }
         if (lane == 0) { ps[64] = m; ps[65] = l; }
+    } else {
+        rows_issue<NBW, PER>(wreg, n4, weight_row);
     }
     RT_DEC_STAMP(4);
     RT_DEC_ABORT_IF(fail);   // also orders the eight states in LDS before wavefront 0 reads them
@@ -364,6 +433,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
                          (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
         }
     }
+    rows_commit<NBW, PER>(wreg, wo_s, A.ldw, n4, weight_gain);
     RT_DEC_ABORT_IF(fail);
     RT_DEC_STAMP(6);
 
@@ -610,6 +680,7 @@ rt_status decode_coop_create(DecodeCoopState &P, const rt_config &cfg, const Lay
     P.nonce = 0;
     P.want_trace = getenv("RT_DECODE_TRACE") != nullptr;
     P.cooperative = getenv("RT_DECODE_COOPERATIVE") != nullptr;
+    P.split_override = getenv("RT_DECODE_SPLIT") ? atoi(getenv("RT_DECODE_SPLIT")) : 0;
     P.available = true;
     return RT_OK;
 }
@@ -631,6 +702,7 @@ rt_status decode_coop_step(DecodeCoopState &P, const LayerDims &D, const Weights
     DecArgs A;
     A.B = D.B; A.d = D.d; A.H = D.H; A.F = D.F; A.BH = D.B * D.H; A.G = P.grid; A.t = t;
     A.S = P.grid / A.BH < kDecMaxSplit ? P.grid / A.BH : kDecMaxSplit;
+    if (P.split_override > 0 && P.split_override < A.S) A.S = P.split_override;
     A.alpha = D.alpha; A.scale = D.scale; A.eps = D.eps; A.alibi = D.alibi; A.norm_free = D.norm_free;
     const Rows r = rows_for(D.d, D.F, P.grid);
     A.R_q = r.R_q; A.R_o = r.R_o; A.R_1 = r.R_1; A.R_kv = r.R_kv; A.R_2 = r.R_2;
