@@ -41,6 +41,7 @@ struct rt_ctx {
     void *par_slab = nullptr;        // activations of the loop-free evaluations (rt_layer_recompute, rt_transformer_layer)
     size_t par_bytes = 0;
     void *bw_slab = nullptr;         // scratch of rt_layer_backward
+    BwpState bw_loop;                // its single-launch reverse loop
     size_t bw_bytes = 0;
     // cached HIP graph of one stepwise prefill
     hipGraphExec_t graph_exec = nullptr;
@@ -215,6 +216,15 @@ static rt_status ensure_backward_scratch(rt_ctx *c)
         return fail(c, e == hipErrorOutOfMemory ? RT_ERR_OOM : RT_ERR_HIP, "backward scratch: %s", hipGetErrorString(e));
     }
     c->bw_bytes = need;
+    size_t xo = 0, xb = 0;
+    backward_exchange_region((size_t)c->cfg.max_batch, (size_t)c->cfg.max_seq, (size_t)c->cfg.d_model, (size_t)c->cfg.d_hidden,
+                             (size_t)c->cfg.n_heads, E, &xo, &xb);
+    if (xb > 0) {
+        e = hipMemset((char *)c->bw_slab + xo, 0, xb);
+        if (e != hipSuccess) return fail_hip(c, e, "backward scratch");
+        (void)bwp_create(c->bw_loop, c->cfg.device, c->cfg.d_model, c->cfg.d_hidden, c->cfg.n_heads, c->cfg.max_batch,
+                         c->use_mfma && !(c->cfg.flags & RT_FLAG_ENGINE_STEPWISE));
+    }
     return RT_OK;
 }
 
@@ -412,8 +422,18 @@ int32_t rt_device_wait_expired(rt_ctx *c)
     if (w) {
         c->broken = true;
         c->err = "a bounded device-side wait expired in the single-launch decoding step";
+        return w;
     }
-    return w;
+    if (c->bw_slab && c->bw_loop.available) {   // abort word of the backward pass's single-launch loop (word 8 of its exchange area)
+        unsigned long long a = 0;
+        if (hipMemcpy(&a, (char *)c->bw_slab + 64, sizeof(a), hipMemcpyDeviceToHost) != hipSuccess) return -1;
+        if (a != 0) {
+            c->broken = true;
+            c->err = "a bounded device-side wait expired in the reverse loop of the backward pass";
+            return 1;
+        }
+    }
+    return 0;
 }
 
 int32_t rt_phase_trace(rt_ctx *c, uint64_t *out, int32_t rows)
@@ -1020,7 +1040,7 @@ extern "C" rt_status rt_layer_backward(rt_ctx *c, const rt_layer_weights *w, con
     BwGrads G = {grads->Wq, grads->Wk, grads->Wv, grads->Wo, grads->W1, grads->W2,
                  grads->g_attn, grads->g_mlp, grads->g_kv, grads->g_q, grads->g_k};
     c->engine = "backward";
-    hipError_t e = c->cfg.dtype == RT_BF16 ? backward_layer<bf16_t>(D, W, x, z, gy, gK, gV, dx, G, c->bw_slab, c->use_mfma, c->stream)
+    hipError_t e = c->cfg.dtype == RT_BF16 ? backward_layer<bf16_t>(D, W, x, z, gy, gK, gV, dx, G, c->bw_slab, c->use_mfma, c->stream, &c->bw_loop)
                                            : backward_layer<float>(D, W, x, z, gy, gK, gV, dx, G, c->bw_slab, false, c->stream);
     if (e != hipSuccess) return fail_hip(c, e, "backward_layer");
     return RT_OK;

@@ -1,6 +1,7 @@
 // Internal interface of the backward pass (rt_backward.hip), paper Sec. 6.4.
 #pragma once
 #include "rt_common.h"
+#include "rt_backward_persistent.h"
 
 namespace rt {
 
@@ -15,8 +16,13 @@ size_t backward_scratch_bytes(size_t B, size_t N, size_t d, size_t F, size_t H, 
 
 // x, z, gy [B][N][d]; gK, gV [N][B][H][64] or null (storage type T); dx [B][N][d] fp32.
 // matrix_cores: with bf16 storage the batched products run on the matrix cores from bf16 copies of their operands.
+// loop: the single-launch reverse loop (or null: one set of launches per position); its exchange words are part of ws
+// and must have been zeroed once (backward_exchange_region).
 template <typename T>
 hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x, const void *z, const void *gy, const void *gK,
-                          const void *gV, float *dx, const BwGrads &G, void *ws, bool matrix_cores, hipStream_t st);
+                          const void *gV, float *dx, const BwGrads &G, void *ws, bool matrix_cores, hipStream_t st,
+                          BwpState *loop = nullptr);
+// where the exchange words of the single-launch loop lie inside a scratch area laid out for B x N positions
+void backward_exchange_region(size_t B, size_t N, size_t d, size_t F, size_t H, size_t E, size_t *offset, size_t *bytes);
 
 }  // namespace rt

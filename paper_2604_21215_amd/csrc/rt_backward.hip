@@ -826,6 +826,12 @@ struct BwBufs {
     bf16_t *WqkvT_b;         // [d][3d]
     bf16_t *tA, *tB;         // transposed operands of the parameter sums, [rows][Mp]
     float *part;             // contraction slices of a parameter sum
+    // single-launch reverse loop: the loop-independent halves of its products (rt_backward_persistent.hip) and its
+    // exchange words
+    bf16_t *gy_pf;           // [M][d] gy with position-first rows
+    float *A_gy, *A_uz;      // [M][F]
+    float *C_gy, *C_uz, *C_uh;   // [M][d]
+    char *exchange;
 };
 
 // contraction slices of the parameter sums over M rows: as many as keep 512 rows and more per slice, at most 16
@@ -840,6 +846,9 @@ size_t carve_bufs(BwBufs &Bf, char *base, size_t B, size_t N, size_t d, size_t F
 {
     Carver cv{base};
     const size_t M = B * N;
+    // the exchange words of the single-launch loop come first: their place does not depend on the call's B and N
+    // (they are zeroed once, when the scratch is allocated)
+    Bf.exchange = E == 2 ? cv.take<char>(bwp_exchange_bytes((int)d, (int)F)) : nullptr;
     Bf.Wqkv_f = cv.take<float>(3 * d * d); Bf.Wo_f = cv.take<float>(d * d); Bf.W1_f = cv.take<float>(F * d); Bf.W2_f = cv.take<float>(d * F);
     Bf.WkvT = cv.take<char>(2 * d * d * E); Bf.W2T = cv.take<char>(F * d * E); Bf.W1T = cv.take<char>(d * F * E); Bf.WoT = cv.take<char>(d * d * E);
     Bf.unit_x = cv.take<float>(M * d); Bf.nxg = gains ? cv.take<float>(M * d) : Bf.unit_x; Bf.rinv_x = cv.take<float>(M);
@@ -860,6 +869,13 @@ size_t carve_bufs(BwBufs &Bf, char *base, size_t B, size_t N, size_t d, size_t F
     Bf.G3_b = cv.take<bf16_t>(M * 3 * d); Bf.WqkvT_b = cv.take<bf16_t>(3 * d * d);
     Bf.tA = cv.take<bf16_t>(wide * Mp); Bf.tB = cv.take<bf16_t>((F > d ? F : d) * Mp);
     Bf.part = cv.take<float>(16 * d * d > 4 * F * d ? 16 * d * d : 4 * F * d);
+    if (E == 2) {
+        Bf.gy_pf = cv.take<bf16_t>(M * d);
+        Bf.A_gy = cv.take<float>(M * F); Bf.A_uz = cv.take<float>(M * F);
+        Bf.C_gy = cv.take<float>(M * d); Bf.C_uz = cv.take<float>(M * d); Bf.C_uh = cv.take<float>(M * d);
+    } else {
+        Bf.gy_pf = nullptr; Bf.A_gy = Bf.A_uz = Bf.C_gy = Bf.C_uz = Bf.C_uh = nullptr;
+    }
     return cv.off;
 }
 
@@ -882,9 +898,27 @@ size_t backward_scratch_bytes(size_t B, size_t N, size_t d, size_t F, size_t H, 
     return carve_bufs(tmp, nullptr, B, N, d, F, H, E, true);
 }
 
+void backward_exchange_region(size_t B, size_t N, size_t d, size_t F, size_t H, size_t E, size_t *offset, size_t *bytes)
+{
+    (void)B; (void)N; (void)H;
+    *offset = 0;
+    *bytes = E == 2 ? bwp_exchange_bytes((int)d, (int)F) : 0;
+}
+
+// rows of a [B][N][d] tensor in position-first order (row n B + b), bf16
+__global__ __launch_bounds__(256) void bw_rows_pf_kernel(const bf16_t *__restrict__ in, bf16_t *__restrict__ out, int B, int N, int d)
+{
+    const size_t n_el = (size_t)B * N * d;
+    for (size_t e = (size_t)blockIdx.x * 256 + threadIdx.x; e < n_el; e += (size_t)gridDim.x * 256) {
+        const size_t r = e / d, c = e % d;
+        const size_t n = r / B, b = r % B;
+        out[e] = in[(b * N + n) * d + c];
+    }
+}
+
 template <typename T>
 hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, const void *z_, const void *gy_, const void *gK_,
-                          const void *gV_, float *dx, const BwGrads &G, void *ws, bool matrix_cores, hipStream_t st)
+                          const void *gV_, float *dx, const BwGrads &G, void *ws, bool matrix_cores, hipStream_t st, BwpState *loop)
 {
     const int B = D.B, N = D.N, d = D.d, F = D.F, H = D.H, M = B * N, BH = B * H, nf = D.norm_free;
     const T *x = (const T *)x_, *z = (const T *)z_, *gy = (const T *)gy_;
@@ -989,6 +1023,45 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
     // ---- (B) the reverse loop
     hipLaunchKernelGGL(bw_init_pairs_kernel<T>, grid1((size_t)M * d), blk, 0, st, (const T *)gK_, (const T *)gV_, Bf.dK, Bf.dV,
                        (size_t)M * d);
+    const bool single_launch = mm && loop != nullptr && Bf.exchange != nullptr && bwp_supported(*loop, D);
+    if (single_launch) {
+        // the halves of the loop's products that do not depend on the loop (see rt_backward_persistent.hip): with gy and
+        // the normalised rows of z and h known for all positions, W2^T and Wo^T of them are batched products here
+        const bf16_t *W2T = (const bf16_t *)Bf.W2T, *WoT = (const bf16_t *)Bf.WoT;
+        hipLaunchKernelGGL(bw_rows_pf_kernel, grid1((size_t)M * d), blk, 0, st, (const bf16_t *)gy, Bf.gy_pf, B, N, d);
+        mm_nt(Bf.gy_pf, d, W2T, d, Bf.A_gy, (size_t)F, M, F, d, 1.f, false, 1);
+        mm_nt(Bf.gy_pf, d, WoT, d, Bf.C_gy, (size_t)d, M, d, d, 1.f, false, 1);
+        hipLaunchKernelGGL(bw_split_rows_kernel, grid1((size_t)M * d), blk, 0, st, Bf.unit_z, (size_t)d, Bf.op_hi, Bf.op_lo, (size_t)d, M, d);
+        mm_nt(Bf.op_lo, d, W2T, d, Bf.A_uz, (size_t)F, M, F, d, 1.f, false, 1);
+        mm_nt(Bf.op_hi, d, W2T, d, Bf.A_uz, (size_t)F, M, F, d, 1.f, true, 1);
+        mm_nt(Bf.op_lo, d, WoT, d, Bf.C_uz, (size_t)d, M, d, d, 1.f, false, 1);
+        mm_nt(Bf.op_hi, d, WoT, d, Bf.C_uz, (size_t)d, M, d, d, 1.f, true, 1);
+        hipLaunchKernelGGL(bw_split_rows_kernel, grid1((size_t)M * d), blk, 0, st, Bf.unit_h, (size_t)d, Bf.op_hi, Bf.op_lo, (size_t)d, M, d);
+        mm_nt(Bf.op_lo, d, WoT, d, Bf.C_uh, (size_t)d, M, d, d, 1.f, false, 1);
+        mm_nt(Bf.op_hi, d, WoT, d, Bf.C_uh, (size_t)d, M, d, d, 1.f, true, 1);
+        BwpTensors Tn;
+        Tn.WkvT = (const bf16_t *)Bf.WkvT; Tn.W2T = W2T; Tn.W1T = (const bf16_t *)Bf.W1T; Tn.WoT = WoT;
+        Tn.g_kv = (const bf16_t *)g_kv; Tn.g_mlp = (const bf16_t *)g_mlp; Tn.g_k = (const bf16_t *)g_k;
+        Tn.gy = (const bf16_t *)gy;
+        Tn.unit_k = Bf.kv; Tn.rk = Bf.rk; Tn.unit_z = Bf.unit_z; Tn.rinv_z = Bf.rinv_z; Tn.unit_h = Bf.unit_h; Tn.rinv_h = Bf.rinv_h;
+        Tn.gp = Bf.gp; Tn.A_gy = Bf.A_gy; Tn.A_uz = Bf.A_uz; Tn.C_gy = Bf.C_gy; Tn.C_uz = Bf.C_uz; Tn.C_uh = Bf.C_uh;
+        Tn.Qn = Bf.Qn; Tn.Ktn = Bf.Ktn; Tn.Vt = Bf.Vt; Tn.Kp = Bf.Kp; Tn.Vp = Bf.Vp; Tn.c = Bf.c; Tn.lse = Bf.lse;
+        Tn.dK = Bf.dK; Tn.dV = Bf.dV; Tn.dkraw = Bf.dkraw; Tn.d_rz = Bf.d_rz; Tn.Gz = Bf.Gz; Tn.dpre = Bf.dpre; Tn.t1 = Bf.t1;
+        Tn.d_h = Bf.d_h; Tn.dc = Bf.dc; Tn.Ds = Bf.Ds; Tn.dq = Bf.dq; Tn.dkt = Bf.dkt; Tn.dvt = Bf.dvt;
+        // one launch per block of kBwPmin positions, last block first; the block of Algorithm 1 that ends just before a
+        // launch's first position takes that launch's (and the later ones') queries to the earlier keys
+        for (int i_lo = ((N - 1) / kBwPmin) * kBwPmin; i_lo >= 0; i_lo -= kBwPmin) {
+            const int i_hi = i_lo + kBwPmin - 1 < N - 1 ? i_lo + kBwPmin - 1 : N - 1;
+            e = bwp_run_block(*loop, D, Tn, Bf.exchange, i_hi, i_lo, st);
+            if (e != hipSuccess) return e;
+            if (i_lo > 0) {
+                const int P = i_lo & -i_lo, nq = P < N - i_lo ? P : N - i_lo;
+                hipLaunchKernelGGL(bw_event_kernel, dim3((unsigned)((P + 63) / 64), BH), blk, kEventLds, st, Bf.Qn, Bf.Kp, Bf.Vp, Bf.dc, Bf.lse,
+                                   Bf.Ds, Bf.dK, Bf.dV, B, H, i_lo - P, P, i_lo, nq, D.scale, D.alibi);
+            }
+        }
+    }
+    if (!single_launch) {
     bool pair_done = false;   // [dkraw | dV] of position i was already prepared by the query after it
     for (int i = N - 1; i >= 0; --i) {
         const size_t ro = (size_t)i * B;
@@ -1015,6 +1088,7 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
             hipLaunchKernelGGL(bw_event_kernel, dim3((unsigned)((P + 63) / 64), BH), blk, kEventLds, st, Bf.Qn, Bf.Kp, Bf.Vp, Bf.dc, Bf.lse,
                                Bf.Ds, Bf.dK, Bf.dV, B, H, i - P, P, i, nq, D.scale, D.alibi);
         }
+    }
     }
 
     // ---- (C) batched remainder
@@ -1104,8 +1178,8 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
 }
 
 template hipError_t backward_layer<float>(const LayerDims &, const Weights &, const void *, const void *, const void *, const void *,
-                                          const void *, float *, const BwGrads &, void *, bool, hipStream_t);
+                                          const void *, float *, const BwGrads &, void *, bool, hipStream_t, BwpState *);
 template hipError_t backward_layer<bf16_t>(const LayerDims &, const Weights &, const void *, const void *, const void *, const void *,
-                                           const void *, float *, const BwGrads &, void *, bool, hipStream_t);
+                                           const void *, float *, const BwGrads &, void *, bool, hipStream_t, BwpState *);
 
 }  // namespace rt

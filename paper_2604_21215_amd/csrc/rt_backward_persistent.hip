@@ -496,8 +496,11 @@ hipError_t bwp_run_block(BwpState &P, const LayerDims &D, const BwpTensors &T, v
     }
     P.nonce += 1;
     A.tag_base = P.nonce << 20;
-    void *args[] = {&A};
-    return hipLaunchCooperativeKernel((const void *)pick(D.d, D.F), dim3(P.grid), dim3(kPThreads), args, (unsigned int)P.lds_bytes, st);
+    // an ordinary launch: one workgroup fills a compute unit and the grid is one workgroup per compute unit, so all of
+    // them are resident once the kernels before it on the stream have drained (the cooperative queue costs about
+    // 20 us per launch, measured on the decoding step)
+    hipLaunchKernelGGL(pick(D.d, D.F), dim3(P.grid), dim3(kPThreads), (unsigned int)P.lds_bytes, st, A);
+    return hipGetLastError();
 }
 
 }  // namespace rt

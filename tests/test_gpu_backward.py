@@ -53,6 +53,7 @@ def _run(oracle, dtype, B, N, d, H, F, *, gains="random", alpha=1.0, scale=1.0, 
         grads.update({k: torch.full((d,), float("nan"), dtype=torch.float32, device="cuda:0") for k in GAINS})
         ctx.rt_layer_backward(dl.struct, xd, zd, dev(gy), dev(gK), dev(gV), dx, grads)
         torch.cuda.synchronize()
+        assert ctx.device_wait_expired() == 0
         assert ctx.engine_name() == "backward"
         got_dx = dx.cpu().numpy().astype(np.float64)
         got = {k: v.cpu().numpy().astype(np.float64) for k, v in grads.items()}
