@@ -298,7 +298,8 @@ def main():
         out["decode_step"] = {"t": t_dec, "us_per_step": us, "tokens_per_s": wl.B / (us * 1e-6), "bound": "hbm",
                               "algorithmic_bytes": dec_bytes, "achieved": dec_bytes / (us * 1e-6) / 1e9, "peak": HBM_PEAK_GBS,
                               "unit": "GB/s", "frac": dec_bytes / (us * 1e-6) / 1e9 / HBM_PEAK_GBS,
-                              "traffic": (measured_traffic(args.workload, "decode") or {}).get("bytes") if t_dec == 2047 else None,
+                              "traffic": (measured_traffic(args.workload, "decode" if ctx.engine_name() == "decode-single-launch"
+                                                            else "decode_multi_launch") or {}).get("bytes") if t_dec == 2047 else None,
                               "engine": ctx.engine_name(),
                               "note": "one launch per step (256 workgroups, weight slices in LDS, cache rows and matrices requested at "
                                       "its start)" if ctx.engine_name() == "decode-single-launch" else

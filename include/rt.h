@@ -117,7 +117,15 @@ rt_status rt_layer_prefill(rt_ctx *ctx, const rt_layer_weights *w, const void *x
  * cached persistent pairs like a Transformer).
  *   x_t [B, d] device; t is 0-based: rows 0..t-1 of K, V are valid, row t is written; y_t [B, d].
  *   0 <= t < kv_cap, t < max_seq.  N successive decode steps equal one prefill of length N.
- *   x_t, y_t, K and V must not overlap one another (RT_ERR_INVALID_ARG, nothing enqueued). */
+ *   x_t, y_t, K and V must not overlap one another (RT_ERR_INVALID_ARG, nothing enqueued).
+ * bf16 storage with the MFMA kernels, d_model in {256, 512, 768, 1024}, d_hidden = 4 d_model, B n_heads <= 256, on a
+ * device with 256 compute units: the whole step is ONE kernel launch of one workgroup per compute unit (engine name
+ * "decode-single-launch"): the cache rows and the rows of all six matrices are requested at its start, the base case
+ * runs on weight slices held in LDS, and the workgroups exchange the vectors between the products through memory.  The
+ * workgroups wait for one another, so two such steps must not run at the same time on one device (two contexts on two
+ * streams): each could hold part of the chip and wait for the rest; their bounded waits would then expire
+ * (rt_device_wait_expired) instead of hanging.  Steps on one stream are ordered and safe.  Any other shape or dtype, and
+ * contexts created with RT_FLAG_ENGINE_STEPWISE, take eight launches per step instead. */
 rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t, void *y_t,
                          void *K, void *V, int32_t kv_cap);
 

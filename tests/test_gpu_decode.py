@@ -86,3 +86,10 @@ def test_decode_alibi_and_norm_free(oracle):
 
 def test_decode_smaller_batch_than_context(oracle):
     _decode_case(oracle, 2, 140, 512, 8, n0=130, steps=list(range(130, 140)), seed=38, max_batch=8)
+
+
+def test_decode_many_chunks_per_wavefront(oracle, monkeypatch):
+    # one workgroup per (b, h) (RT_DECODE_SPLIT = 1): 23 chunks over eight wavefronts - the loop that reloads a
+    # wavefront's two chunk buffers runs, some wavefronts end on the first buffer and some on the second
+    monkeypatch.setenv("RT_DECODE_SPLIT", "1")
+    _decode_case(oracle, 3, 1450, 256, 4, n0=1444, steps=list(range(1444, 1450)), seed=39, scale=0.5)
