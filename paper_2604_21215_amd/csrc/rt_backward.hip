@@ -23,6 +23,7 @@
 #include "rt_base_case.h"
 #include "rt_gemm_tiled.h"
 #include "rt_backward.h"
+#include <cstdlib>
 
 namespace rt {
 
@@ -831,6 +832,7 @@ struct BwBufs {
     bf16_t *gy_pf;           // [M][d] gy with position-first rows
     float *A_gy, *A_uz;      // [M][F]
     float *C_gy, *C_uz, *C_uh;   // [M][d]
+    char *flash;             // bf16 copies of the pairs for the recompute's attention on the matrix cores
     char *exchange;
 };
 
@@ -873,8 +875,10 @@ size_t carve_bufs(BwBufs &Bf, char *base, size_t B, size_t N, size_t d, size_t F
         Bf.gy_pf = cv.take<bf16_t>(M * d);
         Bf.A_gy = cv.take<float>(M * F); Bf.A_uz = cv.take<float>(M * F);
         Bf.C_gy = cv.take<float>(M * d); Bf.C_uz = cv.take<float>(M * d); Bf.C_uh = cv.take<float>(M * d);
+        Bf.flash = cv.take<char>(flash_recompute_scratch_bytes(B, N, d, H));
     } else {
         Bf.gy_pf = nullptr; Bf.A_gy = Bf.A_uz = Bf.C_gy = Bf.C_uz = Bf.C_uh = nullptr;
+        Bf.flash = nullptr;
     }
     return cv.off;
 }
@@ -1012,8 +1016,13 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
     hipLaunchKernelGGL(bw_head_norm_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.kv, 2 * d, 0, g_k, Bf.Kp, Bf.rk, H, D.eps, nf);
     hipLaunchKernelGGL(bw_head_norm_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.kv, 2 * d, d, (const T *)nullptr, Bf.Vp,
                        (float *)nullptr, H, D.eps, nf);
-    hipLaunchKernelGGL(bw_attn_fwd_kernel, dim3(BH, N), dim3(64), 0, st, Bf.Qn, Bf.Ktn, Bf.Vt, Bf.Kp, Bf.Vp, Bf.c, Bf.lse, B, H, D.scale,
-                       D.alibi);
+    if (mm && Bf.flash && getenv("RT_BWD_ALU_ATTENTION") == nullptr) {
+        e = flash_recompute_f32(D, Bf.Qn, Bf.Ktn, Bf.Vt, Bf.Kp, Bf.Vp, Bf.c, Bf.lse, Bf.flash, st);
+        if (e != hipSuccess) return e;
+    } else {
+        hipLaunchKernelGGL(bw_attn_fwd_kernel, dim3(BH, N), dim3(64), 0, st, Bf.Qn, Bf.Ktn, Bf.Vt, Bf.Kp, Bf.Vp, Bf.c, Bf.lse, B, H, D.scale,
+                           D.alibi);
+    }
     act_times_w(Bf.c, W.Wo, Bf.Wo_f, Bf.a, (size_t)d, d);
     hipLaunchKernelGGL(bw_rows_norm_kernel<T>, dim3(M), blk, 0, st, x, Bf.a, D.alpha, g_mlp, Bf.unit_h, Bf.hg, Bf.rinv_h, B, N, d, D.eps,
                        nf);

@@ -273,6 +273,13 @@ hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S
 hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Sblk, void *y, void *K, void *V,
                          void *par, hipStream_t st);
 
+// The attention of every position from fp32 rows (the backward pass's recompute, Sec. 6.1) as the same masked pass on the
+// matrix cores: Qn, Ktn, Vt, Kp, Vp [N][B H][64] fp32 (queries, temporary pairs, persistent pairs) -> c [N][B H][64] and the
+// log-sum-exp of every query's logits lse [N][B H].  Keys enter as bf16 head + remainder, values as bf16.
+size_t flash_recompute_scratch_bytes(size_t B, size_t N, size_t d, size_t H);
+hipError_t flash_recompute_f32(const LayerDims &D, const float *Qn, const float *Ktn, const float *Vt, const float *Kp, const float *Vp,
+                               float *c, float *lse, void *scratch, hipStream_t st);
+
 // embedding lookup and final-norm + output projection of a layer stack (rt_stack.hip)
 template <typename T>
 hipError_t embed_rows_launch(const void *table, const int32_t *ids, void *x, int B, int N, int d, int vocab,

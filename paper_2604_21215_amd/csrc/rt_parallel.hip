@@ -554,16 +554,20 @@ __global__ __launch_bounds__(64) void par_merge_kernel(const bf16_t *__restrict_
 // 8 the workgroups are numbered so that all query tiles of one (b, h) run on the same XCD one after the other (their
 // keys and values then come out of that XCD's L2), the longest first.
 // ---------------------------------------------------------------------------------------------
-template <bool ALIBI>
+// F32OUT (the backward pass's recompute): the result goes out as fp32 rows c_out[(i B H + bh) 64 ..] together with the
+// log-sum-exp of the query's logits (natural log), lse_out[i B H + bh], instead of bf16 rows of a_out.
+template <bool ALIBI, bool F32OUT = false>
 __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict__ Qf, const float *__restrict__ Ktf,
                                                         const bf16_t *__restrict__ Vt, const bf16_t *__restrict__ K,
                                                         const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT,
                                                         int vt_stride, bf16_t *__restrict__ a_out, int BH, int H, int N,
-                                                        int ntiles, float scale, float alibi)
+                                                        int ntiles, float scale, float alibi, float *__restrict__ c_out = nullptr,
+                                                        float *__restrict__ lse_out = nullptr, const bf16_t *__restrict__ VTlo = nullptr,
+                                                        const float *__restrict__ Vt32 = nullptr)
 {
     extern __shared__ __align__(16) unsigned char flash_lds[];
     constexpr int T = 256, PPT = 2;
-    constexpr int TILE = kKC * kTileLd, BUF = 3 * TILE;
+    constexpr int TILE = kKC * kTileLd, BUF = (F32OUT ? 4 : 3) * TILE;   // F32OUT: a fourth tile, the remainder of V^T
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     int bh, qt;
@@ -618,6 +622,11 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
         for (int dt = 0; dt < 2; ++dt)
 #pragma unroll
             for (int j = 0; j < 4; ++j) {
+                if (F32OUT) {   // the temporary value unrounded
+                    const float4 v4 = *reinterpret_cast<const float4 *>(Vt32 + qo + 32 * dt + 8 * j + 4 * hi);
+                    O[dt][4 * j] = v4.x; O[dt][4 * j + 1] = v4.y; O[dt][4 * j + 2] = v4.z; O[dt][4 * j + 3] = v4.w;
+                    continue;
+                }
                 const uint2 v = *reinterpret_cast<const uint2 *>(Vt + qo + 32 * dt + 8 * j + 4 * hi);
                 O[dt][4 * j] = __uint_as_float(v.x << 16);
                 O[dt][4 * j + 1] = __uint_as_float(v.x & 0xFFFF0000u);
@@ -629,9 +638,10 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
 
     // ---- staging of one chunk: thread -> 16-byte piece, 8 consecutive threads cover one row; key rows past the last
     // position are read from the last one (they are masked), V^T columns up to vt_stride exist and hold finite values
-    u32x4_t rk[PPT], rl[PPT], rv[PPT];
+    u32x4_t rk[PPT], rl[PPT], rv[PPT], rv2[PPT];
     const int prow = tid >> 3, pc16 = tid & 7;
     const bf16_t *gv = VT + ((size_t)bh * kHeadDim + prow) * vt_stride + pc16 * 8;
+    const bf16_t *gv2 = F32OUT ? VTlo + ((size_t)bh * kHeadDim + prow) * vt_stride + pc16 * 8 : nullptr;
     const int lds_off = prow * kTileLd + pc16 * 8, lds_off_v = prow * kVLd + pc16 * 8;
 #define RT_FL_FETCH(kc)                                                                                               \
     _Pragma("unroll") for (int i = 0; i < PPT; ++i)                                                                   \
@@ -640,6 +650,7 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
         rk[i] = *reinterpret_cast<const u32x4_t *>(K + ro);                                                           \
         rl[i] = *reinterpret_cast<const u32x4_t *>(Klo + ro);                                                         \
         rv[i] = *reinterpret_cast<const u32x4_t *>(gv + (size_t)(i * (T / 8)) * vt_stride + (kc));                    \
+        if (F32OUT) rv2[i] = *reinterpret_cast<const u32x4_t *>(gv2 + (size_t)(i * (T / 8)) * vt_stride + (kc));      \
     }
 #define RT_FL_STAGE(buf)                                                                                              \
     _Pragma("unroll") for (int i = 0; i < PPT; ++i)                                                                   \
@@ -650,6 +661,11 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
         *reinterpret_cast<uint2 *>(dv) = make_uint2(rv[i][0], rv[i][1]);                                              \
         *reinterpret_cast<uint2 *>(dv + 4) = make_uint2(rv[i][2], rv[i][3]);                                          \
         *reinterpret_cast<u32x4_t *>(dst + 2 * TILE) = rl[i];                                                         \
+        if (F32OUT) {                                                                                                 \
+            bf16_t *dv2 = tiles + (size_t)(buf) * BUF + 3 * TILE + lds_off_v + i * (T / 8) * kVLd;                    \
+            *reinterpret_cast<uint2 *>(dv2) = make_uint2(rv2[i][0], rv2[i][1]);                                       \
+            *reinterpret_cast<uint2 *>(dv2 + 4) = make_uint2(rv2[i][2], rv2[i][3]);                                   \
+        }                                                                                                             \
     }
 
     const int kend = min(qt * 128 + 128, N);        // keys 0 .. kend - 2 are needed by some query of the tile
@@ -717,7 +733,7 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
 #pragma unroll
                 for (int dt = 0; dt < 2; ++dt) O[dt] *= resc;
             }
-            uint4 bp[4];
+            uint4 bp[4], bpl[4];
 #pragma unroll
             for (int s4 = 0; s4 < 4; ++s4) {
                 float pw[8];
@@ -725,6 +741,14 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
                 for (int e = 0; e < 8; ++e) pw[e] = __builtin_amdgcn_exp2f(S[s4 >> 1][8 * (s4 & 1) + e] - m2);
                 bp[s4] = make_uint4(cvt_pk_bf16(pw[0], pw[1]), cvt_pk_bf16(pw[2], pw[3]), cvt_pk_bf16(pw[4], pw[5]), cvt_pk_bf16(pw[6], pw[7]));
                 lsum += ((pw[0] + pw[1]) + (pw[2] + pw[3])) + ((pw[4] + pw[5]) + (pw[6] + pw[7]));
+                if (F32OUT) {   // what the bf16 weights lost: the weights and the values both enter as head + remainder
+                    const uint32_t hw[4] = {bp[s4].x, bp[s4].y, bp[s4].z, bp[s4].w};
+                    uint32_t lw[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        lw[e] = cvt_pk_bf16(pw[2 * e] - __uint_as_float(hw[e] << 16), pw[2 * e + 1] - __uint_as_float(hw[e] & 0xFFFF0000u));
+                    bpl[s4] = make_uint4(lw[0], lw[1], lw[2], lw[3]);
+                }
             }
 #pragma unroll
             for (int s4 = 0; s4 < 4; ++s4) {
@@ -732,6 +756,12 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
                 for (int dt = 0; dt < 2; ++dt) {
                     const bf16_t *vrow = Vs + (dt * 32 + l32) * kVLd + s4 * 16 + 4 * hi;
                     const uint2 v0 = *reinterpret_cast<const uint2 *>(vrow), v1 = *reinterpret_cast<const uint2 *>(vrow + 8);
+                    if (F32OUT) {   // small terms first
+                        const bf16_t *vrow2 = vrow + 2 * TILE;   // the remainder tile
+                        const uint2 u0 = *reinterpret_cast<const uint2 *>(vrow2), u1 = *reinterpret_cast<const uint2 *>(vrow2 + 8);
+                        O[dt] = mfma32u(make_uint4(u0.x, u0.y, u1.x, u1.y), bp[s4], O[dt]);
+                        O[dt] = mfma32u(make_uint4(v0.x, v0.y, v1.x, v1.y), bpl[s4], O[dt]);
+                    }
                     O[dt] = mfma32u(make_uint4(v0.x, v0.y, v1.x, v1.y), bp[s4], O[dt]);
                 }
             }
@@ -744,6 +774,20 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
 #undef RT_FL_FETCH
 #undef RT_FL_STAGE
 
+    if (F32OUT) {
+        if (active && qpos < N) {
+            const float lt = lsum + __shfl_xor(lsum, 32, 64), inv = 1.f / lt;
+            float *crow = c_out + ((size_t)qpos * BH + bh) * kHeadDim + 4 * hi;
+#pragma unroll
+            for (int dt = 0; dt < 2; ++dt)
+#pragma unroll
+                for (int j = 0; j < 4; ++j)
+                    *reinterpret_cast<float4 *>(crow + dt * 32 + 8 * j) =
+                        make_float4(O[dt][4 * j] * inv, O[dt][4 * j + 1] * inv, O[dt][4 * j + 2] * inv, O[dt][4 * j + 3] * inv);
+            if (hi == 0) lse_out[(size_t)qpos * BH + bh] = m2 * kLn2 + logf(lt);
+        }
+        return;
+    }
     if (active && qpos < N) {
         const float inv = 1.f / (lsum + __shfl_xor(lsum, 32, 64));
         const int b = bh / H, h = bh % H;
@@ -820,6 +864,106 @@ static void block_gemms(const LayerDims &D, const Weights &W, const void *x, voi
     hipLaunchKernelGGL(par_gemm_kernel<PG_W2>, dim3(gm, (unsigned)((d + 127) / 128)), dim3(256), 0, st, u_b, (const bf16_t *)W.W2, M, d,
                        F, Nc, D.N, n0, (const bf16_t *)nullptr, D.eps, D.norm_free, D.alpha, (const bf16_t *)nullptr, h_f,
                        (float *)nullptr, (bf16_t *)y);
+}
+
+// For the backward pass's recompute: the persistent pairs and the temporary values as fp32 rows [N][B H][64] -> the bf16
+// head and remainder of the keys, the bf16 values transposed (columns N .. 64 ceil(N / 64) - 1 zero) and the bf16
+// temporary values, 64 positions of one (b, h) per workgroup.  grid (B*H, ceil(N / 64)), block 256.
+__global__ __launch_bounds__(256) void flash_export_f32_kernel(const float *__restrict__ Kf, const float *__restrict__ Vf,
+                                                               const float *__restrict__ Vtf, bf16_t *__restrict__ K,
+                                                               bf16_t *__restrict__ Klo, bf16_t *__restrict__ VT,
+                                                               bf16_t *__restrict__ VTlo, bf16_t *__restrict__ Vt, int vt_stride,
+                                                               int BH, int N)
+{
+    constexpr int kLd = 72;
+    __shared__ __align__(16) bf16_t tile[2 * 64 * kLd];   // head and remainder of the values
+    const int tid = threadIdx.x, r = tid >> 2, c = tid & 3, bh = blockIdx.x, t0 = blockIdx.y * 64;
+    const int t = t0 + r;
+    uint32_t vb[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u}, vl[8] = {0u, 0u, 0u, 0u, 0u, 0u, 0u, 0u};
+    if (t < N) {
+        const size_t off = ((size_t)t * BH + bh) * kHeadDim + 16 * c;
+        float kf[16], vf[16], tf[16];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const float4 a = *reinterpret_cast<const float4 *>(Kf + off + 4 * j), b = *reinterpret_cast<const float4 *>(Vf + off + 4 * j),
+                         e = *reinterpret_cast<const float4 *>(Vtf + off + 4 * j);
+            kf[4 * j] = a.x; kf[4 * j + 1] = a.y; kf[4 * j + 2] = a.z; kf[4 * j + 3] = a.w;
+            vf[4 * j] = b.x; vf[4 * j + 1] = b.y; vf[4 * j + 2] = b.z; vf[4 * j + 3] = b.w;
+            tf[4 * j] = e.x; tf[4 * j + 1] = e.y; tf[4 * j + 2] = e.z; tf[4 * j + 3] = e.w;
+        }
+        uint32_t kh[8], kl[8], tb[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            kh[j] = pack_bf16(kf[2 * j], kf[2 * j + 1]);
+            kl[j] = pack_bf16(kf[2 * j] - __uint_as_float(kh[j] << 16), kf[2 * j + 1] - __uint_as_float(kh[j] & 0xFFFF0000u));
+            vb[j] = pack_bf16(vf[2 * j], vf[2 * j + 1]);
+            vl[j] = pack_bf16(vf[2 * j] - __uint_as_float(vb[j] << 16), vf[2 * j + 1] - __uint_as_float(vb[j] & 0xFFFF0000u));
+            tb[j] = pack_bf16(tf[2 * j], tf[2 * j + 1]);
+        }
+        *reinterpret_cast<uint4 *>(K + off) = make_uint4(kh[0], kh[1], kh[2], kh[3]);
+        *reinterpret_cast<uint4 *>(K + off + 8) = make_uint4(kh[4], kh[5], kh[6], kh[7]);
+        *reinterpret_cast<uint4 *>(Klo + off) = make_uint4(kl[0], kl[1], kl[2], kl[3]);
+        *reinterpret_cast<uint4 *>(Klo + off + 8) = make_uint4(kl[4], kl[5], kl[6], kl[7]);
+        *reinterpret_cast<uint4 *>(Vt + off) = make_uint4(tb[0], tb[1], tb[2], tb[3]);
+        *reinterpret_cast<uint4 *>(Vt + off + 8) = make_uint4(tb[4], tb[5], tb[6], tb[7]);
+    }
+    *reinterpret_cast<uint4 *>(tile + r * kLd + 16 * c) = make_uint4(vb[0], vb[1], vb[2], vb[3]);
+    *reinterpret_cast<uint4 *>(tile + r * kLd + 16 * c + 8) = make_uint4(vb[4], vb[5], vb[6], vb[7]);
+    *reinterpret_cast<uint4 *>(tile + (64 + r) * kLd + 16 * c) = make_uint4(vl[0], vl[1], vl[2], vl[3]);
+    *reinterpret_cast<uint4 *>(tile + (64 + r) * kLd + 16 * c + 8) = make_uint4(vl[4], vl[5], vl[6], vl[7]);
+    __syncthreads();
+#pragma unroll
+    for (int part = 0; part < 2; ++part) {
+        const bf16_t *tp = tile + part * 64 * kLd;
+        uint32_t w[8];
+#pragma unroll
+        for (int j = 0; j < 8; ++j)
+            w[j] = (uint32_t)tp[(16 * c + 2 * j) * kLd + r] | ((uint32_t)tp[(16 * c + 2 * j + 1) * kLd + r] << 16);
+        bf16_t *dst = (part == 0 ? VT : VTlo) + ((size_t)bh * kHeadDim + r) * vt_stride + t0 + 16 * c;
+        *reinterpret_cast<uint4 *>(dst) = make_uint4(w[0], w[1], w[2], w[3]);
+        *reinterpret_cast<uint4 *>(dst + 8) = make_uint4(w[4], w[5], w[6], w[7]);
+    }
+}
+
+size_t flash_recompute_scratch_bytes(size_t B, size_t N, size_t d, size_t H)
+{
+    const size_t M = B * N, vt_stride = (N + 63) / 64 * 64;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    return 3 * up(M * d * 2) + 2 * up(B * H * kHeadDim * vt_stride * 2);
+}
+
+hipError_t flash_recompute_f32(const LayerDims &D, const float *Qn, const float *Ktn, const float *Vt, const float *Kp, const float *Vp,
+                               float *c, float *lse, void *scratch, hipStream_t st)
+{
+    const int B = D.B, N = D.N, BH = B * D.H;
+    const size_t M = (size_t)B * N, vt_stride = ((size_t)N + 63) / 64 * 64;
+    auto up = [](size_t v) { return (v + 255) / 256 * 256; };
+    char *p = (char *)scratch;
+    bf16_t *Kb = (bf16_t *)p; p += up(M * D.d * 2);
+    bf16_t *Klo = (bf16_t *)p; p += up(M * D.d * 2);
+    bf16_t *Vtb = (bf16_t *)p; p += up(M * D.d * 2);
+    bf16_t *VT = (bf16_t *)p; p += up((size_t)BH * kHeadDim * vt_stride * 2);
+    bf16_t *VTlo = (bf16_t *)p;
+    hipLaunchKernelGGL(flash_export_f32_kernel, dim3(BH, (N + 63) / 64), dim3(256), 0, st, Kp, Vp, Vt, Kb, Klo, VT, VTlo, Vtb,
+                       (int)vt_stride, BH, N);
+    const int ntiles = (N + 127) / 128;
+    const size_t lds = 2 * 4 * (size_t)kKC * kTileLd * 2;   // two buffers of four tiles: keys, V^T, key remainder, V^T remainder
+    static bool raised = false;
+    if (!raised) {
+        hipError_t e = hipFuncSetAttribute((const void *)par_flash_kernel<true, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e == hipSuccess)
+            e = hipFuncSetAttribute((const void *)par_flash_kernel<false, true>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        raised = true;
+    }
+    const dim3 grid((unsigned)(ntiles * BH));
+    if (D.alibi > 0.f)
+        hipLaunchKernelGGL((par_flash_kernel<true, true>), grid, dim3(256), lds, st, Qn, Ktn, Vtb, Kb, Klo, VT, (int)vt_stride,
+                           (bf16_t *)nullptr, BH, D.H, N, ntiles, D.scale, D.alibi, c, lse, VTlo, Vt);
+    else
+        hipLaunchKernelGGL((par_flash_kernel<false, true>), grid, dim3(256), lds, st, Qn, Ktn, Vtb, Kb, Klo, VT, (int)vt_stride,
+                           (bf16_t *)nullptr, BH, D.H, N, ntiles, D.scale, D.alibi, c, lse, VTlo, Vt);
+    return hipGetLastError();
 }
 
 bool parallel_supported(const LayerDims &D, bool mfma_bf16) { return mfma_bf16 && D.d % 64 == 0 && D.F % 64 == 0; }
