@@ -22,6 +22,14 @@ template <typename T>
 hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x, const void *z, const void *gy, const void *gK,
                           const void *gV, float *dx, const BwGrads &G, void *ws, bool matrix_cores, hipStream_t st,
                           BwpState *loop = nullptr);
+// The attention-shaped passes on the matrix cores (rt_backward_attn.hip; fp32 rows [N][B H][64] in, bf16 head + remainder
+// operands): dq += the keys' share, after the loop; one block of Algorithm 1 backwards, keys [k0, k0 + P) <- queries
+// [q0, q0 + nq).  bw_attn_mfma_init once per process before the first of them.
+hipError_t bw_attn_mfma_init();
+hipError_t bw_dq_mfma(const LayerDims &D, const float *Qn, const float *Kp, const float *Vp, const float *dc, const float *lse,
+                      const float *Ds, float *dq, hipStream_t st);
+hipError_t bw_event_mfma(const LayerDims &D, const float *Qn, const float *Kp, const float *Vp, const float *dc, const float *lse,
+                         const float *Ds, float *dK, float *dV, int k0, int P, int q0, int nq, hipStream_t st);
 // where the exchange words of the single-launch loop lie inside a scratch area laid out for B x N positions
 void backward_exchange_region(size_t B, size_t N, size_t d, size_t F, size_t H, size_t E, size_t *offset, size_t *bytes);
 

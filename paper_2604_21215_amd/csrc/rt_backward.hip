@@ -1016,7 +1016,16 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
     hipLaunchKernelGGL(bw_head_norm_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.kv, 2 * d, 0, g_k, Bf.Kp, Bf.rk, H, D.eps, nf);
     hipLaunchKernelGGL(bw_head_norm_kernel<T>, dim3(M, H), dim3(64), 0, st, Bf.kv, 2 * d, d, (const T *)nullptr, Bf.Vp,
                        (float *)nullptr, H, D.eps, nf);
-    if (mm && Bf.flash && getenv("RT_BWD_ALU_ATTENTION") == nullptr) {
+    const bool mfma_attn = mm && Bf.flash && getenv("RT_BWD_ALU_ATTENTION") == nullptr;
+    if (mfma_attn && (e = bw_attn_mfma_init()) != hipSuccess) return e;
+    // one block of Algorithm 1 backwards: keys [k0, k0 + P) <- queries [q0, q0 + nq)
+    auto run_event = [&](int k0, int P, int q0, int nq) -> hipError_t {
+        if (mfma_attn) return bw_event_mfma(D, Bf.Qn, Bf.Kp, Bf.Vp, Bf.dc, Bf.lse, Bf.Ds, Bf.dK, Bf.dV, k0, P, q0, nq, st);
+        hipLaunchKernelGGL(bw_event_kernel, dim3((unsigned)((P + 63) / 64), BH), blk, kEventLds, st, Bf.Qn, Bf.Kp, Bf.Vp, Bf.dc, Bf.lse,
+                           Bf.Ds, Bf.dK, Bf.dV, B, H, k0, P, q0, nq, D.scale, D.alibi);
+        return hipSuccess;
+    };
+    if (mfma_attn) {
         e = flash_recompute_f32(D, Bf.Qn, Bf.Ktn, Bf.Vt, Bf.Kp, Bf.Vp, Bf.c, Bf.lse, Bf.flash, st);
         if (e != hipSuccess) return e;
     } else {
@@ -1065,8 +1074,7 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
             if (e != hipSuccess) return e;
             if (i_lo > 0) {
                 const int P = i_lo & -i_lo, nq = P < N - i_lo ? P : N - i_lo;
-                hipLaunchKernelGGL(bw_event_kernel, dim3((unsigned)((P + 63) / 64), BH), blk, kEventLds, st, Bf.Qn, Bf.Kp, Bf.Vp, Bf.dc, Bf.lse,
-                                   Bf.Ds, Bf.dK, Bf.dV, B, H, i_lo - P, P, i_lo, nq, D.scale, D.alibi);
+                if ((e = run_event(i_lo - P, P, i_lo, nq)) != hipSuccess) return e;
             }
         }
     }
@@ -1094,15 +1102,18 @@ hipError_t backward_layer(const LayerDims &D, const Weights &W, const void *x_, 
         const int P = i & -i;   // Algorithm 1's block that ends with key i - 1 (0-based): keys [i - P, i), queries [i, i + P)
         if (i > 0 && P >= kBwPmin) {
             const int nq = P < N - i ? P : N - i;
-            hipLaunchKernelGGL(bw_event_kernel, dim3((unsigned)((P + 63) / 64), BH), blk, kEventLds, st, Bf.Qn, Bf.Kp, Bf.Vp, Bf.dc, Bf.lse,
-                               Bf.Ds, Bf.dK, Bf.dV, B, H, i - P, P, i, nq, D.scale, D.alibi);
+            if ((e = run_event(i - P, P, i, nq)) != hipSuccess) return e;
         }
     }
     }
 
     // ---- (C) batched remainder
-    hipLaunchKernelGGL(bw_dq_kernel, dim3((unsigned)((N + 63) / 64), BH), blk, kDqLds, st, Bf.Qn, Bf.Kp, Bf.Vp, Bf.dc, Bf.lse, Bf.Ds, Bf.dq,
-                       B, H, N, D.scale, D.alibi);
+    if (mfma_attn) {
+        if ((e = bw_dq_mfma(D, Bf.Qn, Bf.Kp, Bf.Vp, Bf.dc, Bf.lse, Bf.Ds, Bf.dq, st)) != hipSuccess) return e;
+    } else {
+        hipLaunchKernelGGL(bw_dq_kernel, dim3((unsigned)((N + 63) / 64), BH), blk, kDqLds, st, Bf.Qn, Bf.Kp, Bf.Vp, Bf.dc, Bf.lse, Bf.Ds,
+                           Bf.dq, B, H, N, D.scale, D.alibi);
+    }
     // gain gradients that need the normalised values (before anything is overwritten)
     auto colsum = [&](const float *A, size_t lda, const float *Bm, size_t ldb, float *out, bool acc) {
         hipLaunchKernelGGL(bw_colsum_kernel, dim3((unsigned)((d + 63) / 64)), blk, 0, st, A, lda, Bm, ldb, M, d, out, acc ? 1 : 0);
