@@ -279,23 +279,55 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
     const bool is_merger = att && s == 0 && wave == 0;
 
     RT_DEC_STAMP(0);
-    // ---- the first two chunks of this wavefront: requested before anything else, used after phase Q.  The cache rows
-    // are most of the step's bytes (2 t B d of 2 t B d + 12 d^2); with them in flight from the first instruction the
-    // memory system is busy for the whole first part of the launch and phase Q hides in their shadow.
-    uint4 krA[8], vrA[8], krB[8], vrB[8];
-    int cA = wave * S + s, cB = cA + nworkers;
-    if (att && cA < nch) dec_load_chunk(A.K, A.V, rs, u, cA * 64, min(64, t - cA * 64), krA, vrA);
-    // ================================================================ input rows and the rows of [Wq; Wk; Wv]
-    for (int idx = tid; idx < B * PER; idx += kPThreads) {
-        const int r = idx / PER, c = idx - r * PER;
-        *reinterpret_cast<uint4 *>(act_s + (size_t)r * A.ldw + c * 8) = global_load16(A.x + (size_t)r * d + c * 8);
-    }
+    // ---- One straight run of requests: the input rows and this workgroup's rows of [Wq; Wk; Wv] (what phase Q waits
+    // for), then the first cache chunk of every wavefront (most of the step's bytes are cache rows: 2 t B d of
+    // 2 t B d + 12 d^2; with them in flight from the start the memory system is busy while phase Q runs).  Loads return
+    // to a wavefront in the order it issued them, so the few bytes of phase Q must be asked for first: with the chunk
+    // ahead of them the rows were staged at 7.5 us instead of 3.  A wavefront without a chunk reads row 0 (unused).
+    constexpr int NXB = (kBMax * PER + kPThreads - 1) / kPThreads, NQB = (RQ * PER + kPThreads - 1) / kPThreads;
     const bf16_t *g_in = A.norm_free ? nullptr : A.g_attn;
-    copy_rows_batched<3, PER>(wq_s, A.ldw, RQ, [&](int r) {
+    uint4 xr[NXB], wr[NQB], gr[NQB];
+#pragma unroll
+    for (int j = 0; j < NXB; ++j) {
+        const int idx = j * kPThreads + tid, r = min(idx / PER, B - 1), c = idx % PER;
+        xr[j] = global_load16(A.x + (size_t)r * d + c * 8);
+    }
+#pragma unroll
+    for (int j = 0; j < NQB; ++j) {
+        const int idx = j * kPThreads + tid, r = min(idx / PER, RQ - 1), c = idx % PER;
         const int o = q_lo + r, which = o / d, row = o - which * d;
         const bf16_t *Wm = which == 0 ? A.Wq : (which == 1 ? A.Wk : A.Wv);
-        return RowSrc{Wm + (size_t)row * d, g_in};
-    });
+        wr[j] = global_load16(Wm + (size_t)row * d + c * 8);
+        gr[j] = global_load16((g_in ? g_in : A.Wq) + c * 8);   // unconditional: a branch here would end the run of requests
+    }
+    uint4 krA[8], vrA[8], krB[8], vrB[8];
+    int cA = wave * S + s, cB = cA + nworkers;
+    {
+        const bool hasA = att && cA < nch;
+        dec_load_chunk(A.K, A.V, rs, att ? u : 0, hasA ? cA * 64 : 0, hasA ? min(64, t - cA * 64) : 1, krA, vrA);
+    }
+    // ================================================================ input rows and the rows of [Wq; Wk; Wv] into LDS
+#pragma unroll
+    for (int j = 0; j < NXB; ++j) {
+        const int idx = j * kPThreads + tid, r = idx / PER, c = idx % PER;
+        if (r < B) *reinterpret_cast<uint4 *>(act_s + (size_t)r * A.ldw + c * 8) = xr[j];
+    }
+#pragma unroll
+    for (int j = 0; j < NQB; ++j) {
+        const int idx = j * kPThreads + tid, r = idx / PER, c = idx % PER;
+        if (r >= RQ) continue;
+        uint4 v = wr[j];
+        if (g_in) {
+            float gg[8], ww[8];
+            load8(reinterpret_cast<const bf16_t *>(&gr[j]), gg);
+            load8(reinterpret_cast<const bf16_t *>(&v), ww);
+            v.x = pack_bf16(ww[0] * gg[0], ww[1] * gg[1]);
+            v.y = pack_bf16(ww[2] * gg[2], ww[3] * gg[3]);
+            v.z = pack_bf16(ww[4] * gg[4], ww[5] * gg[5]);
+            v.w = pack_bf16(ww[6] * gg[6], ww[7] * gg[7]);
+        }
+        *reinterpret_cast<uint4 *>(wq_s + (size_t)r * A.ldw + c * 8) = v;
+    }
 
     __syncthreads();
     RT_DEC_STAMP(1);
