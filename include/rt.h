@@ -133,9 +133,10 @@ rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t
  * harnesses that forbid hipMalloc.  No context is needed and nothing is allocated or freed, on the device or through any
  * allocating library routine: the step's scratch (the position's query and temporary pair, one partial softmax state per
  * 64 cached keys, the vectors between the base case's products) is a static device array of RT_STATIC_SCRATCH_BYTES that
- * every device the library runs on holds until the process ends.  Same kernels, same arguments, same results as
- * rt_decode_step on a context created from *cfg (cfg->max_batch and cfg->max_seq still bound B and t; cfg->stream is the
- * stream the step is enqueued on).
+ * every device the library runs on holds until the process ends.  Same arguments as rt_decode_step; the step runs as
+ * eight launches - the kernels, and bit for bit the results, of rt_decode_step on a context created from *cfg with
+ * RT_FLAG_ENGINE_STEPWISE (cfg->max_batch and cfg->max_seq still bound B and t; cfg->stream is the stream the step is
+ * enqueued on).
  *   Limit: the scratch of the call, about B (66 n_heads ceil(t / 64) + 11 d_model + 3 d_hidden) 4 bytes, must fit the
  *   array (d_model 1024, d_hidden 4096, B = 8: t < 16000); a larger call returns RT_ERR_INVALID_ARG and enqueues
  *   nothing.  rt_last_error(NULL) gives the reason of the calling thread's last failed call.
