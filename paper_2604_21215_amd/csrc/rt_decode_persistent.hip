@@ -1,7 +1,7 @@
 // Single-launch decoding step (paper Sec. 7.3: one position of the recurrence of Sec. 2.2 over a cache of persistent
 // pairs), bf16 storage.
 //
-// One cooperative grid of 256 workgroups (one per compute unit) x 512 threads evaluates the whole position:
+// One grid of 256 workgroups (one per compute unit) x 512 threads evaluates the whole position:
 //
 //   Q    raw [q | k_tmp | v_tmp] = [Wq; Wk; Wv]' x_t / rms(x_t): 3d / 256 rows per workgroup                  -> raw q, k, v
 //   A    attention over the cache rows 0 .. t-1: the 64-key chunks of one (b, h) are dealt to the wavefronts of the
@@ -15,8 +15,10 @@
 //
 // The multi-launch step spends most of its time in the start-up and tail of eight dependent kernels that move 2-8 MB
 // each.  Here every byte the step needs - the cache rows (2 t B d elements) and all six matrices (12 d^2) - is requested
-// in the first microseconds of the launch by the workgroup that will use it, none of it depends on a result of
-// the step, and the dependent part that follows is seven exchanges of small vectors.
+// early in the launch by the workgroup that will use it (none of it depends on a result of the step; the order of the
+// requests - phase Q's rows, a first chunk per wavefront, the second chunk, the other weight slices - follows the
+// order of use, because a wavefront gets its loads back in the order it issued them), and the dependent part that
+// follows is seven exchanges of small vectors.
 // RMS gains are folded into the rows as they are copied to LDS (W diag(g), rounded once), as in the prefill engine.
 // Every wait is bounded (spin limit -> abort word -> every workgroup leaves).
 #include "rt_decode_persistent.h"
@@ -67,59 +69,7 @@ struct DecArgs {
         }                                                                                                               \
     } while (0)
 
-struct RowSrc {
-    const bf16_t *row;    // first of the row's K elements, or null: no such row in this workgroup
-    const bf16_t *gain;   // gain of those K columns, or null
-};
-
-// nrows rows of PER 16-byte pieces each into LDS rows ldw elements apart; src(r) names row r.  NB pieces per thread
-// are requested before the first is stored.
-template <int NB, int PER, typename SRC>
-__device__ __forceinline__ void copy_rows_batched(bf16_t *dst, int ldw, int nrows, SRC src)
-{
-    const int total = nrows * PER;
-    for (int i0 = 0; i0 < total; i0 += NB * kPThreads) {
-        uint4 w[NB], gq[NB];
-        bool on[NB], hg[NB];
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            const int idx = i0 + j * kPThreads + (int)threadIdx.x;
-            on[j] = hg[j] = false;
-            w[j] = gq[j] = make_uint4(0u, 0u, 0u, 0u);
-            if (idx < total) {
-                const int r = idx / PER, c = idx - r * PER;
-                const RowSrc s = src(r);
-                if (s.row) {
-                    on[j] = true;
-                    w[j] = global_load16(s.row + c * 8);
-                    if (s.gain) {
-                        hg[j] = true;
-                        gq[j] = global_load16(s.gain + c * 8);
-                    }
-                }
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < NB; ++j) {
-            if (!on[j]) continue;
-            const int idx = i0 + j * kPThreads + (int)threadIdx.x;
-            const int r = idx / PER, c = idx - r * PER;
-            uint4 v = w[j];
-            if (hg[j]) {
-                float gg[8], ww[8];
-                load8(reinterpret_cast<const bf16_t *>(&gq[j]), gg);
-                load8(reinterpret_cast<const bf16_t *>(&v), ww);
-                v.x = pack_bf16(ww[0] * gg[0], ww[1] * gg[1]);
-                v.y = pack_bf16(ww[2] * gg[2], ww[3] * gg[3]);
-                v.z = pack_bf16(ww[4] * gg[4], ww[5] * gg[5]);
-                v.w = pack_bf16(ww[6] * gg[6], ww[7] * gg[7]);
-            }
-            *reinterpret_cast<uint4 *>(dst + (size_t)r * ldw + c * 8) = v;
-        }
-    }
-}
-
-// The same copy in two halves, so that the rows can be in flight while the wavefront does something else: rows_issue
+// A copy of weight rows into LDS in two halves, so that the rows can be in flight while the wavefront does something else: rows_issue
 // requests this thread's NB pieces (src(r): first element of row r, or null), rows_commit stores them to LDS,
 // multiplied by gain(r) (an LDS row of K gains, or null).
 template <int NB, int PER, typename SRC>
