@@ -123,24 +123,41 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
     const int o_lo = min(wg * A.R_o, d), o_n = min(d, o_lo + A.R_o) - o_lo;          // rows of the d-row matrices
     const int f_lo = min(wg * A.R_1, F), f_n = min(F, f_lo + A.R_1) - f_lo;          // rows of W2^T
     const int rb = wg >> 2, jb = wg & 3, RB = A.R_2;                                  // W1^T: row block x contraction block
-    copy_rows_to_lds(wk_s, A.ldw, A.WkvT, 2 * d, 0, d, o_lo, o_n);
-    copy_rows_to_lds(wv_s, A.ldw, A.WkvT, 2 * d, d, d, o_lo, o_n);
-    copy_rows_to_lds(wo_s, A.ldw, A.WoT, d, 0, d, o_lo, o_n);
-    copy_rows_to_lds(w2_s, A.ldw, A.W2T, d, 0, d, f_lo, f_n);
-    copy_rows_to_lds(w1_s, A.ldw, A.W1T, F, jb * d, d, rb * RB, RB);
+    {   // the five slices are contiguous in LDS: one run of requests (a launch covers only 32 positions, so its start-up counts)
+        constexpr int PERW = 32 * KSD;   // 16-byte pieces of a d-long row
+        constexpr int WROWS = 3 * RO + R1 + 4 * KSD, NBW = (WROWS * PERW + kPThreads - 1) / kPThreads;
+        const int n1 = A.R_o, n2 = 2 * A.R_o, n3 = 3 * A.R_o, n4 = n3 + A.R_1, n5 = n4 + A.R_2;
+        uint4 wreg[NBW];
+        rows_issue<NBW, PERW>(wreg, n5, [&](int r) -> const bf16_t * {
+            if (r < n1) return r < o_n ? A.WkvT + (size_t)(o_lo + r) * 2 * d : nullptr;
+            if (r < n2) return r - n1 < o_n ? A.WkvT + (size_t)(o_lo + r - n1) * 2 * d + d : nullptr;
+            if (r < n3) return r - n2 < o_n ? A.WoT + (size_t)(o_lo + r - n2) * d : nullptr;
+            if (r < n4) return r - n3 < f_n ? A.W2T + (size_t)(f_lo + r - n3) * d : nullptr;
+            return A.W1T + (size_t)(rb * RB + r - n4) * F + (size_t)jb * d;
+        });
+        rows_commit<NBW, PERW>(wreg, wk_s, A.ldw, n5, [](int) -> const bf16_t * { return nullptr; });
+    }
 
     const size_t rs = (size_t)BH * kHeadDim;   // = B d: one position of a position-first tensor
     const int blk_lo = A.i_lo;                 // first position of the block
     const int my_u = wg;                       // the (b, h) of wavefront 0 of workgroups 0 .. BH - 1
     const bool has_u = wave == 0 && my_u < BH;
-    if (has_u) {   // the block's keys, values and gradient accumulators of this (b, h)
-        for (int j = 0; j < kBwpBlock; ++j) {
-            const int pos = min(blk_lo + j, A.N - 1);
+    if (my_u < BH) {   // the block's keys, values and gradient accumulators of this (b, h): every wavefront four rows, all
+                       // sixteen loads of a wavefront in flight at once
+        float kv4[kBwpBlock / kPW][4];
+#pragma unroll
+        for (int jj = 0; jj < kBwpBlock / kPW; ++jj) {
+            const int pos = min(blk_lo + wave + kPW * jj, A.N - 1);
             const size_t o = (size_t)pos * rs + (size_t)my_u * kHeadDim + lane;
-            winK[j * kWinLd + lane] = A.Kp[o];
-            winV[j * kWinLd + lane] = A.Vp[o];
-            accK[j * kHeadDim + lane] = A.dK[o];
-            accV[j * kHeadDim + lane] = A.dV[o];
+            kv4[jj][0] = A.Kp[o]; kv4[jj][1] = A.Vp[o]; kv4[jj][2] = A.dK[o]; kv4[jj][3] = A.dV[o];
+        }
+#pragma unroll
+        for (int jj = 0; jj < kBwpBlock / kPW; ++jj) {
+            const int j = wave + kPW * jj;
+            winK[j * kWinLd + lane] = kv4[jj][0];
+            winV[j * kWinLd + lane] = kv4[jj][1];
+            accK[j * kHeadDim + lane] = kv4[jj][2];
+            accV[j * kHeadDim + lane] = kv4[jj][3];
         }
     }
     __syncthreads();

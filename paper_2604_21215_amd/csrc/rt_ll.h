@@ -289,6 +289,48 @@ __device__ __forceinline__ void copy_rows_to_lds(bf16_t *dst, int ldw, const bf1
     }
 }
 
+// A copy of weight rows (PER 16-byte pieces each) into LDS in two halves, so that all of a thread's pieces are in flight
+// at once and the wavefront can do something else meanwhile: rows_issue requests this thread's NB pieces (src(r): first
+// element of row r, or null), rows_commit stores them to LDS rows ldw elements apart, multiplied by gain(r) (an LDS
+// row of gains, or null).  NB * kPThreads >= nrows * PER.
+template <int NB, int PER, typename SRC>
+__device__ __forceinline__ void rows_issue(uint4 (&w)[NB], int nrows, SRC src)
+{
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int idx = j * kPThreads + (int)threadIdx.x;
+        w[j] = make_uint4(0u, 0u, 0u, 0u);
+        if (idx < nrows * PER) {
+            const int r = idx / PER, c = idx - r * PER;
+            const bf16_t *row = src(r);
+            if (row) w[j] = global_load16(row + c * 8);
+        }
+    }
+}
+template <int NB, int PER, typename GAIN>
+__device__ __forceinline__ void rows_commit(const uint4 (&w)[NB], bf16_t *dst, int ldw, int nrows, GAIN gain)
+{
+#pragma unroll
+    for (int j = 0; j < NB; ++j) {
+        const int idx = j * kPThreads + (int)threadIdx.x;
+        if (idx >= nrows * PER) continue;
+        const int r = idx / PER, c = idx - r * PER;
+        uint4 v = w[j];
+        const bf16_t *g = gain(r);
+        if (g) {
+            const uint4 gq = lds_load16(g + c * 8);
+            float gg[8], ww[8];
+            load8(reinterpret_cast<const bf16_t *>(&gq), gg);
+            load8(reinterpret_cast<const bf16_t *>(&v), ww);
+            v.x = pack_bf16(ww[0] * gg[0], ww[1] * gg[1]);
+            v.y = pack_bf16(ww[2] * gg[2], ww[3] * gg[3]);
+            v.z = pack_bf16(ww[4] * gg[4], ww[5] * gg[5]);
+            v.w = pack_bf16(ww[6] * gg[6], ww[7] * gg[7]);
+        }
+        *reinterpret_cast<uint4 *>(dst + (size_t)r * ldw + c * 8) = v;
+    }
+}
+
 // Bounded poll of NW words per lane.  Every round re-issues all words that are still stale together and checks
 // them together, so a round costs one trip to memory however many words are late (re-polling them one after the
 // other cost one trip per late word: measured 2.3 us for the two words of a new key-value pair).
