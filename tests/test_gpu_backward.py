@@ -116,3 +116,14 @@ def test_backward_bf16_from_the_gpu_forward(oracle):
     """Forward on the GPU (rt_layer_prefill, bf16), backward from ITS output: the pipeline a training step runs.  The
     reference differentiates at the exact output, so the difference includes the forward's own error."""
     _run(oracle, "bf16", 4, 160, 256, 4, 1024, scale=0.125, alpha=0.7, z_from_gpu=True)
+
+
+@pytest.mark.parametrize("kw", [
+    dict(alibi=8.0, scale=0.3),                                   # positional bias in the matrix-core attention passes and the loop
+    dict(norm_free=True, scale=0.02),                             # every normalisation the identity
+    dict(shared_kv_gain=True, with_pair_grads=False, scale=0.5),  # RMS(z) sharing g_attn; no gradient arriving at K, V
+])
+def test_backward_bf16_variants(oracle, kw):
+    """The single-launch reverse loop and the matrix-core attention passes (bf16 storage, d a multiple of 256) with the
+    options the plain cases leave at their defaults; 170 positions: blocks of 32, 64 and 128 keys and a ragged last block."""
+    _run(oracle, "bf16", 3, 170, 256, 4, 1024, alpha=0.8, **kw)

@@ -93,3 +93,8 @@ def test_decode_many_chunks_per_wavefront(oracle, monkeypatch):
     # wavefront's two chunk buffers runs, some wavefronts end on the first buffer and some on the second
     monkeypatch.setenv("RT_DECODE_SPLIT", "1")
     _decode_case(oracle, 3, 1450, 256, 4, n0=1444, steps=list(range(1444, 1450)), seed=39, scale=0.5)
+
+
+def test_decode_largest_layout(oracle):
+    # B H = 256 at d = 1024: one workgroup per (b, h), sixteen staged rows - the largest LDS layout the kernel has
+    _decode_case(oracle, 16, 75, 1024, 16, n0=70, steps=list(range(70, 75)), seed=40, gains="unit")
