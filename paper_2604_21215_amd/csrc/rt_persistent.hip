@@ -372,13 +372,34 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 const size_t off = (size_t)(t - 1) * rs + (size_t)u * kHeadDim + lane;
                 A.K[off] = kb;
                 A.V[off] = vb;
-                A.VT[((size_t)u * kHeadDim + lane) * A.vt_stride + (t - 1)] = vb;
+                if (!A.win_rows) A.VT[((size_t)u * kHeadDim + lane) * A.vt_stride + (t - 1)] = vb;   // else: from the ring, below
                 A.Klo[off] = f32_to_bf16(kr - bf16_to_f32(kb));   // what the stored bf16 key lost; the 32-key tiles add it back
                 A.Kh[off] = f32_to_f16_bits(kr);
                 if (A.win_rows) {   // ring slot of key t-1; only this wavefront reads it back
-                    const size_t slot = (size_t)(u / G) * A.win_rows + ((t - 1) & (A.win_rows - 1));
+                    const size_t ring = (size_t)(u / G) * A.win_rows;
+                    const size_t slot = ring + ((t - 1) & (A.win_rows - 1));
                     win_k[slot * (kHeadDim + 4) + lane] = kr;
                     win_v[slot * kHeadDim + lane] = vb;
+                    // The transposed value copy is written from the ring: 32 positions of a head dimension at a time (one
+                    // 64-byte run per lane) when key t-1 completes a group of 32 - before any tile reads them, the first
+                    // block that contains key t-1 closes at t - and the last, incomplete group two bytes at a time at the
+                    // end.  (One 2-byte store per lane and position cost a 64-byte write each: 0.93 GB of the 3.28 GB this
+                    // kernel wrote per cfg3 call, measured with the stores taken out.)
+                    if ((t & 31) == 0) {
+                        uint32_t w[16];
+#pragma unroll
+                        for (int j = 0; j < 16; ++j) {
+                            const size_t s0 = ring + ((t - 32 + 2 * j) & (A.win_rows - 1)), s1 = ring + ((t - 31 + 2 * j) & (A.win_rows - 1));
+                            w[j] = (uint32_t)win_v[s0 * kHeadDim + lane] | ((uint32_t)win_v[s1 * kHeadDim + lane] << 16);
+                        }
+                        bf16_t *dst = A.VT + ((size_t)u * kHeadDim + lane) * A.vt_stride + (t - 32);
+#pragma unroll
+                        for (int j = 0; j < 4; ++j)
+                            *reinterpret_cast<uint4 *>(dst + 8 * j) = make_uint4(w[4 * j], w[4 * j + 1], w[4 * j + 2], w[4 * j + 3]);
+                    } else if (t == A.N) {
+                        for (int k = t & ~31; k < t; ++k)
+                            A.VT[((size_t)u * kHeadDim + lane) * A.vt_stride + k] = win_v[(ring + (k & (A.win_rows - 1))) * kHeadDim + lane];
+                    }
                 }
                 if (t < A.N) {
                     // the newest key is one position before the query
