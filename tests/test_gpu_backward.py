@@ -127,3 +127,8 @@ def test_backward_bf16_variants(oracle, kw):
     """The single-launch reverse loop and the matrix-core attention passes (bf16 storage, d a multiple of 256) with the
     options the plain cases leave at their defaults; 170 positions: blocks of 32, 64 and 128 keys and a ragged last block."""
     _run(oracle, "bf16", 3, 170, 256, 4, 1024, alpha=0.8, **kw)
+
+
+def test_backward_bf16_full_batch_headline_width(oracle):
+    """B = 8 at d = 1024: the largest layout of the single-launch reverse loop (eight staged rows, 16 x 8 merge units)."""
+    _run(oracle, "bf16", 8, 70, 1024, 16, 4096, scale=0.5, alpha=0.7)

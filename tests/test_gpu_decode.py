@@ -46,6 +46,8 @@ def _decode_case(oracle, B, N, d, H, *, n0, steps, seed, gains="random", alpha=1
                 ey = max(ey, rel_err_rows(tio.to_host(y_t), ref[0][:, t]).max())
                 ek = max(ek, rel_err_rows(tio.to_host(K[t]), ref[1][t]).max())
                 ev = max(ev, rel_err_rows(tio.to_host(V[t]), ref[2][t]).max())
+            if steps[-1] + 1 < N:   # cache rows after the last decoded position are untouched
+                assert float(K[steps[-1] + 1:].abs().max()) == 0.0 and float(V[steps[-1] + 1:].abs().max()) == 0.0
             worst[name] = (ey, ek, ev)
         finally:
             ctx.rt_destroy()
@@ -85,7 +87,7 @@ def test_decode_alibi_and_norm_free(oracle):
 
 
 def test_decode_smaller_batch_than_context(oracle):
-    _decode_case(oracle, 2, 140, 512, 8, n0=130, steps=list(range(130, 140)), seed=38, max_batch=8)
+    _decode_case(oracle, 2, 150, 512, 8, n0=130, steps=list(range(130, 140)), seed=38, max_batch=8)   # rows 140 .. 149 stay untouched
 
 
 def test_decode_many_chunks_per_wavefront(oracle, monkeypatch):
