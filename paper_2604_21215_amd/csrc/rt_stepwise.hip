@@ -5,6 +5,7 @@
 // cross-block update.  The MFMA kernels live in rt_mfma.hip, the single-launch engine in
 // rt_persistent.hip.
 #include "rt_base_case.h"
+#include "rt_ll.h"
 
 namespace rt {
 
@@ -58,8 +59,8 @@ __global__ __launch_bounds__(64) void decode_split_kernel(const T *__restrict__ 
 // walks the value rows eight at a time behind the softmax: nine dependent round trips; here the split's 8 KB of keys and
 // 8 KB of values are requested before anything is computed).  Keys and values alike: piece i of a lane is row
 // 8 i + lane / 8, columns 8 (lane % 8) .. + 7 (eight lanes cover one 128-byte row); the logits are summed over the
-// eight lanes of a row and moved to lane = key, the weights reach the value rows by a shuffle and the eight lanes
-// that share columns are summed at the end.  Rows past the split's end are read from its last row with weight zero.
+// eight lanes of a row and stay there (the value rows have the same layout), and the eight lanes that share columns
+// are summed at the end.  Rows past the split's end are read from its last row with weight zero.
 // One split per wavefront: grid (ceil(nsplit / 4), B*H), block 256.
 __global__ __launch_bounds__(256) void decode_split64_bf16_kernel(const bf16_t *__restrict__ Q, const bf16_t *__restrict__ K,
                                                                  const bf16_t *__restrict__ V, float *__restrict__ pm,
@@ -82,9 +83,12 @@ __global__ __launch_bounds__(256) void decode_split64_bf16_kernel(const bf16_t *
     float q8[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) q8[e] = __shfl(qv, (lane & 7) * 8 + e, 64);
-    // the dot product of row 8 i + lane / 8 over this lane's eight columns, summed over the eight lanes of the row; the
-    // logit of key j is then moved to lane j (it sits, complete, in the lanes 8 (j % 8) .. + 7 of piece j / 8)
-    float acc = 0.f;
+    // the dot product of row 8 i + lane / 8 over this lane's eight columns, summed over the eight lanes of the row inside
+    // the lanes' row of sixteen (no LDS crossbar): every lane of a row holds its logit, and its weight is computed there
+    const float slope = alibi_slope(alibi, bh % H, H);
+    const int r8 = lane >> 3;
+    float sc[8];
+    float mx = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
         const uint32_t w[4] = {kr[i].x, kr[i].y, kr[i].z, kr[i].w};
@@ -94,22 +98,20 @@ __global__ __launch_bounds__(256) void decode_split64_bf16_kernel(const bf16_t *
             d = fmaf(q8[2 * e], __uint_as_float(w[e] << 16), d);
             d = fmaf(q8[2 * e + 1], __uint_as_float(w[e] & 0xFFFF0000u), d);
         }
-        d += __shfl_xor(d, 1, 64);
-        d += __shfl_xor(d, 2, 64);
-        d += __shfl_xor(d, 4, 64);
-        const float mine = __shfl(d, (lane & 7) * 8, 64);   // row 8 i + lane % 8
-        if ((lane >> 3) == i) acc = mine;
+        d += dpp_f(d, 0);
+        d += dpp_f(d, 1);
+        d += dpp_f(d, 2);
+        const int j = 8 * i + r8;
+        sc[i] = j < cnt ? fmaf(-slope, (float)(t - k_lo - j), d * scale) : -INFINITY;
+        mx = fmaxf(mx, sc[i]);
     }
-    const bool valid = lane < cnt;
-    const float slope = alibi_slope(alibi, bh % H, H);
-    const float logit = valid ? fmaf(-slope, (float)(t - k_lo - lane), acc * scale) : -INFINITY;
-    const float m = wave_max(logit);
-    const float p = valid ? expf(logit - m) : 0.f;
-    const float l = wave_sum(p);
+    const float m = fast_max(mx);
+    float psum = 0.f;
     float o8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-        const float pr = __shfl(p, 8 * i + (lane >> 3), 64);
+        const float pr = __expf(sc[i] - m);   // exp(-inf) = 0 for rows past the end
+        psum += pr;
         const uint32_t w[4] = {vr[i].x, vr[i].y, vr[i].z, vr[i].w};
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
@@ -117,6 +119,7 @@ __global__ __launch_bounds__(256) void decode_split64_bf16_kernel(const bf16_t *
             o8[2 * e + 1] = fmaf(pr, __uint_as_float(w[e] & 0xFFFF0000u), o8[2 * e + 1]);
         }
     }
+    const float l = fast_sum(psum) * 0.125f;   // every weight was counted by the eight lanes of its row
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         o8[e] += __shfl_xor(o8[e], 8, 64);
