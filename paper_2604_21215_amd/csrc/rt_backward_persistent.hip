@@ -64,12 +64,17 @@ struct BwpArgs {
     int pre_sleep;
 };
 
-#define RT_BWP_ABORT_IF(cond)                                                                                              \
-    do {                                                                                                                   \
-        if (__syncthreads_or(cond)) {                                                                                      \
-            if (threadIdx.x == 0) __hip_atomic_store(A.bar + 8, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);        \
-            return;                                                                                                        \
-        }                                                                                                                  \
+// Workgroup barrier behind which every wavefront leaves when any of them has given up waiting: that wavefront raises an LDS
+// flag before the barrier, all read it behind the barrier (it is never lowered again).  One barrier and one LDS read instead
+// of a workgroup-wide reduction of the predicate (two barriers and LDS atomics).
+#define RT_BWP_ABORT_IF(cond)                                                                                           \
+    do {                                                                                                                \
+        if (cond) gave_up_s = 1;                                                                                        \
+        __syncthreads();                                                                                                \
+        if (gave_up_s != 0) {                                                                                           \
+            if (threadIdx.x == 0) __hip_atomic_store(A.bar + 8, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     \
+            return;                                                                                                     \
+        }                                                                                                               \
     } while (0)
 
 // <unit row, staged bf16 vector> of batch row `wave` (B <= 8: one wavefront per batch row), u16 = this lane's 16
@@ -93,6 +98,8 @@ template <int KSD>
 __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int gave_up_s;   // raised by a wavefront whose bounded wait ran out; the first barrier below precedes its first use
+    if (threadIdx.x == 0) gave_up_s = 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wg = blockIdx.x, G = A.G;
     const int d = A.d, F = A.F, B = A.B, BH = A.BH, H = A.H;
@@ -452,7 +459,7 @@ bool bwp_create(BwpState &P, int device, int d, int F, int H, int max_batch, boo
     rows_per_wg(d, F, G, &R_o, &R_1);
     if (R_o > kRMax || R_1 > kRMax || d / 64 > kRMax) return false;
     const size_t lds = lds_bytes(d, F, G);
-    if (lds > (size_t)160 * 1024) return false;
+    if (lds + 16 > (size_t)160 * 1024) return false;   // 16: the statically allocated flag word
     if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return false;

@@ -61,9 +61,14 @@ struct DecArgs {
         if (A.trace && threadIdx.x == 0) A.trace[(size_t)blockIdx.x * 16 + (k)] = wall_clock64(); \
     } while (0)
 
+// Workgroup barrier behind which every wavefront leaves when any of them has given up waiting: that wavefront raises an LDS
+// flag before the barrier, all read it behind the barrier (it is never lowered again).  One barrier and one LDS read instead
+// of a workgroup-wide reduction of the predicate (two barriers and LDS atomics).
 #define RT_DEC_ABORT_IF(cond)                                                                                           \
     do {                                                                                                                \
-        if (__syncthreads_or(cond)) {                                                                                   \
+        if (cond) gave_up_s = 1;                                                                                        \
+        __syncthreads();                                                                                                \
+        if (gave_up_s != 0) {                                                                                           \
             if (threadIdx.x == 0) __hip_atomic_store(A.bar + 8, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);     \
             return;                                                                                                     \
         }                                                                                                               \
@@ -150,6 +155,8 @@ template <int KSD>
 __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
 {
     extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int gave_up_s;   // raised by a wavefront whose bounded wait ran out; the first barrier below precedes its first use
+    if (threadIdx.x == 0) gave_up_s = 0;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wg = blockIdx.x, G = A.G;
     const int d = A.d, F = A.F, B = A.B, BH = A.BH, H = A.H, t = A.t;
@@ -589,7 +596,7 @@ rt_status decode_coop_create(DecodeCoopState &P, const rt_config &cfg, const Lay
     const Rows r = rows_for(D.d, D.F, G);
     if (r.R_q > kRMax || r.R_o > kRMax || r.R_1 > kRMax || r.R_kv > kRMax || r.R_2 > kRMax) return RT_ERR_UNSUPPORTED;
     const size_t lds = lds_bytes_for(D.d, D.F, G, P.max_batch);
-    if (lds > (size_t)160 * 1024) return RT_ERR_UNSUPPORTED;
+    if (lds + 16 > (size_t)160 * 1024) return RT_ERR_UNSUPPORTED;   // 16: the statically allocated flag word
     if (hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) {
         (void)hipGetLastError();
         return RT_ERR_UNSUPPORTED;

@@ -362,5 +362,4 @@ __device__ __forceinline__ void ll_wait_n(const ll_t *const (&p)[NW], const bool
     }
 }
 
-
 }  // namespace rt

@@ -136,9 +136,15 @@ __device__ __forceinline__ void attend_lds(float q, const float *ks, const bf16_
             A.trace[((size_t)(wg == 0 ? 0 : A.trace_rows) + t) * 16 + (k)] = wall_clock64(); \
     } while (0)
 
+// Workgroup barrier that also makes every wavefront leave when any of them has given up waiting: the wavefront that gave
+// up raises an LDS flag before the barrier, everybody reads it behind the barrier (the flag is never lowered again, so all
+// wavefronts take the same branch).  One barrier and one LDS read: a workgroup-wide reduction of the predicate costs two
+// barriers and LDS atomics, six times per position.
 #define RT_ABORT_IF(cond)                                                                                  \
     do {                                                                                                   \
-        if (__syncthreads_or(cond)) {                                                                      \
+        if (cond) flag_s[1] = 1;                                                                           \
+        __syncthreads();                                                                                   \
+        if (flag_s[1] != 0) {                                                                              \
             if (threadIdx.x == 0) __hip_atomic_store(A.bar + 8, 1ULL, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); \
             return;                                                                                        \
         }                                                                                                  \
@@ -299,6 +305,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             else copy_rows_to_lds(wkv_s + (size_t)r * A.ldw_d, A.ldw_d, A.Wv, d, 0, d, o - d, 1, gkv);
         }
     }
+    if (tid == 0) flag_s[1] = 0;   // "a wavefront of this workgroup gave up waiting"
     __syncthreads();
 
     const size_t rs = (size_t)BH * kHeadDim;
@@ -310,6 +317,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     // this wavefront's merge unit (at most one: B*H <= G*kPW), and its pre-merged state for the next position
     const int my_u = wg + G * wave;
     const bool has_u = my_u < BH;
+    // gain of the key normalisation for this wavefront's head: fetched once, phase M is on the critical path of every position
+    const float my_gk = (has_u && A.g_k) ? bf16_to_f32(A.g_k[(my_u % A.H) * kHeadDim + lane]) : 1.f;
     const float *my_wk = win_k + (size_t)wave * A.win_rows * (kHeadDim + 4);
     const bf16_t *my_wv = win_v + (size_t)wave * A.win_rows * kHeadDim;
     float cq = 0.f, cm = 0.f, cl = 1.f, co = 0.f;
@@ -366,7 +375,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 const float vr = __uint_as_float((unsigned)w6[5]) * rz;
                 if (!A.norm_free) {
                     const float s2 = fast_sum(kr * kr);
-                    kr *= rsqrtf(s2 / (float)kHeadDim + A.eps) * (A.g_k ? bf16_to_f32(A.g_k[h * kHeadDim + lane]) : 1.f);
+                    kr *= rsqrtf(s2 / (float)kHeadDim + A.eps) * my_gk;
                 }
                 const bf16_t kb = f32_to_bf16(kr), vb = f32_to_bf16(vr);
                 const size_t off = (size_t)(t - 1) * rs + (size_t)u * kHeadDim + lane;
@@ -515,17 +524,16 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         wg_gemv_ll<KSD, RO / 2, true>(w1_s, A.ldw_d, f_n, A.h_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail, sq);
         RT_ABORT_IF(fail);
         RT_STAMP(11);
-        if (tid < kBMax) {   // 1/rms(h) from the values this workgroup just received
-            float s = 0.f;
-#pragma unroll
-            for (int w = 0; w < kPW; ++w) s += sq[w * kBMax + tid];
-            rinv_s[tid] = A.norm_free ? 1.f : rsqrtf(s / (float)d + A.eps);
-        }
-        __syncthreads();
         RT_STAMP(12);
         if (tid < kRMax * kBMax) {
             float uv = 0.f;
-            if (erow < f_n && eb < B) uv = gelu_erf(red_sum(red, erow, eb) * rinv_s[eb]);
+            if (erow < f_n && eb < B) {
+                float s = 0.f;   // |h|^2 of batch row eb from the values this workgroup just received, one part per wavefront
+#pragma unroll
+                for (int w = 0; w < kPW; ++w) s += sq[w * kBMax + eb];
+                const float rinv = A.norm_free ? 1.f : rsqrtf(s / (float)d + A.eps);
+                uv = gelu_erf(red_sum(red, erow, eb) * rinv);
+            }
             const float un = __shfl_down(uv, 16, 64);
             if (!(erow & 1) && erow < f_n && eb < B)
                 ll_store(A.u_ll + par * half_F + pair_word<R1 / 2>(f_lo + erow, eb), tag,
