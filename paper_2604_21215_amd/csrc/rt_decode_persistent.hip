@@ -403,16 +403,15 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
     // ================================================================ phase 1:  u = gelu(W1' h / rms(h))
     wg_gemv_ll<KSD, RO / 2, true>(w1_s, A.ldw, f_n, A.h_ll, B, tag, A, red, act_s, A.ldw, fail, sq);
     RT_DEC_ABORT_IF(fail);
-    if (tid < kBMax) {
-        float ssum = 0.f;
-#pragma unroll
-        for (int w = 0; w < kPW; ++w) ssum += sq[w * kBMax + tid];
-        rinv_s[tid] = A.norm_free ? 1.f : rsqrtf(ssum / (float)d + A.eps);
-    }
-    __syncthreads();
     if (tid < kRMax * kBMax) {
         float uv = 0.f;
-        if (erow < f_n && eb < B) uv = gelu_erf(red_sum(red, erow, eb) * rinv_s[eb]);
+        if (erow < f_n && eb < B) {
+            float ssum = 0.f;   // |h|^2 of batch row eb from the values this workgroup just received, one part per wavefront
+#pragma unroll
+            for (int w = 0; w < kPW; ++w) ssum += sq[w * kBMax + eb];
+            const float rinv = A.norm_free ? 1.f : rsqrtf(ssum / (float)d + A.eps);
+            uv = gelu_bf16_out(red_sum(red, erow, eb) * rinv);   // u crosses the chip as bf16
+        }
         const float un = __shfl_down(uv, 16, 64);
         if (!(erow & 1) && erow < f_n && eb < B)
             ll_store(A.u_ll + pair_word<R1 / 2>(f_lo + erow, eb), tag, (unsigned)f32_to_bf16(uv) | ((unsigned)f32_to_bf16(un) << 16));

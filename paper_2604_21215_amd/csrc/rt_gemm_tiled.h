@@ -88,20 +88,4 @@ __device__ __forceinline__ void tiled_mainloop(const bf16_t *const (&ga)[8], con
 #undef RT_GT_STAGE
 }
 
-// erf by the rational form 1 - (1 + a1 x + ... + a6 x^6)^-16 (Abramowitz and Stegun 7.1.28, |error| < 3e-7 before
-// rounding, about 2e-6 evaluated in fp32): for outputs that are rounded to bf16 (2^-9 relative) right afterwards.
-__device__ __forceinline__ float erf_rational(float x)
-{
-    const float ax = fabsf(x);
-    float p = fmaf(ax, 0.0000430638f, 0.0002765672f);
-    p = fmaf(ax, p, 0.0001520143f);
-    p = fmaf(ax, p, 0.0092705272f);
-    p = fmaf(ax, p, 0.0422820123f);
-    p = fmaf(ax, p, 0.0705230784f);
-    p = fmaf(ax, p, 1.0f);
-    p *= p; p *= p; p *= p; p *= p;
-    return copysignf(1.0f - __frcp_rn(p), x);
-}
-__device__ __forceinline__ float gelu_bf16_out(float u) { return 0.5f * u * (1.0f + erf_rational(u * 0.70710678118654752440f)); }
-
 }  // namespace rt

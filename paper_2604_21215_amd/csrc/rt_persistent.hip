@@ -125,7 +125,17 @@ __device__ __forceinline__ void attend_lds(float q, const float *ks, const bf16_
     const float p = valid ? __expf(logit - m_new) : 0.f;
     l = l * resc + fast_sum(p);
     float on = o * resc;
-    for (int j = 0; j < nkeys; ++j) on = fmaf(lane_bcast(p, j), bf16_to_f32(vs[(size_t)j * kHeadDim + lane]), on);
+    // eight value rows are requested before their products (one dependent LDS read per key cost about a microsecond for a full
+    // window); rows past the end are read from the last row with weight zero
+#pragma unroll
+    for (int j0 = 0; j0 < 64; j0 += 8) {
+        if (j0 >= nkeys) break;   // wavefront-uniform
+        float vv[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) vv[e] = bf16_to_f32(vs[(size_t)min(j0 + e, nkeys - 1) * kHeadDim + lane]);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) on = fmaf(lane_bcast(p, j0 + e), vv[e], on);
+    }
     o = on;
     m = m_new;
 }
@@ -532,7 +542,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 #pragma unroll
                 for (int w = 0; w < kPW; ++w) s += sq[w * kBMax + eb];
                 const float rinv = A.norm_free ? 1.f : rsqrtf(s / (float)d + A.eps);
-                uv = gelu_erf(red_sum(red, erow, eb) * rinv);
+                uv = gelu_bf16_out(red_sum(red, erow, eb) * rinv);   // u crosses the chip as bf16
             }
             const float un = __shfl_down(uv, 16, 64);
             if (!(erow & 1) && erow < f_n && eb < B)
