@@ -189,24 +189,25 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
     const bf16_t *arow = act_s + (size_t)l16 * lda + wave * kw + 8 * g;
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-    float ss = 0.f;
+    float ssp[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         Frag a, b;
         a.u = has_w ? lds_load16(wrow + s * 32) : zero;
         b.u = has_a ? lds_load16(arow + s * 32) : zero;
-        if (SS) {
+        acc = mfma16(a, b, acc);
+        if (SS) {   // four independent partial sums: one chain of 16 KS dependent multiply-adds is as long as the product
             const unsigned w4[4] = {b.u.x, b.u.y, b.u.z, b.u.w};
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
                 const float lo = __uint_as_float(w4[h] << 16), hi = __uint_as_float(w4[h] & 0xFFFF0000u);
-                ss = fmaf(lo, lo, ss);
-                ss = fmaf(hi, hi, ss);
+                ssp[h] = fmaf(lo, lo, ssp[h]);
+                ssp[h] = fmaf(hi, hi, ssp[h]);
             }
         }
-        acc = mfma16(a, b, acc);
     }
     if (SS) {
+        float ss = (ssp[0] + ssp[1]) + (ssp[2] + ssp[3]);
         ss += __shfl_xor(ss, 16, 64);
         ss += __shfl_xor(ss, 32, 64);
         if (g == 0) ss_s[wave * kBMax + l16] = ss;
@@ -231,24 +232,25 @@ __device__ __forceinline__ void wg_product_staged(const bf16_t *w_s, int ldw, in
     const bf16_t *arow = act_s + (size_t)l16 * lda + wave * kw + 8 * g;
     f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
     const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
-    float ss = 0.f;
+    float ssp[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int s = 0; s < KS; ++s) {
         Frag a, b;
         a.u = has_w ? lds_load16(wrow + s * 32) : zero;
         b.u = has_a ? lds_load16(arow + s * 32) : zero;
-        if (SS) {
+        acc = mfma16(a, b, acc);
+        if (SS) {   // four independent partial sums: one chain of 16 KS dependent multiply-adds is as long as the product
             const unsigned w4[4] = {b.u.x, b.u.y, b.u.z, b.u.w};
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
                 const float lo = __uint_as_float(w4[h] << 16), hi = __uint_as_float(w4[h] & 0xFFFF0000u);
-                ss = fmaf(lo, lo, ss);
-                ss = fmaf(hi, hi, ss);
+                ssp[h] = fmaf(lo, lo, ssp[h]);
+                ssp[h] = fmaf(hi, hi, ssp[h]);
             }
         }
-        acc = mfma16(a, b, acc);
     }
     if (SS) {
+        float ss = (ssp[0] + ssp[1]) + (ssp[2] + ssp[3]);
         ss += __shfl_xor(ss, 16, 64);
         ss += __shfl_xor(ss, 32, 64);
         if (g == 0) ss_s[wave * kBMax + l16] = ss;

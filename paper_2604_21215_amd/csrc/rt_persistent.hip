@@ -380,13 +380,15 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 #pragma unroll
                 for (int i = 0; i < 4; ++i)
                     if (act[i]) ss += __uint_as_float((unsigned)w6[i]);
-                const float rz = A.norm_free ? 1.f : rsqrtf(fast_sum(ss) / (float)d + A.eps);
-                float kr = __uint_as_float((unsigned)w6[4]) * rz;
+                // |z|^2, |k|^2 and q . (g k) of the raw key are three independent reductions (one after the other they are three
+                // dependent chains on the critical path of every position); the scales multiply the finished sums
+                const float k0 = __uint_as_float((unsigned)w6[4]);
+                const float kg = A.norm_free ? k0 : k0 * my_gk;
+                const float Sz = fast_sum(ss), Sk = fast_sum(k0 * k0), Sq = fast_sum(q * kg);
+                const float rz = A.norm_free ? 1.f : rsqrtf(Sz / (float)d + A.eps);
+                const float kscale = A.norm_free ? 1.f : rz * rsqrtf(rz * rz * Sk / (float)kHeadDim + A.eps);
+                const float kr = kg * kscale;
                 const float vr = __uint_as_float((unsigned)w6[5]) * rz;
-                if (!A.norm_free) {
-                    const float s2 = fast_sum(kr * kr);
-                    kr *= rsqrtf(s2 / (float)kHeadDim + A.eps) * my_gk;
-                }
                 const bf16_t kb = f32_to_bf16(kr), vb = f32_to_bf16(vr);
                 const size_t off = (size_t)(t - 1) * rs + (size_t)u * kHeadDim + lane;
                 A.K[off] = kb;
@@ -422,7 +424,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 }
                 if (t < A.N) {
                     // the newest key is one position before the query
-                    const float sn = ALIBI ? A.scale * fast_sum(q * kr) - alibi_slope(A.alibi, h, A.H) : A.scale * fast_sum(q * kr);
+                    const float sn = ALIBI ? A.scale * (Sq * kscale) - alibi_slope(A.alibi, h, A.H) : A.scale * (Sq * kscale);
                     const float m_new = fmaxf(m, sn);
                     const float e1 = __expf(m - m_new), e2 = __expf(sn - m_new);
                     l = l * e1 + e2;
