@@ -177,6 +177,15 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
     const float gkv_o = (ep_o && A.g_kv && !A.norm_free) ? bf16_to_f32(A.g_kv[o_lo + erow]) : 1.f;
     const float gmlp_o = (ep_o && A.g_mlp && !A.norm_free) ? bf16_to_f32(A.g_mlp[o_lo + erow]) : 1.f;
 
+    // phase U opens every position: what it needs from memory is requested one position ahead (the gain once)
+    const float gk_u = (has_u && A.g_k) ? bf16_to_f32(A.g_k[(my_u % H) * kHeadDim + lane]) : 1.f;
+    float un_nx = 0.f, rk_nx = 1.f;
+    if (has_u && !A.norm_free) {
+        const size_t rb0 = (size_t)A.i_hi * B + my_u / H;
+        un_nx = A.unit_k[rb0 * 2 * d + (my_u % H) * kHeadDim + lane];
+        rk_nx = A.rk[rb0 * H + my_u % H];
+    }
+
     for (int i = A.i_hi; i >= A.i_lo; --i) {
         const int step = A.i_hi - i, par = step & 1;
         const unsigned tag = A.tag_base | (unsigned)(step + 1);
@@ -224,9 +233,14 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
             A.dV[off] = dv;
             float du = dk;
             if (!A.norm_free) {
-                const float wv = A.g_k ? dk * bf16_to_f32(A.g_k[h * kHeadDim + lane]) : dk;
-                const float un = A.unit_k[(r0 + b) * 2 * d + h * kHeadDim + lane];
-                du = A.rk[(r0 + b) * H + h] * (wv - un * (fast_sum(un * wv) * (1.f / (float)kHeadDim)));
+                const float wv = dk * gk_u;
+                const float un = un_nx, rk = rk_nx;
+                du = rk * (wv - un * (fast_sum(un * wv) * (1.f / (float)kHeadDim)));
+                if (i > A.i_lo) {
+                    const size_t rbn = r0 - B + b;   // position i - 1
+                    un_nx = A.unit_k[rbn * 2 * d + h * kHeadDim + lane];
+                    rk_nx = A.rk[rbn * H + h];
+                }
             }
             A.dkraw[off] = du;
             const float dun = __shfl_down(du, 1, 64), dvn = __shfl_down(dv, 1, 64);
@@ -387,9 +401,24 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
                 const float slope = alibi_slope(A.alibi, h, H);
                 const float p = lane < w ? __expf(fmaf(-slope, (float)(w - lane), s * A.scale) - L) : 0.f;
                 const float ds = p * (dp - Dsum);
-                for (int j = 0; j < w; ++j) {
-                    accV[j * kHeadDim + lane] = fmaf(lane_bcast(p, j), g, accV[j * kHeadDim + lane]);
-                    accK[j * kHeadDim + lane] = fmaf(A.scale * lane_bcast(ds, j), q, accK[j * kHeadDim + lane]);
+                // eight keys at a time: all reads of a group before its writes (one key per trip is a chain of dependent LDS
+                // round trips, up to 31 of them, at the end of every position)
+                for (int j0 = 0; j0 < w; j0 += 8) {
+                    float av[8], ak[8];
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int j = min(j0 + e, w - 1);
+                        av[e] = accV[j * kHeadDim + lane];
+                        ak[e] = accK[j * kHeadDim + lane];
+                    }
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) {
+                        const int j = j0 + e;
+                        if (j < w) {   // wavefront-uniform
+                            accV[j * kHeadDim + lane] = fmaf(lane_bcast(p, j), g, av[e]);
+                            accK[j * kHeadDim + lane] = fmaf(A.scale * lane_bcast(ds, j), q, ak[e]);
+                        }
+                    }
                 }
             }
         }

@@ -222,6 +222,10 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
         const bool hasA = att && cA < nch;
         dec_load_chunk(A.K, A.V, rs, att ? u : 0, hasA ? cA * 64 : 0, hasA ? min(64, t - cA * 64) : 1, krA, vrA);
     }
+    // gains of the per-head normalisation of this wavefront's head: requested behind the run above (loads come back in issue
+    // order), long before the three places on the critical path that use them
+    const float gq_r = (att && A.g_q) ? bf16_to_f32(A.g_q[uh * kHeadDim + lane]) : 1.f;
+    const float gk_r = (att && A.g_k) ? bf16_to_f32(A.g_k[uh * kHeadDim + lane]) : 1.f;
     // ================================================================ input rows and the rows of [Wq; Wk; Wv] into LDS
 #pragma unroll
     for (int j = 0; j < NXB; ++j) {
@@ -303,7 +307,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
         const ll_t wq = ll_wait(A.qkv_ll + single_word<RQ>(uh * kHeadDim + lane, ub), true, tag, A, fail);
         qn = __uint_as_float((unsigned)wq);
         if (!A.norm_free)
-            qn *= rsqrtf(fast_sum(qn * qn) / (float)kHeadDim + A.eps) * (A.g_q ? bf16_to_f32(A.g_q[uh * kHeadDim + lane]) : 1.f);
+            qn *= rsqrtf(fast_sum(qn * qn) / (float)kHeadDim + A.eps) * gq_r;
         float q8[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) q8[e] = __shfl(qn, (lane & 7) * 8 + e, 64);
@@ -364,7 +368,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
             float kt = __uint_as_float((unsigned)w2[0]);
             const float vt = bf16_to_f32(f32_to_bf16(__uint_as_float((unsigned)w2[1])));
             if (!A.norm_free)
-                kt *= rsqrtf(fast_sum(kt * kt) / (float)kHeadDim + A.eps) * (A.g_k ? bf16_to_f32(A.g_k[uh * kHeadDim + lane]) : 1.f);
+                kt *= rsqrtf(fast_sum(kt * kt) / (float)kHeadDim + A.eps) * gk_r;
             dec_combine(M, L, O, A.scale * fast_sum(qn * kt), 1.f, vt);
             for (int sp = 1; sp < S; ++sp) {
                 const ll_t *src = A.part_ll + ((size_t)u * kDecMaxSplit + sp) * kPartWords;
@@ -491,7 +495,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
         float kr = __uint_as_float((unsigned)w6[4]) * rz;
         const float vr = __uint_as_float((unsigned)w6[5]) * rz;
         if (!A.norm_free)
-            kr *= rsqrtf(fast_sum(kr * kr) / (float)kHeadDim + A.eps) * (A.g_k ? bf16_to_f32(A.g_k[uh * kHeadDim + lane]) : 1.f);
+            kr *= rsqrtf(fast_sum(kr * kr) / (float)kHeadDim + A.eps) * gk_r;
         if (!fail) {
             const size_t off = (size_t)t * rs + (size_t)u * kHeadDim + lane;
             A.K[off] = f32_to_bf16(kr);
