@@ -98,6 +98,7 @@ struct PersistArgs {
     unsigned long long *trace;  // optional: [2][trace_rows][16] wall-clock stamps of workgroup 0 and of workgroup trace_wg
     int trace_wg, trace_rows;
     int pre_sleep;              // units of 8 x 64 clocks a bulk pull waits before its first poll
+    int early_premerge;         // the helper wavefront also combines the pre-merge (phase 2b) at positions without an event
     long long spin_limit;
     float alibi;                // maximum ALiBi bias (kernels instantiated with ALIBI only)
 };
@@ -337,6 +338,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     const int help_slot = wave - 4;
     const int help_u = wg + G * help_slot;
     const bool is_helper = help_slot >= 0 && help_slot < A.upw && help_u < BH;
+    const float *help_wk = win_k + (size_t)(is_helper ? help_slot : 0) * A.win_rows * (kHeadDim + 4);
+    const bf16_t *help_wv = win_v + (size_t)(is_helper ? help_slot : 0) * A.win_rows * kHeadDim;
     if (is_helper) {
         PreLoad L;
         pre_issue(A, 0, help_u, L);
@@ -357,6 +360,17 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         if (t < A.N) RT_STAMP(0);
         float xv = 0.f;   // residual input of this workgroup's rows, fetched ahead of phase O
         if (t < A.N && tid < kRMax * kBMax && erow < o_n && eb < B) xv = bf16_to_f32(A.x[((size_t)eb * A.N + t) * d + o_lo + erow]);
+        // At a position without a cross-block event the stored states that the next position's pre-merge reads are complete
+        // already, so the helper wavefront fetches them during phase M (it is idle there), combines them with the window in
+        // phase 2b (idle again) and leaves the finished state in LDS: the owning wavefront then has nothing to do behind the
+        // product of phase KV, which is on the critical path of every position.  At an event position the states arrive
+        // after phase M: there the helper fetches in phase 2b and the owner combines behind phase KV.
+        const bool early = A.early_premerge && !(t >= A.p_min && (t & -t) >= A.p_min) && t + 1 < A.N;
+        if (early && is_helper) {
+            PreLoad L;
+            pre_issue(A, t + 1, help_u, L);
+            pre_to_lds(L, pre_s + (size_t)help_slot * kPreFloats);
+        }
         // ================================================================ phase M
         if (has_u) {
             const int u = my_u;
@@ -567,10 +581,18 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         RT_STAMP(13);
 
         // ================================================================ phase 2b:  z = h + alpha (sum of the four partials)
-        if (is_helper && t + 1 < A.N) {   // wavefronts 4.. are idle in this phase: fetch the next position's merge inputs
+        if (is_helper && t + 1 < A.N) {   // wavefronts 4.. are idle in this phase
             PreLoad L;
-            pre_issue(A, t + 1, help_u, L);
-            pre_to_lds(L, pre_s + (size_t)help_slot * kPreFloats);
+            float *slot = pre_s + (size_t)help_slot * kPreFloats;
+            if (early) {   // combine what phase M fetched; the window holds key t-1 since phase M
+                float rq, rm, rl, ro;
+                pre_from_lds(slot, L);
+                pre_finish<ALIBI>(A, t + 1, help_u, L, help_wk, help_wv, rq, rm, rl, ro);
+                slot[lane] = rq; slot[64 + lane] = rm; slot[128 + lane] = rl; slot[192 + lane] = ro;
+            } else {       // fetch the next position's merge inputs
+                pre_issue(A, t + 1, help_u, L);
+                pre_to_lds(L, slot);
+            }
         }
         if (tid < kRMax * kBMax) {   // four full wavefronts
             float zv = 0.f, zg = 0.f;
@@ -614,10 +636,15 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         RT_ABORT_IF(fail);
         if (tid < kRMax * kBMax && erow < kv_n && eb < B)
             ll_store(A.kv_ll + par * sz_kv + single_word<RKV>(kv_lo + erow, eb), tag, __float_as_uint(red_sum(red, erow, eb)));
-        if (pre) {   // overlaps the raw k, v crossing the chip
-            PreLoad L;
-            pre_from_lds(pre_s + (size_t)wave * kPreFloats, L);
-            pre_finish<ALIBI>(A, t + 1, my_u, L, my_wk, my_wv, cq, cm, cl, co);
+        if (pre) {
+            const float *slot = pre_s + (size_t)wave * kPreFloats;
+            if (early) {   // finished by the helper in phase 2b
+                cq = slot[lane]; cm = slot[64 + lane]; cl = slot[128 + lane]; co = slot[192 + lane];
+            } else {       // overlaps the raw k, v crossing the chip
+                PreLoad L;
+                pre_from_lds(slot, L);
+                pre_finish<ALIBI>(A, t + 1, my_u, L, my_wk, my_wv, cq, cm, cl, co);
+            }
         }
         __syncthreads();
         RT_STAMP(6);
@@ -783,6 +810,7 @@ rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weigh
     A.bar = P.bar; A.trace = P.trace; A.spin_limit = P.spin_limit;
     A.trace_rows = P.trace_rows;
     A.pre_sleep = getenv("RT_PRE_SLEEP") ? atoi(getenv("RT_PRE_SLEEP")) : 1;
+    A.early_premerge = (getenv("RT_EARLY_PREMERGE") ? atoi(getenv("RT_EARLY_PREMERGE")) : 1) && P.win_rows != 0;
     {
         const char *tw = getenv("RT_PERSIST_TRACE_WG");
         A.trace_wg = tw ? atoi(tw) : P.grid - 1;
