@@ -137,10 +137,11 @@ constexpr int kAuxAgent = 16;   // cache-policy operand of the buffer load: sc1 
 template <int KS, int GW, bool SS = false, typename ARGS>
 __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, const ll_t *act, int B,
                                            unsigned tag, const ARGS &A, float *red, bf16_t *act_s, int lda, int &fail,
-                                           float *ss_s = nullptr)
+                                           float *ss_s = nullptr, int pre_sleep_units = -1)
 {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
+    const int pre_sleep = pre_sleep_units >= 0 ? pre_sleep_units : A.pre_sleep;
     constexpr int K = KS * 32 * kPW;
     constexpr int kWords = kBMax * K / 2;                   // words of the vector, unused batch rows included
     constexpr int kMaxChunks = kWords / 2 / kPThreads;      // 16-byte chunks per thread  (= 2 KS)
@@ -158,7 +159,7 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
     long long spins = 0;
     // A poll that leaves before the producers' stores have landed costs a whole extra trip (about 1.2 us); measured,
     // a quarter of a microsecond of waiting first brings the average number of rounds from 1.5 to 1.1.
-    for (int i = 0; i < A.pre_sleep; ++i) __builtin_amdgcn_s_sleep(8);
+    for (int i = 0; i < pre_sleep; ++i) __builtin_amdgcn_s_sleep(8);
     while (__any(need != 0)) {
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i)

@@ -55,6 +55,7 @@
 // leaves the kernel at its next wait, and the host reports it (rt_device_wait_expired).
 #include "rt_persistent.h"
 #include "rt_ll.h"
+#include <cstring>
 #include "rt_cross_tile.h"
 
 #include <cstdlib>
@@ -98,6 +99,7 @@ struct PersistArgs {
     unsigned long long *trace;  // optional: [2][trace_rows][16] wall-clock stamps of workgroup 0 and of workgroup trace_wg
     int trace_wg, trace_rows;
     int pre_sleep;              // units of 8 x 64 clocks a bulk pull waits before its first poll
+    int ps_o, ps_1, ps_2a, ps_kv;   // the same per phase
     int early_premerge;         // the helper wavefront also combines the pre-merge (phase 2b) at positions without an event
     long long spin_limit;
     float alibi;                // maximum ALiBi bias (kernels instantiated with ALIBI only)
@@ -530,7 +532,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 
         // ================================================================ phase O:  h = x_t + alpha Wo a
         RT_STAMP(7);
-        wg_gemv_ll<KSD, 32>(wo_s, A.ldw_d, o_n, A.a_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail);
+        wg_gemv_ll<KSD, 32>(wo_s, A.ldw_d, o_n, A.a_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail, nullptr, A.ps_o);
         RT_ABORT_IF(fail);
         RT_STAMP(8);
         if (tid < kRMax * kBMax) {
@@ -547,7 +549,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         RT_STAMP(3);
 
         // ================================================================ phase 1:  u = gelu(rinv_h * W1 h)
-        wg_gemv_ll<KSD, RO / 2, true>(w1_s, A.ldw_d, f_n, A.h_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail, sq);
+        wg_gemv_ll<KSD, RO / 2, true>(w1_s, A.ldw_d, f_n, A.h_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail, sq, A.ps_1);
         RT_ABORT_IF(fail);
         RT_STAMP(11);
         RT_STAMP(12);
@@ -571,7 +573,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         // ================================================================ phase 2a:  partial W2 u over contraction block jb
         RT_STAMP(9);
         wg_gemv_ll<KSD, R1 / 2>(w2_s, A.ldw_d, RB, A.u_ll + par * half_F + (size_t)jb * (kBMax * (d / 2)), B, tag, A, red, act_s,
-                                A.ldw_d, fail);
+                                A.ldw_d, fail, nullptr, A.ps_2a);
         RT_ABORT_IF(fail);
         RT_STAMP(10);
         if (tid < kRMax * kBMax && erow < RB && eb < B)
@@ -632,7 +634,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
 
         // ================================================================ phase KV:  [Wk; Wv] (z g_kv)
         const bool pre = has_u && t + 1 < A.N;
-        wg_gemv_ll<KSD, RO / 2>(wkv_s, A.ldw_d, kv_n, A.z_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail);
+        wg_gemv_ll<KSD, RO / 2>(wkv_s, A.ldw_d, kv_n, A.z_ll + par * half_d, B, tag, A, red, act_s, A.ldw_d, fail, nullptr, A.ps_kv);
         RT_ABORT_IF(fail);
         if (tid < kRMax * kBMax && erow < kv_n && eb < B)
             ll_store(A.kv_ll + par * sz_kv + single_word<RKV>(kv_lo + erow, eb), tag, __float_as_uint(red_sum(red, erow, eb)));
@@ -809,7 +811,20 @@ rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weigh
     A.R_2 = D.d / 64;
     A.bar = P.bar; A.trace = P.trace; A.spin_limit = P.spin_limit;
     A.trace_rows = P.trace_rows;
+    // Waits before the first poll of the pulls of phases O, 1, 2a, KV in units of 8 x 64 clocks (0.21 us): a poll that leaves
+    // before the producers' stores have landed costs a whole extra trip.  Measured at cfg3 (ms per call): 1,1,1,1 31.45;
+    // 1,2,1,1 30.80; 2,2,1,1 30.76; 2,2,1,0 30.5; 3,2,1,0 30.84; 2,3,1,0 30.91; 1,1,0,1 32.7; 1,1,1,2 31.8.
+    // RT_PRE_SLEEPS (four digits) or RT_PRE_SLEEP (one number for all four) override them.
     A.pre_sleep = getenv("RT_PRE_SLEEP") ? atoi(getenv("RT_PRE_SLEEP")) : 1;
+    {
+        const char *ps = getenv("RT_PRE_SLEEPS");
+        const bool ok = ps && strlen(ps) == 4;
+        const bool one = getenv("RT_PRE_SLEEP") != nullptr;
+        A.ps_o = ok ? ps[0] - '0' : (one ? A.pre_sleep : 2);
+        A.ps_1 = ok ? ps[1] - '0' : (one ? A.pre_sleep : 2);
+        A.ps_2a = ok ? ps[2] - '0' : (one ? A.pre_sleep : 1);
+        A.ps_kv = ok ? ps[3] - '0' : (one ? A.pre_sleep : 0);
+    }
     A.early_premerge = (getenv("RT_EARLY_PREMERGE") ? atoi(getenv("RT_EARLY_PREMERGE")) : 1) && P.win_rows != 0;
     {
         const char *tw = getenv("RT_PERSIST_TRACE_WG");
