@@ -15,6 +15,7 @@ constexpr int kBMax = 16;              // batch rows (MFMA N dimension)
 constexpr int kRMax = 16;              // output rows per workgroup and matrix (MFMA M dimension)
 
 typedef unsigned long long ll_t;       // exchange word: [tag:32 | payload:32]
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 // 64-lane all-reduce with DPP inside each row of 16 lanes (no LDS crossbar), rows combined through
 // scalar reads.  quad_perm [1,0,3,2] = 0xB1, [2,3,0,1] = 0x4E, row_half_mirror = 0x141, row_mirror = 0x140.
@@ -200,10 +201,9 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
         if (SS) {   // four independent partial sums: one chain of 16 KS dependent multiply-adds is as long as the product
             const unsigned w4[4] = {b.u.x, b.u.y, b.u.z, b.u.w};
 #pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                const float lo = __uint_as_float(w4[h] << 16), hi = __uint_as_float(w4[h] & 0xFFFF0000u);
-                ssp[h] = fmaf(lo, lo, ssp[h]);
-                ssp[h] = fmaf(hi, hi, ssp[h]);
+            for (int h = 0; h < 4; ++h) {   // lo lo + hi hi + sum in one instruction (v_dot2c_f32_bf16)
+                const bf16x2_t pr = __builtin_bit_cast(bf16x2_t, w4[h]);
+                ssp[h] = __builtin_amdgcn_fdot2_f32_bf16(pr, pr, ssp[h], false);
             }
         }
     }
@@ -243,10 +243,9 @@ __device__ __forceinline__ void wg_product_staged(const bf16_t *w_s, int ldw, in
         if (SS) {   // four independent partial sums: one chain of 16 KS dependent multiply-adds is as long as the product
             const unsigned w4[4] = {b.u.x, b.u.y, b.u.z, b.u.w};
 #pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                const float lo = __uint_as_float(w4[h] << 16), hi = __uint_as_float(w4[h] & 0xFFFF0000u);
-                ssp[h] = fmaf(lo, lo, ssp[h]);
-                ssp[h] = fmaf(hi, hi, ssp[h]);
+            for (int h = 0; h < 4; ++h) {   // lo lo + hi hi + sum in one instruction (v_dot2c_f32_bf16)
+                const bf16x2_t pr = __builtin_bit_cast(bf16x2_t, w4[h]);
+                ssp[h] = __builtin_amdgcn_fdot2_f32_bf16(pr, pr, ssp[h], false);
             }
         }
     }
