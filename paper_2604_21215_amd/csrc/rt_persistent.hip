@@ -19,11 +19,12 @@
 //   2a   partial W2 u over one quarter of the hidden dimension                               -> 4 partial sums
 //   2b   z = h + alpha (sum of partials), same rows as O                      -> y, bf16(z), partial sums of z^2
 //   KV   [Wk'; Wv'] z  (scale 1/rms(z) applied in M)                                         -> raw k, v
-//        and, on the wavefronts that own a (b, h): the pre-merge of position t+1 (temporary pair,
-//        stored partial states of the bits of c = t at or above p_min, direct window out of LDS).
-//        Its global loads are issued during phase 2b by a wavefront that has nothing else to do there
-//        and parked in LDS; the owner finishes the merge after this phase's own product, in the shadow
-//        of the k, v hop.
+// The pre-merge of position t+1 (temporary pair, stored partial states of the bits of c = t at or above
+// p_min, direct window out of LDS: everything but the newest key) is kept off this chain.  At a position
+// without a cross-block event a helper wavefront of the owning workgroup issues its global loads during
+// phase M, parks them in LDS, combines them with the window during phase 2b (it is idle in both phases)
+// and leaves q, m, l, o in LDS for the owner.  At an event position the stored states only arrive behind
+// phase M: there the helper fetches during phase 2b and the owner combines after the product of phase KV.
 //
 // Logits are formed from unrounded operands: fp32 q and temporary k from the pre-pass, fp32 keys in the
 // LDS window, and for the cross-block tiles the persistent key as bf16 head + bf16 remainder (three MFMA
@@ -164,9 +165,9 @@ __device__ __forceinline__ void attend_lds(float q, const float *ks, const bf16_
     } while (0)
 
 // Part of the merge of a position that does not need its newest key: the temporary pair, the stored
-// partial states (bits of c = t-1 at or above p_min) and the direct window.  The loads are issued one
-// phase ahead (pre_issue, at the start of phase KV of the previous position) and combined after that
-// phase's own work (pre_finish), so that phase M only waits for the raw k, v of the newest key.
+// partial states (bits of c = t-1 at or above p_min) and the direct window.  The loads are issued ahead
+// (pre_issue) and combined later (pre_finish) by the wavefronts named in the file header, so that phase M
+// only waits for the raw k, v of the newest key.
 struct PreLoad {
     float q, kt, vt;
     float pm[kMaxLevels], pl[kMaxLevels], po[kMaxLevels];
@@ -335,8 +336,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
     const float *my_wk = win_k + (size_t)wave * A.win_rows * (kHeadDim + 4);
     const bf16_t *my_wv = win_v + (size_t)wave * A.win_rows * kHeadDim;
     float cq = 0.f, cm = 0.f, cl = 1.f, co = 0.f;
-    // The loads of a pre-merge are made by an otherwise idle helper wavefront (wave 4 + slot, during
-    // phase 2b) and handed over through LDS, so that no wavefront carries them in registers across a phase.
+    // The loads of a pre-merge are made by an otherwise idle helper wavefront (wave 4 + slot) and handed over
+    // through LDS, so that no wavefront carries them in registers across a phase.
     const int help_slot = wave - 4;
     const int help_u = wg + G * help_slot;
     const bool is_helper = help_slot >= 0 && help_slot < A.upw && help_u < BH;
