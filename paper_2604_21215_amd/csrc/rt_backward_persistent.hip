@@ -253,17 +253,13 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
         }
 
         // ================================================================ G1: d_rz = Wk^T dkraw + Wv^T dV_i
-        wg_gemv_ll<KSD, 32>(wk_s, A.ldw, o_n, A.e1k + par * half_d, B, tag, A, red, act_s, A.ldw, fail);
-        RT_BWP_ABORT_IF(fail);
-        float s1 = 0.f;
-        if (ep_o) s1 = red_sum(red, erow, eb);
-        __syncthreads();   // red and the staged rows are reused
-        wg_gemv_ll<KSD, 32>(wv_s, A.ldw, o_n, A.e1v + par * half_d, B, tag, A, red, act_s, A.ldw, fail);
+        wg_gemv_ll_pair<KSD, 32>(wk_s, wv_s, A.ldw, o_n, A.e1k + par * half_d, A.e1v + par * half_d, B, tag, A, red, act_s, A.ldw,
+                                 fail);
         RT_BWP_ABORT_IF(fail);
         if (tid < kRMax * kBMax) {
             float wv = 0.f;
             if (ep_o) {
-                const float drz = s1 + red_sum(red, erow, eb);
+                const float drz = red_sum(red, erow, eb);
                 A.d_rz[(r0 + eb) * d + o_lo + erow] = drz;
                 wv = drz * gkv_o;
             }

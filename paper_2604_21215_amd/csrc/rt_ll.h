@@ -218,6 +218,92 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
     for (int i = 0; i < 4; ++i) r[i * kBMax] = acc[i];
 }
 
+// Two exchanged vectors of the same layout against two weight slices, summed: red = w1 act1 + w2 act2.  Both vectors are
+// polled in the same rounds (one store-to-load trip for the pair instead of one each); the first is staged as it arrives,
+// the second waits in registers until the first product has read the staging rows.
+template <int KS, int GW, typename ARGS>
+__device__ __forceinline__ void wg_gemv_ll_pair(const bf16_t *w1_s, const bf16_t *w2_s, int ldw, int R, const ll_t *act1,
+                                                const ll_t *act2, int B, unsigned tag, const ARGS &A, float *red, bf16_t *act_s,
+                                                int lda, int &fail)
+{
+    static_assert(GW % 2 == 0, "both words of a chunk belong to one batch row");
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int l16 = lane & 15, g = lane >> 4;
+    constexpr int K = KS * 32 * kPW;
+    constexpr int kWords = kBMax * K / 2;
+    constexpr int kMaxChunks = kWords / 2 / kPThreads;
+    const __amdgpu_buffer_rsrc_t rsrc1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<ll_t *>(act1), 0, kWords * 8, 0x00020000);
+    const __amdgpu_buffer_rsrc_t rsrc2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<ll_t *>(act2), 0, kWords * 8, 0x00020000);
+    v4u_t v1[kMaxChunks], v2[kMaxChunks];
+    unsigned need1 = 0, need2 = 0;
+#pragma unroll
+    for (int i = 0; i < kMaxChunks; ++i) {
+        v1[i] = v2[i] = v4u_t{0u, 0u, 0u, 0u};
+        const int w0 = 2 * (i * kPThreads + tid);
+        if ((w0 % (kBMax * GW)) / GW < B) need1 |= 1u << i;
+    }
+    const unsigned mine = need1;
+    need2 = need1;
+    long long spins = 0;
+    for (int i = 0; i < A.pre_sleep; ++i) __builtin_amdgcn_s_sleep(8);
+    while (__any((need1 | need2) != 0)) {
+#pragma unroll
+        for (int i = 0; i < kMaxChunks; ++i) {
+            if (need1 & (1u << i)) v1[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc1, (i * kPThreads + tid) * 16, 0, kAuxAgent);
+            if (need2 & (1u << i)) v2[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc2, (i * kPThreads + tid) * 16, 0, kAuxAgent);
+        }
+#pragma unroll
+        for (int i = 0; i < kMaxChunks; ++i) {
+            if ((need1 & (1u << i)) && v1[i][1] == tag && v1[i][3] == tag) {
+                const int w0 = 2 * (i * kPThreads + tid);
+                const int b0 = (w0 % (kBMax * GW)) / GW, k0 = 2 * ((w0 / (kBMax * GW)) * GW + w0 % GW);
+                *reinterpret_cast<uint2 *>(act_s + (size_t)b0 * lda + k0) = make_uint2(v1[i][0], v1[i][2]);
+                need1 &= ~(1u << i);
+            }
+            if ((need2 & (1u << i)) && v2[i][1] == tag && v2[i][3] == tag) need2 &= ~(1u << i);
+        }
+        if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
+    }
+    __syncthreads();
+    const bool has_w = l16 < R, has_a = l16 < B;
+    constexpr int kw = KS * 32;
+    const bf16_t *arow = act_s + (size_t)l16 * lda + wave * kw + 8 * g;
+    const uint4 zero = make_uint4(0u, 0u, 0u, 0u);
+    f32x4_t acc = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    {
+        const bf16_t *wrow = w1_s + (size_t)l16 * ldw + wave * kw + 8 * g;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            Frag a, b;
+            a.u = has_w ? lds_load16(wrow + s * 32) : zero;
+            b.u = has_a ? lds_load16(arow + s * 32) : zero;
+            acc = mfma16(a, b, acc);
+        }
+    }
+    __syncthreads();   // every wavefront has read the first vector's rows
+#pragma unroll
+    for (int i = 0; i < kMaxChunks; ++i)
+        if (mine & (1u << i)) {
+            const int w0 = 2 * (i * kPThreads + tid);
+            const int b0 = (w0 % (kBMax * GW)) / GW, k0 = 2 * ((w0 / (kBMax * GW)) * GW + w0 % GW);
+            *reinterpret_cast<uint2 *>(act_s + (size_t)b0 * lda + k0) = make_uint2(v2[i][0], v2[i][2]);
+        }
+    __syncthreads();
+    {
+        const bf16_t *wrow = w2_s + (size_t)l16 * ldw + wave * kw + 8 * g;
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+            Frag a, b;
+            a.u = has_w ? lds_load16(wrow + s * 32) : zero;
+            b.u = has_a ? lds_load16(arow + s * 32) : zero;
+            acc = mfma16(a, b, acc);
+        }
+    }
+    float *r = red + ((size_t)wave * kRMax + 4 * g) * kBMax + l16;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) r[i * kBMax] = acc[i];
+}
+
 // The product half of wg_gemv_ll alone: rows of an LDS-resident weight slice times activation rows that are already
 // staged in LDS as bf16 rows act_s[b][lda] (the caller has synchronised).  The per-wavefront 16 x 16 tiles land in
 // red[wave][row][b]; with SS the sum of squares of the staged rows goes to ss_s[wave][b].
