@@ -186,6 +186,41 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
         rk_nx = A.rk[rb0 * H + my_u % H];
     }
 
+    // Phase U: the complete pair gradient (dk_, dv_) of position ipos_ goes out as the vectors of step tag_ / parity par_.  It runs
+    // at the end of the previous position's phase A, as soon as that query's contribution to this one slot is in (the other slots
+    // are updated afterwards, while the vectors cross the chip); for the block's last position it runs before the loop.
+#define RT_BWP_PHASE_U(ipos_, par_, tag_, dk_, dv_)                                                                        \
+    {                                                                                                                      \
+        const int ub_ = my_u / H, uh_ = my_u - ub_ * H;                                                                    \
+        const size_t off_ = (size_t)(ipos_) * rs + (size_t)my_u * kHeadDim + lane;                                         \
+        A.dK[off_] = (dk_);                                                                                                \
+        A.dV[off_] = (dv_);                                                                                                \
+        float du_ = (dk_);                                                                                                 \
+        if (!A.norm_free) {                                                                                                \
+            const float wv_ = (dk_) * gk_u;                                                                                \
+            const float un_ = un_nx, rk_ = rk_nx;                                                                          \
+            du_ = rk_ * (wv_ - un_ * (fast_sum(un_ * wv_) * (1.f / (float)kHeadDim)));                                     \
+            if ((ipos_) > A.i_lo) {                                                                                        \
+                const size_t rbn_ = (size_t)((ipos_) - 1) * B + ub_;                                                       \
+                un_nx = A.unit_k[rbn_ * 2 * d + uh_ * kHeadDim + lane];                                                    \
+                rk_nx = A.rk[rbn_ * H + uh_];                                                                              \
+            }                                                                                                              \
+        }                                                                                                                  \
+        A.dkraw[off_] = du_;                                                                                               \
+        const float dun_ = __shfl_down(du_, 1, 64), dvn_ = __shfl_down((dv_), 1, 64);                                      \
+        if (!(lane & 1)) {                                                                                                 \
+            ll_store(A.e1k + (par_) * half_d + pair_word<32>(uh_ * kHeadDim + lane, ub_), (tag_),                          \
+                     (unsigned)f32_to_bf16(du_) | ((unsigned)f32_to_bf16(dun_) << 16));                                    \
+            ll_store(A.e1v + (par_) * half_d + pair_word<32>(uh_ * kHeadDim + lane, ub_), (tag_),                          \
+                     (unsigned)f32_to_bf16((dv_)) | ((unsigned)f32_to_bf16(dvn_) << 16));                                  \
+        }                                                                                                                  \
+    }
+    if (has_u && A.i_hi >= A.i_lo) {
+        const int slot = A.i_hi - blk_lo;
+        const float dk0 = accK[slot * kHeadDim + lane], dv0 = accV[slot * kHeadDim + lane];
+        RT_BWP_PHASE_U(A.i_hi, 0, A.tag_base | 1u, dk0, dv0)
+    }
+
     for (int i = A.i_hi; i >= A.i_lo; --i) {
         const int step = A.i_hi - i, par = step & 1;
         const unsigned tag = A.tag_base | (unsigned)(step + 1);
@@ -222,34 +257,6 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
         } else {
 #pragma unroll
             for (int e = 0; e < PER; ++e) uz[e] = uh[e] = 0.f;
-        }
-
-        // ================================================================ U: the complete pair gradient of position i
-        if (has_u) {
-            const int u = my_u, b = u / H, h = u - b * H, slot = i - blk_lo;
-            const float dk = accK[slot * kHeadDim + lane], dv = accV[slot * kHeadDim + lane];
-            const size_t off = (size_t)i * rs + (size_t)u * kHeadDim + lane;
-            A.dK[off] = dk;
-            A.dV[off] = dv;
-            float du = dk;
-            if (!A.norm_free) {
-                const float wv = dk * gk_u;
-                const float un = un_nx, rk = rk_nx;
-                du = rk * (wv - un * (fast_sum(un * wv) * (1.f / (float)kHeadDim)));
-                if (i > A.i_lo) {
-                    const size_t rbn = r0 - B + b;   // position i - 1
-                    un_nx = A.unit_k[rbn * 2 * d + h * kHeadDim + lane];
-                    rk_nx = A.rk[rbn * H + h];
-                }
-            }
-            A.dkraw[off] = du;
-            const float dun = __shfl_down(du, 1, 64), dvn = __shfl_down(dv, 1, 64);
-            if (!(lane & 1)) {
-                ll_store(A.e1k + par * half_d + pair_word<32>(h * kHeadDim + lane, b), tag,
-                         (unsigned)f32_to_bf16(du) | ((unsigned)f32_to_bf16(dun) << 16));
-                ll_store(A.e1v + par * half_d + pair_word<32>(h * kHeadDim + lane, b), tag,
-                         (unsigned)f32_to_bf16(dv) | ((unsigned)f32_to_bf16(dvn) << 16));
-            }
         }
 
         // ================================================================ G1: d_rz = Wk^T dkraw + Wv^T dV_i
@@ -397,20 +404,27 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
                 const float slope = alibi_slope(A.alibi, h, H);
                 const float p = lane < w ? __expf(fmaf(-slope, (float)(w - lane), s * A.scale) - L) : 0.f;
                 const float ds = p * (dp - Dsum);
-                // eight keys at a time: all reads of a group before its writes (one key per trip is a chain of dependent LDS
-                // round trips, up to 31 of them, at the end of every position)
-                for (int j0 = 0; j0 < w; j0 += 8) {
+                // the newest slot first: with it the pair gradient of position i - 1 is complete and goes out at once
+                {
+                    const int j = w - 1;
+                    const float dvn = fmaf(lane_bcast(p, j), g, accV[j * kHeadDim + lane]);
+                    const float dkn = fmaf(A.scale * lane_bcast(ds, j), q, accK[j * kHeadDim + lane]);
+                    RT_BWP_PHASE_U(i - 1, par ^ 1, tag + 1u, dkn, dvn)
+                }
+                // the older slots eight keys at a time: all reads of a group before its writes (one key per trip is a chain of
+                // dependent LDS round trips)
+                for (int j0 = 0; j0 < w - 1; j0 += 8) {
                     float av[8], ak[8];
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
-                        const int j = min(j0 + e, w - 1);
+                        const int j = min(j0 + e, w - 2);
                         av[e] = accV[j * kHeadDim + lane];
                         ak[e] = accK[j * kHeadDim + lane];
                     }
 #pragma unroll
                     for (int e = 0; e < 8; ++e) {
                         const int j = j0 + e;
-                        if (j < w) {   // wavefront-uniform
+                        if (j < w - 1) {   // wavefront-uniform
                             accV[j * kHeadDim + lane] = fmaf(lane_bcast(p, j), g, av[e]);
                             accK[j * kHeadDim + lane] = fmaf(A.scale * lane_bcast(ds, j), q, ak[e]);
                         }
