@@ -30,6 +30,8 @@
 // Every wait is bounded (spin limit -> abort word -> every workgroup leaves).
 #include "rt_backward_persistent.h"
 #include "rt_ll.h"
+#include <cstring>
+#include <cstdlib>
 
 #include <cstdlib>
 
@@ -62,6 +64,7 @@ struct BwpArgs {
     unsigned long long *bar;
     long long spin_limit;
     int pre_sleep;
+    int ps_g1, ps_g2, ps_g3, ps_g4;   // waits before the first poll of the four pulls, units of 8 x 64 clocks
 };
 
 // Workgroup barrier behind which every wavefront leaves when any of them has given up waiting: that wavefront raises an LDS
@@ -261,7 +264,7 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
 
         // ================================================================ G1: d_rz = Wk^T dkraw + Wv^T dV_i
         wg_gemv_ll_pair<KSD, 32>(wk_s, wv_s, A.ldw, o_n, A.e1k + par * half_d, A.e1v + par * half_d, B, tag, A, red, act_s, A.ldw,
-                                 fail);
+                                 fail, A.ps_g1);
         RT_BWP_ABORT_IF(fail);
         if (tid < kRMax * kBMax) {
             float wv = 0.f;
@@ -279,7 +282,7 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
         __syncthreads();
 
         // ================================================================ G2: dot, W2^T w, Wo^T w; dpre rows, Gz rows
-        wg_gemv_ll<KSD, RO / 2>(w2_s, A.ldw, f_n, A.e2 + par * half_d, B, tag, A, red, act_s, A.ldw, fail);
+        wg_gemv_ll<KSD, RO / 2>(w2_s, A.ldw, f_n, A.e2 + par * half_d, B, tag, A, red, act_s, A.ldw, fail, nullptr, A.ps_g2);
         RT_BWP_ABORT_IF(fail);
         wg_product_staged<KSD>(wo_s, A.ldw, o_n, B, red2, act_s, A.ldw);
         if (wave < B) {
@@ -311,7 +314,7 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
 
         // ================================================================ G3a: partial W1^T dpre over contraction block jb
         wg_gemv_ll<KSD, R1 / 2>(w1_s, A.ldw, RB, A.e3 + par * half_F + (size_t)jb * (kBMax * (d / 2)), B, tag, A, red, act_s, A.ldw,
-                                fail);
+                                fail, nullptr, A.ps_g3);
         RT_BWP_ABORT_IF(fail);
         if (tid < kRMax * kBMax && erow < RB && eb < B)
             ll_store(A.e4 + ((size_t)(par * 4 + jb) * kBMax + eb) * d + rb * RB + erow, tag, __float_as_uint(red_sum(red, erow, eb)));
@@ -345,7 +348,7 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
         RT_BWP_ABORT_IF(fail);
 
         // ================================================================ G4: dot2, Wo^T w2; dc rows, dh rows
-        wg_gemv_ll<KSD, RO / 2>(wo_s, A.ldw, o_n, A.e5 + par * half_d, B, tag, A, red, act_s, A.ldw, fail);
+        wg_gemv_ll<KSD, RO / 2>(wo_s, A.ldw, o_n, A.e5 + par * half_d, B, tag, A, red, act_s, A.ldw, fail, nullptr, A.ps_g4);
         RT_BWP_ABORT_IF(fail);
         if (wave < B) {
             const float dt = A.norm_free ? 0.f : row_dot<PER>(uh, act_s + (size_t)wave * A.ldw, lane);
@@ -552,6 +555,12 @@ hipError_t bwp_run_block(BwpState &P, const LayerDims &D, const BwpTensors &T, v
     A.e3 = take(2 * kBMax * (F / 2)); A.e4 = take((size_t)2 * 4 * kBMax * d); A.e6 = take(2 * kBMax * d);
     A.spin_limit = P.spin_limit;
     A.pre_sleep = 1;
+    {
+        const char *ps = getenv("RT_BWD_PRE_SLEEPS");   // four digits: the pulls of phases G1, G2, G3a, G4
+        const bool ok = ps && strlen(ps) == 4;
+        // measured at cfg3 (ms per backward pass): 1,1,1,1 48.2; 1,2,1,1 47.8; 1,1,1,2 47.8; 1,2,1,2 47.3; 0,2,1,2 47.2; 1,3,1,2 47.2; 0,0,0,0 49.5
+        A.ps_g1 = ok ? ps[0] - '0' : 1; A.ps_g2 = ok ? ps[1] - '0' : 2; A.ps_g3 = ok ? ps[2] - '0' : 1; A.ps_g4 = ok ? ps[3] - '0' : 2;
+    }
     if (P.nonce >= 4095u) {   // the tags start over: no word of an earlier launch may survive
         hipError_t ce = bwp_clear(exchange, bwp_exchange_bytes(D.d, D.F), st);
         if (ce != hipSuccess) return ce;

@@ -224,7 +224,7 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
 template <int KS, int GW, typename ARGS>
 __device__ __forceinline__ void wg_gemv_ll_pair(const bf16_t *w1_s, const bf16_t *w2_s, int ldw, int R, const ll_t *act1,
                                                 const ll_t *act2, int B, unsigned tag, const ARGS &A, float *red, bf16_t *act_s,
-                                                int lda, int &fail)
+                                                int lda, int &fail, int pre_sleep_units = -1)
 {
     static_assert(GW % 2 == 0, "both words of a chunk belong to one batch row");
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -245,7 +245,8 @@ __device__ __forceinline__ void wg_gemv_ll_pair(const bf16_t *w1_s, const bf16_t
     const unsigned mine = need1;
     need2 = need1;
     long long spins = 0;
-    for (int i = 0; i < A.pre_sleep; ++i) __builtin_amdgcn_s_sleep(8);
+    const int pre_sleep = pre_sleep_units >= 0 ? pre_sleep_units : A.pre_sleep;
+    for (int i = 0; i < pre_sleep; ++i) __builtin_amdgcn_s_sleep(8);
     while (__any((need1 | need2) != 0)) {
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i) {
