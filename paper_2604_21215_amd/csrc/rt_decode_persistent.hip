@@ -347,6 +347,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
     RT_DEC_STAMP(5);
 
     // ================================================================ phase M: partial states -> a
+    bool committed = false;   // wavefront-uniform
     if (att && wave == 0) {
         float M = -INFINITY, L = 0.f, O = 0.f;
 #pragma unroll
@@ -359,18 +360,28 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
             ll_store(mine + lane, tag, __float_as_uint(O));
             if (lane < 2) ll_store(mine + 64 + lane, tag, __float_as_uint(lane == 0 ? M : L));
         } else {
-            // the temporary pair of this position (distance 0: no positional bias)
-            const ll_t *p2[2] = {A.qkv_ll + single_word<RQ>(d + uh * kHeadDim + lane, ub),
-                                 A.qkv_ll + single_word<RQ>(2 * d + uh * kHeadDim + lane, ub)};
+            // The weight slices go from registers to LDS first: the other workgroups' partial states are still crossing the chip,
+            // and the workgroup's barrier before phase O waits for this wavefront.
+            rows_commit<NBW, PER>(wreg, wo_s, A.ldw, n4, weight_gain);
+            committed = true;
+            // the temporary pair of this position (distance 0: no positional bias) and the first partial state in one round
+            const ll_t *src1 = A.part_ll + ((size_t)u * kDecMaxSplit + 1) * kPartWords;
+            const ll_t *p4[4] = {A.qkv_ll + single_word<RQ>(d + uh * kHeadDim + lane, ub),
+                                 A.qkv_ll + single_word<RQ>(2 * d + uh * kHeadDim + lane, ub), src1 + lane, src1 + 64 + (lane & 1)};
+            const bool on4[4] = {true, true, S > 1, S > 1};
             const bool on2[2] = {true, true};
-            ll_t w2[2];
-            ll_wait_n<2>(p2, on2, tag, A, w2, fail);
-            float kt = __uint_as_float((unsigned)w2[0]);
-            const float vt = bf16_to_f32(f32_to_bf16(__uint_as_float((unsigned)w2[1])));
+            ll_t w4[4];
+            ll_wait_n<4>(p4, on4, tag, A, w4, fail);
+            float kt = __uint_as_float((unsigned)w4[0]);
+            const float vt = bf16_to_f32(f32_to_bf16(__uint_as_float((unsigned)w4[1])));
             if (!A.norm_free)
                 kt *= rsqrtf(fast_sum(kt * kt) / (float)kHeadDim + A.eps) * gk_r;
             dec_combine(M, L, O, A.scale * fast_sum(qn * kt), 1.f, vt);
-            for (int sp = 1; sp < S; ++sp) {
+            if (S > 1) {
+                const float ml = __uint_as_float((unsigned)w4[3]);
+                dec_combine(M, L, O, lane_bcast(ml, 0), lane_bcast(ml, 1), __uint_as_float((unsigned)w4[2]));
+            }
+            for (int sp = 2; sp < S; ++sp) {
                 const ll_t *src = A.part_ll + ((size_t)u * kDecMaxSplit + sp) * kPartWords;
                 const ll_t *pp[2] = {src + lane, src + 64 + (lane & 1)};
                 ll_t wp[2];
@@ -385,7 +396,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
                          (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
         }
     }
-    rows_commit<NBW, PER>(wreg, wo_s, A.ldw, n4, weight_gain);
+    if (!committed) rows_commit<NBW, PER>(wreg, wo_s, A.ldw, n4, weight_gain);
     RT_DEC_ABORT_IF(fail);
     RT_DEC_STAMP(6);
 
