@@ -31,6 +31,11 @@ __device__ __forceinline__ float dpp_f(float v, int ctrl_sel)
     }
     return __int_as_float(r);
 }
+// value of lane + 1 for the even lanes (quad_perm [1,1,3,3]): the partner of a bf16 pair without the LDS crossbar
+__device__ __forceinline__ float dpp_odd_neighbour(float v)
+{
+    return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xF5, 0xF, 0xF, true));
+}
 __device__ __forceinline__ float fast_sum(float v)
 {
     v += dpp_f(v, 0);

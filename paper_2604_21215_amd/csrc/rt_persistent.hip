@@ -380,6 +380,8 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
             const int b = u / A.H, h = u - b * A.H;
             float q = cq, m = cm, l = cl, o = co;   // pre-merged one phase ahead
             // (2) the newest key: position t-1's raw k, v arrive from phase KV, are finished and stored here
+            float kr = 0.f;
+            bf16_t kb = 0, vb = 0;
             if (t >= 1) {
                 const ll_t *p[6];
                 bool act[6];
@@ -404,9 +406,29 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                 const float Sz = fast_sum(ss), Sk = fast_sum(k0 * k0), Sq = fast_sum(q * kg);
                 const float rz = A.norm_free ? 1.f : rsqrtf(Sz / (float)d + A.eps);
                 const float kscale = A.norm_free ? 1.f : rz * rsqrtf(rz * rz * Sk / (float)kHeadDim + A.eps);
-                const float kr = kg * kscale;
+                kr = kg * kscale;
                 const float vr = __uint_as_float((unsigned)w6[5]) * rz;
-                const bf16_t kb = f32_to_bf16(kr), vb = f32_to_bf16(vr);
+                kb = f32_to_bf16(kr);
+                vb = f32_to_bf16(vr);
+                if (t < A.N) {
+                    // the newest key is one position before the query
+                    const float sn = ALIBI ? A.scale * (Sq * kscale) - alibi_slope(A.alibi, h, A.H) : A.scale * (Sq * kscale);
+                    const float m_new = fmaxf(m, sn);
+                    const float e1 = __expf(m - m_new), e2 = __expf(sn - m_new);
+                    l = l * e1 + e2;
+                    o = o * e1 + bf16_to_f32(vb) * e2;
+                    m = m_new;
+                }
+            }
+            if (t < A.N) {
+                const float av = o * __builtin_amdgcn_rcpf(l);   // a crosses the chip as bf16
+                const float an = dpp_odd_neighbour(av);
+                if (!(lane & 1))
+                    ll_store(A.a_ll + par * half_d + pair_word<32>(h * kHeadDim + lane, b), tag,
+                             (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
+            }
+            // the stores of the finished pair follow a: only a is on the critical path of the position
+            if (t >= 1) {
                 const size_t off = (size_t)(t - 1) * rs + (size_t)u * kHeadDim + lane;
                 A.K[off] = kb;
                 A.V[off] = vb;
@@ -439,22 +461,6 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
                             A.VT[((size_t)u * kHeadDim + lane) * A.vt_stride + k] = win_v[(ring + (k & (A.win_rows - 1))) * kHeadDim + lane];
                     }
                 }
-                if (t < A.N) {
-                    // the newest key is one position before the query
-                    const float sn = ALIBI ? A.scale * (Sq * kscale) - alibi_slope(A.alibi, h, A.H) : A.scale * (Sq * kscale);
-                    const float m_new = fmaxf(m, sn);
-                    const float e1 = __expf(m - m_new), e2 = __expf(sn - m_new);
-                    l = l * e1 + e2;
-                    o = o * e1 + bf16_to_f32(vb) * e2;
-                    m = m_new;
-                }
-            }
-            if (t < A.N) {
-                const float av = o / l;
-                const float an = __shfl_down(av, 1, 64);
-                if (!(lane & 1))
-                    ll_store(A.a_ll + par * half_d + pair_word<32>(h * kHeadDim + lane, b), tag,
-                             (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
             }
         }
         RT_ABORT_IF(fail);
