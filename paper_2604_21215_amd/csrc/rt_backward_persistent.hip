@@ -64,7 +64,7 @@ struct BwpArgs {
     unsigned long long *bar;
     long long spin_limit;
     int pre_sleep;
-    int ps_g1, ps_g2, ps_g3, ps_g4;   // waits before the first poll of the four pulls, units of 8 x 64 clocks
+    int ps_g1, ps_g2, ps_g3, ps_g4;   // waits before the first poll of the four pulls, units of 4 x 64 clocks
 };
 
 // Workgroup barrier behind which every wavefront leaves when any of them has given up waiting: that wavefront raises an LDS
@@ -554,12 +554,12 @@ hipError_t bwp_run_block(BwpState &P, const LayerDims &D, const BwpTensors &T, v
     A.e1k = take(2 * kBMax * (d / 2)); A.e1v = take(2 * kBMax * (d / 2)); A.e2 = take(2 * kBMax * (d / 2)); A.e5 = take(2 * kBMax * (d / 2));
     A.e3 = take(2 * kBMax * (F / 2)); A.e4 = take((size_t)2 * 4 * kBMax * d); A.e6 = take(2 * kBMax * d);
     A.spin_limit = P.spin_limit;
-    A.pre_sleep = 1;
+    A.pre_sleep = 2;   // units of 4 x 64 clocks
     {
         const char *ps = getenv("RT_BWD_PRE_SLEEPS");   // four digits: the pulls of phases G1, G2, G3a, G4
         const bool ok = ps && strlen(ps) == 4;
-        // measured at cfg3 (ms per backward pass): 1,1,1,1 48.2; 1,2,1,1 47.8; 1,1,1,2 47.8; 1,2,1,2 47.3; 0,2,1,2 47.2; 1,3,1,2 47.2; 0,0,0,0 49.5
-        A.ps_g1 = ok ? ps[0] - '0' : 1; A.ps_g2 = ok ? ps[1] - '0' : 2; A.ps_g3 = ok ? ps[2] - '0' : 1; A.ps_g4 = ok ? ps[3] - '0' : 2;
+        // measured at cfg3 (ms per backward pass, units of 8 x 64 clocks): 1,1,1,1 48.2; 1,2,1,1 47.8; 1,1,1,2 47.8; 1,2,1,2 47.3; 0,2,1,2 47.2; 1,3,1,2 47.2; 0,0,0,0 49.5
+        A.ps_g1 = ok ? ps[0] - '0' : 2; A.ps_g2 = ok ? ps[1] - '0' : 4; A.ps_g3 = ok ? ps[2] - '0' : 2; A.ps_g4 = ok ? ps[3] - '0' : 4;
     }
     if (P.nonce >= 4095u) {   // the tags start over: no word of an earlier launch may survive
         hipError_t ce = bwp_clear(exchange, bwp_exchange_bytes(D.d, D.F), st);

@@ -681,7 +681,7 @@ rt_status decode_coop_step(DecodeCoopState &P, const LayerDims &D, const Weights
     A.a_ll = (ll_t *)(p + s.a); A.h_ll = (ll_t *)(p + s.h); A.z_ll = (ll_t *)(p + s.z); A.u_ll = (ll_t *)(p + s.u);
     A.kv_ll = (ll_t *)(p + s.kv); A.zss_ll = (ll_t *)(p + s.zss); A.zp_ll = (ll_t *)(p + s.zp);
     A.spin_limit = P.spin_limit;
-    A.pre_sleep = 1;
+    A.pre_sleep = 2;   // units of 4 x 64 clocks
     A.trace = P.want_trace ? (unsigned long long *)(p + s.trace) : nullptr;
     // every word of the slab is written at most once per call and carries the call's number; when the numbers start
     // over, no word of an earlier call may survive (the abort word at bar[8] is only ever set, never cleared here)

@@ -165,7 +165,7 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
     long long spins = 0;
     // A poll that leaves before the producers' stores have landed costs a whole extra trip (about 1.2 us); measured,
     // a quarter of a microsecond of waiting first brings the average number of rounds from 1.5 to 1.1.
-    for (int i = 0; i < pre_sleep; ++i) __builtin_amdgcn_s_sleep(8);
+    for (int i = 0; i < pre_sleep; ++i) __builtin_amdgcn_s_sleep(4);
     while (__any(need != 0)) {
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i)
@@ -251,7 +251,7 @@ __device__ __forceinline__ void wg_gemv_ll_pair(const bf16_t *w1_s, const bf16_t
     need2 = need1;
     long long spins = 0;
     const int pre_sleep = pre_sleep_units >= 0 ? pre_sleep_units : A.pre_sleep;
-    for (int i = 0; i < pre_sleep; ++i) __builtin_amdgcn_s_sleep(8);
+    for (int i = 0; i < pre_sleep; ++i) __builtin_amdgcn_s_sleep(4);
     while (__any((need1 | need2) != 0)) {
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i) {

@@ -99,7 +99,7 @@ struct PersistArgs {
     unsigned long long *bar;    // [0] fenced-barrier counter, [8] abort word
     unsigned long long *trace;  // optional: [2][trace_rows][16] wall-clock stamps of workgroup 0 and of workgroup trace_wg
     int trace_wg, trace_rows;
-    int pre_sleep;              // units of 8 x 64 clocks a bulk pull waits before its first poll
+    int pre_sleep;              // units of 4 x 64 clocks a bulk pull waits before its first poll
     int ps_o, ps_1, ps_2a, ps_kv;   // the same per phase
     int early_premerge;         // the helper wavefront also combines the pre-merge (phase 2b) at positions without an event
     long long spin_limit;
@@ -818,18 +818,19 @@ rt_status persistent_prefill(PersistentState &P, const LayerDims &D, const Weigh
     A.R_2 = D.d / 64;
     A.bar = P.bar; A.trace = P.trace; A.spin_limit = P.spin_limit;
     A.trace_rows = P.trace_rows;
-    // Waits before the first poll of the pulls of phases O, 1, 2a, KV in units of 8 x 64 clocks (0.21 us): a poll that leaves
-    // before the producers' stores have landed costs a whole extra trip.  Measured at cfg3 (ms per call): 1,1,1,1 31.45;
-    // 1,2,1,1 30.80; 2,2,1,1 30.76; 2,2,1,0 30.5; 3,2,1,0 30.84; 2,3,1,0 30.91; 1,1,0,1 32.7; 1,1,1,2 31.8.
+    // Waits before the first poll of the pulls of phases O, 1, 2a, KV in units of 4 x 64 clocks (0.1 us): a poll that leaves
+    // before the producers' stores have landed costs a whole extra trip.  Measured at cfg3 (ms per call, units of 0.2 us):
+    // 1,1,1,1 31.45; 1,2,1,1 30.80; 2,2,1,1 30.76; 2,2,1,0 30.5; 3,2,1,0 30.84; 2,3,1,0 30.91; 1,1,0,1 32.7; 1,1,1,2 31.8.
+    // In units of 0.1 us: 4,4,2,0 30.2; 3,4,2,0 30.07; 5,4,2,0 30.43; 4,3,2,0 30.3; 4,4,1,0 30.6; 4,4,2,1 30.3.
     // RT_PRE_SLEEPS (four digits) or RT_PRE_SLEEP (one number for all four) override them.
-    A.pre_sleep = getenv("RT_PRE_SLEEP") ? atoi(getenv("RT_PRE_SLEEP")) : 1;
+    A.pre_sleep = getenv("RT_PRE_SLEEP") ? atoi(getenv("RT_PRE_SLEEP")) : 2;
     {
         const char *ps = getenv("RT_PRE_SLEEPS");
         const bool ok = ps && strlen(ps) == 4;
         const bool one = getenv("RT_PRE_SLEEP") != nullptr;
-        A.ps_o = ok ? ps[0] - '0' : (one ? A.pre_sleep : 2);
-        A.ps_1 = ok ? ps[1] - '0' : (one ? A.pre_sleep : 2);
-        A.ps_2a = ok ? ps[2] - '0' : (one ? A.pre_sleep : 1);
+        A.ps_o = ok ? ps[0] - '0' : (one ? A.pre_sleep : 3);
+        A.ps_1 = ok ? ps[1] - '0' : (one ? A.pre_sleep : 4);
+        A.ps_2a = ok ? ps[2] - '0' : (one ? A.pre_sleep : 2);
         A.ps_kv = ok ? ps[3] - '0' : (one ? A.pre_sleep : 0);
     }
     A.early_premerge = (getenv("RT_EARLY_PREMERGE") ? atoi(getenv("RT_EARLY_PREMERGE")) : 1) && P.win_rows != 0;
