@@ -210,7 +210,7 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
             }                                                                                                              \
         }                                                                                                                  \
         A.dkraw[off_] = du_;                                                                                               \
-        const float dun_ = __shfl_down(du_, 1, 64), dvn_ = __shfl_down((dv_), 1, 64);                                      \
+        const float dun_ = dpp_odd_neighbour(du_), dvn_ = dpp_odd_neighbour((dv_));                                        \
         if (!(lane & 1)) {                                                                                                 \
             ll_store(A.e1k + (par_) * half_d + pair_word<32>(uh_ * kHeadDim + lane, ub_), (tag_),                          \
                      (unsigned)f32_to_bf16(du_) | ((unsigned)f32_to_bf16(dun_) << 16));                                    \
@@ -380,29 +380,37 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
             const size_t off = (size_t)i * rs + (size_t)u * kHeadDim + lane;
             const float q = A.Qn[off], kt = A.Ktn[off], vt = A.Vt[off], cv = A.c[off];
             const float L = A.lse[(size_t)i * BH + u];
+            const int w = i - blk_lo;   // keys of the block before the query: slots 0 .. w - 1
+            // what does not need the gradient of the attention output is formed before the wait for it: the query's own
+            // weight and the logits of the window
+            const float p_own = __expf(A.scale * fast_sum(q * kt) - L);
+            const float *krow = winK + (size_t)min(lane, max(w - 1, 0)) * kWinLd, *vrow = winV + (size_t)min(lane, max(w - 1, 0)) * kWinLd;
+            float s = 0.f;
+            if (w > 0) {
+#pragma unroll
+                for (int c8 = 0; c8 < 8; ++c8) {
+                    float kk[8];
+                    load8(krow + c8 * 8, kk);
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) s = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], s);
+                }
+            }
             const ll_t wd = ll_wait(A.e6 + par * sz_d + single_word<RO>(h * kHeadDim + lane, b), true, tag, A, fail);
             const float g = __uint_as_float((unsigned)wd);
             const float Dsum = fast_sum(g * cv);
-            const float p_own = __expf(A.scale * fast_sum(q * kt) - L);
             const float ds_own = p_own * (fast_sum(g * vt) - Dsum);
             A.dvt[off] = p_own * g;
             A.dkt[off] = A.scale * ds_own * q;
             A.dq[off] = A.scale * ds_own * kt;
             if (lane == 0) A.Ds[(size_t)i * BH + u] = Dsum;
-            const int w = i - blk_lo;   // keys of the block before the query: slots 0 .. w - 1
             if (w > 0) {
-                const float *krow = winK + (size_t)min(lane, w - 1) * kWinLd, *vrow = winV + (size_t)min(lane, w - 1) * kWinLd;
-                float s = 0.f, dp = 0.f;
+                float dp = 0.f;
 #pragma unroll
                 for (int c8 = 0; c8 < 8; ++c8) {
-                    float kk[8], vv[8];
-                    load8(krow + c8 * 8, kk);
+                    float vv[8];
                     load8(vrow + c8 * 8, vv);
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        s = fmaf(lane_bcast(q, c8 * 8 + e), kk[e], s);
-                        dp = fmaf(lane_bcast(g, c8 * 8 + e), vv[e], dp);
-                    }
+                    for (int e = 0; e < 8; ++e) dp = fmaf(lane_bcast(g, c8 * 8 + e), vv[e], dp);
                 }
                 const float slope = alibi_slope(A.alibi, h, H);
                 const float p = lane < w ? __expf(fmaf(-slope, (float)(w - lane), s * A.scale) - L) : 0.f;
