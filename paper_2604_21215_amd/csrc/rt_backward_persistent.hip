@@ -273,7 +273,7 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
                 A.d_rz[(r0 + eb) * d + o_lo + erow] = drz;
                 wv = drz * gkv_o;
             }
-            const float wn = __shfl_down(wv, 16, 64);
+            const float wn = next_row(wv);
             if (!(erow & 1) && ep_o)
                 ll_store(A.e2 + par * half_d + pair_word<RO / 2>(o_lo + erow, eb), tag,
                          (unsigned)f32_to_bf16(wv) | ((unsigned)f32_to_bf16(wn) << 16));
@@ -298,7 +298,7 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
                 dp = e_gp * A.alpha * lin;
                 A.dpre[(r0 + eb) * F + f_lo + erow] = dp;
             }
-            const float dn = __shfl_down(dp, 16, 64);
+            const float dn = next_row(dp);
             if (!(erow & 1) && ep_f)
                 ll_store(A.e3 + par * half_F + pair_word<R1 / 2>(f_lo + erow, eb), tag,
                          (unsigned)f32_to_bf16(dp) | ((unsigned)f32_to_bf16(dn) << 16));
@@ -339,7 +339,7 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
                 A.t1[(r0 + eb) * d + o] = t1v;
                 w2v = t1v * gmlp_o;
             }
-            const float wn = __shfl_down(w2v, 16, 64);
+            const float wn = next_row(w2v);
             if (!(erow & 1) && ep_o)
                 ll_store(A.e5 + par * half_d + pair_word<RO / 2>(o, eb), tag,
                          (unsigned)f32_to_bf16(w2v) | ((unsigned)f32_to_bf16(wn) << 16));

@@ -407,7 +407,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
         float hv = 0.f;
         const int o = o_lo + erow;
         if (erow < o_n && eb < B) hv = xv + A.alpha * red_sum(red, erow, eb);
-        const float hn = __shfl_down(hv, 16, 64);
+        const float hn = next_row(hv);
         if (!(erow & 1) && erow < o_n && eb < B)
             ll_store(A.h_ll + pair_word<RO / 2>(o, eb), tag, (unsigned)f32_to_bf16(hv) | ((unsigned)f32_to_bf16(hn) << 16));
         h_loc[erow * kBMax + eb] = hv;
@@ -427,7 +427,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
             const float rinv = A.norm_free ? 1.f : rsqrtf(ssum / (float)d + A.eps);
             uv = gelu_bf16_out(red_sum(red, erow, eb) * rinv);   // u crosses the chip as bf16
         }
-        const float un = __shfl_down(uv, 16, 64);
+        const float un = next_row(uv);
         if (!(erow & 1) && erow < f_n && eb < B)
             ll_store(A.u_ll + pair_word<R1 / 2>(f_lo + erow, eb), tag, (unsigned)f32_to_bf16(uv) | ((unsigned)f32_to_bf16(un) << 16));
     }
@@ -462,7 +462,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
             zv = h_loc[erow * kBMax + eb] + A.alpha * acc;
             A.y[(size_t)eb * d + o] = f32_to_bf16(zv);
         }
-        const float zn = __shfl_down(zv, 16, 64);
+        const float zn = next_row(zv);
         if (!(erow & 1) && own)
             ll_store(A.z_ll + pair_word<RO / 2>(o, eb), tag, (unsigned)f32_to_bf16(zv) | ((unsigned)f32_to_bf16(zn) << 16));
         sq[erow * kBMax + eb] = zv * zv;

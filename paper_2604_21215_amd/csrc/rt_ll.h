@@ -36,6 +36,27 @@ __device__ __forceinline__ float dpp_odd_neighbour(float v)
 {
     return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xF5, 0xF, 0xF, true));
 }
+// Exchanges between the rows of 16 lanes and between the halves of a wavefront with v_permlane16_swap / v_permlane32_swap
+// (one vector instruction each instead of a trip through the LDS crossbar).  swap16(a, b) returns
+// {[a row 0, b row 0, a row 2, b row 2], [a row 1, b row 1, a row 3, b row 3]}, swap32(a, b) {[a low, b low], [a high, b high]}.
+// next_row: the value of lane + 16 for the lanes of rows 0 and 2 (the other lanes get their own value back).
+__device__ __forceinline__ float next_row(float v)
+{
+    const unsigned u = __float_as_uint(v);
+    return __uint_as_float(__builtin_amdgcn_permlane16_swap(u, u, false, false)[1]);
+}
+__device__ __forceinline__ float xor16(float v)   // value of lane ^ 16
+{
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane16_swap(u, u, false, false);
+    return __uint_as_float((threadIdx.x & 16) ? r[0] : r[1]);
+}
+__device__ __forceinline__ float xor32(float v)   // value of lane ^ 32
+{
+    const unsigned u = __float_as_uint(v);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    return __uint_as_float((threadIdx.x & 32) ? r[0] : r[1]);
+}
 __device__ __forceinline__ float fast_sum(float v)
 {
     v += dpp_f(v, 0);
@@ -214,8 +235,8 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
     }
     if (SS) {
         float ss = (ssp[0] + ssp[1]) + (ssp[2] + ssp[3]);
-        ss += __shfl_xor(ss, 16, 64);
-        ss += __shfl_xor(ss, 32, 64);
+        ss += xor16(ss);
+        ss += xor32(ss);
         if (g == 0) ss_s[wave * kBMax + l16] = ss;
     }
     float *r = red + ((size_t)wave * kRMax + 4 * g) * kBMax + l16;
@@ -343,8 +364,8 @@ __device__ __forceinline__ void wg_product_staged(const bf16_t *w_s, int ldw, in
     }
     if (SS) {
         float ss = (ssp[0] + ssp[1]) + (ssp[2] + ssp[3]);
-        ss += __shfl_xor(ss, 16, 64);
-        ss += __shfl_xor(ss, 32, 64);
+        ss += xor16(ss);
+        ss += xor32(ss);
         if (g == 0) ss_s[wave * kBMax + l16] = ss;
     }
     float *r = red + ((size_t)wave * kRMax + 4 * g) * kBMax + l16;
