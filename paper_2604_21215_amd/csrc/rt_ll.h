@@ -161,7 +161,18 @@ __device__ __forceinline__ uint4 lds_load16(const void *p)
 
 constexpr int kAuxAgent = 16;   // cache-policy operand of the buffer load: sc1 (agent scope)
 
-template <int KS, int GW, bool SS = false, typename ARGS>
+// Which wavefront pulls which chunks: when a wavefront's share of the contraction (KS * 32 elements of every batch row) is a
+// whole number of the layout's blocks (2 GW elements of all batch rows), the words it multiplies are one contiguous eighth of
+// the vector, and it pulls exactly those, still consecutive lanes on consecutive 16-byte chunks.  Its product then depends on
+// its own staging writes only: no workgroup barrier between pull and product (FULL_SYNC asks for one anyway: callers that
+// read whole staged rows afterwards), and a wavefront whose words are in starts multiplying while others still poll.
+__device__ __forceinline__ void wave_sync_lds()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+template <int KS, int GW, bool SS = false, bool FULL_SYNC = false, typename ARGS>
 __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, const ll_t *act, int B,
                                            unsigned tag, const ARGS &A, float *red, bf16_t *act_s, int lda, int &fail,
                                            float *ss_s = nullptr, int pre_sleep_units = -1)
@@ -172,6 +183,9 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
     constexpr int K = KS * 32 * kPW;
     constexpr int kWords = kBMax * K / 2;                   // words of the vector, unused batch rows included
     constexpr int kMaxChunks = kWords / 2 / kPThreads;      // 16-byte chunks per thread  (= 2 KS)
+    constexpr bool kWaveLocal = (KS * 32) % (2 * GW) == 0;
+    const int c0 = kWaveLocal ? wave * (kMaxChunks * 64) + lane : tid;   // chunk i of this thread: c0 + i * cstep
+    constexpr int cstep = kWaveLocal ? 64 : kPThreads;
     const __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<ll_t *>(act), 0, kWords * 8, 0x00020000);
     v4u_t v[kMaxChunks];
     unsigned need = 0;
@@ -179,7 +193,7 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
 #pragma unroll
     for (int i = 0; i < kMaxChunks; ++i) {
         v[i] = v4u_t{0u, 0u, 0u, 0u};
-        const int w0 = 2 * (i * kPThreads + tid);
+        const int w0 = 2 * (c0 + i * cstep);
         const int b0 = (w0 % (kBMax * GW)) / GW, b1 = ((w0 + 1) % (kBMax * GW)) / GW;
         if (b0 < B || b1 < B) need |= 1u << i;
     }
@@ -190,11 +204,11 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
     while (__any(need != 0)) {
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i)
-            if (need & (1u << i)) v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (i * kPThreads + tid) * 16, 0, kAuxAgent);
+            if (need & (1u << i)) v[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc, (c0 + i * cstep) * 16, 0, kAuxAgent);
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i)
             if (need & (1u << i)) {
-                const int w0 = 2 * (i * kPThreads + tid), w1 = w0 + 1;
+                const int w0 = 2 * (c0 + i * cstep), w1 = w0 + 1;
                 const int b0 = (w0 % (kBMax * GW)) / GW, b1 = (w1 % (kBMax * GW)) / GW;
                 const int k0 = 2 * ((w0 / (kBMax * GW)) * GW + w0 % GW), k1 = 2 * ((w1 / (kBMax * GW)) * GW + w1 % GW);
                 const bool u0 = b0 < B, u1 = b1 < B;
@@ -210,7 +224,8 @@ __device__ __forceinline__ void wg_gemv_ll(const bf16_t *w_s, int ldw, int R, co
             }
         if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
     }
-    __syncthreads();
+    if (kWaveLocal && !FULL_SYNC) wave_sync_lds();
+    else __syncthreads();
     const bool has_w = l16 < R, has_a = l16 < B;
     constexpr int kw = KS * 32;
     const bf16_t *wrow = w_s + (size_t)l16 * ldw + wave * kw + 8 * g;
@@ -258,6 +273,9 @@ __device__ __forceinline__ void wg_gemv_ll_pair(const bf16_t *w1_s, const bf16_t
     constexpr int K = KS * 32 * kPW;
     constexpr int kWords = kBMax * K / 2;
     constexpr int kMaxChunks = kWords / 2 / kPThreads;
+    constexpr bool kWaveLocal = (KS * 32) % (2 * GW) == 0;   // see wg_gemv_ll: then the three barriers below are wavefront-local
+    const int c0 = kWaveLocal ? wave * (kMaxChunks * 64) + lane : tid;
+    constexpr int cstep = kWaveLocal ? 64 : kPThreads;
     const __amdgpu_buffer_rsrc_t rsrc1 = __builtin_amdgcn_make_buffer_rsrc(const_cast<ll_t *>(act1), 0, kWords * 8, 0x00020000);
     const __amdgpu_buffer_rsrc_t rsrc2 = __builtin_amdgcn_make_buffer_rsrc(const_cast<ll_t *>(act2), 0, kWords * 8, 0x00020000);
     v4u_t v1[kMaxChunks], v2[kMaxChunks];
@@ -265,7 +283,7 @@ __device__ __forceinline__ void wg_gemv_ll_pair(const bf16_t *w1_s, const bf16_t
 #pragma unroll
     for (int i = 0; i < kMaxChunks; ++i) {
         v1[i] = v2[i] = v4u_t{0u, 0u, 0u, 0u};
-        const int w0 = 2 * (i * kPThreads + tid);
+        const int w0 = 2 * (c0 + i * cstep);
         if ((w0 % (kBMax * GW)) / GW < B) need1 |= 1u << i;
     }
     const unsigned mine = need1;
@@ -276,13 +294,13 @@ __device__ __forceinline__ void wg_gemv_ll_pair(const bf16_t *w1_s, const bf16_t
     while (__any((need1 | need2) != 0)) {
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i) {
-            if (need1 & (1u << i)) v1[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc1, (i * kPThreads + tid) * 16, 0, kAuxAgent);
-            if (need2 & (1u << i)) v2[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc2, (i * kPThreads + tid) * 16, 0, kAuxAgent);
+            if (need1 & (1u << i)) v1[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc1, (c0 + i * cstep) * 16, 0, kAuxAgent);
+            if (need2 & (1u << i)) v2[i] = __builtin_amdgcn_raw_buffer_load_b128(rsrc2, (c0 + i * cstep) * 16, 0, kAuxAgent);
         }
 #pragma unroll
         for (int i = 0; i < kMaxChunks; ++i) {
             if ((need1 & (1u << i)) && v1[i][1] == tag && v1[i][3] == tag) {
-                const int w0 = 2 * (i * kPThreads + tid);
+                const int w0 = 2 * (c0 + i * cstep);
                 const int b0 = (w0 % (kBMax * GW)) / GW, k0 = 2 * ((w0 / (kBMax * GW)) * GW + w0 % GW);
                 *reinterpret_cast<uint2 *>(act_s + (size_t)b0 * lda + k0) = make_uint2(v1[i][0], v1[i][2]);
                 need1 &= ~(1u << i);
@@ -291,7 +309,7 @@ __device__ __forceinline__ void wg_gemv_ll_pair(const bf16_t *w1_s, const bf16_t
         }
         if (++spins > A.spin_limit || ((spins & 255) == 0 && ll_load(A.bar + 8) != 0)) { fail = 1; break; }
     }
-    __syncthreads();
+    if (kWaveLocal) wave_sync_lds(); else __syncthreads();
     const bool has_w = l16 < R, has_a = l16 < B;
     constexpr int kw = KS * 32;
     const bf16_t *arow = act_s + (size_t)l16 * lda + wave * kw + 8 * g;
@@ -307,15 +325,15 @@ __device__ __forceinline__ void wg_gemv_ll_pair(const bf16_t *w1_s, const bf16_t
             acc = mfma16(a, b, acc);
         }
     }
-    __syncthreads();   // every wavefront has read the first vector's rows
+    if (kWaveLocal) wave_sync_lds(); else __syncthreads();   // the first vector's rows have been read
 #pragma unroll
     for (int i = 0; i < kMaxChunks; ++i)
         if (mine & (1u << i)) {
-            const int w0 = 2 * (i * kPThreads + tid);
+            const int w0 = 2 * (c0 + i * cstep);
             const int b0 = (w0 % (kBMax * GW)) / GW, k0 = 2 * ((w0 / (kBMax * GW)) * GW + w0 % GW);
             *reinterpret_cast<uint2 *>(act_s + (size_t)b0 * lda + k0) = make_uint2(v2[i][0], v2[i][2]);
         }
-    __syncthreads();
+    if (kWaveLocal) wave_sync_lds(); else __syncthreads();
     {
         const bf16_t *wrow = w2_s + (size_t)l16 * ldw + wave * kw + 8 * g;
 #pragma unroll
