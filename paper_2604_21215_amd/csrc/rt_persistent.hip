@@ -361,8 +361,13 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         const unsigned ptag = A.tag_base | (unsigned)t;        // words produced at position t-1
         int fail = 0;
         if (t < A.N) RT_STAMP(0);
-        float xv = 0.f;   // residual input of this workgroup's rows, fetched ahead of phase O
-        if (t < A.N && tid < kRMax * kBMax && erow < o_n && eb < B) xv = bf16_to_f32(A.x[((size_t)eb * A.N + t) * d + o_lo + erow]);
+        // The residual input of this workgroup's rows is fetched ahead of phase O - by wavefront 1, into LDS (sq is free until
+        // phase 1): the rows' epilogue threads sit in wavefront 0, which is the merging wavefront, and a wavefront gets its
+        // loads back in issue order: this read of x comes from HBM and would hold up phase M's polls behind it.
+        if (t < A.N && wave == 1) {
+            const int xr = lane >> 4, xb = lane & 15;
+            if (xr < o_n && xb < B) sq[xr * kBMax + xb] = bf16_to_f32(A.x[((size_t)xb * A.N + t) * d + o_lo + xr]);
+        }
         // At a position without a cross-block event the stored states that the next position's pre-merge reads are complete
         // already, so the helper wavefront fetches them during phase M (it is idle there), combines them with the window in
         // phase 2b (idle again) and leaves the finished state in LDS: the owning wavefront then has nothing to do behind the
@@ -545,7 +550,7 @@ __global__ __launch_bounds__(kPThreads) void persistent_kernel(PersistArgs A)
         if (tid < kRMax * kBMax) {
             float hv = 0.f;
             const int o = o_lo + erow;
-            if (erow < o_n && eb < B) hv = xv + A.alpha * red_sum(red, erow, eb);
+            if (erow < o_n && eb < B) hv = sq[erow * kBMax + eb] + A.alpha * red_sum(red, erow, eb);
             const float hn = next_row(hv);
             if (!(erow & 1) && erow < o_n && eb < B)
                 ll_store(A.h_ll + par * half_d + pair_word<RO / 2>(o, eb), tag,
