@@ -80,20 +80,24 @@ struct BwpArgs {
         }                                                                                                               \
     } while (0)
 
-// <unit row, staged bf16 vector> of batch row `wave` (B <= 8: one wavefront per batch row), u16 = this lane's 16
-// elements of the unit row (elements 16 lane .. 16 lane + 15 of each 1024-element stripe are not used: the lane owns
-// elements lane * PER .. + PER - 1 with PER = d / 64)
+// This wavefront's part of <unit row, staged bf16 vector> for every batch row: the wavefront owns the KS * 32 elements of
+// every staged row that it has pulled itself, eight lanes per batch row (b = lane / 8) with PER = KS * 4 elements each;
+// u = those elements of the unit row.  Lanes lane % 8 == 0 return the part of their batch row (B <= 8).  No other
+// wavefront's staging is read: this runs behind the wavefront's own pull, not behind a workgroup barrier.
 template <int PER>
-__device__ __forceinline__ float row_dot(const float (&u)[PER], const bf16_t *act_row, int lane)
+__device__ __forceinline__ float row_dot_part(const float (&u)[PER], const bf16_t *act_mine, int lane)
 {
     float s = 0.f;
 #pragma unroll
     for (int e = 0; e < PER; e += 2) {
-        const unsigned pr = *reinterpret_cast<const unsigned *>(act_row + lane * PER + e);
+        const unsigned pr = *reinterpret_cast<const unsigned *>(act_mine + e);
         s = fmaf(u[e], __uint_as_float(pr << 16), s);
         s = fmaf(u[e + 1], __uint_as_float(pr & 0xFFFF0000u), s);
     }
-    return fast_sum(s);
+    s += dpp_f(s, 0);
+    s += dpp_f(s, 1);
+    s += dpp_f(s, 2);   // the eight lanes of a batch row (half a row of 16 lanes)
+    return s;
 }
 
 // KSD = d / 256.  One workgroup per compute unit, 512 threads.
@@ -108,6 +112,7 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
     const int d = A.d, F = A.F, B = A.B, BH = A.BH, H = A.H;
     constexpr int RO = 2 * ((KSD + 1) / 2), R1 = 4 * KSD;
     constexpr int PER = 4 * KSD;   // elements of a d-long row per lane
+    static_assert((KSD * 32) % RO == 0, "a wavefront pulls exactly the slice of the d-long vectors that it multiplies (wg_gemv_ll)");
 
     // ---- LDS carve-up
     bf16_t *wk_s = reinterpret_cast<bf16_t *>(smem);                 // Wk^T rows  [R_o][ldw]
@@ -121,9 +126,9 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
     float *gz_loc = w_loc + kRMax * kBMax;
     float *cw_loc = gz_loc + kRMax * kBMax;
     float *w2_loc = cw_loc + kRMax * kBMax;
-    float *dot_s = w2_loc + kRMax * kBMax;                            // [kBMax]
-    float *dot2_s = dot_s + kBMax;
-    float *winK = dot2_s + kBMax;                                     // [32][kWinLd] keys of the block (this workgroup's (b, h))
+    float *dot_s = w2_loc + kRMax * kBMax;                            // [kPW][kBMax]: one part per wavefront
+    float *dot2_s = dot_s + kPW * kBMax;
+    float *winK = dot2_s + kPW * kBMax;                                     // [32][kWinLd] keys of the block (this workgroup's (b, h))
     float *winV = winK + kBwpBlock * kWinLd;
     float *accK = winV + kBwpBlock * kWinLd;                          // [32][64] dK, dV of the block's positions
     float *accV = accK + kBwpBlock * kHeadDim;
@@ -196,8 +201,6 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
     {                                                                                                                      \
         const int ub_ = my_u / H, uh_ = my_u - ub_ * H;                                                                    \
         const size_t off_ = (size_t)(ipos_) * rs + (size_t)my_u * kHeadDim + lane;                                         \
-        A.dK[off_] = (dk_);                                                                                                \
-        A.dV[off_] = (dv_);                                                                                                \
         float du_ = (dk_);                                                                                                 \
         if (!A.norm_free) {                                                                                                \
             const float wv_ = (dk_) * gk_u;                                                                                \
@@ -209,7 +212,6 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
                 rk_nx = A.rk[rbn_ * H + uh_];                                                                              \
             }                                                                                                              \
         }                                                                                                                  \
-        A.dkraw[off_] = du_;                                                                                               \
         const float dun_ = dpp_odd_neighbour(du_), dvn_ = dpp_odd_neighbour((dv_));                                        \
         if (!(lane & 1)) {                                                                                                 \
             ll_store(A.e1k + (par_) * half_d + pair_word<32>(uh_ * kHeadDim + lane, ub_), (tag_),                          \
@@ -217,6 +219,9 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
             ll_store(A.e1v + (par_) * half_d + pair_word<32>(uh_ * kHeadDim + lane, ub_), (tag_),                          \
                      (unsigned)f32_to_bf16((dv_)) | ((unsigned)f32_to_bf16(dvn_) << 16));                                  \
         }                                                                                                                  \
+        A.dK[off_] = (dk_);                                                                                                \
+        A.dV[off_] = (dv_);                                                                                                \
+        A.dkraw[off_] = du_;                                                                                               \
     }
     if (has_u && A.i_hi >= A.i_lo) {
         const int slot = A.i_hi - blk_lo;
@@ -247,10 +252,11 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
                 e_gp = A.gp[f]; e_agy = A.A_gy[f]; e_auz = A.A_uz[f];
             }
         }
-        // the normalised rows of batch row `wave` for the two row-wide sums (B <= 8)
+        // this wavefront's slice of the normalised rows of every batch row, for its parts of the two row-wide sums (B <= 8)
         float uz[PER], uh[PER];
-        if (wave < B) {
-            const float *pz = A.unit_z + (r0 + wave) * d + lane * PER, *ph = A.unit_h + (r0 + wave) * d + lane * PER;
+        const int db = lane >> 3, dcol = wave * (KSD * 32) + (lane & 7) * PER;
+        if (db < B) {
+            const float *pz = A.unit_z + (r0 + db) * d + dcol, *ph = A.unit_h + (r0 + db) * d + dcol;
 #pragma unroll
             for (int e = 0; e < PER; e += 4) {
                 const float4 a = *reinterpret_cast<const float4 *>(pz + e), b4 = *reinterpret_cast<const float4 *>(ph + e);
@@ -283,28 +289,33 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
 
         // ================================================================ G2: dot, W2^T w, Wo^T w; dpre rows, Gz rows
         wg_gemv_ll<KSD, RO / 2>(w2_s, A.ldw, f_n, A.e2 + par * half_d, B, tag, A, red, act_s, A.ldw, fail, nullptr, A.ps_g2);
-        RT_BWP_ABORT_IF(fail);
+        // the second product and this wavefront's part of the row-wide sum read only what the wavefront staged itself: both
+        // run before the barrier
         wg_product_staged<KSD>(wo_s, A.ldw, o_n, B, red2, act_s, A.ldw);
-        if (wave < B) {
-            const float dt = A.norm_free ? 0.f : row_dot<PER>(uz, act_s + (size_t)wave * A.ldw, lane);
-            if (lane == 0) dot_s[wave] = dt;
+        {
+            const float dt = (A.norm_free || db >= B) ? 0.f : row_dot_part<PER>(uz, act_s + (size_t)min(db, B - 1) * A.ldw + dcol, lane);
+            if ((lane & 7) == 0) dot_s[wave * kBMax + db] = dt;
         }
-        __syncthreads();
+        RT_BWP_ABORT_IF(fail);
         if (tid < kRMax * kBMax) {
-            float dp = 0.f;
+            float dp = 0.f, dot = 0.f;
+            if (ep) {
+#pragma unroll
+                for (int w = 0; w < kPW; ++w) dot += dot_s[w * kBMax + eb];
+            }
             if (ep_f) {
                 const float v = red_sum(red, erow, eb);
-                const float lin = A.norm_free ? e_agy + v : e_agy + e_rz * (v - dot_s[eb] * inv_d * e_auz);
+                const float lin = A.norm_free ? e_agy + v : e_agy + e_rz * (v - dot * inv_d * e_auz);
                 dp = e_gp * A.alpha * lin;
-                A.dpre[(r0 + eb) * F + f_lo + erow] = dp;
             }
             const float dn = next_row(dp);
             if (!(erow & 1) && ep_f)
                 ll_store(A.e3 + par * half_F + pair_word<R1 / 2>(f_lo + erow, eb), tag,
                          (unsigned)f32_to_bf16(dp) | ((unsigned)f32_to_bf16(dn) << 16));
+            if (ep_f) A.dpre[(r0 + eb) * F + f_lo + erow] = dp;
             if (ep_o) {
                 const float wv = w_loc[erow * kBMax + eb];
-                const float gz = A.norm_free ? e_gy + wv : e_gy + e_rz * (wv - e_uz * dot_s[eb] * inv_d);
+                const float gz = A.norm_free ? e_gy + wv : e_gy + e_rz * (wv - e_uz * dot * inv_d);
                 A.Gz[(r0 + eb) * d + o_lo + erow] = gz;
                 gz_loc[erow * kBMax + eb] = gz;
                 cw_loc[erow * kBMax + eb] = red_sum(red2, erow, eb);
@@ -349,12 +360,11 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
 
         // ================================================================ G4: dot2, Wo^T w2; dc rows, dh rows
         wg_gemv_ll<KSD, RO / 2>(wo_s, A.ldw, o_n, A.e5 + par * half_d, B, tag, A, red, act_s, A.ldw, fail, nullptr, A.ps_g4);
-        RT_BWP_ABORT_IF(fail);
-        if (wave < B) {
-            const float dt = A.norm_free ? 0.f : row_dot<PER>(uh, act_s + (size_t)wave * A.ldw, lane);
-            if (lane == 0) dot2_s[wave] = dt;
+        {   // this wavefront's part of the second row-wide sum, before the barrier (see G2)
+            const float dt = (A.norm_free || db >= B) ? 0.f : row_dot_part<PER>(uh, act_s + (size_t)min(db, B - 1) * A.ldw + dcol, lane);
+            if ((lane & 7) == 0) dot2_s[wave * kBMax + db] = dt;
         }
-        __syncthreads();
+        RT_BWP_ABORT_IF(fail);
         if (tid < kRMax * kBMax && ep_o) {
             const int o = o_lo + erow;
             const float v = red_sum(red, erow, eb), cw = cw_loc[erow * kBMax + eb];
@@ -364,17 +374,22 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
                 dcv = A.alpha * (e_cgy + cw + v);
                 dh = gz + w2v;
             } else {
-                const float k1 = dot_s[eb] * inv_d, k2 = dot2_s[eb] * inv_d;
+                float k1 = 0.f, k2 = 0.f;
+#pragma unroll
+                for (int w = 0; w < kPW; ++w) { k1 += dot_s[w * kBMax + eb]; k2 += dot2_s[w * kBMax + eb]; }
+                k1 *= inv_d; k2 *= inv_d;
                 dcv = A.alpha * (e_cgy + e_rz * (cw - k1 * e_cuz) + e_rh * (v - k2 * e_cuh));
                 dh = gz + e_rh * (w2v - e_uh * k2);
             }
+            ll_store(A.e6 + par * sz_d + single_word<RO>(o, eb), tag, __float_as_uint(dcv));
             A.dc[(r0 + eb) * d + o] = dcv;
             A.d_h[(r0 + eb) * d + o] = dh;
-            ll_store(A.e6 + par * sz_d + single_word<RO>(o, eb), tag, __float_as_uint(dcv));
         }
         __syncthreads();
 
         // ================================================================ A: softmax backward of query i
+        float t_p = 0.f, t_ds = 0.f, t_g = 0.f, t_q = 0.f;   // for the older slots, updated behind the barrier below
+        int t_w = 0;
         if (has_u) {
             const int u = my_u, b = u / H, h = u - b * H;
             const size_t off = (size_t)i * rs + (size_t)u * kHeadDim + lane;
@@ -399,10 +414,6 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
             const float g = __uint_as_float((unsigned)wd);
             const float Dsum = fast_sum(g * cv);
             const float ds_own = p_own * (fast_sum(g * vt) - Dsum);
-            A.dvt[off] = p_own * g;
-            A.dkt[off] = A.scale * ds_own * q;
-            A.dq[off] = A.scale * ds_own * kt;
-            if (lane == 0) A.Ds[(size_t)i * BH + u] = Dsum;
             if (w > 0) {
                 float dp = 0.f;
 #pragma unroll
@@ -422,28 +433,37 @@ __global__ __launch_bounds__(kPThreads) void bwp_kernel(BwpArgs A)
                     const float dkn = fmaf(A.scale * lane_bcast(ds, j), q, accK[j * kHeadDim + lane]);
                     RT_BWP_PHASE_U(i - 1, par ^ 1, tag + 1u, dkn, dvn)
                 }
-                // the older slots eight keys at a time: all reads of a group before its writes (one key per trip is a chain of
-                // dependent LDS round trips)
-                for (int j0 = 0; j0 < w - 1; j0 += 8) {
-                    float av[8], ak[8];
+                t_p = p; t_ds = ds; t_g = g; t_q = q; t_w = w;
+            }
+            // the query's own gradients follow the pair gradient of the next position: only that one is waited for
+            A.dvt[off] = p_own * g;
+            A.dkt[off] = A.scale * ds_own * q;
+            A.dq[off] = A.scale * ds_own * kt;
+            if (lane == 0) A.Ds[(size_t)i * BH + u] = Dsum;
+        }
+        // every other wavefront goes on as soon as the pair gradient has left; the owner follows after the older slots
+        RT_BWP_ABORT_IF(fail);
+        if (has_u && t_w > 1) {
+            // the older slots eight keys at a time: all reads of a group before its writes (one key per trip is a chain of
+            // dependent LDS round trips)
+            for (int j0 = 0; j0 < t_w - 1; j0 += 8) {
+                float av[8], ak[8];
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int j = min(j0 + e, w - 2);
-                        av[e] = accV[j * kHeadDim + lane];
-                        ak[e] = accK[j * kHeadDim + lane];
-                    }
+                for (int e = 0; e < 8; ++e) {
+                    const int j = min(j0 + e, t_w - 2);
+                    av[e] = accV[j * kHeadDim + lane];
+                    ak[e] = accK[j * kHeadDim + lane];
+                }
 #pragma unroll
-                    for (int e = 0; e < 8; ++e) {
-                        const int j = j0 + e;
-                        if (j < w - 1) {   // wavefront-uniform
-                            accV[j * kHeadDim + lane] = fmaf(lane_bcast(p, j), g, av[e]);
-                            accK[j * kHeadDim + lane] = fmaf(A.scale * lane_bcast(ds, j), q, ak[e]);
-                        }
+                for (int e = 0; e < 8; ++e) {
+                    const int j = j0 + e;
+                    if (j < t_w - 1) {   // wavefront-uniform
+                        accV[j * kHeadDim + lane] = fmaf(lane_bcast(t_p, j), t_g, av[e]);
+                        accK[j * kHeadDim + lane] = fmaf(A.scale * lane_bcast(t_ds, j), t_q, ak[e]);
                     }
                 }
             }
         }
-        RT_BWP_ABORT_IF(fail);
     }
 }
 
@@ -476,7 +496,7 @@ size_t lds_bytes(int d, int F, int G)
     const size_t ldw = d + 8;
     size_t b = ((size_t)(3 * R_o + R_1 + d / 64) * ldw) * 2;
     b = (b + 15) / 16 * 16;
-    b += (size_t)(2 * kPW * kRMax * kBMax + 4 * kRMax * kBMax + 2 * kBMax) * 4;
+    b += (size_t)(2 * kPW * kRMax * kBMax + 4 * kRMax * kBMax + 2 * kPW * kBMax) * 4;
     b += (size_t)(2 * kBwpBlock * kWinLd + 2 * kBwpBlock * kHeadDim) * 4;
     b = (b + 15) / 16 * 16;
     b += (size_t)8 * ldw * 2;
@@ -567,7 +587,7 @@ hipError_t bwp_run_block(BwpState &P, const LayerDims &D, const BwpTensors &T, v
         const char *ps = getenv("RT_BWD_PRE_SLEEPS");   // four digits: the pulls of phases G1, G2, G3a, G4
         const bool ok = ps && strlen(ps) == 4;
         // measured at cfg3 (ms per backward pass, units of 8 x 64 clocks): 1,1,1,1 48.2; 1,2,1,1 47.8; 1,1,1,2 47.8; 1,2,1,2 47.3; 0,2,1,2 47.2; 1,3,1,2 47.2; 0,0,0,0 49.5
-        A.ps_g1 = ok ? ps[0] - '0' : 2; A.ps_g2 = ok ? ps[1] - '0' : 4; A.ps_g3 = ok ? ps[2] - '0' : 2; A.ps_g4 = ok ? ps[3] - '0' : 4;
+        A.ps_g1 = ok ? ps[0] - '0' : 0; A.ps_g2 = ok ? ps[1] - '0' : 4; A.ps_g3 = ok ? ps[2] - '0' : 2; A.ps_g4 = ok ? ps[3] - '0' : 4;
     }
     if (P.nonce >= 4095u) {   // the tags start over: no word of an earlier launch may survive
         hipError_t ce = bwp_clear(exchange, bwp_exchange_bytes(D.d, D.F), st);
