@@ -389,8 +389,8 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
                 const float ml = __uint_as_float((unsigned)wp[1]);
                 dec_combine(M, L, O, lane_bcast(ml, 0), lane_bcast(ml, 1), __uint_as_float((unsigned)wp[0]));
             }
-            const float av = O / L;
-            const float an = __shfl_down(av, 1, 64);
+            const float av = O * __builtin_amdgcn_rcpf(L);   // a crosses the chip as bf16
+            const float an = dpp_odd_neighbour(av);
             if (!(lane & 1))
                 ll_store(A.a_ll + pair_word<32>(uh * kHeadDim + lane, ub), tag,
                          (unsigned)f32_to_bf16(av) | ((unsigned)f32_to_bf16(an) << 16));
@@ -502,11 +502,12 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
 #pragma unroll
         for (int i = 0; i < 4; ++i)
             if (on6[i]) ssum += __uint_as_float((unsigned)w6[i]);
-        const float rz = A.norm_free ? 1.f : rsqrtf(fast_sum(ssum) / (float)d + A.eps);
-        float kr = __uint_as_float((unsigned)w6[4]) * rz;
+        // |z|^2 and |k|^2 of the raw key are independent reductions; the scales multiply the finished sums
+        const float k0 = __uint_as_float((unsigned)w6[4]);
+        const float Sz = fast_sum(ssum), Sk = fast_sum(k0 * k0);
+        const float rz = A.norm_free ? 1.f : rsqrtf(Sz / (float)d + A.eps);
+        const float kr = A.norm_free ? k0 : k0 * gk_r * (rz * rsqrtf(rz * rz * Sk / (float)kHeadDim + A.eps));
         const float vr = __uint_as_float((unsigned)w6[5]) * rz;
-        if (!A.norm_free)
-            kr *= rsqrtf(fast_sum(kr * kr) / (float)kHeadDim + A.eps) * gk_r;
         if (!fail) {
             const size_t off = (size_t)t * rs + (size_t)u * kHeadDim + lane;
             A.K[off] = f32_to_bf16(kr);
