@@ -191,6 +191,13 @@ def test_persistent_small_and_ragged(oracle, B, N):
     _run_case(oracle, "bf16", B, N, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_PERSISTENT, expect_engine="persistent")
 
 
+def test_persistent_full_batch_at_the_headline_width(oracle):
+    """B = 16, d = 1024: every one of the 256 workgroups owns a (b, h) (merging and helper wavefront in each), 16 batch rows
+    fill the matrix instructions' column dimension and the staged activations take their largest LDS share."""
+    b = _flags()
+    _run_case(oracle, "bf16", 16, 100, 1024, 16, 4096, flags=b.RT_FLAG_ENGINE_PERSISTENT, expect_engine="persistent")
+
+
 def test_persistent_gains_scales_levels(oracle):
     b = _flags()
     _run_case(oracle, "bf16", 3, 300, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_PERSISTENT, gains="random", alpha=0.7,
