@@ -104,6 +104,7 @@ def test_backward_fp32_without_pair_gradients(oracle):
 
 @pytest.mark.parametrize("B,N,d,H,F,scale,no_mfma", [(3, 200, 256, 4, 1024, 0.25, False), (8, 130, 512, 8, 2048, 0.125, False),
                                                      (2, 300, 1024, 16, 4096, 1.0, False),   # the headline width, unscaled logits
+                                                     (2, 100, 768, 12, 3072, 0.25, False),   # three contraction steps per wavefront
                                                      (5, 333, 192, 3, 448, 0.25, False),     # ragged tiles of the products
                                                      (3, 200, 256, 4, 1024, 0.25, True)])    # fp32 products on bf16 storage
 def test_backward_bf16_storage(oracle, B, N, d, H, F, scale, no_mfma):
