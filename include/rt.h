@@ -25,8 +25,8 @@
  * All pointers named "device" are device (HBM) addresses valid on rt_config.device.  The calls return
  * without synchronising, and their work is ordered on rt_config.stream: it starts after everything
  * enqueued there before the call, and whatever is enqueued there after the call sees its outputs.
- * Every entry point enqueues on that stream alone except rt_stack_prefill, which may put half of its
- * layers on a second stream the context owns, forked from and joined back into rt_config.stream by
+ * Every entry point enqueues on that stream alone except rt_stack_prefill, which puts two of its three
+ * groups of layers on streams the context owns, forked from and joined back into rt_config.stream by
  * events inside the call (see there).  The caller owns x, y, K, V and the weights; the context owns
  * only scratch memory.  No exceptions cross this boundary.
  */
@@ -161,9 +161,10 @@ rt_status rt_decode_step_static(const rt_config *cfg, const rt_layer_weights *w,
  * Unless rt_config.reserve_stack_layers reserved them at rt_create, the first call allocates one scratch set per layer
  * (RT_ERR_OOM if that fails); it is kept until rt_destroy and
  * reused by later calls with the same chunk and at most as many layers (another shape synchronises the stream
- * and reallocates).  Half of the layers are enqueued on a second stream that the context owns (default priority;
- * it starts after the work already enqueued on rt_config.stream and that stream continues after it; the
- * environment variable RT_WAVE_STREAMS = 1..4 sets the number of layer groups / streams, default 2).
+ * and reallocates).  The layers run as three groups: the first on rt_config.stream, the others on two streams that
+ * the context owns (default priority; they start after the work already enqueued on rt_config.stream and that
+ * stream continues after them; the environment variable RT_WAVE_STREAMS = 1..4 sets the number of layer groups /
+ * streams, default 3).
  * rt_decode_step continues from the caches layer by layer. */
 rt_status rt_stack_prefill(rt_ctx *ctx, const rt_layer_weights *layers, int32_t L, const void *x, int32_t B, int32_t N,
                            void *const *y, void *const *K, void *const *V, int32_t kv_cap, int32_t chunk);
