@@ -543,8 +543,10 @@ __global__ __launch_bounds__(64) void par_merge_kernel(const bf16_t *__restrict_
 // Attention of ALL positions in one launch when every key-value pair is known in advance (Sec. 6.1 recompute,
 // Sec. 2.1 Transformer layer): query i against the cache rows j < i plus its own temporary pair, as one masked
 // flash-style pass instead of Algorithm 1's blocks (no partial states to write and merge).  The inner loop is the one
-// of cross_tile_wg (K, K remainder and V^T chunks of 64 keys staged in LDS and shared by four wavefronts of 32
-// queries; high-precision logits: three products per tile); additionally
+// of cross_tile_wg (key and V^T chunks of 64 keys staged in LDS and shared by four wavefronts of 32 queries; logits
+// from unrounded operands: with F16 the queries (fp32, times scale log2 e) and the keys (the fp16 copy of the cache,
+// passed in the Klo argument; K is then not read) are rounded once to fp16 and S^T is one product, as in the tiles of
+// the sequential engines; without it bf16 head + remainder and three products per tile); additionally
 //   - the state of a query starts from its temporary pair (m = its logit from the unrounded q and k_tmp, l = 1,
 //     o = v_tmp), so that every query has a finite reference before the first key,
 //   - chunks that reach a wavefront's own positions mask keys j >= i with -inf,
@@ -556,7 +558,7 @@ __global__ __launch_bounds__(64) void par_merge_kernel(const bf16_t *__restrict_
 // ---------------------------------------------------------------------------------------------
 // F32OUT (the backward pass's recompute): the result goes out as fp32 rows c_out[(i B H + bh) 64 ..] together with the
 // log-sum-exp of the query's logits (natural log), lse_out[i B H + bh], instead of bf16 rows of a_out.
-template <bool ALIBI, bool F32OUT = false>
+template <bool ALIBI, bool F32OUT = false, bool F16 = !F32OUT>
 __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict__ Qf, const float *__restrict__ Ktf,
                                                         const bf16_t *__restrict__ Vt, const bf16_t *__restrict__ K,
                                                         const bf16_t *__restrict__ Klo, const bf16_t *__restrict__ VT,
@@ -567,7 +569,8 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
 {
     extern __shared__ __align__(16) unsigned char flash_lds[];
     constexpr int T = 256, PPT = 2;
-    constexpr int TILE = kKC * kTileLd, BUF = (F32OUT ? 4 : 3) * TILE;   // F32OUT: a fourth tile, the remainder of V^T
+    static_assert(!(F32OUT && F16), "the fp32-output form keeps the three-product logits");
+    constexpr int TILE = kKC * kTileLd, BUF = (F32OUT ? 4 : (F16 ? 2 : 3)) * TILE;   // keys, V^T[, key remainder[, V^T remainder]]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int l32 = lane & 31, hi = lane >> 5;
     int bh, qt;
@@ -603,6 +606,14 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
             float f[8], r[8], kf[8];
             load8(Qf + qo + 8 * hi + ks * 16, f);
             load8(Ktf + qo + 8 * hi + ks * 16, kf);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot = fmaf(f[e], kf[e], dot);
+            if (F16) {   // the product then delivers the logits in log2 units
+                bq[ks] = make_uint4(cvt_pk_f16(f[0] * c2, f[1] * c2), cvt_pk_f16(f[2] * c2, f[3] * c2), cvt_pk_f16(f[4] * c2, f[5] * c2),
+                                    cvt_pk_f16(f[6] * c2, f[7] * c2));
+                bql[ks] = bq[ks];   // not used
+                continue;
+            }
             uint32_t h2[4];
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
@@ -610,8 +621,6 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
                 r[2 * e] = f[2 * e] - __uint_as_float(h2[e] << 16);
                 r[2 * e + 1] = f[2 * e + 1] - __uint_as_float(h2[e] & 0xFFFF0000u);
             }
-#pragma unroll
-            for (int e = 0; e < 8; ++e) dot = fmaf(f[e], kf[e], dot);
             bq[ks] = make_uint4(h2[0], h2[1], h2[2], h2[3]);
             bql[ks] = make_uint4(cvt_pk_bf16(r[0], r[1]), cvt_pk_bf16(r[2], r[3]), cvt_pk_bf16(r[4], r[5]), cvt_pk_bf16(r[6], r[7]));
         }
@@ -647,8 +656,8 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
     _Pragma("unroll") for (int i = 0; i < PPT; ++i)                                                                   \
     {                                                                                                                 \
         const size_t ro = (size_t)min((kc) + prow + i * (T / 8), N - 1) * rs + (size_t)bh * kHeadDim + pc16 * 8;      \
-        rk[i] = *reinterpret_cast<const u32x4_t *>(K + ro);                                                           \
-        rl[i] = *reinterpret_cast<const u32x4_t *>(Klo + ro);                                                         \
+        rk[i] = *reinterpret_cast<const u32x4_t *>((F16 ? Klo : K) + ro);                                             \
+        if (!F16) rl[i] = *reinterpret_cast<const u32x4_t *>(Klo + ro);                                               \
         rv[i] = *reinterpret_cast<const u32x4_t *>(gv + (size_t)(i * (T / 8)) * vt_stride + (kc));                    \
         if (F32OUT) rv2[i] = *reinterpret_cast<const u32x4_t *>(gv2 + (size_t)(i * (T / 8)) * vt_stride + (kc));      \
     }
@@ -660,7 +669,7 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
         bf16_t *dv = tiles + (size_t)(buf) * BUF + TILE + lds_off_v + i * (T / 8) * kVLd;                             \
         *reinterpret_cast<uint2 *>(dv) = make_uint2(rv[i][0], rv[i][1]);                                              \
         *reinterpret_cast<uint2 *>(dv + 4) = make_uint2(rv[i][2], rv[i][3]);                                          \
-        *reinterpret_cast<u32x4_t *>(dst + 2 * TILE) = rl[i];                                                         \
+        if (!F16) *reinterpret_cast<u32x4_t *>(dst + 2 * TILE) = rl[i];                                               \
         if (F32OUT) {                                                                                                 \
             bf16_t *dv2 = tiles + (size_t)(buf) * BUF + 3 * TILE + lds_off_v + i * (T / 8) * kVLd;                    \
             *reinterpret_cast<uint2 *>(dv2) = make_uint2(rv2[i][0], rv2[i][1]);                                       \
@@ -690,23 +699,29 @@ __global__ __launch_bounds__(256) void par_flash_kernel(const float *__restrict_
                 f32x16_t acc;
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+                if (F16) {
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks)      // small terms first
-                    acc = mfma32u(*reinterpret_cast<const uint4 *>(krow + 2 * TILE + ks * 16), bq[ks], acc);
+                    for (int ks = 0; ks < 4; ++ks) acc = mfma32h(ka[ks], bq[ks], acc);
+                } else {
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bql[ks], acc);
+                    for (int ks = 0; ks < 4; ++ks)      // small terms first
+                        acc = mfma32u(*reinterpret_cast<const uint4 *>(krow + 2 * TILE + ks * 16), bq[ks], acc);
 #pragma unroll
-                for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bq[ks], acc);
+                    for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bql[ks], acc);
+#pragma unroll
+                    for (int ks = 0; ks < 4; ++ks) acc = mfma32u(ka[ks], bq[ks], acc);
+                }
                 S[kt] = acc;
             }
             // register i of tile kt is key 64c + 32kt + 8(i/4) + 4hi + i%4; from here on S is in log2 units
-            {
+            if (ALIBI || !F16) {
                 const float base = ALIBI ? s2 * (float)(c * kKC + 4 * hi - qpos) : 0.f;
+                const float cs = F16 ? 1.f : c2;
 #pragma unroll
                 for (int kt = 0; kt < 2; ++kt)
 #pragma unroll
                     for (int i = 0; i < 16; ++i)
-                        S[kt][i] = ALIBI ? fmaf(S[kt][i], c2, fmaf(s2, (float)(32 * kt + 8 * (i / 4) + (i % 4)), base)) : S[kt][i] * c2;
+                        S[kt][i] = ALIBI ? fmaf(S[kt][i], cs, fmaf(s2, (float)(32 * kt + 8 * (i / 4) + (i % 4)), base)) : S[kt][i] * cs;
             }
             if (c * kKC + kKC > q0w) {               // the chunk reaches this wavefront's own positions: keys j >= i out
                 const int lim = qpos - (c * kKC + 4 * hi);   // valid iff 32kt + 8(i/4) + i%4 < lim
@@ -995,14 +1010,15 @@ hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S
     }
     {   // attention of all positions: one masked pass over the cache rows plus the temporary pair
         const int ntiles = (N + 127) / 128;
-        const size_t lds = 2 * (size_t)cross_tile_lds_bytes<true, false>();   // three tiles per buffer: head, V^T, remainder
+        const size_t lds = 2 * (size_t)cross_tile_lds_bytes<true, true>();   // two tiles per buffer: fp16 keys, V^T
         const dim3 grid((unsigned)(ntiles * BH));
+        const bf16_t *Kh = (const bf16_t *)S.Kh;   // 2-byte elements either way; the kernel reads them as fp16
         if (D.alibi > 0.f)
             hipLaunchKernelGGL(par_flash_kernel<true>, grid, dim3(256), lds, st, S.Qf, S.Ktf, (const bf16_t *)S.Vt, (const bf16_t *)K,
-                               S.Klo, S.VT, S.vt_stride, a_b, BH, D.H, N, ntiles, D.scale, D.alibi);
+                               Kh, S.VT, S.vt_stride, a_b, BH, D.H, N, ntiles, D.scale, D.alibi);
         else
             hipLaunchKernelGGL(par_flash_kernel<false>, grid, dim3(256), lds, st, S.Qf, S.Ktf, (const bf16_t *)S.Vt, (const bf16_t *)K,
-                               S.Klo, S.VT, S.vt_stride, a_b, BH, D.H, N, ntiles, D.scale, D.alibi);
+                               Kh, S.VT, S.vt_stride, a_b, BH, D.H, N, ntiles, D.scale, D.alibi);
     }
     block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, S.rinv, 0, N, st);
     return hipGetLastError();
