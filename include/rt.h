@@ -291,7 +291,8 @@ int32_t rt_decode_phase_trace(rt_ctx *ctx, uint64_t *out, int32_t workgroups);
  * caller's K, V): queries t1+1 .. t1+nq (1-based) against the keys t1-P+1 .. t1.  Rewrites those queries' partial
  * states of level log2(P) with the values the stand-alone kernel computes; outputs of the prefill are not touched.
  * The tile runs in the form that prefill's engine uses: after the persistent engine (and the loop-free layers) with
- * high-precision logits (unrounded queries, key remainders: three products per logit tile), else with plain bf16 ones.
+ * logits from the unrounded queries and keys (each rounded once to fp16, one product per logit tile; blocks of 32 keys:
+ * bf16 head + remainder, three products), else with plain bf16 ones.
  *   B = batch of that prefill; P a power of two >= p_min; t1 a positive multiple of P; 1 <= nq <= P; t1 + nq <= N.
  * Used by the benchmark to time the cross-block kernel alone. */
 rt_status rt_cross_block_event(rt_ctx *ctx, const void *K, const void *V, int32_t B, int32_t t1, int32_t P, int32_t nq);
