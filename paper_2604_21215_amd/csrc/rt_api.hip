@@ -26,6 +26,10 @@ struct rt_ctx {
     bool use_mfma = false;
     bool broken = false;
     int last_B = 0, last_N = 0;   // shape of the last prefill (what the scratch holds)
+    // K and V of one batch chunk, [max_seq][chunk][d] each: a batch beyond the single-launch engine's rows runs as
+    // chunks of that many rows, whose pairs are copied into the caller's position-major cache afterwards
+    void *kv_chunk = nullptr;
+    size_t kv_chunk_bytes = 0;
     bool last_hp = false;         // that prefill formed high-precision logits (scratch holds unrounded queries and key remainders)
     std::string err;
     std::string engine;
@@ -359,6 +363,11 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
         delete c;
         return ps;
     }
+    if (c->persist.available && c->cfg.max_batch > c->persist.max_batch) {
+        const size_t two = 2 * Nm * (size_t)c->persist.max_batch * d * E;
+        if (hipMalloc(&c->kv_chunk, two) == hipSuccess) c->kv_chunk_bytes = two;
+        else { (void)hipGetLastError(); c->kv_chunk = nullptr; }   // such batches then take the per-position engine
+    }
     (void)decode_coop_create(c->dec, c->cfg, D);   // shapes it does not cover keep the multi-launch step
     // scratch of the other entry points, when the caller wants no allocation inside a later call
     rt_status rs = RT_OK;
@@ -388,6 +397,7 @@ rt_status rt_destroy(rt_ctx *c)
     if (c->capture_stream) (void)hipStreamDestroy(c->capture_stream);
     persistent_destroy(c->persist);
     decode_coop_destroy(c->dec);
+    if (c->kv_chunk) (void)hipFree(c->kv_chunk);
     if (c->stack_slab) (void)hipFree(c->stack_slab);
     if (c->stack_dev) (void)hipFree(c->stack_dev);
     if (c->par_slab) (void)hipFree(c->par_slab);
@@ -405,7 +415,9 @@ static const char *static_last_error();
 const char *rt_last_error(const rt_ctx *c) { return c ? c->err.c_str() : static_last_error(); }
 uint64_t rt_workspace_bytes(const rt_ctx *c)
 {
-    return c ? (uint64_t)c->slab_bytes + persistent_bytes(c->persist) + decode_coop_bytes(c->dec) + c->stack_bytes + c->par_bytes + c->bw_bytes : 0;
+    return c ? (uint64_t)c->slab_bytes + c->kv_chunk_bytes + persistent_bytes(c->persist) + decode_coop_bytes(c->dec) + c->stack_bytes +
+                   c->par_bytes + c->bw_bytes
+             : 0;
 }
 const char *rt_engine_name(const rt_ctx *c) { return c ? c->engine.c_str() : ""; }
 
@@ -588,6 +600,35 @@ extern "C" rt_status rt_layer_prefill(rt_ctx *c, const rt_layer_weights *w, cons
         s = persistent_prefill(c->persist, D, W, c->S, x, y, K, V, c->stream, perr);
         if (s != RT_OK) { c->err = perr; if (s == RT_ERR_HIP) c->broken = true; }
         return s;
+    }
+    LayerDims Dc = D;
+    Dc.B = c->persist.max_batch;
+    if (!want_stepwise && c->kv_chunk && B > c->persist.max_batch && persistent_supported(c->persist, Dc)) {
+        // batch rows are independent: chunks of the engine's rows, one after the other on the stream; x and y of a chunk are
+        // contiguous slices, its pairs go through the chunk buffers (the cache is position-major over the whole batch)
+        c->engine = "persistent";
+        c->last_hp = true;
+        c->last_B = 0;   // the scratch holds the last chunk only: no stand-alone tile on it
+        const Weights W = to_weights(w);
+        const size_t d = (size_t)c->cfg.d_model, row = d * E;
+        char *Kc = (char *)c->kv_chunk, *Vc = Kc + c->kv_chunk_bytes / 2;
+        for (int b0 = 0; b0 < B; b0 += c->persist.max_batch) {
+            const int nb = B - b0 < c->persist.max_batch ? B - b0 : c->persist.max_batch;
+            Dc.B = nb; Dc.kv_cap = N;
+            const char *xc = (const char *)x + (size_t)b0 * N * row;
+            char *yc = (char *)y + (size_t)b0 * N * row;
+            if (b0 > 0) poison_partials(c, c->S);
+            hipError_t e = Launch<bf16_t>::prepass(Dc, W, c->S, xc, nb, N, c->use_mfma, c->stream);
+            if (e != hipSuccess) return fail_hip(c, e, "prepass");
+            std::string perr;
+            s = persistent_prefill(c->persist, Dc, W, c->S, xc, yc, Kc, Vc, c->stream, perr);
+            if (s != RT_OK) { c->err = perr; if (s == RT_ERR_HIP) c->broken = true; return s; }
+            RT_TRY(hipMemcpy2DAsync((char *)K + (size_t)b0 * row, (size_t)B * row, Kc, (size_t)nb * row, (size_t)nb * row, (size_t)N,
+                                    hipMemcpyDeviceToDevice, c->stream), "hipMemcpy2DAsync");
+            RT_TRY(hipMemcpy2DAsync((char *)V + (size_t)b0 * row, (size_t)B * row, Vc, (size_t)nb * row, (size_t)nb * row, (size_t)N,
+                                    hipMemcpyDeviceToDevice, c->stream), "hipMemcpy2DAsync");
+        }
+        return RT_OK;
     }
     if (c->cfg.flags & RT_FLAG_ENGINE_PERSISTENT)
         return fail(c, RT_ERR_UNSUPPORTED, "the persistent engine does not cover this shape%s");

@@ -198,6 +198,15 @@ def test_persistent_full_batch_at_the_headline_width(oracle):
     _run_case(oracle, "bf16", 16, 100, 1024, 16, 4096, flags=b.RT_FLAG_ENGINE_PERSISTENT, expect_engine="persistent")
 
 
+@pytest.mark.parametrize("B,N,d", [(35, 70, 256), (20, 40, 1024)])
+def test_persistent_batches_beyond_its_rows_run_in_chunks(oracle, B, N, d):
+    """More sequences than the single-launch engine stages at once (16): the call runs chunks of 16 rows one after the
+    other (16 + 16 + 3; 16 + 4) and copies each chunk's pairs into the position-major cache; cache rows beyond N stay
+    untouched and a decoding step over the assembled cache agrees with the oracle."""
+    _run_case(oracle, "bf16", B, N, d, d // 64, 4 * d, gains="random", scale=0.5, alpha=0.7, kv_cap=N + 5, n_decode=1,
+              expect_engine="persistent")
+
+
 def test_persistent_gains_scales_levels(oracle):
     b = _flags()
     _run_case(oracle, "bf16", 3, 300, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_PERSISTENT, gains="random", alpha=0.7,
