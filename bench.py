@@ -124,6 +124,45 @@ def stack_section(stream, layer_by_layer=True, reps=2, alibi=0.0, layers=0, posi
     return sec
 
 
+def batch_sweep_section(stream):
+    """rt_layer_prefill at the shapes of the paper's latency table (Sec. 6.2, Table 1: one layer, N = 512, d = 1024, 16 heads,
+    batch sizes 32 .. 1024; bf16 here, logits scaled by 1/8): ms per call and what the paper measured on its own hardware.
+    Context, not the headline: every batch size takes the engine rt_layer_prefill selects for it."""
+    import numpy as np
+    import torch
+    from paper_2604_21215_amd import binding, inputs as gen, torch_io as tio
+    d, H, F, N = 1024, 16, 4096, 512
+    paper_ms = {32: 38.85, 64: 42.28, 128: 48.95, 256: 61.39, 512: 81.73, 1024: 134.09}
+    li = gen.make_custom(3, "bf16", 32, N, d, H, F)
+    dl = tio.DeviceLayer(li.weights, li.gains, "bf16")
+    x32 = tio.to_device(li.x, "bf16")
+    rows = []
+    for B in sorted(paper_ms):
+        x = x32.repeat(B // 32, 1, 1).contiguous()        # the same 32 sequences repeated: timing does not depend on the values
+        y = torch.empty_like(x)
+        K = torch.zeros((N, B, H, d // H), dtype=x.dtype, device=x.device)
+        V = torch.zeros_like(K)
+        ctx = binding.RTContext(d, H, F, B, N, "bf16", attn_scale=0.125, stream=stream.cuda_stream)
+        try:
+            ctx.rt_layer_prefill(dl.struct, x, y, K, V)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(stream)
+            for _ in range(2):
+                ctx.rt_layer_prefill(dl.struct, x, y, K, V)
+            e1.record(stream)
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / 2
+            rows.append({"B": B, "engine": ctx.engine_name(), "ms_per_call": ms, "us_per_position": ms * 1e3 / N,
+                         "tokens_per_s": B * N / (ms * 1e-3), "paper_ms_other_hardware": paper_ms[B]})
+        finally:
+            ctx.rt_destroy()
+        del x, y, K, V
+    return {"workload": "one layer, N=512, d_model=1024, 16 heads, hidden 4096, bf16 (the shapes of the paper's Table 1)",
+            "note": "paper_ms_other_hardware: the paper's figures with CUDA Graphs on one H100, quoted as context, not as a baseline",
+            "rows": rows}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,6 +180,7 @@ def main():
                     help="skip rt_layer_prefill_blocked (thousands of launches: slow under a counter-collecting profiler)")
     ap.add_argument("--no-backward", action="store_true", help="skip rt_layer_backward")
     ap.add_argument("--no-stack", action="store_true", help="skip the 12-layer stack measurement (rt_stack_prefill)")
+    ap.add_argument("--no-batch-sweep", action="store_true", help="skip rt_layer_prefill at N = 512 for batch sizes 32 .. 1024")
     ap.add_argument("--stack-only", action="store_true",
                     help="only the 12-layer stack through rt_stack_prefill (for profiling): prints its section alone")
     ap.add_argument("--stack-layers", type=int, default=0, help="with --stack-only: number of layers (default: the workload's 12)")
@@ -405,6 +445,11 @@ def main():
 
     if not args.no_stack and args.workload == "cfg3":
         out["stack_wavefront"] = stack_section(stream, alibi=args.alibi)
+    if not args.no_batch_sweep and args.workload == "cfg3":
+        try:
+            out["batch_sweep"] = batch_sweep_section(stream)
+        except Exception as exc:   # context only: never lose the headline line over it
+            out["batch_sweep"] = {"error": repr(exc)[:300]}
     print(json.dumps(out))
 
 

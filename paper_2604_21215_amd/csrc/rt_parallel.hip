@@ -214,7 +214,8 @@ __global__ __launch_bounds__(256) void par_rinv_kernel(const float *__restrict__
 // (each the full tile over K / NWV); a wavefront issues the loads of four steps (128 indices: 32 fragments) before
 // their 64 matrix instructions; the partial tiles and the partial row statistics meet in LDS (four tile slots:
 // wavefronts 4..7 add theirs onto the slots of wavefronts 0..3), then thread (row, quarter) of the first 256
-// finishes 16 consecutive outputs of one row.
+// finishes 16 consecutive outputs of one row.  CT = 32 / 16: tiles of 64 x 32 / 64 x 16 outputs (8 / 4 per thread) - two /
+// four times the workgroups, for products of so few rows that 64-column tiles do not keep the memory system busy.
 //   PG_PRE: the pre-pass projection: W = [Wq; Wk; Wv] by column block (one head each), A rows RMS-normalised with
 //           `gain`, then qkRMS per head for q and k_tmp; rows go to Q / Kt / Vt (and fp32 Qf / Ktf) position-first.
 // grid (ceil(M / 64), Nn / 64), block 64 NWV, 70 KB of LDS.
@@ -235,7 +236,7 @@ struct PreOut {   // PG_PRE only
     int vt_stride;
 };
 
-template <int EPI, int NWV>
+template <int EPI, int NWV, int CT = 64>
 __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__restrict__ A, const bf16_t *__restrict__ W, int M, int Nn,
                                                        int K, int Nc, int N, int n0, const bf16_t *__restrict__ gain, float eps,
                                                        int norm_free, float alpha, const bf16_t *__restrict__ res_b,
@@ -247,7 +248,9 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
     float *ssq_s = part + 4 * 64 * kSkLd;                             // [8][64]
     const int tid = threadIdx.x, lane = tid & 63, kw = tid >> 6;
     const int l16 = lane & 15, g = lane >> 4;
-    const int m0 = blockIdx.x * 64, nb0 = blockIdx.y * 64;
+    static_assert(CT == 64 || ((CT == 32 || CT == 16) && EPI != PG_PRE), "the pre-pass form owns whole heads");
+    constexpr int NJ = CT / 16, PER = CT / 4;   // column fragments per wavefront; outputs per epilogue thread
+    const int m0 = blockIdx.x * 64, nb0 = blockIdx.y * CT;
     const bf16_t *Wt = W;
     if (EPI == PG_PRE) {
         const int by = (int)blockIdx.y + po.y0;
@@ -255,18 +258,19 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
         Wt = (which == 0 ? po.Wq : (which == 1 ? po.Wk : po.Wv)) + (size_t)h * kHeadDim * K - (size_t)nb0 * K;
     }
     const int klen = K / NWV, kbeg = kw * klen;
-    f32x4_t acc[4][4];
+    f32x4_t acc[4][NJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
-    const bf16_t *arow[4], *brow[4];
+        for (int j = 0; j < NJ; ++j) acc[i][j] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    const bf16_t *arow[4], *brow[NJ];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         const int mr = min(m0 + i * 16 + l16, M - 1);
         arow[i] = A + ((size_t)(mr / Nc) * N + n0 + mr % Nc) * K + kbeg + 8 * g;
-        brow[i] = Wt + (size_t)(nb0 + i * 16 + l16) * K + kbeg + 8 * g;
     }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) brow[j] = Wt + (size_t)(nb0 + j * 16 + l16) * K + kbeg + 8 * g;
     const bool normed = (EPI == PG_W1 || EPI == PG_PRE) && !norm_free;
     const bool use_gain = normed && gain != nullptr;
     float ssq[4] = {0.f, 0.f, 0.f, 0.f};
@@ -290,28 +294,27 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
             }                                                                                                   \
         }                                                                                                       \
         _Pragma("unroll") for (int i = 0; i < 4; ++i)                                                           \
-            _Pragma("unroll") for (int j = 0; j < 4; ++j) acc[i][j] = mfma16(av[i], bv[j], acc[i][j]);          \
+            _Pragma("unroll") for (int j = 0; j < NJ; ++j) acc[i][j] = mfma16(av[i], bv[j], acc[i][j]);         \
     }
     int k = 0;
     for (; k + 128 <= klen; k += 128) {   // four steps: 32 fragment loads in flight, then their 64 matrix instructions
-        Frag a[4][4], b[4][4];
+        Frag a[4][4], b[4][NJ];
 #pragma unroll
-        for (int st = 0; st < 4; ++st)
+        for (int st = 0; st < 4; ++st) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                a[st][i].u = *reinterpret_cast<const uint4 *>(arow[i] + k + 32 * st);
-                b[st][i].u = *reinterpret_cast<const uint4 *>(brow[i] + k + 32 * st);
-            }
+            for (int i = 0; i < 4; ++i) a[st][i].u = *reinterpret_cast<const uint4 *>(arow[i] + k + 32 * st);
+#pragma unroll
+            for (int j = 0; j < NJ; ++j) b[st][j].u = *reinterpret_cast<const uint4 *>(brow[j] + k + 32 * st);
+        }
 #pragma unroll
         for (int st = 0; st < 4; ++st) RT_SK_STEP(a[st], b[st], k + 32 * st)
     }
     for (; k < klen; k += 32) {
-        Frag a[4], b[4];
+        Frag a[4], b[NJ];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            a[i].u = *reinterpret_cast<const uint4 *>(arow[i] + k);
-            b[i].u = *reinterpret_cast<const uint4 *>(brow[i] + k);
-        }
+        for (int i = 0; i < 4; ++i) a[i].u = *reinterpret_cast<const uint4 *>(arow[i] + k);
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) b[j].u = *reinterpret_cast<const uint4 *>(brow[j] + k);
         RT_SK_STEP(a, b, k)
     }
 #undef RT_SK_STEP
@@ -325,7 +328,7 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
         }
         if (kw < 4) {
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < NJ; ++j)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) part[(kw * 64 + i * 16 + 4 * g + r) * kSkLd + j * 16 + l16] = acc[i][j][r];
         }
@@ -336,19 +339,19 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
 #pragma unroll
             for (int i = 0; i < 4; ++i)
 #pragma unroll
-                for (int j = 0; j < 4; ++j)
+                for (int j = 0; j < NJ; ++j)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) part[((kw - 4) * 64 + i * 16 + 4 * g + r) * kSkLd + j * 16 + l16] += acc[i][j][r];
         }
         __syncthreads();
         if (kw >= 4) return;   // no barrier below
     }
-    // thread (row, quarter): 16 consecutive outputs of one row
-    const int row = tid >> 2, qc = (tid & 3) * 16;
+    // thread (row, quarter): PER consecutive outputs of one row
+    const int row = tid >> 2, qc = (tid & 3) * PER;
     const int m = m0 + row;
     float v[16];
 #pragma unroll
-    for (int c4 = 0; c4 < 4; ++c4) {
+    for (int c4 = 0; c4 < PER / 4; ++c4) {
         float4 s4 = *reinterpret_cast<const float4 *>(part + (size_t)row * kSkLd + qc + 4 * c4);
 #pragma unroll
         for (int w = 1; w < 4; ++w) {
@@ -378,7 +381,7 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
             const int bb = m / Nc, n = n0 + m % Nc;
             const size_t oo = ((size_t)n * po.Bc + bb) * K + h * kHeadDim + qc;   // the projection is square: row length = K = d
             if (po.K != nullptr && which > 0) {   // straight into the cache: the rows of the pre-pass buffers are laid out like it
-                bf16_t *vt = po.VT + ((size_t)(bb * po.H + h) * kHeadDim + qc) * po.vt_stride + n;
+                bf16_t *vt = po.VT ? po.VT + ((size_t)(bb * po.H + h) * kHeadDim + qc) * po.vt_stride + n : nullptr;
 #pragma unroll
                 for (int e = 0; e < 16; ++e) {
                     float val = v[e] * sc;
@@ -390,7 +393,7 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
                         po.Kh[oo + e] = f32_to_f16_bits(val);
                     } else {
                         po.V[oo + e] = r;
-                        vt[(size_t)e * po.vt_stride] = r;
+                        if (vt) vt[(size_t)e * po.vt_stride] = r;   // else the caller transposes whole runs of positions later
                     }
                 }
                 return;
@@ -410,7 +413,7 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
     if (m >= M) return;
     const size_t o = ((size_t)(m / Nc) * N + n0 + m % Nc) * Nn + nb0 + qc;
 #pragma unroll
-    for (int e = 0; e < 16; ++e) {
+    for (int e = 0; e < PER; ++e) {
         if (EPI == PG_WO) {
             const float h = bf16_to_f32(res_b[o + e]) + alpha * v[e];
             out_f[o + e] = h;
@@ -424,20 +427,21 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
 }
 
 constexpr size_t kBlkLds = (size_t)(4 * 64 * kSkLd + 8 * 64) * 4;
-template <int EPI, int NWV>
+constexpr int kNarrowM = 512, kNarrow16M = 64;
+template <int EPI, int NWV, int CT = 64>
 static hipError_t blk_gemm_launch_n(dim3 grid, hipStream_t st, const bf16_t *A, const bf16_t *W, int M, int Nn, int K, int Nc, int N,
                                     int n0, const bf16_t *gain, float eps, int norm_free, float alpha, const bf16_t *res_b,
                                     const float *res_f, float *out_f, bf16_t *out_b, const PreOut &po)
 {
     static bool raised = false;   // more than the default 64 KB of dynamic LDS
     if (!raised) {
-        hipError_t e = hipFuncSetAttribute((const void *)blk_gemm_kernel<EPI, NWV>, hipFuncAttributeMaxDynamicSharedMemorySize,
+        hipError_t e = hipFuncSetAttribute((const void *)blk_gemm_kernel<EPI, NWV, CT>, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kBlkLds);
         if (e != hipSuccess) return e;
         raised = true;
     }
-    hipLaunchKernelGGL((blk_gemm_kernel<EPI, NWV>), grid, dim3(64 * NWV), kBlkLds, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free,
-                       alpha, res_b, res_f, out_f, out_b, po);
+    hipLaunchKernelGGL((blk_gemm_kernel<EPI, NWV, CT>), grid, dim3(64 * NWV), kBlkLds, st, A, W, M, Nn, K, Nc, N, n0, gain, eps,
+                       norm_free, alpha, res_b, res_f, out_f, out_b, po);
     return hipSuccess;
 }
 // eight wavefronts when every share of the contraction is still a whole number of 32-index steps
@@ -446,7 +450,25 @@ static hipError_t blk_gemm_launch(dim3 grid, hipStream_t st, const bf16_t *A, co
                                   int n0, const bf16_t *gain, float eps, int norm_free, float alpha, const bf16_t *res_b,
                                   const float *res_f, float *out_f, bf16_t *out_b, const PreOut &po)
 {
-    if (K % 256 == 0)
+    if constexpr (EPI != PG_PRE) {
+        // few rows: 64-column tiles are then too few workgroups for the weight stream.  Tiles of 32 columns up to kNarrowM
+        // rows (MI355X, d = 1024, one position of B sequences: B = 128 52.1 -> 42.0 ms per 512 positions, B = 512 76.6 -> 73.5,
+        // B = 1024 139 -> 154), of 16 columns up to kNarrow16M (32 rows: 35.1 -> 31.7 ms per 2048 positions in blocks of 4;
+        // 128 rows: 42.3 -> 47.4)
+        if (M <= kNarrow16M && K % 256 == 0 && Nn % 32 == 0) {
+            grid.y = (unsigned)(Nn / 16);
+            return blk_gemm_launch_n<EPI, 8, 16>(grid, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free, alpha, res_b, res_f, out_f,
+                                                 out_b, po);
+        }
+        if (M <= kNarrowM && K % 256 == 0 && Nn % 32 == 0) {
+            grid.y = (unsigned)(Nn / 32);
+            return blk_gemm_launch_n<EPI, 8, 32>(grid, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free, alpha, res_b, res_f, out_f,
+                                                 out_b, po);
+        }
+    }
+    // eight shares of a contraction of 1024 are one step group each: with many row tiles four wavefronts (two groups each, one
+    // pass less through LDS) are faster (1024 rows, d = 1024: 123.1 -> 121.8 ms per 512 positions)
+    if (K % 256 == 0 && !(M >= kNarrowM && K <= 1024))
         return blk_gemm_launch_n<EPI, 8>(grid, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free, alpha, res_b, res_f, out_f, out_b, po);
     return blk_gemm_launch_n<EPI, 4>(grid, st, A, W, M, Nn, K, Nc, N, n0, gain, eps, norm_free, alpha, res_b, res_f, out_f, out_b, po);
 }
@@ -820,8 +842,9 @@ constexpr int kSmallM = 2048;   // up to this many rows the split-contraction ke
 
 // the pre-pass projection of positions n0 .. n0 + Nc - 1 of every batch row of `src` with the split-contraction kernel
 // pairs_to: the caller's K (with V): only the pairs are projected and they go straight into the cache rows and their copies
+// write_vt = false: the transposed copy of the values is left to vt_from_rows_kernel
 static hipError_t small_prepass(const LayerDims &D, const Weights &W, const Scratch &S, const void *src, int n0, int Nc, hipStream_t st,
-                                void *pairs_K = nullptr, void *pairs_V = nullptr)
+                                void *pairs_K = nullptr, void *pairs_V = nullptr, bool write_vt = true)
 {
     PreOut po = {};
     po.Wq = (const bf16_t *)W.Wq; po.Wk = (const bf16_t *)W.Wk; po.Wv = (const bf16_t *)W.Wv;
@@ -830,7 +853,8 @@ static hipError_t small_prepass(const LayerDims &D, const Weights &W, const Scra
     po.H = D.H; po.Bc = D.B;
     if (pairs_K) {
         po.y0 = D.H;
-        po.K = (bf16_t *)pairs_K; po.V = (bf16_t *)pairs_V; po.Klo = S.Klo; po.Kh = S.Kh; po.VT = S.VT; po.vt_stride = S.vt_stride;
+        po.K = (bf16_t *)pairs_K; po.V = (bf16_t *)pairs_V; po.Klo = S.Klo; po.Kh = S.Kh; po.VT = write_vt ? S.VT : nullptr;
+        po.vt_stride = S.vt_stride;
     }
     const int M = D.B * Nc;
     return blk_gemm_launch<PG_PRE>(dim3((unsigned)((M + 63) / 64), (unsigned)((pairs_K ? 2 : 3) * D.H)), st, (const bf16_t *)src, nullptr, M, 3 * D.d,
@@ -1029,6 +1053,29 @@ hipError_t parallel_layer(const LayerDims &D, const Weights &W, const Scratch &S
 // a block is evaluated its rows of K, V hold the TEMPORARY pairs (the direct window of merge_body then reads
 // persistent pairs of earlier blocks and temporary pairs of the own block without knowing the difference); after the
 // block's outputs are there they are overwritten with the persistent pairs projected from those outputs.
+// The transposed copy of the values for positions t_lo + 32 blockIdx.y .. + 31 of head (b, h) = blockIdx.x from the cache rows:
+// written position by position it costs a 64-byte write per 2-byte element; here a workgroup turns a 32 x 64 tile through
+// LDS and writes 64-byte runs.  t_lo a multiple of 32.  grid (B*H, positions / 32), block 256.
+__global__ __launch_bounds__(256) void vt_from_rows_kernel(const bf16_t *__restrict__ V, bf16_t *__restrict__ VT, int vt_stride, int BH,
+                                                           int t_lo)
+{
+    constexpr int kLd = 72;
+    __shared__ __align__(16) bf16_t tile[32 * kLd];
+    const int tid = threadIdx.x, bh = blockIdx.x, t0 = t_lo + 32 * (int)blockIdx.y;
+    {
+        const int r = tid >> 3, c = tid & 7;
+        *reinterpret_cast<uint4 *>(tile + r * kLd + 8 * c) =
+            *reinterpret_cast<const uint4 *>(V + ((size_t)(t0 + r) * BH + bh) * kHeadDim + 8 * c);
+    }
+    __syncthreads();
+    const int dim = tid >> 2, q = tid & 3;
+    uint32_t w[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+        w[j] = (uint32_t)tile[(8 * q + 2 * j) * kLd + dim] | ((uint32_t)tile[(8 * q + 2 * j + 1) * kLd + dim] << 16);
+    *reinterpret_cast<uint4 *>(VT + ((size_t)bh * kHeadDim + dim) * vt_stride + t0 + 8 * q) = make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S, const void *x, int Sblk, void *y, void *K, void *V,
                          void *par, hipStream_t st)
 {
@@ -1056,9 +1103,15 @@ hipError_t blocked_layer(const LayerDims &D, const Weights &W, const Scratch &S,
                            D.p_min, D.log2_pmin, S.levels, S.slots, D.scale, D.alibi, t0);
         block_gemms(D, W, x, y, a_b, h_f, h_b, u_b, S.rinv, t0, nr, st);
         // persistent pairs of the block from its outputs (rows t0.. of the pre-pass buffers are free again)
+        // the tiles of Algorithm 1 are the only readers of the transposed values: with p_min a multiple of 32 it is written
+        // in runs of p_min positions right before the tile that closes them
+        const bool lazy_vt = D.p_min % 32 == 0;
         if (B * nr <= kSmallM && d % 128 == 0) {
-            e = small_prepass(D, Wp, S, y, t0, nr, st, K, V);   // pairs only, written into the cache by the product's epilogue
+            e = small_prepass(D, Wp, S, y, t0, nr, st, K, V, !lazy_vt);   // pairs only, written into the cache by the product's epilogue
             if (e != hipSuccess) return e;
+            if (lazy_vt && (t0 + nr) % D.p_min == 0)
+                hipLaunchKernelGGL(vt_from_rows_kernel, dim3(BH, (unsigned)(D.p_min / 32)), dim3(256), 0, st, (const bf16_t *)V, S.VT,
+                                   S.vt_stride, BH, t0 + nr - D.p_min);
         } else {
             e = Launch<bf16_t>::prepass(D, Wp, S, y, B, nr, true, st, (size_t)N * d, t0);
             if (e != hipSuccess) return e;

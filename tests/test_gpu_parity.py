@@ -207,6 +207,13 @@ def test_persistent_batches_beyond_its_rows_run_in_chunks(oracle, B, N, d):
               expect_engine="persistent")
 
 
+def test_many_sequences_take_the_position_batched_engine(oracle):
+    """From 81 sequences on rt_layer_prefill evaluates one position of all sequences per step with batched matrix products
+    (chunks of 16 rows on the single-launch engine would take longer): same results, same bounds."""
+    _run_case(oracle, "bf16", 100, 70, 256, 4, 1024, gains="random", scale=0.5, alpha=0.7, kv_cap=72, n_decode=1,
+              expect_engine="position-batched")
+
+
 def test_persistent_gains_scales_levels(oracle):
     b = _flags()
     _run_case(oracle, "bf16", 3, 300, 256, 4, 1024, flags=b.RT_FLAG_ENGINE_PERSISTENT, gains="random", alpha=0.7,
