@@ -111,9 +111,11 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out);
  *   1 <= B <= max_batch, 1 <= N <= max_seq, N <= kv_cap.
  * Batch rows are independent; where the single-launch engine applies (bf16) it stages at most 16 of them, and a larger
  * batch runs as chunks of 16 rows one after the other on the stream, each chunk's pairs copied into K, V from a
- * buffer of 2 * max_seq * 16 * d elements that rt_create allocates when max_batch > 16.  From 81 rows on (bf16, matrix-core
- * kernels) the call instead steps through the positions with all rows at once, the base-case products as batched matrix
- * products (scratch of the loop-free entry points, reserved at rt_create when max_batch >= 81).
+ * buffer of 2 * max_seq * 16 * d elements that rt_create allocates when max_batch > 16.  With bf16 and the matrix-core
+ * kernels, 49 to 128 rows run as a stack of one layer on rt_stack_prefill's engine, and more rows step through the
+ * positions with all rows at once, the base-case products as batched matrix products; rt_create reserves the workspace
+ * of the former when max_batch >= 49 and the scratch of the loop-free entry points, which the latter uses, when
+ * max_batch >= 81 (where a reservation fails the call falls back to the chunks).
  * Host-detectable errors are returned before anything is enqueued and leave the outputs untouched. */
 rt_status rt_layer_prefill(rt_ctx *ctx, const rt_layer_weights *w, const void *x, int32_t B, int32_t N, void *y,
                            void *K, void *V, int32_t kv_cap);

@@ -191,6 +191,11 @@ static rt_status stack_workspace(rt_ctx *c, int L, int chunk);
 // than chunks of 16 rows on the single-launch engine (MI355X, d = 1024, 512 positions: 5 chunks take 39.3 ms, 6 take 47.1;
 // the batched steps 40.8 ms at B = 80, 41.3 at B = 96, 42.4 at B = 128)
 constexpr int kBatchedFrom = 81;
+// ... and between these batch sizes the layer-wavefront engine with a single layer (its small-M products on the matrix cores, a
+// batch tile of 16 rows per workgroup) is faster than both (same shapes, ms per call at B = 48 / 56 / 64 / 80 / 128 / 160: chunks
+// 23.6 / 30.7 / 31.4 / 39.3 / - / -, batched steps 35.4 / 37.5 / 39.8 / 40.5 / 41.7 / 48.4, this engine 28.5 / 28.3 / 29.2 / 30.9 /
+// 33.2 / 49.2)
+constexpr int kWaveFrom = 49, kWaveTo = 128;
 
 // Scratch of the loop-free evaluations / of the backward pass for max_batch x max_seq positions: allocated once, at
 // rt_create when rt_config.reserve asks for it, else by the first call that needs it.
@@ -387,6 +392,10 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
                                  !(cfg->flags & RT_FLAG_ENGINE_PERSISTENT) && parallel_supported(D, c->use_mfma);
     if (rs == RT_OK && (cfg->reserve & RT_RESERVE_LOOP_FREE)) rs = ensure_loop_free_scratch(c);
     if (rs == RT_OK && batched_prefill && ensure_loop_free_scratch(c) != RT_OK) c->err.clear();   // such batches then run in chunks
+    const bool wave_prefill = cfg->max_batch >= kWaveFrom && cfg->dtype == RT_BF16 && !(cfg->flags & RT_FLAG_ENGINE_STEPWISE) &&
+                              !(cfg->flags & RT_FLAG_ENGINE_PERSISTENT) && p_min <= 64 &&
+                              wavefront_uses_matrix_cores(cfg->d_model, cfg->d_hidden, c->use_mfma);
+    if (rs == RT_OK && wave_prefill && !c->stack_slab && stack_workspace(c, 1, 64) != RT_OK) c->err.clear();
     if (rs == RT_OK && (cfg->reserve & RT_RESERVE_BACKWARD)) rs = ensure_backward_scratch(c);
     if (rs != RT_OK) {
         (void)rt_destroy(c);
@@ -607,6 +616,13 @@ extern "C" rt_status rt_layer_prefill(rt_ctx *c, const rt_layer_weights *w, cons
         s = persistent_prefill(c->persist, D, W, c->S, x, y, K, V, c->stream, perr);
         if (s != RT_OK) { c->err = perr; if (s == RT_ERR_HIP) c->broken = true; }
         return s;
+    }
+    if (!want_stepwise && !(c->cfg.flags & RT_FLAG_ENGINE_PERSISTENT) && B >= kWaveFrom && B <= kWaveTo && c->cfg.dtype == RT_BF16 &&
+        c->stack_slab && c->stack_chunk == 64 && c->base.p_min <= 64 &&
+        wavefront_uses_matrix_cores(c->cfg.d_model, c->cfg.d_hidden, c->use_mfma)) {
+        // a stack of one layer on the layer-wavefront engine (workspace reserved at rt_create for such contexts)
+        void *y1 = y, *K1 = K, *V1 = V;
+        return rt_stack_prefill(c, w, 1, x, B, N, &y1, &K1, &V1, kv_cap, 64);
     }
     if (!want_stepwise && !(c->cfg.flags & RT_FLAG_ENGINE_PERSISTENT) && B >= kBatchedFrom && c->cfg.dtype == RT_BF16 &&
         parallel_supported(D, c->use_mfma) && c->par_slab) {

@@ -207,10 +207,13 @@ def test_persistent_batches_beyond_its_rows_run_in_chunks(oracle, B, N, d):
               expect_engine="persistent")
 
 
-def test_many_sequences_take_the_position_batched_engine(oracle):
-    """From 81 sequences on rt_layer_prefill evaluates one position of all sequences per step with batched matrix products
-    (chunks of 16 rows on the single-launch engine would take longer): same results, same bounds."""
-    _run_case(oracle, "bf16", 100, 70, 256, 4, 1024, gains="random", scale=0.5, alpha=0.7, kv_cap=72, n_decode=1,
+def test_many_sequences_take_the_engines_cut_for_them(oracle):
+    """rt_layer_prefill by batch size: up to 48 sequences chunks of 16 rows on the single-launch engine, from 49 to 128 the
+    layer-wavefront engine with one layer, beyond that one position of all sequences per step with batched matrix products
+    (each the fastest there): same results, same bounds."""
+    _run_case(oracle, "bf16", 60, 70, 256, 4, 1024, gains="random", scale=0.5, alpha=0.7, kv_cap=72, n_decode=1,
+              expect_engine="wavefront")
+    _run_case(oracle, "bf16", 130, 70, 256, 4, 1024, gains="random", scale=0.5, alpha=0.7, kv_cap=72, n_decode=1,
               expect_engine="position-batched")
 
 
