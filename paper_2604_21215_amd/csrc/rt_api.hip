@@ -622,6 +622,7 @@ extern "C" rt_status rt_layer_prefill(rt_ctx *c, const rt_layer_weights *w, cons
         wavefront_uses_matrix_cores(c->cfg.d_model, c->cfg.d_hidden, c->use_mfma)) {
         // a stack of one layer on the layer-wavefront engine (workspace reserved at rt_create for such contexts)
         void *y1 = y, *K1 = K, *V1 = V;
+        c->last_B = 0;   // the engine keeps its state in the stack workspace: no stand-alone tile on the context's scratch
         return rt_stack_prefill(c, w, 1, x, B, N, &y1, &K1, &V1, kv_cap, 64);
     }
     if (!want_stepwise && !(c->cfg.flags & RT_FLAG_ENGINE_PERSISTENT) && B >= kBatchedFrom && c->cfg.dtype == RT_BF16 &&
