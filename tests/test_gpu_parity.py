@@ -215,6 +215,9 @@ def test_many_sequences_take_the_engines_cut_for_them(oracle):
               expect_engine="wavefront")
     _run_case(oracle, "bf16", 130, 70, 256, 4, 1024, gains="random", scale=0.5, alpha=0.7, kv_cap=72, n_decode=1,
               expect_engine="position-batched")
+    # the largest batch a context takes: 1024 rows per step (other tile shapes of the products than at 130)
+    _run_case(oracle, "bf16", 1024, 34, 256, 4, 1024, gains="random", scale=0.5, alpha=0.7, n_decode=1,
+              expect_engine="position-batched")
 
 
 def test_persistent_gains_scales_levels(oracle):
