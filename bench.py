@@ -124,7 +124,7 @@ def stack_section(stream, layer_by_layer=True, reps=2, alibi=0.0, layers=0, posi
     return sec
 
 
-def batch_sweep_section(stream):
+def batch_sweep_section(stream, sizes=None):
     """rt_layer_prefill at the shapes of the paper's latency table (Sec. 6.2, Table 1: one layer, N = 512, d = 1024, 16 heads,
     batch sizes 32 .. 1024; bf16 here, logits scaled by 1/8): ms per call and what the paper measured on its own hardware.
     Context, not the headline: every batch size takes the engine rt_layer_prefill selects for it."""
@@ -137,7 +137,7 @@ def batch_sweep_section(stream):
     dl = tio.DeviceLayer(li.weights, li.gains, "bf16")
     x32 = tio.to_device(li.x, "bf16")
     rows = []
-    for B in sorted(paper_ms):
+    for B in (sizes or sorted(paper_ms)):
         x = x32.repeat(B // 32, 1, 1).contiguous()        # the same 32 sequences repeated: timing does not depend on the values
         y = torch.empty_like(x)
         K = torch.zeros((N, B, H, d // H), dtype=x.dtype, device=x.device)
@@ -154,7 +154,7 @@ def batch_sweep_section(stream):
             torch.cuda.synchronize()
             ms = e0.elapsed_time(e1) / 2
             rows.append({"B": B, "engine": ctx.engine_name(), "ms_per_call": ms, "us_per_position": ms * 1e3 / N,
-                         "tokens_per_s": B * N / (ms * 1e-3), "paper_ms_other_hardware": paper_ms[B]})
+                         "tokens_per_s": B * N / (ms * 1e-3), "paper_ms_other_hardware": paper_ms.get(B)})
         finally:
             ctx.rt_destroy()
         del x, y, K, V
@@ -181,6 +181,8 @@ def main():
     ap.add_argument("--no-backward", action="store_true", help="skip rt_layer_backward")
     ap.add_argument("--no-stack", action="store_true", help="skip the 12-layer stack measurement (rt_stack_prefill)")
     ap.add_argument("--no-batch-sweep", action="store_true", help="skip rt_layer_prefill at N = 512 for batch sizes 32 .. 1024")
+    ap.add_argument("--batch-sweep-only", action="store_true", help="only that sweep (for profiling): prints its section alone")
+    ap.add_argument("--batch-sweep-sizes", default="", help="with --batch-sweep-only: comma-separated batch sizes, multiples of 32")
     ap.add_argument("--stack-only", action="store_true",
                     help="only the 12-layer stack through rt_stack_prefill (for profiling): prints its section alone")
     ap.add_argument("--stack-layers", type=int, default=0, help="with --stack-only: number of layers (default: the workload's 12)")
@@ -206,6 +208,10 @@ def main():
         big2 = big.clone()          # one copy kernel: reads 256 MiB, writes 256 MiB
         torch.cuda.synchronize()
         del big, big2
+    if args.batch_sweep_only:
+        sizes = [int(v) for v in args.batch_sweep_sizes.split(",") if v] or None
+        print(json.dumps({"batch_sweep": batch_sweep_section(torch.cuda.current_stream(), sizes)}))
+        return
     if args.stack_only:
         print(json.dumps({"stack_wavefront": stack_section(torch.cuda.current_stream(), layer_by_layer=False,
                                                            reps=args.steps, alibi=args.alibi, layers=args.stack_layers,
