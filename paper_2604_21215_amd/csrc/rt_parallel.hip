@@ -382,19 +382,30 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
             const size_t oo = ((size_t)n * po.Bc + bb) * K + h * kHeadDim + qc;   // the projection is square: row length = K = d
             if (po.K != nullptr && which > 0) {   // straight into the cache: the rows of the pre-pass buffers are laid out like it
                 bf16_t *vt = po.VT ? po.VT + ((size_t)(bb * po.H + h) * kHeadDim + qc) * po.vt_stride + n : nullptr;
+                uint32_t hb[8], lb[8], fb[8];   // the 16 outputs as bf16 head, bf16 remainder and fp16 pairs: 32-byte runs per array
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    float val = v[e] * sc;
-                    if (qk && gn) val *= bf16_to_f32(gn[h * kHeadDim + qc + e]);
-                    const bf16_t r = f32_to_bf16(val);
-                    if (which == 1) {
-                        po.K[oo + e] = r;
-                        po.Klo[oo + e] = f32_to_bf16(val - bf16_to_f32(r));
-                        po.Kh[oo + e] = f32_to_f16_bits(val);
-                    } else {
-                        po.V[oo + e] = r;
-                        if (vt) vt[(size_t)e * po.vt_stride] = r;   // else the caller transposes whole runs of positions later
+                for (int e2 = 0; e2 < 8; ++e2) {
+                    float v0 = v[2 * e2] * sc, v1 = v[2 * e2 + 1] * sc;
+                    if (qk && gn) {
+                        v0 *= bf16_to_f32(gn[h * kHeadDim + qc + 2 * e2]);
+                        v1 *= bf16_to_f32(gn[h * kHeadDim + qc + 2 * e2 + 1]);
                     }
+                    hb[e2] = pack_bf16(v0, v1);
+                    lb[e2] = pack_bf16(v0 - __uint_as_float(hb[e2] << 16), v1 - __uint_as_float(hb[e2] & 0xFFFF0000u));
+                    fb[e2] = pack_f16(v0, v1);
+                    if (which == 2 && vt) {   // else the caller transposes whole runs of positions later
+                        vt[(size_t)(2 * e2) * po.vt_stride] = (bf16_t)(hb[e2] & 0xFFFFu);
+                        vt[(size_t)(2 * e2 + 1) * po.vt_stride] = (bf16_t)(hb[e2] >> 16);
+                    }
+                }
+                bf16_t *row = (which == 1 ? po.K : po.V) + oo;
+                *reinterpret_cast<uint4 *>(row) = make_uint4(hb[0], hb[1], hb[2], hb[3]);
+                *reinterpret_cast<uint4 *>(row + 8) = make_uint4(hb[4], hb[5], hb[6], hb[7]);
+                if (which == 1) {
+                    *reinterpret_cast<uint4 *>(po.Klo + oo) = make_uint4(lb[0], lb[1], lb[2], lb[3]);
+                    *reinterpret_cast<uint4 *>(po.Klo + oo + 8) = make_uint4(lb[4], lb[5], lb[6], lb[7]);
+                    *reinterpret_cast<uint4 *>(po.Kh + oo) = make_uint4(fb[0], fb[1], fb[2], fb[3]);
+                    *reinterpret_cast<uint4 *>(po.Kh + oo + 8) = make_uint4(fb[4], fb[5], fb[6], fb[7]);
                 }
                 return;
             }
