@@ -423,17 +423,26 @@ __global__ __launch_bounds__(64 * NWV) void blk_gemm_kernel(const bf16_t *__rest
     }
     if (m >= M) return;
     const size_t o = ((size_t)(m / Nc) * N + n0 + m % Nc) * Nn + nb0 + qc;
+    // PER consecutive outputs: loads and stores in pieces of four elements (8 bytes of bf16, 16 bytes of fp32)
 #pragma unroll
-    for (int e = 0; e < PER; ++e) {
+    for (int e4 = 0; e4 < PER / 4; ++e4) {
+        float r[4];
         if (EPI == PG_WO) {
-            const float h = bf16_to_f32(res_b[o + e]) + alpha * v[e];
-            out_f[o + e] = h;
-            out_b[o + e] = f32_to_bf16(h);
+            const uint2 xr = *reinterpret_cast<const uint2 *>(res_b + o + 4 * e4);
+            const float x4[4] = {__uint_as_float(xr.x << 16), __uint_as_float(xr.x & 0xFFFF0000u), __uint_as_float(xr.y << 16),
+                                 __uint_as_float(xr.y & 0xFFFF0000u)};
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = x4[e] + alpha * v[4 * e4 + e];
+            *reinterpret_cast<float4 *>(out_f + o + 4 * e4) = make_float4(r[0], r[1], r[2], r[3]);
         } else if (EPI == PG_W1) {
-            out_b[o + e] = f32_to_bf16(gelu_erf(v[e] * rs));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) r[e] = gelu_erf(v[4 * e4 + e] * rs);
         } else {
-            out_b[o + e] = f32_to_bf16(res_f[o + e] + alpha * v[e]);
+            const float4 h4 = *reinterpret_cast<const float4 *>(res_f + o + 4 * e4);
+            r[0] = h4.x + alpha * v[4 * e4]; r[1] = h4.y + alpha * v[4 * e4 + 1];
+            r[2] = h4.z + alpha * v[4 * e4 + 2]; r[3] = h4.w + alpha * v[4 * e4 + 3];
         }
+        *reinterpret_cast<uint2 *>(out_b + o + 4 * e4) = make_uint2(pack_bf16(r[0], r[1]), pack_bf16(r[2], r[3]));
     }
 }
 
