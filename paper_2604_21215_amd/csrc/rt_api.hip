@@ -375,7 +375,7 @@ rt_status rt_create(const rt_config *cfg, rt_ctx **out)
     if (c->persist.available && c->cfg.max_batch > c->persist.max_batch) {
         const size_t two = 2 * Nm * (size_t)c->persist.max_batch * d * E;
         if (hipMalloc(&c->kv_chunk, two) == hipSuccess) c->kv_chunk_bytes = two;
-        else { (void)hipGetLastError(); c->kv_chunk = nullptr; }   // such batches then take the per-position engine
+        else { (void)hipGetLastError(); c->kv_chunk = nullptr; }   // such batches then never run in chunks
     }
     (void)decode_coop_create(c->dec, c->cfg, D);   // shapes it does not cover keep the multi-launch step
     // scratch of the other entry points, when the caller wants no allocation inside a later call

@@ -899,8 +899,8 @@ static void block_gemms(const LayerDims &D, const Weights &W, const void *x, voi
                                (const bf16_t *)W.W1, M, F, d, Nc, D.N, n0, (const bf16_t *)W.g_mlp, D.eps, D.norm_free, D.alpha,
                                (const bf16_t *)nullptr, (const float *)nullptr, (float *)nullptr, u_b);
         else
-        (void)blk_gemm_launch<PG_W1>(dim3(gs, (unsigned)(F / 64)), st, h_b, (const bf16_t *)W.W1, M, F, d, Nc, D.N, n0,
-                                     (const bf16_t *)W.g_mlp, D.eps, D.norm_free, D.alpha, nullptr, nullptr, nullptr, u_b, none);
+            (void)blk_gemm_launch<PG_W1>(dim3(gs, (unsigned)(F / 64)), st, h_b, (const bf16_t *)W.W1, M, F, d, Nc, D.N, n0,
+                                         (const bf16_t *)W.g_mlp, D.eps, D.norm_free, D.alpha, nullptr, nullptr, nullptr, u_b, none);
         (void)blk_gemm_launch<PG_W2>(dim3(gs, (unsigned)(d / 64)), st, u_b, (const bf16_t *)W.W2, M, d, F, Nc, D.N, n0, nullptr, D.eps,
                                      D.norm_free, D.alpha, nullptr, h_f, nullptr, (bf16_t *)y, none);
         return;
