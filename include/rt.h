@@ -131,8 +131,9 @@ rt_status rt_layer_prefill(rt_ctx *ctx, const rt_layer_weights *w, const void *x
  * runs on weight slices held in LDS, and the workgroups exchange the vectors between the products through memory.  The
  * workgroups wait for one another, so two such steps must not run at the same time on one device (two contexts on two
  * streams): each could hold part of the chip and wait for the rest; their bounded waits would then expire
- * (rt_device_wait_expired) instead of hanging.  Steps on one stream are ordered and safe.  Any other shape or dtype, and
- * contexts created with RT_FLAG_ENGINE_STEPWISE, take eight launches per step instead. */
+ * (rt_device_wait_expired) instead of hanging.  Steps on one stream are ordered and safe.  A batch of up to three times
+ * the rows one launch takes (min(16, 256 / n_heads)) runs as one such launch per chunk of rows, one after the other.  Any
+ * other shape, dtype or batch size, and contexts created with RT_FLAG_ENGINE_STEPWISE, take eight launches per step instead. */
 rt_status rt_decode_step(rt_ctx *ctx, const rt_layer_weights *w, const void *x_t, int32_t B, int32_t t, void *y_t,
                          void *K, void *V, int32_t kv_cap);
 

@@ -26,9 +26,11 @@ rt_status decode_coop_create(DecodeCoopState &P, const rt_config &cfg, const Lay
 void decode_coop_destroy(DecodeCoopState &P);
 size_t decode_coop_bytes(const DecodeCoopState &P);
 bool decode_coop_supported(const DecodeCoopState &P, const LayerDims &D);
-// one position t over the cache rows 0 .. t-1 of K, V; writes y_t and row t of K, V
+// one position t over the cache rows 0 .. t-1 of K, V; writes y_t and row t of K, V.  kv_row_elems: elements between two
+// rows of the cache when the D.B sequences are a chunk of a larger batch (K, V then point at the chunk's first sequence
+// inside row 0); 0: the rows hold these D.B sequences only
 rt_status decode_coop_step(DecodeCoopState &P, const LayerDims &D, const Weights &W, const void *x_t, int t, void *y_t, void *K,
-                           void *V, hipStream_t st, std::string &err);
+                           void *V, hipStream_t st, std::string &err, size_t kv_row_elems = 0);
 int decode_coop_wait_expired(DecodeCoopState &P);
 int decode_coop_read_trace(DecodeCoopState &P, unsigned long long *out, int workgroups);
 

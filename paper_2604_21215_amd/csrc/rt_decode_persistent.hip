@@ -42,6 +42,7 @@ struct DecArgs {
     const bf16_t *x;               // [B][d]
     bf16_t *y;                     // [B][d]
     bf16_t *K, *V;                 // [kv_cap][B][H][64]: rows 0 .. t-1 read, row t written
+    size_t kv_rs;                  // elements between cache rows: B H 64, or the whole batch's when this call is a chunk of it
     ll_t *qkv_ll;                  // [3d] x kBMax, one fp32 per word
     ll_t *part_ll;                 // [B H][kDecMaxSplit][kPartWords]
     ll_t *a_ll, *h_ll, *z_ll;      // [kBMax][d/2]   two bf16 per word
@@ -191,7 +192,7 @@ __global__ __launch_bounds__(kPThreads) void decode_coop_kernel(DecArgs A)
     const int ub = att ? u / H : 0, uh = att ? u - ub * H : 0;
     const int nch = (t + 63) >> 6;            // chunks of 64 cached keys
     const int nworkers = kPW * S;
-    const size_t rs = (size_t)BH * kHeadDim;
+    const size_t rs = A.kv_rs;
     const bool is_merger = att && s == 0 && wave == 0;
 
     RT_DEC_STAMP(0);
@@ -660,7 +661,7 @@ size_t decode_coop_bytes(const DecodeCoopState &P) { return P.slab ? P.slab_byte
 bool decode_coop_supported(const DecodeCoopState &P, const LayerDims &D) { return P.available && D.B <= P.max_batch; }
 
 rt_status decode_coop_step(DecodeCoopState &P, const LayerDims &D, const Weights &W, const void *x_t, int t, void *y_t, void *K,
-                           void *V, hipStream_t st, std::string &err)
+                           void *V, hipStream_t st, std::string &err, size_t kv_row_elems)
 {
     DecArgs A;
     A.B = D.B; A.d = D.d; A.H = D.H; A.F = D.F; A.BH = D.B * D.H; A.G = P.grid; A.t = t;
@@ -675,6 +676,7 @@ rt_status decode_coop_step(DecodeCoopState &P, const LayerDims &D, const Weights
     A.g_attn = (const bf16_t *)W.g_attn; A.g_mlp = (const bf16_t *)W.g_mlp; A.g_kv = (const bf16_t *)W.g_kv;
     A.g_q = (const bf16_t *)W.g_q; A.g_k = (const bf16_t *)W.g_k;
     A.x = (const bf16_t *)x_t; A.y = (bf16_t *)y_t; A.K = (bf16_t *)K; A.V = (bf16_t *)V;
+    A.kv_rs = kv_row_elems ? kv_row_elems : (size_t)A.BH * kHeadDim;
     const Slab s = slab_for(D.d, D.F, P.grid);
     char *p = (char *)P.slab;
     A.bar = (unsigned long long *)(p + s.bar);

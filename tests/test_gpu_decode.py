@@ -100,3 +100,10 @@ def test_decode_many_chunks_per_wavefront(oracle, monkeypatch):
 def test_decode_largest_layout(oracle):
     # B H = 256 at d = 1024: one workgroup per (b, h), sixteen staged rows - the largest LDS layout the kernel has
     _decode_case(oracle, 16, 75, 1024, 16, n0=70, steps=list(range(70, 75)), seed=40, gains="unit")
+
+
+def test_decode_batches_beyond_the_single_launch_run_in_chunks(oracle):
+    # 40 sequences: three launches of 16 + 16 + 8 rows, each on its slice of the position-major cache rows (row stride of the
+    # whole batch); 20 at the headline width: 16 + 4
+    _decode_case(oracle, 40, 70, 256, 4, n0=64, steps=list(range(64, 70)), seed=41, scale=0.5, alibi=8.0)
+    _decode_case(oracle, 20, 40, 1024, 16, n0=36, steps=list(range(36, 40)), seed=42, scale=0.25)
